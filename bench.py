@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""One-GPU benchmark of the recurrent Q-network hot path.
+
+A step is one pass of the whole path over one batch of synthetic input: one decision step
+for E environments x N agents (marl_act_step, Q values written) followed by one unroll+TD over
+B episodes x T transitions with a distinct target network (marl_unroll_td).  Inputs are
+resident in HBM before timing starts; the act-step inputs rotate through a pool larger than
+the 256 MB last-level cache so that they are read from HBM.
+
+Prints ONE JSON line.  value = agent-steps/s of the whole step,
+(E*N + B*T*N) / time per step; the act-step and unroll figures are reported separately next
+to it, with a roofline object for the dominant kernel and the oracle's CPU timing.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"hbm_GBs": 8000.0, "fp32_TFs": 157.3, "bf16_TFs": 2500.0}
+LLC_BYTES = 256 << 20
+
+
+def flops_per_agent_step(N, D, A, H):
+    # fc1 (the one-hot id is a column gather, not a multiply), two GRU products, fc2
+    return 2 * D * H + 2 * (3 * H * H) * 2 + 2 * H * A
+
+
+def act_bytes_per_agent_step(N, D, A, H, with_q=True):
+    # obs + avail + h in + h out + action (+ Q)
+    return 4 * D + A + 8 * H + 4 + (4 * A if with_q else 0)
+
+
+def unroll_bytes_per_agent_step(N, D, A, H):
+    # obs + avail + action + q_taken + next_max + td_target
+    return 4 * D + A + 16
+
+
+class Bench:
+    def __init__(self, ci, two_nets=True):
+        import torch
+        from paper_2205_05248_amd import binding, workloads as wl
+        self.torch, self.wl = torch, wl
+        self.cfg = cfg = wl.config(ci)
+        self.dims = dims = wl.dims(cfg)
+        N, D, A, H = dims
+        self.w_on, self.w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
+        self.online = binding.QNet(dims, self.w_on, cfg["dtype"])
+        self.target = binding.QNet(dims, self.w_tg, cfg["dtype"]) if two_nets else None
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+        E, B, T = cfg["E"], cfg["B"], cfg["T"]
+        set_bytes = E * N * act_bytes_per_agent_step(*dims)
+        self.pool = max(2, min(64, -(-2 * LLC_BYTES // set_bytes)))
+        self.act_in = []
+        for s in range(self.pool):
+            inp = wl.make_act_inputs(cfg, stream=s % 4)
+            self.act_in.append({k: dev(inp[k]) for k in ("obs", "avail", "h_in", "reset", "step_t")})
+            self.act_meta = inp
+        self.h_out = [torch.empty(E, N, H, device="cuda") for _ in range(self.pool)]
+        self.action = torch.empty(E, N, dtype=torch.int32, device="cuda")
+        self.q = [torch.empty(E, N, A, device="cuda") for _ in range(self.pool)]
+        u = wl.make_unroll_inputs(cfg)
+        self.u_host = u
+        self.u = {k: dev(u[k]) for k in ("obs", "avail", "actions", "reward", "terminated", "filled")}
+        self.u_out = [torch.empty(B, T, N, device="cuda") for _ in range(3)]
+        self.n_act = 0
+        torch.cuda.synchronize()
+
+    def act(self):
+        i = self.n_act % self.pool
+        self.n_act += 1
+        a = self.act_in[i]
+        self.online.act_step(a["obs"], a["avail"], a["h_in"], a["reset"], a["step_t"], self.act_meta["epsilon"],
+                             self.act_meta["seed"] + self.n_act, self.h_out[i], self.action, self.q[i])
+
+    def unroll(self):
+        u = self.u
+        self.online.unroll_td(self.target, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
+                              u["filled"], self.u_host["gamma"], *self.u_out)
+
+    def run(self, steps, warmup):
+        torch = self.torch
+        for _ in range(warmup):
+            self.act(); self.unroll()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            ev[k][0].record(); self.act(); ev[k][1].record(); self.unroll(); ev[k][2].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        act_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        unroll_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        return wall, act_ms, unroll_ms
+
+    def back_to_back_act(self, n=200):
+        torch = self.torch
+        for _ in range(5):
+            self.act()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            self.act()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    def close(self):
+        self.online.close()
+        if self.target is not None:
+            self.target.close()
+
+
+def cpu_baseline(ci, budget_rows=1024):
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload."""
+    from oracle import marl_oracle as orc
+    from paper_2205_05248_amd import workloads as wl
+    cfg = wl.config(ci)
+    dims = wl.dims(cfg)
+    N = cfg["N"]
+    w_on, w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
+    inp = wl.make_act_inputs(cfg)
+    threads = orc.default_threads()
+    orc.act_step(dims, w_on, inp["obs"][:8], inp["avail"][:8], inp["h_in"][:8], inp["reset"][:8], inp["step_t"][:8],
+                 0.0, 1)                                           # build / page in
+    t0 = time.perf_counter()
+    reps = 3
+    for _ in range(reps):
+        orc.act_step(dims, w_on, inp["obs"], inp["avail"], inp["h_in"], inp["reset"], inp["step_t"],
+                     inp["epsilon"], inp["seed"], nthreads=threads)
+    t_act = (time.perf_counter() - t0) / reps
+    u = wl.make_unroll_inputs(cfg)
+    rows_total = cfg["B"] * N
+    rows = np.arange(min(rows_total, budget_rows), dtype=np.int32)
+    t0 = time.perf_counter()
+    orc.unroll_td(dims, w_on, w_tg, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"], u["filled"],
+                  u["gamma"], want_q_all=False, rows=rows, nthreads=threads)
+    t_unroll = (time.perf_counter() - t0) * rows_total / rows.size       # scaled to the whole batch
+    steps_act = cfg["E"] * N
+    steps_unroll = cfg["B"] * cfg["T"] * N
+    return {
+        "value": (steps_act + steps_unroll) / (t_act + t_unroll), "unit": "agent-steps/s", "cores": threads,
+        "kind": "oracle",
+        "sample": f"act-step: all {steps_act} rows x{reps}; unroll+TD (two networks): first {rows.size} of "
+                  f"{rows_total} (episode, agent) rows over all T+1 slots, time scaled to the full batch",
+        "act_agent_steps_per_s": steps_act / t_act,
+        "unroll_episode_steps_per_s": cfg["B"] * cfg["T"] / t_unroll,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=4, help="workload index 0..4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--single-net", action="store_true", help="target == online in the unroll")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU only: every (env, agent) row is independent, so more GPUs "
+                 "would each run this same kernel on their own share; run with --gpus 1")
+    import torch
+    from paper_2205_05248_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    b = Bench(args.config, two_nets=not args.single_net)
+    cfg, dims = b.cfg, b.dims
+    N, D, A, H = dims
+    E, B, T = cfg["E"], cfg["B"], cfg["T"]
+    wall, act_ms, unroll_ms = b.run(args.steps, args.warmup)
+    act_b2b_ms = b.back_to_back_act()
+    b.close()
+
+    ms_per_step = wall * 1e3 / args.steps
+    steps_act, steps_unroll = E * N, B * T * N
+    nets = 1 if args.single_net else 2
+    fl = flops_per_agent_step(*dims)
+    act_bytes = steps_act * act_bytes_per_agent_step(*dims)
+    unroll_flops = nets * B * (T + 1) * N * fl
+    peak_tf = PEAK["bf16_TFs"] if cfg["dtype"] == "bf16" else PEAK["fp32_TFs"]
+    unroll_tfs = unroll_flops / (unroll_ms * 1e-3) / 1e12
+    act_gbs = act_bytes / (act_b2b_ms * 1e-3) / 1e9
+    out = {
+        "metric": "agent-steps/s (act-step) and episode-steps/s (unroll+TD); % HBM/MFMA peak",
+        "value": (steps_act + steps_unroll) / (ms_per_step * 1e-3),
+        "unit": "agent-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 weights, f32 accumulate" if cfg["dtype"] == "bf16" else "f32",
+        "data": "synthetic",
+        "config": {"workload": cfg["name"], "E": E, "N": N, "obs_dim": D, "n_actions": A, "hidden": H,
+                   "B": B, "T": T, "target_network": "distinct" if nets == 2 else "same",
+                   "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
+        "act_step": {"agent_steps_per_s": steps_act / (act_b2b_ms * 1e-3), "kernel_ms_in_step": act_ms,
+                     "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": act_gbs,
+                     "hbm_frac": act_gbs / PEAK["hbm_GBs"],
+                     "tflops": steps_act * fl / (act_b2b_ms * 1e-3) / 1e12,
+                     "input_pool_bytes": b.pool * act_bytes},
+        "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),
+                      "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "call_ms": unroll_ms,
+                      "tflops": unroll_tfs},
+        "roofline": {"kernel": "unroll_td", "bound": "mfma", "achieved": unroll_tfs, "peak": peak_tf,
+                     "unit": "TFLOP/s", "frac": unroll_tfs / peak_tf, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(args.config)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,171 @@
+/*
+ * marl_qnet.h - C ABI of the batched per-agent recurrent Q-network for MI355X (gfx950).
+ *
+ * The library evaluates one shared network
+ *     x  = ReLU(W1 [obs, onehot(agent)] + b1)
+ *     h' = GRUCell(x, h)            (gates r, z, n; n = tanh(W_in x + b_in + r * (W_hn h + b_hn));
+ *                                    h' = (1 - z) * n + z * h)
+ *     Q  = W2 h' + b2
+ * for every agent of every environment, with a hidden state kept separately per
+ * agent and per environment (the paper's multidimensional hidden state, Fig. 3,
+ * and the passage around it: agents of different environments must not share
+ * history).  Two uses:
+ *
+ *   marl_act_step  - the worker's decision step (Alg. 2, "make decisions based on
+ *                    policy, a ~ pi(a|o)"; step 2 of the actor-worker framework):
+ *                    one network step for E environments x N agents, then the
+ *                    available-action mask and an epsilon-greedy choice.
+ *   marl_unroll_td - the forward half of the learner's TD step (Alg. 3, "calculate
+ *                    the gradient": y - Q(s, a; theta)) on a batch of B whole
+ *                    trajectories (the actor sends whole tracks, Alg. 1): the
+ *                    network unrolled over T+1 observation slots, Q of the taken
+ *                    actions, the masked maximum of the next slot, and the 1-step
+ *                    target y = r + gamma (1 - terminated) max_a' Q_target(t+1, a').
+ *
+ * Conventions
+ *   - "dev" pointers are device memory of the handle's device; "host" pointers
+ *     are ordinary host memory.  The caller owns every buffer it passes and keeps
+ *     it alive until the stream has run the call.  The library owns the handle,
+ *     its device copy of the weights, and a cached scratch buffer (see
+ *     marl_unroll_td).
+ *   - All arrays are dense, row-major, last index fastest.
+ *   - Calls validate their arguments on the host before anything is enqueued,
+ *     enqueue on `hip_stream` (a hipStream_t; NULL = the default stream) and
+ *     return without synchronising.  Outputs are valid once the stream has
+ *     reached the call.
+ *   - Return value: 0 on success, a negative MARL_ERR_* otherwise.  Nothing is
+ *     written to outputs when an error is returned.  The library never throws or
+ *     aborts.
+ *   - One handle must not be used by two host threads at once.
+ *
+ * Packed weights (host, fp32, row-major), Din = obs_dim + n_agents, H = hidden:
+ *   W1[H,Din], b1[H], W_ih[3H,H], W_hh[3H,H], b_ih[3H], b_hh[3H], W2[A,H], b2[A];
+ *   the three row blocks of W_ih, W_hh, b_ih, b_hh are the gates r, z, n.
+ *   Column obs_dim + n of W1 belongs to the one-hot id of agent n.
+ */
+#ifndef MARL_QNET_H
+#define MARL_QNET_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MARL_OK             0
+#define MARL_ERR_NULL      -1   /* a required pointer is NULL */
+#define MARL_ERR_BAD_DIM   -2   /* a size is <= 0 or outside the supported range */
+#define MARL_ERR_BAD_DTYPE -3   /* weight_dtype is not MARL_DTYPE_F32 / MARL_DTYPE_BF16 */
+#define MARL_ERR_MISMATCH  -4   /* n_weights != parameter count, or online/target differ */
+#define MARL_ERR_BAD_ARG   -5   /* epsilon or gamma outside [0,1] or not finite */
+#define MARL_ERR_DEVICE    -6   /* a HIP runtime call failed; see marl_last_device_error */
+#define MARL_ERR_NOMEM     -7   /* host or device allocation failed */
+
+#define MARL_DTYPE_F32   0      /* fp32 weights, fp32 accumulation */
+#define MARL_DTYPE_BF16  1      /* matrices rounded to bf16 (nearest even) at create; biases, hidden
+                                   state and accumulation stay fp32 */
+
+/* Supported ranges (checked by marl_qnet_create). */
+#define MARL_MAX_AGENTS   64
+#define MARL_MAX_OBS_DIM  1024
+#define MARL_MAX_ACTIONS  64
+/* hidden must be 64 or 128 */
+
+typedef struct marl_qnet marl_qnet;          /* opaque, library-owned */
+
+typedef struct {
+    int32_t n_agents;      /* N */
+    int32_t obs_dim;       /* D, without the agent id */
+    int32_t n_actions;     /* A */
+    int32_t hidden;        /* H */
+    int32_t weight_dtype;  /* MARL_DTYPE_* */
+    int32_t device;        /* HIP device ordinal */
+} marl_qnet_desc;
+
+/* Number of fp32 values in the packed weight vector for desc, 0 if desc is invalid. */
+size_t marl_param_count(const marl_qnet_desc *desc);
+
+/*
+ * Create a network on desc->device from packed host weights (copied; the caller
+ * may free them on return).  n_weights must equal marl_param_count(desc).
+ * The description is validated before the device is touched.
+ */
+int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size_t n_weights,
+                     marl_qnet **out);
+
+/* Copy of the description the handle was created with. */
+int marl_qnet_get_desc(const marl_qnet *q, marl_qnet_desc *out);
+
+/*
+ * Decision step for E environments (worker, Alg. 2).
+ *   obs     dev [E,N,D] f32      observations
+ *   avail   dev [E,N,A] u8       1 = action available, 0 = not
+ *   h_in    dev [E,N,H] f32      hidden state before the step
+ *   reset   dev [E] u8 or NULL   1 = environment e starts an episode: h_in[e] is read as zero
+ *   step_t  dev [E] i32          step counter of environment e (environments run asynchronously,
+ *                                so each has its own); only feeds the random-number key
+ *   epsilon in [0,1]; seed any 64-bit value
+ *   h_out   dev [E,N,H] f32      hidden state after the step; may be the same buffer as h_in
+ *   action  dev [E,N] i32        chosen action
+ *   q_out   dev [E,N,A] f32 or NULL   unmasked Q values
+ *
+ * Action rule.  greedy = lowest index among the maxima of Q over available
+ * actions.  Random numbers are SplitMix64 outputs: S(v) = mix(v + 0x9E3779B97F4A7C15);
+ * key = S(S(S(S(seed) ^ e) ^ n) ^ step_t[e]) (step_t taken as its unsigned 32-bit
+ * pattern), r1 = S(key), r2 = S(key + 0x9E3779B97F4A7C15).  Explore iff
+ * (float)(r1 >> 40) * 2^-24 < epsilon (fp32 compare); the explored action is the
+ * j-th available one in ascending order, j = ((r2 >> 32) * c) >> 32, c = number
+ * of available actions.  With no available action the result is action 0.
+ */
+int marl_act_step(marl_qnet *q, int32_t E,
+                  const float *obs, const uint8_t *avail, const float *h_in,
+                  const uint8_t *reset, const int32_t *step_t,
+                  float epsilon, uint64_t seed,
+                  float *h_out, int32_t *action, float *q_out, void *hip_stream);
+
+/*
+ * Unroll over a batch of B trajectories of T transitions and form TD targets
+ * (learner, Alg. 3).  online and target must have equal descriptions and live on
+ * the same device; target may be the same handle as online.
+ *   obs        dev [B,T+1,N,D] f32
+ *   avail      dev [B,T+1,N,A] u8
+ *   actions    dev [B,T,N] i32      taken actions, each in [0,A)
+ *   reward     dev [B,T] f32        team reward
+ *   terminated dev [B,T] u8         1 = the episode truly ended at this transition (no bootstrap)
+ *   filled     dev [B,T] u8         1 = real transition, 0 = padding
+ *   gamma in [0,1]
+ *   q_taken    dev [B,T,N] f32      filled * Q_online(t)[action]
+ *   next_max   dev [B,T,N] f32      filled * max over available a of Q_target(t+1)[a] (0 if none)
+ *   td_target  dev [B,T,N] f32      filled * (reward + gamma * (1 - terminated) * that maximum)
+ *   q_all      dev [B,T+1,N,A] f32 or NULL   Q_online at every slot, unmasked
+ * Both networks start from a zero hidden state at slot 0 and keep stepping
+ * through padding.  Actions outside [0,A) are clamped into range.
+ *
+ * Scratch: the library keeps one device buffer per handle for intermediate
+ * activations, grown (never shrunk) when a call needs more than any earlier
+ * call; growing synchronises the device.  marl_qnet_reserve_unroll sizes it
+ * ahead of time so that later calls up to that size allocate nothing.
+ */
+int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
+                   const float *obs, const uint8_t *avail, const int32_t *actions,
+                   const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                   float gamma,
+                   float *q_taken, float *next_max, float *td_target, float *q_all,
+                   void *hip_stream);
+
+int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
+
+/* Free the handle, its weights and scratch.  Synchronises the device.  NULL is allowed. */
+int marl_destroy(marl_qnet *q);
+
+/* Static description of a status code. */
+const char *marl_strerror(int status);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *marl_last_device_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MARL_QNET_H */

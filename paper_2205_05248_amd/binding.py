@@ -1,0 +1,175 @@
+"""ctypes binding of libmarl_qnet.so (include/marl_qnet.h), same entry-point names.
+
+Argument marshalling only: tensors are checked for dtype, shape, contiguity and
+device, and their addresses handed to the C ABI together with torch's current
+HIP stream.  Every step of the network, the action rule and the TD targets run
+in the library's kernels.  There is no CPU fallback: if the library is not
+built, or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmarl_qnet.so")
+
+MARL_DTYPE_F32 = 0
+MARL_DTYPE_BF16 = 1
+DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
+
+EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
+           "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
+           "marl_last_device_error"]
+
+
+class MarlError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"marl_qnet error {status}: {text}")
+        self.status = status
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("n_agents", ctypes.c_int32), ("obs_dim", ctypes.c_int32), ("n_actions", ctypes.c_int32),
+                ("hidden", ctypes.c_int32), ("weight_dtype", ctypes.c_int32), ("device", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def load():
+    """Load the built library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2205_05248_amd.build` "
+                "(there is no CPU fallback)")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, f32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_uint64
+        lib.marl_param_count.restype = ctypes.c_size_t
+        lib.marl_param_count.argtypes = [ctypes.POINTER(Desc)]
+        lib.marl_qnet_create.restype = ctypes.c_int
+        lib.marl_qnet_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+        lib.marl_qnet_get_desc.restype = ctypes.c_int
+        lib.marl_qnet_get_desc.argtypes = [vp, ctypes.POINTER(Desc)]
+        lib.marl_act_step.restype = ctypes.c_int
+        lib.marl_act_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, f32, u64, vp, vp, vp, vp]
+        lib.marl_unroll_td.restype = ctypes.c_int
+        lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
+        lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
+        lib.marl_destroy.restype = ctypes.c_int
+        lib.marl_destroy.argtypes = [vp]
+        lib.marl_strerror.restype = ctypes.c_char_p
+        lib.marl_strerror.argtypes = [ctypes.c_int]
+        lib.marl_last_device_error.restype = ctypes.c_char_p
+        lib.marl_last_device_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def check(status):
+    if status != 0:
+        lib = load()
+        text = lib.marl_strerror(status).decode()
+        if status == -6:
+            text += " (" + lib.marl_last_device_error().decode() + ")"
+        raise MarlError(status, text)
+
+
+def marl_param_count(n_agents, obs_dim, n_actions, hidden, weight_dtype=MARL_DTYPE_F32, device=0):
+    d = Desc(n_agents, obs_dim, n_actions, hidden, weight_dtype, device)
+    return int(load().marl_param_count(ctypes.byref(d)))
+
+
+def marl_qnet_create(n_agents, obs_dim, n_actions, hidden, weight_dtype, device, host_weights):
+    """Returns an opaque handle (int).  host_weights: packed fp32 numpy array."""
+    w = np.ascontiguousarray(host_weights, dtype=np.float32)
+    d = Desc(n_agents, obs_dim, n_actions, hidden, weight_dtype, device)
+    out = ctypes.c_void_p()
+    check(load().marl_qnet_create(ctypes.byref(d), w.ctypes.data_as(ctypes.c_void_p), w.size, ctypes.byref(out)))
+    return out.value
+
+
+def marl_destroy(handle):
+    check(load().marl_destroy(ctypes.c_void_p(handle)))
+
+
+def _dev(t, dtype, shape, name, optional=False):
+    import torch
+    if t is None:
+        if optional:
+            return None
+        raise ValueError(f"{name} is required")
+    want = {"f32": torch.float32, "u8": torch.uint8, "i32": torch.int32}[dtype]
+    if t.dtype != want or tuple(t.shape) != tuple(shape) or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: expected contiguous device {dtype} tensor of shape {tuple(shape)}, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def marl_act_step(handle, dims, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
+    """dims = (N, D, A, H) of the handle; tensors live on the handle's device."""
+    N, D, A, H = dims
+    E = obs.shape[0]
+    check(load().marl_act_step(
+        ctypes.c_void_p(handle), E,
+        _dev(obs, "f32", (E, N, D), "obs"), _dev(avail, "u8", (E, N, A), "avail"),
+        _dev(h_in, "f32", (E, N, H), "h_in"), _dev(reset, "u8", (E,), "reset", optional=True),
+        _dev(step_t, "i32", (E,), "step_t"), float(epsilon), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        _dev(h_out, "f32", (E, N, H), "h_out"), _dev(action, "i32", (E, N), "action"),
+        _dev(q_out, "f32", (E, N, A), "q_out", optional=True), _stream()))
+
+
+def marl_unroll_td(online, target, dims, obs, avail, actions, reward, terminated, filled, gamma,
+                   q_taken, next_max, td_target, q_all=None):
+    N, D, A, H = dims
+    B, T = obs.shape[0], obs.shape[1] - 1
+    check(load().marl_unroll_td(
+        ctypes.c_void_p(online), ctypes.c_void_p(target), B, T,
+        _dev(obs, "f32", (B, T + 1, N, D), "obs"), _dev(avail, "u8", (B, T + 1, N, A), "avail"),
+        _dev(actions, "i32", (B, T, N), "actions"), _dev(reward, "f32", (B, T), "reward"),
+        _dev(terminated, "u8", (B, T), "terminated"), _dev(filled, "u8", (B, T), "filled"), float(gamma),
+        _dev(q_taken, "f32", (B, T, N), "q_taken"), _dev(next_max, "f32", (B, T, N), "next_max"),
+        _dev(td_target, "f32", (B, T, N), "td_target"), _dev(q_all, "f32", (B, T + 1, N, A), "q_all", optional=True),
+        _stream()))
+
+
+def marl_qnet_reserve_unroll(handle, B, T):
+    check(load().marl_qnet_reserve_unroll(ctypes.c_void_p(handle), B, T))
+
+
+class QNet:
+    """Convenience owner of one handle (create on init, destroy on close)."""
+
+    def __init__(self, dims, weights, dtype="fp32", device=0):
+        self.dims = tuple(int(v) for v in dims)
+        N, D, A, H = self.dims
+        self.device = device
+        self.handle = marl_qnet_create(N, D, A, H, DTYPES[dtype], device, weights)
+
+    def act_step(self, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
+        marl_act_step(self.handle, self.dims, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out)
+
+    def unroll_td(self, target, obs, avail, actions, reward, terminated, filled, gamma,
+                  q_taken, next_max, td_target, q_all=None):
+        tgt = self if target is None else target
+        marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
+                       gamma, q_taken, next_max, td_target, q_all)
+
+    def close(self):
+        if self.handle:
+            marl_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -1,0 +1,54 @@
+// Device-side scalar helpers shared by the kernels of this library: gate
+// non-linearities of the GRU cell, the SplitMix64 counter generator used by the
+// epsilon-greedy rule of the decision step, and the per-row action choice.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace marl {
+
+__device__ __forceinline__ float sigmoidf_fast(float v) { return 1.0f / (1.0f + __expf(-v)); }
+
+// tanh(v) = 1 - 2 / (1 + e^{2v}); absolute error ~1e-7, saturates cleanly for |v| large.
+__device__ __forceinline__ float tanhf_fast(float v) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * v)); }
+
+// SplitMix64 (Steele, Lea, Flood 2014): state += golden gamma, then the 64-bit finaliser.
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;
+
+__device__ __forceinline__ uint64_t splitmix_out(uint64_t v)
+{
+    v += kGolden;
+    v ^= v >> 30; v *= 0xBF58476D1CE4E5B9ull;
+    v ^= v >> 27; v *= 0x94D049BB133111EBull;
+    v ^= v >> 31;
+    return v;
+}
+
+// Two draws for (seed, env, agent, step): the key chains the four words through the generator.
+__device__ __forceinline__ void rng_draw(uint64_t seed, uint32_t e, uint32_t n, uint32_t t,
+                                         uint64_t &r1, uint64_t &r2)
+{
+    uint64_t k = splitmix_out(splitmix_out(splitmix_out(splitmix_out(seed) ^ e) ^ n) ^ t);
+    r1 = splitmix_out(k);
+    r2 = splitmix_out(k + kGolden);
+}
+
+// Epsilon-greedy over the available actions of one (env, agent) row, given the
+// greedy action and the availability bits (bit a of avail_bits = action a usable).
+__device__ __forceinline__ int eps_greedy_pick(int greedy, uint64_t avail_bits, float epsilon,
+                                               uint64_t seed, uint32_t e, uint32_t n, uint32_t t)
+{
+    uint64_t r1, r2;
+    rng_draw(seed, e, n, t, r1, r2);
+    float u = (float)(uint32_t)(r1 >> 40) * (1.0f / 16777216.0f);
+    if (!(u < epsilon)) return greedy;
+    uint32_t c = (uint32_t)__popcll(avail_bits);
+    if (c == 0) return 0;
+    uint32_t j = (uint32_t)(((r2 >> 32) * (uint64_t)c) >> 32);
+    // index of the j-th set bit
+    uint64_t bits = avail_bits;
+    for (uint32_t i = 0; i < j; ++i) bits &= bits - 1;
+    return __ffsll((long long)bits) - 1;
+}
+
+}  // namespace marl

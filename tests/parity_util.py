@@ -1,0 +1,95 @@
+"""Helpers of the GPU parity tests: run one call through the C ABI and through the oracle
+on the same seeded inputs and compare element by element."""
+import numpy as np
+
+from oracle import marl_oracle as orc
+from paper_2205_05248_amd import workloads as wl
+
+# max abs error on Q, hidden state and TD quantities: fp32 weights / bf16 weights with fp32 accumulation
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def oracle_weights(cfg, w):
+    """The oracle computes in fp64 on the values the network really has: for bf16 networks
+    every matrix entry rounded to bf16 (by the oracle's own rounding), biases unchanged."""
+    if cfg["dtype"] != "bf16":
+        return w
+    out = np.array(w, np.float32)
+    for name, (a, b, shp) in wl.weight_slices(*wl.dims(cfg)).items():
+        if len(shp) == 2:
+            out[a:b] = orc.round_bf16(out[a:b])
+    return out
+
+
+def to_dev(inp, keys):
+    import torch
+    return {k: (None if inp[k] is None else torch.from_numpy(np.ascontiguousarray(inp[k])).cuda()) for k in keys}
+
+
+def gpu_act(net, cfg, inp, want_q=True, alias_h=False):
+    import torch
+    N, D, A, H = wl.dims(cfg)
+    d = to_dev(inp, ["obs", "avail", "h_in", "reset", "step_t"])
+    E = inp["obs"].shape[0]
+    h_out = d["h_in"] if alias_h else torch.full((E, N, H), float("nan"), device="cuda")
+    action = torch.full((E, N), -7, dtype=torch.int32, device="cuda")
+    q = torch.full((E, N, A), float("nan"), device="cuda") if want_q else None
+    net.act_step(d["obs"], d["avail"], d["h_in"], d["reset"], d["step_t"], inp["epsilon"], inp["seed"],
+                 h_out, action, q)
+    torch.cuda.synchronize()
+    return dict(h_out=h_out.cpu().numpy(), action=action.cpu().numpy(), q=None if q is None else q.cpu().numpy())
+
+
+def compare_act(cfg, inp, got, ref, tol):
+    """Returns the number of near-ties.  Q and h within tol; actions exact on explored rows and
+    wherever the oracle's best available Q leads the runner-up by more than tol; inside a
+    near-tie any available action within tol of the best is accepted."""
+    if got["q"] is not None:
+        err_q = np.abs(got["q"] - ref["q"]).max() if ref["q"].size else 0.0
+        assert err_q <= tol, f"max |Q - oracle| = {err_q}"
+    err_h = np.abs(got["h_out"] - ref["h_out"]).max() if ref["h_out"].size else 0.0
+    assert err_h <= tol, f"max |h - oracle| = {err_h}"
+    avail = inp["avail"] != 0
+    masked = np.where(avail, ref["q"], -np.inf)
+    top = np.sort(masked, -1)
+    best = top[..., -1]
+    second = top[..., -2] if masked.shape[-1] > 1 else np.full(best.shape, -np.inf)
+    clear = (ref["explored"] != 0) | ((best - second) > tol) | ~avail.any(-1)
+    assert (got["action"][clear] == ref["action"][clear]).all(), "action mismatch outside near-ties"
+    tie = ~clear
+    if tie.any():
+        a = got["action"][tie].astype(np.int64)
+        q_sel = np.take_along_axis(masked[tie], a[:, None], -1)[:, 0]
+        assert (q_sel >= best[tie] - tol).all(), "near-tie action is not one of the leaders"
+    return int(tie.sum())
+
+
+def gpu_unroll(online, target, cfg, u, want_q_all=True):
+    import torch
+    N, D, A, H = wl.dims(cfg)
+    d = to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
+    B, T = u["actions"].shape[0], u["actions"].shape[1]
+    outs = {k: torch.full((B, T, N), float("nan"), device="cuda") for k in ("q_taken", "next_max", "td_target")}
+    q_all = torch.full((B, T + 1, N, A), float("nan"), device="cuda") if want_q_all else None
+    online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                     u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
+    torch.cuda.synchronize()
+    res = {k: v.cpu().numpy() for k, v in outs.items()}
+    res["q_all"] = None if q_all is None else q_all.cpu().numpy()
+    return res
+
+
+def compare_unroll(got, ref, tol, rows=None, N=None):
+    worst = 0.0
+    for k in ("q_taken", "next_max", "td_target", "q_all"):
+        if got.get(k) is None or ref.get(k) is None:
+            continue
+        g, r = got[k], ref[k]
+        if rows is not None:
+            b, n = np.asarray(rows) // N, np.asarray(rows) % N
+            g, r = g[b, :, n], r[b, :, n]
+        assert np.isfinite(g).all(), f"{k}: non-finite output"
+        err = np.abs(g - r).max() if r.size else 0.0
+        assert err <= tol, f"max |{k} - oracle| = {err}"
+        worst = max(worst, err)
+    return worst

@@ -1,0 +1,272 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Tolerances: max abs error 1e-4 with fp32 weights, 2e-2
+with bf16 weights (fp32 accumulation); integer outputs exact outside near-ties."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import marl_oracle as orc
+from paper_2205_05248_amd import binding, workloads as wl
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    binding.load()                      # a missing library is an error, not a skip
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this container")
+
+
+def make_net(cfg, stream=0, weights=None):
+    w = wl.make_weights(cfg, stream) if weights is None else weights
+    return binding.QNet(wl.dims(cfg), w, cfg["dtype"]), pu.oracle_weights(cfg, w)
+
+
+def oracle_act(cfg, w, inp):
+    return orc.act_step(wl.dims(cfg), w, inp["obs"], inp["avail"], inp["h_in"], inp["reset"], inp["step_t"],
+                        inp["epsilon"], inp["seed"])
+
+
+def oracle_unroll(cfg, w_on, w_tg, u, rows=None):
+    return orc.unroll_td(wl.dims(cfg), w_on, w_tg, u["obs"], u["avail"], u["actions"], u["reward"],
+                         u["terminated"], u["filled"], u["gamma"], rows=rows)
+
+
+# ------------------------------------------------------------------ act-step
+@pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
+def test_act_step_full_config(ci):
+    cfg = wl.config(ci)
+    tol = pu.TOL[cfg["dtype"]]
+    net, w = make_net(cfg)
+    inp = wl.make_act_inputs(cfg)
+    ref = oracle_act(cfg, w, inp)
+    got = pu.gpu_act(net, cfg, inp)
+    ties = pu.compare_act(cfg, inp, got, ref, tol)
+    print(f"cfg{ci}: rows={cfg['E'] * cfg['N']} maxerr_q={np.abs(got['q'] - ref['q']).max():.3e} near_ties={ties}")
+    differ = int((got["action"] != ref["action"]).sum())
+    print(f"cfg{ci}: actions differing from the oracle inside near-ties: {differ}")
+    # same call without the optional Q output and with h_out aliasing h_in
+    got2 = pu.gpu_act(net, cfg, inp, want_q=False, alias_h=True)
+    np.testing.assert_array_equal(got2["action"], got["action"])
+    np.testing.assert_array_equal(got2["h_out"], got["h_out"])
+    net.close()
+
+
+@pytest.mark.parametrize("ci,E", [(0, 1), (0, 5), (0, 11), (1, 3), (1, 37), (3, 13), (3, 203), (4, 1), (4, 9)])
+def test_act_step_ragged_sizes(ci, E):
+    cfg = wl.config(ci)
+    net, w = make_net(cfg)
+    for eps in (0.0, 0.5, 1.0):
+        inp = wl.make_act_inputs(cfg, E=E, stream=E)
+        inp["epsilon"] = eps
+        ref = oracle_act(cfg, w, inp)
+        got = pu.gpu_act(net, cfg, inp)
+        pu.compare_act(cfg, inp, got, ref, pu.TOL[cfg["dtype"]])
+        chosen = np.take_along_axis(inp["avail"], got["action"][..., None].astype(np.int64), -1)
+        assert chosen.all()
+    inp["reset"] = None                                   # optional pointer
+    ref = oracle_act(cfg, w, inp)
+    got = pu.gpu_act(net, cfg, inp)
+    pu.compare_act(cfg, inp, got, ref, pu.TOL[cfg["dtype"]])
+    net.close()
+
+
+def test_act_step_closed_forms_on_gpu():
+    cfg = wl.config(0)
+    dims = wl.dims(cfg)
+    N, D, A, H = dims
+    zero = {k: np.zeros(shp) for k, (_, _, shp) in wl.weight_slices(*dims).items()}
+    inp = wl.make_act_inputs(cfg, E=21)
+    inp["reset"][:] = 0
+    # every GRU weight zero: r = z = 1/2, candidate 0 -> h' = h / 2 ; Q = b2
+    parts = dict(zero)
+    parts["b2"] = np.linspace(-1, 1, A)
+    net, _ = make_net(cfg, weights=wl.pack_weights(dims, parts))
+    got = pu.gpu_act(net, cfg, inp)
+    np.testing.assert_allclose(got["h_out"], inp["h_in"] * 0.5, atol=1e-6)
+    np.testing.assert_allclose(got["q"], np.broadcast_to(parts["b2"].astype(np.float32), got["q"].shape), atol=1e-6)
+    net.close()
+    # update gate saturated: h' = h
+    parts = {k: np.array(v) for k, v in wl.unpack_weights(dims, wl.make_weights(cfg)).items()}
+    parts["b_ih"][H:2 * H] = 40.0
+    net, _ = make_net(cfg, weights=wl.pack_weights(dims, parts))
+    got = pu.gpu_act(net, cfg, inp)
+    np.testing.assert_allclose(got["h_out"], inp["h_in"], atol=1e-6)
+    net.close()
+    # exact ties: lowest index wins; an unavailable leader is skipped
+    parts = dict(zero)
+    parts["b2"] = np.array([0.1, 0.9, 0.3, 0.9, -1.0, 0.9, 0, 0, 0])
+    net, w = make_net(cfg, weights=wl.pack_weights(dims, parts))
+    inp["epsilon"] = 0.0
+    got = pu.gpu_act(net, cfg, inp)
+    np.testing.assert_array_equal(got["action"], oracle_act(cfg, w, inp)["action"])
+    none = dict(inp); none["avail"] = np.zeros_like(inp["avail"])
+    for eps in (0.0, 1.0):
+        none["epsilon"] = eps
+        assert (pu.gpu_act(net, cfg, none)["action"] == 0).all()      # nothing available -> action 0
+    net.close()
+
+
+def test_act_step_episode_loop_feeds_hidden_state_back():
+    cfg = wl.config(0)
+    N, D, A, H = wl.dims(cfg)
+    net, w = make_net(cfg)
+    E, T = 5, cfg["T"]
+    u = wl.make_unroll_inputs(cfg, B=E)
+    h_gpu = np.zeros((E, N, H), np.float32)
+    h_ref = np.zeros((E, N, H))
+    for t in range(T + 1):
+        inp = dict(obs=u["obs"][:, t], avail=u["avail"][:, t], reset=np.full(E, t == 0, np.uint8),
+                   step_t=np.full(E, t, np.int32), epsilon=0.3, seed=99)
+        ref = oracle_act(cfg, w, dict(inp, h_in=h_ref))
+        got = pu.gpu_act(net, cfg, dict(inp, h_in=h_gpu))
+        pu.compare_act(cfg, inp, got, ref, 1e-4)
+        h_gpu, h_ref = got["h_out"], ref["h_out"]
+    net.close()
+
+
+def test_act_step_is_deterministic_and_isolated():
+    cfg = wl.config(1)
+    net, _ = make_net(cfg)
+    inp = wl.make_act_inputs(cfg, E=64)
+    a = pu.gpu_act(net, cfg, inp)
+    b = pu.gpu_act(net, cfg, inp)
+    for k in ("q", "h_out", "action"):
+        np.testing.assert_array_equal(a[k], b[k])
+    mod = {k: (v.copy() if isinstance(v, np.ndarray) else v) for k, v in inp.items()}
+    mod["obs"][5] += 1.0
+    mod["h_in"][5] *= -1.0
+    c = pu.gpu_act(net, cfg, mod)
+    others = np.arange(64) != 5
+    for k in ("q", "h_out", "action"):
+        np.testing.assert_array_equal(c[k][others], a[k][others])
+    assert (c["q"][5] != a["q"][5]).any()
+    # a sub-batch of the first environments gives the same rows
+    sub = {k: (v[:17] if isinstance(v, np.ndarray) else v) for k, v in inp.items()}
+    d = pu.gpu_act(net, cfg, sub)
+    np.testing.assert_array_equal(d["action"], a["action"][:17])
+    np.testing.assert_allclose(d["q"], a["q"][:17], atol=1e-6)
+    net.close()
+
+
+# ------------------------------------------------------------------ unroll + TD
+@pytest.mark.parametrize("ci", [0, 1, 2, 3])
+def test_unroll_td_full_config(ci):
+    cfg = wl.config(ci)
+    tol = pu.TOL[cfg["dtype"]]
+    online, w_on = make_net(cfg, 0)
+    target, w_tg = make_net(cfg, 1)
+    u = wl.make_unroll_inputs(cfg)
+    got = pu.gpu_unroll(online, target, cfg, u)
+    ref = oracle_unroll(cfg, w_on, w_tg, u)
+    worst = pu.compare_unroll(got, ref, tol)
+    pad = u["filled"] == 0
+    for k in ("q_taken", "next_max", "td_target"):
+        assert (got[k][pad] == 0.0).all()                 # padded transitions are exactly zero
+    got1 = pu.gpu_unroll(online, None, cfg, u, want_q_all=False)     # target == online, no q_all
+    ref1 = oracle_unroll(cfg, w_on, None, u)
+    worst1 = pu.compare_unroll(got1, ref1, tol)
+    print(f"cfg{ci}: two nets maxerr={worst:.3e}, one net maxerr={worst1:.3e}")
+    online.close(); target.close()
+
+
+def test_unroll_td_full_config_4_sampled_rows():
+    cfg = wl.config(4)
+    tol = pu.TOL[cfg["dtype"]]
+    online, w_on = make_net(cfg, 0)
+    target, w_tg = make_net(cfg, 1)
+    u = wl.make_unroll_inputs(cfg)
+    got = pu.gpu_unroll(online, target, cfg, u)
+    rows_total = cfg["B"] * cfg["N"]
+    rng = np.random.default_rng(4)
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, rows_total - 1], rng.integers(0, rows_total, 160)])).astype(np.int32)
+    ref = oracle_unroll(cfg, w_on, w_tg, u, rows=rows)
+    worst = pu.compare_unroll(got, ref, tol, rows=rows, N=cfg["N"])
+    print(f"cfg4: {rows.size} sampled rows, maxerr={worst:.3e}")
+    # properties that hold for every row at full size
+    pad = u["filled"] == 0
+    for k in ("q_taken", "next_max", "td_target"):
+        assert np.isfinite(got[k]).all()
+        assert (got[k][pad] == 0.0).all()
+    g = np.float32(u["gamma"])
+    keep = (1.0 - u["terminated"].astype(np.float32))[..., None]
+    expect = (u["reward"][..., None] + g * keep * got["next_max"]) * u["filled"][..., None]
+    np.testing.assert_allclose(got["td_target"], expect, atol=1e-5)
+    taken = np.take_along_axis(got["q_all"][:, :-1], u["actions"][..., None].astype(np.int64), -1)[..., 0]
+    np.testing.assert_array_equal(got["q_taken"], taken * u["filled"][..., None])
+    online.close(); target.close()
+
+
+@pytest.mark.parametrize("ci,B,T", [(0, 1, 1), (0, 3, 7), (1, 5, 9), (2, 7, 3), (3, 33, 5), (4, 2, 6)])
+def test_unroll_td_ragged_sizes(ci, B, T):
+    cfg = wl.config(ci)
+    online, w_on = make_net(cfg, 0)
+    target, w_tg = make_net(cfg, 1)
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    got = pu.gpu_unroll(online, target, cfg, u)
+    ref = oracle_unroll(cfg, w_on, w_tg, u)
+    pu.compare_unroll(got, ref, pu.TOL[cfg["dtype"]])
+    online.close(); target.close()
+
+
+def test_unroll_td_special_cases():
+    cfg = wl.config(0)
+    online, w_on = make_net(cfg, 0)
+    u = wl.make_unroll_inputs(cfg, B=6, T=11)
+    u0 = dict(u, gamma=0.0)
+    got = pu.gpu_unroll(online, None, cfg, u0)
+    expect = np.broadcast_to((u["reward"] * u["filled"])[..., None], got["td_target"].shape)
+    np.testing.assert_array_equal(got["td_target"], expect)              # gamma = 0: y = r
+    u1 = dict(u, terminated=np.ones_like(u["terminated"]))
+    got = pu.gpu_unroll(online, None, cfg, u1)
+    np.testing.assert_array_equal(got["td_target"], expect)              # terminated: y = r
+    u2 = dict(u, avail=np.zeros_like(u["avail"]))
+    got = pu.gpu_unroll(online, None, cfg, u2)
+    assert (got["next_max"] == 0.0).all()                                 # nothing available: bootstrap 0
+    online.close()
+
+
+def test_unroll_matches_iterated_act_step_on_gpu():
+    cfg = wl.config(1)
+    N, D, A, H = wl.dims(cfg)
+    net, _ = make_net(cfg)
+    B, T = 6, 20
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    got = pu.gpu_unroll(net, None, cfg, u)
+    h = np.zeros((B, N, H), np.float32)
+    for t in range(T + 1):
+        inp = dict(obs=u["obs"][:, t], avail=u["avail"][:, t], h_in=h, reset=np.full(B, t == 0, np.uint8),
+                   step_t=np.full(B, t, np.int32), epsilon=0.0, seed=1)
+        a = pu.gpu_act(net, cfg, inp)
+        np.testing.assert_allclose(a["q"], got["q_all"][:, t], atol=2e-5)
+        h = a["h_out"]
+    net.close()
+
+
+# ------------------------------------------------------------------ boundary behaviour on the device
+def test_empty_batches_and_argument_errors():
+    cfg = wl.config(0)
+    N, D, A, H = wl.dims(cfg)
+    net, _ = make_net(cfg)
+    other, _ = make_net(wl.config(1))
+    lib = binding.load()
+    import ctypes
+    hp = ctypes.c_void_p(net.handle)
+    assert lib.marl_act_step(hp, 0, None, None, None, None, None, 0.1, 0, None, None, None, None) == 0
+    assert lib.marl_unroll_td(hp, hp, 0, 5, None, None, None, None, None, None, 0.9, None, None, None, None, None) == 0
+    assert lib.marl_act_step(hp, -1, None, None, None, None, None, 0.1, 0, None, None, None, None) == -2
+    assert lib.marl_act_step(hp, 4, None, None, None, None, None, 0.1, 0, None, None, None, None) == -1
+    assert lib.marl_act_step(hp, 4, None, None, None, None, None, 1.5, 0, None, None, None, None) == -5
+    assert lib.marl_act_step(hp, 4, None, None, None, None, None, float("nan"), 0, None, None, None, None) == -5
+    assert lib.marl_unroll_td(hp, hp, 2, 0, None, None, None, None, None, None, 0.9, None, None, None, None, None) == -2
+    assert lib.marl_unroll_td(hp, hp, 2, 3, None, None, None, None, None, None, -0.1, None, None, None, None, None) == -5
+    assert lib.marl_unroll_td(hp, ctypes.c_void_p(other.handle), 2, 3, None, None, None, None, None, None, 0.9,
+                              None, None, None, None, None) == -4
+    d = binding.Desc()
+    assert lib.marl_qnet_get_desc(hp, ctypes.byref(d)) == 0 and (d.n_agents, d.obs_dim, d.n_actions, d.hidden) == (N, D, A, H)
+    with pytest.raises(ValueError):
+        net.act_step(torch.zeros(2, N, D), torch.zeros(2, N, A, dtype=torch.uint8), torch.zeros(2, N, H), None,
+                     torch.zeros(2, dtype=torch.int32), 0.0, 0, torch.zeros(2, N, H), torch.zeros(2, N, dtype=torch.int32))
+    net.close(); other.close()
