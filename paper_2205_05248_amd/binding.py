@@ -45,6 +45,9 @@ def load():
             raise FileNotFoundError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2205_05248_amd.build` "
                 "(there is no CPU fallback)")
+        # The library must share one HIP runtime with torch, whose tensors and streams it is
+        # handed: import torch first so that its libamdhip64 is the copy already in the process.
+        import torch  # noqa: F401
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, f32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_uint64
         lib.marl_param_count.restype = ctypes.c_size_t
