@@ -1,0 +1,290 @@
+// gfx950 kernels of the recurrent Q-network and their launchers.
+//
+//   act_step_kernel      decision step: every wavefront owns 32 (env, agent) rows and runs
+//                        fc1 -> GRU cell -> fc2 -> mask/argmax/epsilon-greedy without leaving
+//                        registers.
+//   input_proj_kernel    unroll, part 1: fc1 and the input half of the GRU gates for every
+//                        (episode, slot, agent); no dependence on the hidden state, so all
+//                        B (T+1) N rows run in parallel.  Results go to a scratch buffer in the
+//                        accumulator layout of the consumer.
+//   recurrent_td_kernel  unroll, part 2: one wavefront per 32 (episode, agent) rows walks the
+//                        T+1 slots with the hidden state in registers, adds the hidden half of
+//                        the gates, applies fc2 and emits q_taken / next_max / td_target.
+#include "mfma_tile.h"
+
+namespace marl {
+
+constexpr int kWavesPerGroup = 4;
+
+// Two waves per SIMD when the operand fragments of one row tile fit in 256 registers.
+#define MARL_WAVES_PER_EU(H, P) (((H) * (P) <= 128) ? 2 : 1)
+
+// ------------------------------------------------------------------------------------------ act-step
+template <int H, int P, int MB2>
+__global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void act_step_kernel(
+    NetFrags net, int rows, const float *__restrict__ obs, const uint8_t *__restrict__ avail, const float *h_in,
+    const uint8_t *__restrict__ reset, const int32_t *__restrict__ step_t, float epsilon, uint64_t seed,
+    float *h_out, int32_t *__restrict__ action, float *__restrict__ q_out)
+{
+    constexpr int FB = H / 32, KCH = H / 16;
+    const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
+    const int tile = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
+    if (tile * 32 >= rows) return;                       // whole wavefront leaves; no barriers below
+    const int row = tile * 32 + col;
+    const bool valid = row < rows;
+    const int N = net.N, D = net.D, A = net.A;
+    const int e = valid ? row / N : 0, n = valid ? row % N : 0;
+    const bool keep_h = valid && !(reset && reset[e]);
+    const float *h_row = h_in + (size_t)row * H;
+
+    // hidden state as operand fragments (the same k order as an accumulator leaves)
+    Frag<P> hf[KCH];
+#pragma unroll
+    for (int b = 0; b < FB; ++b) {
+        f32x16 hv;
+        if (keep_h) hv = load_feature_block(h_row, b, g);
+        else
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+        hf[2 * b] = frag_of_half<P>(hv, 0);
+        hf[2 * b + 1] = frag_of_half<P>(hv, 1);
+    }
+
+    Frag<P> x[KCH];
+    fc1_tile<H, P>(net, valid ? obs + (size_t)row * D : nullptr, n, lane, x);
+
+    Frag<P> hq[KCH];
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+        f32x16 ar, az, ain, ahn;
+        input_gates_block<H, P>(net, x, fb, lane, ar, az, ain);
+        hidden_gates_block<H, P>(net, hf, fb, lane, ar, az, ahn);
+        f32x16 hv;                                       // exact fp32 hidden state for the blend
+        if (keep_h) hv = load_feature_block(h_row, fb, g);
+        else
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+        const f32x16 hn = gru_blend(ar, az, ain, ahn, hv);
+        if (valid) store_feature_block(h_out + (size_t)row * H, fb, g, hn);
+        hq[2 * fb] = frag_of_half<P>(hn, 0);
+        hq[2 * fb + 1] = frag_of_half<P>(hn, 1);
+    }
+
+    f32x16 q[MB2];
+    fc2_tile<H, P, MB2>(net, hq, lane, q);
+    if (q_out && valid) store_q_row<MB2>(q_out + (size_t)row * A, q, A, lane);
+
+    float best_q; int best; uint64_t bits;
+    masked_argmax_row<MB2>(q, valid ? avail + (size_t)row * A : nullptr, A, lane, best_q, best, bits);
+    if (valid && g == 0) {
+        if (best < 0) best = 0;
+        action[row] = eps_greedy_pick(best, bits, epsilon, seed, (uint32_t)e, (uint32_t)n, (uint32_t)step_t[e]);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ unroll, part 1
+// Scratch layout, fp32: [row tile][slot][3 gates][H/32][64 lanes][16].
+template <int H, int P>
+__global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void input_proj_kernel(
+    NetFrags online, NetFrags target, float *__restrict__ gi_online, float *__restrict__ gi_target, int B, int T,
+    const float *__restrict__ obs)
+{
+    constexpr int FB = H / 32, KCH = H / 16;
+    const NetFrags &net = blockIdx.y ? target : online;
+    float *__restrict__ gi = blockIdx.y ? gi_target : gi_online;
+    const int lane = threadIdx.x & 63, col = lane & 31;
+    const int N = net.N, D = net.D;
+    const int rows = B * N, S = T + 1;
+    const int ntiles = (rows + 31) / 32;
+    const long work = (long)blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);     // (row tile, slot)
+    if (work >= (long)ntiles * S) return;
+    const int rt = (int)(work / S), t = (int)(work % S);
+    const int row = rt * 32 + col;
+    const bool valid = row < rows;
+    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+
+    Frag<P> x[KCH];
+    fc1_tile<H, P>(net, valid ? obs + (((size_t)b * S + t) * N + n) * D : nullptr, n, lane, x);
+
+    float *dst = gi + ((size_t)rt * S + t) * (3 * FB * 64 * 16) + (size_t)lane * 16;
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+        f32x16 ar, az, ain;
+        input_gates_block<H, P>(net, x, fb, lane, ar, az, ain);
+        *reinterpret_cast<f32x16 *>(dst + (size_t)(0 * FB + fb) * 1024) = ar;
+        *reinterpret_cast<f32x16 *>(dst + (size_t)(1 * FB + fb) * 1024) = az;
+        *reinterpret_cast<f32x16 *>(dst + (size_t)(2 * FB + fb) * 1024) = ain;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ unroll, part 2
+// grid = (row tiles, networks).  blockIdx.y = 0: online network, emits q_taken (and q_all);
+// blockIdx.y = 1 (distinct target network): emits next_max and td_target.  With one network a
+// single pass emits everything.
+template <int H, int P, int MB2>
+__global__ __launch_bounds__(64, 1) void recurrent_td_kernel(
+    NetFrags online, NetFrags target, const float *__restrict__ gi_online, const float *__restrict__ gi_target,
+    int two_nets, int B, int T, const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
+    const float *__restrict__ reward, const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled,
+    float gamma, float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target,
+    float *__restrict__ q_all)
+{
+    constexpr int FB = H / 32, KCH = H / 16;
+    const bool is_target = blockIdx.y == 1;
+    const NetFrags &net = is_target ? target : online;
+    const float *__restrict__ gi = is_target ? gi_target : gi_online;
+    const bool emit_online = !is_target, emit_target = is_target || !two_nets;
+    const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
+    const int N = net.N, A = net.A;
+    const int rows = B * N, S = T + 1;
+    const int rt = blockIdx.x;
+    const int row = rt * 32 + col;
+    const bool valid = row < rows;
+    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+
+    f32x16 h[FB];
+    Frag<P> hf[KCH];
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) h[fb][r] = 0.0f;
+        hf[2 * fb] = frag_of_half<P>(h[fb], 0);
+        hf[2 * fb + 1] = frag_of_half<P>(h[fb], 1);
+    }
+
+    for (int t = 0; t <= T; ++t) {
+        // The weight fragments do not fit in registers: keep the compiler from hoisting their
+        // loads out of the time loop (they come from L1/L2 every step).
+        asm volatile("" ::: "memory");
+        const float *src = gi + ((size_t)rt * S + t) * (3 * FB * 64 * 16) + (size_t)lane * 16;
+        Frag<P> hq[KCH];
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb) {
+            f32x16 ar = *reinterpret_cast<const f32x16 *>(src + (size_t)(0 * FB + fb) * 1024);
+            f32x16 az = *reinterpret_cast<const f32x16 *>(src + (size_t)(1 * FB + fb) * 1024);
+            const f32x16 ain = *reinterpret_cast<const f32x16 *>(src + (size_t)(2 * FB + fb) * 1024);
+            f32x16 ahn;
+            hidden_gates_block<H, P>(net, hf, fb, lane, ar, az, ahn);
+            h[fb] = gru_blend(ar, az, ain, ahn, h[fb]);
+            hq[2 * fb] = frag_of_half<P>(h[fb], 0);
+            hq[2 * fb + 1] = frag_of_half<P>(h[fb], 1);
+        }
+#pragma unroll
+        for (int kc = 0; kc < KCH; ++kc) hf[kc] = hq[kc];
+
+        f32x16 q[MB2];
+        fc2_tile<H, P, MB2>(net, hq, lane, q);
+
+        if (emit_online) {
+            if (q_all && valid) store_q_row<MB2>(q_all + (((size_t)b * S + t) * N + n) * A, q, A, lane);
+            if (t < T) {
+                const size_t bt = (size_t)b * T + t;
+                int u = valid ? actions[bt * N + n] : 0;
+                u = min(max(u, 0), A - 1);
+                const float qu = pick_action_value<MB2>(q, u, lane);
+                if (valid && g == 0) q_taken[bt * N + n] = filled[bt] ? qu : 0.0f;
+            }
+        }
+        if (emit_target && t >= 1) {
+            float best_q; int best; uint64_t bits;
+            masked_argmax_row<MB2>(q, valid ? avail + (((size_t)b * S + t) * N + n) * A : nullptr, A, lane, best_q,
+                                   best, bits);
+            if (valid && g == 0) {
+                const size_t bt = (size_t)b * T + (t - 1);
+                const float keep = terminated[bt] ? 0.0f : 1.0f;
+                const float y = reward[bt] + gamma * keep * best_q;
+                const bool f = filled[bt] != 0;
+                next_max[bt * N + n] = f ? best_q : 0.0f;
+                td_target[bt * N + n] = f ? y : 0.0f;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ launchers
+namespace {
+
+template <int H, int P>
+hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const uint8_t *avail, const float *h_in,
+                        const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
+                        int32_t *action, float *q_out, hipStream_t stream)
+{
+    const int tiles = (rows + 31) / 32;
+    const dim3 grid((unsigned)((tiles + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
+    if (net.mb2 == 1)
+        hipLaunchKernelGGL((act_step_kernel<H, P, 1>), grid, block, 0, stream, net, rows, obs, avail, h_in, reset,
+                           step_t, epsilon, seed, h_out, action, q_out);
+    else
+        hipLaunchKernelGGL((act_step_kernel<H, P, 2>), grid, block, 0, stream, net, rows, obs, avail, h_in, reset,
+                           step_t, epsilon, seed, h_out, action, q_out);
+    return hipGetLastError();
+}
+
+template <int H, int P>
+hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, float *gi_on, float *gi_tg,
+                           int B, int T, const float *obs, const uint8_t *avail, const int32_t *actions,
+                           const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
+                           float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream)
+{
+    const int rows = B * online.N, tiles = (rows + 31) / 32;
+    const long work = (long)tiles * (T + 1);
+    const unsigned nets = two_nets ? 2u : 1u;
+    {
+        const dim3 grid((unsigned)((work + kWavesPerGroup - 1) / kWavesPerGroup), nets), block(64 * kWavesPerGroup);
+        hipLaunchKernelGGL((input_proj_kernel<H, P>), grid, block, 0, stream, online, target, gi_on, gi_tg, B, T, obs);
+        hipError_t err = hipGetLastError();
+        if (err != hipSuccess) return err;
+    }
+    const dim3 grid((unsigned)tiles, nets), block(64);
+    const int two = two_nets ? 1 : 0;
+    if (online.mb2 == 1)
+        hipLaunchKernelGGL((recurrent_td_kernel<H, P, 1>), grid, block, 0, stream, online, target, gi_on, gi_tg, two, B,
+                           T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);
+    else
+        hipLaunchKernelGGL((recurrent_td_kernel<H, P, 2>), grid, block, 0, stream, online, target, gi_on, gi_tg, two, B,
+                           T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const uint8_t *avail, const float *h_in,
+                           const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
+                           int32_t *action, float *q_out, hipStream_t stream)
+{
+    const int rows = E * net.N;
+#define MARL_ACT(HH, PP) \
+    return act_dispatch<HH, PP>(net, rows, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream)
+    if (net.H == 64 && net.planes == 2) MARL_ACT(64, 2);
+    if (net.H == 64 && net.planes == 1) MARL_ACT(64, 1);
+    if (net.H == 128 && net.planes == 2) MARL_ACT(128, 2);
+    if (net.H == 128 && net.planes == 1) MARL_ACT(128, 1);
+#undef MARL_ACT
+    return hipErrorInvalidValue;
+}
+
+size_t unroll_scratch_bytes(const NetFrags &net, int B, int T)
+{
+    const size_t tiles = ((size_t)B * net.N + 31) / 32;
+    return tiles * (size_t)(T + 1) * 3 * net.H * 32 * sizeof(float);
+}
+
+hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
+                            void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
+                            const int32_t *actions, const float *reward, const uint8_t *terminated,
+                            const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
+                            float *q_all, hipStream_t stream)
+{
+    float *gi_on = static_cast<float *>(scratch_online), *gi_tg = static_cast<float *>(scratch_target);
+#define MARL_UNROLL(HH, PP)                                                                                        \
+    return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, obs, avail, actions, reward,      \
+                                   terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream)
+    if (online.H == 64 && online.planes == 2) MARL_UNROLL(64, 2);
+    if (online.H == 64 && online.planes == 1) MARL_UNROLL(64, 1);
+    if (online.H == 128 && online.planes == 2) MARL_UNROLL(128, 2);
+    if (online.H == 128 && online.planes == 1) MARL_UNROLL(128, 1);
+#undef MARL_UNROLL
+    return hipErrorInvalidValue;
+}
+
+}  // namespace marl

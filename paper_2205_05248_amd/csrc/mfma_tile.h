@@ -1,0 +1,253 @@
+// Wave-level building blocks: one wavefront evaluates the network for a tile of
+// 32 (env, agent) rows with 32x32x16 bf16 MFMAs.  Weights are the A operand
+// (32 output features x 16 k), activations the B operand (16 k x 32 rows), so an
+// accumulator holds [32 features x 32 rows] and lane l owns row l % 32.  Because
+// both lanes l and l + 32 of a row keep whole groups of four consecutive
+// features, a result is converted to the next layer's B operand in registers
+// (the weight fragments are stored in the matching k order).
+//
+// P = 1: bf16 weights, activations rounded to bf16, fp32 accumulation.
+// P = 2: fp32 weights and activations, each split into a bf16 high part and the
+//        bf16 of the remainder; products hi*hi + hi*lo + lo*hi in fp32
+//        accumulators (error about 2^-16 relative per product).
+#pragma once
+#include "device_math.h"
+#include "qnet_internal.h"
+
+namespace marl {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int P> struct Frag;
+template <> struct Frag<1> { bf16x8 hi; };
+template <> struct Frag<2> { bf16x8 hi, lo; };
+
+template <int P>
+__device__ __forceinline__ Frag<P> to_frag(const float (&v)[8])
+{
+    Frag<P> f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f.hi[i] = (__bf16)v[i];
+    if constexpr (P == 2) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) f.lo[i] = (__bf16)(v[i] - (float)f.hi[i]);
+    }
+    return f;
+}
+
+// Values r = 8c .. 8c+7 of an accumulator block become k-chunk 2*block + c of the next operand.
+template <int P>
+__device__ __forceinline__ Frag<P> frag_of_half(const f32x16 &acc, int c)
+{
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v[i] = c ? acc[8 + i] : acc[i];
+    return to_frag<P>(v);
+}
+
+// acc += Wfrag * b ; `a` points at this lane's 16 bytes of plane 0 of the fragment.
+template <int P>
+__device__ __forceinline__ void mma(f32x16 &acc, const bf16x8 *__restrict__ a, const Frag<P> &b)
+{
+    const bf16x8 ah = a[0];
+    if constexpr (P == 2) {
+        const bf16x8 al = a[64];
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b.hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b.lo, acc, 0, 0, 0);
+    }
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b.hi, acc, 0, 0, 0);
+}
+
+// Feature held in accumulator slot r of block `blk` by a lane of half g: 32 blk + 8 (r / 4) + 4 g + r % 4.
+// The four slots 4j .. 4j+3 are consecutive features, so per-feature tables load as float4.
+__device__ __forceinline__ f32x16 load_feature_block(const float *__restrict__ table, int blk, int g)
+{
+    f32x16 v;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(table + 32 * blk + 8 * j + 4 * g);
+        v[4 * j + 0] = t[0]; v[4 * j + 1] = t[1]; v[4 * j + 2] = t[2]; v[4 * j + 3] = t[3];
+    }
+    return v;
+}
+
+__device__ __forceinline__ void store_feature_block(float *dst, int blk, int g, const f32x16 &v)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        f32x4 t = {v[4 * j + 0], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+        *reinterpret_cast<f32x4 *>(dst + 32 * blk + 8 * j + 4 * g) = t;
+    }
+}
+
+// Eight observation values 16 kc + 8 g + (0..7) of one row, zero beyond D or for a missing row.
+__device__ __forceinline__ void load_obs_chunk(const float *__restrict__ row, int D, bool vec4, int kc, int g, float (&v)[8])
+{
+    const int k0 = 16 * kc + 8 * g;
+    if (vec4) {   // D % 4 == 0 and the row is 16-byte aligned: whole float4s are in or out of range
+        f32x4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+        if (row && k0 < D) a = *reinterpret_cast<const f32x4 *>(row + k0);
+        if (row && k0 + 4 < D) b = *reinterpret_cast<const f32x4 *>(row + k0 + 4);
+        v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
+        v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[i] = (row && k0 + i < D) ? row[k0 + i] : 0.0f;
+    }
+}
+
+// fc1 + ReLU for the wave's 32 rows.  obs_row: this lane's row (nullptr if the row does not exist).
+template <int H, int P>
+__device__ __forceinline__ void fc1_tile(const NetFrags &net, const float *__restrict__ obs_row, int agent, int lane,
+                                         Frag<P> (&x)[H / 16])
+{
+    constexpr int MB = H / 32;
+    const int g = lane >> 5;
+    const int KC = net.kc1, D = net.D;
+    const bool vec4 = (D % 4) == 0 && (reinterpret_cast<uintptr_t>(obs_row) & 15u) == 0;
+    f32x16 acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = load_feature_block(net.bias1 + (size_t)agent * H, mb, g);
+
+    const bf16x8 *wf = net.w1 + lane;
+    float cur[8], nxt[8];
+    load_obs_chunk(obs_row, D, vec4, 0, g, cur);
+    for (int kc = 0; kc < KC; ++kc) {
+        if (kc + 1 < KC) load_obs_chunk(obs_row, D, vec4, kc + 1, g, nxt);
+        const Frag<P> b = to_frag<P>(cur);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) mma<P>(acc[mb], wf + (size_t)(mb * KC + kc) * P * 64, b);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
+    }
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] = fmaxf(acc[mb][r], 0.0f);
+        x[2 * mb] = frag_of_half<P>(acc[mb], 0);
+        x[2 * mb + 1] = frag_of_half<P>(acc[mb], 1);
+    }
+}
+
+// Input projection of the GRU for one hidden block: gi_r (+ both r biases), gi_z (+ both z biases), gi_n (+ b_in).
+template <int H, int P>
+__device__ __forceinline__ void input_gates_block(const NetFrags &net, const Frag<P> (&x)[H / 16], int fb, int lane,
+                                                  f32x16 &ar, f32x16 &az, f32x16 &ain)
+{
+    constexpr int FB = H / 32, KCH = H / 16;
+    const int g = lane >> 5;
+    ar = load_feature_block(net.bias_r, fb, g);
+    az = load_feature_block(net.bias_z, fb, g);
+    ain = load_feature_block(net.bias_in, fb, g);
+    const bf16x8 *wi = net.wih + lane;
+#pragma unroll
+    for (int kc = 0; kc < KCH; ++kc) {
+        mma<P>(ar, wi + (size_t)((0 * FB + fb) * KCH + kc) * P * 64, x[kc]);
+        mma<P>(az, wi + (size_t)((1 * FB + fb) * KCH + kc) * P * 64, x[kc]);
+        mma<P>(ain, wi + (size_t)((2 * FB + fb) * KCH + kc) * P * 64, x[kc]);
+    }
+}
+
+// Hidden projection added on top: ar += W_hr h, az += W_hz h, ahn = b_hn + W_hn h.
+template <int H, int P>
+__device__ __forceinline__ void hidden_gates_block(const NetFrags &net, const Frag<P> (&hf)[H / 16], int fb, int lane,
+                                                   f32x16 &ar, f32x16 &az, f32x16 &ahn)
+{
+    constexpr int FB = H / 32, KCH = H / 16;
+    const int g = lane >> 5;
+    ahn = load_feature_block(net.bias_hn, fb, g);
+    const bf16x8 *wh = net.whh + lane;
+#pragma unroll
+    for (int kc = 0; kc < KCH; ++kc) {
+        mma<P>(ar, wh + (size_t)((0 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
+        mma<P>(az, wh + (size_t)((1 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
+        mma<P>(ahn, wh + (size_t)((2 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
+    }
+}
+
+// h' = (1 - z) * n + z * h on one block of 16 slots.
+__device__ __forceinline__ f32x16 gru_blend(const f32x16 &ar, const f32x16 &az, const f32x16 &ain, const f32x16 &ahn,
+                                            const f32x16 &h)
+{
+    f32x16 out;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const float rr = sigmoidf_fast(ar[r]), zz = sigmoidf_fast(az[r]);
+        const float nn = tanhf_fast(ain[r] + rr * ahn[r]);
+        out[r] = (1.0f - zz) * nn + zz * h[r];
+    }
+    return out;
+}
+
+// Q = W2 h' + b2: MB2 blocks of 32 actions (rows beyond A are zero weights).
+template <int H, int P, int MB2>
+__device__ __forceinline__ void fc2_tile(const NetFrags &net, const Frag<P> (&hq)[H / 16], int lane, f32x16 (&q)[MB2])
+{
+    constexpr int KCH = H / 16;
+    const int g = lane >> 5;
+    const bf16x8 *w2 = net.w2 + lane;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb) {
+        q[mb] = load_feature_block(net.b2, mb, g);
+#pragma unroll
+        for (int kc = 0; kc < KCH; ++kc) mma<P>(q[mb], w2 + (size_t)(mb * KCH + kc) * P * 64, hq[kc]);
+    }
+}
+
+// A row's Q values are split over lanes l and l ^ 32.  Masked maximum with the lowest index on ties;
+// returns the availability bits of the whole row.  idx = -1 when nothing is available.
+template <int MB2>
+__device__ __forceinline__ void masked_argmax_row(const f32x16 (&q)[MB2], const uint8_t *__restrict__ avail_row,
+                                                  int A, int lane, float &best_q, int &best_idx, uint64_t &bits)
+{
+    const int g = lane >> 5;
+    best_q = 0.0f; best_idx = -1; bits = 0;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int a = 32 * mb + 8 * (r / 4) + 4 * g + (r % 4);
+            if (avail_row && a < A && avail_row[a]) {
+                bits |= 1ull << a;
+                if (best_idx < 0 || q[mb][r] > best_q) { best_q = q[mb][r]; best_idx = a; }
+            }
+        }
+    const float oq = __shfl_xor(best_q, 32);
+    const int oi = __shfl_xor(best_idx, 32);
+    const uint32_t olo = __shfl_xor((uint32_t)bits, 32), ohi = __shfl_xor((uint32_t)(bits >> 32), 32);
+    bits |= ((uint64_t)ohi << 32) | olo;
+    if (oi >= 0 && (best_idx < 0 || oq > best_q || (oq == best_q && oi < best_idx))) { best_q = oq; best_idx = oi; }
+}
+
+// Q value of action u of this lane's row (the owner lane has it; the pair is summed).
+template <int MB2>
+__device__ __forceinline__ float pick_action_value(const f32x16 (&q)[MB2], int u, int lane)
+{
+    const int g = lane >> 5;
+    float v = 0.0f;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int a = 32 * mb + 8 * (r / 4) + 4 * g + (r % 4);
+            v = (a == u) ? q[mb][r] : v;
+        }
+    return v + __shfl_xor(v, 32);
+}
+
+// Store this lane's share of a row of Q ([A] floats at q_row).
+template <int MB2>
+__device__ __forceinline__ void store_q_row(float *__restrict__ q_row, const f32x16 (&q)[MB2], int A, int lane)
+{
+    const int g = lane >> 5;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int a = 32 * mb + 8 * (r / 4) + 4 * g + (r % 4);
+            if (a < A) q_row[a] = q[mb][r];
+        }
+}
+
+}  // namespace marl

@@ -1,0 +1,80 @@
+// Internal definitions shared by the host code and the gfx950 kernels of the
+// recurrent Q-network library: the handle, and the device-side view of one
+// network whose matrices are stored as MFMA operand fragments.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/marl_qnet.h"
+
+namespace marl {
+
+// 8 bf16 values = the per-lane share of one 32x16 MFMA operand.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+// Fragment storage.  A matrix W[M][K] (M padded to 32, K padded to 16) is cut
+// into fragments of 32 rows x 16 k.  Fragment (mb, kc) holds, for lane l
+// (g = l / 32, m = l % 32) and idx = 0..7, W[32 mb + m][perm(16 kc + 8 g + idx)].
+// A fragment is P planes (P = 1: the bf16 value; P = 2: bf16 high part, then the
+// bf16 of the remainder) of 64 lanes x 8 bf16 = 1 KiB each, planes adjacent.
+//
+// perm is the identity for the first layer (its input is the observation) and
+//   permC(16 kc + 8 g + idx) = 16 kc + 8 (idx / 4) + 4 g + idx % 4
+// for layers fed by an MFMA result: that is where the 32x32 accumulator layout
+// leaves feature values, so a result converts to the next operand in registers.
+struct NetFrags {
+    const bf16x8 *w1;     // [H/32][kc1][P][64]
+    const bf16x8 *wih;    // [3][H/32][H/16][P][64]   gates r, z, n
+    const bf16x8 *whh;    // [3][H/32][H/16][P][64]
+    const bf16x8 *w2;     // [mb2][H/16][P][64]
+    const float *bias1;   // [N][H]   b1 + W1[:, D + n]
+    const float *bias_r;  // [H]      b_ir + b_hr
+    const float *bias_z;  // [H]      b_iz + b_hz
+    const float *bias_in; // [H]
+    const float *bias_hn; // [H]
+    const float *b2;      // [32 mb2] zero padded
+    int N, D, A, H;
+    int kc1;              // ceil(D / 16)
+    int mb2;              // ceil(A / 32)
+    int planes;           // P
+};
+
+}  // namespace marl
+
+struct marl_qnet {
+    marl_qnet_desc desc;
+    size_t n_params;
+    void *dev_weights;        // one allocation holding every fragment array and bias table
+    size_t dev_weight_bytes;
+    marl::NetFrags net;
+    void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
+    size_t scratch_bytes;
+};
+
+namespace marl {
+
+// Host: build the device image of a network from packed fp32 weights.
+// Returns bytes; fills `image` (host) and offsets into `net` relative to base 0.
+struct PackedImage {
+    void *host;        // malloc'ed image, caller frees
+    size_t bytes;
+    size_t off_w1, off_wih, off_whh, off_w2, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    int kc1, mb2, planes;
+};
+bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
+
+// Launchers (kernels.hip).  All enqueue on `stream` and return the HIP status.
+hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const uint8_t *avail, const float *h_in,
+                           const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
+                           int32_t *action, float *q_out, hipStream_t stream);
+
+size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
+
+hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
+                            void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
+                            const int32_t *actions, const float *reward, const uint8_t *terminated,
+                            const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
+                            float *q_all, hipStream_t stream);
+
+}  // namespace marl
