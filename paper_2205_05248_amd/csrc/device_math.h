@@ -7,10 +7,21 @@
 
 namespace marl {
 
-__device__ __forceinline__ float sigmoidf_fast(float v) { return 1.0f / (1.0f + __expf(-v)); }
+// Gate non-linearities on the hardware exp2 / reciprocal units (about 1 ulp each).
+// exp2 overflowing to +inf gives rcp = 0 and underflowing to 0 gives rcp(1) = 1, so both
+// functions saturate cleanly for large |v|.
+constexpr float kLog2e = 1.4426950408889634f;
 
-// tanh(v) = 1 - 2 / (1 + e^{2v}); absolute error ~1e-7, saturates cleanly for |v| large.
-__device__ __forceinline__ float tanhf_fast(float v) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * v)); }
+__device__ __forceinline__ float sigmoidf_fast(float v)
+{
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-kLog2e * v));
+}
+
+// tanh(v) = 1 - 2 / (1 + e^{2v}); absolute error about 1e-7.
+__device__ __forceinline__ float tanhf_fast(float v)
+{
+    return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.0f * kLog2e * v)), 1.0f);
+}
 
 // SplitMix64 (Steele, Lea, Flood 2014): state += golden gamma, then the 64-bit finaliser.
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ull;

@@ -83,7 +83,19 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
 }
 
 // ------------------------------------------------------------------------------------------ unroll, part 1
-// Scratch layout, fp32: [row tile][slot][3 gates][H/32][64 lanes][16].
+// Scratch layout, fp32: [row tile][slot][3 gates][H/32][4][64 lanes][4]: accumulator slots
+// 4j .. 4j+3 of lane l are the float4 at [..][j][l], so every wave-wide access is 1 KiB contiguous.
+constexpr int kGiPiece = 64 * 4;   // floats per [j] piece
+
+__device__ __forceinline__ void store_gi_block(float *__restrict__ dst, int lane, const f32x16 &v)
+{
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const f32x4 t = {v[4 * j + 0], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+        *reinterpret_cast<f32x4 *>(dst + j * kGiPiece + lane * 4) = t;
+    }
+}
+
 template <int H, int P>
 __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void input_proj_kernel(
     NetFrags online, NetFrags target, float *__restrict__ gi_online, float *__restrict__ gi_target, int B, int T,
@@ -106,97 +118,217 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
     Frag<P> x[KCH];
     fc1_tile<H, P>(net, valid ? obs + (((size_t)b * S + t) * N + n) * D : nullptr, n, lane, x);
 
-    float *dst = gi + ((size_t)rt * S + t) * (3 * FB * 64 * 16) + (size_t)lane * 16;
+    float *dst = gi + ((size_t)rt * S + t) * (3 * FB * 1024);
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {
         f32x16 ar, az, ain;
         input_gates_block<H, P>(net, x, fb, lane, ar, az, ain);
-        *reinterpret_cast<f32x16 *>(dst + (size_t)(0 * FB + fb) * 1024) = ar;
-        *reinterpret_cast<f32x16 *>(dst + (size_t)(1 * FB + fb) * 1024) = az;
-        *reinterpret_cast<f32x16 *>(dst + (size_t)(2 * FB + fb) * 1024) = ain;
+        store_gi_block(dst + (size_t)(0 * FB + fb) * 1024, lane, ar);
+        store_gi_block(dst + (size_t)(1 * FB + fb) * 1024, lane, az);
+        store_gi_block(dst + (size_t)(2 * FB + fb) * 1024, lane, ain);
     }
 }
 
 // ------------------------------------------------------------------------------------------ unroll, part 2
+// One workgroup per 32 (episode, agent) rows and network; its wavefronts have three roles:
+//   compute wave w (w < H/32)  owns hidden units 32w .. 32w+31: its slice of W_hh stays in
+//                              registers for the whole episode; each slot it reads the full
+//                              hidden state (operand form) and its gate inputs from LDS, does
+//                              the hidden projection, the gates, and publishes its 32 new units.
+//   epilogue wave              one slot behind: fc2 on the published hidden state (W2 in
+//                              registers), then q_taken / masked max / TD target.
+//   prefetch waves             copy the gate inputs of the next slots from the scratch buffer
+//                              into LDS, one slot ahead in LDS and one more in registers.
+// All waves meet at one barrier per slot; LDS buffers are double-buffered across it.
+//
 // grid = (row tiles, networks).  blockIdx.y = 0: online network, emits q_taken (and q_all);
 // blockIdx.y = 1 (distinct target network): emits next_max and td_target.  With one network a
 // single pass emits everything.
+template <int H> struct RecurrentShape {
+    static constexpr int kCompute = H / 32;
+    static constexpr int kPrefetch = H == 128 ? 3 : 1;
+    static constexpr int kWaves = kCompute + 1 + kPrefetch;
+    static constexpr int kGiFloats = 3 * (H / 32) * 1024;                // per (tile, slot)
+    static constexpr int kVecPerLane = kGiFloats / 4 / 64 / kPrefetch;   // float4 per prefetch lane and slot
+};
+
 template <int H, int P, int MB2>
-__global__ __launch_bounds__(64, 1) void recurrent_td_kernel(
+__global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_td_kernel(
     NetFrags online, NetFrags target, const float *__restrict__ gi_online, const float *__restrict__ gi_target,
     int two_nets, int B, int T, const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
     const float *__restrict__ reward, const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled,
     float gamma, float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target,
     float *__restrict__ q_all)
 {
+    using Shape = RecurrentShape<H>;
     constexpr int FB = H / 32, KCH = H / 16;
+    __shared__ __attribute__((aligned(16))) float gi_lds[2][Shape::kGiFloats];
+    __shared__ bf16x8 h_lds[2][KCH][P][64];
+
     const bool is_target = blockIdx.y == 1;
     const NetFrags &net = is_target ? target : online;
     const float *__restrict__ gi = is_target ? gi_target : gi_online;
-    const bool emit_online = !is_target, emit_target = is_target || !two_nets;
     const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
-    const int N = net.N, A = net.A;
-    const int rows = B * N, S = T + 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int S = T + 1;
     const int rt = blockIdx.x;
-    const int row = rt * 32 + col;
-    const bool valid = row < rows;
-    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+    const float *gi_tile = gi + (size_t)rt * S * Shape::kGiFloats;
 
-    f32x16 h[FB];
-    Frag<P> hf[KCH];
+    if (wave < Shape::kCompute) {
+        // ---------------------------------------------------------------- compute wave
+        const int fb = wave;
+        bf16x8 w[3][KCH][P];
 #pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
+        for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) h[fb][r] = 0.0f;
-        hf[2 * fb] = frag_of_half<P>(h[fb], 0);
-        hf[2 * fb + 1] = frag_of_half<P>(h[fb], 1);
-    }
-
-    for (int t = 0; t <= T; ++t) {
-        // The weight fragments do not fit in registers: keep the compiler from hoisting their
-        // loads out of the time loop (they come from L1/L2 every step).
-        asm volatile("" ::: "memory");
-        const float *src = gi + ((size_t)rt * S + t) * (3 * FB * 64 * 16) + (size_t)lane * 16;
-        Frag<P> hq[KCH];
+            for (int kc = 0; kc < KCH; ++kc)
 #pragma unroll
-        for (int fb = 0; fb < FB; ++fb) {
-            f32x16 ar = *reinterpret_cast<const f32x16 *>(src + (size_t)(0 * FB + fb) * 1024);
-            f32x16 az = *reinterpret_cast<const f32x16 *>(src + (size_t)(1 * FB + fb) * 1024);
-            const f32x16 ain = *reinterpret_cast<const f32x16 *>(src + (size_t)(2 * FB + fb) * 1024);
-            f32x16 ahn;
-            hidden_gates_block<H, P>(net, hf, fb, lane, ar, az, ahn);
-            h[fb] = gru_blend(ar, az, ain, ahn, h[fb]);
-            hq[2 * fb] = frag_of_half<P>(h[fb], 0);
-            hq[2 * fb + 1] = frag_of_half<P>(h[fb], 1);
-        }
+                for (int p = 0; p < P; ++p) w[gate][kc][p] = net.whh[((size_t)((gate * FB + fb) * KCH + kc) * P + p) * 64 + lane];
+        const f32x16 bias_hn = load_feature_block(net.bias_hn, fb, g);
+        f32x16 h;
 #pragma unroll
-        for (int kc = 0; kc < KCH; ++kc) hf[kc] = hq[kc];
-
-        f32x16 q[MB2];
-        fc2_tile<H, P, MB2>(net, hq, lane, q);
-
-        if (emit_online) {
-            if (q_all && valid) store_q_row<MB2>(q_all + (((size_t)b * S + t) * N + n) * A, q, A, lane);
-            if (t < T) {
-                const size_t bt = (size_t)b * T + t;
-                int u = valid ? actions[bt * N + n] : 0;
-                u = min(max(u, 0), A - 1);
-                const float qu = pick_action_value<MB2>(q, u, lane);
-                if (valid && g == 0) q_taken[bt * N + n] = filled[bt] ? qu : 0.0f;
+        for (int r = 0; r < 16; ++r) h[r] = 0.0f;
+        {
+            const Frag<P> z0 = frag_of_half<P>(h, 0);
+#pragma unroll
+            for (int c = 0; c < 2; ++c) {
+                h_lds[0][2 * fb + c][0][lane] = z0.hi;
+                if constexpr (P == 2) h_lds[0][2 * fb + c][1][lane] = z0.lo;
             }
         }
-        if (emit_target && t >= 1) {
-            float best_q; int best; uint64_t bits;
-            masked_argmax_row<MB2>(q, valid ? avail + (((size_t)b * S + t) * N + n) * A : nullptr, A, lane, best_q,
-                                   best, bits);
-            if (valid && g == 0) {
-                const size_t bt = (size_t)b * T + (t - 1);
-                const float keep = terminated[bt] ? 0.0f : 1.0f;
-                const float y = reward[bt] + gamma * keep * best_q;
-                const bool f = filled[bt] != 0;
-                next_max[bt * N + n] = f ? best_q : 0.0f;
-                td_target[bt * N + n] = f ? y : 0.0f;
+        __syncthreads();
+        for (int it = 0; it <= T + 1; ++it) {
+            if (it <= T) {
+                const int cur = it & 1;
+                f32x16 acc[3];
+#pragma unroll
+                for (int gate = 0; gate < 2; ++gate)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const f32x4 v = *reinterpret_cast<const f32x4 *>(&gi_lds[cur][(gate * FB + fb) * 1024 + j * kGiPiece + lane * 4]);
+                        acc[gate][4 * j + 0] = v[0]; acc[gate][4 * j + 1] = v[1]; acc[gate][4 * j + 2] = v[2]; acc[gate][4 * j + 3] = v[3];
+                    }
+                acc[2] = bias_hn;
+#pragma unroll
+                for (int kc = 0; kc < KCH; ++kc) {
+                    Frag<P> hb;
+                    hb.hi = h_lds[cur][kc][0][lane];
+                    if constexpr (P == 2) hb.lo = h_lds[cur][kc][1][lane];
+#pragma unroll
+                    for (int gate = 0; gate < 3; ++gate) {
+                        if constexpr (P == 2) {
+                            acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][1], hb.hi, acc[gate], 0, 0, 0);
+                            acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][0], hb.lo, acc[gate], 0, 0, 0);
+                        }
+                        acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][0], hb.hi, acc[gate], 0, 0, 0);
+                    }
+                }
+                f32x16 ain;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(&gi_lds[cur][(2 * FB + fb) * 1024 + j * kGiPiece + lane * 4]);
+                    ain[4 * j + 0] = v[0]; ain[4 * j + 1] = v[1]; ain[4 * j + 2] = v[2]; ain[4 * j + 3] = v[3];
+                }
+                h = gru_blend(acc[0], acc[1], ain, acc[2], h);
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const Frag<P> f = frag_of_half<P>(h, c);
+                    h_lds[cur ^ 1][2 * fb + c][0][lane] = f.hi;
+                    if constexpr (P == 2) h_lds[cur ^ 1][2 * fb + c][1][lane] = f.lo;
+                }
             }
+            __syncthreads();
+        }
+    } else if (wave == Shape::kCompute) {
+        // ---------------------------------------------------------------- epilogue wave
+        const bool emit_online = !is_target, emit_target = is_target || !two_nets;
+        const int N = net.N, A = net.A;
+        const int rows = B * N;
+        const int row = rt * 32 + col;
+        const bool valid = row < rows;
+        const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+        bf16x8 w2[MB2][KCH][P];
+#pragma unroll
+        for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc)
+#pragma unroll
+                for (int p = 0; p < P; ++p) w2[mb][kc][p] = net.w2[((size_t)(mb * KCH + kc) * P + p) * 64 + lane];
+        f32x16 b2[MB2];
+#pragma unroll
+        for (int mb = 0; mb < MB2; ++mb) b2[mb] = load_feature_block(net.b2, mb, g);
+        __syncthreads();
+        for (int it = 0; it <= T + 1; ++it) {
+            if (it >= 1) {
+                const int t = it - 1, cur = it & 1;          // h_t was published during iteration t
+                f32x16 q[MB2];
+#pragma unroll
+                for (int mb = 0; mb < MB2; ++mb) q[mb] = b2[mb];
+#pragma unroll
+                for (int kc = 0; kc < KCH; ++kc) {
+                    Frag<P> hb;
+                    hb.hi = h_lds[cur][kc][0][lane];
+                    if constexpr (P == 2) hb.lo = h_lds[cur][kc][1][lane];
+#pragma unroll
+                    for (int mb = 0; mb < MB2; ++mb) {
+                        if constexpr (P == 2) {
+                            q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][1], hb.hi, q[mb], 0, 0, 0);
+                            q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][0], hb.lo, q[mb], 0, 0, 0);
+                        }
+                        q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][0], hb.hi, q[mb], 0, 0, 0);
+                    }
+                }
+                if (emit_online) {
+                    if (q_all && valid) store_q_row<MB2>(q_all + (((size_t)b * S + t) * N + n) * A, q, A, lane);
+                    if (t < T) {
+                        const size_t bt = (size_t)b * T + t;
+                        int u = valid ? actions[bt * N + n] : 0;
+                        u = min(max(u, 0), A - 1);
+                        const float qu = pick_action_value<MB2>(q, u, lane);
+                        if (valid && g == 0) q_taken[bt * N + n] = filled[bt] ? qu : 0.0f;
+                    }
+                }
+                if (emit_target && t >= 1) {
+                    float best_q; int best; uint64_t bits;
+                    masked_argmax_row<MB2>(q, valid ? avail + (((size_t)b * S + t) * N + n) * A : nullptr, A, lane,
+                                           best_q, best, bits);
+                    if (valid && g == 0) {
+                        const size_t bt = (size_t)b * T + (t - 1);
+                        const float keep = terminated[bt] ? 0.0f : 1.0f;
+                        const float y = reward[bt] + gamma * keep * best_q;
+                        const bool f = filled[bt] != 0;
+                        next_max[bt * N + n] = f ? best_q : 0.0f;
+                        td_target[bt * N + n] = f ? y : 0.0f;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    } else {
+        // ---------------------------------------------------------------- prefetch wave
+        constexpr int V = Shape::kVecPerLane;
+        const int p = wave - Shape::kCompute - 1;
+        const int base = (p * V * 64 + lane) * 4;                        // float offset of this lane's first float4
+        f32x4 stage[V];
+        auto fetch = [&](int slot) {
+            const float *src = gi_tile + (size_t)slot * Shape::kGiFloats + base;
+#pragma unroll
+            for (int i = 0; i < V; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(src + i * 256);
+        };
+        auto publish = [&](int buf) {
+#pragma unroll
+            for (int i = 0; i < V; ++i) *reinterpret_cast<f32x4 *>(&gi_lds[buf][base + i * 256]) = stage[i];
+        };
+        fetch(0);
+        publish(0);
+        if (T >= 1) fetch(1);
+        __syncthreads();
+        for (int it = 0; it <= T + 1; ++it) {
+            if (it + 1 <= T) {
+                publish((it + 1) & 1);
+                if (it + 2 <= T) fetch(it + 2);
+            }
+            __syncthreads();
         }
     }
 }
@@ -235,7 +367,7 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
     }
-    const dim3 grid((unsigned)tiles, nets), block(64);
+    const dim3 grid((unsigned)tiles, nets), block(64 * RecurrentShape<H>::kWaves);
     const int two = two_nets ? 1 : 0;
     if (online.mb2 == 1)
         hipLaunchKernelGGL((recurrent_td_kernel<H, P, 1>), grid, block, 0, stream, online, target, gi_on, gi_tg, two, B,

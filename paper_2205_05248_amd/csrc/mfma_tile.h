@@ -175,7 +175,7 @@ __device__ __forceinline__ f32x16 gru_blend(const f32x16 &ar, const f32x16 &az, 
     for (int r = 0; r < 16; ++r) {
         const float rr = sigmoidf_fast(ar[r]), zz = sigmoidf_fast(az[r]);
         const float nn = tanhf_fast(ain[r] + rr * ahn[r]);
-        out[r] = (1.0f - zz) * nn + zz * h[r];
+        out[r] = fmaf(zz, h[r] - nn, nn);            // (1 - z) n + z h
     }
     return out;
 }
