@@ -36,6 +36,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
     const int e = valid ? row / N : 0, n = valid ? row % N : 0;
     const bool keep_h = valid && !(reset && reset[e]);
     const float *h_row = h_in + (size_t)row * H;
+    const uint8_t *avail_row = avail + (valid ? (size_t)row * A : 0);
+    uint32_t avail_raw[MB2 * 4];
+    if (A >= 4) issue_avail_loads<MB2>(avail_row, A, lane, avail_raw);      // consumed after fc2
 
     // hidden state as operand fragments (the same k order as an accumulator leaves)
     Frag<P> hf[KCH];
@@ -74,8 +77,11 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
     fc2_tile<H, P, MB2>(net, hq, lane, q);
     if (q_out && valid) store_q_row<MB2>(q_out + (size_t)row * A, q, A, lane);
 
-    float best_q; int best; uint64_t bits;
-    masked_argmax_row<MB2>(q, valid ? avail + (size_t)row * A : nullptr, A, lane, best_q, best, bits);
+    const uint32_t slots = A >= 4 ? avail_mask_from_raw<MB2>(avail_raw, A, lane, valid)
+                                  : avail_mask_small(avail_row, A, lane, valid);
+    float best_q; int best;
+    masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
+    const uint64_t bits = row_avail_bits<MB2>(slots, lane);
     if (valid && g == 0) {
         if (best < 0) best = 0;
         action[row] = eps_greedy_pick(best, bits, epsilon, seed, (uint32_t)e, (uint32_t)n, (uint32_t)step_t[e]);
@@ -144,6 +150,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
 // grid = (row tiles, networks).  blockIdx.y = 0: online network, emits q_taken (and q_all);
 // blockIdx.y = 1 (distinct target network): emits next_max and td_target.  With one network a
 // single pass emits everything.
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store of the wave, which would expose the latency of the prefetches that are meant
+// to stay in flight across slots.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 template <int H> struct RecurrentShape {
     static constexpr int kCompute = H / 32;
     static constexpr int kPrefetch = H == 128 ? 3 : 1;
@@ -152,7 +168,7 @@ template <int H> struct RecurrentShape {
     static constexpr int kVecPerLane = kGiFloats / 4 / 64 / kPrefetch;   // float4 per prefetch lane and slot
 };
 
-template <int H, int P, int MB2>
+template <int H, int P, int MB2, bool QALL>
 __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_td_kernel(
     NetFrags online, NetFrags target, const float *__restrict__ gi_online, const float *__restrict__ gi_target,
     int two_nets, int B, int T, const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
@@ -196,7 +212,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                 if constexpr (P == 2) h_lds[0][2 * fb + c][1][lane] = z0.lo;
             }
         }
-        __syncthreads();
+        lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it <= T) {
                 const int cur = it & 1;
@@ -237,7 +253,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                     if constexpr (P == 2) h_lds[cur ^ 1][2 * fb + c][1][lane] = f.lo;
                 }
             }
-            __syncthreads();
+            lds_barrier();
         }
     } else if (wave == Shape::kCompute) {
         // ---------------------------------------------------------------- epilogue wave
@@ -257,10 +273,37 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
         f32x16 b2[MB2];
 #pragma unroll
         for (int mb = 0; mb < MB2; ++mb) b2[mb] = load_feature_block(net.b2, mb, g);
-        __syncthreads();
+
+        // Per-slot inputs of the TD step, fetched one slot ahead so that their latency hides
+        // behind the other waves' work.
+        // 32-bit element offsets (the host bounds every array to 2^30 elements): uniform base
+        // pointer + per-lane offset + per-slot stride.
+        const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // actions / outputs: + t N
+        const uint32_t av0 = ((uint32_t)(b * S) * N + n) * A;     // avail / q_all:     + t N A
+        const uint32_t bt0 = (uint32_t)(b * T);                   // per-episode flags: + t
+        struct SlotIn { int u; uint32_t avail_raw[MB2 * 4]; float reward; uint8_t on_filled, terminated, tg_filled; };
+        auto fetch_slot = [&](int t) {
+            SlotIn in{};
+            if (t > T) return in;
+            if (emit_online && t < T) {
+                in.u = valid ? actions[btn0 + (uint32_t)t * N] : 0;
+                in.on_filled = valid ? filled[bt0 + t] : 0;
+            }
+            if (emit_target && t >= 1) {
+                if (A >= 4) issue_avail_loads<MB2>(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, in.avail_raw);
+                in.reward = valid ? reward[bt0 + t - 1] : 0.0f;
+                in.terminated = valid ? terminated[bt0 + t - 1] : 0;
+                in.tg_filled = valid ? filled[bt0 + t - 1] : 0;
+            }
+            return in;
+        };
+        SlotIn nxt = fetch_slot(0);
+        lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it >= 1) {
                 const int t = it - 1, cur = it & 1;          // h_t was published during iteration t
+                const SlotIn in = nxt;
+                nxt = fetch_slot(t + 1);
                 f32x16 q[MB2];
 #pragma unroll
                 for (int mb = 0; mb < MB2; ++mb) q[mb] = b2[mb];
@@ -279,30 +322,31 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                     }
                 }
                 if (emit_online) {
-                    if (q_all && valid) store_q_row<MB2>(q_all + (((size_t)b * S + t) * N + n) * A, q, A, lane);
+                    if constexpr (QALL) {
+                        if (valid) store_q_row<MB2>(q_all + (av0 + (uint32_t)t * N * A), q, A, lane);
+                    }
                     if (t < T) {
-                        const size_t bt = (size_t)b * T + t;
-                        int u = valid ? actions[bt * N + n] : 0;
-                        u = min(max(u, 0), A - 1);
+                        const int u = min(max(in.u, 0), A - 1);
                         const float qu = pick_action_value<MB2>(q, u, lane);
-                        if (valid && g == 0) q_taken[bt * N + n] = filled[bt] ? qu : 0.0f;
+                        if (valid && g == 0) q_taken[btn0 + (uint32_t)t * N] = in.on_filled ? qu : 0.0f;
                     }
                 }
                 if (emit_target && t >= 1) {
-                    float best_q; int best; uint64_t bits;
-                    masked_argmax_row<MB2>(q, valid ? avail + (((size_t)b * S + t) * N + n) * A : nullptr, A, lane,
-                                           best_q, best, bits);
+                    const uint32_t slots =
+                        A >= 4 ? avail_mask_from_raw<MB2>(in.avail_raw, A, lane, valid)
+                               : avail_mask_small(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, valid);
+                    float best_q; int best;
+                    masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
                     if (valid && g == 0) {
-                        const size_t bt = (size_t)b * T + (t - 1);
-                        const float keep = terminated[bt] ? 0.0f : 1.0f;
-                        const float y = reward[bt] + gamma * keep * best_q;
-                        const bool f = filled[bt] != 0;
-                        next_max[bt * N + n] = f ? best_q : 0.0f;
-                        td_target[bt * N + n] = f ? y : 0.0f;
+                        const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
+                        const float keep = in.terminated ? 0.0f : 1.0f;
+                        const float y = in.reward + gamma * keep * best_q;
+                        next_max[o] = in.tg_filled ? best_q : 0.0f;
+                        td_target[o] = in.tg_filled ? y : 0.0f;
                     }
                 }
             }
-            __syncthreads();
+            lds_barrier();
         }
     } else {
         // ---------------------------------------------------------------- prefetch wave
@@ -322,13 +366,13 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
         fetch(0);
         publish(0);
         if (T >= 1) fetch(1);
-        __syncthreads();
+        lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it + 1 <= T) {
                 publish((it + 1) & 1);
                 if (it + 2 <= T) fetch(it + 2);
             }
-            __syncthreads();
+            lds_barrier();
         }
     }
 }
@@ -369,12 +413,12 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
     }
     const dim3 grid((unsigned)tiles, nets), block(64 * RecurrentShape<H>::kWaves);
     const int two = two_nets ? 1 : 0;
-    if (online.mb2 == 1)
-        hipLaunchKernelGGL((recurrent_td_kernel<H, P, 1>), grid, block, 0, stream, online, target, gi_on, gi_tg, two, B,
-                           T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);
-    else
-        hipLaunchKernelGGL((recurrent_td_kernel<H, P, 2>), grid, block, 0, stream, online, target, gi_on, gi_tg, two, B,
-                           T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);
+#define MARL_REC(MB, QA)                                                                                             \
+    hipLaunchKernelGGL((recurrent_td_kernel<H, P, MB, QA>), grid, block, 0, stream, online, target, gi_on, gi_tg, two,  \
+                       B, T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all)
+    if (online.mb2 == 1) { if (q_all) MARL_REC(1, true); else MARL_REC(1, false); }
+    else                 { if (q_all) MARL_REC(2, true); else MARL_REC(2, false); }
+#undef MARL_REC
     return hipGetLastError();
 }
 

@@ -191,7 +191,11 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     if (a.n_agents != b.n_agents || a.obs_dim != b.obs_dim || a.n_actions != b.n_actions || a.hidden != b.hidden ||
         a.weight_dtype != b.weight_dtype || a.device != b.device)
         return MARL_ERR_MISMATCH;
-    if (B < 0 || T < 1 || (int64_t)B * a.n_agents > (int64_t)1 << 30 || (int64_t)T > (int64_t)1 << 20) return MARL_ERR_BAD_DIM;
+    if (B < 0 || T < 1 || (int64_t)T > (int64_t)1 << 20) return MARL_ERR_BAD_DIM;
+    {   // every array is indexed with 32-bit element offsets
+        const int64_t widest = a.obs_dim > a.n_actions ? a.obs_dim : a.n_actions;
+        if ((int64_t)B * (T + 1) * a.n_agents * widest >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+    }
     if (!unit_interval(gamma)) return MARL_ERR_BAD_ARG;
     if (B == 0) return MARL_OK;
     if (!obs || !avail || !actions || !reward || !terminated || !filled || !q_taken || !next_max || !td_target)

@@ -195,29 +195,95 @@ __device__ __forceinline__ void fc2_tile(const NetFrags &net, const Frag<P> (&hq
     }
 }
 
-// A row's Q values are split over lanes l and l ^ 32.  Masked maximum with the lowest index on ties;
-// returns the availability bits of the whole row.  idx = -1 when nothing is available.
+// Availability of the actions this lane holds, in two steps so that the loads can be issued
+// long before the mask is needed.
+//
+// issue_avail_loads: the four actions of one accumulator group (32 mb + 8 j + 4 g + 0..3) are
+// adjacent bytes and are fetched with one, possibly unaligned, 32-bit load whose address is
+// clamped into the row; every load is unconditional and independent.  avail_row must point at a
+// readable row of A >= 4 bytes (rows with fewer actions use avail_mask_small).
 template <int MB2>
-__device__ __forceinline__ void masked_argmax_row(const f32x16 (&q)[MB2], const uint8_t *__restrict__ avail_row,
-                                                  int A, int lane, float &best_q, int &best_idx, uint64_t &bits)
+__device__ __forceinline__ void issue_avail_loads(const uint8_t *__restrict__ avail_row, int A, int lane,
+                                                  uint32_t (&raw)[MB2 * 4])
 {
     const int g = lane >> 5;
-    best_q = 0.0f; best_idx = -1; bits = 0;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int base = min(32 * mb + 8 * j + 4 * g, A - 4);
+            __builtin_memcpy(&raw[mb * 4 + j], avail_row + base, 4);
+        }
+}
+
+// Bit 16 mb + r of the result is set when action 32 mb + 8 (r / 4) + 4 g + r % 4 exists and is
+// available.
+template <int MB2>
+__device__ __forceinline__ uint32_t avail_mask_from_raw(const uint32_t (&raw)[MB2 * 4], int A, int lane, bool valid)
+{
+    const int g = lane >> 5;
+    uint32_t mask = 0;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int a0 = 32 * mb + 8 * j + 4 * g;
+            const int skip = a0 - min(a0, A - 4);                  // bytes of the word that precede a0
+            const uint32_t w = skip < 4 ? raw[mb * 4 + j] >> (8 * skip) : 0u;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) mask |= ((w >> (8 * i)) & 0xFFu) ? (1u << (16 * mb + 4 * j + i)) : 0u;
+        }
+    return valid ? mask : 0u;
+}
+
+// Rows with fewer than four actions: they all sit in the first group of the lower half-wave.
+__device__ __forceinline__ uint32_t avail_mask_small(const uint8_t *__restrict__ avail_row, int A, int lane, bool valid)
+{
+    uint32_t mask = 0;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t v = avail_row[min(i, A - 1)];
+        mask |= (i < A && v) ? (1u << i) : 0u;
+    }
+    return (valid && lane < 32) ? mask : 0u;
+}
+
+// A row's Q values are split over lanes l and l ^ 32.  Masked maximum with the lowest index on ties.
+// idx = -1 and best_q = 0 when nothing is available.
+template <int MB2>
+__device__ __forceinline__ void masked_argmax_slots(const f32x16 (&q)[MB2], uint32_t slots, int lane, float &best_q,
+                                                    int &best_idx)
+{
+    const int g = lane >> 5;
+    best_q = 0.0f; best_idx = -1;
 #pragma unroll
     for (int mb = 0; mb < MB2; ++mb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const int a = 32 * mb + 8 * (r / 4) + 4 * g + (r % 4);
-            if (avail_row && a < A && avail_row[a]) {
-                bits |= 1ull << a;
-                if (best_idx < 0 || q[mb][r] > best_q) { best_q = q[mb][r]; best_idx = a; }
-            }
+            const bool ok = (slots >> (16 * mb + r)) & 1u;
+            if (ok && (best_idx < 0 || q[mb][r] > best_q)) { best_q = q[mb][r]; best_idx = a; }
         }
     const float oq = __shfl_xor(best_q, 32);
     const int oi = __shfl_xor(best_idx, 32);
-    const uint32_t olo = __shfl_xor((uint32_t)bits, 32), ohi = __shfl_xor((uint32_t)(bits >> 32), 32);
-    bits |= ((uint64_t)ohi << 32) | olo;
     if (oi >= 0 && (best_idx < 0 || oq > best_q || (oq == best_q && oi < best_idx))) { best_q = oq; best_idx = oi; }
+}
+
+// Availability bits of the whole row (bit a = action a) from the two lanes' slot masks.
+template <int MB2>
+__device__ __forceinline__ uint64_t row_avail_bits(uint32_t slots, int lane)
+{
+    const int g = lane >> 5;
+    uint64_t bits = 0;
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int a = 32 * mb + 8 * (r / 4) + 4 * g + (r % 4);
+            if ((slots >> (16 * mb + r)) & 1u) bits |= 1ull << a;
+        }
+    const uint32_t olo = __shfl_xor((uint32_t)bits, 32), ohi = __shfl_xor((uint32_t)(bits >> 32), 32);
+    return bits | ((uint64_t)ohi << 32) | olo;
 }
 
 // Q value of action u of this lane's row (the owner lane has it; the pair is summed).
