@@ -180,6 +180,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
     constexpr int FB = H / 32, KCH = H / 16;
     __shared__ __attribute__((aligned(16))) float gi_lds[2][Shape::kGiFloats];
     __shared__ bf16x8 h_lds[2][KCH][P][64];
+    __shared__ __attribute__((aligned(16))) float b2_lds[32 * MB2];
 
     const bool is_target = blockIdx.y == 1;
     const NetFrags &net = is_target ? target : online;
@@ -270,9 +271,10 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
             for (int kc = 0; kc < KCH; ++kc)
 #pragma unroll
                 for (int p = 0; p < P; ++p) w2[mb][kc][p] = net.w2[((size_t)(mb * KCH + kc) * P + p) * 64 + lane];
-        f32x16 b2[MB2];
-#pragma unroll
-        for (int mb = 0; mb < MB2; ++mb) b2[mb] = load_feature_block(net.b2, mb, g);
+        if (lane < 32 * MB2 / 2) {                 // the output bias lives in LDS, not in registers
+            b2_lds[2 * lane] = net.b2[2 * lane];
+            b2_lds[2 * lane + 1] = net.b2[2 * lane + 1];
+        }
 
         // Per-slot inputs of the TD step, fetched one slot ahead so that their latency hides
         // behind the other waves' work.
@@ -306,7 +308,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                 nxt = fetch_slot(t + 1);
                 f32x16 q[MB2];
 #pragma unroll
-                for (int mb = 0; mb < MB2; ++mb) q[mb] = b2[mb];
+                for (int mb = 0; mb < MB2; ++mb) q[mb] = load_feature_block(b2_lds, mb, g);
 #pragma unroll
                 for (int kc = 0; kc < KCH; ++kc) {
                     Frag<P> hb;
@@ -335,8 +337,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                     const uint32_t slots =
                         A >= 4 ? avail_mask_from_raw<MB2>(in.avail_raw, A, lane, valid)
                                : avail_mask_small(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, valid);
-                    float best_q; int best;
-                    masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
+                    const float best_q = masked_max_slots<MB2>(q, slots);
                     if (valid && g == 0) {
                         const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
                         const float keep = in.terminated ? 0.0f : 1.0f;

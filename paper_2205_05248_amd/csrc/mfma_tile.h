@@ -61,7 +61,7 @@ __device__ __forceinline__ void mma(f32x16 &acc, const bf16x8 *__restrict__ a, c
 
 // Feature held in accumulator slot r of block `blk` by a lane of half g: 32 blk + 8 (r / 4) + 4 g + r % 4.
 // The four slots 4j .. 4j+3 are consecutive features, so per-feature tables load as float4.
-__device__ __forceinline__ f32x16 load_feature_block(const float *__restrict__ table, int blk, int g)
+__device__ __forceinline__ f32x16 load_feature_block(const float *table, int blk, int g)
 {
     f32x16 v;
 #pragma unroll
@@ -267,6 +267,19 @@ __device__ __forceinline__ void masked_argmax_slots(const f32x16 (&q)[MB2], uint
     const float oq = __shfl_xor(best_q, 32);
     const int oi = __shfl_xor(best_idx, 32);
     if (oi >= 0 && (best_idx < 0 || oq > best_q || (oq == best_q && oi < best_idx))) { best_q = oq; best_idx = oi; }
+}
+
+// Maximum of the row's available Q values (0 when nothing is available); no index.
+template <int MB2>
+__device__ __forceinline__ float masked_max_slots(const f32x16 (&q)[MB2], uint32_t slots)
+{
+    float m = -__builtin_inff();
+#pragma unroll
+    for (int mb = 0; mb < MB2; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) m = fmaxf(m, ((slots >> (16 * mb + r)) & 1u) ? q[mb][r] : -__builtin_inff());
+    m = fmaxf(m, __shfl_xor(m, 32));
+    return m == -__builtin_inff() ? 0.0f : m;
 }
 
 // Availability bits of the whole row (bit a = action a) from the two lanes' slot masks.
