@@ -85,19 +85,21 @@ class Bench:
                               u["filled"], self.u_host["gamma"], *self.u_out)
 
     def run(self, steps, warmup):
+        """K timed steps.  The library records HIP events around each of its kernels on the
+        stream it launches on, so per-kernel means come from the same timed region."""
         torch = self.torch
         for _ in range(warmup):
             self.act(); self.unroll()
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
         torch.cuda.synchronize()
+        self.online.set_timing(True)
         t0 = time.perf_counter()
-        for k in range(steps):
-            ev[k][0].record(); self.act(); ev[k][1].record(); self.unroll(); ev[k][2].record()
+        for _ in range(steps):
+            self.act(); self.unroll()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-        act_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-        unroll_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-        return wall, act_ms, unroll_ms
+        k = self.online.timing_read()
+        self.online.set_timing(False)
+        return wall, k
 
     def back_to_back_act(self, n=200):
         torch = self.torch
@@ -177,40 +179,67 @@ def main():
     cfg, dims = b.cfg, b.dims
     N, D, A, H = dims
     E, B, T = cfg["E"], cfg["B"], cfg["T"]
-    wall, act_ms, unroll_ms = b.run(args.steps, args.warmup)
+    wall, k = b.run(args.steps, args.warmup)
     act_b2b_ms = b.back_to_back_act()
     b.close()
 
     ms_per_step = wall * 1e3 / args.steps
     steps_act, steps_unroll = E * N, B * T * N
     nets = 1 if args.single_net else 2
-    fl = flops_per_agent_step(*dims)
-    act_bytes = steps_act * act_bytes_per_agent_step(*dims)
-    unroll_flops = nets * B * (T + 1) * N * fl
-    peak_tf = PEAK["bf16_TFs"] if cfg["dtype"] == "bf16" else PEAK["fp32_TFs"]
-    unroll_tfs = unroll_flops / (unroll_ms * 1e-3) / 1e12
-    act_gbs = act_bytes / (act_b2b_ms * 1e-3) / 1e9
+    slots = B * (T + 1) * N                                   # network evaluations per net in the unroll
+    bf16 = cfg["dtype"] == "bf16"
+    # every contraction runs on the bf16 MFMA pipe (fp32 networks as three bf16 products per
+    # multiply), so the matrix peak is the bf16 one; flops counted are the algorithmic ones
+    peak_tf = PEAK["bf16_TFs"]
+    act_ms, proj_ms, rec_ms = k["act_ms"], k["input_proj_ms"], k["recurrent_ms"]
+    kernels = {
+        "act_step": {
+            "ms": act_ms, "calls": k["act_calls"], "bound": "hbm",
+            "bytes": steps_act * act_bytes_per_agent_step(*dims), "flops": steps_act * flops_per_agent_step(*dims)},
+        "input_proj": {
+            "ms": proj_ms, "calls": k["unroll_calls"], "bound": "mfma",
+            "bytes": slots * 4 * D, "flops": nets * slots * (2 * D * H + 2 * 3 * H * H)},
+        "recurrent_td": {
+            "ms": rec_ms, "calls": k["unroll_calls"], "bound": "mfma",
+            "bytes": slots * A + B * T * N * 16, "flops": nets * slots * (2 * 3 * H * H + 2 * H * A)},
+    }
+    for v in kernels.values():
+        sec = max(v["ms"], 1e-9) * 1e-3
+        v["GBs"] = v["bytes"] / sec / 1e9
+        v["TFLOPs"] = v["flops"] / sec / 1e12
+        v["hbm_frac"] = v["GBs"] / PEAK["hbm_GBs"]
+        v["mfma_frac"] = v["TFLOPs"] / peak_tf
+    dom_name = max(kernels, key=lambda n: kernels[n]["ms"])
+    dom = kernels[dom_name]
+    if dom["bound"] == "hbm":
+        roofline = {"kernel": dom_name, "bound": "hbm", "achieved": dom["GBs"], "peak": PEAK["hbm_GBs"],
+                    "unit": "GB/s", "frac": dom["hbm_frac"], "traffic": None}
+    else:
+        roofline = {"kernel": dom_name, "bound": "mfma", "achieved": dom["TFLOPs"], "peak": peak_tf,
+                    "unit": "TFLOP/s", "frac": dom["mfma_frac"], "traffic": None,
+                    "mfma_products_per_multiply": 1 if bf16 else 3}
+    unroll_ms = proj_ms + rec_ms
     out = {
         "metric": "agent-steps/s (act-step) and episode-steps/s (unroll+TD); % HBM/MFMA peak",
         "value": (steps_act + steps_unroll) / (ms_per_step * 1e-3),
         "unit": "agent-steps/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 weights, f32 accumulate" if cfg["dtype"] == "bf16" else "f32",
+        "dtype": "bf16 weights, f32 accumulate" if bf16 else "f32 (bf16 hi/lo split MFMA, f32 accumulate)",
         "data": "synthetic",
         "config": {"workload": cfg["name"], "E": E, "N": N, "obs_dim": D, "n_actions": A, "hidden": H,
                    "B": B, "T": T, "target_network": "distinct" if nets == 2 else "same",
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
-        "act_step": {"agent_steps_per_s": steps_act / (act_b2b_ms * 1e-3), "kernel_ms_in_step": act_ms,
-                     "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": act_gbs,
-                     "hbm_frac": act_gbs / PEAK["hbm_GBs"],
-                     "tflops": steps_act * fl / (act_b2b_ms * 1e-3) / 1e12,
-                     "input_pool_bytes": b.pool * act_bytes},
+        "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
+                     "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": kernels["act_step"]["GBs"],
+                     "hbm_frac": kernels["act_step"]["hbm_frac"], "mfma_frac": kernels["act_step"]["mfma_frac"],
+                     "input_pool_bytes": b.pool * kernels["act_step"]["bytes"]},
         "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),
-                      "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "call_ms": unroll_ms,
-                      "tflops": unroll_tfs},
-        "roofline": {"kernel": "unroll_td", "bound": "mfma", "achieved": unroll_tfs, "peak": peak_tf,
-                     "unit": "TFLOP/s", "frac": unroll_tfs / peak_tf, "traffic": None},
+                      "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "kernels_ms": unroll_ms,
+                      "input_proj_ms": proj_ms, "recurrent_ms": rec_ms,
+                      "mfma_frac_input_proj": kernels["input_proj"]["mfma_frac"],
+                      "mfma_frac_recurrent": kernels["recurrent_td"]["mfma_frac"]},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)

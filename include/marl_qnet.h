@@ -156,6 +156,21 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
 
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
+/*
+ * Kernel timing for benchmarks.  While timing is enabled on a handle, marl_act_step and
+ * marl_unroll_td (the `online` handle's setting counts) record HIP events on the caller's
+ * stream around each kernel they launch, for up to MARL_TIMING_MAX_CALLS calls (later calls
+ * run untimed).  marl_qnet_timing_read waits for the recorded events, returns the mean
+ * duration in milliseconds of each kernel over the recorded calls, and clears the record:
+ *   act_ms      decision-step kernel, over *act_calls calls
+ *   unroll_ms   [0] input-projection kernel, [1] recurrent TD kernel, over *unroll_calls calls
+ * Means of zero calls are 0.  Event records cost a little stream time; leave timing off in
+ * production.  Enabling or disabling clears the record.
+ */
+#define MARL_TIMING_MAX_CALLS 1024
+int marl_qnet_set_timing(marl_qnet *q, int32_t enable);
+int marl_qnet_timing_read(marl_qnet *q, float *act_ms, int32_t *act_calls, float unroll_ms[2], int32_t *unroll_calls);
+
 /* Free the handle, its weights and scratch.  Synchronises the device.  NULL is allowed. */
 int marl_destroy(marl_qnet *q);
 

@@ -20,7 +20,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
-           "marl_last_device_error"]
+           "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read"]
 
 
 class MarlError(RuntimeError):
@@ -62,6 +62,11 @@ def load():
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
+        lib.marl_qnet_set_timing.restype = ctypes.c_int
+        lib.marl_qnet_set_timing.argtypes = [vp, i32]
+        lib.marl_qnet_timing_read.restype = ctypes.c_int
+        lib.marl_qnet_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32),
+                                              ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         lib.marl_destroy.restype = ctypes.c_int
         lib.marl_destroy.argtypes = [vp]
         lib.marl_strerror.restype = ctypes.c_char_p
@@ -148,6 +153,20 @@ def marl_qnet_reserve_unroll(handle, B, T):
     check(load().marl_qnet_reserve_unroll(ctypes.c_void_p(handle), B, T))
 
 
+def marl_qnet_set_timing(handle, enable):
+    check(load().marl_qnet_set_timing(ctypes.c_void_p(handle), int(bool(enable))))
+
+
+def marl_qnet_timing_read(handle):
+    """Mean kernel durations (ms) over the calls recorded since timing was enabled / last read."""
+    act, n_act, n_unroll = ctypes.c_float(), ctypes.c_int32(), ctypes.c_int32()
+    unroll = (ctypes.c_float * 2)()
+    check(load().marl_qnet_timing_read(ctypes.c_void_p(handle), ctypes.byref(act), ctypes.byref(n_act), unroll,
+                                       ctypes.byref(n_unroll)))
+    return dict(act_ms=act.value, act_calls=n_act.value, input_proj_ms=unroll[0], recurrent_ms=unroll[1],
+                unroll_calls=n_unroll.value)
+
+
 class QNet:
     """Convenience owner of one handle (create on init, destroy on close)."""
 
@@ -165,6 +184,12 @@ class QNet:
         tgt = self if target is None else target
         marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                        gamma, q_taken, next_max, td_target, q_all)
+
+    def set_timing(self, enable):
+        marl_qnet_set_timing(self.handle, enable)
+
+    def timing_read(self):
+        return marl_qnet_timing_read(self.handle)
 
     def close(self):
         if self.handle:

@@ -401,7 +401,8 @@ template <int H, int P>
 hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, float *gi_on, float *gi_tg,
                            int B, int T, const float *obs, const uint8_t *avail, const int32_t *actions,
                            const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
-                           float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream)
+                           float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream,
+                           hipEvent_t between)
 {
     const int rows = B * online.N, tiles = (rows + 31) / 32;
     const long work = (long)tiles * (T + 1);
@@ -411,6 +412,10 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
         hipLaunchKernelGGL((input_proj_kernel<H, P>), grid, block, 0, stream, online, target, gi_on, gi_tg, B, T, obs);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
+        if (between) {
+            err = hipEventRecord(between, stream);
+            if (err != hipSuccess) return err;
+        }
     }
     const dim3 grid((unsigned)tiles, nets), block(64 * RecurrentShape<H>::kWaves);
     const int two = two_nets ? 1 : 0;
@@ -450,12 +455,12 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
-                            float *q_all, hipStream_t stream)
+                            float *q_all, hipStream_t stream, hipEvent_t between)
 {
     float *gi_on = static_cast<float *>(scratch_online), *gi_tg = static_cast<float *>(scratch_target);
 #define MARL_UNROLL(HH, PP)                                                                                        \
     return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, obs, avail, actions, reward,      \
-                                   terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream)
+                                   terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream, between)
     if (online.H == 64 && online.planes == 2) MARL_UNROLL(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_UNROLL(64, 1);
     if (online.H == 128 && online.planes == 2) MARL_UNROLL(128, 2);

@@ -83,6 +83,23 @@ int ensure_scratch(marl_qnet *q, size_t bytes)
     return MARL_OK;
 }
 
+// Hands out `count` events for one timed call, or nullptr when the record is full.
+hipEvent_t *take_events(marl_qnet *q, int count, int *rc)
+{
+    *rc = MARL_OK;
+    if (q->timed_calls.size() >= MARL_TIMING_MAX_CALLS) return nullptr;
+    while (q->ev_pool.size() < q->ev_used + count) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) { *rc = device_fail(err, "hipEventCreate"); return nullptr; }
+        q->ev_pool.push_back(e);
+    }
+    hipEvent_t *ev = &q->ev_pool[q->ev_used];
+    q->ev_used += count;
+    q->timed_calls.push_back(count);
+    return ev;
+}
+
 }  // namespace
 
 extern "C" {
@@ -123,6 +140,8 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     q->dev_weight_bytes = img.bytes;
     q->scratch = nullptr;
     q->scratch_bytes = 0;
+    q->timing = false;
+    q->ev_used = 0;
     err = hipMalloc(&q->dev_weights, img.bytes);
     if (err != hipSuccess) { delete q; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipMalloc"); }
     err = hipMemcpy(q->dev_weights, img.host, img.bytes, hipMemcpyHostToDevice);
@@ -166,8 +185,17 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
 
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
-    MARL_HIP(marl::launch_act_step(q->net, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out,
-                                   static_cast<hipStream_t>(hip_stream)));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t *ev = nullptr;
+    if (q->timing) {
+        q->ev_pool.reserve(3 * MARL_TIMING_MAX_CALLS);      // keeps handed-out pointers stable
+        int rc;
+        ev = take_events(q, 2, &rc);
+        if (rc != MARL_OK) return rc;
+    }
+    if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
+    MARL_HIP(marl::launch_act_step(q->net, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
+    if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
     return MARL_OK;
 }
 
@@ -208,9 +236,55 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     int rc = ensure_scratch(online, need);
     if (rc == MARL_OK && two) rc = ensure_scratch(target, need);
     if (rc != MARL_OK) return rc;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipEvent_t *ev = nullptr;
+    if (online->timing) {
+        online->ev_pool.reserve(3 * MARL_TIMING_MAX_CALLS);
+        ev = take_events(online, 3, &rc);
+        if (rc != MARL_OK) return rc;
+    }
+    if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
     MARL_HIP(marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, obs, avail,
                                     actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
-                                    static_cast<hipStream_t>(hip_stream)));
+                                    stream, ev ? ev[1] : nullptr));
+    if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
+    return MARL_OK;
+}
+
+int marl_qnet_set_timing(marl_qnet *q, int32_t enable)
+{
+    if (!q) return MARL_ERR_NULL;
+    q->timing = enable != 0;
+    q->ev_used = 0;
+    q->timed_calls.clear();
+    return MARL_OK;
+}
+
+int marl_qnet_timing_read(marl_qnet *q, float *act_ms, int32_t *act_calls, float unroll_ms[2], int32_t *unroll_calls)
+{
+    if (!q || !act_ms || !act_calls || !unroll_ms || !unroll_calls) return MARL_ERR_NULL;
+    DeviceGuard guard(q->desc.device);
+    if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    double act = 0.0, proj = 0.0, rec = 0.0;
+    int n_act = 0, n_unroll = 0;
+    size_t at = 0;
+    for (int count : q->timed_calls) {
+        hipEvent_t *ev = &q->ev_pool[at];
+        at += count;
+        MARL_HIP(hipEventSynchronize(ev[count - 1]));
+        float a = 0.0f, b = 0.0f;
+        MARL_HIP(hipEventElapsedTime(&a, ev[0], ev[1]));
+        if (count == 2) { act += a; ++n_act; continue; }
+        MARL_HIP(hipEventElapsedTime(&b, ev[1], ev[2]));
+        proj += a; rec += b; ++n_unroll;
+    }
+    *act_ms = n_act ? (float)(act / n_act) : 0.0f;
+    *act_calls = n_act;
+    unroll_ms[0] = n_unroll ? (float)(proj / n_unroll) : 0.0f;
+    unroll_ms[1] = n_unroll ? (float)(rec / n_unroll) : 0.0f;
+    *unroll_calls = n_unroll;
+    q->ev_used = 0;
+    q->timed_calls.clear();
     return MARL_OK;
 }
 
@@ -220,6 +294,7 @@ int marl_destroy(marl_qnet *q)
     int rc = MARL_OK;
     {
         DeviceGuard guard(q->desc.device);
+        for (hipEvent_t e : q->ev_pool) (void)hipEventDestroy(e);
         for (void *p : {q->dev_weights, q->scratch}) {
             if (!p) continue;
             hipError_t err = hipFree(p);

@@ -6,6 +6,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/marl_qnet.h"
 
 namespace marl {
@@ -50,6 +52,10 @@ struct marl_qnet {
     marl::NetFrags net;
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
+    bool timing;                       // record events around the kernels of each call
+    std::vector<hipEvent_t> ev_pool;   // events created so far (reused after a read)
+    size_t ev_used;                    // events handed out since the last read
+    std::vector<int> timed_calls;      // per recorded call: 2 = decision step (2 events), 3 = unroll (3 events)
 };
 
 namespace marl {
@@ -75,6 +81,6 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
-                            float *q_all, hipStream_t stream);
+                            float *q_all, hipStream_t stream, hipEvent_t between);
 
 }  // namespace marl
