@@ -11,86 +11,32 @@
 //                        T+1 slots with the hidden state in registers, adds the hidden half of
 //                        the gates, applies fc2 and emits q_taken / next_max / td_target.
 #include "mfma_tile.h"
+#include "stream_layout.h"
 
 namespace marl {
 
-constexpr int kWavesPerGroup = 4;
-
-// Two waves per SIMD when the operand fragments of one row tile fit in 256 registers.
-#define MARL_WAVES_PER_EU(H, P) (((H) * (P) <= 128) ? 2 : 1)
-
-// ------------------------------------------------------------------------------------------ act-step
-template <int H, int P, int MB2>
-__global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void act_step_kernel(
-    NetFrags net, int rows, const float *__restrict__ obs, const uint8_t *__restrict__ avail, const float *h_in,
-    const uint8_t *__restrict__ reset, const int32_t *__restrict__ step_t, float epsilon, uint64_t seed,
-    float *h_out, int32_t *__restrict__ action, float *__restrict__ q_out)
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store of the wave, which would expose the latency of the prefetches that are meant
+// to stay in flight across slots.
+__device__ __forceinline__ void lds_barrier()
 {
-    constexpr int FB = H / 32, KCH = H / 16;
-    const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
-    const int tile = blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);
-    if (tile * 32 >= rows) return;                       // whole wavefront leaves; no barriers below
-    const int row = tile * 32 + col;
-    const bool valid = row < rows;
-    const int N = net.N, D = net.D, A = net.A;
-    const int e = valid ? row / N : 0, n = valid ? row % N : 0;
-    const bool keep_h = valid && !(reset && reset[e]);
-    const float *h_row = h_in + (size_t)row * H;
-    const uint8_t *avail_row = avail + (valid ? (size_t)row * A : 0);
-    uint32_t avail_raw[MB2 * 4];
-    if (A >= 4) issue_avail_loads<MB2>(avail_row, A, lane, avail_raw);      // consumed after fc2
-
-    // hidden state as operand fragments (the same k order as an accumulator leaves)
-    Frag<P> hf[KCH];
-#pragma unroll
-    for (int b = 0; b < FB; ++b) {
-        f32x16 hv;
-        if (keep_h) hv = load_feature_block(h_row, b, g);
-        else
-#pragma unroll
-            for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
-        hf[2 * b] = frag_of_half<P>(hv, 0);
-        hf[2 * b + 1] = frag_of_half<P>(hv, 1);
-    }
-
-    Frag<P> x[KCH];
-    fc1_tile<H, P>(net, valid ? obs + (size_t)row * D : nullptr, n, lane, x);
-
-    Frag<P> hq[KCH];
-#pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-        f32x16 ar, az, ain, ahn;
-        input_gates_block<H, P>(net, x, fb, lane, ar, az, ain);
-        hidden_gates_block<H, P>(net, hf, fb, lane, ar, az, ahn);
-        f32x16 hv;                                       // exact fp32 hidden state for the blend
-        if (keep_h) hv = load_feature_block(h_row, fb, g);
-        else
-#pragma unroll
-            for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
-        const f32x16 hn = gru_blend(ar, az, ain, ahn, hv);
-        if (valid) store_feature_block(h_out + (size_t)row * H, fb, g, hn);
-        hq[2 * fb] = frag_of_half<P>(hn, 0);
-        hq[2 * fb + 1] = frag_of_half<P>(hn, 1);
-    }
-
-    f32x16 q[MB2];
-    fc2_tile<H, P, MB2>(net, hq, lane, q);
-    if (q_out && valid) store_q_row<MB2>(q_out + (size_t)row * A, q, A, lane);
-
-    const uint32_t slots = A >= 4 ? avail_mask_from_raw<MB2>(avail_raw, A, lane, valid)
-                                  : avail_mask_small(avail_row, A, lane, valid);
-    float best_q; int best;
-    masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
-    const uint64_t bits = row_avail_bits<MB2>(slots, lane);
-    if (valid && g == 0) {
-        if (best < 0) best = 0;
-        action[row] = eps_greedy_pick(best, bits, epsilon, seed, (uint32_t)e, (uint32_t)n, (uint32_t)step_t[e]);
-    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-// ------------------------------------------------------------------------------------------ unroll, part 1
-// Scratch layout, fp32: [row tile][slot][3 gates][H/32][4][64 lanes][4]: accumulator slots
-// 4j .. 4j+3 of lane l are the float4 at [..][j][l], so every wave-wide access is 1 KiB contiguous.
+// ------------------------------------------------------------------------------------------ front end
+// Decision step (ACT) and input projection of the unroll (!ACT) share one kernel.  A workgroup
+// of NW wavefronts owns NW tiles of 32 rows; each wavefront keeps its rows' activations in
+// registers from layer to layer.  The weights are not read per wavefront from global memory:
+// the whole workgroup pulls them through LDS in chunks of kChunkPlanes fragment planes, in the
+// order of use fixed by stream_layout.h, double-buffered: while chunk c is consumed, chunk c+1
+// sits in registers on its way to the other LDS buffer and chunk c+2 is in flight from L2.
+// One LDS-only barrier per chunk.
+//
+// Scratch layout written by the input projection, fp32:
+// [row tile][slot][3 gates][H/32][4][64 lanes][4]: accumulator slots 4j .. 4j+3 of lane l are the
+// float4 at [..][j][l], so every wave-wide access is 1 KiB contiguous.
 constexpr int kGiPiece = 64 * 4;   // floats per [j] piece
 
 __device__ __forceinline__ void store_gi_block(float *__restrict__ dst, int lane, const f32x16 &v)
@@ -102,36 +48,252 @@ __device__ __forceinline__ void store_gi_block(float *__restrict__ dst, int lane
     }
 }
 
-template <int H, int P>
-__global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void input_proj_kernel(
-    NetFrags online, NetFrags target, float *__restrict__ gi_online, float *__restrict__ gi_target, int B, int T,
-    const float *__restrict__ obs)
+struct FrontArgs {
+    NetFrags net[2];            // ACT: net[0]; projection: online, target (blockIdx.y)
+    // decision step
+    int rows;
+    const float *obs;
+    const uint8_t *avail;
+    const float *h_in;
+    const uint8_t *reset;
+    const int32_t *step_t;
+    float epsilon;
+    uint64_t seed;
+    float *h_out;
+    int32_t *action;
+    float *q_out;
+    // input projection
+    float *gi[2];
+    int B, T;
+};
+
+// Wavefronts per workgroup: 8 (two per SIMD) when one row tile's operands fit in 256 registers.
+constexpr int front_waves(int H, int P) { return (H * P <= 128) ? 8 : 4; }
+constexpr int front_waves_per_simd(int H, int P) { return front_waves(H, P) / 4; }
+template <int H, int P> struct FrontShape {
+    static constexpr int kWaves = front_waves(H, P);
+    static constexpr int kStage = kChunkVecs / (64 * kWaves);     // 16-byte vectors per thread and chunk
+};
+
+template <int H, int P, int MB2, bool ACT>
+__global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P)) void front_kernel(
+    const FrontArgs args)
 {
-    constexpr int FB = H / 32, KCH = H / 16;
-    const NetFrags &net = blockIdx.y ? target : online;
-    float *__restrict__ gi = blockIdx.y ? gi_target : gi_online;
-    const int lane = threadIdx.x & 63, col = lane & 31;
-    const int N = net.N, D = net.D;
-    const int rows = B * N, S = T + 1;
-    const int ntiles = (rows + 31) / 32;
-    const long work = (long)blockIdx.x * kWavesPerGroup + (threadIdx.x >> 6);     // (row tile, slot)
-    if (work >= (long)ntiles * S) return;
-    const int rt = (int)(work / S), t = (int)(work % S);
-    const int row = rt * 32 + col;
-    const bool valid = row < rows;
-    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+    constexpr int MB = H / 32, FB = H / 32, KCH = H / 16;
+    constexpr int NW = FrontShape<H, P>::kWaves, NT = 64 * NW, STG = FrontShape<H, P>::kStage;
+    constexpr StreamDims SD = stream_dims(H, P, MB2);
+    constexpr int OB = SD.kpc <= 6 ? SD.kpc : 6;      // observation k-steps fetched ahead as one block
+    constexpr int SUB = SD.kpc / OB;
+    static_assert(SD.kpc % OB == 0, "fc1 chunk must hold whole observation blocks");
+    __shared__ bf16x8 wbuf[2][kChunkVecs];
 
+    const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, col = lane & 31;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const NetFrags &net = args.net[ACT ? 0 : blockIdx.y];
+    const int N = net.N, D = net.D, A = net.A;
+
+    // ---- which rows this wavefront owns
+    bool valid;
+    int row, n;
+    const float *obs_row;
+    [[maybe_unused]] int e = 0;
+    [[maybe_unused]] float *gi_dst = nullptr;
+    if constexpr (ACT) {
+        row = (blockIdx.x * NW + wave) * 32 + col;
+        valid = row < args.rows;
+        e = valid ? row / N : 0;
+        n = valid ? row % N : 0;
+        obs_row = args.obs + (valid ? (size_t)row * D : 0);       // rows past the end read row 0, results unused
+    } else {
+        const int rows = args.B * N, S = args.T + 1, ntiles = (rows + 31) / 32;
+        const long work = (long)blockIdx.x * NW + wave;               // (row tile, slot)
+        const bool in_range = work < (long)ntiles * S;
+        const int rt = in_range ? (int)(work / S) : 0, t = in_range ? (int)(work % S) : 0;
+        row = rt * 32 + col;
+        valid = in_range && row < rows;
+        const int b = valid ? row / N : 0;
+        n = valid ? row % N : 0;
+        obs_row = args.obs + (valid ? (((size_t)b * S + t) * N + n) * D : 0);
+        gi_dst = in_range ? args.gi[blockIdx.y] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
+    }
+
+    // ---- weight pipeline
+    const bf16x8 *stream = ACT ? net.act_stream : net.proj_stream;
+    const int total = ACT ? net.act_chunks : net.proj_chunks;
+    bf16x8 stage[STG];
+    int chunk = 0;
+    auto fetch = [&](int c) {
+        if (c < total) {
+            const bf16x8 *src = stream + (size_t)c * kChunkVecs + tid;
+#pragma unroll
+            for (int i = 0; i < STG; ++i) stage[i] = src[i * NT];
+        }
+    };
+    auto commit = [&](int c) {
+        if (c < total) {
+            bf16x8 *dst = &wbuf[c & 1][tid];
+#pragma unroll
+            for (int i = 0; i < STG; ++i) dst[i * NT] = stage[i];
+        }
+    };
+    auto advance = [&]() {          // done with chunk `chunk`: publish the next one, start the one after
+        commit(chunk + 1);
+        fetch(chunk + 2);
+        lds_barrier();
+        ++chunk;
+    };
+    fetch(0);
+
+    // ---- decision step: issue the row's other inputs early
+    [[maybe_unused]] bool keep_h = false;
+    [[maybe_unused]] const float *h_row = nullptr;
+    [[maybe_unused]] const uint8_t *avail_row = nullptr;
+    [[maybe_unused]] uint32_t avail_raw[MB2 * 4];
+    [[maybe_unused]] Frag<P> hf[KCH];
+    if constexpr (ACT) {
+        keep_h = valid && !(args.reset && args.reset[e]);
+        h_row = args.h_in + (size_t)row * H;
+        avail_row = args.avail + (valid ? (size_t)row * A : 0);
+        if (A >= 4) issue_avail_loads<MB2>(avail_row, A, lane, avail_raw);      // consumed after fc2
+#pragma unroll
+        for (int b = 0; b < FB; ++b) {                  // hidden state as operand fragments
+            f32x16 hv;
+            if (keep_h) hv = load_feature_block(h_row, b, g);
+            else
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+            hf[2 * b] = frag_of_half<P>(hv, 0);
+            hf[2 * b + 1] = frag_of_half<P>(hv, 1);
+        }
+    }
+
+    // ---- fc1 + ReLU
+    const bool vec4 = (D % 4) == 0 && (reinterpret_cast<uintptr_t>(obs_row) & 15u) == 0;
+    float cur[OB][8], nxt[OB][8];
+#pragma unroll
+    for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row, D, vec4, kk, g, cur[kk]);
+    f32x16 acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) acc[mb] = load_feature_block(net.bias1 + (size_t)n * H, mb, g);
+    commit(0);
+    fetch(1);
+    lds_barrier();
+
+    for (int c1 = 0; c1 < net.nc1; ++c1) {
+        const bf16x8 *wb = &wbuf[chunk & 1][lane];
+#pragma unroll
+        for (int s = 0; s < SUB; ++s) {
+            const int next_block = c1 * SUB + s + 1;
+#pragma unroll
+            for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row, D, vec4, next_block * OB + kk, g, nxt[kk]);
+#pragma unroll
+            for (int kk = 0; kk < OB; ++kk) {
+                const Frag<P> bfrag = to_frag<P>(cur[kk]);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) mma<P>(acc[mb], wb + (((s * OB + kk) * MB + mb) * P) * 64, bfrag);
+            }
+#pragma unroll
+            for (int kk = 0; kk < OB; ++kk)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) cur[kk][i] = nxt[kk][i];
+        }
+        advance();
+    }
     Frag<P> x[KCH];
-    fc1_tile<H, P>(net, valid ? obs + (((size_t)b * S + t) * N + n) * D : nullptr, n, lane, x);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[mb][r] = fmaxf(acc[mb][r], 0.0f);
+        x[2 * mb] = frag_of_half<P>(acc[mb], 0);
+        x[2 * mb + 1] = frag_of_half<P>(acc[mb], 1);
+    }
 
-    float *dst = gi + ((size_t)rt * S + t) * (3 * FB * 1024);
+    // ---- GRU
+    [[maybe_unused]] Frag<P> hq[KCH];
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {
-        f32x16 ar, az, ain;
-        input_gates_block<H, P>(net, x, fb, lane, ar, az, ain);
-        store_gi_block(dst + (size_t)(0 * FB + fb) * 1024, lane, ar);
-        store_gi_block(dst + (size_t)(1 * FB + fb) * 1024, lane, az);
-        store_gi_block(dst + (size_t)(2 * FB + fb) * 1024, lane, ain);
+        f32x16 ar = load_feature_block(net.bias_r, fb, g);
+        f32x16 az = load_feature_block(net.bias_z, fb, g);
+        f32x16 ain = load_feature_block(net.bias_in, fb, g);
+        if constexpr (ACT) {
+            f32x16 ahn = load_feature_block(net.bias_hn, fb, g);
+#pragma unroll
+            for (int cc = 0; cc < SD.cpf; ++cc) {
+                const bf16x8 *wb = &wbuf[chunk & 1][lane];
+#pragma unroll
+                for (int kk = 0; kk < SD.kpg; ++kk) {
+                    const int kc = cc * SD.kpg + kk;
+                    const bf16x8 *m = wb + (kk * 6 * P) * 64;
+                    mma<P>(ar, m + 0 * P * 64, x[kc]);
+                    mma<P>(az, m + 1 * P * 64, x[kc]);
+                    mma<P>(ain, m + 2 * P * 64, x[kc]);
+                    mma<P>(ar, m + 3 * P * 64, hf[kc]);
+                    mma<P>(az, m + 4 * P * 64, hf[kc]);
+                    mma<P>(ahn, m + 5 * P * 64, hf[kc]);
+                }
+                advance();
+            }
+            f32x16 hv;                                       // exact fp32 hidden state for the blend
+            if (keep_h) hv = load_feature_block(h_row, fb, g);
+            else
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+            const f32x16 hn = gru_blend(ar, az, ain, ahn, hv);
+            if (valid) store_feature_block(args.h_out + (size_t)row * H, fb, g, hn);
+            hq[2 * fb] = frag_of_half<P>(hn, 0);
+            hq[2 * fb + 1] = frag_of_half<P>(hn, 1);
+        } else {
+#pragma unroll
+            for (int cc = 0; cc < SD.cpj; ++cc) {
+                const bf16x8 *wb = &wbuf[chunk & 1][lane];
+#pragma unroll
+                for (int kk = 0; kk < SD.kpj; ++kk) {
+                    const int kc = cc * SD.kpj + kk;
+                    const bf16x8 *m = wb + (kk * 3 * P) * 64;
+                    mma<P>(ar, m + 0 * P * 64, x[kc]);
+                    mma<P>(az, m + 1 * P * 64, x[kc]);
+                    mma<P>(ain, m + 2 * P * 64, x[kc]);
+                }
+                advance();
+            }
+            if (gi_dst) {
+                store_gi_block(gi_dst + (size_t)(0 * FB + fb) * 1024, lane, ar);
+                store_gi_block(gi_dst + (size_t)(1 * FB + fb) * 1024, lane, az);
+                store_gi_block(gi_dst + (size_t)(2 * FB + fb) * 1024, lane, ain);
+            }
+        }
+    }
+
+    // ---- fc2, mask, action
+    if constexpr (ACT) {
+        f32x16 q[MB2];
+#pragma unroll
+        for (int mb = 0; mb < MB2; ++mb) q[mb] = load_feature_block(net.b2, mb, g);
+#pragma unroll
+        for (int cf = 0; cf < SD.ncf; ++cf) {
+            const bf16x8 *wb = &wbuf[chunk & 1][lane];
+#pragma unroll
+            for (int kk = 0; kk < SD.kpf; ++kk) {
+                const int kc = cf * SD.kpf + kk;
+                if (kc < KCH) {
+#pragma unroll
+                    for (int mb = 0; mb < MB2; ++mb) mma<P>(q[mb], wb + ((kk * MB2 + mb) * P) * 64, hq[kc]);
+                }
+            }
+            advance();
+        }
+        if (args.q_out && valid) store_q_row<MB2>(args.q_out + (size_t)row * A, q, A, lane);
+
+        const uint32_t slots = A >= 4 ? avail_mask_from_raw<MB2>(avail_raw, A, lane, valid)
+                                      : avail_mask_small(avail_row, A, lane, valid);
+        float best_q; int best;
+        masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
+        const uint64_t bits = row_avail_bits<MB2>(slots, lane);
+        if (valid && g == 0) {
+            if (best < 0) best = 0;
+            args.action[row] = eps_greedy_pick(best, bits, args.epsilon, args.seed, (uint32_t)e, (uint32_t)n,
+                                               (uint32_t)args.step_t[e]);
+        }
     }
 }
 
@@ -150,16 +312,6 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, MARL_WAVES_PER_EU(H, P)) void 
 // grid = (row tiles, networks).  blockIdx.y = 0: online network, emits q_taken (and q_all);
 // blockIdx.y = 1 (distinct target network): emits next_max and td_target.  With one network a
 // single pass emits everything.
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
-// load and store of the wave, which would expose the latency of the prefetches that are meant
-// to stay in flight across slots.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
 template <int H> struct RecurrentShape {
     static constexpr int kCompute = H / 32;
     static constexpr int kPrefetch = H == 128 ? 3 : 1;
@@ -386,14 +538,15 @@ hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const u
                         const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
                         int32_t *action, float *q_out, hipStream_t stream)
 {
+    constexpr int NW = FrontShape<H, P>::kWaves;
+    FrontArgs a{};
+    a.net[0] = net;
+    a.rows = rows; a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
+    a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out;
     const int tiles = (rows + 31) / 32;
-    const dim3 grid((unsigned)((tiles + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
-    if (net.mb2 == 1)
-        hipLaunchKernelGGL((act_step_kernel<H, P, 1>), grid, block, 0, stream, net, rows, obs, avail, h_in, reset,
-                           step_t, epsilon, seed, h_out, action, q_out);
-    else
-        hipLaunchKernelGGL((act_step_kernel<H, P, 2>), grid, block, 0, stream, net, rows, obs, avail, h_in, reset,
-                           step_t, epsilon, seed, h_out, action, q_out);
+    const dim3 grid((unsigned)((tiles + NW - 1) / NW)), block(64 * NW);
+    if (net.mb2 == 1) hipLaunchKernelGGL((front_kernel<H, P, 1, true>), grid, block, 0, stream, a);
+    else              hipLaunchKernelGGL((front_kernel<H, P, 2, true>), grid, block, 0, stream, a);
     return hipGetLastError();
 }
 
@@ -408,8 +561,14 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
     const long work = (long)tiles * (T + 1);
     const unsigned nets = two_nets ? 2u : 1u;
     {
-        const dim3 grid((unsigned)((work + kWavesPerGroup - 1) / kWavesPerGroup), nets), block(64 * kWavesPerGroup);
-        hipLaunchKernelGGL((input_proj_kernel<H, P>), grid, block, 0, stream, online, target, gi_on, gi_tg, B, T, obs);
+        constexpr int NW = FrontShape<H, P>::kWaves;
+        FrontArgs a{};
+        a.net[0] = online; a.net[1] = target;
+        a.gi[0] = gi_on; a.gi[1] = gi_tg;
+        a.B = B; a.T = T; a.obs = obs;
+        const dim3 grid((unsigned)((work + NW - 1) / NW), nets), block(64 * NW);
+        // the fc2 block count does not enter the projection; one instantiation serves both
+        hipLaunchKernelGGL((front_kernel<H, P, 1, false>), grid, block, 0, stream, a);
         hipError_t err = hipGetLastError();
         if (err != hipSuccess) return err;
         if (between) {

@@ -149,8 +149,8 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
 
     const char *base = static_cast<const char *>(q->dev_weights);
     marl::NetFrags &n = q->net;
-    n.w1 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w1);
-    n.wih = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih);
+    n.act_stream = reinterpret_cast<const marl::bf16x8 *>(base + img.off_act);
+    n.proj_stream = reinterpret_cast<const marl::bf16x8 *>(base + img.off_proj);
     n.whh = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh);
     n.w2 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2);
     n.bias1 = reinterpret_cast<const float *>(base + img.off_bias1);
@@ -161,6 +161,7 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.b2 = reinterpret_cast<const float *>(base + img.off_b2);
     n.N = desc->n_agents; n.D = desc->obs_dim; n.A = desc->n_actions; n.H = desc->hidden;
     n.kc1 = img.kc1; n.mb2 = img.mb2; n.planes = img.planes;
+    n.nc1 = img.nc1; n.act_chunks = img.act_chunks; n.proj_chunks = img.proj_chunks;
     *out = q;
     return MARL_OK;
 }

@@ -48,7 +48,7 @@ __device__ __forceinline__ Frag<P> frag_of_half(const f32x16 &acc, int c)
 
 // acc += Wfrag * b ; `a` points at this lane's 16 bytes of plane 0 of the fragment.
 template <int P>
-__device__ __forceinline__ void mma(f32x16 &acc, const bf16x8 *__restrict__ a, const Frag<P> &b)
+__device__ __forceinline__ void mma(f32x16 &acc, const bf16x8 *a, const Frag<P> &b)
 {
     const bf16x8 ah = a[0];
     if constexpr (P == 2) {
@@ -81,88 +81,21 @@ __device__ __forceinline__ void store_feature_block(float *dst, int blk, int g, 
     }
 }
 
-// Eight observation values 16 kc + 8 g + (0..7) of one row, zero beyond D or for a missing row.
+// Eight observation values 16 kc + 8 g + (0..7) of one row.  Branch-free on purpose: a guarded
+// load makes the compiler wait for each one separately.  Positions at or beyond D are read from
+// clamped (in-row) addresses instead; the weight fragments are zero there, so whatever finite
+// value arrives contributes nothing.  `row` must always point at a readable row.
 __device__ __forceinline__ void load_obs_chunk(const float *__restrict__ row, int D, bool vec4, int kc, int g, float (&v)[8])
 {
     const int k0 = 16 * kc + 8 * g;
-    if (vec4) {   // D % 4 == 0 and the row is 16-byte aligned: whole float4s are in or out of range
-        f32x4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
-        if (row && k0 < D) a = *reinterpret_cast<const f32x4 *>(row + k0);
-        if (row && k0 + 4 < D) b = *reinterpret_cast<const f32x4 *>(row + k0 + 4);
+    if (vec4) {   // D % 4 == 0 and the row is 16-byte aligned
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(row + min(k0, D - 4));
+        const f32x4 b = *reinterpret_cast<const f32x4 *>(row + min(k0 + 4, D - 4));
         v[0] = a[0]; v[1] = a[1]; v[2] = a[2]; v[3] = a[3];
         v[4] = b[0]; v[5] = b[1]; v[6] = b[2]; v[7] = b[3];
     } else {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) v[i] = (row && k0 + i < D) ? row[k0 + i] : 0.0f;
-    }
-}
-
-// fc1 + ReLU for the wave's 32 rows.  obs_row: this lane's row (nullptr if the row does not exist).
-template <int H, int P>
-__device__ __forceinline__ void fc1_tile(const NetFrags &net, const float *__restrict__ obs_row, int agent, int lane,
-                                         Frag<P> (&x)[H / 16])
-{
-    constexpr int MB = H / 32;
-    const int g = lane >> 5;
-    const int KC = net.kc1, D = net.D;
-    const bool vec4 = (D % 4) == 0 && (reinterpret_cast<uintptr_t>(obs_row) & 15u) == 0;
-    f32x16 acc[MB];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[mb] = load_feature_block(net.bias1 + (size_t)agent * H, mb, g);
-
-    const bf16x8 *wf = net.w1 + lane;
-    float cur[8], nxt[8];
-    load_obs_chunk(obs_row, D, vec4, 0, g, cur);
-    for (int kc = 0; kc < KC; ++kc) {
-        if (kc + 1 < KC) load_obs_chunk(obs_row, D, vec4, kc + 1, g, nxt);
-        const Frag<P> b = to_frag<P>(cur);
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb) mma<P>(acc[mb], wf + (size_t)(mb * KC + kc) * P * 64, b);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) cur[i] = nxt[i];
-    }
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][r] = fmaxf(acc[mb][r], 0.0f);
-        x[2 * mb] = frag_of_half<P>(acc[mb], 0);
-        x[2 * mb + 1] = frag_of_half<P>(acc[mb], 1);
-    }
-}
-
-// Input projection of the GRU for one hidden block: gi_r (+ both r biases), gi_z (+ both z biases), gi_n (+ b_in).
-template <int H, int P>
-__device__ __forceinline__ void input_gates_block(const NetFrags &net, const Frag<P> (&x)[H / 16], int fb, int lane,
-                                                  f32x16 &ar, f32x16 &az, f32x16 &ain)
-{
-    constexpr int FB = H / 32, KCH = H / 16;
-    const int g = lane >> 5;
-    ar = load_feature_block(net.bias_r, fb, g);
-    az = load_feature_block(net.bias_z, fb, g);
-    ain = load_feature_block(net.bias_in, fb, g);
-    const bf16x8 *wi = net.wih + lane;
-#pragma unroll
-    for (int kc = 0; kc < KCH; ++kc) {
-        mma<P>(ar, wi + (size_t)((0 * FB + fb) * KCH + kc) * P * 64, x[kc]);
-        mma<P>(az, wi + (size_t)((1 * FB + fb) * KCH + kc) * P * 64, x[kc]);
-        mma<P>(ain, wi + (size_t)((2 * FB + fb) * KCH + kc) * P * 64, x[kc]);
-    }
-}
-
-// Hidden projection added on top: ar += W_hr h, az += W_hz h, ahn = b_hn + W_hn h.
-template <int H, int P>
-__device__ __forceinline__ void hidden_gates_block(const NetFrags &net, const Frag<P> (&hf)[H / 16], int fb, int lane,
-                                                   f32x16 &ar, f32x16 &az, f32x16 &ahn)
-{
-    constexpr int FB = H / 32, KCH = H / 16;
-    const int g = lane >> 5;
-    ahn = load_feature_block(net.bias_hn, fb, g);
-    const bf16x8 *wh = net.whh + lane;
-#pragma unroll
-    for (int kc = 0; kc < KCH; ++kc) {
-        mma<P>(ar, wh + (size_t)((0 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
-        mma<P>(az, wh + (size_t)((1 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
-        mma<P>(ahn, wh + (size_t)((2 * FB + fb) * KCH + kc) * P * 64, hf[kc]);
+        for (int i = 0; i < 8; ++i) v[i] = row[min(k0 + i, D - 1)];
     }
 }
 
@@ -178,21 +111,6 @@ __device__ __forceinline__ f32x16 gru_blend(const f32x16 &ar, const f32x16 &az, 
         out[r] = fmaf(zz, h[r] - nn, nn);            // (1 - z) n + z h
     }
     return out;
-}
-
-// Q = W2 h' + b2: MB2 blocks of 32 actions (rows beyond A are zero weights).
-template <int H, int P, int MB2>
-__device__ __forceinline__ void fc2_tile(const NetFrags &net, const Frag<P> (&hq)[H / 16], int lane, f32x16 (&q)[MB2])
-{
-    constexpr int KCH = H / 16;
-    const int g = lane >> 5;
-    const bf16x8 *w2 = net.w2 + lane;
-#pragma unroll
-    for (int mb = 0; mb < MB2; ++mb) {
-        q[mb] = load_feature_block(net.b2, mb, g);
-#pragma unroll
-        for (int kc = 0; kc < KCH; ++kc) mma<P>(q[mb], w2 + (size_t)(mb * KCH + kc) * P * 64, hq[kc]);
-    }
 }
 
 // Availability of the actions this lane holds, in two steps so that the loads can be issued

@@ -3,7 +3,10 @@
 #include <cstdlib>
 #include <cstring>
 
+#include <vector>
+
 #include "qnet_internal.h"
+#include "stream_layout.h"
 
 namespace marl {
 namespace {
@@ -67,9 +70,13 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     const float *bih = Whh + (size_t)3 * H * H, *bhh = bih + 3 * H, *W2 = bhh + 3 * H, *b2 = W2 + (size_t)A * H;
 
     const size_t frag_bytes = (size_t)planes * 1024;
+    const StreamDims sd = stream_dims(H, planes, mb2);
+    const int nc1 = (kc1 + sd.kpc - 1) / sd.kpc;
+    const int act_chunks = nc1 + FB * sd.cpf + sd.ncf, proj_chunks = nc1 + FB * sd.cpj;
+    const size_t chunk_bytes = (size_t)kChunkPlanes * 1024;
     size_t off = 0;
-    out->off_w1 = off;      off = align256(off + (size_t)FB * kc1 * frag_bytes);
-    out->off_wih = off;     off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
+    out->off_act = off;     off = align256(off + (size_t)act_chunks * chunk_bytes);
+    out->off_proj = off;    off = align256(off + (size_t)proj_chunks * chunk_bytes);
     out->off_whh = off;     off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
     out->off_w2 = off;      off = align256(off + (size_t)mb2 * KCH * frag_bytes);
     out->off_bias1 = off;   off = align256(off + sizeof(float) * (size_t)N * H);
@@ -80,17 +87,54 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     out->off_b2 = off;      off = align256(off + sizeof(float) * 32 * mb2);
     out->bytes = off;
     out->kc1 = kc1; out->mb2 = mb2; out->planes = planes;
+    out->nc1 = nc1; out->act_chunks = act_chunks; out->proj_chunks = proj_chunks;
     char *img = static_cast<char *>(std::calloc(off, 1));
     if (!img) return false;
     out->host = img;
 
-    pack_frags(reinterpret_cast<uint16_t *>(img + out->off_w1), W1, H, D, Din, false, planes);
+    // Fragment arrays per matrix: [block][k-step][plane][512 bf16].
+    const size_t frag_elems = (size_t)planes * 512;
+    std::vector<uint16_t> w1f((size_t)FB * kc1 * frag_elems), wihf((size_t)3 * FB * KCH * frag_elems);
+    uint16_t *whhf = reinterpret_cast<uint16_t *>(img + out->off_whh);
+    uint16_t *w2f = reinterpret_cast<uint16_t *>(img + out->off_w2);
+    pack_frags(w1f.data(), W1, H, D, Din, false, planes);
     for (int gate = 0; gate < 3; ++gate) {
-        const size_t per_gate = (size_t)FB * KCH * frag_bytes;
-        pack_frags(reinterpret_cast<uint16_t *>(img + out->off_wih + gate * per_gate), Wih + (size_t)gate * H * H, H, H, H, true, planes);
-        pack_frags(reinterpret_cast<uint16_t *>(img + out->off_whh + gate * per_gate), Whh + (size_t)gate * H * H, H, H, H, true, planes);
+        const size_t per_gate = (size_t)FB * KCH * frag_elems;
+        pack_frags(wihf.data() + gate * per_gate, Wih + (size_t)gate * H * H, H, H, H, true, planes);
+        pack_frags(whhf + gate * per_gate, Whh + (size_t)gate * H * H, H, H, H, true, planes);
     }
-    pack_frags(reinterpret_cast<uint16_t *>(img + out->off_w2), W2, A, H, H, true, planes);
+    pack_frags(w2f, W2, A, H, H, true, planes);
+
+    // Streams: copy fragments into their order of use; k-steps beyond a matrix stay zero.
+    auto frag_w1 = [&](int mb, int kc) { return kc < kc1 ? w1f.data() + ((size_t)mb * kc1 + kc) * frag_elems : nullptr; };
+    auto frag_gru = [&](const uint16_t *base, int gate, int fb, int kc) { return base + ((size_t)(gate * FB + fb) * KCH + kc) * frag_elems; };
+    auto frag_w2 = [&](int mb, int kc) { return w2f + ((size_t)mb * KCH + kc) * frag_elems; };
+    for (int which = 0; which < 2; ++which) {           // 0: decision step, 1: input projection
+        uint16_t *dst = reinterpret_cast<uint16_t *>(img + (which ? out->off_proj : out->off_act));
+        const size_t chunk_elems = (size_t)kChunkPlanes * 512;
+        int chunk = 0;
+        auto put = [&](int slot, const uint16_t *frag) {   // slot = fragment index inside the chunk
+            if (frag) std::memcpy(dst + chunk * chunk_elems + (size_t)slot * frag_elems, frag, frag_elems * 2);
+        };
+        for (int c = 0; c < nc1; ++c, ++chunk)
+            for (int kk = 0; kk < sd.kpc; ++kk)
+                for (int mb = 0; mb < FB; ++mb) put(kk * FB + mb, frag_w1(mb, c * sd.kpc + kk));
+        const int nmat = which ? 3 : 6, kper = which ? sd.kpj : sd.kpg, cper = which ? sd.cpj : sd.cpf;
+        for (int fb = 0; fb < FB; ++fb)
+            for (int cc = 0; cc < cper; ++cc, ++chunk)
+                for (int kk = 0; kk < kper; ++kk)
+                    for (int m = 0; m < nmat; ++m) {
+                        const int kc = cc * kper + kk;
+                        put(kk * nmat + m, m < 3 ? frag_gru(wihf.data(), m, fb, kc) : frag_gru(whhf, m - 3, fb, kc));
+                    }
+        if (!which)
+            for (int cf = 0; cf < sd.ncf; ++cf, ++chunk)
+                for (int kk = 0; kk < sd.kpf; ++kk)
+                    for (int mb = 0; mb < mb2; ++mb) {
+                        const int kc = cf * sd.kpf + kk;
+                        if (kc < KCH) put(kk * mb2 + mb, frag_w2(mb, kc));
+                    }
+    }
 
     // The agent-id column of W1 is a per-agent bias.  A bf16 network uses the rounded weight.
     float *bias1 = reinterpret_cast<float *>(img + out->off_bias1);

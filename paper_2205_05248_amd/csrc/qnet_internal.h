@@ -26,9 +26,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 // for layers fed by an MFMA result: that is where the 32x32 accumulator layout
 // leaves feature values, so a result converts to the next operand in registers.
 struct NetFrags {
-    const bf16x8 *w1;     // [H/32][kc1][P][64]
-    const bf16x8 *wih;    // [3][H/32][H/16][P][64]   gates r, z, n
-    const bf16x8 *whh;    // [3][H/32][H/16][P][64]
+    const bf16x8 *act_stream;   // decision step: fc1, GRU (6 matrices), fc2 in order of use (stream_layout.h)
+    const bf16x8 *proj_stream;  // input projection: fc1, GRU input matrices in order of use
+    const bf16x8 *whh;    // [3][H/32][H/16][P][64]   gates r, z, n
     const bf16x8 *w2;     // [mb2][H/16][P][64]
     const float *bias1;   // [N][H]   b1 + W1[:, D + n]
     const float *bias_r;  // [H]      b_ir + b_hr
@@ -38,6 +38,8 @@ struct NetFrags {
     const float *b2;      // [32 mb2] zero padded
     int N, D, A, H;
     int kc1;              // ceil(D / 16)
+    int nc1;              // fc1 chunks in the streams
+    int act_chunks, proj_chunks;
     int mb2;              // ceil(A / 32)
     int planes;           // P
 };
@@ -65,8 +67,8 @@ namespace marl {
 struct PackedImage {
     void *host;        // malloc'ed image, caller frees
     size_t bytes;
-    size_t off_w1, off_wih, off_whh, off_w2, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
-    int kc1, mb2, planes;
+    size_t off_act, off_proj, off_whh, off_w2, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
 
