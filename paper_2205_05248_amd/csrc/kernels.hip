@@ -67,22 +67,21 @@ struct FrontArgs {
     int B, T;
 };
 
-// Wavefronts per workgroup: 8 (two per SIMD) when one row tile's operands fit in 256 registers.
-constexpr int front_waves(int H, int P) { return (H * P <= 128) ? 8 : 4; }
-constexpr int front_waves_per_simd(int H, int P) { return front_waves(H, P) / 4; }
-template <int H, int P> struct FrontShape {
-    static constexpr int kWaves = front_waves(H, P);
-    static constexpr int kStage = kChunkVecs / (64 * kWaves);     // 16-byte vectors per thread and chunk
-};
+// Four wavefronts per workgroup, one per SIMD with the whole register file, each owning NC column
+// blocks of 32 rows: a weight fragment read from LDS then feeds NC MFMAs, which keeps LDS reads
+// below the matrix pipe's appetite.  NC = 2 whenever two blocks' operands fit in 512 registers.
+constexpr int kFrontWaves = 4;
+constexpr int kFrontThreads = 64 * kFrontWaves;
+constexpr int kFrontStage = kChunkVecs / kFrontThreads;          // 16-byte vectors per thread and chunk
+constexpr int front_col_blocks(int H, int P) { return (H * P <= 128) ? 2 : 1; }
 
 template <int H, int P, int MB2, bool ACT>
-__global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P)) void front_kernel(
-    const FrontArgs args)
+__global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs args)
 {
     constexpr int MB = H / 32, FB = H / 32, KCH = H / 16;
-    constexpr int NW = FrontShape<H, P>::kWaves, NT = 64 * NW, STG = FrontShape<H, P>::kStage;
+    constexpr int NC = front_col_blocks(H, P), NT = kFrontThreads, STG = kFrontStage;
     constexpr StreamDims SD = stream_dims(H, P, MB2);
-    constexpr int OB = SD.kpc <= 6 ? SD.kpc : 6;      // observation k-steps fetched ahead as one block
+    constexpr int OB = 3;                             // observation k-steps fetched ahead as one block
     constexpr int SUB = SD.kpc / OB;
     static_assert(SD.kpc % OB == 0, "fc1 chunk must hold whole observation blocks");
     __shared__ bf16x8 wbuf[2][kChunkVecs];
@@ -92,29 +91,33 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
     const NetFrags &net = args.net[ACT ? 0 : blockIdx.y];
     const int N = net.N, D = net.D, A = net.A;
 
-    // ---- which rows this wavefront owns
-    bool valid;
-    int row, n;
-    const float *obs_row;
-    [[maybe_unused]] int e = 0;
-    [[maybe_unused]] float *gi_dst = nullptr;
-    if constexpr (ACT) {
-        row = (blockIdx.x * NW + wave) * 32 + col;
-        valid = row < args.rows;
-        e = valid ? row / N : 0;
-        n = valid ? row % N : 0;
-        obs_row = args.obs + (valid ? (size_t)row * D : 0);       // rows past the end read row 0, results unused
-    } else {
-        const int rows = args.B * N, S = args.T + 1, ntiles = (rows + 31) / 32;
-        const long work = (long)blockIdx.x * NW + wave;               // (row tile, slot)
-        const bool in_range = work < (long)ntiles * S;
-        const int rt = in_range ? (int)(work / S) : 0, t = in_range ? (int)(work % S) : 0;
-        row = rt * 32 + col;
-        valid = in_range && row < rows;
-        const int b = valid ? row / N : 0;
-        n = valid ? row % N : 0;
-        obs_row = args.obs + (valid ? (((size_t)b * S + t) * N + n) * D : 0);
-        gi_dst = in_range ? args.gi[blockIdx.y] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
+    // ---- which rows this wavefront owns: column block c holds rows row[c] = 32 (tile + c) + col
+    bool valid[NC];
+    int row[NC], n[NC];
+    const float *obs_row[NC];
+    [[maybe_unused]] int e[NC];
+    [[maybe_unused]] float *gi_dst[NC];
+#pragma unroll
+    for (int c = 0; c < NC; ++c) {
+        if constexpr (ACT) {
+            row[c] = ((blockIdx.x * kFrontWaves + wave) * NC + c) * 32 + col;
+            valid[c] = row[c] < args.rows;
+            e[c] = valid[c] ? row[c] / N : 0;
+            n[c] = valid[c] ? row[c] % N : 0;
+            obs_row[c] = args.obs + (valid[c] ? (size_t)row[c] * D : 0);     // rows past the end read row 0, unused
+        } else {
+            const int rows = args.B * N, S = args.T + 1, ntiles = (rows + 31) / 32, ngroups = (ntiles + NC - 1) / NC;
+            const long work = (long)blockIdx.x * kFrontWaves + wave;      // (group of NC row tiles, slot)
+            const bool in_range = work < (long)ngroups * S;
+            const int rt = (in_range ? (int)(work / S) : 0) * NC + c, t = in_range ? (int)(work % S) : 0;
+            const bool tile_ok = in_range && rt < ntiles;
+            row[c] = rt * 32 + col;
+            valid[c] = tile_ok && row[c] < rows;
+            const int b = valid[c] ? row[c] / N : 0;
+            n[c] = valid[c] ? row[c] % N : 0;
+            obs_row[c] = args.obs + (valid[c] ? (((size_t)b * S + t) * N + n[c]) * D : 0);
+            gi_dst[c] = tile_ok ? args.gi[blockIdx.y] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
+        }
     }
 
     // ---- weight pipeline
@@ -144,37 +147,45 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
     };
     fetch(0);
 
-    // ---- decision step: issue the row's other inputs early
-    [[maybe_unused]] bool keep_h = false;
-    [[maybe_unused]] const float *h_row = nullptr;
-    [[maybe_unused]] const uint8_t *avail_row = nullptr;
-    [[maybe_unused]] uint32_t avail_raw[MB2 * 4];
-    [[maybe_unused]] Frag<P> hf[KCH];
+    // ---- decision step: issue the rows' other inputs early
+    [[maybe_unused]] bool keep_h[NC];
+    [[maybe_unused]] const float *h_row[NC];
+    [[maybe_unused]] const uint8_t *avail_row[NC];
+    [[maybe_unused]] uint32_t avail_raw[NC][MB2 * 4];
+    [[maybe_unused]] Frag<P> hf[NC][KCH];
     if constexpr (ACT) {
-        keep_h = valid && !(args.reset && args.reset[e]);
-        h_row = args.h_in + (size_t)row * H;
-        avail_row = args.avail + (valid ? (size_t)row * A : 0);
-        if (A >= 4) issue_avail_loads<MB2>(avail_row, A, lane, avail_raw);      // consumed after fc2
 #pragma unroll
-        for (int b = 0; b < FB; ++b) {                  // hidden state as operand fragments
-            f32x16 hv;
-            if (keep_h) hv = load_feature_block(h_row, b, g);
-            else
+        for (int c = 0; c < NC; ++c) {
+            keep_h[c] = valid[c] && !(args.reset && args.reset[e[c]]);
+            h_row[c] = args.h_in + (size_t)row[c] * H;
+            avail_row[c] = args.avail + (valid[c] ? (size_t)row[c] * A : 0);
+            if (A >= 4) issue_avail_loads<MB2>(avail_row[c], A, lane, avail_raw[c]);      // consumed after fc2
 #pragma unroll
-                for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
-            hf[2 * b] = frag_of_half<P>(hv, 0);
-            hf[2 * b + 1] = frag_of_half<P>(hv, 1);
+            for (int b = 0; b < FB; ++b) {                  // hidden state as operand fragments
+                f32x16 hv;
+                if (keep_h[c]) hv = load_feature_block(h_row[c], b, g);
+                else
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+                hf[c][2 * b] = frag_of_half<P>(hv, 0);
+                hf[c][2 * b + 1] = frag_of_half<P>(hv, 1);
+            }
         }
     }
 
     // ---- fc1 + ReLU
-    const bool vec4 = (D % 4) == 0 && (reinterpret_cast<uintptr_t>(obs_row) & 15u) == 0;
-    float cur[OB][8], nxt[OB][8];
+    bool vec4 = (D % 4) == 0;
 #pragma unroll
-    for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row, D, vec4, kk, g, cur[kk]);
-    f32x16 acc[MB];
+    for (int c = 0; c < NC; ++c) vec4 = vec4 && (reinterpret_cast<uintptr_t>(obs_row[c]) & 15u) == 0;
+    float cur[NC][OB][8], nxt[NC][OB][8];
+    f32x16 acc[NC][MB];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) acc[mb] = load_feature_block(net.bias1 + (size_t)n * H, mb, g);
+    for (int c = 0; c < NC; ++c) {
+#pragma unroll
+        for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row[c], D, vec4, kk, g, cur[c][kk]);
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb) acc[c][mb] = load_feature_block(net.bias1 + (size_t)n[c] * H, mb, g);
+    }
     commit(0);
     fetch(1);
     lds_barrier();
@@ -185,38 +196,56 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
         for (int s = 0; s < SUB; ++s) {
             const int next_block = c1 * SUB + s + 1;
 #pragma unroll
-            for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row, D, vec4, next_block * OB + kk, g, nxt[kk]);
+            for (int c = 0; c < NC; ++c)
+#pragma unroll
+                for (int kk = 0; kk < OB; ++kk) load_obs_chunk(obs_row[c], D, vec4, next_block * OB + kk, g, nxt[c][kk]);
 #pragma unroll
             for (int kk = 0; kk < OB; ++kk) {
-                const Frag<P> bfrag = to_frag<P>(cur[kk]);
+                Frag<P> bfrag[NC];
 #pragma unroll
-                for (int mb = 0; mb < MB; ++mb) mma<P>(acc[mb], wb + (((s * OB + kk) * MB + mb) * P) * 64, bfrag);
+                for (int c = 0; c < NC; ++c) bfrag[c] = to_frag<P>(cur[c][kk]);
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const WFrag<P> w = load_wfrag<P>(wb + (((s * OB + kk) * MB + mb) * P) * 64);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) mma<P>(acc[c][mb], w, bfrag[c]);
+                }
             }
 #pragma unroll
-            for (int kk = 0; kk < OB; ++kk)
+            for (int c = 0; c < NC; ++c)
 #pragma unroll
-                for (int i = 0; i < 8; ++i) cur[kk][i] = nxt[kk][i];
+                for (int kk = 0; kk < OB; ++kk)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) cur[c][kk][i] = nxt[c][kk][i];
         }
         advance();
     }
-    Frag<P> x[KCH];
+    Frag<P> x[NC][KCH];
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) {
+    for (int c = 0; c < NC; ++c)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mb][r] = fmaxf(acc[mb][r], 0.0f);
-        x[2 * mb] = frag_of_half<P>(acc[mb], 0);
-        x[2 * mb + 1] = frag_of_half<P>(acc[mb], 1);
-    }
+        for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[c][mb][r] = fmaxf(acc[c][mb][r], 0.0f);
+            x[c][2 * mb] = frag_of_half<P>(acc[c][mb], 0);
+            x[c][2 * mb + 1] = frag_of_half<P>(acc[c][mb], 1);
+        }
 
     // ---- GRU
-    [[maybe_unused]] Frag<P> hq[KCH];
+    [[maybe_unused]] Frag<P> hq[NC][KCH];
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {
-        f32x16 ar = load_feature_block(net.bias_r, fb, g);
-        f32x16 az = load_feature_block(net.bias_z, fb, g);
-        f32x16 ain = load_feature_block(net.bias_in, fb, g);
+        f32x16 ar[NC], az[NC], ain[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            ar[c] = load_feature_block(net.bias_r, fb, g);
+            az[c] = load_feature_block(net.bias_z, fb, g);
+            ain[c] = load_feature_block(net.bias_in, fb, g);
+        }
         if constexpr (ACT) {
-            f32x16 ahn = load_feature_block(net.bias_hn, fb, g);
+            f32x16 ahn[NC];
+#pragma unroll
+            for (int c = 0; c < NC; ++c) ahn[c] = load_feature_block(net.bias_hn, fb, g);
 #pragma unroll
             for (int cc = 0; cc < SD.cpf; ++cc) {
                 const bf16x8 *wb = &wbuf[chunk & 1][lane];
@@ -224,24 +253,33 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
                 for (int kk = 0; kk < SD.kpg; ++kk) {
                     const int kc = cc * SD.kpg + kk;
                     const bf16x8 *m = wb + (kk * 6 * P) * 64;
-                    mma<P>(ar, m + 0 * P * 64, x[kc]);
-                    mma<P>(az, m + 1 * P * 64, x[kc]);
-                    mma<P>(ain, m + 2 * P * 64, x[kc]);
-                    mma<P>(ar, m + 3 * P * 64, hf[kc]);
-                    mma<P>(az, m + 4 * P * 64, hf[kc]);
-                    mma<P>(ahn, m + 5 * P * 64, hf[kc]);
+                    const WFrag<P> wir = load_wfrag<P>(m + 0 * P * 64), wiz = load_wfrag<P>(m + 1 * P * 64);
+                    const WFrag<P> win = load_wfrag<P>(m + 2 * P * 64), whr = load_wfrag<P>(m + 3 * P * 64);
+                    const WFrag<P> whz = load_wfrag<P>(m + 4 * P * 64), whn = load_wfrag<P>(m + 5 * P * 64);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        mma<P>(ar[c], wir, x[c][kc]);
+                        mma<P>(az[c], wiz, x[c][kc]);
+                        mma<P>(ain[c], win, x[c][kc]);
+                        mma<P>(ar[c], whr, hf[c][kc]);
+                        mma<P>(az[c], whz, hf[c][kc]);
+                        mma<P>(ahn[c], whn, hf[c][kc]);
+                    }
                 }
                 advance();
             }
-            f32x16 hv;                                       // exact fp32 hidden state for the blend
-            if (keep_h) hv = load_feature_block(h_row, fb, g);
-            else
 #pragma unroll
-                for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
-            const f32x16 hn = gru_blend(ar, az, ain, ahn, hv);
-            if (valid) store_feature_block(args.h_out + (size_t)row * H, fb, g, hn);
-            hq[2 * fb] = frag_of_half<P>(hn, 0);
-            hq[2 * fb + 1] = frag_of_half<P>(hn, 1);
+            for (int c = 0; c < NC; ++c) {
+                f32x16 hv;                                       // exact fp32 hidden state for the blend
+                if (keep_h[c]) hv = load_feature_block(h_row[c], fb, g);
+                else
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) hv[r] = 0.0f;
+                const f32x16 hn = gru_blend(ar[c], az[c], ain[c], ahn[c], hv);
+                if (valid[c]) store_feature_block(args.h_out + (size_t)row[c] * H, fb, g, hn);
+                hq[c][2 * fb] = frag_of_half<P>(hn, 0);
+                hq[c][2 * fb + 1] = frag_of_half<P>(hn, 1);
+            }
         } else {
 #pragma unroll
             for (int cc = 0; cc < SD.cpj; ++cc) {
@@ -250,25 +288,34 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
                 for (int kk = 0; kk < SD.kpj; ++kk) {
                     const int kc = cc * SD.kpj + kk;
                     const bf16x8 *m = wb + (kk * 3 * P) * 64;
-                    mma<P>(ar, m + 0 * P * 64, x[kc]);
-                    mma<P>(az, m + 1 * P * 64, x[kc]);
-                    mma<P>(ain, m + 2 * P * 64, x[kc]);
+                    const WFrag<P> wir = load_wfrag<P>(m + 0 * P * 64), wiz = load_wfrag<P>(m + 1 * P * 64);
+                    const WFrag<P> win = load_wfrag<P>(m + 2 * P * 64);
+#pragma unroll
+                    for (int c = 0; c < NC; ++c) {
+                        mma<P>(ar[c], wir, x[c][kc]);
+                        mma<P>(az[c], wiz, x[c][kc]);
+                        mma<P>(ain[c], win, x[c][kc]);
+                    }
                 }
                 advance();
             }
-            if (gi_dst) {
-                store_gi_block(gi_dst + (size_t)(0 * FB + fb) * 1024, lane, ar);
-                store_gi_block(gi_dst + (size_t)(1 * FB + fb) * 1024, lane, az);
-                store_gi_block(gi_dst + (size_t)(2 * FB + fb) * 1024, lane, ain);
-            }
+#pragma unroll
+            for (int c = 0; c < NC; ++c)
+                if (gi_dst[c]) {
+                    store_gi_block(gi_dst[c] + (size_t)(0 * FB + fb) * 1024, lane, ar[c]);
+                    store_gi_block(gi_dst[c] + (size_t)(1 * FB + fb) * 1024, lane, az[c]);
+                    store_gi_block(gi_dst[c] + (size_t)(2 * FB + fb) * 1024, lane, ain[c]);
+                }
         }
     }
 
     // ---- fc2, mask, action
     if constexpr (ACT) {
-        f32x16 q[MB2];
+        f32x16 q[NC][MB2];
 #pragma unroll
-        for (int mb = 0; mb < MB2; ++mb) q[mb] = load_feature_block(net.b2, mb, g);
+        for (int c = 0; c < NC; ++c)
+#pragma unroll
+            for (int mb = 0; mb < MB2; ++mb) q[c][mb] = load_feature_block(net.b2, mb, g);
 #pragma unroll
         for (int cf = 0; cf < SD.ncf; ++cf) {
             const bf16x8 *wb = &wbuf[chunk & 1][lane];
@@ -277,22 +324,28 @@ __global__ __launch_bounds__(64 * front_waves(H, P), front_waves_per_simd(H, P))
                 const int kc = cf * SD.kpf + kk;
                 if (kc < KCH) {
 #pragma unroll
-                    for (int mb = 0; mb < MB2; ++mb) mma<P>(q[mb], wb + ((kk * MB2 + mb) * P) * 64, hq[kc]);
+                    for (int mb = 0; mb < MB2; ++mb) {
+                        const WFrag<P> w = load_wfrag<P>(wb + ((kk * MB2 + mb) * P) * 64);
+#pragma unroll
+                        for (int c = 0; c < NC; ++c) mma<P>(q[c][mb], w, hq[c][kc]);
+                    }
                 }
             }
             advance();
         }
-        if (args.q_out && valid) store_q_row<MB2>(args.q_out + (size_t)row * A, q, A, lane);
-
-        const uint32_t slots = A >= 4 ? avail_mask_from_raw<MB2>(avail_raw, A, lane, valid)
-                                      : avail_mask_small(avail_row, A, lane, valid);
-        float best_q; int best;
-        masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
-        const uint64_t bits = row_avail_bits<MB2>(slots, lane);
-        if (valid && g == 0) {
-            if (best < 0) best = 0;
-            args.action[row] = eps_greedy_pick(best, bits, args.epsilon, args.seed, (uint32_t)e, (uint32_t)n,
-                                               (uint32_t)args.step_t[e]);
+#pragma unroll
+        for (int c = 0; c < NC; ++c) {
+            if (args.q_out && valid[c]) store_q_row<MB2>(args.q_out + (size_t)row[c] * A, q[c], A, lane);
+            const uint32_t slots = A >= 4 ? avail_mask_from_raw<MB2>(avail_raw[c], A, lane, valid[c])
+                                          : avail_mask_small(avail_row[c], A, lane, valid[c]);
+            float best_q; int best;
+            masked_argmax_slots<MB2>(q[c], slots, lane, best_q, best);
+            const uint64_t bits = row_avail_bits<MB2>(slots, lane);
+            if (valid[c] && g == 0) {
+                if (best < 0) best = 0;
+                args.action[row[c]] = eps_greedy_pick(best, bits, args.epsilon, args.seed, (uint32_t)e[c],
+                                                      (uint32_t)n[c], (uint32_t)args.step_t[e[c]]);
+            }
         }
     }
 }
@@ -538,13 +591,12 @@ hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const u
                         const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
                         int32_t *action, float *q_out, hipStream_t stream)
 {
-    constexpr int NW = FrontShape<H, P>::kWaves;
+    constexpr int RPW = 32 * front_col_blocks(H, P) * kFrontWaves;     // rows per workgroup
     FrontArgs a{};
     a.net[0] = net;
     a.rows = rows; a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
     a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out;
-    const int tiles = (rows + 31) / 32;
-    const dim3 grid((unsigned)((tiles + NW - 1) / NW)), block(64 * NW);
+    const dim3 grid((unsigned)((rows + RPW - 1) / RPW)), block(kFrontThreads);
     if (net.mb2 == 1) hipLaunchKernelGGL((front_kernel<H, P, 1, true>), grid, block, 0, stream, a);
     else              hipLaunchKernelGGL((front_kernel<H, P, 2, true>), grid, block, 0, stream, a);
     return hipGetLastError();
@@ -558,15 +610,15 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
                            hipEvent_t between)
 {
     const int rows = B * online.N, tiles = (rows + 31) / 32;
-    const long work = (long)tiles * (T + 1);
     const unsigned nets = two_nets ? 2u : 1u;
     {
-        constexpr int NW = FrontShape<H, P>::kWaves;
+        constexpr int NC = front_col_blocks(H, P);
+        const long groups = (long)((tiles + NC - 1) / NC) * (T + 1);      // wavefront work items
         FrontArgs a{};
         a.net[0] = online; a.net[1] = target;
         a.gi[0] = gi_on; a.gi[1] = gi_tg;
         a.B = B; a.T = T; a.obs = obs;
-        const dim3 grid((unsigned)((work + NW - 1) / NW), nets), block(64 * NW);
+        const dim3 grid((unsigned)((groups + kFrontWaves - 1) / kFrontWaves), nets), block(kFrontThreads);
         // the fc2 block count does not enter the projection; one instantiation serves both
         hipLaunchKernelGGL((front_kernel<H, P, 1, false>), grid, block, 0, stream, a);
         hipError_t err = hipGetLastError();

@@ -59,6 +59,30 @@ __device__ __forceinline__ void mma(f32x16 &acc, const bf16x8 *a, const Frag<P> 
     acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b.hi, acc, 0, 0, 0);
 }
 
+// A weight fragment held in registers so that it can feed several column blocks.
+template <int P> struct WFrag;
+template <> struct WFrag<1> { bf16x8 hi; };
+template <> struct WFrag<2> { bf16x8 hi, lo; };
+
+template <int P>
+__device__ __forceinline__ WFrag<P> load_wfrag(const bf16x8 *a)
+{
+    WFrag<P> w;
+    w.hi = a[0];
+    if constexpr (P == 2) w.lo = a[64];
+    return w;
+}
+
+template <int P>
+__device__ __forceinline__ void mma(f32x16 &acc, const WFrag<P> &w, const Frag<P> &b)
+{
+    if constexpr (P == 2) {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.lo, b.hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.hi, b.lo, acc, 0, 0, 0);
+    }
+    acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w.hi, b.hi, acc, 0, 0, 0);
+}
+
 // Feature held in accumulator slot r of block `blk` by a lane of half g: 32 blk + 8 (r / 4) + 4 g + r % 4.
 // The four slots 4j .. 4j+3 are consecutive features, so per-feature tables load as float4.
 __device__ __forceinline__ f32x16 load_feature_block(const float *table, int blk, int g)
