@@ -65,6 +65,7 @@ struct FrontArgs {
     // input projection
     float *gi[2];
     int B, T;
+    unsigned nets;              // 1 or 2
 };
 
 // Four wavefronts per workgroup, one per SIMD with the whole register file, each owning NC column
@@ -88,7 +89,11 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
 
     const int tid = threadIdx.x, lane = tid & 63, g = lane >> 5, col = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const NetFrags &net = args.net[ACT ? 0 : blockIdx.y];
+    // projection: the two networks' workgroups alternate in launch order, so the second one to
+    // read an observation tile finds it in cache
+    const int net_id = ACT ? 0 : (int)(blockIdx.x % args.nets);
+    const unsigned group_id = ACT ? blockIdx.x : blockIdx.x / args.nets;
+    const NetFrags &net = args.net[net_id];
     const int N = net.N, D = net.D, A = net.A;
 
     // ---- which rows this wavefront owns: column block c holds rows row[c] = 32 (tile + c) + col
@@ -100,14 +105,14 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         if constexpr (ACT) {
-            row[c] = ((blockIdx.x * kFrontWaves + wave) * NC + c) * 32 + col;
+            row[c] = ((group_id * kFrontWaves + wave) * NC + c) * 32 + col;
             valid[c] = row[c] < args.rows;
             e[c] = valid[c] ? row[c] / N : 0;
             n[c] = valid[c] ? row[c] % N : 0;
             obs_row[c] = args.obs + (valid[c] ? (size_t)row[c] * D : 0);     // rows past the end read row 0, unused
         } else {
             const int rows = args.B * N, S = args.T + 1, ntiles = (rows + 31) / 32, ngroups = (ntiles + NC - 1) / NC;
-            const long work = (long)blockIdx.x * kFrontWaves + wave;      // (group of NC row tiles, slot)
+            const long work = (long)group_id * kFrontWaves + wave;        // (group of NC row tiles, slot)
             const bool in_range = work < (long)ngroups * S;
             const int rt = (in_range ? (int)(work / S) : 0) * NC + c, t = in_range ? (int)(work % S) : 0;
             const bool tile_ok = in_range && rt < ntiles;
@@ -116,7 +121,7 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
             const int b = valid[c] ? row[c] / N : 0;
             n[c] = valid[c] ? row[c] % N : 0;
             obs_row[c] = args.obs + (valid[c] ? (((size_t)b * S + t) * N + n[c]) * D : 0);
-            gi_dst[c] = tile_ok ? args.gi[blockIdx.y] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
+            gi_dst[c] = tile_ok ? args.gi[net_id] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
         }
     }
 
@@ -595,7 +600,7 @@ hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const u
     FrontArgs a{};
     a.net[0] = net;
     a.rows = rows; a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
-    a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out;
+    a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out; a.nets = 1;
     const dim3 grid((unsigned)((rows + RPW - 1) / RPW)), block(kFrontThreads);
     if (net.mb2 == 1) hipLaunchKernelGGL((front_kernel<H, P, 1, true>), grid, block, 0, stream, a);
     else              hipLaunchKernelGGL((front_kernel<H, P, 2, true>), grid, block, 0, stream, a);
@@ -617,8 +622,8 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
         FrontArgs a{};
         a.net[0] = online; a.net[1] = target;
         a.gi[0] = gi_on; a.gi[1] = gi_tg;
-        a.B = B; a.T = T; a.obs = obs;
-        const dim3 grid((unsigned)((groups + kFrontWaves - 1) / kFrontWaves), nets), block(kFrontThreads);
+        a.B = B; a.T = T; a.obs = obs; a.nets = nets;
+        const dim3 grid((unsigned)((groups + kFrontWaves - 1) / kFrontWaves) * nets), block(kFrontThreads);
         // the fc2 block count does not enter the projection; one instantiation serves both
         hipLaunchKernelGGL((front_kernel<H, P, 1, false>), grid, block, 0, stream, a);
         hipError_t err = hipGetLastError();
