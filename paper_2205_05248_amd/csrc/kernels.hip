@@ -34,18 +34,59 @@ __device__ __forceinline__ void lds_barrier()
 // sits in registers on its way to the other LDS buffer and chunk c+2 is in flight from L2.
 // One LDS-only barrier per chunk.
 //
-// Scratch layout written by the input projection, fp32:
-// [row tile][slot][3 gates][H/32][4][64 lanes][4]: accumulator slots 4j .. 4j+3 of lane l are the
-// float4 at [..][j][l], so every wave-wide access is 1 KiB contiguous.
-constexpr int kGiPiece = 64 * 4;   // floats per [j] piece
+// Scratch written by the input projection and read by the recurrent kernel: one record per
+// (row tile, slot) holding, for each gate and hidden block, the 32x32 accumulator of that block in
+// lane order, so that every wave-wide access is contiguous.
+//   fp32 networks: fp32 values, [3 gates][H/32][4][64 lanes][4]   (slots 4j..4j+3 of lane l at [j][l])
+//   bf16 networks: bf16 values, [3 gates][H/32][2][64 lanes][8]   (slots 8p..8p+7 of lane l at [p][l])
+// bf16 halves the traffic of the two kernels, which are bound by it; the rounding (2^-9 relative on
+// pre-activations of order one) stays well inside that mode's tolerance.
+template <int P> struct GiLayout {
+    static constexpr bool kBf16 = P == 1;
+    static constexpr int kBlockBytes = kBf16 ? 2048 : 4096;            // one gate, one hidden block
+    static constexpr int block_vecs() { return kBlockBytes / 16; }
+};
 
-__device__ __forceinline__ void store_gi_block(float *__restrict__ dst, int lane, const f32x16 &v)
+template <int P>
+__device__ __forceinline__ void store_gi_block(char *__restrict__ dst, int lane, const f32x16 &v)
 {
+    if constexpr (GiLayout<P>::kBf16) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const f32x4 t = {v[4 * j + 0], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
-        *reinterpret_cast<f32x4 *>(dst + j * kGiPiece + lane * 4) = t;
+        for (int p = 0; p < 2; ++p) {
+            bf16x8 t;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t[i] = (__bf16)v[8 * p + i];
+            *reinterpret_cast<bf16x8 *>(dst + p * 1024 + lane * 16) = t;
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 t = {v[4 * j + 0], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
+            *reinterpret_cast<f32x4 *>(dst + j * 1024 + lane * 16) = t;
+        }
     }
+}
+
+// The same block read back from an LDS copy of the record.
+template <int P>
+__device__ __forceinline__ f32x16 load_gi_block(const char *src, int lane)
+{
+    f32x16 v;
+    if constexpr (GiLayout<P>::kBf16) {
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(src + p * 1024 + lane * 16);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[8 * p + i] = (float)t[i];
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const f32x4 t = *reinterpret_cast<const f32x4 *>(src + j * 1024 + lane * 16);
+            v[4 * j + 0] = t[0]; v[4 * j + 1] = t[1]; v[4 * j + 2] = t[2]; v[4 * j + 3] = t[3];
+        }
+    }
+    return v;
 }
 
 struct FrontArgs {
@@ -63,7 +104,7 @@ struct FrontArgs {
     int32_t *action;
     float *q_out;
     // input projection
-    float *gi[2];
+    char *gi[2];
     int B, T;
     unsigned nets;              // 1 or 2
 };
@@ -101,7 +142,7 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
     int row[NC], n[NC];
     const float *obs_row[NC];
     [[maybe_unused]] int e[NC];
-    [[maybe_unused]] float *gi_dst[NC];
+    [[maybe_unused]] char *gi_dst[NC];
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         if constexpr (ACT) {
@@ -121,7 +162,7 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
             const int b = valid[c] ? row[c] / N : 0;
             n[c] = valid[c] ? row[c] % N : 0;
             obs_row[c] = args.obs + (valid[c] ? (((size_t)b * S + t) * N + n[c]) * D : 0);
-            gi_dst[c] = tile_ok ? args.gi[net_id] + ((size_t)rt * S + t) * (3 * FB * 1024) : nullptr;
+            gi_dst[c] = tile_ok ? args.gi[net_id] + ((size_t)rt * S + t) * (3 * FB * GiLayout<P>::kBlockBytes) : nullptr;
         }
     }
 
@@ -307,9 +348,9 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
 #pragma unroll
             for (int c = 0; c < NC; ++c)
                 if (gi_dst[c]) {
-                    store_gi_block(gi_dst[c] + (size_t)(0 * FB + fb) * 1024, lane, ar[c]);
-                    store_gi_block(gi_dst[c] + (size_t)(1 * FB + fb) * 1024, lane, az[c]);
-                    store_gi_block(gi_dst[c] + (size_t)(2 * FB + fb) * 1024, lane, ain[c]);
+                    store_gi_block<P>(gi_dst[c] + (0 * FB + fb) * GiLayout<P>::kBlockBytes, lane, ar[c]);
+                    store_gi_block<P>(gi_dst[c] + (1 * FB + fb) * GiLayout<P>::kBlockBytes, lane, az[c]);
+                    store_gi_block<P>(gi_dst[c] + (2 * FB + fb) * GiLayout<P>::kBlockBytes, lane, ain[c]);
                 }
         }
     }
@@ -370,36 +411,38 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
 // grid = (row tiles, networks).  blockIdx.y = 0: online network, emits q_taken (and q_all);
 // blockIdx.y = 1 (distinct target network): emits next_max and td_target.  With one network a
 // single pass emits everything.
-template <int H> struct RecurrentShape {
+constexpr int recurrent_waves(int H) { return H / 32 + 1 + (H == 128 ? 3 : 1); }
+template <int H, int P> struct RecurrentShape {
     static constexpr int kCompute = H / 32;
     static constexpr int kPrefetch = H == 128 ? 3 : 1;
     static constexpr int kWaves = kCompute + 1 + kPrefetch;
-    static constexpr int kGiFloats = 3 * (H / 32) * 1024;                // per (tile, slot)
-    static constexpr int kVecPerLane = kGiFloats / 4 / 64 / kPrefetch;   // float4 per prefetch lane and slot
+    static constexpr int kGiBytes = 3 * (H / 32) * GiLayout<P>::kBlockBytes;   // per (tile, slot)
+    static constexpr int kVecPerLane = kGiBytes / 16 / 64 / kPrefetch;         // 16-byte vectors per prefetch lane and slot
+    static_assert(kVecPerLane * 16 * 64 * kPrefetch == kGiBytes, "record must split evenly over the prefetch lanes");
 };
 
 template <int H, int P, int MB2, bool QALL>
-__global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_td_kernel(
-    NetFrags online, NetFrags target, const float *__restrict__ gi_online, const float *__restrict__ gi_target,
+__global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kernel(
+    NetFrags online, NetFrags target, const char *__restrict__ gi_online, const char *__restrict__ gi_target,
     int two_nets, int B, int T, const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
     const float *__restrict__ reward, const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled,
     float gamma, float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target,
     float *__restrict__ q_all)
 {
-    using Shape = RecurrentShape<H>;
+    using Shape = RecurrentShape<H, P>;
     constexpr int FB = H / 32, KCH = H / 16;
-    __shared__ __attribute__((aligned(16))) float gi_lds[2][Shape::kGiFloats];
+    __shared__ __attribute__((aligned(16))) char gi_lds[2][Shape::kGiBytes];
     __shared__ bf16x8 h_lds[2][KCH][P][64];
     __shared__ __attribute__((aligned(16))) float b2_lds[32 * MB2];
 
     const bool is_target = blockIdx.y == 1;
     const NetFrags &net = is_target ? target : online;
-    const float *__restrict__ gi = is_target ? gi_target : gi_online;
+    const char *__restrict__ gi = is_target ? gi_target : gi_online;
     const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int S = T + 1;
     const int rt = blockIdx.x;
-    const float *gi_tile = gi + (size_t)rt * S * Shape::kGiFloats;
+    const char *gi_tile = gi + (size_t)rt * S * Shape::kGiBytes;
 
     if (wave < Shape::kCompute) {
         // ---------------------------------------------------------------- compute wave
@@ -430,11 +473,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                 f32x16 acc[3];
 #pragma unroll
                 for (int gate = 0; gate < 2; ++gate)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        const f32x4 v = *reinterpret_cast<const f32x4 *>(&gi_lds[cur][(gate * FB + fb) * 1024 + j * kGiPiece + lane * 4]);
-                        acc[gate][4 * j + 0] = v[0]; acc[gate][4 * j + 1] = v[1]; acc[gate][4 * j + 2] = v[2]; acc[gate][4 * j + 3] = v[3];
-                    }
+                    acc[gate] = load_gi_block<P>(&gi_lds[cur][(gate * FB + fb) * GiLayout<P>::kBlockBytes], lane);
                 acc[2] = bias_hn;
 #pragma unroll
                 for (int kc = 0; kc < KCH; ++kc) {
@@ -450,12 +489,7 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
                         acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][0], hb.hi, acc[gate], 0, 0, 0);
                     }
                 }
-                f32x16 ain;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const f32x4 v = *reinterpret_cast<const f32x4 *>(&gi_lds[cur][(2 * FB + fb) * 1024 + j * kGiPiece + lane * 4]);
-                    ain[4 * j + 0] = v[0]; ain[4 * j + 1] = v[1]; ain[4 * j + 2] = v[2]; ain[4 * j + 3] = v[3];
-                }
+                const f32x16 ain = load_gi_block<P>(&gi_lds[cur][(2 * FB + fb) * GiLayout<P>::kBlockBytes], lane);
                 h = gru_blend(acc[0], acc[1], ain, acc[2], h);
 #pragma unroll
                 for (int c = 0; c < 2; ++c) {
@@ -563,16 +597,16 @@ __global__ __launch_bounds__(64 * RecurrentShape<H>::kWaves, 2) void recurrent_t
         // ---------------------------------------------------------------- prefetch wave
         constexpr int V = Shape::kVecPerLane;
         const int p = wave - Shape::kCompute - 1;
-        const int base = (p * V * 64 + lane) * 4;                        // float offset of this lane's first float4
+        const int base = (p * V * 64 + lane) * 16;                       // byte offset of this lane's first vector
         f32x4 stage[V];
         auto fetch = [&](int slot) {
-            const float *src = gi_tile + (size_t)slot * Shape::kGiFloats + base;
+            const char *src = gi_tile + (size_t)slot * Shape::kGiBytes + base;
 #pragma unroll
-            for (int i = 0; i < V; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(src + i * 256);
+            for (int i = 0; i < V; ++i) stage[i] = *reinterpret_cast<const f32x4 *>(src + i * 1024);
         };
         auto publish = [&](int buf) {
 #pragma unroll
-            for (int i = 0; i < V; ++i) *reinterpret_cast<f32x4 *>(&gi_lds[buf][base + i * 256]) = stage[i];
+            for (int i = 0; i < V; ++i) *reinterpret_cast<f32x4 *>(&gi_lds[buf][base + i * 1024]) = stage[i];
         };
         fetch(0);
         publish(0);
@@ -608,7 +642,7 @@ hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const u
 }
 
 template <int H, int P>
-hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, float *gi_on, float *gi_tg,
+hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, char *gi_on, char *gi_tg,
                            int B, int T, const float *obs, const uint8_t *avail, const int32_t *actions,
                            const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
                            float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream,
@@ -633,7 +667,7 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
             if (err != hipSuccess) return err;
         }
     }
-    const dim3 grid((unsigned)tiles, nets), block(64 * RecurrentShape<H>::kWaves);
+    const dim3 grid((unsigned)tiles, nets), block(64 * RecurrentShape<H, P>::kWaves);
     const int two = two_nets ? 1 : 0;
 #define MARL_REC(MB, QA)                                                                                             \
     hipLaunchKernelGGL((recurrent_td_kernel<H, P, MB, QA>), grid, block, 0, stream, online, target, gi_on, gi_tg, two,  \
@@ -664,7 +698,8 @@ hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const u
 size_t unroll_scratch_bytes(const NetFrags &net, int B, int T)
 {
     const size_t tiles = ((size_t)B * net.N + 31) / 32;
-    return tiles * (size_t)(T + 1) * 3 * net.H * 32 * sizeof(float);
+    const size_t block_bytes = net.planes == 1 ? GiLayout<1>::kBlockBytes : GiLayout<2>::kBlockBytes;
+    return tiles * (size_t)(T + 1) * 3 * (net.H / 32) * block_bytes;
 }
 
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
@@ -673,7 +708,7 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
                             float *q_all, hipStream_t stream, hipEvent_t between)
 {
-    float *gi_on = static_cast<float *>(scratch_online), *gi_tg = static_cast<float *>(scratch_target);
+    char *gi_on = static_cast<char *>(scratch_online), *gi_tg = static_cast<char *>(scratch_target);
 #define MARL_UNROLL(HH, PP)                                                                                        \
     return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, obs, avail, actions, reward,      \
                                    terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream, between)
