@@ -142,10 +142,18 @@ int marl_act_step(marl_qnet *q, int32_t E,
  * Both networks start from a zero hidden state at slot 0 and keep stepping
  * through padding.  Actions outside [0,A) are clamped into range.
  *
- * Scratch: the library keeps one device buffer per handle for intermediate
- * activations, grown (never shrunk) when a call needs more than any earlier
- * call; growing synchronises the device.  marl_qnet_reserve_unroll sizes it
- * ahead of time so that later calls up to that size allocate nothing.
+ * Two implementations exist and compute the same function (see
+ * marl_qnet_set_unroll_path).  The two-kernel path writes the input half of
+ * the GRU gates for every slot to a scratch buffer and then runs the
+ * recurrence; the fused path keeps every intermediate on chip and needs no
+ * scratch, but only serves networks whose shape fits its on-chip buffers
+ * (obs_dim <= 384 and, for fp32 weights, hidden = 64 with obs_dim <= 272).
+ *
+ * Scratch (two-kernel path only): the library keeps one device buffer per
+ * handle for intermediate activations, grown (never shrunk) when a call needs
+ * more than any earlier call; growing synchronises the device.
+ * marl_qnet_reserve_unroll sizes it ahead of time so that later calls up to
+ * that size allocate nothing (it does nothing for handles on the fused path).
  */
 int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
                    const float *obs, const uint8_t *avail, const int32_t *actions,
@@ -157,13 +165,26 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*
+ * Choice of the unroll implementation for calls whose `online` handle is q.
+ *   MARL_UNROLL_AUTO   the faster one for the network's shape (the default)
+ *   MARL_UNROLL_SPLIT  always the two-kernel path
+ *   MARL_UNROLL_FUSED  always the fused kernel; MARL_ERR_BAD_DIM if the network does not fit it
+ * Returns MARL_ERR_BAD_ARG for any other value.
+ */
+#define MARL_UNROLL_AUTO 0
+#define MARL_UNROLL_SPLIT 1
+#define MARL_UNROLL_FUSED 2
+int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path);
+
+/*
  * Kernel timing for benchmarks.  While timing is enabled on a handle, marl_act_step and
  * marl_unroll_td (the `online` handle's setting counts) record HIP events on the caller's
  * stream around each kernel they launch, for up to MARL_TIMING_MAX_CALLS calls (later calls
  * run untimed).  marl_qnet_timing_read waits for the recorded events, returns the mean
  * duration in milliseconds of each kernel over the recorded calls, and clears the record:
  *   act_ms      decision-step kernel, over *act_calls calls
- *   unroll_ms   [0] input-projection kernel, [1] recurrent TD kernel, over *unroll_calls calls
+ *   unroll_ms   two-kernel path: [0] input-projection kernel, [1] recurrent TD kernel;
+ *               fused path: [0] is 0 and [1] the fused kernel; over *unroll_calls calls
  * Means of zero calls are 0.  Event records cost a little stream time; leave timing off in
  * production.  Enabling or disabling clears the record.
  */

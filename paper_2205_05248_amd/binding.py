@@ -20,7 +20,8 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
-           "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read"]
+           "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
+           "marl_qnet_set_unroll_path"]
 
 
 class MarlError(RuntimeError):
@@ -62,6 +63,8 @@ def load():
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
+        lib.marl_qnet_set_unroll_path.restype = ctypes.c_int
+        lib.marl_qnet_set_unroll_path.argtypes = [vp, i32]
         lib.marl_qnet_set_timing.restype = ctypes.c_int
         lib.marl_qnet_set_timing.argtypes = [vp, i32]
         lib.marl_qnet_timing_read.restype = ctypes.c_int
@@ -153,6 +156,13 @@ def marl_qnet_reserve_unroll(handle, B, T):
     check(load().marl_qnet_reserve_unroll(ctypes.c_void_p(handle), B, T))
 
 
+UNROLL_AUTO, UNROLL_SPLIT, UNROLL_FUSED = 0, 1, 2
+
+
+def marl_qnet_set_unroll_path(handle, path):
+    check(load().marl_qnet_set_unroll_path(ctypes.c_void_p(handle), int(path)))
+
+
 def marl_qnet_set_timing(handle, enable):
     check(load().marl_qnet_set_timing(ctypes.c_void_p(handle), int(bool(enable))))
 
@@ -184,6 +194,9 @@ class QNet:
         tgt = self if target is None else target
         marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                        gamma, q_taken, next_max, td_target, q_all)
+
+    def set_unroll_path(self, path):
+        marl_qnet_set_unroll_path(self.handle, path)
 
     def set_timing(self, enable):
         marl_qnet_set_timing(self.handle, enable)

@@ -12,18 +12,9 @@
 //                        the gates, applies fc2 and emits q_taken / next_max / td_target.
 #include "mfma_tile.h"
 #include "stream_layout.h"
+#include "recurrent_roles.h"
 
 namespace marl {
-
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
-// load and store of the wave, which would expose the latency of the prefetches that are meant
-// to stay in flight across slots.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
 
 // ------------------------------------------------------------------------------------------ front end
 // Decision step (ACT) and input projection of the unroll (!ACT) share one kernel.  A workgroup
@@ -34,61 +25,6 @@ __device__ __forceinline__ void lds_barrier()
 // sits in registers on its way to the other LDS buffer and chunk c+2 is in flight from L2.
 // One LDS-only barrier per chunk.
 //
-// Scratch written by the input projection and read by the recurrent kernel: one record per
-// (row tile, slot) holding, for each gate and hidden block, the 32x32 accumulator of that block in
-// lane order, so that every wave-wide access is contiguous.
-//   fp32 networks: fp32 values, [3 gates][H/32][4][64 lanes][4]   (slots 4j..4j+3 of lane l at [j][l])
-//   bf16 networks: bf16 values, [3 gates][H/32][2][64 lanes][8]   (slots 8p..8p+7 of lane l at [p][l])
-// bf16 halves the traffic of the two kernels, which are bound by it; the rounding (2^-9 relative on
-// pre-activations of order one) stays well inside that mode's tolerance.
-template <int P> struct GiLayout {
-    static constexpr bool kBf16 = P == 1;
-    static constexpr int kBlockBytes = kBf16 ? 2048 : 4096;            // one gate, one hidden block
-    static constexpr int block_vecs() { return kBlockBytes / 16; }
-};
-
-template <int P>
-__device__ __forceinline__ void store_gi_block(char *__restrict__ dst, int lane, const f32x16 &v)
-{
-    if constexpr (GiLayout<P>::kBf16) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            bf16x8 t;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) t[i] = (__bf16)v[8 * p + i];
-            *reinterpret_cast<bf16x8 *>(dst + p * 1024 + lane * 16) = t;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 t = {v[4 * j + 0], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
-            *reinterpret_cast<f32x4 *>(dst + j * 1024 + lane * 16) = t;
-        }
-    }
-}
-
-// The same block read back from an LDS copy of the record.
-template <int P>
-__device__ __forceinline__ f32x16 load_gi_block(const char *src, int lane)
-{
-    f32x16 v;
-    if constexpr (GiLayout<P>::kBf16) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const bf16x8 t = *reinterpret_cast<const bf16x8 *>(src + p * 1024 + lane * 16);
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[8 * p + i] = (float)t[i];
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const f32x4 t = *reinterpret_cast<const f32x4 *>(src + j * 1024 + lane * 16);
-            v[4 * j + 0] = t[0]; v[4 * j + 1] = t[1]; v[4 * j + 2] = t[2]; v[4 * j + 3] = t[3];
-        }
-    }
-    return v;
-}
-
 struct FrontArgs {
     NetFrags net[2];            // ACT: net[0]; projection: online, target (blockIdx.y)
     // decision step
@@ -430,7 +366,7 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
     float *__restrict__ q_all)
 {
     using Shape = RecurrentShape<H, P>;
-    constexpr int FB = H / 32, KCH = H / 16;
+    constexpr int KCH = H / 16;
     __shared__ __attribute__((aligned(16))) char gi_lds[2][Shape::kGiBytes];
     __shared__ bf16x8 h_lds[2][KCH][P][64];
     __shared__ __attribute__((aligned(16))) float b2_lds[32 * MB2];
@@ -438,161 +374,17 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
     const bool is_target = blockIdx.y == 1;
     const NetFrags &net = is_target ? target : online;
     const char *__restrict__ gi = is_target ? gi_target : gi_online;
-    const int lane = threadIdx.x & 63, g = lane >> 5, col = lane & 31;
+    const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int S = T + 1;
     const int rt = blockIdx.x;
     const char *gi_tile = gi + (size_t)rt * S * Shape::kGiBytes;
 
     if (wave < Shape::kCompute) {
-        // ---------------------------------------------------------------- compute wave
-        const int fb = wave;
-        bf16x8 w[3][KCH][P];
-#pragma unroll
-        for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-            for (int kc = 0; kc < KCH; ++kc)
-#pragma unroll
-                for (int p = 0; p < P; ++p) w[gate][kc][p] = net.whh[((size_t)((gate * FB + fb) * KCH + kc) * P + p) * 64 + lane];
-        const f32x16 bias_hn = load_feature_block(net.bias_hn, fb, g);
-        f32x16 h;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) h[r] = 0.0f;
-        {
-            const Frag<P> z0 = frag_of_half<P>(h, 0);
-#pragma unroll
-            for (int c = 0; c < 2; ++c) {
-                h_lds[0][2 * fb + c][0][lane] = z0.hi;
-                if constexpr (P == 2) h_lds[0][2 * fb + c][1][lane] = z0.lo;
-            }
-        }
-        lds_barrier();
-        for (int it = 0; it <= T + 1; ++it) {
-            if (it <= T) {
-                const int cur = it & 1;
-                f32x16 acc[3];
-#pragma unroll
-                for (int gate = 0; gate < 2; ++gate)
-                    acc[gate] = load_gi_block<P>(&gi_lds[cur][(gate * FB + fb) * GiLayout<P>::kBlockBytes], lane);
-                acc[2] = bias_hn;
-#pragma unroll
-                for (int kc = 0; kc < KCH; ++kc) {
-                    Frag<P> hb;
-                    hb.hi = h_lds[cur][kc][0][lane];
-                    if constexpr (P == 2) hb.lo = h_lds[cur][kc][1][lane];
-#pragma unroll
-                    for (int gate = 0; gate < 3; ++gate) {
-                        if constexpr (P == 2) {
-                            acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][1], hb.hi, acc[gate], 0, 0, 0);
-                            acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][0], hb.lo, acc[gate], 0, 0, 0);
-                        }
-                        acc[gate] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w[gate][kc][0], hb.hi, acc[gate], 0, 0, 0);
-                    }
-                }
-                const f32x16 ain = load_gi_block<P>(&gi_lds[cur][(2 * FB + fb) * GiLayout<P>::kBlockBytes], lane);
-                h = gru_blend(acc[0], acc[1], ain, acc[2], h);
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                    const Frag<P> f = frag_of_half<P>(h, c);
-                    h_lds[cur ^ 1][2 * fb + c][0][lane] = f.hi;
-                    if constexpr (P == 2) h_lds[cur ^ 1][2 * fb + c][1][lane] = f.lo;
-                }
-            }
-            lds_barrier();
-        }
+        compute_role<H, P>(net, wave, lane, T, 1, &gi_lds[0][0], h_lds);
     } else if (wave == Shape::kCompute) {
-        // ---------------------------------------------------------------- epilogue wave
-        const bool emit_online = !is_target, emit_target = is_target || !two_nets;
-        const int N = net.N, A = net.A;
-        const int rows = B * N;
-        const int row = rt * 32 + col;
-        const bool valid = row < rows;
-        const int b = valid ? row / N : 0, n = valid ? row % N : 0;
-        bf16x8 w2[MB2][KCH][P];
-#pragma unroll
-        for (int mb = 0; mb < MB2; ++mb)
-#pragma unroll
-            for (int kc = 0; kc < KCH; ++kc)
-#pragma unroll
-                for (int p = 0; p < P; ++p) w2[mb][kc][p] = net.w2[((size_t)(mb * KCH + kc) * P + p) * 64 + lane];
-        if (lane < 32 * MB2 / 2) {                 // the output bias lives in LDS, not in registers
-            b2_lds[2 * lane] = net.b2[2 * lane];
-            b2_lds[2 * lane + 1] = net.b2[2 * lane + 1];
-        }
-
-        // Per-slot inputs of the TD step, fetched one slot ahead so that their latency hides
-        // behind the other waves' work.
-        // 32-bit element offsets (the host bounds every array to 2^30 elements): uniform base
-        // pointer + per-lane offset + per-slot stride.
-        const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // actions / outputs: + t N
-        const uint32_t av0 = ((uint32_t)(b * S) * N + n) * A;     // avail / q_all:     + t N A
-        const uint32_t bt0 = (uint32_t)(b * T);                   // per-episode flags: + t
-        struct SlotIn { int u; uint32_t avail_raw[MB2 * 4]; float reward; uint8_t on_filled, terminated, tg_filled; };
-        auto fetch_slot = [&](int t) {
-            SlotIn in{};
-            if (t > T) return in;
-            if (emit_online && t < T) {
-                in.u = valid ? actions[btn0 + (uint32_t)t * N] : 0;
-                in.on_filled = valid ? filled[bt0 + t] : 0;
-            }
-            if (emit_target && t >= 1) {
-                if (A >= 4) issue_avail_loads<MB2>(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, in.avail_raw);
-                in.reward = valid ? reward[bt0 + t - 1] : 0.0f;
-                in.terminated = valid ? terminated[bt0 + t - 1] : 0;
-                in.tg_filled = valid ? filled[bt0 + t - 1] : 0;
-            }
-            return in;
-        };
-        SlotIn nxt = fetch_slot(0);
-        lds_barrier();
-        for (int it = 0; it <= T + 1; ++it) {
-            if (it >= 1) {
-                const int t = it - 1, cur = it & 1;          // h_t was published during iteration t
-                const SlotIn in = nxt;
-                nxt = fetch_slot(t + 1);
-                f32x16 q[MB2];
-#pragma unroll
-                for (int mb = 0; mb < MB2; ++mb) q[mb] = load_feature_block(b2_lds, mb, g);
-#pragma unroll
-                for (int kc = 0; kc < KCH; ++kc) {
-                    Frag<P> hb;
-                    hb.hi = h_lds[cur][kc][0][lane];
-                    if constexpr (P == 2) hb.lo = h_lds[cur][kc][1][lane];
-#pragma unroll
-                    for (int mb = 0; mb < MB2; ++mb) {
-                        if constexpr (P == 2) {
-                            q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][1], hb.hi, q[mb], 0, 0, 0);
-                            q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][0], hb.lo, q[mb], 0, 0, 0);
-                        }
-                        q[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(w2[mb][kc][0], hb.hi, q[mb], 0, 0, 0);
-                    }
-                }
-                if (emit_online) {
-                    if constexpr (QALL) {
-                        if (valid) store_q_row<MB2>(q_all + (av0 + (uint32_t)t * N * A), q, A, lane);
-                    }
-                    if (t < T) {
-                        const int u = min(max(in.u, 0), A - 1);
-                        const float qu = pick_action_value<MB2>(q, u, lane);
-                        if (valid && g == 0) q_taken[btn0 + (uint32_t)t * N] = in.on_filled ? qu : 0.0f;
-                    }
-                }
-                if (emit_target && t >= 1) {
-                    const uint32_t slots =
-                        A >= 4 ? avail_mask_from_raw<MB2>(in.avail_raw, A, lane, valid)
-                               : avail_mask_small(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, valid);
-                    const float best_q = masked_max_slots<MB2>(q, slots);
-                    if (valid && g == 0) {
-                        const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
-                        const float keep = in.terminated ? 0.0f : 1.0f;
-                        const float y = in.reward + gamma * keep * best_q;
-                        next_max[o] = in.tg_filled ? best_q : 0.0f;
-                        td_target[o] = in.tg_filled ? y : 0.0f;
-                    }
-                }
-            }
-            lds_barrier();
-        }
+        const TdArrays td{avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all};
+        epilogue_role<H, P, MB2, QALL>(net, td, !is_target, is_target || !two_nets, rt, lane, B, T, 1, h_lds, b2_lds);
     } else {
         // ---------------------------------------------------------------- prefetch wave
         constexpr int V = Shape::kVecPerLane;

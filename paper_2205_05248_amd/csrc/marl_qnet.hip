@@ -140,6 +140,7 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     q->dev_weight_bytes = img.bytes;
     q->scratch = nullptr;
     q->scratch_bytes = 0;
+    q->unroll_path = MARL_UNROLL_AUTO;
     q->timing = false;
     q->ev_used = 0;
     err = hipMalloc(&q->dev_weights, img.bytes);
@@ -153,6 +154,8 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.proj_stream = reinterpret_cast<const marl::bf16x8 *>(base + img.off_proj);
     n.whh = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh);
     n.w2 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2);
+    n.w1_seq = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w1_seq);
+    n.wih_seq = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih_seq);
     n.bias1 = reinterpret_cast<const float *>(base + img.off_bias1);
     n.bias_r = reinterpret_cast<const float *>(base + img.off_bias_r);
     n.bias_z = reinterpret_cast<const float *>(base + img.off_bias_z);
@@ -200,6 +203,11 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
     return MARL_OK;
 }
 
+namespace {
+// AUTO: the two-kernel path is the faster one for every shape measured so far.
+bool takes_fused_path(const marl_qnet *q) { return q->unroll_path == MARL_UNROLL_FUSED; }
+}  // namespace
+
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
 {
     if (!q) return MARL_ERR_NULL;
@@ -207,7 +215,17 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
         return MARL_ERR_BAD_DIM;
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    if (takes_fused_path(q)) return MARL_OK;
     return ensure_scratch(q, marl::unroll_scratch_bytes(q->net, B, T));
+}
+
+int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path)
+{
+    if (!q) return MARL_ERR_NULL;
+    if (path != MARL_UNROLL_AUTO && path != MARL_UNROLL_SPLIT && path != MARL_UNROLL_FUSED) return MARL_ERR_BAD_ARG;
+    if (path == MARL_UNROLL_FUSED && !marl::unroll_fused_fits(q->net)) return MARL_ERR_BAD_DIM;
+    q->unroll_path = path;
+    return MARL_OK;
 }
 
 int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const float *obs,
@@ -233,10 +251,14 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     DeviceGuard guard(a.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     const bool two = online != target;
-    const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
-    int rc = ensure_scratch(online, need);
-    if (rc == MARL_OK && two) rc = ensure_scratch(target, need);
-    if (rc != MARL_OK) return rc;
+    const bool fused = takes_fused_path(online);
+    int rc = MARL_OK;
+    if (!fused) {
+        const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
+        rc = ensure_scratch(online, need);
+        if (rc == MARL_OK && two) rc = ensure_scratch(target, need);
+        if (rc != MARL_OK) return rc;
+    }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipEvent_t *ev = nullptr;
     if (online->timing) {
@@ -245,6 +267,13 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
         if (rc != MARL_OK) return rc;
     }
     if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
+    if (fused) {
+        if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
+        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, obs, avail, actions, reward, terminated,
+                                           filled, gamma, q_taken, next_max, td_target, q_all, stream));
+        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
+        return MARL_OK;
+    }
     MARL_HIP(marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, obs, avail,
                                     actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
                                     stream, ev ? ev[1] : nullptr));

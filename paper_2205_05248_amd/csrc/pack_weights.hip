@@ -79,6 +79,8 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     out->off_proj = off;    off = align256(off + (size_t)proj_chunks * chunk_bytes);
     out->off_whh = off;     off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
     out->off_w2 = off;      off = align256(off + (size_t)mb2 * KCH * frag_bytes);
+    out->off_w1_seq = off;  off = align256(off + (size_t)FB * kc1 * frag_bytes);
+    out->off_wih_seq = off; off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
     out->off_bias1 = off;   off = align256(off + sizeof(float) * (size_t)N * H);
     out->off_bias_r = off;  off = align256(off + sizeof(float) * H);
     out->off_bias_z = off;  off = align256(off + sizeof(float) * H);
@@ -134,6 +136,25 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
                         const int kc = cf * sd.kpf + kk;
                         if (kc < KCH) put(kk * mb2 + mb, frag_w2(mb, kc));
                     }
+    }
+
+    // Fused unroll: each projection wavefront reads its fragments straight from global memory, so
+    // they are stored in that wavefront's order of use.
+    //   fc1:        [k-step][feature block]
+    //   GRU input:  [pass][k-step][block of the pass], pass = three consecutive (gate, hidden block) blocks
+    {
+        uint16_t *w1s = reinterpret_cast<uint16_t *>(img + out->off_w1_seq);
+        for (int kc = 0; kc < kc1; ++kc)
+            for (int mb = 0; mb < FB; ++mb)
+                std::memcpy(w1s + ((size_t)kc * FB + mb) * frag_elems, frag_w1(mb, kc), frag_elems * 2);
+        uint16_t *wis = reinterpret_cast<uint16_t *>(img + out->off_wih_seq);
+        for (int pass = 0; pass < FB; ++pass)
+            for (int kc = 0; kc < KCH; ++kc)
+                for (int b = 0; b < 3; ++b) {
+                    const int blk = 3 * pass + b;                       // = gate * FB + fb
+                    std::memcpy(wis + (((size_t)pass * KCH + kc) * 3 + b) * frag_elems,
+                                wihf.data() + ((size_t)blk * KCH + kc) * frag_elems, frag_elems * 2);
+                }
     }
 
     // The agent-id column of W1 is a per-agent bias.  A bf16 network uses the rounded weight.

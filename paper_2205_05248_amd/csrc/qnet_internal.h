@@ -30,6 +30,8 @@ struct NetFrags {
     const bf16x8 *proj_stream;  // input projection: fc1, GRU input matrices in order of use
     const bf16x8 *whh;    // [3][H/32][H/16][P][64]   gates r, z, n
     const bf16x8 *w2;     // [mb2][H/16][P][64]
+    const bf16x8 *w1_seq;   // fused unroll, fc1:       [kc1][H/32][P][64]
+    const bf16x8 *wih_seq;  // fused unroll, GRU input: [H/32 passes][H/16][3][P][64]
     const float *bias1;   // [N][H]   b1 + W1[:, D + n]
     const float *bias_r;  // [H]      b_ir + b_hr
     const float *bias_z;  // [H]      b_iz + b_hz
@@ -54,6 +56,7 @@ struct marl_qnet {
     marl::NetFrags net;
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
+    int unroll_path;                   // MARL_UNROLL_AUTO / MARL_UNROLL_SPLIT
     bool timing;                       // record events around the kernels of each call
     std::vector<hipEvent_t> ev_pool;   // events created so far (reused after a read)
     size_t ev_used;                    // events handed out since the last read
@@ -67,7 +70,7 @@ namespace marl {
 struct PackedImage {
     void *host;        // malloc'ed image, caller frees
     size_t bytes;
-    size_t off_act, off_proj, off_whh, off_w2, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    size_t off_act, off_proj, off_whh, off_w2, off_w1_seq, off_wih_seq, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
     int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
@@ -84,5 +87,13 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
                             float *q_all, hipStream_t stream, hipEvent_t between);
+
+// Fused unroll (unroll_fused.hip): no scratch buffer.  `fits` tells whether the network's shape
+// fits the kernel's LDS and register budgets; otherwise the two-kernel path above is used.
+bool unroll_fused_fits(const NetFrags &net);
+hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
+                               const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
+                               const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
+                               float *next_max, float *td_target, float *q_all, hipStream_t stream);
 
 }  // namespace marl

@@ -152,12 +152,19 @@ def test_act_step_is_deterministic_and_isolated():
 
 
 # ------------------------------------------------------------------ unroll + TD
+# Both implementations of the unroll are held to the same bar.
+PATHS = [binding.UNROLL_SPLIT, binding.UNROLL_FUSED]
+PATH_IDS = ["split", "fused"]
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("ci", [0, 1, 2, 3])
-def test_unroll_td_full_config(ci):
+def test_unroll_td_full_config(ci, path):
     cfg = wl.config(ci)
     tol = pu.TOL[cfg["dtype"]]
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
+    online.set_unroll_path(path)
     u = wl.make_unroll_inputs(cfg)
     got = pu.gpu_unroll(online, target, cfg, u)
     ref = oracle_unroll(cfg, w_on, w_tg, u)
@@ -172,11 +179,13 @@ def test_unroll_td_full_config(ci):
     online.close(); target.close()
 
 
-def test_unroll_td_full_config_4_sampled_rows():
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_unroll_td_full_config_4_sampled_rows(path):
     cfg = wl.config(4)
     tol = pu.TOL[cfg["dtype"]]
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
+    online.set_unroll_path(path)
     u = wl.make_unroll_inputs(cfg)
     got = pu.gpu_unroll(online, target, cfg, u)
     rows_total = cfg["B"] * cfg["N"]
@@ -199,11 +208,13 @@ def test_unroll_td_full_config_4_sampled_rows():
     online.close(); target.close()
 
 
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("ci,B,T", [(0, 1, 1), (0, 3, 7), (1, 5, 9), (2, 7, 3), (3, 33, 5), (4, 2, 6)])
-def test_unroll_td_ragged_sizes(ci, B, T):
+def test_unroll_td_ragged_sizes(ci, B, T, path):
     cfg = wl.config(ci)
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
+    online.set_unroll_path(path)
     u = wl.make_unroll_inputs(cfg, B=B, T=T)
     got = pu.gpu_unroll(online, target, cfg, u)
     ref = oracle_unroll(cfg, w_on, w_tg, u)
