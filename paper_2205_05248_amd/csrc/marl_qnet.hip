@@ -154,8 +154,10 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.proj_stream = reinterpret_cast<const marl::bf16x8 *>(base + img.off_proj);
     n.whh = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh);
     n.w2 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2);
-    n.w1_seq = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w1_seq);
-    n.wih_seq = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih_seq);
+    n.w1_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w1_16);
+    n.wih_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih_16);
+    n.whh_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh_16);
+    n.w2_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2_16);
     n.bias1 = reinterpret_cast<const float *>(base + img.off_bias1);
     n.bias_r = reinterpret_cast<const float *>(base + img.off_bias_r);
     n.bias_z = reinterpret_cast<const float *>(base + img.off_bias_z);

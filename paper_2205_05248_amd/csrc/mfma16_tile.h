@@ -1,0 +1,131 @@
+// Wave-level building blocks for tiles of 16 (episode, agent) rows with 16x16x32 bf16 MFMAs.
+// As with the 32-row tiles the weights are the A operand (16 output features x 32 k) and the
+// activations the B operand (32 k x 16 rows).  Lane l (q = l / 16, c = l % 16):
+//   A  : feature c,  k = 8 q + 0..7
+//   B  : row c,      k = 8 q + 0..7
+//   C  : row c,      features 4 q + 0..3      (four fp32 values)
+// The accumulators of two adjacent feature blocks hold, per lane, exactly the eight values of
+// one k-step of the next layer's B operand; the weight fragments of such layers are stored in
+// the matching k order (pack_weights.hip), so results never leave registers between layers.
+#pragma once
+#include "mfma_tile.h"
+
+namespace marl {
+
+template <int P>
+__device__ __forceinline__ void mma16(f32x4 &acc, const WFrag<P> &w, const Frag<P> &b)
+{
+    if constexpr (P == 2) {
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.lo, b.hi, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.hi, b.lo, acc, 0, 0, 0);
+    }
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.hi, b.hi, acc, 0, 0, 0);
+}
+
+// Feature blocks 2 j and 2 j + 1 of a result -> k-step j of the next operand.
+template <int P>
+__device__ __forceinline__ Frag<P> frag_of_pair(const f32x4 &even, const f32x4 &odd)
+{
+    const float v[8] = {even[0], even[1], even[2], even[3], odd[0], odd[1], odd[2], odd[3]};
+    return to_frag<P>(v);
+}
+
+// The four per-feature table entries this lane's accumulator slots of block blk refer to.
+__device__ __forceinline__ f32x4 load_feature4(const float *table, int blk, int q)
+{
+    return *reinterpret_cast<const f32x4 *>(table + 16 * blk + 4 * q);
+}
+
+// h' = (1 - z) n + z h on the four slots of one block.
+__device__ __forceinline__ f32x4 gru_blend4(const f32x4 &ar, const f32x4 &az, const f32x4 &ain, const f32x4 &ahn, const f32x4 &h)
+{
+    f32x4 out;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const float rr = sigmoidf_fast(ar[r]), zz = sigmoidf_fast(az[r]);
+        const float nn = tanhf_fast(ain[r] + rr * ahn[r]);
+        out[r] = fmaf(zz, h[r] - nn, nn);
+    }
+    return out;
+}
+
+// ---- action-side helpers: a row's Q values sit in the four lanes c, c + 16, c + 32, c + 48;
+// lane q holds actions 16 ab + 4 q + 0..3 of action block ab.
+
+// One (possibly unaligned) 32-bit load per action block fetches the availability bytes of the
+// lane's four actions; the address is clamped into the row (A >= 4), every load unconditional.
+template <int AB>
+__device__ __forceinline__ void issue_avail_loads16(const uint8_t *__restrict__ avail_row, int A, int q, uint32_t (&raw)[AB])
+{
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab) __builtin_memcpy(&raw[ab], avail_row + min(16 * ab + 4 * q, A - 4), 4);
+}
+
+// Bit 4 ab + r is set when action 16 ab + 4 q + r exists and is available.
+template <int AB>
+__device__ __forceinline__ uint32_t avail_mask16(const uint32_t (&raw)[AB], int A, int q, bool valid)
+{
+    uint32_t mask = 0;
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab) {
+        const int a0 = 16 * ab + 4 * q;
+        const int skip = a0 - min(a0, A - 4);                  // bytes of the word that precede a0
+        const uint32_t w = skip < 4 ? raw[ab] >> (8 * skip) : 0u;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mask |= ((w >> (8 * i)) & 0xFFu) ? (1u << (4 * ab + i)) : 0u;
+    }
+    return valid ? mask : 0u;
+}
+
+// Rows with fewer than four actions: all of them belong to lane quarter 0, block 0.
+__device__ __forceinline__ uint32_t avail_mask_small16(const uint8_t *__restrict__ avail_row, int A, int q, bool valid)
+{
+    uint32_t mask = 0;
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const uint32_t v = avail_row[min(i, A - 1)];
+        mask |= (i < A && v) ? (1u << i) : 0u;
+    }
+    return (valid && q == 0) ? mask : 0u;
+}
+
+// Maximum of the row's available Q values (0 when nothing is available).
+template <int AB>
+__device__ __forceinline__ float masked_max16(const f32x4 (&qv)[AB], uint32_t slots)
+{
+    float m = -__builtin_inff();
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) m = fmaxf(m, ((slots >> (4 * ab + r)) & 1u) ? qv[ab][r] : -__builtin_inff());
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+    return m == -__builtin_inff() ? 0.0f : m;
+}
+
+// Q value of action u of this lane's row (one of the four lanes has it; they are summed).
+template <int AB>
+__device__ __forceinline__ float pick_action_value16(const f32x4 (&qv)[AB], int u, int q)
+{
+    float v = 0.0f;
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v = (16 * ab + 4 * q + r == u) ? qv[ab][r] : v;
+    v += __shfl_xor(v, 16);
+    return v + __shfl_xor(v, 32);
+}
+
+template <int AB>
+__device__ __forceinline__ void store_q_row16(float *__restrict__ q_row, const f32x4 (&qv)[AB], int A, int q)
+{
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int a = 16 * ab + 4 * q + r;
+            if (a < A) q_row[a] = qv[ab][r];
+        }
+}
+
+}  // namespace marl

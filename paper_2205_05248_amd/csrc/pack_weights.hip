@@ -59,6 +59,36 @@ void pack_frags(uint16_t *out, const float *W, int M, int K, int ld, bool use_pe
                 }
 }
 
+// 16x16x32 MFMA operand fragments (fused unroll): W is cut into fragments of 16 rows x 32 k.
+// Fragment (mb, ks), lane l (q = l / 16, m = l % 16), idx = 0..7 holds W[16 mb + m][perm(32 ks + 8 q + idx)].
+// perm is the identity for the first layer; for layers fed by an MFMA result it is
+//   perm16(32 ks + 8 q + idx) = 32 ks + 16 (idx / 4) + 4 q + idx % 4,
+// where the 16x16 accumulators of two adjacent feature blocks leave their values.
+int perm16(int p)
+{
+    const int ks = p / 32, q = (p / 8) % 4, idx = p % 8;
+    return 32 * ks + 16 * (idx / 4) + 4 * q + idx % 4;
+}
+
+// Output: [ceil(M/16)][ceil(K/32)][planes][64][8] bf16.
+void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_perm, int planes)
+{
+    const int MB = (M + 15) / 16, KS = (K + 31) / 32;
+    for (int mb = 0; mb < MB; ++mb)
+        for (int ks = 0; ks < KS; ++ks)
+            for (int lane = 0; lane < 64; ++lane)
+                for (int idx = 0; idx < 8; ++idx) {
+                    const int m = 16 * mb + lane % 16;
+                    const int p = 32 * ks + 8 * (lane / 16) + idx;
+                    const int k = use_perm ? perm16(p) : p;
+                    const float w = (m < M && k < K) ? W[(size_t)m * ld + k] : 0.0f;
+                    const uint16_t hi = bf16_bits(w);
+                    uint16_t *frag = out + ((size_t)(mb * KS + ks) * planes) * 512;
+                    frag[lane * 8 + idx] = hi;
+                    if (planes == 2) frag[512 + lane * 8 + idx] = bf16_bits(w - bf16_value(hi));
+                }
+}
+
 }  // namespace
 
 bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
@@ -79,8 +109,11 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     out->off_proj = off;    off = align256(off + (size_t)proj_chunks * chunk_bytes);
     out->off_whh = off;     off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
     out->off_w2 = off;      off = align256(off + (size_t)mb2 * KCH * frag_bytes);
-    out->off_w1_seq = off;  off = align256(off + (size_t)FB * kc1 * frag_bytes);
-    out->off_wih_seq = off; off = align256(off + (size_t)3 * FB * KCH * frag_bytes);
+    const int ks1 = (D + 31) / 32, ab = (A + 15) / 16, FBK = H / 16, KS = H / 32;
+    out->off_w1_16 = off;   off = align256(off + (size_t)FBK * ks1 * frag_bytes);
+    out->off_wih_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
+    out->off_whh_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
+    out->off_w2_16 = off;   off = align256(off + (size_t)ab * KS * frag_bytes);
     out->off_bias1 = off;   off = align256(off + sizeof(float) * (size_t)N * H);
     out->off_bias_r = off;  off = align256(off + sizeof(float) * H);
     out->off_bias_z = off;  off = align256(off + sizeof(float) * H);
@@ -138,23 +171,17 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
                     }
     }
 
-    // Fused unroll: each projection wavefront reads its fragments straight from global memory, so
-    // they are stored in that wavefront's order of use.
-    //   fc1:        [k-step][feature block]
-    //   GRU input:  [pass][k-step][block of the pass], pass = three consecutive (gate, hidden block) blocks
+    // Fused unroll: 16-row tiles, 16x16x32 fragments.
     {
-        uint16_t *w1s = reinterpret_cast<uint16_t *>(img + out->off_w1_seq);
-        for (int kc = 0; kc < kc1; ++kc)
-            for (int mb = 0; mb < FB; ++mb)
-                std::memcpy(w1s + ((size_t)kc * FB + mb) * frag_elems, frag_w1(mb, kc), frag_elems * 2);
-        uint16_t *wis = reinterpret_cast<uint16_t *>(img + out->off_wih_seq);
-        for (int pass = 0; pass < FB; ++pass)
-            for (int kc = 0; kc < KCH; ++kc)
-                for (int b = 0; b < 3; ++b) {
-                    const int blk = 3 * pass + b;                       // = gate * FB + fb
-                    std::memcpy(wis + (((size_t)pass * KCH + kc) * 3 + b) * frag_elems,
-                                wihf.data() + ((size_t)blk * KCH + kc) * frag_elems, frag_elems * 2);
-                }
+        pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_w1_16), W1, H, D, Din, false, planes);
+        const size_t per_gate16 = (size_t)FBK * KS * frag_elems;
+        for (int gate = 0; gate < 3; ++gate) {
+            pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_wih_16) + gate * per_gate16,
+                         Wih + (size_t)gate * H * H, H, H, H, true, planes);
+            pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_whh_16) + gate * per_gate16,
+                         Whh + (size_t)gate * H * H, H, H, H, true, planes);
+        }
+        pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_w2_16), W2, A, H, H, true, planes);
     }
 
     // The agent-id column of W1 is a per-agent bias.  A bf16 network uses the rounded weight.

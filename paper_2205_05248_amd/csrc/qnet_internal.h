@@ -30,8 +30,11 @@ struct NetFrags {
     const bf16x8 *proj_stream;  // input projection: fc1, GRU input matrices in order of use
     const bf16x8 *whh;    // [3][H/32][H/16][P][64]   gates r, z, n
     const bf16x8 *w2;     // [mb2][H/16][P][64]
-    const bf16x8 *w1_seq;   // fused unroll, fc1:       [kc1][H/32][P][64]
-    const bf16x8 *wih_seq;  // fused unroll, GRU input: [H/32 passes][H/16][3][P][64]
+    // fused unroll: fragments of 16 rows x 32 k for the 16x16x32 MFMA (layout in pack_weights.hip)
+    const bf16x8 *w1_16;    // [H/16][ceil(D/32)][P][64]
+    const bf16x8 *wih_16;   // [3][H/16][H/32][P][64]
+    const bf16x8 *whh_16;   // [3][H/16][H/32][P][64]
+    const bf16x8 *w2_16;    // [ceil(A/16)][H/32][P][64]
     const float *bias1;   // [N][H]   b1 + W1[:, D + n]
     const float *bias_r;  // [H]      b_ir + b_hr
     const float *bias_z;  // [H]      b_iz + b_hz
@@ -70,7 +73,7 @@ namespace marl {
 struct PackedImage {
     void *host;        // malloc'ed image, caller frees
     size_t bytes;
-    size_t off_act, off_proj, off_whh, off_w2, off_w1_seq, off_wih_seq, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
     int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
