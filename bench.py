@@ -42,8 +42,11 @@ def unroll_bytes_per_agent_step(N, D, A, H):
     return 4 * D + A + 16
 
 
+UNROLL_PATHS = {"auto": 0, "split": 1, "fused": 2}
+
+
 class Bench:
-    def __init__(self, ci, two_nets=True):
+    def __init__(self, ci, two_nets=True, unroll_path="auto"):
         import torch
         from paper_2205_05248_amd import binding, workloads as wl
         self.torch, self.wl = torch, wl
@@ -53,6 +56,8 @@ class Bench:
         self.w_on, self.w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
         self.online = binding.QNet(dims, self.w_on, cfg["dtype"])
         self.target = binding.QNet(dims, self.w_tg, cfg["dtype"]) if two_nets else None
+        self.online.set_unroll_path(UNROLL_PATHS[unroll_path])
+        self.fused = self.online.unroll_path_in_use() == binding.UNROLL_FUSED
         dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         E, B, T = cfg["E"], cfg["B"], cfg["T"]
         set_bytes = E * N * act_bytes_per_agent_step(*dims)
@@ -165,6 +170,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload index 0..4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-net", action="store_true", help="target == online in the unroll")
+    ap.add_argument("--unroll-path", choices=sorted(UNROLL_PATHS), default="auto",
+                    help="implementation of the unroll (auto: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: every (env, agent) row is independent, so more GPUs "
@@ -175,7 +182,7 @@ def main():
         build.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    b = Bench(args.config, two_nets=not args.single_net)
+    b = Bench(args.config, two_nets=not args.single_net, unroll_path=args.unroll_path)
     cfg, dims = b.cfg, b.dims
     N, D, A, H = dims
     E, B, T = cfg["E"], cfg["B"], cfg["T"]
@@ -196,13 +203,22 @@ def main():
         "act_step": {
             "ms": act_ms, "calls": k["act_calls"], "bound": "hbm",
             "bytes": steps_act * act_bytes_per_agent_step(*dims), "flops": steps_act * flops_per_agent_step(*dims)},
-        "input_proj": {
-            "ms": proj_ms, "calls": k["unroll_calls"], "bound": "mfma",
-            "bytes": slots * 4 * D, "flops": nets * slots * (2 * D * H + 2 * 3 * H * H)},
-        "recurrent_td": {
-            "ms": rec_ms, "calls": k["unroll_calls"], "bound": "mfma",
-            "bytes": slots * A + B * T * N * 16, "flops": nets * slots * (2 * 3 * H * H + 2 * H * A)},
     }
+    unroll_io_bytes = slots * (4 * D + A) + B * T * N * 16        # obs + avail once; action in, three outputs
+    if b.fused:
+        # one kernel does the whole unroll; nothing but its inputs and outputs touches HBM
+        proj_ms = 0.0
+        kernels["unroll_fused"] = {
+            "ms": rec_ms, "calls": k["unroll_calls"], "bound": "mfma",
+            "bytes": unroll_io_bytes, "flops": nets * slots * flops_per_agent_step(*dims)}
+    else:
+        gi_bytes = nets * slots * 3 * H * (2 if bf16 else 4)     # written by the projection, read by the recurrence
+        kernels["input_proj"] = {
+            "ms": proj_ms, "calls": k["unroll_calls"], "bound": "hbm",
+            "bytes": slots * 4 * D + gi_bytes, "flops": nets * slots * (2 * D * H + 2 * 3 * H * H)}
+        kernels["recurrent_td"] = {
+            "ms": rec_ms, "calls": k["unroll_calls"], "bound": "mfma",
+            "bytes": gi_bytes + slots * A + B * T * N * 16, "flops": nets * slots * (2 * 3 * H * H + 2 * H * A)}
     for v in kernels.values():
         sec = max(v["ms"], 1e-9) * 1e-3
         v["GBs"] = v["bytes"] / sec / 1e9
@@ -229,6 +245,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["name"], "E": E, "N": N, "obs_dim": D, "n_actions": A, "hidden": H,
                    "B": B, "T": T, "target_network": "distinct" if nets == 2 else "same",
+                   "unroll_path": "fused" if b.fused else "split",
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
         "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
                      "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": kernels["act_step"]["GBs"],
@@ -236,9 +253,9 @@ def main():
                      "input_pool_bytes": b.pool * kernels["act_step"]["bytes"]},
         "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),
                       "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "kernels_ms": unroll_ms,
-                      "input_proj_ms": proj_ms, "recurrent_ms": rec_ms,
-                      "mfma_frac_input_proj": kernels["input_proj"]["mfma_frac"],
-                      "mfma_frac_recurrent": kernels["recurrent_td"]["mfma_frac"]},
+                      "kernels": {n: {"ms": v["ms"], "TFLOPs": v["TFLOPs"], "mfma_frac": v["mfma_frac"],
+                                      "GBs": v["GBs"], "hbm_frac": v["hbm_frac"]}
+                                  for n, v in kernels.items() if n != "act_step"}},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:

@@ -147,7 +147,7 @@ int marl_act_step(marl_qnet *q, int32_t E,
  * the GRU gates for every slot to a scratch buffer and then runs the
  * recurrence; the fused path keeps every intermediate on chip and needs no
  * scratch, but only serves networks whose shape fits its on-chip buffers
- * (obs_dim <= 384 and, for fp32 weights, hidden = 64 with obs_dim <= 272).
+ * (bf16 weights: obs_dim <= 320; fp32 weights: hidden = 64 and obs_dim <= 160).
  *
  * Scratch (two-kernel path only): the library keeps one device buffer per
  * handle for intermediate activations, grown (never shrunk) when a call needs
@@ -166,7 +166,7 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*
  * Choice of the unroll implementation for calls whose `online` handle is q.
- *   MARL_UNROLL_AUTO   the faster one for the network's shape (the default)
+ *   MARL_UNROLL_AUTO   the fused kernel when the network fits it, else the two-kernel path (the default)
  *   MARL_UNROLL_SPLIT  always the two-kernel path
  *   MARL_UNROLL_FUSED  always the fused kernel; MARL_ERR_BAD_DIM if the network does not fit it
  * Returns MARL_ERR_BAD_ARG for any other value.
@@ -175,6 +175,10 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 #define MARL_UNROLL_SPLIT 1
 #define MARL_UNROLL_FUSED 2
 int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path);
+
+/* The implementation marl_unroll_td uses for this handle as things stand: MARL_UNROLL_SPLIT or
+ * MARL_UNROLL_FUSED (never AUTO); MARL_ERR_NULL (negative) for a null handle. */
+int marl_qnet_unroll_path_in_use(const marl_qnet *q);
 
 /*
  * Kernel timing for benchmarks.  While timing is enabled on a handle, marl_act_step and

@@ -21,7 +21,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
-           "marl_qnet_set_unroll_path"]
+           "marl_qnet_set_unroll_path", "marl_qnet_unroll_path_in_use"]
 
 
 class MarlError(RuntimeError):
@@ -63,6 +63,8 @@ def load():
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
+        lib.marl_qnet_unroll_path_in_use.restype = ctypes.c_int
+        lib.marl_qnet_unroll_path_in_use.argtypes = [vp]
         lib.marl_qnet_set_unroll_path.restype = ctypes.c_int
         lib.marl_qnet_set_unroll_path.argtypes = [vp, i32]
         lib.marl_qnet_set_timing.restype = ctypes.c_int
@@ -163,6 +165,13 @@ def marl_qnet_set_unroll_path(handle, path):
     check(load().marl_qnet_set_unroll_path(ctypes.c_void_p(handle), int(path)))
 
 
+def marl_qnet_unroll_path_in_use(handle):
+    rc = load().marl_qnet_unroll_path_in_use(ctypes.c_void_p(handle))
+    if rc < 0:
+        check(rc)
+    return rc
+
+
 def marl_qnet_set_timing(handle, enable):
     check(load().marl_qnet_set_timing(ctypes.c_void_p(handle), int(bool(enable))))
 
@@ -197,6 +206,9 @@ class QNet:
 
     def set_unroll_path(self, path):
         marl_qnet_set_unroll_path(self.handle, path)
+
+    def unroll_path_in_use(self):
+        return marl_qnet_unroll_path_in_use(self.handle)
 
     def set_timing(self, enable):
         marl_qnet_set_timing(self.handle, enable)

@@ -206,8 +206,11 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
 }
 
 namespace {
-// AUTO: the two-kernel path is the faster one for every shape measured so far.
-bool takes_fused_path(const marl_qnet *q) { return q->unroll_path == MARL_UNROLL_FUSED; }
+// AUTO: the fused kernel wherever the network fits it (it was the faster one on every shape measured).
+bool takes_fused_path(const marl_qnet *q)
+{
+    return q->unroll_path == MARL_UNROLL_FUSED || (q->unroll_path == MARL_UNROLL_AUTO && marl::unroll_fused_fits(q->net));
+}
 }  // namespace
 
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
@@ -219,6 +222,12 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     if (takes_fused_path(q)) return MARL_OK;
     return ensure_scratch(q, marl::unroll_scratch_bytes(q->net, B, T));
+}
+
+int marl_qnet_unroll_path_in_use(const marl_qnet *q)
+{
+    if (!q) return MARL_ERR_NULL;
+    return takes_fused_path(q) ? MARL_UNROLL_FUSED : MARL_UNROLL_SPLIT;
 }
 
 int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path)
