@@ -44,15 +44,18 @@ template <int H, int P> struct Fused16 {
     static constexpr int KS = H / 32;                  // k-steps over the hidden layer
     static constexpr int NC = H / 32;                  // compute waves
     static constexpr int NF = H == 128 ? 2 : 1;        // fc1 waves
-    static constexpr int kEpilogue = NC, kGates = NC + 1, kFc1 = NC + 2, kWaves = NC + 2 + NF;
+    static constexpr int NG = H == 128 ? 1 : 2;        // gates waves (the first one also moves the observations)
+    static constexpr int kEpilogue = NC, kGates = NC + 1, kFc1 = NC + 1 + NG, kWaves = NC + 1 + NG + NF;
     static constexpr int NBF = FBK / NF;               // fc1 feature blocks per fc1 wave
     static constexpr int kKs1Max = 40 / (NBF * P);     // observation k-steps whose W1 fragments fit 160 registers
     static constexpr int kFrag = P * 1024;             // bytes of one fragment (all planes)
     static constexpr int kGiBlock = P == 1 ? 512 : 1024;   // one 16x16 gate-input block: bf16 / fp32 accumulator form
     static constexpr int kGiBytes = 3 * FBK * kGiBlock;
-    // gate blocks [0, kEpiBlocks) are computed by the epilogue wave, the rest by the gates wave:
-    // the split evens out the matrix and vector work of the four SIMDs
+    // Gate blocks [0, kEpiBlocks) are computed by the epilogue wave, [kEpiBlocks, kGate1Blocks) by
+    // the first gates wave and the rest by the second one, if there is one: the split evens out
+    // the work of the wavefronts.
     static constexpr int kEpiBlocks = H == 128 ? 4 : 0;
+    static constexpr int kGate1Blocks = H == 128 ? 3 * FBK : 4;
     // LDS layout (byte offsets)
     static constexpr int oWih = 0;                                  // [3 FBK][KS][P][64] bf16x8
     static constexpr int oGi = oWih + 3 * FBK * KS * kFrag;         // [2][3 FBK][kGiBlock]
@@ -64,7 +67,7 @@ template <int H, int P> struct Fused16 {
     static constexpr size_t lds_bytes(int ks1) { return (size_t)oObs + (size_t)2 * ks1 * kFrag; }
 };
 
-constexpr int fused_threads(int H) { return 64 * (H / 32 + 2 + (H == 128 ? 2 : 1)); }
+constexpr int fused_threads(int H) { return 64 * (H / 32 + 1 + (H == 128 ? 1 : 2) + (H == 128 ? 2 : 1)); }
 
 // gate-input block <-> LDS
 template <int P>
@@ -380,7 +383,14 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
                 for (int i = 0; i < 8; ++i) last[i] = r[last_off[i]];
             }
-            if (gs >= 0 && gs <= T) gate_inputs<H, P, Sh::kEpiBlocks, 3 * FBK>(lds, gs, lane, q4);      // W_ih x + b of slot gs
+            if (gs >= 0 && gs <= T) gate_inputs<H, P, Sh::kEpiBlocks, Sh::kGate1Blocks>(lds, gs, lane, q4);      // W_ih x + b of slot gs
+            lds_barrier();
+        }
+    } else if (wave < Sh::kFc1) {
+        // ---------------------------------------------------------------- second gates wave
+        for (int s = -LEAD; s <= T + 1; ++s) {
+            const int gs = s + 1;
+            if (gs >= 0 && gs <= T) gate_inputs<H, P, Sh::kGate1Blocks, 3 * FBK>(lds, gs, lane, q4);
             lds_barrier();
         }
     } else {
