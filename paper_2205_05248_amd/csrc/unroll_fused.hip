@@ -4,28 +4,29 @@
 // observation rows and the TD inputs, and writes the TD outputs.
 //
 // Where the weights live (H = 128, bf16: 278 KB in total):
-//   W_hh   registers of the compute waves (each owns 32 hidden units: 3 gates x 2 blocks x H/32 k-steps)
+//   W_hh   registers of the compute waves (each owns H/64 feature blocks of 16 hidden units, all three gates)
+//   W_ih   LDS, copied once at kernel start; each compute wave reads the fragments of its own
+//          blocks from there every slot (A operands come from LDS at 16 bytes per lane)
 //   W1     registers of the fc1 waves (each owns H/16/NF feature blocks x ceil(D/32) k-steps)
-//   W_ih   LDS, copied once at kernel start (A operands are read from LDS at 16 bytes per lane)
 //   W2     registers of the epilogue wave
 //
 // The work of a slot is cut into pipeline stages that run concurrently on different wavefronts,
 // each on a different slot, and meet at ONE LDS-only barrier per slot.  In the step in which the
 // recurrence handles slot s:
 //
-//   gates wave     first writes the observations of slot s+3 (loaded during the previous step) to
-//                  LDS as bf16 operand fragments and issues the loads of slot s+4, then computes
-//                  W_ih x + b for slot s+1 (x from LDS) and leaves the result in LDS in the
-//                  accumulator form the recurrence reads;
-//   fc1 waves      x = ReLU(W1 o + b1[agent]) for slot s+2, observation fragments from LDS, x to
-//                  LDS as the next operand;
-//   compute waves  slot s of the recurrence: W_hh h, gates, new hidden state to LDS as operand;
+//   loader wave    writes the observations of slot s+2 (loaded during the previous step) to LDS
+//                  as bf16 operand fragments and issues the loads of slot s+3;
+//   fc1 waves      x = ReLU(W1 o + b1[agent]) for slot s+1, observation fragments from LDS, x to
+//                  LDS as the next operand; the first one also touches the observations of a
+//                  later slot so that the loader's loads hit L2;
+//   compute waves  slot s of the GRU: W_ih x + W_hh h + b for their hidden units, gates, new hidden
+//                  state to LDS as operand;
 //   epilogue wave  fc2 / TD step of slot s-1.
 //
-// Only the recurrence is a dependent chain; the other stages are throughput work that hides
-// under it.  Tiles of 16 rows (16x16x32 MFMAs) rather than 32 give twice as many workgroups, so
-// that episode batches of a few thousand rows still occupy every compute unit, and halve the
-// length of the chain per slot.
+// Only the GRU is a dependent chain; the other stages are throughput work that hides under it.
+// Tiles of 16 rows (16x16x32 MFMAs) rather than 32 give twice as many workgroups, so that
+// episode batches of a few thousand rows still occupy every compute unit, and halve the length
+// of the chain per slot.
 //
 // Every LDS buffer is double-buffered on the parity of the slot it holds; a buffer written in
 // step s was last read in step s-1 and is first read in step s+1.
@@ -36,30 +37,22 @@
 
 namespace marl {
 
-constexpr int kFusedLead = 4;         // steps before slot 0 enters the recurrence
+constexpr int kFusedLead = 3;         // steps before slot 0 enters the recurrence
 constexpr int kLdsLimit = 160 * 1024;
 
 template <int H, int P> struct Fused16 {
     static constexpr int FBK = H / 16;                 // feature blocks of the hidden layer
     static constexpr int KS = H / 32;                  // k-steps over the hidden layer
-    static constexpr int NC = H / 32;                  // compute waves
+    static constexpr int NC = 4;                       // compute waves
+    static constexpr int NBC = FBK / NC;               // feature blocks per compute wave (2 or 1)
     static constexpr int NF = H == 128 ? 2 : 1;        // fc1 waves
-    static constexpr int NG = H == 128 ? 1 : 2;        // gates waves (the first one also moves the observations)
-    static constexpr int kEpilogue = NC, kGates = NC + 1, kFc1 = NC + 1 + NG, kWaves = NC + 1 + NG + NF;
+    static constexpr int kEpilogue = NC, kLoader = NC + 1, kFc1 = NC + 2, kWaves = NC + 2 + NF;
     static constexpr int NBF = FBK / NF;               // fc1 feature blocks per fc1 wave
     static constexpr int kKs1Max = 40 / (NBF * P);     // observation k-steps whose W1 fragments fit 160 registers
     static constexpr int kFrag = P * 1024;             // bytes of one fragment (all planes)
-    static constexpr int kGiBlock = P == 1 ? 512 : 1024;   // one 16x16 gate-input block: bf16 / fp32 accumulator form
-    static constexpr int kGiBytes = 3 * FBK * kGiBlock;
-    // Gate blocks [0, kEpiBlocks) are computed by the epilogue wave, [kEpiBlocks, kGate1Blocks) by
-    // the first gates wave and the rest by the second one, if there is one: the split evens out
-    // the work of the wavefronts.
-    static constexpr int kEpiBlocks = H == 128 ? 4 : 0;
-    static constexpr int kGate1Blocks = H == 128 ? 3 * FBK : 4;
     // LDS layout (byte offsets)
     static constexpr int oWih = 0;                                  // [3 FBK][KS][P][64] bf16x8
-    static constexpr int oGi = oWih + 3 * FBK * KS * kFrag;         // [2][3 FBK][kGiBlock]
-    static constexpr int oH = oGi + 2 * kGiBytes;                   // [2][KS][P][64] bf16x8
+    static constexpr int oH = oWih + 3 * FBK * KS * kFrag;          // [2][KS][P][64] bf16x8
     static constexpr int oX = oH + 2 * KS * kFrag;                  // [2][KS][P][64] bf16x8
     static constexpr int oGBias = oX + 2 * KS * kFrag;              // [3 H] floats: b_ir + b_hr, b_iz + b_hz, b_in
     static constexpr int oB2 = oGBias + 3 * H * 4;                  // [64] floats
@@ -67,96 +60,7 @@ template <int H, int P> struct Fused16 {
     static constexpr size_t lds_bytes(int ks1) { return (size_t)oObs + (size_t)2 * ks1 * kFrag; }
 };
 
-constexpr int fused_threads(int H) { return 64 * (H / 32 + 1 + (H == 128 ? 1 : 2) + (H == 128 ? 2 : 1)); }
-
-// gate-input block <-> LDS
-template <int P>
-__device__ __forceinline__ void store_gi16(char *dst, int lane, const f32x4 &v)
-{
-    if constexpr (P == 1) {
-        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-        const bf16x4 t = {(__bf16)v[0], (__bf16)v[1], (__bf16)v[2], (__bf16)v[3]};
-        *reinterpret_cast<bf16x4 *>(dst + lane * 8) = t;
-    } else {
-        *reinterpret_cast<f32x4 *>(dst + lane * 16) = v;
-    }
-}
-
-template <int P>
-__device__ __forceinline__ f32x4 load_gi16(const char *src, int lane)
-{
-    if constexpr (P == 1) {
-        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-        const bf16x4 t = *reinterpret_cast<const bf16x4 *>(src + lane * 8);
-        const f32x4 v = {(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
-        return v;
-    } else {
-        return *reinterpret_cast<const f32x4 *>(src + lane * 16);
-    }
-}
-
-// W_ih x + b for gate blocks [B0, B1) of one slot: x and the weight fragments come from LDS, the
-// results go back to LDS for the compute waves.  Blocks are taken four at a time and k-step by
-// k-step, so that an accumulator is touched by every fourth MFMA only (a dependent MFMA cannot
-// issue before its predecessor has left the pipe).  The four fragments of a k-step are requested
-// two k-steps ahead of their MFMAs; scheduling barriers keep the compiler from sinking those
-// reads back next to their use.  A group's results are stored one k-step into the next group,
-// when its last MFMAs have long finished; its accumulators start from the gate biases.
-template <int H, int P, int B0, int B1>
-__device__ __forceinline__ void gate_inputs(char *lds, int slot, int lane, int q4)
-{
-    using Sh = Fused16<H, P>;
-    constexpr int KS = Sh::KS, GB = 4, NG = (B1 - B0) / GB, NT = NG * KS, DEPTH = 3;
-    constexpr int NACC = KS >= 3 ? 2 : 3;            // accumulator sets in rotation (see the bias request below)
-    static_assert((B1 - B0) % GB == 0, "groups of four blocks");
-    if constexpr (NG > 0) {
-        const int buf = slot & 1;
-        // The per-lane offsets are made opaque once per call: otherwise the compiler precomputes
-        // one address register per fragment, keeps them across the slot loop and spills them.
-        // Two bases because an LDS access encodes at most 64 KB of constant offset.
-        uint32_t lane_off = lane * 16, lane_off_hi = lane * 16 + 65536;
-        asm volatile("" : "+v"(lane_off), "+v"(lane_off_hi));
-        const char *wih_lane = lds + Sh::oWih + lane_off, *wih_lane_hi = lds + Sh::oWih + lane_off_hi;
-        const float *gb = reinterpret_cast<const float *>(lds + Sh::oGBias);
-        char *gi_dst = lds + Sh::oGi + buf * Sh::kGiBytes;
-        Frag<P> x[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 *src = reinterpret_cast<const bf16x8 *>(lds + Sh::oX) + (size_t)((buf * KS + ks) * P) * 64 + lane;
-            x[ks].hi = src[0];
-            if constexpr (P == 2) x[ks].lo = src[64];
-        }
-        WFrag<P> w[DEPTH][GB];
-        f32x4 acc[NACC][GB];
-        auto request = [&](int t) {                  // fragments of step t = (group, k-step); a group's biases with its first step
-            const int g = t / KS, ks = t % KS;
-#pragma unroll
-            for (int j = 0; j < GB; ++j) {
-                const int blk = B0 + g * GB + j, off = (blk * KS + ks) * Sh::kFrag;
-                w[t % DEPTH][j] = load_wfrag<P>(reinterpret_cast<const bf16x8 *>(off + Sh::kFrag <= 65536 ? wih_lane + off : wih_lane_hi + (off - 65536)));
-                if (ks == 0) acc[g % NACC][j] = load_feature4(gb, blk, q4);
-            }
-        };
-        auto store_group = [&](int g) {
-#pragma unroll
-            for (int j = 0; j < GB; ++j) store_gi16<P>(gi_dst + (B0 + g * GB + j) * Sh::kGiBlock, lane, acc[g % NACC][j]);
-        };
-#pragma unroll
-        for (int t = 0; t < DEPTH - 1; ++t)
-            if (t < NT) request(t);
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int g = t / KS, ks = t % KS;
-            if (t + DEPTH - 1 < NT) request(t + DEPTH - 1);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int j = 0; j < GB; ++j) mma16<P>(acc[g % NACC][j], w[t % DEPTH][j], x[ks]);
-            if (ks == 1 % KS && g > 0) store_group(g - 1);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        store_group(NG - 1);
-    }
-}
+constexpr int fused_threads(int H) { return 64 * (4 + 2 + (H == 128 ? 2 : 1)); }
 
 template <int H, int P, int AB, bool QALL>
 __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
@@ -186,7 +90,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     const bool valid = row < rows;                     // rows past the end compute on row 0's inputs; results dropped
     const int b = valid ? row / N : 0, n = valid ? row % N : 0;
 
-    // W_ih -> LDS, all waves.  Its first reader starts after at least three barriers.
+    // W_ih -> LDS, all waves.  Its first readers start after kFusedLead barriers.
     {
         constexpr int kVecs = 3 * FBK * KS * P * 64;
         for (int i = threadIdx.x; i < kVecs; i += fused_threads(H)) wih_lds[i] = net.wih_16[i];
@@ -195,60 +99,119 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 
     if (wave < Sh::NC) {
         // ---------------------------------------------------------------- compute wave
-        // hidden units 32 w .. 32 w + 31 = feature blocks 2 w, 2 w + 1 = k-step w of the next operand
+        // feature blocks NBC w .. NBC w + NBC - 1 of the hidden state, all three gates
+        constexpr int NBC = Sh::NBC;
         const int w = wave;
-        WFrag<P> whh[3][2][KS];
+        WFrag<P> whh[3][NBC][KS];
 #pragma unroll
         for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < NBC; ++j)
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + 2 * w + j) * KS + ks) * P) * 64 + lane);
-        f32x4 bias_hn[2], hv[2];
+                    whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + NBC * w + j) * KS + ks) * P) * 64 + lane);
+        f32x4 bias_hn[NBC], hv[NBC];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            bias_hn[j] = load_feature4(net.bias_hn, 2 * w + j, q4);
+        for (int j = 0; j < NBC; ++j) {
+            bias_hn[j] = load_feature4(net.bias_hn, NBC * w + j, q4);
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[j][r] = 0.0f;
         }
-        {
-            const Frag<P> z0 = frag_of_pair<P>(hv[0], hv[1]);
-            h_lds[0][w][0][lane] = z0.hi;
-            if constexpr (P == 2) h_lds[0][w][1][lane] = z0.lo;
-        }
+        float *const gb = reinterpret_cast<float *>(lds + Sh::oGBias);
+        if (w == 0)
+            for (int i = lane; i < 3 * H; i += 64) {
+                const int gate = i / H, j = i % H;   // = feature 16 (gate FBK + j / 16) + j % 16 of the stacked gates
+                const float *src = gate == 0 ? net.bias_r : gate == 1 ? net.bias_z : net.bias_in;
+                gb[i] = src[j];
+            }
+        // The hidden state as next operand: two adjacent feature blocks make one k-step.  A wave
+        // with two blocks writes a whole fragment, a wave with one block its half of every lane's
+        // 16 bytes.
+        auto publish = [&](int buf) {
+            if constexpr (NBC == 2) {
+                const Frag<P> f = frag_of_pair<P>(hv[0], hv[1]);
+                h_lds[buf][w][0][lane] = f.hi;
+                if constexpr (P == 2) h_lds[buf][w][1][lane] = f.lo;
+            } else {
+                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                bf16x4 hi, lo;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    hi[r] = (__bf16)hv[0][r];
+                    lo[r] = (__bf16)(hv[0][r] - (float)hi[r]);
+                }
+                char *dst = reinterpret_cast<char *>(&h_lds[buf][w / 2][0][lane]) + (w & 1) * 8;
+                *reinterpret_cast<bf16x4 *>(dst) = hi;
+                if constexpr (P == 2) *reinterpret_cast<bf16x4 *>(dst + 1024) = lo;
+            }
+        };
+        publish(0);
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it <= T) {
                 const int cur = it & 1;
-                const char *gi_cur = lds + Sh::oGi + cur * Sh::kGiBytes;
-                f32x4 acc[3][2];
+                // The per-lane offsets are made opaque once per slot: otherwise the compiler
+                // precomputes one address register per fragment and keeps them across the loop.
+                // Two bases because an LDS access encodes at most 64 KB of constant offset.
+                uint32_t lane_off = lane * 16, lane_off_hi = lane * 16 + 65536;
+                asm volatile("" : "+v"(lane_off), "+v"(lane_off_hi));
+                const char *wih_lane = lds + Sh::oWih + lane_off, *wih_lane_hi = lds + Sh::oWih + lane_off_hi;
+                WFrag<P> wi[2][3][NBC];              // W_ih fragments of two k-steps in rotation
+                auto request = [&](int ks) {
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    acc[0][j] = load_gi16<P>(gi_cur + (0 * FBK + 2 * w + j) * Sh::kGiBlock, lane);
-                    acc[1][j] = load_gi16<P>(gi_cur + (1 * FBK + 2 * w + j) * Sh::kGiBlock, lane);
-                    acc[2][j] = bias_hn[j];
-                }
-                Frag<P> hb[KS];
+                    for (int gate = 0; gate < 3; ++gate)
+#pragma unroll
+                        for (int j = 0; j < NBC; ++j) {
+                            const int off = ((gate * FBK + NBC * w + j) * KS + ks) * Sh::kFrag;
+                            wi[ks % 2][gate][j] = load_wfrag<P>(reinterpret_cast<const bf16x8 *>(
+                                off + Sh::kFrag <= 65536 ? wih_lane + off : wih_lane_hi + (off - 65536)));
+                        }
+                };
+                Frag<P> hb[KS], x[KS];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     hb[ks].hi = h_lds[cur][ks][0][lane];
                     if constexpr (P == 2) hb[ks].lo = h_lds[cur][ks][1][lane];
                 }
+                f32x4 acc_r[NBC], acc_z[NBC], acc_in[NBC], acc_hn[NBC];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-                    for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-                        for (int j = 0; j < 2; ++j) mma16<P>(acc[gate][j], whh[gate][j][ks], hb[ks]);
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const f32x4 ain = load_gi16<P>(gi_cur + (2 * FBK + 2 * w + j) * Sh::kGiBlock, lane);
-                    hv[j] = gru_blend4(acc[0][j], acc[1][j], ain, acc[2][j], hv[j]);
+                for (int j = 0; j < NBC; ++j) {
+                    acc_r[j] = load_feature4(gb, 0 * FBK + NBC * w + j, q4);
+                    acc_z[j] = load_feature4(gb, 1 * FBK + NBC * w + j, q4);
+                    acc_in[j] = load_feature4(gb, 2 * FBK + NBC * w + j, q4);
+                    acc_hn[j] = bias_hn[j];
                 }
-                const Frag<P> f = frag_of_pair<P>(hv[0], hv[1]);
-                h_lds[cur ^ 1][w][0][lane] = f.hi;
-                if constexpr (P == 2) h_lds[cur ^ 1][w][1][lane] = f.lo;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    x[ks].hi = x_lds[cur][ks][0][lane];
+                    if constexpr (P == 2) x[ks].lo = x_lds[cur][ks][1][lane];
+                }
+                request(0);
+                request(1);
+                __builtin_amdgcn_sched_barrier(0);
+                // per k-step: the hidden product from registers, then the input product whose
+                // fragments were requested two k-steps earlier
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                    for (int j = 0; j < NBC; ++j) {
+                        mma16<P>(acc_r[j], whh[0][j][ks], hb[ks]);
+                        mma16<P>(acc_z[j], whh[1][j][ks], hb[ks]);
+                        mma16<P>(acc_hn[j], whh[2][j][ks], hb[ks]);
+                    }
+#pragma unroll
+                    for (int j = 0; j < NBC; ++j) {
+                        mma16<P>(acc_r[j], wi[ks % 2][0][j], x[ks]);
+                        mma16<P>(acc_z[j], wi[ks % 2][1][j], x[ks]);
+                        mma16<P>(acc_in[j], wi[ks % 2][2][j], x[ks]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ks + 2 < KS) request(ks + 2);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int j = 0; j < NBC; ++j) hv[j] = gru_blend4(acc_r[j], acc_z[j], acc_in[j], acc_hn[j], hv[j]);
+                publish(cur ^ 1);
             }
             lds_barrier();
         }
@@ -283,13 +246,8 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             return in;
         };
         SlotIn nxt = fetch_slot(0);
-        // lead-in steps: the epilogue wave's share of the gate inputs of slot 0 belongs to step -1
-        for (int i = 0; i < LEAD; ++i) {
-            if (i == LEAD - 1) gate_inputs<H, P, 0, Sh::kEpiBlocks>(lds, 0, lane, q4);
-            lds_barrier();
-        }
+        for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
-            if (it + 1 <= T) gate_inputs<H, P, 0, Sh::kEpiBlocks>(lds, it + 1, lane, q4);
             if (it >= 1) {
                 const int t = it - 1, cur = it & 1;          // h_t was published during iteration t
                 const SlotIn in = nxt;
@@ -331,14 +289,8 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             }
             lds_barrier();
         }
-    } else if (wave == Sh::kGates) {
-        // ---------------------------------------------------------------- gates wave (and observation loader)
-        float *const gb = reinterpret_cast<float *>(lds + Sh::oGBias);       // private to this wave
-        for (int i = lane; i < 3 * H; i += 64) {
-            const int gate = i / H, j = i % H;       // = feature 16 (gate FBK + j / 16) + j % 16 of the stacked gates
-            const float *src = gate == 0 ? net.bias_r : gate == 1 ? net.bias_z : net.bias_in;
-            gb[i] = src[j];
-        }
+    } else if (wave == Sh::kLoader) {
+        // ---------------------------------------------------------------- loader wave
         // Observations: this lane's row, floats 32 ks + 8 q + 0..7 of k-step ks (the B operand's
         // k order).  Every k-step but the last lies wholly inside the row and is fetched as two
         // 16-byte loads at constant offsets from one address (only 4-byte alignment is assumed).
@@ -356,7 +308,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         for (int i = 0; i < 8; ++i) last[i] = 0.0f;
 
         for (int s = -LEAD; s <= T + 1; ++s) {
-            const int ws = s + 3, ls = s + 4, gs = s + 1;
+            const int ws = s + 2, ls = s + 3;
             if (ws >= 0 && ws <= T) {                // observations of slot ws: registers -> LDS
                 bf16x8 *dst = obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane;
                 auto put = [&](bf16x8 *at, const float (&v)[8]) {
@@ -383,14 +335,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
                 for (int i = 0; i < 8; ++i) last[i] = r[last_off[i]];
             }
-            if (gs >= 0 && gs <= T) gate_inputs<H, P, Sh::kEpiBlocks, Sh::kGate1Blocks>(lds, gs, lane, q4);      // W_ih x + b of slot gs
-            lds_barrier();
-        }
-    } else if (wave < Sh::kFc1) {
-        // ---------------------------------------------------------------- second gates wave
-        for (int s = -LEAD; s <= T + 1; ++s) {
-            const int gs = s + 1;
-            if (gs >= 0 && gs <= T) gate_inputs<H, P, Sh::kGate1Blocks, 3 * FBK>(lds, gs, lane, q4);
             lds_barrier();
         }
     } else {
@@ -426,14 +370,14 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         // consumes it) before it is loaded again.  The sets never move and the loop below is
         // unrolled over them, so no wait covers a load younger than kTouchAhead - 1 steps.
         auto touch = [&](uint32_t (&set)[TL], int s) {
-            const float *r = touch_row + (size_t)min(max(s + 4 + kTouchAhead, 0), T) * N * D;   // ends: touched twice
+            const float *r = touch_row + (size_t)min(max(s + 3 + kTouchAhead, 0), T) * N * D;   // ends: touched twice
 #pragma unroll
             for (int j = 0; j < TL; ++j) asm volatile("" ::"v"(set[j]));
 #pragma unroll
             for (int j = 0; j < TL; ++j) set[j] = __builtin_bit_cast(uint32_t, r[touch_off[j]]);
         };
         auto fc1_step = [&](int s) {
-            const int slot = s + 2;
+            const int slot = s + 1;
             if (slot >= 0 && slot <= T) {
                 f32x4 acc[NBF];
 #pragma unroll
