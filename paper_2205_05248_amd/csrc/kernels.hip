@@ -1,15 +1,17 @@
-// gfx950 kernels of the recurrent Q-network and their launchers.
+// gfx950 kernels of the recurrent Q-network on tiles of 32 rows, and their launchers.
 //
-//   act_step_kernel      decision step: every wavefront owns 32 (env, agent) rows and runs
-//                        fc1 -> GRU cell -> fc2 -> mask/argmax/epsilon-greedy without leaving
-//                        registers.
-//   input_proj_kernel    unroll, part 1: fc1 and the input half of the GRU gates for every
-//                        (episode, slot, agent); no dependence on the hidden state, so all
-//                        B (T+1) N rows run in parallel.  Results go to a scratch buffer in the
-//                        accumulator layout of the consumer.
-//   recurrent_td_kernel  unroll, part 2: one wavefront per 32 (episode, agent) rows walks the
-//                        T+1 slots with the hidden state in registers, adds the hidden half of
-//                        the gates, applies fc2 and emits q_taken / next_max / td_target.
+//   front_kernel<.., ACT>    decision step: every wavefront owns tiles of 32 (env, agent) rows and
+//                            runs fc1 -> GRU cell -> fc2 -> mask/argmax/epsilon-greedy without its
+//                            activations leaving registers; the weights stream through LDS.
+//   front_kernel<.., !ACT>   two-kernel unroll, part 1: fc1 and the input half of the GRU gates for
+//                            every (episode, slot, agent); no dependence on the hidden state, so all
+//                            B (T+1) N rows run in parallel.  Results go to a scratch buffer in the
+//                            accumulator layout of the consumer.
+//   recurrent_td_kernel      two-kernel unroll, part 2: one workgroup per 32 (episode, agent) rows
+//                            walks the T+1 slots, adds the hidden half of the gates, applies fc2 and
+//                            emits q_taken / next_max / td_target.
+// The default unroll is the fused kernel of unroll_fused.hip; this pair serves the networks that do
+// not fit it.
 #include "mfma_tile.h"
 #include "stream_layout.h"
 #include "recurrent_roles.h"
