@@ -42,11 +42,11 @@ def unroll_bytes_per_agent_step(N, D, A, H):
     return 4 * D + A + 16
 
 
-UNROLL_PATHS = {"auto": 0, "split": 1, "fused": 2}
+KERNELS = {"auto": 0, "tile32": 1, "fused16": 2}
 
 
 class Bench:
-    def __init__(self, ci, two_nets=True, unroll_path="auto"):
+    def __init__(self, ci, two_nets=True, kernels="auto"):
         import torch
         from paper_2205_05248_amd import binding, workloads as wl
         self.torch, self.wl = torch, wl
@@ -56,8 +56,9 @@ class Bench:
         self.w_on, self.w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
         self.online = binding.QNet(dims, self.w_on, cfg["dtype"])
         self.target = binding.QNet(dims, self.w_tg, cfg["dtype"]) if two_nets else None
-        self.online.set_unroll_path(UNROLL_PATHS[unroll_path])
-        self.fused = self.online.unroll_path_in_use() == binding.UNROLL_FUSED
+        self.online.set_kernels(KERNELS[kernels])
+        self.fused = self.online.kernels_in_use(binding.ENTRY_UNROLL_TD) == binding.KERNELS_FUSED16
+        self.act_fused = self.online.kernels_in_use(binding.ENTRY_ACT_STEP) == binding.KERNELS_FUSED16
         dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         E, B, T = cfg["E"], cfg["B"], cfg["T"]
         set_bytes = E * N * act_bytes_per_agent_step(*dims)
@@ -170,8 +171,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload index 0..4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--single-net", action="store_true", help="target == online in the unroll")
-    ap.add_argument("--unroll-path", choices=sorted(UNROLL_PATHS), default="auto",
-                    help="implementation of the unroll (auto: the library's choice)")
+    ap.add_argument("--kernels", choices=sorted(KERNELS), default="auto",
+                    help="kernel family (auto: the library's choice)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU only: every (env, agent) row is independent, so more GPUs "
@@ -182,7 +183,7 @@ def main():
         build.build()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    b = Bench(args.config, two_nets=not args.single_net, unroll_path=args.unroll_path)
+    b = Bench(args.config, two_nets=not args.single_net, kernels=args.kernels)
     cfg, dims = b.cfg, b.dims
     N, D, A, H = dims
     E, B, T = cfg["E"], cfg["B"], cfg["T"]
@@ -245,7 +246,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["name"], "E": E, "N": N, "obs_dim": D, "n_actions": A, "hidden": H,
                    "B": B, "T": T, "target_network": "distinct" if nets == 2 else "same",
-                   "unroll_path": "fused" if b.fused else "split",
+                   "kernels": {"act_step": "fused16" if b.act_fused else "tile32",
+                               "unroll_td": "fused16" if b.fused else "tile32"},
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
         "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
                      "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": kernels["act_step"]["GBs"],

@@ -143,13 +143,11 @@ int marl_act_step(marl_qnet *q, int32_t E,
  * through padding.  Actions outside [0,A) are clamped into range.
  *
  * Two implementations exist and compute the same function (see
- * marl_qnet_set_unroll_path).  The two-kernel path writes the input half of
- * the GRU gates for every slot to a scratch buffer and then runs the
- * recurrence; the fused path keeps every intermediate on chip and needs no
- * scratch, but only serves networks whose shape fits its on-chip buffers
- * (bf16 weights: obs_dim <= 320; fp32 weights: hidden = 64 and obs_dim <= 160).
+ * marl_qnet_set_kernels).  The tile32 one writes the input half of the GRU
+ * gates for every slot to a scratch buffer and then runs the recurrence; the
+ * fused16 one keeps every intermediate on chip and needs no scratch.
  *
- * Scratch (two-kernel path only): the library keeps one device buffer per
+ * Scratch (tile32 kernels only): the library keeps one device buffer per
  * handle for intermediate activations, grown (never shrunk) when a call needs
  * more than any earlier call; growing synchronises the device.
  * marl_qnet_reserve_unroll sizes it ahead of time so that later calls up to
@@ -165,20 +163,28 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*
- * Choice of the unroll implementation for calls whose `online` handle is q.
- *   MARL_UNROLL_AUTO   the fused kernel when the network fits it, else the two-kernel path (the default)
- *   MARL_UNROLL_SPLIT  always the two-kernel path
- *   MARL_UNROLL_FUSED  always the fused kernel; MARL_ERR_BAD_DIM if the network does not fit it
+ * Choice of the kernel family for calls on this handle (for marl_unroll_td: the `online` handle).
+ * Two families compute the same functions:
+ *   fused16  tiles of 16 rows, every weight resident on chip, one kernel per call; serves the
+ *            networks that fit its on-chip buffers (bf16 weights: obs_dim <= 320; fp32 weights:
+ *            hidden = 64 and obs_dim <= 160)
+ *   tile32   tiles of 32 rows, weights streamed; the unroll is two kernels with a scratch buffer
+ *            between them; serves every network
+ *   MARL_KERNELS_AUTO     fused16 when the network fits it, else tile32 (the default)
+ *   MARL_KERNELS_TILE32   always tile32
+ *   MARL_KERNELS_FUSED16  always fused16; MARL_ERR_BAD_DIM if the network does not fit it
  * Returns MARL_ERR_BAD_ARG for any other value.
  */
-#define MARL_UNROLL_AUTO 0
-#define MARL_UNROLL_SPLIT 1
-#define MARL_UNROLL_FUSED 2
-int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path);
+#define MARL_KERNELS_AUTO 0
+#define MARL_KERNELS_TILE32 1
+#define MARL_KERNELS_FUSED16 2
+int marl_qnet_set_kernels(marl_qnet *q, int32_t which);
 
-/* The implementation marl_unroll_td uses for this handle as things stand: MARL_UNROLL_SPLIT or
- * MARL_UNROLL_FUSED (never AUTO); MARL_ERR_NULL (negative) for a null handle. */
-int marl_qnet_unroll_path_in_use(const marl_qnet *q);
+/* The family an entry point uses for this handle as things stand: MARL_KERNELS_TILE32 or
+ * MARL_KERNELS_FUSED16 (never AUTO).  Negative status for a null handle or an unknown entry. */
+#define MARL_ENTRY_ACT_STEP 0
+#define MARL_ENTRY_UNROLL_TD 1
+int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry);
 
 /*
  * Kernel timing for benchmarks.  While timing is enabled on a handle, marl_act_step and

@@ -21,7 +21,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
-           "marl_qnet_set_unroll_path", "marl_qnet_unroll_path_in_use"]
+           "marl_qnet_set_kernels", "marl_qnet_kernels_in_use"]
 
 
 class MarlError(RuntimeError):
@@ -63,10 +63,10 @@ def load():
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
-        lib.marl_qnet_unroll_path_in_use.restype = ctypes.c_int
-        lib.marl_qnet_unroll_path_in_use.argtypes = [vp]
-        lib.marl_qnet_set_unroll_path.restype = ctypes.c_int
-        lib.marl_qnet_set_unroll_path.argtypes = [vp, i32]
+        lib.marl_qnet_kernels_in_use.restype = ctypes.c_int
+        lib.marl_qnet_kernels_in_use.argtypes = [vp, i32]
+        lib.marl_qnet_set_kernels.restype = ctypes.c_int
+        lib.marl_qnet_set_kernels.argtypes = [vp, i32]
         lib.marl_qnet_set_timing.restype = ctypes.c_int
         lib.marl_qnet_set_timing.argtypes = [vp, i32]
         lib.marl_qnet_timing_read.restype = ctypes.c_int
@@ -158,15 +158,18 @@ def marl_qnet_reserve_unroll(handle, B, T):
     check(load().marl_qnet_reserve_unroll(ctypes.c_void_p(handle), B, T))
 
 
-UNROLL_AUTO, UNROLL_SPLIT, UNROLL_FUSED = 0, 1, 2
+KERNELS_AUTO, KERNELS_TILE32, KERNELS_FUSED16 = 0, 1, 2
 
 
-def marl_qnet_set_unroll_path(handle, path):
-    check(load().marl_qnet_set_unroll_path(ctypes.c_void_p(handle), int(path)))
+def marl_qnet_set_kernels(handle, path):
+    check(load().marl_qnet_set_kernels(ctypes.c_void_p(handle), int(path)))
 
 
-def marl_qnet_unroll_path_in_use(handle):
-    rc = load().marl_qnet_unroll_path_in_use(ctypes.c_void_p(handle))
+ENTRY_ACT_STEP, ENTRY_UNROLL_TD = 0, 1
+
+
+def marl_qnet_kernels_in_use(handle, entry):
+    rc = load().marl_qnet_kernels_in_use(ctypes.c_void_p(handle), int(entry))
     if rc < 0:
         check(rc)
     return rc
@@ -204,11 +207,11 @@ class QNet:
         marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                        gamma, q_taken, next_max, td_target, q_all)
 
-    def set_unroll_path(self, path):
-        marl_qnet_set_unroll_path(self.handle, path)
+    def set_kernels(self, path):
+        marl_qnet_set_kernels(self.handle, path)
 
-    def unroll_path_in_use(self):
-        return marl_qnet_unroll_path_in_use(self.handle)
+    def kernels_in_use(self, entry):
+        return marl_qnet_kernels_in_use(self.handle, entry)
 
     def set_timing(self, enable):
         marl_qnet_set_timing(self.handle, enable)

@@ -1,0 +1,38 @@
+// Shape and LDS layout shared by the fused kernels on tiles of 16 rows (unroll_fused.hip,
+// act_fused.hip): which wavefront plays which role, what stays resident where, and the byte
+// offsets of the LDS buffers.
+#pragma once
+#include "mfma16_tile.h"
+#include "unroll_common.h"
+
+namespace marl {
+
+constexpr int kFusedLead = 3;         // steps before slot 0 enters the recurrence
+constexpr int kLdsLimit = 160 * 1024;
+
+template <int H, int P> struct Fused16 {
+    static constexpr int FBK = H / 16;                 // feature blocks of the hidden layer
+    static constexpr int KS = H / 32;                  // k-steps over the hidden layer
+    static constexpr int NC = 4;                       // compute waves
+    static constexpr int NBC = FBK / NC;               // feature blocks per compute wave (2 or 1)
+    static constexpr int NF = H == 128 ? 2 : 1;        // fc1 waves
+    static constexpr int kEpilogue = NC, kLoader = NC + 1, kFc1 = NC + 2, kWaves = NC + 2 + NF;
+    static constexpr int NBF = FBK / NF;               // fc1 feature blocks per fc1 wave
+    static constexpr int kKs1Max = 40 / (NBF * P);     // observation k-steps whose W1 fragments fit 160 registers
+    static constexpr int kFrag = P * 1024;             // bytes of one fragment (all planes)
+    // LDS layout (byte offsets)
+    static constexpr int oWih = 0;                                  // [3 FBK][KS][P][64] bf16x8
+    static constexpr int oH = oWih + 3 * FBK * KS * kFrag;          // [2][KS][P][64] bf16x8
+    static constexpr int oX = oH + 2 * KS * kFrag;                  // [2][KS][P][64] bf16x8
+    static constexpr int oGBias = oX + 2 * KS * kFrag;              // [3 H] floats: b_ir + b_hr, b_iz + b_hz, b_in
+    static constexpr int oB2 = oGBias + 3 * H * 4;                  // [64] floats
+    static constexpr int oObs = oB2 + 256;                          // [2][ks1][P][64] bf16x8
+    static constexpr size_t lds_bytes(int ks1) { return (size_t)oObs + (size_t)2 * ks1 * kFrag; }
+    // decision step only: the incoming hidden state as operand fragments, [2][KS][P][64] bf16x8 after the observations
+    static constexpr size_t hin_offset(int ks1) { return lds_bytes(ks1); }
+    static constexpr size_t lds_bytes_act(int ks1) { return lds_bytes(ks1) + (size_t)2 * KS * kFrag; }
+};
+
+constexpr int fused_threads(int H) { return 64 * (4 + 2 + (H == 128 ? 2 : 1)); }
+
+}  // namespace marl

@@ -140,7 +140,12 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     q->dev_weight_bytes = img.bytes;
     q->scratch = nullptr;
     q->scratch_bytes = 0;
-    q->unroll_path = MARL_UNROLL_AUTO;
+    q->kernels = MARL_KERNELS_AUTO;
+    {
+        int n_cu = 0;
+        if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, desc->device) != hipSuccess || n_cu <= 0) n_cu = 256;
+        q->n_cu = n_cu;
+    }
     q->timing = false;
     q->ev_used = 0;
     err = hipMalloc(&q->dev_weights, img.bytes);
@@ -178,6 +183,15 @@ int marl_qnet_get_desc(const marl_qnet *q, marl_qnet_desc *out)
     return MARL_OK;
 }
 
+namespace {
+// AUTO: the fused kernels wherever the network fits them (they were the faster ones on every shape measured).
+bool takes_fused_path(const marl_qnet *q, bool for_unroll)
+{
+    if (q->kernels == MARL_KERNELS_TILE32) return false;
+    return for_unroll ? marl::unroll_fused_fits(q->net) : marl::act_fused_fits(q->net);
+}
+}  // namespace
+
 int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avail, const float *h_in,
                   const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed,
                   float *h_out, int32_t *action, float *q_out, void *hip_stream)
@@ -200,18 +214,13 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
         if (rc != MARL_OK) return rc;
     }
     if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
-    MARL_HIP(marl::launch_act_step(q->net, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
+    if (takes_fused_path(q, false))
+        MARL_HIP(marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
+    else
+        MARL_HIP(marl::launch_act_step(q->net, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
     if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
     return MARL_OK;
 }
-
-namespace {
-// AUTO: the fused kernel wherever the network fits it (it was the faster one on every shape measured).
-bool takes_fused_path(const marl_qnet *q)
-{
-    return q->unroll_path == MARL_UNROLL_FUSED || (q->unroll_path == MARL_UNROLL_AUTO && marl::unroll_fused_fits(q->net));
-}
-}  // namespace
 
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
 {
@@ -220,22 +229,23 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
         return MARL_ERR_BAD_DIM;
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
-    if (takes_fused_path(q)) return MARL_OK;
+    if (takes_fused_path(q, true)) return MARL_OK;
     return ensure_scratch(q, marl::unroll_scratch_bytes(q->net, B, T));
 }
 
-int marl_qnet_unroll_path_in_use(const marl_qnet *q)
+int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry)
 {
     if (!q) return MARL_ERR_NULL;
-    return takes_fused_path(q) ? MARL_UNROLL_FUSED : MARL_UNROLL_SPLIT;
+    if (entry != MARL_ENTRY_ACT_STEP && entry != MARL_ENTRY_UNROLL_TD) return MARL_ERR_BAD_ARG;
+    return takes_fused_path(q, entry == MARL_ENTRY_UNROLL_TD) ? MARL_KERNELS_FUSED16 : MARL_KERNELS_TILE32;
 }
 
-int marl_qnet_set_unroll_path(marl_qnet *q, int32_t path)
+int marl_qnet_set_kernels(marl_qnet *q, int32_t path)
 {
     if (!q) return MARL_ERR_NULL;
-    if (path != MARL_UNROLL_AUTO && path != MARL_UNROLL_SPLIT && path != MARL_UNROLL_FUSED) return MARL_ERR_BAD_ARG;
-    if (path == MARL_UNROLL_FUSED && !marl::unroll_fused_fits(q->net)) return MARL_ERR_BAD_DIM;
-    q->unroll_path = path;
+    if (path != MARL_KERNELS_AUTO && path != MARL_KERNELS_TILE32 && path != MARL_KERNELS_FUSED16) return MARL_ERR_BAD_ARG;
+    if (path == MARL_KERNELS_FUSED16 && !(marl::unroll_fused_fits(q->net) && marl::act_fused_fits(q->net))) return MARL_ERR_BAD_DIM;
+    q->kernels = path;
     return MARL_OK;
 }
 
@@ -262,7 +272,7 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     DeviceGuard guard(a.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     const bool two = online != target;
-    const bool fused = takes_fused_path(online);
+    const bool fused = takes_fused_path(online, true);
     int rc = MARL_OK;
     if (!fused) {
         const size_t need = marl::unroll_scratch_bytes(online->net, B, T);

@@ -59,7 +59,8 @@ struct marl_qnet {
     marl::NetFrags net;
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
-    int unroll_path;                   // MARL_UNROLL_AUTO / MARL_UNROLL_SPLIT
+    int n_cu;                          // compute units of the device
+    int kernels;                       // MARL_KERNELS_AUTO / MARL_KERNELS_TILE32
     bool timing;                       // record events around the kernels of each call
     std::vector<hipEvent_t> ev_pool;   // events created so far (reused after a read)
     size_t ev_used;                    // events handed out since the last read
@@ -90,6 +91,13 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
                             float *q_all, hipStream_t stream, hipEvent_t between);
+
+// Fused decision step (act_fused.hip).  `fits` as below; groups_hint = workgroups to spread the
+// tiles over (0: one per compute unit).
+bool act_fused_fits(const NetFrags &net);
+hipError_t launch_act_fused(const NetFrags &net, int E, int groups_hint, const float *obs, const uint8_t *avail,
+                            const float *h_in, const uint8_t *reset, const int32_t *step_t, float epsilon,
+                            uint64_t seed, float *h_out, int32_t *action, float *q_out, hipStream_t stream);
 
 // Fused unroll (unroll_fused.hip): no scratch buffer.  `fits` tells whether the network's shape
 // fits the kernel's LDS and register budgets; otherwise the two-kernel path above is used.

@@ -19,9 +19,12 @@ def _need_gpu():
         pytest.skip("no GPU in this container")
 
 
-def make_net(cfg, stream=0, weights=None):
+def make_net(cfg, stream=0, weights=None, kernels=None):
     w = wl.make_weights(cfg, stream) if weights is None else weights
-    return binding.QNet(wl.dims(cfg), w, cfg["dtype"]), pu.oracle_weights(cfg, w)
+    net = binding.QNet(wl.dims(cfg), w, cfg["dtype"])
+    if kernels is not None:
+        net.set_kernels(kernels)
+    return net, pu.oracle_weights(cfg, w)
 
 
 def oracle_act(cfg, w, inp):
@@ -34,12 +37,18 @@ def oracle_unroll(cfg, w_on, w_tg, u, rows=None):
                          u["terminated"], u["filled"], u["gamma"], rows=rows)
 
 
+# Both kernel families are held to the same bar.
+PATHS = [binding.KERNELS_TILE32, binding.KERNELS_FUSED16]
+PATH_IDS = ["tile32", "fused16"]
+
+
 # ------------------------------------------------------------------ act-step
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
-def test_act_step_full_config(ci):
+def test_act_step_full_config(ci, path):
     cfg = wl.config(ci)
     tol = pu.TOL[cfg["dtype"]]
-    net, w = make_net(cfg)
+    net, w = make_net(cfg, kernels=path)
     inp = wl.make_act_inputs(cfg)
     ref = oracle_act(cfg, w, inp)
     got = pu.gpu_act(net, cfg, inp)
@@ -54,10 +63,11 @@ def test_act_step_full_config(ci):
     net.close()
 
 
-@pytest.mark.parametrize("ci,E", [(0, 1), (0, 5), (0, 11), (1, 3), (1, 37), (3, 13), (3, 203), (4, 1), (4, 9)])
-def test_act_step_ragged_sizes(ci, E):
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("ci,E", [(0, 1), (0, 5), (0, 11), (1, 3), (1, 37), (3, 13), (3, 203), (3, 1000), (4, 1), (4, 9)])
+def test_act_step_ragged_sizes(ci, E, path):
     cfg = wl.config(ci)
-    net, w = make_net(cfg)
+    net, w = make_net(cfg, kernels=path)
     for eps in (0.0, 0.5, 1.0):
         inp = wl.make_act_inputs(cfg, E=E, stream=E)
         inp["epsilon"] = eps
@@ -152,11 +162,6 @@ def test_act_step_is_deterministic_and_isolated():
 
 
 # ------------------------------------------------------------------ unroll + TD
-# Both implementations of the unroll are held to the same bar.
-PATHS = [binding.UNROLL_SPLIT, binding.UNROLL_FUSED]
-PATH_IDS = ["split", "fused"]
-
-
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("ci", [0, 1, 2, 3])
 def test_unroll_td_full_config(ci, path):
@@ -164,7 +169,7 @@ def test_unroll_td_full_config(ci, path):
     tol = pu.TOL[cfg["dtype"]]
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
-    online.set_unroll_path(path)
+    online.set_kernels(path)
     u = wl.make_unroll_inputs(cfg)
     got = pu.gpu_unroll(online, target, cfg, u)
     ref = oracle_unroll(cfg, w_on, w_tg, u)
@@ -185,7 +190,7 @@ def test_unroll_td_full_config_4_sampled_rows(path):
     tol = pu.TOL[cfg["dtype"]]
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
-    online.set_unroll_path(path)
+    online.set_kernels(path)
     u = wl.make_unroll_inputs(cfg)
     got = pu.gpu_unroll(online, target, cfg, u)
     rows_total = cfg["B"] * cfg["N"]
@@ -214,7 +219,7 @@ def test_unroll_td_ragged_sizes(ci, B, T, path):
     cfg = wl.config(ci)
     online, w_on = make_net(cfg, 0)
     target, w_tg = make_net(cfg, 1)
-    online.set_unroll_path(path)
+    online.set_kernels(path)
     u = wl.make_unroll_inputs(cfg, B=B, T=T)
     got = pu.gpu_unroll(online, target, cfg, u)
     ref = oracle_unroll(cfg, w_on, w_tg, u)
