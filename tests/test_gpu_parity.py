@@ -286,3 +286,31 @@ def test_empty_batches_and_argument_errors():
         net.act_step(torch.zeros(2, N, D), torch.zeros(2, N, A, dtype=torch.uint8), torch.zeros(2, N, H), None,
                      torch.zeros(2, dtype=torch.int32), 0.0, 0, torch.zeros(2, N, H), torch.zeros(2, N, dtype=torch.int32))
     net.close(); other.close()
+
+
+# ------------------------------------------------------------------ kernel families
+@pytest.mark.parametrize("D,dtype,fused", [(320, "bf16", True), (352, "bf16", False), (160, "fp32", True), (176, "fp32", False)])
+def test_kernel_family_follows_the_network_shape(D, dtype, fused):
+    """Networks at and just past the fused kernels' limits: the library picks the family that
+    fits, both stay inside the tolerance, and forcing the fused family on a misfit is refused."""
+    base = wl.config(4 if dtype == "bf16" else 2)
+    cfg = dict(base, D=D, dtype=dtype, E=6, B=3, T=7)
+    net, w = make_net(cfg)
+    target, w_tg = make_net(cfg, 1)
+    want = binding.KERNELS_FUSED16 if fused else binding.KERNELS_TILE32
+    assert net.kernels_in_use(binding.ENTRY_ACT_STEP) == want
+    assert net.kernels_in_use(binding.ENTRY_UNROLL_TD) == want
+    if not fused:
+        with pytest.raises(binding.MarlError) as err:
+            net.set_kernels(binding.KERNELS_FUSED16)
+        assert err.value.status == -2                     # MARL_ERR_BAD_DIM
+    with pytest.raises(binding.MarlError):
+        net.set_kernels(7)
+    inp = wl.make_act_inputs(cfg)
+    pu.compare_act(cfg, inp, pu.gpu_act(net, cfg, inp), oracle_act(cfg, w, inp), pu.TOL[dtype])
+    u = wl.make_unroll_inputs(cfg)
+    pu.compare_unroll(pu.gpu_unroll(net, target, cfg, u), oracle_unroll(cfg, w, w_tg, u), pu.TOL[dtype])
+    net.set_kernels(binding.KERNELS_TILE32)
+    assert net.kernels_in_use(binding.ENTRY_UNROLL_TD) == binding.KERNELS_TILE32
+    pu.compare_unroll(pu.gpu_unroll(net, target, cfg, u), oracle_unroll(cfg, w, w_tg, u), pu.TOL[dtype])
+    net.close(); target.close()
