@@ -95,6 +95,18 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
                      marl_qnet **out);
 
 /* Copy of the description the handle was created with. */
+/*
+ * Replace the weights of a network in place (the learner publishing new parameters to the
+ * worker's copy; Sec. "Learner" and Alg. 3, the periodic parameter copy).  host_weights: the same
+ * packed fp32 layout and count as at create.  The call converts on the host into a pinned staging
+ * buffer the handle owns and enqueues one host-to-device copy on hip_stream, so it is ordered
+ * like a kernel on that stream: calls enqueued earlier on the stream use the old weights, calls
+ * enqueued later the new ones.  Work on other streams is not ordered against it; that is the
+ * caller's business.  A second call waits on the host until the previous call's copy has left
+ * the staging buffer.  host_weights may be reused as soon as the call returns.
+ */
+int marl_qnet_set_weights(marl_qnet *q, const float *host_weights, size_t n_weights, void *hip_stream);
+
 int marl_qnet_get_desc(const marl_qnet *q, marl_qnet_desc *out);
 
 /*

@@ -21,7 +21,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
-           "marl_qnet_set_kernels", "marl_qnet_kernels_in_use"]
+           "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 
 
 class MarlError(RuntimeError):
@@ -53,6 +53,8 @@ def load():
         vp, i32, f32, u64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_uint64
         lib.marl_param_count.restype = ctypes.c_size_t
         lib.marl_param_count.argtypes = [ctypes.POINTER(Desc)]
+        lib.marl_qnet_set_weights.restype = ctypes.c_int
+        lib.marl_qnet_set_weights.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.marl_qnet_create.restype = ctypes.c_int
         lib.marl_qnet_create.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
         lib.marl_qnet_get_desc.restype = ctypes.c_int
@@ -103,6 +105,12 @@ def marl_qnet_create(n_agents, obs_dim, n_actions, hidden, weight_dtype, device,
     out = ctypes.c_void_p()
     check(load().marl_qnet_create(ctypes.byref(d), w.ctypes.data_as(ctypes.c_void_p), w.size, ctypes.byref(out)))
     return out.value
+
+
+def marl_qnet_set_weights(handle, host_weights):
+    """Stream-ordered in-place weight refresh on torch's current stream."""
+    w = np.ascontiguousarray(host_weights, dtype=np.float32)
+    check(load().marl_qnet_set_weights(ctypes.c_void_p(handle), w.ctypes.data_as(ctypes.c_void_p), w.size, _stream()))
 
 
 def marl_destroy(handle):
@@ -206,6 +214,9 @@ class QNet:
         tgt = self if target is None else target
         marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                        gamma, q_taken, next_max, td_target, q_all)
+
+    def set_weights(self, weights):
+        marl_qnet_set_weights(self.handle, weights)
 
     def set_kernels(self, path):
         marl_qnet_set_kernels(self.handle, path)

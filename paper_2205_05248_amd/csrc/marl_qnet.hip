@@ -138,6 +138,8 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     q->n_params = n_weights;
     q->dev_weights = nullptr;
     q->dev_weight_bytes = img.bytes;
+    q->staging = nullptr;
+    q->staging_done = nullptr;
     q->scratch = nullptr;
     q->scratch_bytes = 0;
     q->kernels = MARL_KERNELS_AUTO;
@@ -173,6 +175,32 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.kc1 = img.kc1; n.mb2 = img.mb2; n.planes = img.planes;
     n.nc1 = img.nc1; n.act_chunks = img.act_chunks; n.proj_chunks = img.proj_chunks;
     *out = q;
+    return MARL_OK;
+}
+
+int marl_qnet_set_weights(marl_qnet *q, const float *host_weights, size_t n_weights, void *hip_stream)
+{
+    if (!q || !host_weights) return MARL_ERR_NULL;
+    if (n_weights != q->n_params) return MARL_ERR_MISMATCH;
+    marl::PackedImage img{};
+    if (!marl::pack_network(q->desc, host_weights, &img)) return MARL_ERR_NOMEM;
+    struct FreeHost { void *p; ~FreeHost() { std::free(p); } } free_host{img.host};
+    if (img.bytes != q->dev_weight_bytes) return MARL_ERR_MISMATCH;       // cannot happen: the layout depends on the descriptor only
+
+    DeviceGuard guard(q->desc.device);
+    if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    if (!q->staging) {
+        hipError_t err = hipHostMalloc(&q->staging, img.bytes, hipHostMallocDefault);
+        if (err != hipSuccess) { q->staging = nullptr; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipHostMalloc"); }
+        err = hipEventCreateWithFlags(&q->staging_done, hipEventDisableTiming);
+        if (err != hipSuccess) { (void)hipHostFree(q->staging); q->staging = nullptr; q->staging_done = nullptr; return device_fail(err, "hipEventCreate"); }
+    } else {
+        MARL_HIP(hipEventSynchronize(q->staging_done));                   // the previous upload still reads the buffer
+    }
+    std::memcpy(q->staging, img.host, img.bytes);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    MARL_HIP(hipMemcpyAsync(q->dev_weights, q->staging, img.bytes, hipMemcpyHostToDevice, stream));
+    MARL_HIP(hipEventRecord(q->staging_done, stream));
     return MARL_OK;
 }
 
@@ -349,8 +377,10 @@ int marl_destroy(marl_qnet *q)
         for (void *p : {q->dev_weights, q->scratch}) {
             if (!p) continue;
             hipError_t err = hipFree(p);
-            if (err != hipSuccess) rc = device_fail(err, "hipFree");
+            if (err != hipSuccess) rc = device_fail(err, "hipFree");        // hipFree waits for the device
         }
+        if (q->staging_done) (void)hipEventDestroy(q->staging_done);
+        if (q->staging) (void)hipHostFree(q->staging);
     }
     delete q;
     return rc;

@@ -57,6 +57,8 @@ struct marl_qnet {
     void *dev_weights;        // one allocation holding every fragment array and bias table
     size_t dev_weight_bytes;
     marl::NetFrags net;
+    void *staging;            // pinned host copy of the image, for marl_qnet_set_weights (allocated on first use)
+    hipEvent_t staging_done;  // recorded after the last upload from `staging`
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
     int n_cu;                          // compute units of the device

@@ -314,3 +314,38 @@ def test_kernel_family_follows_the_network_shape(D, dtype, fused):
     assert net.kernels_in_use(binding.ENTRY_UNROLL_TD) == binding.KERNELS_TILE32
     pu.compare_unroll(pu.gpu_unroll(net, target, cfg, u), oracle_unroll(cfg, w, w_tg, u), pu.TOL[dtype])
     net.close(); target.close()
+
+
+# ------------------------------------------------------------------ weight refresh
+@pytest.mark.parametrize("ci", [1, 4])
+def test_set_weights_is_ordered_on_the_stream(ci):
+    """New parameters published in place: calls enqueued before the refresh see the old network,
+    calls after it the new one, with no synchronisation in between; a second refresh right after
+    the first does not disturb it."""
+    cfg = dict(wl.config(ci), E=64, B=4, T=9)
+    w0, w1, w2 = (wl.make_weights(cfg, s) for s in (0, 1, 2))
+    net = binding.QNet(wl.dims(cfg), w0, cfg["dtype"])
+    inp = wl.make_act_inputs(cfg)
+    u = wl.make_unroll_inputs(cfg)
+    tol = pu.TOL[cfg["dtype"]]
+    N, D, A, H = wl.dims(cfg)
+    d = pu.to_dev(inp, ["obs", "avail", "h_in", "reset", "step_t"])
+    outs = []
+    for w in (None, w1, w2):
+        if w is not None:
+            net.set_weights(w)
+        h_out = torch.empty(cfg["E"], N, H, device="cuda")
+        act = torch.empty(cfg["E"], N, dtype=torch.int32, device="cuda")
+        q = torch.empty(cfg["E"], N, A, device="cuda")
+        net.act_step(d["obs"], d["avail"], d["h_in"], d["reset"], d["step_t"], inp["epsilon"], inp["seed"], h_out, act, q)
+        outs.append((h_out, act, q))
+    torch.cuda.synchronize()
+    for (h_out, act, q), w in zip(outs, (w0, w1, w2)):
+        ref = oracle_act(cfg, pu.oracle_weights(cfg, w), inp)
+        got = {"h_out": h_out.cpu().numpy(), "action": act.cpu().numpy(), "q": q.cpu().numpy()}
+        pu.compare_act(cfg, inp, got, ref, tol)
+    ref = oracle_unroll(cfg, pu.oracle_weights(cfg, w2), None, u)
+    pu.compare_unroll(pu.gpu_unroll(net, None, cfg, u), ref, tol)
+    with pytest.raises(binding.MarlError):
+        net.set_weights(w0[:-1])
+    net.close()
