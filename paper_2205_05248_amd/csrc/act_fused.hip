@@ -19,7 +19,7 @@
 // loading the weights (once per workgroup) is amortised over the run of tiles.
 #include <hip/hip_runtime.h>
 
-#include "fused16.h"
+#include "fused16_roles.h"
 
 namespace marl {
 
@@ -111,24 +111,9 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         // ---------------------------------------------------------------- compute wave
         constexpr int NBC = Sh::NBC;
         const int w = wave;
-        WFrag<P> whh[3][NBC][KS];
-#pragma unroll
-        for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-            for (int j = 0; j < NBC; ++j)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + NBC * w + j) * KS + ks) * P) * 64 + lane);
-        f32x4 bias_hn[NBC];
-#pragma unroll
-        for (int j = 0; j < NBC; ++j) bias_hn[j] = load_feature4(net.bias_hn, NBC * w + j, q4);
-        float *const gb = reinterpret_cast<float *>(lds + Sh::oGBias);
-        if (w == 0)
-            for (int i = lane; i < 3 * H; i += 64) {
-                const int gate = i / H, j = i % H;
-                const float *src = gate == 0 ? net.bias_r : gate == 1 ? net.bias_z : net.bias_in;
-                gb[i] = src[j];
-            }
+        GruWave<H, P> gru;
+        gru.load(net, w, lane, q4);
+        if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int s = 0; s <= count; ++s) {
             if (s < count) {
@@ -145,82 +130,11 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 #pragma unroll
                     for (int r = 0; r < 4; ++r) hv[j][r] = keep ? t[r] : 0.0f;
                 }
-                uint32_t lane_off = lane * 16, lane_off_hi = lane * 16 + 65536;
-                asm volatile("" : "+v"(lane_off), "+v"(lane_off_hi));
-                const char *wih_lane = lds + Sh::oWih + lane_off, *wih_lane_hi = lds + Sh::oWih + lane_off_hi;
-                WFrag<P> wi[2][3][NBC];
-                auto request = [&](int ks) {
+                gru.step(lds, w, lane, q4, hin_lds[cur], x_lds[cur], hv);
 #pragma unroll
-                    for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-                        for (int j = 0; j < NBC; ++j) {
-                            const int off = ((gate * FBK + NBC * w + j) * KS + ks) * Sh::kFrag;
-                            wi[ks % 2][gate][j] = load_wfrag<P>(reinterpret_cast<const bf16x8 *>(
-                                off + Sh::kFrag <= 65536 ? wih_lane + off : wih_lane_hi + (off - 65536)));
-                        }
-                };
-                Frag<P> hb[KS], x[KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    hb[ks].hi = hin_lds[cur][ks][0][lane];
-                    if constexpr (P == 2) hb[ks].lo = hin_lds[cur][ks][1][lane];
-                }
-                f32x4 acc_r[NBC], acc_z[NBC], acc_in[NBC], acc_hn[NBC];
-#pragma unroll
-                for (int j = 0; j < NBC; ++j) {
-                    acc_r[j] = load_feature4(gb, 0 * FBK + NBC * w + j, q4);
-                    acc_z[j] = load_feature4(gb, 1 * FBK + NBC * w + j, q4);
-                    acc_in[j] = load_feature4(gb, 2 * FBK + NBC * w + j, q4);
-                    acc_hn[j] = bias_hn[j];
-                }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    x[ks].hi = x_lds[cur][ks][0][lane];
-                    if constexpr (P == 2) x[ks].lo = x_lds[cur][ks][1][lane];
-                }
-                request(0);
-                request(1);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                    for (int j = 0; j < NBC; ++j) {
-                        mma16<P>(acc_r[j], whh[0][j][ks], hb[ks]);
-                        mma16<P>(acc_z[j], whh[1][j][ks], hb[ks]);
-                        mma16<P>(acc_hn[j], whh[2][j][ks], hb[ks]);
-                    }
-#pragma unroll
-                    for (int j = 0; j < NBC; ++j) {
-                        mma16<P>(acc_r[j], wi[ks % 2][0][j], x[ks]);
-                        mma16<P>(acc_z[j], wi[ks % 2][1][j], x[ks]);
-                        mma16<P>(acc_in[j], wi[ks % 2][2][j], x[ks]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (ks + 2 < KS) request(ks + 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int j = 0; j < NBC; ++j) {
-                    hv[j] = gru_blend4(acc_r[j], acc_z[j], acc_in[j], acc_hn[j], hv[j]);
+                for (int j = 0; j < NBC; ++j)
                     if (valid) *reinterpret_cast<f32x4 *>(args.h_out + (size_t)row * H + 16 * (NBC * w + j) + 4 * q4) = hv[j];
-                }
-                // the new state as operand for fc2 (two adjacent feature blocks make one k-step)
-                if constexpr (NBC == 2) {
-                    const Frag<P> f = frag_of_pair<P>(hv[0], hv[1]);
-                    h_lds[cur][w][0][lane] = f.hi;
-                    if constexpr (P == 2) h_lds[cur][w][1][lane] = f.lo;
-                } else {
-                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                    bf16x4 hi, lo;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        hi[r] = (__bf16)hv[0][r];
-                        lo[r] = (__bf16)(hv[0][r] - (float)hi[r]);
-                    }
-                    char *dst = reinterpret_cast<char *>(&h_lds[cur][w / 2][0][lane]) + (w & 1) * 8;
-                    *reinterpret_cast<bf16x4 *>(dst) = hi;
-                    if constexpr (P == 2) *reinterpret_cast<bf16x4 *>(dst + 1024) = lo;
-                }
+                GruWave<H, P>::publish(h_lds[cur], w, lane, hv);         // operand of fc2
             }
             lds_barrier();
         }
@@ -279,58 +193,26 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         }
     } else if (wave == Sh::kLoader) {
         // ---------------------------------------------------------------- loader wave
-        // Observations: this lane's row, floats 32 ks + 8 q + 0..7 of k-step ks (the B operand's
-        // k order).  Every k-step but the last lies wholly inside the row and is fetched as two
-        // 16-byte loads (only 4-byte alignment is assumed).  The last k-step, which may be partial,
-        // is fetched element by element from positions clamped into the row; the weights are
-        // zero where the clamp changes a position.
         // Hidden state: the operand of k-step ks wants features 32 ks + 16 (idx / 4) + 4 q + idx % 4,
         // i.e. two aligned groups of four floats.
-        constexpr int KM = Sh::kKs1Max;
-        const int nfull = ks1 - 1;
-        int last_off[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) last_off[i] = min(32 * nfull + 8 * q4 + i, D - 1) - 8 * q4;
-        float stage[KM - 1 > 0 ? KM - 1 : 1][8], last[8], hstage[KS][8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) last[i] = 0.0f;
+        ObsStage<H, P> st;
+        st.init(D, ks1, q4);
+        float hstage[KS][8];
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
             for (int i = 0; i < 8; ++i) hstage[ks][i] = 0.0f;
-        auto put = [&](bf16x8 *at, const float (&v)[8]) {
-            const Frag<P> f = to_frag<P>(v);
-            at[0] = f.hi;
-            if constexpr (P == 2) at[64] = f.lo;
-        };
         for (int s = -LEAD; s <= count; ++s) {
             const int ws = s + 2, ls = s + 3;        // observations: item written / loaded in this step
             const int hw = s + 1, hl = s + 2;        // hidden state: one item closer to its use
-            if (ws >= 0 && ws < count) {
-                bf16x8 *dst = obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane;
-#pragma unroll
-                for (int k = 0; k < KM - 1; ++k)
-                    if (k < nfull) put(dst + (k * P) * 64, stage[k]);
-                put(dst + (nfull * P) * 64, last);
-            }
+            if (ws >= 0 && ws < count) st.write(obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);
             if (hw >= 0 && hw < count) {
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) put(&hin_lds[hw & 1][ks][0][lane], hstage[ks]);
+                for (int ks = 0; ks < KS; ++ks) ObsStage<H, P>::put(&hin_lds[hw & 1][ks][0][lane], hstage[ks]);
             }
             if (ls >= 0 && ls < count) {
                 const int row = item_row(ls);
-                const float *r = args.obs + (size_t)(row < rows ? row : 0) * D + 8 * q4;
-#pragma unroll
-                for (int k = 0; k < KM - 1; ++k)
-                    if (k < nfull) {
-                        f32x4 lo4, hi4;
-                        __builtin_memcpy(&lo4, r + 32 * k, 16);
-                        __builtin_memcpy(&hi4, r + 32 * k + 4, 16);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) { stage[k][i] = lo4[i]; stage[k][4 + i] = hi4[i]; }
-                    }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) last[i] = r[last_off[i]];
+                st.load(args.obs + (size_t)(row < rows ? row : 0) * D + 8 * q4);
             }
             if (hl >= 0 && hl < count) {
                 const int row = item_row(hl);
@@ -352,72 +234,26 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         }
     } else {
         // ---------------------------------------------------------------- fc1 wave
-        constexpr int NBF = Sh::NBF, KM = Sh::kKs1Max;
         const int f = wave - Sh::kFc1;
-        WFrag<P> w1[NBF][KM];
-#pragma unroll
-        for (int j = 0; j < NBF; ++j)
-#pragma unroll
-            for (int ks = 0; ks < KM; ++ks)
-                if (ks < ks1) w1[j][ks] = load_wfrag<P>(net.w1_16 + ((size_t)((f * NBF + j) * ks1 + ks) * P) * 64 + lane);
-        auto obs_frag = [&](int item, int ks) {
-            const bf16x8 *src = obuf + (size_t)(((item & 1) * ks1 + ks) * P) * 64 + lane;
-            Frag<P> fr;
-            fr.hi = src[0];
-            if constexpr (P == 2) fr.lo = src[64];
-            return fr;
-        };
-        // Touching ahead: one 4-byte load per 128 bytes of the observation and hidden-state rows
-        // of a later item (see unroll_fused.hip).
-        constexpr int kTouchAhead = 4, TLO = (KM * 32 + 127) / 128, TL = TLO + 1;
-        int touch_off[TLO];
-#pragma unroll
-        for (int j = 0; j < TLO; ++j) touch_off[j] = min(32 * (4 * j + q4), D - 1);
+        Fc1Wave<H, P> fc1;
+        fc1.load(net, f, ks1, lane);
+        ObsTouch<H, P, 1> tch;                       // one more value per set: the hidden-state row
+        tch.init(D, q4);
         const int touch_off_h = min(32 * q4, H - 1);
-        uint32_t touched[kTouchAhead][TL] = {};
-        auto touch = [&](uint32_t (&set)[TL], int s) {
+        auto touch = [&](int c, int s) {             // the item the loader will load kTouchAhead steps from now
             const int row = item_row(s + 3 + kTouchAhead);
             const size_t rr = row < rows ? row : 0;
-            const float *r = args.obs + rr * D;
-#pragma unroll
-            for (int j = 0; j < TL; ++j) asm volatile("" ::"v"(set[j]));
-#pragma unroll
-            for (int j = 0; j < TLO; ++j) set[j] = __builtin_bit_cast(uint32_t, r[touch_off[j]]);
-            set[TLO] = __builtin_bit_cast(uint32_t, args.h_in[rr * H + touch_off_h]);
+            tch.consume(c);
+            tch.touch(c, args.obs + rr * D);
+            tch.set[c][tch.TLO] = __builtin_bit_cast(uint32_t, args.h_in[rr * H + touch_off_h]);
         };
         auto fc1_step = [&](int s) {
             const int item = s + 1;
             if (item >= 0 && item < count) {
                 const int row = item_row(item);
-                const int n = (row < rows ? row : 0) % N;
-                f32x4 b1v[NBF];
-#pragma unroll
-                for (int j = 0; j < NBF; ++j) b1v[j] = load_feature4(net.bias1 + (size_t)n * H, f * NBF + j, q4);
-                f32x4 acc[NBF];
-#pragma unroll
-                for (int j = 0; j < NBF; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[j][r] = 0.0f;
-                Frag<P> bq[3];
-                bq[0] = obs_frag(item, 0);
-                bq[1] = obs_frag(item, min(1, ks1 - 1));
-#pragma unroll
-                for (int ks = 0; ks < KM; ++ks)
-                    if (ks < ks1) {
-                        bq[(ks + 2) % 3] = obs_frag(item, min(ks + 2, ks1 - 1));
-#pragma unroll
-                        for (int j = 0; j < NBF; ++j) mma16<P>(acc[j], w1[j][ks], bq[ks % 3]);
-                    }
-#pragma unroll
-                for (int j = 0; j < NBF; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[j][r] = fmaxf(acc[j][r] + b1v[j][r], 0.0f);
-#pragma unroll
-                for (int jj = 0; jj < NBF / 2; ++jj) {
-                    const Frag<P> fr = frag_of_pair<P>(acc[2 * jj], acc[2 * jj + 1]);
-                    x_lds[item & 1][f * (NBF / 2) + jj][0][lane] = fr.hi;
-                    if constexpr (P == 2) x_lds[item & 1][f * (NBF / 2) + jj][1][lane] = fr.lo;
-                }
+                f32x4 b1v[Sh::NBF];
+                Fc1Wave<H, P>::load_bias(net, f, (row < rows ? row : 0) % N, q4, b1v);
+                fc1.step(obuf + (size_t)((item & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[item & 1]);
             }
             lds_barrier();
         };
@@ -425,10 +261,10 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         if (f == 0) {
             static_assert(kTouchAhead == 4, "the loop is unrolled over the register sets");
             for (; s + 3 <= count; s += 4) {
-                touch(touched[0], s);     fc1_step(s);
-                touch(touched[1], s + 1); fc1_step(s + 1);
-                touch(touched[2], s + 2); fc1_step(s + 2);
-                touch(touched[3], s + 3); fc1_step(s + 3);
+                touch(0, s);     fc1_step(s);
+                touch(1, s + 1); fc1_step(s + 1);
+                touch(2, s + 2); fc1_step(s + 2);
+                touch(3, s + 3); fc1_step(s + 3);
             }
         }
         for (; s <= count; ++s) fc1_step(s);

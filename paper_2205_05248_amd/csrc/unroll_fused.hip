@@ -32,7 +32,7 @@
 // step s was last read in step s-1 and is first read in step s+1.
 #include <hip/hip_runtime.h>
 
-#include "fused16.h"
+#include "fused16_roles.h"
 
 namespace marl {
 
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     bf16x8 *const wih_lds = reinterpret_cast<bf16x8 *>(lds + Sh::oWih);     // [((blk KS + ks) P + p)][64]
 
     const bool is_target = blockIdx.y == 1;
-    const NetFrags &net = is_target ? target : online;
+    const NetFrags net = is_target ? target : online;     // by value: uniform, lives in scalar registers
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int rt = blockIdx.x;
@@ -73,119 +73,22 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 
     if (wave < Sh::NC) {
         // ---------------------------------------------------------------- compute wave
-        // feature blocks NBC w .. NBC w + NBC - 1 of the hidden state, all three gates
-        constexpr int NBC = Sh::NBC;
         const int w = wave;
-        WFrag<P> whh[3][NBC][KS];
+        GruWave<H, P> gru;
+        gru.load(net, w, lane, q4);
+        if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
+        f32x4 hv[Sh::NBC];                           // this wave's units of the hidden state, fp32
 #pragma unroll
-        for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-            for (int j = 0; j < NBC; ++j)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + NBC * w + j) * KS + ks) * P) * 64 + lane);
-        f32x4 bias_hn[NBC], hv[NBC];
-#pragma unroll
-        for (int j = 0; j < NBC; ++j) {
-            bias_hn[j] = load_feature4(net.bias_hn, NBC * w + j, q4);
+        for (int j = 0; j < Sh::NBC; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[j][r] = 0.0f;
-        }
-        float *const gb = reinterpret_cast<float *>(lds + Sh::oGBias);
-        if (w == 0)
-            for (int i = lane; i < 3 * H; i += 64) {
-                const int gate = i / H, j = i % H;   // = feature 16 (gate FBK + j / 16) + j % 16 of the stacked gates
-                const float *src = gate == 0 ? net.bias_r : gate == 1 ? net.bias_z : net.bias_in;
-                gb[i] = src[j];
-            }
-        // The hidden state as next operand: two adjacent feature blocks make one k-step.  A wave
-        // with two blocks writes a whole fragment, a wave with one block its half of every lane's
-        // 16 bytes.
-        auto publish = [&](int buf) {
-            if constexpr (NBC == 2) {
-                const Frag<P> f = frag_of_pair<P>(hv[0], hv[1]);
-                h_lds[buf][w][0][lane] = f.hi;
-                if constexpr (P == 2) h_lds[buf][w][1][lane] = f.lo;
-            } else {
-                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-                bf16x4 hi, lo;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    hi[r] = (__bf16)hv[0][r];
-                    lo[r] = (__bf16)(hv[0][r] - (float)hi[r]);
-                }
-                char *dst = reinterpret_cast<char *>(&h_lds[buf][w / 2][0][lane]) + (w & 1) * 8;
-                *reinterpret_cast<bf16x4 *>(dst) = hi;
-                if constexpr (P == 2) *reinterpret_cast<bf16x4 *>(dst + 1024) = lo;
-            }
-        };
-        publish(0);
+        GruWave<H, P>::publish(h_lds[0], w, lane, hv);
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it <= T) {
                 const int cur = it & 1;
-                // The per-lane offsets are made opaque once per slot: otherwise the compiler
-                // precomputes one address register per fragment and keeps them across the loop.
-                // Two bases because an LDS access encodes at most 64 KB of constant offset.
-                uint32_t lane_off = lane * 16, lane_off_hi = lane * 16 + 65536;
-                asm volatile("" : "+v"(lane_off), "+v"(lane_off_hi));
-                const char *wih_lane = lds + Sh::oWih + lane_off, *wih_lane_hi = lds + Sh::oWih + lane_off_hi;
-                WFrag<P> wi[2][3][NBC];              // W_ih fragments of two k-steps in rotation
-                auto request = [&](int ks) {
-#pragma unroll
-                    for (int gate = 0; gate < 3; ++gate)
-#pragma unroll
-                        for (int j = 0; j < NBC; ++j) {
-                            const int off = ((gate * FBK + NBC * w + j) * KS + ks) * Sh::kFrag;
-                            wi[ks % 2][gate][j] = load_wfrag<P>(reinterpret_cast<const bf16x8 *>(
-                                off + Sh::kFrag <= 65536 ? wih_lane + off : wih_lane_hi + (off - 65536)));
-                        }
-                };
-                Frag<P> hb[KS], x[KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    hb[ks].hi = h_lds[cur][ks][0][lane];
-                    if constexpr (P == 2) hb[ks].lo = h_lds[cur][ks][1][lane];
-                }
-                f32x4 acc_r[NBC], acc_z[NBC], acc_in[NBC], acc_hn[NBC];
-#pragma unroll
-                for (int j = 0; j < NBC; ++j) {
-                    acc_r[j] = load_feature4(gb, 0 * FBK + NBC * w + j, q4);
-                    acc_z[j] = load_feature4(gb, 1 * FBK + NBC * w + j, q4);
-                    acc_in[j] = load_feature4(gb, 2 * FBK + NBC * w + j, q4);
-                    acc_hn[j] = bias_hn[j];
-                }
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    x[ks].hi = x_lds[cur][ks][0][lane];
-                    if constexpr (P == 2) x[ks].lo = x_lds[cur][ks][1][lane];
-                }
-                request(0);
-                request(1);
-                __builtin_amdgcn_sched_barrier(0);
-                // per k-step: the hidden product from registers, then the input product whose
-                // fragments were requested two k-steps earlier
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                    for (int j = 0; j < NBC; ++j) {
-                        mma16<P>(acc_r[j], whh[0][j][ks], hb[ks]);
-                        mma16<P>(acc_z[j], whh[1][j][ks], hb[ks]);
-                        mma16<P>(acc_hn[j], whh[2][j][ks], hb[ks]);
-                    }
-#pragma unroll
-                    for (int j = 0; j < NBC; ++j) {
-                        mma16<P>(acc_r[j], wi[ks % 2][0][j], x[ks]);
-                        mma16<P>(acc_z[j], wi[ks % 2][1][j], x[ks]);
-                        mma16<P>(acc_in[j], wi[ks % 2][2][j], x[ks]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (ks + 2 < KS) request(ks + 2);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int j = 0; j < NBC; ++j) hv[j] = gru_blend4(acc_r[j], acc_z[j], acc_in[j], acc_hn[j], hv[j]);
-                publish(cur ^ 1);
+                gru.step(lds, w, lane, q4, h_lds[cur], x_lds[cur], hv);
+                GruWave<H, P>::publish(h_lds[cur ^ 1], w, lane, hv);
             }
             lds_barrier();
         }
@@ -265,131 +168,44 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         }
     } else if (wave == Sh::kLoader) {
         // ---------------------------------------------------------------- loader wave
-        // Observations: this lane's row, floats 32 ks + 8 q + 0..7 of k-step ks (the B operand's
-        // k order).  Every k-step but the last lies wholly inside the row and is fetched as two
-        // 16-byte loads at constant offsets from one address (only 4-byte alignment is assumed).
-        // The last k-step, which may be partial, is fetched element by element from positions
-        // clamped into the row; the weights are zero where the clamp changes a position.
-        constexpr int KM = Sh::kKs1Max;
-        const float *base = obs + ((size_t)b * S * N + n) * D + 8 * q4;      // slot 0
+        const float *base = obs + ((size_t)b * S * N + n) * D + 8 * q4;      // the lane's row at slot 0
         const size_t slot_stride = (size_t)N * D;
-        const int nfull = ks1 - 1;                   // k-steps handled by the vector path
-        int last_off[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) last_off[i] = min(32 * nfull + 8 * q4 + i, D - 1) - 8 * q4;
-        float stage[KM - 1 > 0 ? KM - 1 : 1][8], last[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) last[i] = 0.0f;
-
+        ObsStage<H, P> st;
+        st.init(D, ks1, q4);
         for (int s = -LEAD; s <= T + 1; ++s) {
             const int ws = s + 2, ls = s + 3;
-            if (ws >= 0 && ws <= T) {                // observations of slot ws: registers -> LDS
-                bf16x8 *dst = obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane;
-                auto put = [&](bf16x8 *at, const float (&v)[8]) {
-                    const Frag<P> f = to_frag<P>(v);
-                    at[0] = f.hi;
-                    if constexpr (P == 2) at[64] = f.lo;
-                };
-#pragma unroll
-                for (int k = 0; k < KM - 1; ++k)
-                    if (k < nfull) put(dst + (k * P) * 64, stage[k]);
-                put(dst + (nfull * P) * 64, last);
-            }
-            if (ls >= 0 && ls <= T) {                // observations of slot ls: issue the loads
-                const float *r = base + (size_t)ls * slot_stride;
-#pragma unroll
-                for (int k = 0; k < KM - 1; ++k)
-                    if (k < nfull) {
-                        f32x4 lo4, hi4;
-                        __builtin_memcpy(&lo4, r + 32 * k, 16);
-                        __builtin_memcpy(&hi4, r + 32 * k + 4, 16);
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) { stage[k][i] = lo4[i]; stage[k][4 + i] = hi4[i]; }
-                    }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) last[i] = r[last_off[i]];
-            }
+            if (ws >= 0 && ws <= T) st.write(obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
+            if (ls >= 0 && ls <= T) st.load(base + (size_t)ls * slot_stride);                      // issue the loads
             lds_barrier();
         }
     } else {
         // ---------------------------------------------------------------- fc1 wave
-        constexpr int NBF = Sh::NBF, KM = Sh::kKs1Max;
-        const int f = wave - Sh::kFc1;               // owns feature blocks f NBF .. f NBF + NBF - 1 = k-steps f NBF/2 ..
-        WFrag<P> w1[NBF][KM];
-#pragma unroll
-        for (int j = 0; j < NBF; ++j)
-#pragma unroll
-            for (int ks = 0; ks < KM; ++ks)
-                if (ks < ks1) w1[j][ks] = load_wfrag<P>(net.w1_16 + ((size_t)((f * NBF + j) * ks1 + ks) * P) * 64 + lane);
-        f32x4 b1v[NBF];
-#pragma unroll
-        for (int j = 0; j < NBF; ++j) b1v[j] = load_feature4(net.bias1 + (size_t)n * H, f * NBF + j, q4);
-        auto obs_frag = [&](int slot, int ks) {
-            const bf16x8 *src = obuf + (size_t)(((slot & 1) * ks1 + ks) * P) * 64 + lane;
-            Frag<P> fr;
-            fr.hi = src[0];
-            if constexpr (P == 2) fr.lo = src[64];
-            return fr;
-        };
-        // The first fc1 wave also pulls the observations of a later slot into L2 (one 4-byte load
-        // per 128 bytes of every row, values unused), kTouchAhead steps before the gates wave loads
-        // them for real: a first touch from HBM takes longer than one step, an L2 hit does not.
-        constexpr int kTouchAhead = 4, TL = (KM * 32 + 127) / 128;          // loads per lane: the lane's lines q, q + 4, ...
+        const int f = wave - Sh::kFc1;
+        Fc1Wave<H, P> fc1;
+        fc1.load(net, f, ks1, lane);
+        f32x4 b1v[Sh::NBF];
+        Fc1Wave<H, P>::load_bias(net, f, n, q4, b1v);
         const float *touch_row = obs + ((size_t)b * S * N + n) * D;
-        int touch_off[TL];
-#pragma unroll
-        for (int j = 0; j < TL; ++j) touch_off[j] = min(32 * (4 * j + q4), D - 1);
-        uint32_t touched[kTouchAhead][TL] = {};
-        // Register set c: what it fetched kTouchAhead steps ago must have arrived (the empty asm
-        // consumes it) before it is loaded again.  The sets never move and the loop below is
-        // unrolled over them, so no wait covers a load younger than kTouchAhead - 1 steps.
-        auto touch = [&](uint32_t (&set)[TL], int s) {
-            const float *r = touch_row + (size_t)min(max(s + 3 + kTouchAhead, 0), T) * N * D;   // ends: touched twice
-#pragma unroll
-            for (int j = 0; j < TL; ++j) asm volatile("" ::"v"(set[j]));
-#pragma unroll
-            for (int j = 0; j < TL; ++j) set[j] = __builtin_bit_cast(uint32_t, r[touch_off[j]]);
+        ObsTouch<H, P, 0> tch;
+        tch.init(D, q4);
+        auto touch = [&](int c, int s) {             // the slot the loader will load kTouchAhead steps from now
+            tch.consume(c);
+            tch.touch(c, touch_row + (size_t)min(max(s + 3 + kTouchAhead, 0), T) * N * D);   // ends: touched twice
         };
         auto fc1_step = [&](int s) {
             const int slot = s + 1;
-            if (slot >= 0 && slot <= T) {
-                f32x4 acc[NBF];
-#pragma unroll
-                for (int j = 0; j < NBF; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[j][r] = 0.0f;
-                // observation fragments are read two k-steps ahead of their MFMAs (LDS latency)
-                Frag<P> bq[3];
-                bq[0] = obs_frag(slot, 0);
-                bq[1] = obs_frag(slot, min(1, ks1 - 1));
-#pragma unroll
-                for (int ks = 0; ks < KM; ++ks)
-                    if (ks < ks1) {
-                        bq[(ks + 2) % 3] = obs_frag(slot, min(ks + 2, ks1 - 1));
-#pragma unroll
-                        for (int j = 0; j < NBF; ++j) mma16<P>(acc[j], w1[j][ks], bq[ks % 3]);
-                    }
-#pragma unroll
-                for (int j = 0; j < NBF; ++j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[j][r] = fmaxf(acc[j][r] + b1v[j][r], 0.0f);
-#pragma unroll
-                for (int jj = 0; jj < NBF / 2; ++jj) {
-                    const Frag<P> fr = frag_of_pair<P>(acc[2 * jj], acc[2 * jj + 1]);
-                    x_lds[slot & 1][f * (NBF / 2) + jj][0][lane] = fr.hi;
-                    if constexpr (P == 2) x_lds[slot & 1][f * (NBF / 2) + jj][1][lane] = fr.lo;
-                }
-            }
+            if (slot >= 0 && slot <= T)
+                fc1.step(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1]);
             lds_barrier();
         };
         int s = -LEAD;
         if (f == 0) {
             static_assert(kTouchAhead == 4, "the loop is unrolled over the register sets");
             for (; s + 3 <= T + 1; s += 4) {
-                touch(touched[0], s);     fc1_step(s);
-                touch(touched[1], s + 1); fc1_step(s + 1);
-                touch(touched[2], s + 2); fc1_step(s + 2);
-                touch(touched[3], s + 3); fc1_step(s + 3);
+                touch(0, s);     fc1_step(s);
+                touch(1, s + 1); fc1_step(s + 1);
+                touch(2, s + 2); fc1_step(s + 2);
+                touch(3, s + 3); fc1_step(s + 3);
             }
         }
         for (; s <= T + 1; ++s) fc1_step(s);
