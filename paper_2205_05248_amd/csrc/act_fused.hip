@@ -284,8 +284,7 @@ hipError_t act_dispatch(const ActFusedArgs &a, hipStream_t stream)
 #define MARL_ACTF(ABLK)                                                                                             \
     do {                                                                                                            \
         auto kernel = act_fused_kernel<H, P, ABLK>;                                                                 \
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),                               \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
+        hipError_t err = allow_large_lds<act_fused_kernel<H, P, ABLK>>(kLdsLimit);                                  \
         if (err != hipSuccess) return err;                                                                          \
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, a);                                                    \
     } while (0)

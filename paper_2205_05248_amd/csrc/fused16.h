@@ -2,10 +2,28 @@
 // act_fused.hip): which wavefront plays which role, what stays resident where, and the byte
 // offsets of the LDS buffers.
 #pragma once
+#include <atomic>
+
 #include "mfma16_tile.h"
 #include "unroll_common.h"
 
 namespace marl {
+
+// Host: the runtime has to be told, once per kernel and device, that launches of it may ask for
+// more than 64 KB of dynamic LDS.  The current device is the one the launch will go to.
+template <auto Kernel>
+hipError_t allow_large_lds(int bytes)
+{
+    static std::atomic<uint64_t> done{0};            // one bit per device id
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    const uint64_t bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+    err = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+    return err;
+}
 
 constexpr int kFusedLead = 3;         // steps before slot 0 enters the recurrence
 constexpr int kLdsLimit = 160 * 1024;

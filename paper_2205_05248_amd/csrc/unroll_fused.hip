@@ -230,8 +230,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
 #define MARL_FUSED(ABLK, QA)                                                                                        \
     do {                                                                                                            \
         auto kernel = unroll_fused_kernel<H, P, ABLK, QA>;                                                          \
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),                               \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
+        hipError_t err = allow_large_lds<unroll_fused_kernel<H, P, ABLK, QA>>(kLdsLimit);                           \
         if (err != hipSuccess) return err;                                                                          \
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, obs, avail, actions,        \
                            reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);                 \
