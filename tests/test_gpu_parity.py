@@ -349,3 +349,37 @@ def test_set_weights_is_ordered_on_the_stream(ci):
     with pytest.raises(binding.MarlError):
         net.set_weights(w0[:-1])
     net.close()
+
+
+# ------------------------------------------------------------------ shapes at the edges of the supported range
+ODD_SHAPES = [
+    # N, D, A, H, dtype
+    (1, 1, 1, 64, "fp32"),          # one agent, one observation value, one action
+    (2, 7, 3, 64, "fp32"),          # fewer than four actions (byte-wise availability path)
+    (3, 31, 4, 64, "bf16"),
+    (5, 32, 17, 64, "fp32"),        # exactly one full k-step; two action blocks, ragged
+    (7, 33, 33, 128, "bf16"),       # one value past a k-step; three action blocks
+    (64, 64, 64, 128, "bf16"),      # the maxima of N and A
+    (4, 97, 48, 64, "bf16"),
+    (6, 160, 16, 64, "fp32"),       # the largest obs_dim the fused fp32 kernels take
+    (9, 320, 40, 128, "bf16"),      # the largest obs_dim the fused bf16 kernels take
+]
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("shape", ODD_SHAPES, ids=lambda s: "N%d_D%d_A%d_H%d_%s" % s)
+def test_odd_shapes(shape, path):
+    N, D, A, H, dtype = shape
+    cfg = dict(wl.config(0), N=N, D=D, A=A, H=H, dtype=dtype, E=11, B=5, T=6)
+    tol = pu.TOL[dtype]
+    net, w = make_net(cfg, kernels=path)
+    target, w_tg = make_net(cfg, 1)
+    for eps in (0.0, 1.0):
+        inp = wl.make_act_inputs(cfg, stream=3)
+        inp["epsilon"] = eps
+        got = pu.gpu_act(net, cfg, inp)
+        pu.compare_act(cfg, inp, got, oracle_act(cfg, w, inp), tol)
+        assert np.take_along_axis(inp["avail"], got["action"][..., None].astype(np.int64), -1).all()
+    u = wl.make_unroll_inputs(cfg)
+    pu.compare_unroll(pu.gpu_unroll(net, target, cfg, u), oracle_unroll(cfg, w, w_tg, u), tol)
+    net.close(); target.close()
