@@ -179,12 +179,13 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
  * Two families compute the same functions:
  *   fused16  tiles of 16 rows, every weight resident on chip, one kernel per call; serves the
  *            networks that fit its on-chip buffers (bf16 weights: obs_dim <= 320; fp32 weights:
- *            hidden = 64 and obs_dim <= 160)
+ *            hidden = 64 and obs_dim <= 160; for marl_act_step also n_actions >= 4)
  *   tile32   tiles of 32 rows, weights streamed; the unroll is two kernels with a scratch buffer
  *            between them; serves every network
- *   MARL_KERNELS_AUTO     fused16 when the network fits it, else tile32 (the default)
+ *   MARL_KERNELS_AUTO     per entry point, fused16 when the network fits it, else tile32 (the default)
  *   MARL_KERNELS_TILE32   always tile32
- *   MARL_KERNELS_FUSED16  always fused16; MARL_ERR_BAD_DIM if the network does not fit it
+ *   MARL_KERNELS_FUSED16  always fused16; MARL_ERR_BAD_DIM if the network does not fit it for both
+ *                         entry points
  * Returns MARL_ERR_BAD_ARG for any other value.
  */
 #define MARL_KERNELS_AUTO 0

@@ -6,18 +6,25 @@
 // over the slots of an episode: a workgroup owns a run of consecutive tiles, and in the step in
 // which the GRU handles item k (the k-th tile of the run)
 //
-//   loader wave    writes the observations of item k+2 and the incoming hidden state of item k+1
-//                  (both loaded during the previous step) to LDS as bf16 operand fragments, and
-//                  issues the loads of items k+3 / k+2;
-//   fc1 waves      x = ReLU(W1 o + b1[agent]) for item k+1; the first one also touches the
-//                  observations of a later item so that the loader's loads hit L2;
+//   loader wave    writes the observations of item k+2 to LDS as bf16 operand fragments and asks
+//                  for those of item k+4;
+//   fc1 waves      x = ReLU(W1 o + b1[agent]) for item k+1;
 //   compute waves  item k of the GRU: W_ih x + W_hh h + b for their hidden units, gates, new hidden
 //                  state to global memory (fp32) and to LDS (operand form);
-//   epilogue wave  item k-1: fc2, Q store, availability mask, argmax, epsilon-greedy, action store.
+//   epilogue wave  item k-1: fc2, Q store, availability mask, argmax, epsilon-greedy, action store;
+//                  it also feeds the incoming hidden state: item k+1 goes to LDS (operand
+//                  fragments for the product, fp32 for the blend), item k+3 is asked for.
 //
-// Nothing depends on the previous item, so the steps are pure throughput; the per-launch cost of
-// loading the weights (once per workgroup) is amortised over the run of tiles.
+// Every input is read once from HBM and nothing of it is reused, so the whole job is hiding the
+// latency of a first touch (a few microseconds under load, longer than a step): each wave that
+// reads global memory keeps two items in flight in two register sets, indexed by the parity of the
+// item, with the step loop unrolled twice so that the sets never move and a wait covers only the
+// loads issued two steps earlier.  The first two items are asked for before the weights are
+// loaded.  Nothing depends on the previous item, so the steps are pure throughput; the per-launch
+// cost of loading the weights (once per workgroup) is amortised over the run of tiles.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "fused16_roles.h"
 
@@ -76,19 +83,25 @@ __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)
     return ((uint64_t)hi << 32) | lo;
 }
 
+constexpr int kActLead = 2;          // steps before item 0 enters the GRU
+constexpr int kRawBuffer = 0x00020000;       // descriptor word 3: untyped 32-bit data, no swizzle, offsets checked against the size
+
 template <int H, int P, int AB>
 __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const ActFusedArgs args)
 {
     using Sh = Fused16<H, P>;
-    constexpr int FBK = Sh::FBK, KS = Sh::KS, LEAD = kFusedLead;
+    constexpr int FBK = Sh::FBK, KS = Sh::KS, LEAD = kActLead;
+    static_assert(LEAD % 2 == 0, "register sets are indexed by the parity of the step");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     typedef bf16x8 (*FragBuf)[KS][P][64];
+    typedef f32x4 (*StateBuf)[FBK][64];
     const NetFrags &net = args.net;
     const int N = net.N, D = net.D, A = net.A;
     const int ks1 = (D + 31) / 32;
     const FragBuf h_lds = reinterpret_cast<FragBuf>(lds + Sh::oH);                   // new hidden state, compute -> epilogue
     const FragBuf x_lds = reinterpret_cast<FragBuf>(lds + Sh::oX);
-    const FragBuf hin_lds = reinterpret_cast<FragBuf>(lds + Sh::hin_offset(ks1));    // old hidden state, loader -> compute
+    const FragBuf hin_lds = reinterpret_cast<FragBuf>(lds + Sh::hin_offset(ks1));    // old hidden state as operand
+    const StateBuf hf_lds = reinterpret_cast<StateBuf>(lds + Sh::hf_offset(ks1));    // old hidden state in fp32, by feature block
     bf16x8 *const obuf = reinterpret_cast<bf16x8 *>(lds + Sh::oObs);
     bf16x8 *const wih_lds = reinterpret_cast<bf16x8 *>(lds + Sh::oWih);
 
@@ -98,38 +111,36 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
     const int tiles = (rows + 15) / 16;
     const int first = blockIdx.x * args.tiles_per_group;
     const int count = min(args.tiles_per_group, tiles - first);       // >= 1 by construction of the grid
-    // item k (0 <= k < count) is tile first + k; items past the run re-use its last tile (reads only)
+    // item k (0 <= k < count) is tile first + k; items past the run re-use its last tile (reads only),
+    // rows past the end row 0
     auto item_row = [&](int k) { return (first + min(max(k, 0), count - 1)) * 16 + c; };
+    auto read_row = [&](int k) { const int row = item_row(k); return row < rows ? row : 0; };
     // Steps run s = -LEAD .. count, one barrier at the end of each: LEAD + count + 1 barriers per wave.
+    // Step s = s0 + u of the unrolled loops has the parity of u.
 
-    {
+    auto stage_wih = [&]() {             // every wave's share of W_ih -> LDS
         constexpr int kVecs = 3 * FBK * KS * P * 64;
         for (int i = threadIdx.x; i < kVecs; i += fused_threads(H)) wih_lds[i] = net.wih_16[i];
-    }
+    };
 
     if (wave < Sh::NC) {
         // ---------------------------------------------------------------- compute wave
         constexpr int NBC = Sh::NBC;
         const int w = wave;
+        stage_wih();
         GruWave<H, P> gru;
         gru.load(net, w, lane, q4);
         if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
+        gru.settle_weights();
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int s = 0; s <= count; ++s) {
             if (s < count) {
                 const int cur = s & 1;
                 const int row = item_row(s);
                 const bool valid = row < rows;
-                const int rr = valid ? row : 0;
-                const bool keep = !(args.reset && args.reset[rr / N]);
-                // this wave's own units of the old state in fp32, for the blend
-                f32x4 hv[NBC];
+                f32x4 hv[NBC];           // this wave's own units of the old state in fp32, for the blend
 #pragma unroll
-                for (int j = 0; j < NBC; ++j) {
-                    const f32x4 t = *reinterpret_cast<const f32x4 *>(args.h_in + (size_t)rr * H + 16 * (NBC * w + j) + 4 * q4);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) hv[j][r] = keep ? t[r] : 0.0f;
-                }
+                for (int j = 0; j < NBC; ++j) hv[j] = hf_lds[cur][NBC * w + j][lane];
                 gru.step(lds, w, lane, q4, hin_lds[cur], x_lds[cur], hv);
 #pragma unroll
                 for (int j = 0; j < NBC; ++j)
@@ -140,6 +151,41 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         }
     } else if (wave == Sh::kEpilogue) {
         // ---------------------------------------------------------------- epilogue wave
+        // Its steps are straight-line code with the same memory operations in every step, so
+        // that a wait on a register set counts exactly the operations issued since and covers
+        // nothing younger: loads of items outside the run read clamped rows, stores of items
+        // outside the run (and of rows past the end, and of Q when it is not wanted) carry an
+        // offset outside their buffer descriptor and are dropped by the hardware.
+        struct ItemIn { uint32_t avail_raw[AB]; int step; };
+        // Hidden state: the operand of k-step ks wants features 32 ks + 16 (idx / 4) + 4 q + idx % 4,
+        // i.e. two aligned groups of four floats, which are also the lane's share of feature
+        // blocks 2 ks and 2 ks + 1.
+        struct StateIn { f32x4 a[KS], b[KS]; uint32_t flag; };
+        const bool has_reset = args.reset != nullptr;
+        // without reset flags the byte is read from step_t instead and ignored
+        const uint8_t *const flag_src = has_reset ? args.reset : reinterpret_cast<const uint8_t *>(args.step_t);
+        auto fetch_item = [&](int k) {
+            ItemIn in;
+            const int rr = read_row(k);
+            issue_avail_loads16<AB>(args.avail + (size_t)rr * A, A, q4, in.avail_raw);
+            in.step = args.step_t[rr / N];
+            return in;
+        };
+        auto fetch_state = [&](int k) {
+            StateIn st;
+            const int rr = read_row(k);
+            const float *r = args.h_in + (size_t)rr * H + 4 * q4;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                st.a[ks] = *reinterpret_cast<const f32x4 *>(r + 32 * ks);
+                st.b[ks] = *reinterpret_cast<const f32x4 *>(r + 32 * ks + 16);
+            }
+            st.flag = flag_src[rr / N];
+            return st;
+        };
+        ItemIn in[2] = {fetch_item(0), fetch_item(1)};
+        StateIn state[2] = {fetch_state(0), fetch_state(1)};
+        stage_wih();
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
         WFrag<P> w2[AB][KS];
 #pragma unroll
@@ -147,25 +193,24 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) w2[ab][ks] = load_wfrag<P>(net.w2_16 + ((size_t)(ab * KS + ks) * P) * 64 + lane);
         if (lane < 16 * AB) b2_lds[lane] = lane < A ? net.b2[lane] : 0.0f;
-        struct ItemIn { uint32_t avail_raw[AB]; int step; };
-        auto fetch_item = [&](int k) {          // inputs of item k, requested one step before they are used
-            ItemIn in{};
-            const int row = item_row(k);
-            const int rr = row < rows ? row : 0;
-            if (A >= 4) issue_avail_loads16<AB>(args.avail + (size_t)rr * A, A, q4, in.avail_raw);
-            in.step = args.step_t[rr / N];
-            return in;
-        };
-        ItemIn nxt = fetch_item(0);
-        for (int i = 0; i < LEAD; ++i) lds_barrier();
-        for (int s = 0; s <= count; ++s) {
-            if (s >= 1) {
+#pragma unroll
+        for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) settle(w2[ab][ks]);
+        // outputs of this workgroup's run of tiles, addressed by row within the run
+        const int run_rows = min(count * 16, rows - first * 16);
+        const __amdgpu_buffer_rsrc_t q_buf = __builtin_amdgcn_make_buffer_rsrc(
+            args.q_out + (size_t)first * 16 * A, 0, args.q_out ? run_rows * A * 4 : 0, kRawBuffer);
+        const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(args.action + (size_t)first * 16, 0, run_rows * 4, kRawBuffer);
+        constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
+        auto step = [&](auto set, int s) {
+            constexpr int p = 1 - decltype(set)::value;      // parity of items s - 1, s + 1, s + 3
+            {   // item s - 1: Q, mask, choice
                 const int k = s - 1, cur = k & 1;
-                const ItemIn in = nxt;
-                nxt = fetch_item(k + 1);
-                const int row = item_row(k);
-                const bool valid = row < rows;
-                const int rr = valid ? row : 0;
+                const int lr = k * 16 + c;                   // row within the run
+                uint32_t dead = k >= 0 ? 0u : kDrop;         // in a vector register: the step must not fork on it
+                asm volatile("" : "+v"(dead));
+                const int rr = read_row(k);
                 const int e = rr / N, n = rr % N;
                 f32x4 qv[AB];
 #pragma unroll
@@ -178,96 +223,90 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 #pragma unroll
                     for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb);
                 }
-                if (args.q_out && valid) store_q_row16<AB>(args.q_out + (size_t)row * A, qv, A, q4);
-                const uint32_t slots = A >= 4 ? avail_mask16<AB>(in.avail_raw, A, q4, valid)
-                                              : avail_mask_small16(args.avail + (size_t)rr * A, A, q4, valid);
+#pragma unroll
+                for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int a = 16 * ab + 4 * q4 + r;
+                        const float value = qv[ab][r];
+                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value), q_buf,
+                                                              (a < A ? (uint32_t)(lr * A + a) * 4u : kDrop) | dead, 0, 0);
+                    }
+                const uint32_t slots = avail_mask16<AB>(in[p].avail_raw, A, q4, true);
                 float best_q; int best;
                 masked_argmax16<AB>(qv, slots, q4, best_q, best);
                 const uint64_t bits = row_avail_bits16<AB>(slots, q4);
-                if (valid && q4 == 0) {
-                    if (best < 0) best = 0;
-                    args.action[row] = eps_greedy_pick(best, bits, args.epsilon, args.seed, (uint32_t)e, (uint32_t)n, (uint32_t)in.step);
-                }
+                const int pick = eps_greedy_pick(max(best, 0), bits, args.epsilon, args.seed, (uint32_t)e, (uint32_t)n, (uint32_t)in[p].step);
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, (q4 == 0 ? (uint32_t)lr * 4u : kDrop) | dead, 0, 0);
+                in[p] = fetch_item(s + 1);
             }
-            lds_barrier();
-        }
-    } else if (wave == Sh::kLoader) {
-        // ---------------------------------------------------------------- loader wave
-        // Hidden state: the operand of k-step ks wants features 32 ks + 16 (idx / 4) + 4 q + idx % 4,
-        // i.e. two aligned groups of four floats.
-        ObsStage<H, P> st;
-        st.init(D, ks1, q4);
-        float hstage[KS][8];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) hstage[ks][i] = 0.0f;
-        for (int s = -LEAD; s <= count; ++s) {
-            const int ws = s + 2, ls = s + 3;        // observations: item written / loaded in this step
-            const int hw = s + 1, hl = s + 2;        // hidden state: one item closer to its use
-            if (ws >= 0 && ws < count) st.write(obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);
-            if (hw >= 0 && hw < count) {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) ObsStage<H, P>::put(&hin_lds[hw & 1][ks][0][lane], hstage[ks]);
-            }
-            if (ls >= 0 && ls < count) {
-                const int row = item_row(ls);
-                st.load(args.obs + (size_t)(row < rows ? row : 0) * D + 8 * q4);
-            }
-            if (hl >= 0 && hl < count) {
-                const int row = item_row(hl);
-                const int rr = row < rows ? row : 0;
-                const bool keep = !(args.reset && args.reset[rr / N]);
-                const float *r = args.h_in + (size_t)rr * H + 4 * q4;
+            {   // incoming hidden state of item s + 1 -> LDS, that of item s + 3 asked for
+                const int nb = (s + 1) & 1;
+                const bool keep = !(has_reset && (state[p].flag & 0xFFu));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const f32x4 a = *reinterpret_cast<const f32x4 *>(r + 32 * ks);
-                    const f32x4 b = *reinterpret_cast<const f32x4 *>(r + 32 * ks + 16);
+                    f32x4 a = state[p].a[ks], b = state[p].b[ks];
+                    float v[8];
 #pragma unroll
                     for (int i = 0; i < 4; ++i) {
-                        hstage[ks][i] = keep ? a[i] : 0.0f;
-                        hstage[ks][4 + i] = keep ? b[i] : 0.0f;
+                        a[i] = keep ? a[i] : 0.0f;
+                        b[i] = keep ? b[i] : 0.0f;
+                        v[i] = a[i];
+                        v[4 + i] = b[i];
                     }
+                    ObsStage<H, P>::put(&hin_lds[nb][ks][0][lane], v);
+                    hf_lds[nb][2 * ks][lane] = a;
+                    hf_lds[nb][2 * ks + 1][lane] = b;
                 }
-            }
-            lds_barrier();
-        }
-    } else {
-        // ---------------------------------------------------------------- fc1 wave
-        const int f = wave - Sh::kFc1;
-        Fc1Wave<H, P> fc1;
-        fc1.load(net, f, ks1, lane);
-        ObsTouch<H, P, 1> tch;                       // one more value per set: the hidden-state row
-        tch.init(D, q4);
-        const int touch_off_h = min(32 * q4, H - 1);
-        auto touch = [&](int c, int s) {             // the item the loader will load kTouchAhead steps from now
-            const int row = item_row(s + 3 + kTouchAhead);
-            const size_t rr = row < rows ? row : 0;
-            tch.consume(c);
-            tch.touch(c, args.obs + rr * D);
-            tch.set[c][tch.TLO] = __builtin_bit_cast(uint32_t, args.h_in[rr * H + touch_off_h]);
-        };
-        auto fc1_step = [&](int s) {
-            const int item = s + 1;
-            if (item >= 0 && item < count) {
-                const int row = item_row(item);
-                f32x4 b1v[Sh::NBF];
-                Fc1Wave<H, P>::load_bias(net, f, (row < rows ? row : 0) % N, q4, b1v);
-                fc1.step(obuf + (size_t)((item & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[item & 1]);
+                state[p] = fetch_state(s + 3);
             }
             lds_barrier();
         };
         int s = -LEAD;
-        if (f == 0) {
-            static_assert(kTouchAhead == 4, "the loop is unrolled over the register sets");
-            for (; s + 3 <= count; s += 4) {
-                touch(0, s);     fc1_step(s);
-                touch(1, s + 1); fc1_step(s + 1);
-                touch(2, s + 2); fc1_step(s + 2);
-                touch(3, s + 3); fc1_step(s + 3);
-            }
+        for (; s + 1 <= count; s += 2) {
+            step(std::integral_constant<int, 0>{}, s);
+            step(std::integral_constant<int, 1>{}, s + 1);
         }
-        for (; s <= count; ++s) fc1_step(s);
+        if (s <= count) step(std::integral_constant<int, 0>{}, s);
+    } else if (wave == Sh::kLoader) {
+        // ---------------------------------------------------------------- loader wave
+        // straight-line steps like the epilogue's; items past the run are read again from its
+        // last tile and land in LDS buffers that nobody reads any more
+        ObsStage<H, P> st;
+        st.init(D, ks1, q4);
+        ObsRegs<H, P> regs[2];
+        auto obs_row8 = [&](int k) { return args.obs + (size_t)read_row(k) * D + 8 * q4; };
+        st.load(regs[0], obs_row8(0));
+        st.load(regs[1], obs_row8(1));
+        stage_wih();
+        auto step = [&](auto set, int s) {
+            constexpr int u = decltype(set)::value;          // parity of items s + 2, s + 4
+            st.write(regs[u], obuf + (size_t)((s & 1) * ks1) * P * 64 + lane);
+            st.load(regs[u], obs_row8(s + 4));
+            lds_barrier();
+        };
+        int s = -LEAD;
+        for (; s + 1 <= count; s += 2) {
+            step(std::integral_constant<int, 0>{}, s);
+            step(std::integral_constant<int, 1>{}, s + 1);
+        }
+        if (s <= count) step(std::integral_constant<int, 0>{}, s);
+    } else {
+        // ---------------------------------------------------------------- fc1 wave
+        const int f = wave - Sh::kFc1;
+        stage_wih();
+        Fc1Wave<H, P> fc1;
+        fc1.load(net, f, ks1, lane);
+        fc1.settle_weights(ks1);
+        for (int s = -LEAD; s <= count; ++s) {
+            const int item = s + 1;
+            if (item >= 0 && item < count) {
+                f32x4 b1v[Sh::NBF];
+                Fc1Wave<H, P>::load_bias(net, f, read_row(item) % N, q4, b1v);
+                fc1.step(obuf + (size_t)((item & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[item & 1]);
+            }
+            lds_barrier();
+        }
     }
 }
 
@@ -309,7 +348,7 @@ template <int H, int P> bool fits_act(const NetFrags &net)
 
 bool act_fused_fits(const NetFrags &net)
 {
-    if (net.A > 64) return false;
+    if (net.A > 64 || net.A < 4) return false;       // availability is read four bytes at a time
     if (net.H == 64 && net.planes == 2) return fits_act<64, 2>(net);
     if (net.H == 64 && net.planes == 1) return fits_act<64, 1>(net);
     if (net.H == 128 && net.planes == 1) return fits_act<128, 1>(net);

@@ -46,9 +46,11 @@ template <int H, int P> struct Fused16 {
     static constexpr int oB2 = oGBias + 3 * H * 4;                  // [64] floats
     static constexpr int oObs = oB2 + 256;                          // [2][ks1][P][64] bf16x8
     static constexpr size_t lds_bytes(int ks1) { return (size_t)oObs + (size_t)2 * ks1 * kFrag; }
-    // decision step only: the incoming hidden state as operand fragments, [2][KS][P][64] bf16x8 after the observations
+    // decision step only, after the observations: the incoming hidden state as operand fragments
+    // [2][KS][P][64] bf16x8, then in fp32 by feature block [2][FBK][64] float4
     static constexpr size_t hin_offset(int ks1) { return lds_bytes(ks1); }
-    static constexpr size_t lds_bytes_act(int ks1) { return lds_bytes(ks1) + (size_t)2 * KS * kFrag; }
+    static constexpr size_t hf_offset(int ks1) { return hin_offset(ks1) + (size_t)2 * KS * kFrag; }
+    static constexpr size_t lds_bytes_act(int ks1) { return hf_offset(ks1) + (size_t)2 * FBK * 1024; }
 };
 
 constexpr int fused_threads(int H) { return 64 * (4 + 2 + (H == 128 ? 2 : 1)); }

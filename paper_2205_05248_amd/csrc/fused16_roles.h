@@ -4,13 +4,23 @@
 //   GruWave    a compute wave: its slice of W_hh in registers, W_ih fragments from LDS, both GRU
 //              products, the gates, and the new hidden state as next operand
 //   Fc1Wave    an fc1 wave: its feature blocks of W1 in registers, x = ReLU(W1 o + b1[agent])
-//   ObsStage   the loader's observation registers: global memory -> registers -> bf16 operand
-//              fragments in LDS
+//   ObsStage   the loader's observation registers (ObsRegs): global memory -> registers -> bf16
+//              operand fragments in LDS
 //   ObsTouch   the reads that pull a later item's rows into L2 ahead of the loader
 #pragma once
 #include "fused16.h"
 
 namespace marl {
+
+// Weights are loaded into registers once, before a loop that also has global memory traffic of
+// its own.  Consuming them here places the wait for their arrival before the loop; otherwise it
+// sits at their first use inside the loop, where it would also cover whatever the previous
+// iteration left in flight.
+template <int P> __device__ __forceinline__ void settle(const WFrag<P> &w)
+{
+    asm volatile("" ::"v"(w.hi));
+    if constexpr (P == 2) asm volatile("" ::"v"(w.lo));
+}
 
 template <int H, int P> struct GruWave {
     using Sh = Fused16<H, P>;
@@ -31,6 +41,18 @@ template <int H, int P> struct GruWave {
                     whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + NBC * w + j) * KS + ks) * P) * 64 + lane);
 #pragma unroll
         for (int j = 0; j < NBC; ++j) bias_hn[j] = load_feature4(net.bias_hn, NBC * w + j, q4);
+    }
+
+    __device__ __forceinline__ void settle_weights() const
+    {
+#pragma unroll
+        for (int gate = 0; gate < 3; ++gate)
+#pragma unroll
+            for (int j = 0; j < NBC; ++j)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) settle(whh[gate][j][ks]);
+#pragma unroll
+        for (int j = 0; j < NBC; ++j) asm volatile("" ::"v"(bias_hn[j]));
     }
 
     // Gate biases (b_ir + b_hr, b_iz + b_hz, b_in) -> LDS, by one wave; read after a barrier.
@@ -152,6 +174,15 @@ template <int H, int P> struct Fc1Wave {
                 if (ks < ks1) w1[j][ks] = load_wfrag<P>(net.w1_16 + ((size_t)((f * NBF + j) * ks1 + ks) * P) * 64 + lane);
     }
 
+    __device__ __forceinline__ void settle_weights(int ks1) const
+    {
+#pragma unroll
+        for (int j = 0; j < NBF; ++j)
+#pragma unroll
+            for (int ks = 0; ks < KM; ++ks)
+                if (ks < ks1) settle(w1[j][ks]);
+    }
+
     static __device__ __forceinline__ void load_bias(const NetFrags &net, int f, int n, int q4, f32x4 (&b1v)[NBF])
     {
 #pragma unroll
@@ -203,10 +234,15 @@ template <int H, int P> struct Fc1Wave {
 // inside the row and is fetched as two 16-byte loads at constant offsets from one address (only
 // 4-byte alignment is assumed).  The last k-step, which may be partial, is fetched element by
 // element from positions clamped into the row; the weights are zero where the clamp changes a
-// position.
-template <int H, int P> struct ObsStage {
+// position.  ObsRegs is one item's worth of registers (a loader that runs several items ahead
+// keeps several), ObsStage what all of them share.
+template <int H, int P> struct ObsRegs {
     static constexpr int KM = Fused16<H, P>::kKs1Max;
     float stage[KM - 1 > 0 ? KM - 1 : 1][8], last[8];
+};
+
+template <int H, int P> struct ObsStage {
+    static constexpr int KM = Fused16<H, P>::kKs1Max;
     int last_off[8];
     int nfull;                                       // k-steps handled by the vector path
 
@@ -214,14 +250,11 @@ template <int H, int P> struct ObsStage {
     {
         nfull = ks1 - 1;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            last_off[i] = min(32 * nfull + 8 * q4 + i, D - 1) - 8 * q4;
-            last[i] = 0.0f;
-        }
+        for (int i = 0; i < 8; ++i) last_off[i] = min(32 * nfull + 8 * q4 + i, D - 1) - 8 * q4;
     }
 
     // row8 = the lane's row + 8 q
-    __device__ __forceinline__ void load(const float *row8)
+    __device__ __forceinline__ void load(ObsRegs<H, P> &r, const float *row8) const
     {
 #pragma unroll
         for (int k = 0; k < KM - 1; ++k)
@@ -230,10 +263,10 @@ template <int H, int P> struct ObsStage {
                 __builtin_memcpy(&lo4, row8 + 32 * k, 16);
                 __builtin_memcpy(&hi4, row8 + 32 * k + 4, 16);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { stage[k][i] = lo4[i]; stage[k][4 + i] = hi4[i]; }
+                for (int i = 0; i < 4; ++i) { r.stage[k][i] = lo4[i]; r.stage[k][4 + i] = hi4[i]; }
             }
 #pragma unroll
-        for (int i = 0; i < 8; ++i) last[i] = row8[last_off[i]];
+        for (int i = 0; i < 8; ++i) r.last[i] = row8[last_off[i]];
     }
 
     static __device__ __forceinline__ void put(bf16x8 *at, const float (&v)[8])
@@ -244,12 +277,12 @@ template <int H, int P> struct ObsStage {
     }
 
     // dst = this lane's slot in the item's first fragment
-    __device__ __forceinline__ void write(bf16x8 *dst) const
+    __device__ __forceinline__ void write(const ObsRegs<H, P> &r, bf16x8 *dst) const
     {
 #pragma unroll
         for (int k = 0; k < KM - 1; ++k)
-            if (k < nfull) put(dst + (k * P) * 64, stage[k]);
-        put(dst + (nfull * P) * 64, last);
+            if (k < nfull) put(dst + (k * P) * 64, r.stage[k]);
+        put(dst + (nfull * P) * 64, r.last);
     }
 };
 

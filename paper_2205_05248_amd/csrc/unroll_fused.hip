@@ -172,10 +172,11 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         const size_t slot_stride = (size_t)N * D;
         ObsStage<H, P> st;
         st.init(D, ks1, q4);
+        ObsRegs<H, P> regs;
         for (int s = -LEAD; s <= T + 1; ++s) {
             const int ws = s + 2, ls = s + 3;
-            if (ws >= 0 && ws <= T) st.write(obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
-            if (ls >= 0 && ls <= T) st.load(base + (size_t)ls * slot_stride);                      // issue the loads
+            if (ws >= 0 && ws <= T) st.write(regs, obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
+            if (ls >= 0 && ls <= T) st.load(regs, base + (size_t)ls * slot_stride);                      // issue the loads
             lds_barrier();
         }
     } else {
