@@ -84,6 +84,7 @@ __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)
 }
 
 constexpr int kActLead = 2;          // steps before item 0 enters the GRU
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int kRawBuffer = 0x00020000;       // descriptor word 3: untyped 32-bit data, no swizzle, offsets checked against the size
 
 template <int H, int P, int AB>
@@ -203,6 +204,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
             args.q_out + (size_t)first * 16 * A, 0, args.q_out ? run_rows * A * 4 : 0, kRawBuffer);
         const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(args.action + (size_t)first * 16, 0, run_rows * 4, kRawBuffer);
         constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
+        struct { int best; uint64_t bits; int step; } kept = {0, 0, 0};
         auto step = [&](auto set, int s) {
             constexpr int p = 1 - decltype(set)::value;      // parity of items s - 1, s + 1, s + 3
             {   // item s - 1: Q, mask, choice
@@ -210,8 +212,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
                 const int lr = k * 16 + c;                   // row within the run
                 uint32_t dead = k >= 0 ? 0u : kDrop;         // in a vector register: the step must not fork on it
                 asm volatile("" : "+v"(dead));
-                const int rr = read_row(k);
-                const int e = rr / N, n = rr % N;
                 f32x4 qv[AB];
 #pragma unroll
                 for (int ab = 0; ab < AB; ++ab) qv[ab] = load_feature4(b2_lds, ab, q4);
@@ -223,21 +223,44 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 #pragma unroll
                     for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb);
                 }
+                if ((A & 3) == 0) {                          // a lane's four actions of a block: 16 aligned bytes
 #pragma unroll
-                for (int ab = 0; ab < AB; ++ab)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int a = 16 * ab + 4 * q4 + r;
-                        const float value = qv[ab][r];
-                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value), q_buf,
-                                                              (a < A ? (uint32_t)(lr * A + a) * 4u : kDrop) | dead, 0, 0);
+                    for (int ab = 0; ab < AB; ++ab) {
+                        const int a = 16 * ab + 4 * q4;
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, qv[ab]), q_buf,
+                                                               (a < A ? (uint32_t)(lr * A + a) * 4u : kDrop) | dead, 0, 0);
                     }
+                } else {
+#pragma unroll
+                    for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int a = 16 * ab + 4 * q4 + r;
+                            const float value = qv[ab][r];
+                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(value), q_buf,
+                                                                  (a < A ? (uint32_t)(lr * A + a) * 4u : kDrop) | dead, 0, 0);
+                        }
+                }
                 const uint32_t slots = avail_mask16<AB>(in[p].avail_raw, A, q4, true);
                 float best_q; int best;
                 masked_argmax16<AB>(qv, slots, q4, best_q, best);
                 const uint64_t bits = row_avail_bits16<AB>(slots, q4);
-                const int pick = eps_greedy_pick(max(best, 0), bits, args.epsilon, args.seed, (uint32_t)e, (uint32_t)n, (uint32_t)in[p].step);
-                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, (q4 == 0 ? (uint32_t)lr * 4u : kDrop) | dead, 0, 0);
+                // The four lanes of a row now agree; quarter q keeps items 4 i + q.  The draw is
+                // the same work for one lane or sixty-four, so it waits until every quarter has
+                // an item (or the run ends) and is then made for four items at once.
+                const bool mine = (k & 3) == q4;
+                kept.best = mine ? max(best, 0) : kept.best;
+                kept.bits = mine ? bits : kept.bits;
+                kept.step = mine ? in[p].step : kept.step;
+                int pick = 0;
+                uint32_t pick_at = kDrop;
+                if ((k & 3) == 3 || k == count - 1) {
+                    const int kk = (k & ~3) + q4;            // the item this lane kept, if it is <= k
+                    const int rr = read_row(kk);
+                    pick = eps_greedy_pick(kept.best, kept.bits, args.epsilon, args.seed, (uint32_t)(rr / N), (uint32_t)(rr % N), (uint32_t)kept.step);
+                    pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
+                }
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
                 in[p] = fetch_item(s + 1);
             }
             {   // incoming hidden state of item s + 1 -> LDS, that of item s + 3 asked for

@@ -44,22 +44,46 @@ __device__ __forceinline__ void rng_draw(uint64_t seed, uint32_t e, uint32_t n, 
     r2 = splitmix_out(k + kGolden);
 }
 
+// Index of the j-th set bit of bits (j counted from 0, j < popcount(bits)): a binary search on
+// the population counts of the lower halves, the same number of steps for every lane.
+__device__ __forceinline__ int nth_set_bit(uint64_t bits, uint32_t j)
+{
+    uint32_t word = (uint32_t)bits;
+    int base = 0;
+    const uint32_t below = (uint32_t)__popc(word);
+    if (j >= below) { j -= below; word = (uint32_t)(bits >> 32); base = 32; }
+#pragma unroll
+    for (int half = 16; half >= 1; half >>= 1) {
+        const uint32_t low = word & ((1u << half) - 1u);
+        const uint32_t cnt = (uint32_t)__popc(low);
+        const bool up = j >= cnt;
+        j = up ? j - cnt : j;
+        word = up ? word >> half : low;
+        base = up ? base + half : base;
+    }
+    return base;
+}
+
+// The uniform draw and the raw second draw for (seed, env, agent, step); explore when u < epsilon.
+struct ExploreDraw { float u; uint32_t pick_bits; };
+__device__ __forceinline__ ExploreDraw explore_draw(uint64_t seed, uint32_t e, uint32_t n, uint32_t t)
+{
+    uint64_t r1, r2;
+    rng_draw(seed, e, n, t, r1, r2);
+    return {(float)(uint32_t)(r1 >> 40) * (1.0f / 16777216.0f), (uint32_t)(r2 >> 32)};
+}
+
 // Epsilon-greedy over the available actions of one (env, agent) row, given the
 // greedy action and the availability bits (bit a of avail_bits = action a usable).
 __device__ __forceinline__ int eps_greedy_pick(int greedy, uint64_t avail_bits, float epsilon,
                                                uint64_t seed, uint32_t e, uint32_t n, uint32_t t)
 {
-    uint64_t r1, r2;
-    rng_draw(seed, e, n, t, r1, r2);
-    float u = (float)(uint32_t)(r1 >> 40) * (1.0f / 16777216.0f);
-    if (!(u < epsilon)) return greedy;
-    uint32_t c = (uint32_t)__popcll(avail_bits);
+    const ExploreDraw d = explore_draw(seed, e, n, t);
+    if (!(d.u < epsilon)) return greedy;
+    const uint32_t c = (uint32_t)__popcll(avail_bits);
     if (c == 0) return 0;
-    uint32_t j = (uint32_t)(((r2 >> 32) * (uint64_t)c) >> 32);
-    // index of the j-th set bit
-    uint64_t bits = avail_bits;
-    for (uint32_t i = 0; i < j; ++i) bits &= bits - 1;
-    return __ffsll((long long)bits) - 1;
+    const uint32_t j = (uint32_t)(((uint64_t)d.pick_bits * (uint64_t)c) >> 32);      // uniform over 0 .. c-1
+    return nth_set_bit(avail_bits, j);
 }
 
 }  // namespace marl
