@@ -59,12 +59,16 @@ __device__ __forceinline__ void masked_argmax16(const f32x4 (&qv)[AB], uint32_t 
             const bool ok = (slots >> (4 * ab + r)) & 1u;
             if (ok && (best_idx < 0 || qv[ab][r] > best_q)) { best_q = qv[ab][r]; best_idx = 16 * ab + 4 * q + r; }
         }
-#pragma unroll
-    for (int m = 16; m <= 32; m <<= 1) {
-        const float oq = __shfl_xor(best_q, m);
-        const int oi = __shfl_xor(best_idx, m);
-        if (oi >= 0 && (best_idx < 0 || oq > best_q || (oq == best_q && oi < best_idx))) { best_q = oq; best_idx = oi; }
-    }
+    auto better = [](float qa, int ia, float qb, int ib, float &q_out, int &i_out) {      // a: the lower quarter
+        const bool take_b = ib >= 0 && (ia < 0 || qb > qa || (qb == qa && ib < ia));
+        q_out = take_b ? qb : qa;
+        i_out = take_b ? ib : ia;
+    };
+    LanePair pq = halves16(__float_as_uint(best_q)), pi = halves16((uint32_t)best_idx);
+    better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
+    pq = halves32(__float_as_uint(best_q));
+    pi = halves32((uint32_t)best_idx);
+    better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
 }
 
 // Availability bits of the whole row (bit a = action a) from the four lanes' slot masks.
@@ -74,13 +78,7 @@ __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)
     uint64_t bits = 0;
 #pragma unroll
     for (int ab = 0; ab < AB; ++ab) bits |= (uint64_t)((slots >> (4 * ab)) & 0xFu) << (16 * ab + 4 * q);
-    uint32_t lo = (uint32_t)bits, hi = (uint32_t)(bits >> 32);
-#pragma unroll
-    for (int m = 16; m <= 32; m <<= 1) {
-        lo |= __shfl_xor(lo, m);
-        hi |= __shfl_xor(hi, m);
-    }
-    return ((uint64_t)hi << 32) | lo;
+    return ((uint64_t)or_quarters((uint32_t)(bits >> 32)) << 32) | or_quarters((uint32_t)bits);
 }
 
 constexpr int kActLead = 2;          // steps before item 0 enters the GRU
@@ -207,22 +205,48 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         struct { int best; uint64_t bits; int step; } kept = {0, 0, 0};
         auto step = [&](auto set, int s) {
             constexpr int p = 1 - decltype(set)::value;      // parity of items s - 1, s + 1, s + 3
+            // item s - 1: every LDS read it needs is asked for first (the LDS queue is long while
+            // the compute waves stream W_ih through it) and arrives during the work on the state
+            const int k = s - 1, cur = k & 1;
+            f32x4 qv[AB];
+            Frag<P> hb[KS];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                hb[ks].hi = h_lds[cur][ks][0][lane];
+                if constexpr (P == 2) hb[ks].lo = h_lds[cur][ks][1][lane];
+            }
+#pragma unroll
+            for (int ab = 0; ab < AB; ++ab) qv[ab] = load_feature4(b2_lds, ab, q4);
+            __builtin_amdgcn_sched_barrier(0);
+            {   // incoming hidden state of item s + 1 -> LDS, that of item s + 3 asked for
+                const int nb = (s + 1) & 1;
+                const bool keep = !(has_reset && (state[p].flag & 0xFFu));
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    f32x4 a = state[p].a[ks], b = state[p].b[ks];
+                    float v[8];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        a[i] = keep ? a[i] : 0.0f;
+                        b[i] = keep ? b[i] : 0.0f;
+                        v[i] = a[i];
+                        v[4 + i] = b[i];
+                    }
+                    ObsStage<H, P>::put(&hin_lds[nb][ks][0][lane], v);
+                    hf_lds[nb][2 * ks][lane] = a;
+                    hf_lds[nb][2 * ks + 1][lane] = b;
+                }
+                state[p] = fetch_state(s + 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
             {   // item s - 1: Q, mask, choice
-                const int k = s - 1, cur = k & 1;
                 const int lr = k * 16 + c;                   // row within the run
                 uint32_t dead = k >= 0 ? 0u : kDrop;         // in a vector register: the step must not fork on it
                 asm volatile("" : "+v"(dead));
-                f32x4 qv[AB];
 #pragma unroll
-                for (int ab = 0; ab < AB; ++ab) qv[ab] = load_feature4(b2_lds, ab, q4);
+                for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    Frag<P> hb;
-                    hb.hi = h_lds[cur][ks][0][lane];
-                    if constexpr (P == 2) hb.lo = h_lds[cur][ks][1][lane];
-#pragma unroll
-                    for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb);
-                }
+                    for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb[ks]);
                 if ((A & 3) == 0) {                          // a lane's four actions of a block: 16 aligned bytes
 #pragma unroll
                     for (int ab = 0; ab < AB; ++ab) {
@@ -262,26 +286,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
                 }
                 __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
                 in[p] = fetch_item(s + 1);
-            }
-            {   // incoming hidden state of item s + 1 -> LDS, that of item s + 3 asked for
-                const int nb = (s + 1) & 1;
-                const bool keep = !(has_reset && (state[p].flag & 0xFFu));
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    f32x4 a = state[p].a[ks], b = state[p].b[ks];
-                    float v[8];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        a[i] = keep ? a[i] : 0.0f;
-                        b[i] = keep ? b[i] : 0.0f;
-                        v[i] = a[i];
-                        v[4 + i] = b[i];
-                    }
-                    ObsStage<H, P>::put(&hin_lds[nb][ks][0][lane], v);
-                    hf_lds[nb][2 * ks][lane] = a;
-                    hf_lds[nb][2 * ks + 1][lane] = b;
-                }
-                state[p] = fetch_state(s + 3);
             }
             lds_barrier();
         };

@@ -89,6 +89,36 @@ __device__ __forceinline__ uint32_t avail_mask_small16(const uint8_t *__restrict
     return (valid && q == 0) ? mask : 0u;
 }
 
+// A row's Q values sit in the four lanes c, c + 16, c + 32, c + 48 (lane quarters 0..3).  The two
+// swaps below hand every lane a pair of quarters' values without a trip through LDS:
+// halves16: (quarter 0, quarter 1) in the lanes of quarters 0 and 1, (2, 3) in those of 2 and 3;
+// halves32: (q & 1, (q & 1) + 2).  One after the other they combine all four, and every lane ends
+// with the same result, the operands always in quarter order.
+struct LanePair { uint32_t lower, upper; };
+__device__ __forceinline__ LanePair halves16(uint32_t x)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+    return {r[0], r[1]};
+}
+__device__ __forceinline__ LanePair halves32(uint32_t x)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+    return {r[0], r[1]};
+}
+template <class Op> __device__ __forceinline__ float combine_quarters(float x, Op op)
+{
+    LanePair p = halves16(__float_as_uint(x));
+    const float y = op(__uint_as_float(p.lower), __uint_as_float(p.upper));
+    p = halves32(__float_as_uint(y));
+    return op(__uint_as_float(p.lower), __uint_as_float(p.upper));
+}
+__device__ __forceinline__ uint32_t or_quarters(uint32_t x)
+{
+    LanePair p = halves16(x);
+    p = halves32(p.lower | p.upper);
+    return p.lower | p.upper;
+}
+
 // Maximum of the row's available Q values (0 when nothing is available).
 template <int AB>
 __device__ __forceinline__ float masked_max16(const f32x4 (&qv)[AB], uint32_t slots)
@@ -98,8 +128,7 @@ __device__ __forceinline__ float masked_max16(const f32x4 (&qv)[AB], uint32_t sl
     for (int ab = 0; ab < AB; ++ab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) m = fmaxf(m, ((slots >> (4 * ab + r)) & 1u) ? qv[ab][r] : -__builtin_inff());
-    m = fmaxf(m, __shfl_xor(m, 16));
-    m = fmaxf(m, __shfl_xor(m, 32));
+    m = combine_quarters(m, [](float a, float b) { return fmaxf(a, b); });
     return m == -__builtin_inff() ? 0.0f : m;
 }
 
@@ -112,8 +141,7 @@ __device__ __forceinline__ float pick_action_value16(const f32x4 (&qv)[AB], int 
     for (int ab = 0; ab < AB; ++ab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) v = (16 * ab + 4 * q + r == u) ? qv[ab][r] : v;
-    v += __shfl_xor(v, 16);
-    return v + __shfl_xor(v, 32);
+    return combine_quarters(v, [](float a, float b) { return a + b; });
 }
 
 template <int AB>
