@@ -7,13 +7,16 @@
 // which the GRU handles item k (the k-th tile of the run)
 //
 //   loader wave    writes the observations of item k+2 to LDS as bf16 operand fragments and asks
-//                  for those of item k+4;
+//                  for those of item k+4; it also owns the choice of action apart from the
+//                  argmax: availability of item k -> slot masks for the epilogue, and once four
+//                  items have their greedy action (or the run ends) the epsilon-greedy draws
+//                  for their 64 rows at once and the action store;
 //   fc1 waves      x = ReLU(W1 o + b1[agent]) for item k+1;
 //   compute waves  item k of the GRU: W_ih x + W_hh h + b for their hidden units, gates, new hidden
 //                  state to global memory (fp32) and to LDS (operand form);
-//   epilogue wave  item k-1: fc2, Q store, availability mask, argmax, epsilon-greedy, action store;
-//                  it also feeds the incoming hidden state: item k+1 goes to LDS (operand
-//                  fragments for the product, fp32 for the blend), item k+3 is asked for.
+//   epilogue wave  item k-1: fc2, Q store, masked argmax (greedy action -> LDS); it also feeds the
+//                  incoming hidden state: item k+1 goes to LDS (operand fragments for the
+//                  product, fp32 for the blend), item k+3 is asked for.
 //
 // Every input is read once from HBM and nothing of it is reused, so the whole job is hiding the
 // latency of a first touch (a few microseconds under load, longer than a step): each wave that
@@ -101,6 +104,10 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
     const FragBuf x_lds = reinterpret_cast<FragBuf>(lds + Sh::oX);
     const FragBuf hin_lds = reinterpret_cast<FragBuf>(lds + Sh::hin_offset(ks1));    // old hidden state as operand
     const StateBuf hf_lds = reinterpret_cast<StateBuf>(lds + Sh::hf_offset(ks1));    // old hidden state in fp32, by feature block
+    uint32_t (*const slots_lds)[64] = reinterpret_cast<uint32_t (*)[64]>(lds + Sh::slots_offset(ks1));
+    struct RowChoice { uint32_t bits_lo, bits_hi; int step; };                       // 12 bytes
+    RowChoice (*const choice_lds)[16] = reinterpret_cast<RowChoice (*)[16]>(lds + Sh::choice_offset(ks1));
+    uint8_t (*const greedy_lds)[16] = reinterpret_cast<uint8_t (*)[16]>(lds + Sh::greedy_offset(ks1));
     bf16x8 *const obuf = reinterpret_cast<bf16x8 *>(lds + Sh::oObs);
     bf16x8 *const wih_lds = reinterpret_cast<bf16x8 *>(lds + Sh::oWih);
 
@@ -110,11 +117,12 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
     const int tiles = (rows + 15) / 16;
     const int first = blockIdx.x * args.tiles_per_group;
     const int count = min(args.tiles_per_group, tiles - first);       // >= 1 by construction of the grid
+    const int last = count + 1;                                       // the last step
     // item k (0 <= k < count) is tile first + k; items past the run re-use its last tile (reads only),
     // rows past the end row 0
     auto item_row = [&](int k) { return (first + min(max(k, 0), count - 1)) * 16 + c; };
     auto read_row = [&](int k) { const int row = item_row(k); return row < rows ? row : 0; };
-    // Steps run s = -LEAD .. count, one barrier at the end of each: LEAD + count + 1 barriers per wave.
+    // Steps run s = -LEAD .. count + 1, one barrier at the end of each: LEAD + count + 2 barriers per wave.
     // Step s = s0 + u of the unrolled loops has the parity of u.
 
     auto stage_wih = [&]() {             // every wave's share of W_ih -> LDS
@@ -132,7 +140,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
         gru.settle_weights();
         for (int i = 0; i < LEAD; ++i) lds_barrier();
-        for (int s = 0; s <= count; ++s) {
+        for (int s = 0; s <= last; ++s) {
             if (s < count) {
                 const int cur = s & 1;
                 const int row = item_row(s);
@@ -155,7 +163,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         // nothing younger: loads of items outside the run read clamped rows, stores of items
         // outside the run (and of rows past the end, and of Q when it is not wanted) carry an
         // offset outside their buffer descriptor and are dropped by the hardware.
-        struct ItemIn { uint32_t avail_raw[AB]; int step; };
         // Hidden state: the operand of k-step ks wants features 32 ks + 16 (idx / 4) + 4 q + idx % 4,
         // i.e. two aligned groups of four floats, which are also the lane's share of feature
         // blocks 2 ks and 2 ks + 1.
@@ -163,13 +170,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         const bool has_reset = args.reset != nullptr;
         // without reset flags the byte is read from step_t instead and ignored
         const uint8_t *const flag_src = has_reset ? args.reset : reinterpret_cast<const uint8_t *>(args.step_t);
-        auto fetch_item = [&](int k) {
-            ItemIn in;
-            const int rr = read_row(k);
-            issue_avail_loads16<AB>(args.avail + (size_t)rr * A, A, q4, in.avail_raw);
-            in.step = args.step_t[rr / N];
-            return in;
-        };
         auto fetch_state = [&](int k) {
             StateIn st;
             const int rr = read_row(k);
@@ -182,7 +182,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
             st.flag = flag_src[rr / N];
             return st;
         };
-        ItemIn in[2] = {fetch_item(0), fetch_item(1)};
         StateIn state[2] = {fetch_state(0), fetch_state(1)};
         stage_wih();
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
@@ -200,9 +199,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         const int run_rows = min(count * 16, rows - first * 16);
         const __amdgpu_buffer_rsrc_t q_buf = __builtin_amdgcn_make_buffer_rsrc(
             args.q_out + (size_t)first * 16 * A, 0, args.q_out ? run_rows * A * 4 : 0, kRawBuffer);
-        const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(args.action + (size_t)first * 16, 0, run_rows * 4, kRawBuffer);
         constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
-        struct { int best; uint64_t bits; int step; } kept = {0, 0, 0};
         auto step = [&](auto set, int s) {
             constexpr int p = 1 - decltype(set)::value;      // parity of items s - 1, s + 1, s + 3
             // item s - 1: every LDS read it needs is asked for first (the LDS queue is long while
@@ -265,36 +262,19 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
                                                                   (a < A ? (uint32_t)(lr * A + a) * 4u : kDrop) | dead, 0, 0);
                         }
                 }
-                const uint32_t slots = avail_mask16<AB>(in[p].avail_raw, A, q4, true);
+                const uint32_t slots = slots_lds[cur][lane];     // from the loader, one step ago
                 float best_q; int best;
                 masked_argmax16<AB>(qv, slots, q4, best_q, best);
-                const uint64_t bits = row_avail_bits16<AB>(slots, q4);
-                // The four lanes of a row now agree; quarter q keeps items 4 i + q.  The draw is
-                // the same work for one lane or sixty-four, so it waits until every quarter has
-                // an item (or the run ends) and is then made for four items at once.
-                const bool mine = (k & 3) == q4;
-                kept.best = mine ? max(best, 0) : kept.best;
-                kept.bits = mine ? bits : kept.bits;
-                kept.step = mine ? in[p].step : kept.step;
-                int pick = 0;
-                uint32_t pick_at = kDrop;
-                if ((k & 3) == 3 || k == count - 1) {
-                    const int kk = (k & ~3) + q4;            // the item this lane kept, if it is <= k
-                    const int rr = read_row(kk);
-                    pick = eps_greedy_pick(kept.best, kept.bits, args.epsilon, args.seed, (uint32_t)(rr / N), (uint32_t)(rr % N), (uint32_t)kept.step);
-                    pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
-                }
-                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
-                in[p] = fetch_item(s + 1);
+                greedy_lds[k & 7][c] = (uint8_t)max(best, 0);    // the four lanes of a row agree
             }
             lds_barrier();
         };
         int s = -LEAD;
-        for (; s + 1 <= count; s += 2) {
+        for (; s + 1 <= last; s += 2) {
             step(std::integral_constant<int, 0>{}, s);
             step(std::integral_constant<int, 1>{}, s + 1);
         }
-        if (s <= count) step(std::integral_constant<int, 0>{}, s);
+        if (s <= last) step(std::integral_constant<int, 0>{}, s);
     } else if (wave == Sh::kLoader) {
         // ---------------------------------------------------------------- loader wave
         // straight-line steps like the epilogue's; items past the run are read again from its
@@ -302,22 +282,59 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         ObsStage<H, P> st;
         st.init(D, ks1, q4);
         ObsRegs<H, P> regs[2];
+        struct ItemIn { uint32_t avail_raw[AB]; int step; };
         auto obs_row8 = [&](int k) { return args.obs + (size_t)read_row(k) * D + 8 * q4; };
+        auto fetch_item = [&](int k) {
+            ItemIn in;
+            const int rr = read_row(k);
+            issue_avail_loads16<AB>(args.avail + (size_t)rr * A, A, q4, in.avail_raw);
+            in.step = args.step_t[rr / N];
+            return in;
+        };
         st.load(regs[0], obs_row8(0));
         st.load(regs[1], obs_row8(1));
+        ItemIn in[2] = {fetch_item(0), fetch_item(1)};
         stage_wih();
+        // actions of this workgroup's run of tiles, addressed by row within the run
+        const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(
+            args.action + (size_t)first * 16, 0, min(count * 16, rows - first * 16) * 4, kRawBuffer);
+        constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
         auto step = [&](auto set, int s) {
-            constexpr int u = decltype(set)::value;          // parity of items s + 2, s + 4
+            constexpr int u = decltype(set)::value;          // parity of items s, s + 2, s + 4
             st.write(regs[u], obuf + (size_t)((s & 1) * ks1) * P * 64 + lane);
             st.load(regs[u], obs_row8(s + 4));
+            {   // availability of item s: slot masks for the epilogue's argmax, the row's bits for the draw
+                const uint32_t slots = avail_mask16<AB>(in[u].avail_raw, A, q4, true);
+                slots_lds[s & 1][lane] = slots;
+                const uint64_t bits = row_avail_bits16<AB>(slots, q4);
+                choice_lds[s & 7][c] = {(uint32_t)bits, (uint32_t)(bits >> 32), in[u].step};      // the four lanes of a row agree
+                in[u] = fetch_item(s + 2);
+            }
+            // The draw is the same work for one lane or sixty-four, so it waits until four items
+            // have their greedy action (or the run ends) and is then made for their 64 rows at
+            // once: lane quarter q takes item 4 i + q.  Item s - 2 got its greedy action in the
+            // previous step.
+            const int k = s - 2;
+            int pick = 0;
+            uint32_t pick_at = kDrop;
+            if ((k & 3) == 3 || k == count - 1) {
+                const int kk = (k & ~3) + q4;
+                const RowChoice ch = choice_lds[kk & 7][c];
+                const int greedy = greedy_lds[kk & 7][c];
+                const int rr = read_row(kk);
+                pick = eps_greedy_pick(greedy, ((uint64_t)ch.bits_hi << 32) | ch.bits_lo, args.epsilon, args.seed,
+                                       (uint32_t)(rr / N), (uint32_t)(rr % N), (uint32_t)ch.step);
+                pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
+            }
+            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
             lds_barrier();
         };
         int s = -LEAD;
-        for (; s + 1 <= count; s += 2) {
+        for (; s + 1 <= last; s += 2) {
             step(std::integral_constant<int, 0>{}, s);
             step(std::integral_constant<int, 1>{}, s + 1);
         }
-        if (s <= count) step(std::integral_constant<int, 0>{}, s);
+        if (s <= last) step(std::integral_constant<int, 0>{}, s);
     } else {
         // ---------------------------------------------------------------- fc1 wave
         const int f = wave - Sh::kFc1;
@@ -325,7 +342,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         Fc1Wave<H, P> fc1;
         fc1.load(net, f, ks1, lane);
         fc1.settle_weights(ks1);
-        for (int s = -LEAD; s <= count; ++s) {
+        for (int s = -LEAD; s <= last; ++s) {
             const int item = s + 1;
             if (item >= 0 && item < count) {
                 f32x4 b1v[Sh::NBF];

@@ -50,7 +50,13 @@ template <int H, int P> struct Fused16 {
     // [2][KS][P][64] bf16x8, then in fp32 by feature block [2][FBK][64] float4
     static constexpr size_t hin_offset(int ks1) { return lds_bytes(ks1); }
     static constexpr size_t hf_offset(int ks1) { return hin_offset(ks1) + (size_t)2 * KS * kFrag; }
-    static constexpr size_t lds_bytes_act(int ks1) { return hf_offset(ks1) + (size_t)2 * FBK * 1024; }
+    // then what the loader and the epilogue hand each other about the choice of action: the
+    // availability slots of every lane [2][64] words, and per row of the last eight items the
+    // availability bits and step number [8][16] x 12 bytes and the greedy action [8][16] bytes
+    static constexpr size_t slots_offset(int ks1) { return hf_offset(ks1) + (size_t)2 * FBK * 1024; }
+    static constexpr size_t choice_offset(int ks1) { return slots_offset(ks1) + 512; }
+    static constexpr size_t greedy_offset(int ks1) { return choice_offset(ks1) + 8 * 16 * 12; }
+    static constexpr size_t lds_bytes_act(int ks1) { return greedy_offset(ks1) + 8 * 16; }
 };
 
 constexpr int fused_threads(int H) { return 64 * (4 + 2 + (H == 128 ? 2 : 1)); }

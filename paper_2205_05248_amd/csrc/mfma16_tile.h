@@ -105,13 +105,6 @@ __device__ __forceinline__ LanePair halves32(uint32_t x)
     const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
     return {r[0], r[1]};
 }
-template <class Op> __device__ __forceinline__ float combine_quarters(float x, Op op)
-{
-    LanePair p = halves16(__float_as_uint(x));
-    const float y = op(__uint_as_float(p.lower), __uint_as_float(p.upper));
-    p = halves32(__float_as_uint(y));
-    return op(__uint_as_float(p.lower), __uint_as_float(p.upper));
-}
 __device__ __forceinline__ uint32_t or_quarters(uint32_t x)
 {
     LanePair p = halves16(x);
@@ -119,6 +112,11 @@ __device__ __forceinline__ uint32_t or_quarters(uint32_t x)
     return p.lower | p.upper;
 }
 
+// The unroll's per-slot reductions below go through LDS shuffles instead: they cost the wave a
+// wait but no vector issue slots, which it shares with a compute wave; and with their cost off
+// the SIMD the online and the target workgroup of a tile keep the same pace, so the second of them
+// to read an observation line still finds it in L2.
+//
 // Maximum of the row's available Q values (0 when nothing is available).
 template <int AB>
 __device__ __forceinline__ float masked_max16(const f32x4 (&qv)[AB], uint32_t slots)
@@ -128,7 +126,8 @@ __device__ __forceinline__ float masked_max16(const f32x4 (&qv)[AB], uint32_t sl
     for (int ab = 0; ab < AB; ++ab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) m = fmaxf(m, ((slots >> (4 * ab + r)) & 1u) ? qv[ab][r] : -__builtin_inff());
-    m = combine_quarters(m, [](float a, float b) { return fmaxf(a, b); });
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
     return m == -__builtin_inff() ? 0.0f : m;
 }
 
@@ -141,7 +140,8 @@ __device__ __forceinline__ float pick_action_value16(const f32x4 (&qv)[AB], int 
     for (int ab = 0; ab < AB; ++ab)
 #pragma unroll
         for (int r = 0; r < 4; ++r) v = (16 * ab + 4 * q + r == u) ? qv[ab][r] : v;
-    return combine_quarters(v, [](float a, float b) { return a + b; });
+    v += __shfl_xor(v, 16);
+    return v + __shfl_xor(v, 32);
 }
 
 template <int AB>

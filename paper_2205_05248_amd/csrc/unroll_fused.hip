@@ -52,14 +52,19 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     bf16x8 *const obuf = reinterpret_cast<bf16x8 *>(lds + Sh::oObs);        // [((slot & 1) ks1 + ks) P + p][64]
     bf16x8 *const wih_lds = reinterpret_cast<bf16x8 *>(lds + Sh::oWih);     // [((blk KS + ks) P + p)][64]
 
-    const bool is_target = blockIdx.y == 1;
+    // Workgroup -> (tile, network).  With two networks the online and the target workgroup of a tile
+    // sit eight apart in a block of sixteen consecutive workgroups: consecutive workgroups go round
+    // the eight XCDs, so the pair shares one XCD's L2 (the second read of an observation line hits
+    // there) and is dispatched at about the same time.
+    const int rt = two_nets ? (int)(blockIdx.x >> 4) * 8 + (int)(blockIdx.x & 7) : (int)blockIdx.x;
+    const bool is_target = two_nets && ((blockIdx.x >> 3) & 1);
+    const int rows = B * online.N;
+    if (rt * 16 >= rows) return;                          // padding of the last block of sixteen
     const NetFrags net = is_target ? target : online;     // by value: uniform, lives in scalar registers
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rt = blockIdx.x;
     const int N = net.N, D = net.D, A = net.A, S = T + 1;
     const int ks1 = (D + 31) / 32;
-    const int rows = B * N;
     const int row = rt * 16 + c;
     const bool valid = row < rows;                     // rows past the end compute on row 0's inputs; results dropped
     const int b = valid ? row / N : 0, n = valid ? row % N : 0;
@@ -200,7 +205,10 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             lds_barrier();
         };
         int s = -LEAD;
-        if (f == 0) {
+        // With two networks only the online workgroup touches: its partner on the tile reads the
+        // same lines a few steps later and finds them in L2.  A partner that runs ahead misses,
+        // waits for HBM and falls back behind, so the pair settles into that order by itself.
+        if (f == 0 && !is_target) {
             static_assert(kTouchAhead == 4, "the loop is unrolled over the register sets");
             for (; s + 3 <= T + 1; s += 4) {
                 touch(0, s);     fc1_step(s);
@@ -224,7 +232,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
 {
     using Sh = Fused16<H, P>;
     const int tiles = (B * online.N + 15) / 16;
-    const dim3 grid((unsigned)tiles, two_nets ? 2u : 1u), block(fused_threads(H));
+    const dim3 grid(two_nets ? (unsigned)((tiles + 7) / 8) * 16u : (unsigned)tiles), block(fused_threads(H));
     const size_t lds = Sh::lds_bytes((online.D + 31) / 32);
     const int two = two_nets ? 1 : 0;
     const int ab = (online.A + 15) / 16;
