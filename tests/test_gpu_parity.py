@@ -393,3 +393,63 @@ def test_odd_shapes(shape, path):
     u = wl.make_unroll_inputs(cfg)
     pu.compare_unroll(pu.gpu_unroll(net, target, cfg, u), oracle_unroll(cfg, w, w_tg, u), tol)
     net.close(); target.close()
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_calls_replay_from_a_hip_graph(path):
+    """One decision step and one unroll captured into a HIP graph (after one eager call, which
+    sizes whatever the handle caches) and replayed three times on fresh input values, with eager
+    work and synchronisation between the replays: every replay matches the eager call on the same
+    values bit for bit, and the first also matches the oracle."""
+    cfg = dict(wl.config(1), E=96, B=6, T=11)
+    N, D, A, H = wl.dims(cfg)
+    tol = pu.TOL[cfg["dtype"]]
+    net, w = make_net(cfg, kernels=path)
+    target, w_tg = make_net(cfg, 1, kernels=path)
+    inputs = [(wl.make_act_inputs(cfg, stream=s), wl.make_unroll_inputs(cfg, stream=s)) for s in range(3)]
+    a_keys, u_keys = ["obs", "avail", "h_in", "reset", "step_t"], ["obs", "avail", "actions", "reward", "terminated", "filled"]
+    a = pu.to_dev(inputs[0][0], a_keys)
+    u = pu.to_dev(inputs[0][1], u_keys)
+    E, B, T = cfg["E"], cfg["B"], cfg["T"]
+    out = dict(h=torch.empty(E, N, H, device="cuda"), act=torch.empty(E, N, dtype=torch.int32, device="cuda"),
+               q=torch.empty(E, N, A, device="cuda"), u=[torch.empty(B, T, N, device="cuda") for _ in range(3)])
+
+    def calls():
+        net.act_step(a["obs"], a["avail"], a["h_in"], a["reset"], a["step_t"], inputs[0][0]["epsilon"],
+                     inputs[0][0]["seed"], out["h"], out["act"], out["q"])
+        net.unroll_td(target, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"], u["filled"],
+                      inputs[0][1]["gamma"], *out["u"])
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [out["h"].clone(), out["act"].clone(), out["q"].clone()] + [t.clone() for t in out["u"]]
+
+    calls()                                   # eager: caches are sized, launch attributes set
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            calls()
+    torch.cuda.synchronize()
+    for r, (ai, ui) in enumerate(inputs):
+        for k in a_keys:
+            a[k].copy_(torch.from_numpy(np.ascontiguousarray(ai[k])))
+        for k in u_keys:
+            u[k].copy_(torch.from_numpy(np.ascontiguousarray(ui[k])))
+        calls()
+        eager = snapshot()
+        for t in [out["h"], out["q"]] + out["u"]:
+            t.fill_(float("nan"))
+        out["act"].fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        replayed = snapshot()
+        for e, g in zip(eager, replayed):
+            assert torch.equal(e, g), f"replay {r} differs from the eager call"
+        if r == 0:
+            got = {"h_out": replayed[0].cpu().numpy(), "action": replayed[1].cpu().numpy(), "q": replayed[2].cpu().numpy()}
+            pu.compare_act(cfg, ai, got, oracle_act(cfg, w, ai), tol)
+    net.close(); target.close()
