@@ -1,0 +1,130 @@
+/*
+ * CPU oracle for the monotonic mixing network that turns the per-agent values
+ * of the learner's batch into Q_total and the target y^total of Alg. 3
+ * (learner: "calculate the gradient" uses (y^total - Q_total)).
+ *
+ * THIS FILE IS TEST INFRASTRUCTURE.  Plain double-precision evaluation with
+ * libm, one transition at a time, written to be checked by eye.  It shares no
+ * code, header, table or helper with the GPU library, and the GPU library
+ * never calls it.
+ *
+ * The paper names the mixer (its experiments train "Qmix" variants, Sec.
+ * Experimental Display) and gives the state sizes (Table 2) but prints no
+ * equations for it.  What is evaluated here is the monotonic-mixing
+ * definition: Q_total is a two-layer network over the agents' chosen values
+ * whose weights are produced from the global state and forced non-negative, so
+ * that Q_total never decreases when an agent's value increases.  The concrete
+ * form (one linear map per generated weight, absolute value for
+ * non-negativity, ELU hidden units, a two-layer state-value offset) is this
+ * repository's reading, stated in full below:
+ *
+ *   W1[n][m] = | Hw1[n M + m] . s + hb1[n M + m] |        n < N, m < M
+ *   b1[m]    =   Hb1[m] . s + hbb1[m]
+ *   w2[m]    = | Hw2[m] . s + hb2[m] |
+ *   v        =   sum_m v2[m] relu(V1[m] . s + c1[m]) + c2
+ *   hid[m]   =   elu( sum_n q[n] W1[n][m] + b1[m] )       elu(x) = x > 0 ? x : exp(x) - 1
+ *   Q_total  =   sum_m w2[m] hid[m] + v
+ *
+ * Packed parameter order (row-major, fp32): Hw1[N M, S], hb1[N M], Hb1[M, S],
+ * hbb1[M], Hw2[M, S], hb2[M], V1[M, S], c1[M], v2[M], c2[1].
+ *
+ * Pinned by tests that do not call this file for their expected values:
+ * monotonicity in every agent value, closed forms on hand-set parameters (both
+ * ELU branches, the absolute values, the state-value offset), one-hot states
+ * against explicit column picks, a tensor-library evaluation, brute-force TD
+ * targets on tiny inputs.  "Parity unpinned" by any number printed in the
+ * paper: it prints none for the mixer.
+ */
+#include <math.h>
+#include <stdint.h>
+
+typedef struct {
+    int N, M, S;
+    const float *Hw1, *hb1, *Hb1, *hbb1, *Hw2, *hb2, *V1, *c1, *v2, *c2;
+} mixer_t;
+
+long mixer_param_count(int N, int M, int S)
+{
+    return (long)(N * M + 3 * M) * (S + 1) + M + 1;
+}
+
+static void mixer_bind(mixer_t *mx, int N, int M, int S, const float *w)
+{
+    mx->N = N; mx->M = M; mx->S = S;
+    mx->Hw1 = w;  w += (long)N * M * S;
+    mx->hb1 = w;  w += (long)N * M;
+    mx->Hb1 = w;  w += (long)M * S;
+    mx->hbb1 = w; w += M;
+    mx->Hw2 = w;  w += (long)M * S;
+    mx->hb2 = w;  w += M;
+    mx->V1 = w;   w += (long)M * S;
+    mx->c1 = w;   w += M;
+    mx->v2 = w;   w += M;
+    mx->c2 = w;
+}
+
+static double dot_state(const float *row, const float *s, int S)
+{
+    double acc = 0.0;
+    for (int k = 0; k < S; ++k) acc += (double)row[k] * (double)s[k];
+    return acc;
+}
+
+/* Q_total of one transition: q[N] the agents' values, s[S] the global state. */
+static double mix(const mixer_t *mx, const double *q, const float *s)
+{
+    const int N = mx->N, M = mx->M, S = mx->S;
+    double total = 0.0;
+    for (int m = 0; m < M; ++m) {
+        double pre = dot_state(mx->Hb1 + (long)m * S, s, S) + (double)mx->hbb1[m];
+        for (int n = 0; n < N; ++n) {
+            const long f = (long)n * M + m;
+            pre += q[n] * fabs(dot_state(mx->Hw1 + f * S, s, S) + (double)mx->hb1[f]);
+        }
+        const double hid = pre > 0.0 ? pre : exp(pre) - 1.0;
+        total += fabs(dot_state(mx->Hw2 + (long)m * S, s, S) + (double)mx->hb2[m]) * hid;
+    }
+    double v = (double)mx->c2[0];
+    for (int m = 0; m < M; ++m) {
+        const double a = dot_state(mx->V1 + (long)m * S, s, S) + (double)mx->c1[m];
+        v += (double)mx->v2[m] * (a > 0.0 ? a : 0.0);
+    }
+    return total + v;
+}
+
+/* One mixer on a list of R (values, state) pairs: q [R, N] doubles, s [R, S]. */
+void mixer_forward(int N, int M, int S, const float *w, long R, const double *q, const float *s, double *q_total)
+{
+    mixer_t mx;
+    mixer_bind(&mx, N, M, S, w);
+    for (long r = 0; r < R; ++r) q_total[r] = mix(&mx, q + r * N, s + r * S);
+}
+
+/*
+ * The learner's use (Alg. 3): for every transition (b, t)
+ *   q_total = Mix(theta;  q_taken[b, t, :], state[b, t])
+ *   y_total = reward + gamma (1 - terminated) Mix(theta-; next_max[b, t, :], state[b, t + 1])
+ *   td_err  = filled ? y_total - q_total : 0
+ * state [B, T+1, S]; q_taken, next_max [B, T, N] doubles; outputs [B, T] doubles.
+ */
+void mixer_td(int N, int M, int S, const float *w_online, const float *w_target, int B, int T,
+              const float *state, const double *q_taken, const double *next_max, const float *reward,
+              const uint8_t *terminated, const uint8_t *filled, float gamma,
+              double *q_total, double *y_total, double *td_err)
+{
+    mixer_t on, tg;
+    mixer_bind(&on, N, M, S, w_online);
+    mixer_bind(&tg, N, M, S, w_target);
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t) {
+            const long i = (long)b * T + t;
+            const float *s_now = state + ((long)b * (T + 1) + t) * S;
+            const float *s_next = s_now + S;
+            const double qt = mix(&on, q_taken + i * N, s_now);
+            const double boot = mix(&tg, next_max + i * N, s_next);
+            const double y = (double)reward[i] + (double)gamma * (terminated[i] ? 0.0 : 1.0) * boot;
+            q_total[i] = qt;
+            y_total[i] = y;
+            td_err[i] = filled[i] ? y - qt : 0.0;
+        }
+}

@@ -166,3 +166,79 @@ def make_unroll_inputs(cfg, B=None, T=None, stream=0):
     reward = rng.standard_normal((B, T)).astype(np.float32) * filled
     return dict(obs=obs, avail=avail, actions=actions, reward=reward, terminated=terminated,
                 filled=filled, gamma=float(cfg["gamma"]), lengths=L)
+
+
+# ------------------------------------------------------------------ mixing network (learner, Alg. 3)
+# Global state sizes of Table 2 for the four scenarios; the scale-up workload has no counterpart.
+STATE_DIMS = [48, 168, 120, 98, 512]
+MIX_EMBED = 32
+
+
+def mixer_dims(cfg):
+    """(N agents, M hidden units of the mixer, S state size)."""
+    return (cfg["N"], MIX_EMBED, STATE_DIMS[cfg["index"]] if "S" not in cfg else cfg["S"])
+
+
+def mixer_param_count(N, M, S):
+    return (N * M + 3 * M) * (S + 1) + M + 1
+
+
+def mixer_slices(N, M, S):
+    """Offsets of each tensor in the packed mixer parameter vector, in packing order."""
+    shapes = [("Hw1", (N * M, S)), ("hb1", (N * M,)), ("Hb1", (M, S)), ("hbb1", (M,)), ("Hw2", (M, S)),
+              ("hb2", (M,)), ("V1", (M, S)), ("c1", (M,)), ("v2", (M,)), ("c2", (1,))]
+    out, off = {}, 0
+    for name, shp in shapes:
+        n = int(np.prod(shp))
+        out[name] = (off, off + n, shp)
+        off += n
+    return out
+
+
+def pack_mixer(dims_, parts):
+    sl = mixer_slices(*dims_)
+    w = np.zeros(mixer_param_count(*dims_), np.float32)
+    for k, (a, b, shp) in sl.items():
+        w[a:b] = np.asarray(parts[k], np.float32).reshape(-1)
+    return w
+
+
+def make_mixer_weights(cfg, stream=0):
+    """Matrices uniform with the fan-in bound 1/sqrt(S) (1/sqrt(M) for v2), biases U(-0.05, 0.05)."""
+    dims_ = mixer_dims(cfg)
+    rng = np.random.default_rng([cfg["seed"], 4000 + stream])
+    parts = {}
+    for name, (_, _, shp) in mixer_slices(*dims_).items():
+        if len(shp) == 2:
+            bound = 1.0 / np.sqrt(shp[1])
+            parts[name] = rng.uniform(-bound, bound, shp)
+        elif name == "v2":
+            parts[name] = rng.uniform(-1.0, 1.0, shp) / np.sqrt(shp[0])
+        else:
+            parts[name] = rng.uniform(-0.05, 0.05, shp)
+    return pack_mixer(dims_, parts)
+
+
+def make_mixer_inputs(cfg, B=None, T=None, stream=0):
+    """The learner batch as the mixer sees it: global states of all T+1 slots, the agents' chosen
+    values and bootstrap values per transition (values of the size the Q-network emits), and the
+    batch's reward / terminated / filled arrays (same episode-length recipe as the unroll)."""
+    cfg = dict(cfg)
+    if T is not None:
+        cfg["T"] = T
+    B = cfg["B"] if B is None else B
+    T, N = cfg["T"], cfg["N"]
+    S = mixer_dims(cfg)[2]
+    rng = np.random.default_rng([cfg["seed"], 5000 + stream])
+    L, term = _lengths(rng, cfg, B)
+    state = rng.random((B, T + 1, S), dtype=np.float32)
+    state[rng.random(state.shape, dtype=np.float32) < 0.3] = 0.0
+    state[np.arange(T + 1)[None, :] > L[:, None]] = 0.0
+    q_taken = (rng.standard_normal((B, T, N)) * 0.5).astype(np.float32)
+    next_max = (rng.standard_normal((B, T, N)) * 0.5 + 0.3).astype(np.float32)
+    step = np.arange(T)[None, :]
+    filled = (step < L[:, None]).astype(np.uint8)
+    terminated = ((step == (L[:, None] - 1)) & term[:, None]).astype(np.uint8)
+    reward = rng.standard_normal((B, T)).astype(np.float32) * filled
+    return dict(state=state, q_taken=q_taken, next_max=next_max, reward=reward, terminated=terminated,
+                filled=filled, gamma=float(cfg["gamma"]))

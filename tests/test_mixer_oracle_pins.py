@@ -1,0 +1,149 @@
+"""Pins of the mixing-network oracle (oracle/mixer_oracle.c) against things it did not produce:
+the monotonicity that defines the mixer, closed forms on hand-set parameters, one-hot states
+against explicit column picks, a tensor-library evaluation, and TD targets worked out by hand.
+The paper (learner step, Alg. 3; state sizes, Table 2) prints no mixer values, so there is no
+golden file for it."""
+import numpy as np
+import pytest
+
+from oracle import mixer_oracle as mxo
+from paper_2205_05248_amd import workloads as wl
+
+
+def zero_parts(dims):
+    return {k: np.zeros(shp, np.float32) for k, (_, _, shp) in wl.mixer_slices(*dims).items()}
+
+
+def test_param_count_matches_the_packing():
+    for dims in [(3, 32, 48), (8, 32, 168), (1, 16, 5), (64, 32, 512)]:
+        assert mxo.param_count(*dims) == wl.mixer_param_count(*dims)
+        assert list(wl.mixer_slices(*dims).values())[-1][1] == wl.mixer_param_count(*dims)
+
+
+def test_q_total_never_decreases_in_an_agent_value():
+    """The property the mixer exists for.  A sign slip on any generated weight breaks it."""
+    rng = np.random.default_rng(7)
+    for trial in range(20):
+        N, M, S = int(rng.integers(1, 9)), int(rng.integers(1, 6)) * 8, int(rng.integers(1, 40))
+        w = (rng.standard_normal(wl.mixer_param_count(N, M, S)) * 0.7).astype(np.float32)
+        R = 32
+        q = rng.standard_normal((R, N)) * 2
+        s = rng.standard_normal((R, S)).astype(np.float32)
+        base = mxo.forward((N, M, S), w, q, s)
+        for n in range(N):
+            up = q.copy(); up[:, n] += rng.random(R) * 3
+            assert (mxo.forward((N, M, S), w, up, s) >= base - 1e-12).all()
+
+
+def test_closed_form_constant_weights_both_elu_branches():
+    """All state maps zero: W1 = |hb1| = c, w2 = |hb2| = d (biases set NEGATIVE, so a missing
+    absolute value flips the result), b1 = 0, offset = c2.  Then
+    Q_total = M d elu(c sum_n q_n) + c2."""
+    N, M, S = 4, 16, 6
+    c, d, c2 = 0.75, 0.5, -1.25
+    p = zero_parts((N, M, S))
+    p["hb1"][:] = -c; p["hb2"][:] = -d; p["c2"][:] = c2
+    p["c1"][:] = -1.0; p["v2"][:] = 3.0                 # relu(-1) = 0: contributes nothing
+    w = wl.pack_mixer((N, M, S), p)
+    q = np.array([[0.5, 0.25, 1.0, 0.25], [-1.0, -0.5, 0.25, -0.75], [0, 0, 0, 0]], np.float64)
+    s = np.random.default_rng(1).standard_normal((3, S)).astype(np.float32)
+    got = mxo.forward((N, M, S), w, q, s)
+    tot = q.sum(-1)
+    want = np.array([M * d * (c * tot[0]) + c2, M * d * (np.exp(c * tot[1]) - 1.0) + c2, c2])
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+    assert tot[0] > 0 > tot[1]
+
+
+def test_closed_form_offset_and_hidden_bias():
+    """Hand numbers.  S = 2, M = 2, N = 1, state (2, -1).
+    offset: V1 = [[1, 1], [1, 3]], c1 = (0.5, 0.5) -> pre-activations (1.5, -0.5) -> relu (1.5, 0);
+    v2 = (2, 7), c2 = 0.25 -> v = 3.25.
+    hidden: Hb1 = [[0.5, 0], [0, 1]], hbb1 = (0, 0.5) -> b1 = (1, -0.5); W1 = |hb1| = (1, 2); q = 0.5
+    -> pre (1.5, 0.5) -> elu (1.5, 0.5); w2 = |Hw2 s + hb2| with Hw2 = [[-1, 0], [0, 2]], hb2 = 0 -> (2, 2)
+    Q_total = 2*1.5 + 2*0.5 + 3.25 = 7.25."""
+    dims = (1, 2, 2)
+    p = zero_parts(dims)
+    p["V1"][:] = [[1, 1], [1, 3]]; p["c1"][:] = 0.5; p["v2"][:] = [2, 7]; p["c2"][:] = 0.25
+    p["Hb1"][:] = [[0.5, 0], [0, 1]]; p["hbb1"][:] = [0, 0.5]
+    p["hb1"][:] = [1, -2]
+    p["Hw2"][:] = [[-1, 0], [0, 2]]
+    got = mxo.forward(dims, wl.pack_mixer(dims, p), np.array([[0.5]]), np.array([[2.0, -1.0]], np.float32))
+    np.testing.assert_allclose(got, [7.25], rtol=0, atol=1e-12)
+
+
+def test_one_hot_state_picks_columns():
+    """With state e_k every generated quantity is column k of its matrix plus the bias: the
+    expected value is assembled here by explicit indexing (no matrix product), so a transposed
+    matrix or a wrong (agent, unit) order in Hw1 shows."""
+    rng = np.random.default_rng(3)
+    N, M, S = 3, 8, 5
+    dims = (N, M, S)
+    w = rng.standard_normal(wl.mixer_param_count(*dims)).astype(np.float32)
+    sl = {k: w[a:b].reshape(shp).astype(np.float64) for k, (a, b, shp) in wl.mixer_slices(*dims).items()}
+    q = rng.standard_normal((S, N))
+    got = mxo.forward(dims, w, q, np.eye(S, dtype=np.float32))
+    for k in range(S):
+        total = sl["c2"][0]
+        for m in range(M):
+            pre = sl["Hb1"][m, k] + sl["hbb1"][m]
+            for n in range(N):
+                pre += q[k, n] * abs(sl["Hw1"][n * M + m, k] + sl["hb1"][n * M + m])
+            hid = pre if pre > 0 else np.expm1(pre)
+            total += abs(sl["Hw2"][m, k] + sl["hb2"][m]) * hid
+            total += sl["v2"][m] * max(sl["V1"][m, k] + sl["c1"][m], 0.0)
+        assert abs(got[k] - total) < 1e-9
+
+
+def test_against_a_tensor_library():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    rng = np.random.default_rng(11)
+    for cfg_i in (0, 1, 3):
+        cfg = wl.config(cfg_i)
+        N, M, S = dims = wl.mixer_dims(cfg)
+        w = wl.make_mixer_weights(cfg)
+        R = 40
+        q = rng.standard_normal((R, N)); s = rng.random((R, S)).astype(np.float32)
+        t = {k: torch.from_numpy(w[a:b].reshape(shp).astype(np.float64)) for k, (a, b, shp) in wl.mixer_slices(*dims).items()}
+        ts, tq = torch.from_numpy(s.astype(np.float64)), torch.from_numpy(q)
+        W1 = torch.abs(F.linear(ts, t["Hw1"], t["hb1"])).view(R, N, M)
+        hid = F.elu(torch.bmm(tq.view(R, 1, N), W1).view(R, M) + F.linear(ts, t["Hb1"], t["hbb1"]))
+        w2 = torch.abs(F.linear(ts, t["Hw2"], t["hb2"]))
+        v = F.relu(F.linear(ts, t["V1"], t["c1"])) @ t["v2"] + t["c2"]
+        want = (hid * w2).sum(-1) + v
+        np.testing.assert_allclose(mxo.forward(dims, w, q, s), want.numpy(), rtol=0, atol=1e-10)
+
+
+def test_td_targets_by_hand():
+    """Mixers reduced to Q_total = c2 + M d c sum_n q_n (positive sums only), online and target
+    with different constants: every output follows by hand.  Terminated transitions drop the
+    bootstrap, unfilled ones have zero error, the bootstrap uses the NEXT slot's state (the target
+    mixer here reads it through its offset term)."""
+    N, M, S = 2, 8, 3
+    dims = (N, M, S)
+    def constant(c, d, c2, state_gain=0.0):
+        p = zero_parts(dims)
+        p["hb1"][:] = -c; p["hb2"][:] = d; p["c2"][:] = c2
+        p["V1"][0, 0] = 1.0; p["v2"][0] = state_gain          # offset += gain * relu(state[0])
+        return wl.pack_mixer(dims, p)
+    w_on, w_tg = constant(0.5, 0.25, 1.0), constant(1.0, 0.125, -2.0, state_gain=10.0)
+    B, T = 2, 3
+    state = np.zeros((B, T + 1, S), np.float32)
+    state[:, :, 0] = [[0.1, 0.2, 0.3, 0.4], [0.5, 0.6, 0.7, 0.8]]
+    q_taken = np.full((B, T, N), 0.5); next_max = np.full((B, T, N), 1.0)
+    q_taken[1, 2] = [0.25, 0.75]; next_max[0, 1] = [2.0, 0.0]
+    reward = np.array([[1.0, -1.0, 0.5], [0.0, 2.0, 0.0]], np.float32)
+    terminated = np.array([[0, 0, 1], [0, 0, 0]], np.uint8)
+    filled = np.array([[1, 1, 1], [1, 1, 0]], np.uint8)
+    gamma = 0.5
+    out = mxo.td(dims, w_on, w_tg, state, q_taken, next_max, reward, terminated, filled, gamma)
+    q_tot = 1.0 + M * 0.25 * 0.5 * q_taken.sum(-1)                       # = 1 + sum
+    boot = -2.0 + M * 0.125 * 1.0 * next_max.sum(-1) + 10.0 * state[:, 1:, 0]
+    y = reward + gamma * (1 - terminated) * boot
+    np.testing.assert_allclose(out["q_total"], q_tot, atol=1e-6)        # states are float32 inputs
+    np.testing.assert_allclose(out["y_total"], y, atol=1e-6)
+    np.testing.assert_allclose(out["td_err"], (y - q_tot) * filled, atol=1e-6)
+    assert out["y_total"][0, 2] == reward[0, 2] and out["td_err"][1, 2] == 0.0
+    assert abs(out["y_total"][0, 0] - (1.0 + 0.5 * (-2.0 + 2.0 + 2.0))) < 1e-6   # next slot's state 0.2
+    same = mxo.td(dims, w_on, None, state, q_taken, next_max, reward, terminated, filled, gamma)
+    np.testing.assert_allclose(same["y_total"], reward + gamma * (1 - terminated) * (1.0 + next_max.sum(-1)), atol=1e-6)
