@@ -22,12 +22,19 @@ EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_a
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
+# include/marl_mixer.h
+MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td"]
 
 
 class MarlError(RuntimeError):
     def __init__(self, status, text):
         super().__init__(f"marl_qnet error {status}: {text}")
         self.status = status
+
+
+class MixerDesc(ctypes.Structure):
+    _fields_ = [("n_agents", ctypes.c_int32), ("embed", ctypes.c_int32), ("state_dim", ctypes.c_int32),
+                ("weight_dtype", ctypes.c_int32), ("device", ctypes.c_int32)]
 
 
 class Desc(ctypes.Structure):
@@ -80,6 +87,14 @@ def load():
         lib.marl_strerror.argtypes = [ctypes.c_int]
         lib.marl_last_device_error.restype = ctypes.c_char_p
         lib.marl_last_device_error.argtypes = []
+        lib.marl_mixer_param_count.restype = ctypes.c_size_t
+        lib.marl_mixer_param_count.argtypes = [ctypes.POINTER(MixerDesc)]
+        lib.marl_mixer_create.restype = ctypes.c_int
+        lib.marl_mixer_create.argtypes = [ctypes.POINTER(MixerDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+        lib.marl_mixer_destroy.restype = None
+        lib.marl_mixer_destroy.argtypes = [vp]
+        lib.marl_mixer_td.restype = ctypes.c_int
+        lib.marl_mixer_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -233,6 +248,60 @@ class QNet:
     def close(self):
         if self.handle:
             marl_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ------------------------------------------------------------------ mixing network (include/marl_mixer.h)
+def marl_mixer_param_count(n_agents, embed, state_dim, weight_dtype=MARL_DTYPE_F32, device=0):
+    d = MixerDesc(n_agents, embed, state_dim, weight_dtype, device)
+    return int(load().marl_mixer_param_count(ctypes.byref(d)))
+
+
+def marl_mixer_create(n_agents, embed, state_dim, weight_dtype, device, host_weights):
+    w = np.ascontiguousarray(host_weights, dtype=np.float32)
+    d = MixerDesc(n_agents, embed, state_dim, weight_dtype, device)
+    out = ctypes.c_void_p()
+    check(load().marl_mixer_create(ctypes.byref(d), w.ctypes.data_as(ctypes.c_void_p), w.size, ctypes.byref(out)))
+    return out.value
+
+
+def marl_mixer_destroy(handle):
+    load().marl_mixer_destroy(ctypes.c_void_p(handle))
+
+
+def marl_mixer_td(online, target, dims, state, q_taken, next_max, reward, terminated, filled, gamma,
+                  q_total, y_total, td_err):
+    N, M, S = dims
+    B, T = int(state.shape[0]), int(state.shape[1]) - 1
+    check(load().marl_mixer_td(
+        ctypes.c_void_p(online), ctypes.c_void_p(target) if target else None, B, T,
+        _dev(state, "f32", (B, T + 1, S), "state"), _dev(q_taken, "f32", (B, T, N), "q_taken"),
+        _dev(next_max, "f32", (B, T, N), "next_max"), _dev(reward, "f32", (B, T), "reward"),
+        _dev(terminated, "u8", (B, T), "terminated"), _dev(filled, "u8", (B, T), "filled"), float(gamma),
+        _dev(q_total, "f32", (B, T), "q_total", optional=True), _dev(y_total, "f32", (B, T), "y_total", optional=True),
+        _dev(td_err, "f32", (B, T), "td_err", optional=True), _stream()))
+
+
+class Mixer:
+    """Thin owner of a marl_mixer handle."""
+
+    def __init__(self, dims, weights, dtype="fp32", device=0):
+        self.dims = tuple(int(v) for v in dims)
+        self.handle = marl_mixer_create(*self.dims, DTYPES[dtype], device, weights)
+
+    def td(self, target, state, q_taken, next_max, reward, terminated, filled, gamma, q_total, y_total, td_err):
+        marl_mixer_td(self.handle, None if target is None else target.handle, self.dims, state, q_taken, next_max,
+                      reward, terminated, filled, gamma, q_total, y_total, td_err)
+
+    def close(self):
+        if self.handle:
+            marl_mixer_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -102,6 +102,10 @@ hipEvent_t *take_events(marl_qnet *q, int count, int *rc)
 
 }  // namespace
 
+namespace marl {
+int report_device_error(hipError_t err, const char *what) { return device_fail(err, what); }
+}  // namespace marl
+
 extern "C" {
 
 size_t marl_param_count(const marl_qnet_desc *desc)

@@ -1,0 +1,333 @@
+// Mixing network of the learner step (include/marl_mixer.h): handle, packing, kernel, entry points.
+//
+// The work is one dense contraction, [ (N + 3) M generated quantities x S ] . [ S x B T states ],
+// followed by a cheap per-transition combination, done for the online mixer on state[b, t] and for
+// the target mixer on state[b, t + 1].  A workgroup of four wavefronts takes 64 consecutive
+// transitions, one tile of 16 per wave; a wave keeps its tile's states in registers as MFMA B
+// operands (bf16, plus the bf16 remainder for fp32 parameters) for a whole pass.  The state
+// matrices stream past as A-operand fragments, one block of 16 generated quantities at a time:
+// the block's fragments are copied global -> registers -> LDS by all four waves while the previous
+// block is being multiplied, so every wave reads them from LDS and L2 sees each block once per
+// workgroup.  A block's 16 x 16 result lands with lane (row c, quarter q) holding quantities
+// 4 q .. 4 q + 3 of row c, and is folded into the running mix right away:
+//   blocks of agent n        hidden += q[n] |result + hb1|
+//   blocks of b1             hidden += result + hbb1
+//   blocks of w2             total  += |result + hb2| elu(hidden)     (hidden is complete by then)
+//   blocks of the offset     total  += v2 relu(result + c1)
+// and at the end the row's four lanes add their totals.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "../../include/marl_mixer.h"
+#include "fused16.h"
+#include "qnet_internal.h"
+
+struct marl_mixer {
+    marl_mixer_desc desc;
+    int planes;                  // 1: bf16 matrices, 2: bf16 + remainder
+    int ks;                      // k-steps of 32 over the state
+    void *image;                 // device: fragments, then the fp32 tables
+    const marl::bf16x8 *frags;   // [(N + 3) M / 16][ks][planes][64]
+    const float *bias;           // [(N + 3) M]: hb1 | hbb1 | hb2 | c1
+    const float *v2;             // [M]
+    float c2;
+};
+
+namespace marl {
+namespace {
+
+constexpr int kMixWaves = 4, kMixThreads = 64 * kMixWaves;
+
+struct MixerArgs {
+    const bf16x8 *frags[2];
+    const float *bias[2], *v2[2];
+    float c2[2];
+    int N, S, ks, rows, T;
+    const float *state, *q[2], *reward;
+    const uint8_t *terminated, *filled;
+    float gamma;
+    float *q_total, *y_total, *td_err;
+};
+
+// KSM: the most k-steps a wave's state registers hold (KSM * P * 4 registers).
+template <int MB, int P, int KSM>
+__global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = a.N, S = a.S, KS = a.ks, T = a.T;
+    const int row = (blockIdx.x * kMixWaves + wave) * 16 + c;      // transition b T + t
+    const bool valid = row < a.rows;
+    const int rr = valid ? row : a.rows - 1;                       // rows past the end re-read the last one
+    const int b = rr / T, t = rr % T;
+    const int n_blocks = (N + 3) * MB;
+    const int chunk_vecs = KS * P * 64;                            // 16-byte vectors of one block
+    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);           // [2][chunk_vecs]
+    constexpr int kStage = (KSM * P * 64 + kMixThreads - 1) / kMixThreads;      // vectors per thread and block
+
+    float mixed[2];
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        // pass 0: online mixer, chosen values, state of the slot; pass 1: target mixer,
+        // bootstrap values, state of the next slot
+        const bf16x8 *frags = a.frags[pass];
+        const float *bias = a.bias[pass];
+        const float *srow = a.state + ((size_t)b * (T + 1) + t + pass) * S;
+        const float *qrow = a.q[pass] + (size_t)rr * N;
+        Frag<P> st[KSM];
+#pragma unroll
+        for (int ks = 0; ks < KSM; ++ks)
+            if (ks < KS) {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int k = 32 * ks + 8 * q4 + i;
+                    v[i] = k < S ? srow[k] : 0.0f;
+                }
+                st[ks] = to_frag<P>(v);
+            }
+        bf16x8 stage[kStage];
+        auto fetch = [&](int blk) {                // the block's fragments, this thread's share
+            const bf16x8 *src = frags + (size_t)blk * chunk_vecs;
+#pragma unroll
+            for (int i = 0; i < kStage; ++i) {
+                const int at = i * kMixThreads + threadIdx.x;
+                if (at < chunk_vecs) stage[i] = src[at];
+            }
+        };
+        auto stash = [&](int blk) {
+            bf16x8 *dst = buf + (size_t)(blk & 1) * chunk_vecs;
+#pragma unroll
+            for (int i = 0; i < kStage; ++i) {
+                const int at = i * kMixThreads + threadIdx.x;
+                if (at < chunk_vecs) dst[at] = stage[i];
+            }
+        };
+        fetch(0);
+        lds_barrier();                             // the previous pass has finished reading both buffers
+        stash(0);
+        lds_barrier();
+        f32x4 hidden[MB];
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) hidden[j][r] = 0.0f;
+        float total = 0.0f;
+        float qn = qrow[0];
+        for (int blk = 0; blk < n_blocks; ++blk) {
+            if (blk + 1 < n_blocks) fetch(blk + 1);
+            const int group = blk / MB, j = blk % MB;              // group: agents 0 .. N-1, then b1, w2, offset
+            const float q_next = qrow[min(group + 1, N - 1)];
+            const bf16x8 *src = buf + (size_t)(blk & 1) * chunk_vecs + lane;
+            f32x4 acc = load_feature4(bias, blk, q4);
+#pragma unroll
+            for (int ks = 0; ks < KSM; ++ks)
+                if (ks < KS) {
+                    WFrag<P> w;
+                    w.hi = src[(ks * P) * 64];
+                    if constexpr (P == 2) w.lo = src[(ks * P + 1) * 64];
+                    mma16<P>(acc, w, st[ks]);
+                }
+            if (group < N) {
+#pragma unroll
+                for (int jj = 0; jj < MB; ++jj)
+                    if (jj == j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) hidden[jj][r] = fmaf(qn, fabsf(acc[r]), hidden[jj][r]);
+                if (j == MB - 1) qn = q_next;
+            } else if (group == N) {
+#pragma unroll
+                for (int jj = 0; jj < MB; ++jj)
+                    if (jj == j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) hidden[jj][r] += acc[r];
+            } else if (group == N + 1) {
+#pragma unroll
+                for (int jj = 0; jj < MB; ++jj)
+                    if (jj == j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const float x = hidden[jj][r];
+                            total = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total);
+                        }
+            } else {
+                const f32x4 gain = load_feature4(a.v2[pass], j, q4);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) total = fmaf(gain[r], fmaxf(acc[r], 0.0f), total);
+            }
+            if (blk + 1 < n_blocks) stash(blk + 1);
+            lds_barrier();
+        }
+        total += __shfl_xor(total, 16);
+        total += __shfl_xor(total, 32);
+        mixed[pass] = total + a.c2[pass];
+    }
+    if (valid && q4 == 0) {
+        const float y = a.reward[row] + a.gamma * (a.terminated[row] ? 0.0f : 1.0f) * mixed[1];
+        if (a.q_total) a.q_total[row] = mixed[0];
+        if (a.y_total) a.y_total[row] = y;
+        if (a.td_err) a.td_err[row] = a.filled[row] ? y - mixed[0] : 0.0f;
+    }
+}
+
+template <int MB, int P, int KSM>
+hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((a.rows + 16 * kMixWaves - 1) / (16 * kMixWaves))), block(kMixThreads);
+    const size_t lds = (size_t)2 * a.ks * P * 1024;
+    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KSM>>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KSM>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int P, int KSM>
+hipError_t mixer_dispatch(int mb, const MixerArgs &a, hipStream_t stream)
+{
+    switch (mb) {
+    case 1: return mixer_launch<1, P, KSM>(a, stream);
+    case 2: return mixer_launch<2, P, KSM>(a, stream);
+    case 4: return mixer_launch<4, P, KSM>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+bool mixer_desc_valid(const marl_mixer_desc *d, int *why)
+{
+    if (d->weight_dtype != MARL_DTYPE_F32 && d->weight_dtype != MARL_DTYPE_BF16) {
+        *why = MARL_ERR_BAD_DTYPE;
+        return false;
+    }
+    const int s_max = d->weight_dtype == MARL_DTYPE_BF16 ? MARL_MIXER_MAX_STATE_BF16 : MARL_MIXER_MAX_STATE_F32;
+    if (d->n_agents < 1 || d->n_agents > MARL_MAX_AGENTS || (d->embed != 16 && d->embed != 32 && d->embed != 64) ||
+        d->state_dim < 1 || d->state_dim > s_max || d->device < 0) {
+        *why = MARL_ERR_BAD_DIM;
+        return false;
+    }
+    return true;
+}
+
+size_t mixer_params(const marl_mixer_desc *d)
+{
+    const size_t N = d->n_agents, M = d->embed, S = d->state_dim;
+    return (N * M + 3 * M) * (S + 1) + M + 1;
+}
+
+struct MixerDeviceGuard {
+    int prev = -1;
+    bool ok = false;
+    explicit MixerDeviceGuard(int dev) { ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(dev) == hipSuccess; }
+    ~MixerDeviceGuard() { if (ok && prev >= 0) (void)hipSetDevice(prev); }
+};
+
+}  // namespace
+}  // namespace marl
+
+extern "C" {
+
+size_t marl_mixer_param_count(const marl_mixer_desc *desc)
+{
+    int why;
+    if (!desc || !marl::mixer_desc_valid(desc, &why)) return 0;
+    return marl::mixer_params(desc);
+}
+
+int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, size_t n_weights, marl_mixer **out)
+{
+    if (!desc || !host_weights || !out) return MARL_ERR_NULL;
+    *out = nullptr;
+    int why;
+    if (!marl::mixer_desc_valid(desc, &why)) return why;
+    if (n_weights != marl::mixer_params(desc)) return MARL_ERR_MISMATCH;
+    const int N = desc->n_agents, M = desc->embed, S = desc->state_dim;
+    const int planes = desc->weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
+    const int ks = (S + 31) / 32, F = (N + 3) * M;
+    const float *Hw1 = host_weights, *hb1 = Hw1 + (size_t)N * M * S, *Hb1 = hb1 + (size_t)N * M, *hbb1 = Hb1 + (size_t)M * S;
+    const float *Hw2 = hbb1 + M, *hb2 = Hw2 + (size_t)M * S, *V1 = hb2 + M, *c1 = V1 + (size_t)M * S, *v2 = c1 + M, *c2 = v2 + M;
+
+    const size_t frag_bytes = (size_t)(F / 16) * ks * planes * 1024;
+    const size_t bytes = frag_bytes + sizeof(float) * (F + M);
+    char *host = static_cast<char *>(std::calloc(1, bytes));
+    if (!host) return MARL_ERR_NOMEM;
+    // generated quantities in the order the kernel walks them: W1 rows (agent-major), b1, w2, offset layer
+    uint16_t *frags = reinterpret_cast<uint16_t *>(host);
+    const size_t per_block = (size_t)ks * planes * 512;
+    marl::pack_frags16(frags, Hw1, N * M, S, S, false, planes);
+    marl::pack_frags16(frags + (size_t)(N * M / 16) * per_block, Hb1, M, S, S, false, planes);
+    marl::pack_frags16(frags + (size_t)((N + 1) * M / 16) * per_block, Hw2, M, S, S, false, planes);
+    marl::pack_frags16(frags + (size_t)((N + 2) * M / 16) * per_block, V1, M, S, S, false, planes);
+    float *bias = reinterpret_cast<float *>(host + frag_bytes);
+    std::memcpy(bias, hb1, sizeof(float) * N * M);
+    std::memcpy(bias + (size_t)N * M, hbb1, sizeof(float) * M);
+    std::memcpy(bias + (size_t)(N + 1) * M, hb2, sizeof(float) * M);
+    std::memcpy(bias + (size_t)(N + 2) * M, c1, sizeof(float) * M);
+    std::memcpy(bias + F, v2, sizeof(float) * M);
+
+    marl_mixer *m = new (std::nothrow) marl_mixer();
+    if (!m) { std::free(host); return MARL_ERR_NOMEM; }
+    m->desc = *desc; m->planes = planes; m->ks = ks; m->c2 = c2[0]; m->image = nullptr;
+    marl::MixerDeviceGuard guard(desc->device);
+    hipError_t err = guard.ok ? hipMalloc(&m->image, bytes) : hipErrorInvalidDevice;
+    if (err == hipSuccess) err = hipMemcpy(m->image, host, bytes, hipMemcpyHostToDevice);
+    std::free(host);
+    if (err != hipSuccess) {
+        if (m->image) (void)hipFree(m->image);
+        delete m;
+        return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : marl::report_device_error(err, "marl_mixer_create");
+    }
+    m->frags = static_cast<const marl::bf16x8 *>(m->image);
+    m->bias = reinterpret_cast<const float *>(static_cast<char *>(m->image) + frag_bytes);
+    m->v2 = m->bias + F;
+    *out = m;
+    return MARL_OK;
+}
+
+void marl_mixer_destroy(marl_mixer *m)
+{
+    if (!m) return;
+    marl::MixerDeviceGuard guard(m->desc.device);
+    if (m->image) (void)hipFree(m->image);
+    delete m;
+}
+
+int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, const float *state,
+                  const float *q_taken, const float *next_max, const float *reward, const uint8_t *terminated,
+                  const uint8_t *filled, float gamma, float *q_total, float *y_total, float *td_err,
+                  void *hip_stream)
+{
+    if (!online) return MARL_ERR_NULL;
+    if (!target) target = online;
+    if (std::memcmp(&online->desc, &target->desc, sizeof(marl_mixer_desc)) != 0) return MARL_ERR_MISMATCH;
+    if (B < 0 || T < 1 || (int64_t)B * T >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+    if (!(std::isfinite(gamma) && gamma >= 0.0f && gamma <= 1.0f)) return MARL_ERR_BAD_ARG;
+    if (B == 0) return MARL_OK;
+    if (!state || !q_taken || !next_max || !reward || !terminated || !filled) return MARL_ERR_NULL;
+    marl::MixerDeviceGuard guard(online->desc.device);
+    if (!guard.ok) return marl::report_device_error(hipErrorInvalidDevice, "hipSetDevice");
+    marl::MixerArgs a{};
+    a.frags[0] = online->frags; a.frags[1] = target->frags;
+    a.bias[0] = online->bias; a.bias[1] = target->bias;
+    a.v2[0] = online->v2; a.v2[1] = target->v2;
+    a.c2[0] = online->c2; a.c2[1] = target->c2;
+    a.N = online->desc.n_agents; a.S = online->desc.state_dim; a.ks = online->ks; a.rows = B * T; a.T = T;
+    a.state = state; a.q[0] = q_taken; a.q[1] = next_max; a.reward = reward; a.terminated = terminated; a.filled = filled;
+    a.gamma = gamma; a.q_total = q_total; a.y_total = y_total; a.td_err = td_err;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const int mb = online->desc.embed / 16;
+    hipError_t err;
+    if (online->planes == 2) {
+        err = a.ks <= 8 ? marl::mixer_dispatch<2, 8>(mb, a, stream) : marl::mixer_dispatch<2, 16>(mb, a, stream);
+    } else {
+        err = a.ks <= 8 ? marl::mixer_dispatch<1, 8>(mb, a, stream)
+            : a.ks <= 16 ? marl::mixer_dispatch<1, 16>(mb, a, stream) : marl::mixer_dispatch<1, 32>(mb, a, stream);
+    }
+    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td launch");
+    return MARL_OK;
+}
+
+}  // extern "C"

@@ -70,6 +70,8 @@ int perm16(int p)
     return 32 * ks + 16 * (idx / 4) + 4 * q + idx % 4;
 }
 
+}  // namespace
+
 // Output: [ceil(M/16)][ceil(K/32)][planes][64][8] bf16.
 void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_perm, int planes)
 {
@@ -89,7 +91,6 @@ void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_
                 }
 }
 
-}  // namespace
 
 bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
 {

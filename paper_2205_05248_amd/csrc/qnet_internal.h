@@ -81,6 +81,15 @@ struct PackedImage {
 };
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
 
+// W [M rows, K columns, leading dimension ld] -> 16x16x32 A-operand fragments
+// [ceil(M/16)][ceil(K/32)][planes][64 lanes][8] bf16, zero padded; plane 1 holds the bf16 remainder.
+// use_perm: k order in which a pair of accumulators is the next operand (see mfma16_tile.h).
+void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_perm, int planes);
+
+// Shared by the C-ABI source files: records the text marl_last_device_error() returns and
+// yields MARL_ERR_DEVICE.
+int report_device_error(hipError_t err, const char *what);
+
 // Launchers (kernels.hip).  All enqueue on `stream` and return the HIP status.
 hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const uint8_t *avail, const float *h_in,
                            const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,

@@ -28,6 +28,13 @@ def test_every_declared_symbol_is_exported(lib):
     for name in declared:
         assert hasattr(lib, name), name
     assert declared == set(binding.EXPORTS)
+    mixer = open(os.path.join(ROOT, "include", "marl_mixer.h")).read()
+    mixer = re.sub(r"/\*.*?\*/", "", mixer, flags=re.S)
+    declared = set(re.findall(r"\b(marl_[a-z_]+)\s*\(", mixer))
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.MIXER_EXPORTS)
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["marl_mixer.h", "marl_qnet.h"]
 
 
 def test_param_count_matches_packing(lib):
@@ -75,3 +82,24 @@ def test_binding_fails_loudly_without_library(monkeypatch):
     monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libmarl_qnet.so")
     with pytest.raises(FileNotFoundError):
         binding.load()
+
+
+def test_mixer_rejects_bad_arguments_before_using_a_device(lib):
+    assert binding.marl_mixer_param_count(3, 32, 48) == wl.mixer_param_count(3, 32, 48)
+    assert binding.marl_mixer_param_count(3, 24, 48) == 0           # embed must be 16, 32 or 64
+    assert binding.marl_mixer_param_count(3, 32, 513) == 0          # fp32 state limit
+    assert binding.marl_mixer_param_count(3, 32, 1024, binding.MARL_DTYPE_BF16) == wl.mixer_param_count(3, 32, 1024)
+    assert binding.marl_mixer_param_count(65, 32, 48) == 0
+    w = np.zeros(wl.mixer_param_count(3, 32, 48), np.float32)
+    wp = w.ctypes.data_as(ctypes.c_void_p)
+    out = ctypes.c_void_p()
+    mk = lambda **k: binding.MixerDesc(**{**dict(n_agents=3, embed=32, state_dim=48, weight_dtype=0, device=0), **k})
+    create = lib.marl_mixer_create
+    assert create(None, wp, w.size, ctypes.byref(out)) == -1
+    assert create(ctypes.byref(mk()), wp, w.size, None) == -1
+    assert create(ctypes.byref(mk(embed=20)), wp, w.size, ctypes.byref(out)) == -2
+    assert create(ctypes.byref(mk(state_dim=0)), wp, w.size, ctypes.byref(out)) == -2
+    assert create(ctypes.byref(mk(weight_dtype=5)), wp, w.size, ctypes.byref(out)) == -3
+    assert create(ctypes.byref(mk()), wp, w.size - 1, ctypes.byref(out)) == -4
+    assert lib.marl_mixer_td(None, None, 1, 1, None, None, None, None, None, None, 0.5, None, None, None, None) == -1
+    lib.marl_mixer_destroy(None)

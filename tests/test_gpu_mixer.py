@@ -1,0 +1,172 @@
+"""GPU parity of the mixing network (include/marl_mixer.h) against its oracle, through the C ABI,
+element by element on the same seeded inputs.
+
+Tolerance: Q_total is a sum of M products w2 * elu(.) whose magnitude grows with the number of
+agents (values up to a few tens on the scale-up workload), so the bound is stated relative to
+the largest reference value of the case: max |gpu - oracle| <= tol * max(1, max |oracle|), with
+tol = 1e-4 for fp32 parameters (bf16 value + remainder products, fp32 accumulation) and 2e-2 for
+bf16 parameters, the same figures the Q-network is held to."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+from oracle import marl_oracle as orc, mixer_oracle as mxo
+from paper_2205_05248_amd import binding, workloads as wl
+
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+
+
+def oracle_mixer_weights(dims, w, dtype):
+    """bf16 mixers compute on the four state matrices rounded to bf16 (by the oracle's own rounding)."""
+    if dtype != "bf16":
+        return w
+    out = np.array(w, np.float32)
+    for name, (a, b, shp) in wl.mixer_slices(*dims).items():
+        if len(shp) == 2:
+            out[a:b] = orc.round_bf16(out[a:b])
+    return out
+
+
+def gpu_td(online, target, m, outputs=("q_total", "y_total", "td_err")):
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    B, T = m["reward"].shape
+    out = {k: (torch.full((B, T), float("nan"), device="cuda") if k in outputs else None)
+           for k in ("q_total", "y_total", "td_err")}
+    online.td(target, dev(m["state"]), dev(m["q_taken"]), dev(m["next_max"]), dev(m["reward"]), dev(m["terminated"]),
+              dev(m["filled"]), m["gamma"], out["q_total"], out["y_total"], out["td_err"])
+    torch.cuda.synchronize()
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+def check(got, ref, tol):
+    worst = 0.0
+    for k in ("q_total", "y_total", "td_err"):
+        if got[k] is None:
+            continue
+        assert np.isfinite(got[k]).all(), k
+        scale = max(1.0, float(np.abs(ref[k]).max()))
+        err = float(np.abs(got[k] - ref[k]).max()) / scale
+        assert err <= tol, f"{k}: max error {err:.3g} of scale {scale:.3g}"
+        worst = max(worst, err)
+    return worst
+
+
+def run_case(cfg, dtype, B=None, T=None, distinct=True, stream=0):
+    dims = wl.mixer_dims(cfg)
+    w_on, w_tg = wl.make_mixer_weights(cfg, 0), wl.make_mixer_weights(cfg, 1)
+    online = binding.Mixer(dims, w_on, dtype)
+    target = binding.Mixer(dims, w_tg, dtype) if distinct else None
+    m = wl.make_mixer_inputs(cfg, B=B, T=T, stream=stream)
+    got = gpu_td(online, target, m)
+    ref = mxo.td(dims, oracle_mixer_weights(dims, w_on, dtype), oracle_mixer_weights(dims, w_tg, dtype) if distinct else None,
+                 m["state"], m["q_taken"], m["next_max"], m["reward"], m["terminated"], m["filled"], m["gamma"])
+    worst = check(got, ref, TOL[dtype])
+    online.close()
+    if target is not None:
+        target.close()
+    return worst
+
+
+@pytest.mark.parametrize("ci", [0, 1, 2, 3])
+def test_mixer_paper_scenarios(ci):
+    """The four scenarios' agent counts, state sizes (Table 2) and time-step limits, whole batch."""
+    cfg = wl.config(ci)
+    run_case(cfg, cfg["dtype"], B=min(cfg["B"], 32))
+
+
+def test_mixer_scaleup_reduced_batch_both_dtypes():
+    cfg = wl.config(4)
+    run_case(cfg, "bf16", B=6)
+    run_case(dict(cfg, S=512), "fp32", B=3)
+
+
+def test_mixer_scaleup_full_size_sampled():
+    """The bench's launch configuration (B = 64, T = 200, 32 agents, state 512, bf16): 200 sampled
+    transitions are evaluated one by one by the oracle; everything else must be finite, padding
+    transitions must have zero error, terminated ones y_total = reward."""
+    cfg = wl.config(4)
+    dims = wl.mixer_dims(cfg)
+    w_on, w_tg = wl.make_mixer_weights(cfg, 0), wl.make_mixer_weights(cfg, 1)
+    online, target = binding.Mixer(dims, w_on, "bf16"), binding.Mixer(dims, w_tg, "bf16")
+    m = wl.make_mixer_inputs(cfg)
+    got = gpu_td(online, target, m)
+    B, T = m["reward"].shape
+    rng = np.random.default_rng(5)
+    pick = rng.choice(B * T, 200, replace=False)
+    b, t = pick // T, pick % T
+    q_ref = mxo.forward(dims, oracle_mixer_weights(dims, w_on, "bf16"), m["q_taken"][b, t], m["state"][b, t])
+    boot = mxo.forward(dims, oracle_mixer_weights(dims, w_tg, "bf16"), m["next_max"][b, t], m["state"][b, t + 1])
+    y_ref = m["reward"][b, t] + np.float32(m["gamma"]) * (1 - m["terminated"][b, t]) * boot
+    scale = max(1.0, np.abs(q_ref).max(), np.abs(y_ref).max())
+    assert np.abs(got["q_total"][b, t] - q_ref).max() <= TOL["bf16"] * scale
+    assert np.abs(got["y_total"][b, t] - y_ref).max() <= TOL["bf16"] * scale
+    for k in got:
+        assert np.isfinite(got[k]).all()
+    assert (got["td_err"][m["filled"] == 0] == 0).all()
+    np.testing.assert_array_equal(got["y_total"][m["terminated"] != 0], m["reward"][m["terminated"] != 0])
+    np.testing.assert_allclose(got["td_err"], (got["y_total"] - got["q_total"]) * m["filled"], atol=1e-5)
+    online.close(); target.close()
+
+
+SHAPES = [
+    # N, M, S, dtype, B, T
+    (1, 16, 1, "fp32", 1, 1),            # the smallest of everything: one transition
+    (2, 16, 31, "fp32", 3, 5),           # one partial k-step, 15 transitions: less than a tile
+    (3, 32, 32, "bf16", 1, 16),          # exactly one tile, one full k-step
+    (5, 64, 33, "fp32", 13, 5),          # one value past a k-step, 65 transitions: one past a workgroup
+    (64, 32, 98, "bf16", 2, 40),         # the most agents
+    (4, 32, 512, "fp32", 2, 9),          # the largest fp32 state
+    (4, 16, 1024, "bf16", 2, 9),         # the largest bf16 state
+    (7, 64, 257, "bf16", 5, 27),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "N%d_M%d_S%d_%s_B%d_T%d" % s)
+def test_mixer_shapes_at_the_edges(shape):
+    N, M, S, dtype, B, T = shape
+    cfg = dict(wl.config(0), N=N, S=S, B=B, T=T, lengths="uniform_all")
+    dims = (N, M, S)
+    w_on, w_tg = (wl.pack_mixer(dims, {k: np.random.default_rng([9, s, i]).uniform(-1, 1, shp) / np.sqrt(max(shp[-1], 1) if len(shp) == 2 else 4)
+                                      for i, (k, (_, _, shp)) in enumerate(wl.mixer_slices(*dims).items())}) for s in (0, 1))
+    online, target = binding.Mixer(dims, w_on, dtype), binding.Mixer(dims, w_tg, dtype)
+    m = wl.make_mixer_inputs(cfg)
+    got = gpu_td(online, target, m)
+    ref = mxo.td(dims, oracle_mixer_weights(dims, w_on, dtype), oracle_mixer_weights(dims, w_tg, dtype), m["state"],
+                 m["q_taken"], m["next_max"], m["reward"], m["terminated"], m["filled"], m["gamma"])
+    check(got, ref, TOL[dtype])
+    online.close(); target.close()
+
+
+def test_mixer_target_defaults_to_online_and_outputs_are_optional():
+    cfg = dict(wl.config(1), B=4, T=11)
+    run_case(cfg, "fp32", distinct=False)
+    dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    mixer = binding.Mixer(dims, w, "fp32")
+    m = wl.make_mixer_inputs(cfg)
+    only = gpu_td(mixer, None, m, outputs=("td_err",))
+    full = gpu_td(mixer, mixer, m)
+    np.testing.assert_array_equal(only["td_err"], full["td_err"])
+    assert only["q_total"] is None
+    other = binding.Mixer((dims[0], 16, dims[2]), wl.pack_mixer((dims[0], 16, dims[2]), {k: np.zeros(s) for k, (_, _, s) in wl.mixer_slices(dims[0], 16, dims[2]).items()}), "fp32")
+    with pytest.raises(binding.MarlError) as err:
+        gpu_td(mixer, other, m)
+    assert err.value.status == -4                     # MARL_ERR_MISMATCH
+    mixer.close(); other.close()
+
+
+def test_mixer_is_monotone_on_the_device():
+    """The defining property, checked on the kernel's own outputs: raising one agent's value never
+    lowers Q_total (beyond rounding)."""
+    cfg = dict(wl.config(3), B=8, T=20)
+    dims = wl.mixer_dims(cfg)
+    mixer = binding.Mixer(dims, wl.make_mixer_weights(cfg), "fp32")
+    m = wl.make_mixer_inputs(cfg)
+    base = gpu_td(mixer, None, m)["q_total"]
+    for n in range(dims[0]):
+        up = dict(m, q_taken=m["q_taken"].copy())
+        up["q_taken"][..., n] += 1.5
+        assert (gpu_td(mixer, None, up)["q_total"] >= base - 1e-4).all()
+    mixer.close()
