@@ -198,6 +198,52 @@ def cpu_baseline(ci, budget_rows=1024):
     }
 
 
+def mixer_section(ci, with_cpu, launches=20):
+    """The mixing network on the same workload's batch (the row after the unroll in the learner
+    step; not part of the timed step above): kernel time from events on the launch stream, and
+    the mixer oracle on a bounded sample of transitions."""
+    import torch
+    from paper_2205_05248_amd import binding, workloads as wl
+    cfg = wl.config(ci)
+    dims = N, M, S = wl.mixer_dims(cfg)
+    B, T = cfg["B"], cfg["T"]
+    w_on, w_tg = wl.make_mixer_weights(cfg, 0), wl.make_mixer_weights(cfg, 1)
+    online, target = binding.Mixer(dims, w_on, cfg["dtype"]), binding.Mixer(dims, w_tg, cfg["dtype"])
+    m = wl.make_mixer_inputs(cfg)
+    d = {k2: torch.from_numpy(np.ascontiguousarray(m[k2])).cuda()
+         for k2 in ("state", "q_taken", "next_max", "reward", "terminated", "filled")}
+    outs = [torch.empty(B, T, device="cuda") for _ in range(3)]
+    call = lambda: online.td(target, d["state"], d["q_taken"], d["next_max"], d["reward"], d["terminated"],
+                             d["filled"], m["gamma"], *outs)
+    for _ in range(3):
+        call()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(launches):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / launches
+    online.close(); target.close()
+    flops = 2 * B * T * 2 * (N * M + 3 * M) * S                  # two mixers, one multiply-add per generated quantity and state value
+    io_bytes = B * (T + 1) * S * 4 + 2 * B * T * N * 4 + B * T * (4 + 2 + 12)
+    out = {"kernel": "mixer_td", "ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "bound": "mfma",
+           "TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK["bf16_TFs"],
+           "GBs": io_bytes / (ms * 1e-3) / 1e9, "hbm_frac": io_bytes / (ms * 1e-3) / 1e9 / PEAK["hbm_GBs"],
+           "config": {"n_agents": N, "embed": M, "state_dim": S, "B": B, "T": T, "mixers": "online + target"}}
+    if with_cpu:
+        from oracle import mixer_oracle as mxo
+        sample_b = max(1, min(B, 4096 // T))
+        t0 = time.perf_counter()
+        mxo.td(dims, w_on, w_tg, m["state"][:sample_b], m["q_taken"][:sample_b], m["next_max"][:sample_b],
+               m["reward"][:sample_b], m["terminated"][:sample_b], m["filled"][:sample_b], m["gamma"])
+        sec = time.perf_counter() - t0
+        out["cpu_oracle"] = {"transitions_per_s": sample_b * T / sec, "cores": 1,
+                             "sample": f"first {sample_b} of {B} episodes, all {T} transitions"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +342,7 @@ def main():
                                   for n, v in kernels.items() if n != "act_step"}},
         "roofline": roofline,
     }
+    out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

@@ -7,8 +7,8 @@
 // operands (bf16, plus the bf16 remainder for fp32 parameters) for a whole pass.  The state
 // matrices stream past as A-operand fragments, one block of 16 generated quantities at a time:
 // the block's fragments are copied global -> registers -> LDS by all four waves while the previous
-// block is being multiplied, so every wave reads them from LDS and L2 sees each block once per
-// workgroup.  A block's 16 x 16 result lands with lane (row c, quarter q) holding quantities
+// blocks are being multiplied (asked for four blocks ahead), so every wave reads them from LDS and
+// L2 sees each block once per workgroup.  A block's 16 x 16 result lands with lane (row c, quarter q) holding quantities
 // 4 q .. 4 q + 3 of row c, and is folded into the running mix right away:
 //   blocks of agent n        hidden += q[n] |result + hb1|
 //   blocks of b1             hidden += result + hbb1
@@ -21,6 +21,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <type_traits>
 
 #include "../../include/marl_mixer.h"
 #include "fused16.h"
@@ -41,34 +42,39 @@ namespace marl {
 namespace {
 
 constexpr int kMixWaves = 4, kMixThreads = 64 * kMixWaves;
+constexpr int kAhead = 4;             // blocks between asking for a block's fragments and multiplying them
 
 struct MixerArgs {
     const bf16x8 *frags[2];
     const float *bias[2], *v2[2];
     float c2[2];
-    int N, S, ks, rows, T;
+    int N, S, ks, rows, T;                 // ks: padded k-steps of the packed fragments
     const float *state, *q[2], *reward;
     const uint8_t *terminated, *filled;
     float gamma;
     float *q_total, *y_total, *td_err;
 };
 
-// KSM: the most k-steps a wave's state registers hold (KSM * P * 4 registers).
-template <int MB, int P, int KSM>
+// KS: k-steps of 32 over the state (the packed fragments are zero past the state's end).
+template <int MB, int P, int KS>
 __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int N = a.N, S = a.S, KS = a.ks, T = a.T;
-    const int row = (blockIdx.x * kMixWaves + wave) * 16 + c;      // transition b T + t
+    const int N = a.N, S = a.S, T = a.T;
+    const int tile_row0 = (blockIdx.x * kMixWaves + wave) * 16;
+    const int row = tile_row0 + c;                                 // transition b T + t
     const bool valid = row < a.rows;
     const int rr = valid ? row : a.rows - 1;                       // rows past the end re-read the last one
     const int b = rr / T, t = rr % T;
-    const int n_blocks = (N + 3) * MB;
-    const int chunk_vecs = KS * P * 64;                            // 16-byte vectors of one block
-    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);           // [2][chunk_vecs]
-    constexpr int kStage = (KSM * P * 64 + kMixThreads - 1) / kMixThreads;      // vectors per thread and block
+    const int n_blocks = (N + 3) * MB, F = n_blocks * 16;
+    constexpr int kChunk = KS * P * 64;                            // 16-byte vectors of one block
+    constexpr int kStage = (kChunk + kMixThreads - 1) / kMixThreads;      // vectors per thread and block
+    // LDS: two block buffers, the pass's bias table, the tiles' agent values [wave][agent][row]
+    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);
+    float *const bias_lds = reinterpret_cast<float *>(lds + (size_t)2 * kChunk * 16);
+    float *const q_lds = bias_lds + F + (size_t)wave * N * 16;
 
     float mixed[2];
 #pragma unroll
@@ -76,41 +82,64 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         // pass 0: online mixer, chosen values, state of the slot; pass 1: target mixer,
         // bootstrap values, state of the next slot
         const bf16x8 *frags = a.frags[pass];
-        const float *bias = a.bias[pass];
         const float *srow = a.state + ((size_t)b * (T + 1) + t + pass) * S;
-        const float *qrow = a.q[pass] + (size_t)rr * N;
-        Frag<P> st[KSM];
+        // Fragments travel global -> registers -> LDS.  A block is asked for kAhead blocks before
+        // it is multiplied (an L2 round trip is several blocks long) into one of kAhead register
+        // sets, indexed by block % kAhead with the loop unrolled over them so that a wait covers
+        // only that set; it moves to LDS one block ahead of its use.  Blocks past the last one
+        // re-read it and contribute nothing, which keeps every step the same straight-line code
+        // with no other global access in it (biases and agent values come from LDS).
+        bf16x8 stage[kAhead][kStage];
+        auto fetch = [&](int set, int blk) {       // the block's fragments, this thread's share
+            const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
 #pragma unroll
-        for (int ks = 0; ks < KSM; ++ks)
-            if (ks < KS) {
-                float v[8];
+            for (int i = 0; i < kStage; ++i) stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
+        };
+        auto stash = [&](int set, int blk) {
+            bf16x8 *dst = buf + (size_t)(blk & 1) * kChunk;
+#pragma unroll
+            for (int i = 0; i < kStage; ++i) {
+                const int at = i * kMixThreads + threadIdx.x;
+                if (at < kChunk) dst[at] = stage[set][i];
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+        lds_barrier();                             // the previous pass has finished with LDS
+        for (int i = threadIdx.x; i < F; i += kMixThreads) bias_lds[i] = a.bias[pass][i];
+        for (int i = lane; i < 16 * N; i += 64) {  // this wave's tile: rows are consecutive in memory
+            const int r = i / N, n = i % N;
+            q_lds[n * 16 + r] = a.q[pass][(size_t)min(tile_row0 + r, a.rows - 1) * N + n];
+        }
+        // The tile's states as B operands: lane (row c, quarter q) holds values 32 ks + 8 q + 0..7.
+        // K-steps wholly inside the row are two 16-byte loads (only 4-byte alignment is assumed);
+        // a partial one is read element by element from positions clamped into the row and
+        // zeroed past its end.
+        const int nfull = S / 32;
+        Frag<P> st[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            float v[8];
+            if (ks < nfull) {
+                f32x4 lo4, hi4;
+                __builtin_memcpy(&lo4, srow + 32 * ks + 8 * q4, 16);
+                __builtin_memcpy(&hi4, srow + 32 * ks + 8 * q4 + 4, 16);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { v[i] = lo4[i]; v[4 + i] = hi4[i]; }
+            } else {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int k = 32 * ks + 8 * q4 + i;
-                    v[i] = k < S ? srow[k] : 0.0f;
+                    const int at = 32 * ks + 8 * q4 + i;
+                    const float x = srow[min(at, S - 1)];
+                    v[i] = at < S ? x : 0.0f;
                 }
-                st[ks] = to_frag<P>(v);
             }
-        bf16x8 stage[kStage];
-        auto fetch = [&](int blk) {                // the block's fragments, this thread's share
-            const bf16x8 *src = frags + (size_t)blk * chunk_vecs;
+            st[ks] = to_frag<P>(v);
+        }
+        f32x4 gain[MB];                            // v2, this lane's units
 #pragma unroll
-            for (int i = 0; i < kStage; ++i) {
-                const int at = i * kMixThreads + threadIdx.x;
-                if (at < chunk_vecs) stage[i] = src[at];
-            }
-        };
-        auto stash = [&](int blk) {
-            bf16x8 *dst = buf + (size_t)(blk & 1) * chunk_vecs;
-#pragma unroll
-            for (int i = 0; i < kStage; ++i) {
-                const int at = i * kMixThreads + threadIdx.x;
-                if (at < chunk_vecs) dst[at] = stage[i];
-            }
-        };
-        fetch(0);
-        lds_barrier();                             // the previous pass has finished reading both buffers
-        stash(0);
+        for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2[pass], j, q4);
+        stash(0, 0);
         lds_barrier();
         f32x4 hidden[MB];
 #pragma unroll
@@ -118,50 +147,54 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
 #pragma unroll
             for (int r = 0; r < 4; ++r) hidden[j][r] = 0.0f;
         float total = 0.0f;
-        float qn = qrow[0];
-        for (int blk = 0; blk < n_blocks; ++blk) {
-            if (blk + 1 < n_blocks) fetch(blk + 1);
-            const int group = blk / MB, j = blk % MB;              // group: agents 0 .. N-1, then b1, w2, offset
-            const float q_next = qrow[min(group + 1, N - 1)];
-            const bf16x8 *src = buf + (size_t)(blk & 1) * chunk_vecs + lane;
-            f32x4 acc = load_feature4(bias, blk, q4);
+        for (int base = 0; base < n_blocks; base += kAhead) {
 #pragma unroll
-            for (int ks = 0; ks < KSM; ++ks)
-                if (ks < KS) {
-                    WFrag<P> w;
-                    w.hi = src[(ks * P) * 64];
-                    if constexpr (P == 2) w.lo = src[(ks * P + 1) * 64];
-                    mma16<P>(acc, w, st[ks]);
+            for (int u = 0; u < kAhead; ++u) {
+                const int blk = base + u;
+                fetch(u, blk + kAhead);                            // this set held block blk, already in LDS
+                const int group = blk / MB, j = blk % MB;          // group: agents 0 .. N-1, then b1, w2, offset
+                const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
+                WFrag<P> w[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    w[ks].hi = src[(ks * P) * 64];
+                    if constexpr (P == 2) w[ks].lo = src[(ks * P + 1) * 64];
                 }
-            if (group < N) {
+                f32x4 acc = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
+                const float qn = q_lds[min(group, N - 1) * 16 + c];
 #pragma unroll
-                for (int jj = 0; jj < MB; ++jj)
-                    if (jj == j)
+                for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[ks]);
+                if (group < N) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) hidden[jj][r] = fmaf(qn, fabsf(acc[r]), hidden[jj][r]);
-                if (j == MB - 1) qn = q_next;
-            } else if (group == N) {
+                    for (int jj = 0; jj < MB; ++jj)
+                        if (jj == j)
 #pragma unroll
-                for (int jj = 0; jj < MB; ++jj)
-                    if (jj == j)
+                            for (int r = 0; r < 4; ++r) hidden[jj][r] = fmaf(qn, fabsf(acc[r]), hidden[jj][r]);
+                } else if (group == N) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) hidden[jj][r] += acc[r];
-            } else if (group == N + 1) {
+                    for (int jj = 0; jj < MB; ++jj)
+                        if (jj == j)
 #pragma unroll
-                for (int jj = 0; jj < MB; ++jj)
-                    if (jj == j)
+                            for (int r = 0; r < 4; ++r) hidden[jj][r] += acc[r];
+                } else if (group == N + 1) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const float x = hidden[jj][r];
-                            total = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total);
-                        }
-            } else {
-                const f32x4 gain = load_feature4(a.v2[pass], j, q4);
+                    for (int jj = 0; jj < MB; ++jj)
+                        if (jj == j)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) total = fmaf(gain[r], fmaxf(acc[r], 0.0f), total);
+                            for (int r = 0; r < 4; ++r) {
+                                const float x = hidden[jj][r];
+                                total = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total);
+                            }
+                } else if (group == N + 2) {
+#pragma unroll
+                    for (int jj = 0; jj < MB; ++jj)
+                        if (jj == j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) total = fmaf(gain[jj][r], fmaxf(acc[r], 0.0f), total);
+                }
+                stash((u + 1) % kAhead, blk + 1);
+                lds_barrier();
             }
-            if (blk + 1 < n_blocks) stash(blk + 1);
-            lds_barrier();
         }
         total += __shfl_xor(total, 16);
         total += __shfl_xor(total, 32);
@@ -175,24 +208,48 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
     }
 }
 
-template <int MB, int P, int KSM>
+template <int MB, int P, int KS>
 hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
 {
     const dim3 grid((unsigned)((a.rows + 16 * kMixWaves - 1) / (16 * kMixWaves))), block(kMixThreads);
-    const size_t lds = (size_t)2 * a.ks * P * 1024;
-    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KSM>>(kLdsLimit);
+    const size_t lds = (size_t)2 * KS * P * 1024 + sizeof(float) * ((size_t)(a.N + 3) * MB * 16 + (size_t)kMixWaves * a.N * 16);
+    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KS>>(kLdsLimit);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KSM>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KS>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
 
-template <int P, int KSM>
+template <int P, int KS>
 hipError_t mixer_dispatch(int mb, const MixerArgs &a, hipStream_t stream)
 {
     switch (mb) {
-    case 1: return mixer_launch<1, P, KSM>(a, stream);
-    case 2: return mixer_launch<2, P, KSM>(a, stream);
-    case 4: return mixer_launch<4, P, KSM>(a, stream);
+    case 1: return mixer_launch<1, P, KS>(a, stream);
+    case 2: return mixer_launch<2, P, KS>(a, stream);
+    case 4: return mixer_launch<4, P, KS>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+// The kernels exist for these numbers of k-steps; a state is padded (with zero fragments) to the next.
+constexpr int kStepChoices[] = {2, 4, 6, 8, 16, 32};
+int padded_ksteps(int S)
+{
+    const int ks = (S + 31) / 32;
+    for (int choice : kStepChoices)
+        if (ks <= choice) return choice;
+    return 0;
+}
+
+template <int P>
+hipError_t mixer_dispatch_ks(int ks, int mb, const MixerArgs &a, hipStream_t stream)
+{
+    switch (ks) {
+    case 2: return mixer_dispatch<P, 2>(mb, a, stream);
+    case 4: return mixer_dispatch<P, 4>(mb, a, stream);
+    case 6: return mixer_dispatch<P, 6>(mb, a, stream);
+    case 8: return mixer_dispatch<P, 8>(mb, a, stream);
+    case 16: return mixer_dispatch<P, 16>(mb, a, stream);
+    case 32: if constexpr (P == 1) return mixer_dispatch<1, 32>(mb, a, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -246,7 +303,7 @@ int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, si
     if (n_weights != marl::mixer_params(desc)) return MARL_ERR_MISMATCH;
     const int N = desc->n_agents, M = desc->embed, S = desc->state_dim;
     const int planes = desc->weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
-    const int ks = (S + 31) / 32, F = (N + 3) * M;
+    const int ks = marl::padded_ksteps(S), F = (N + 3) * M;
     const float *Hw1 = host_weights, *hb1 = Hw1 + (size_t)N * M * S, *Hb1 = hb1 + (size_t)N * M, *hbb1 = Hb1 + (size_t)M * S;
     const float *Hw2 = hbb1 + M, *hb2 = Hw2 + (size_t)M * S, *V1 = hb2 + M, *c1 = V1 + (size_t)M * S, *v2 = c1 + M, *c2 = v2 + M;
 
@@ -257,10 +314,14 @@ int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, si
     // generated quantities in the order the kernel walks them: W1 rows (agent-major), b1, w2, offset layer
     uint16_t *frags = reinterpret_cast<uint16_t *>(host);
     const size_t per_block = (size_t)ks * planes * 512;
-    marl::pack_frags16(frags, Hw1, N * M, S, S, false, planes);
-    marl::pack_frags16(frags + (size_t)(N * M / 16) * per_block, Hb1, M, S, S, false, planes);
-    marl::pack_frags16(frags + (size_t)((N + 1) * M / 16) * per_block, Hw2, M, S, S, false, planes);
-    marl::pack_frags16(frags + (size_t)((N + 2) * M / 16) * per_block, V1, M, S, S, false, planes);
+    auto pack_rows = [&](int first_block, const float *W, int n_rows) {      // blocks of 16 rows, ks k-steps each (zero past S)
+        for (int fb = 0; fb < n_rows / 16; ++fb)
+            marl::pack_frags16(frags + (size_t)(first_block + fb) * per_block, W + (size_t)16 * fb * S, 16, S, S, false, planes);
+    };
+    pack_rows(0, Hw1, N * M);
+    pack_rows(N * M / 16, Hb1, M);
+    pack_rows((N + 1) * M / 16, Hw2, M);
+    pack_rows((N + 2) * M / 16, V1, M);
     float *bias = reinterpret_cast<float *>(host + frag_bytes);
     std::memcpy(bias, hb1, sizeof(float) * N * M);
     std::memcpy(bias + (size_t)N * M, hbb1, sizeof(float) * M);
@@ -320,12 +381,8 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int mb = online->desc.embed / 16;
     hipError_t err;
-    if (online->planes == 2) {
-        err = a.ks <= 8 ? marl::mixer_dispatch<2, 8>(mb, a, stream) : marl::mixer_dispatch<2, 16>(mb, a, stream);
-    } else {
-        err = a.ks <= 8 ? marl::mixer_dispatch<1, 8>(mb, a, stream)
-            : a.ks <= 16 ? marl::mixer_dispatch<1, 16>(mb, a, stream) : marl::mixer_dispatch<1, 32>(mb, a, stream);
-    }
+    if (online->planes == 2) err = marl::mixer_dispatch_ks<2>(a.ks, mb, a, stream);
+    else err = marl::mixer_dispatch_ks<1>(a.ks, mb, a, stream);
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td launch");
     return MARL_OK;
 }
