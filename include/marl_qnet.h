@@ -137,6 +137,25 @@ int marl_act_step(marl_qnet *q, int32_t E,
                   float *h_out, int32_t *action, float *q_out, void *hip_stream);
 
 /*
+ * Decision step for a sub-batch: only the environments listed in env_index are served (the
+ * paper's actors run asynchronously and a worker decides for whichever environments have
+ * delivered a new observation; Sec. "Actor-worker" framework, Alg. 2).
+ *   env_index dev [n_listed] i32   environments to serve, each in [0, E), no duplicates, any order
+ * Every other array is the same E-environment array marl_act_step takes; only the rows of the
+ * listed environments are read and written (h_out may be h_in: the hidden states are then a table
+ * updated in place, one row per agent of a served environment).  The random-number key uses the
+ * environment's own index e, so a listed environment gets exactly the action marl_act_step over
+ * all E environments would give it.  An index outside [0, E) is clamped into the range (the call
+ * cannot check device data); duplicates make the duplicated rows' outputs unspecified.
+ * n_listed = 0 is a no-op.  Runs on the tile32 kernels.  Errors as marl_act_step, plus
+ * MARL_ERR_BAD_DIM for n_listed < 0 or n_listed > E.
+ */
+int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int32_t n_listed,
+                          const float *obs, const uint8_t *avail, const float *h_in,
+                          const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed,
+                          float *h_out, int32_t *action, float *q_out, void *hip_stream);
+
+/*
  * Unroll over a batch of B trajectories of T transitions and form TD targets
  * (learner, Alg. 3).  online and target must have equal descriptions and live on
  * the same device; target may be the same handle as online.

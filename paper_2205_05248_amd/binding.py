@@ -18,7 +18,7 @@ MARL_DTYPE_F32 = 0
 MARL_DTYPE_BF16 = 1
 DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
-EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step",
+EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
@@ -68,6 +68,8 @@ def load():
         lib.marl_qnet_get_desc.argtypes = [vp, ctypes.POINTER(Desc)]
         lib.marl_act_step.restype = ctypes.c_int
         lib.marl_act_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, f32, u64, vp, vp, vp, vp]
+        lib.marl_act_step_indexed.restype = ctypes.c_int
+        lib.marl_act_step_indexed.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, f32, u64, vp, vp, vp, vp]
         lib.marl_unroll_td.restype = ctypes.c_int
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
@@ -163,6 +165,21 @@ def marl_act_step(handle, dims, obs, avail, h_in, reset, step_t, epsilon, seed, 
         _dev(q_out, "f32", (E, N, A), "q_out", optional=True), _stream()))
 
 
+def marl_act_step_indexed(handle, dims, env_index, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action,
+                          q_out=None):
+    """Serves only the environments listed in env_index (device int32 vector); arrays as in marl_act_step."""
+    N, D, A, H = dims
+    E = obs.shape[0]
+    n_listed = int(env_index.shape[0])
+    check(load().marl_act_step_indexed(
+        ctypes.c_void_p(handle), E, _dev(env_index, "i32", (n_listed,), "env_index"), n_listed,
+        _dev(obs, "f32", (E, N, D), "obs"), _dev(avail, "u8", (E, N, A), "avail"),
+        _dev(h_in, "f32", (E, N, H), "h_in"), _dev(reset, "u8", (E,), "reset", optional=True),
+        _dev(step_t, "i32", (E,), "step_t"), float(epsilon), int(seed) & 0xFFFFFFFFFFFFFFFF,
+        _dev(h_out, "f32", (E, N, H), "h_out"), _dev(action, "i32", (E, N), "action"),
+        _dev(q_out, "f32", (E, N, A), "q_out", optional=True), _stream()))
+
+
 def marl_unroll_td(online, target, dims, obs, avail, actions, reward, terminated, filled, gamma,
                    q_taken, next_max, td_target, q_all=None):
     N, D, A, H = dims
@@ -223,6 +240,10 @@ class QNet:
 
     def act_step(self, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
         marl_act_step(self.handle, self.dims, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out)
+
+    def act_step_indexed(self, env_index, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
+        marl_act_step_indexed(self.handle, self.dims, env_index, obs, avail, h_in, reset, step_t, epsilon, seed,
+                              h_out, action, q_out)
 
     def unroll_td(self, target, obs, avail, actions, reward, terminated, filled, gamma,
                   q_taken, next_max, td_target, q_all=None):

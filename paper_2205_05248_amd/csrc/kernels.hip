@@ -30,7 +30,9 @@ namespace marl {
 struct FrontArgs {
     NetFrags net[2];            // ACT: net[0]; projection: online, target (blockIdx.y)
     // decision step
-    int rows;
+    int rows;                   // rows to process: (listed) environments x agents
+    const int32_t *env_index;   // null: environments 0 .. rows/N - 1; else the environments to serve, in any order
+    int n_envs;                 // environments the arrays hold (listed indices are clamped into it)
     const float *obs;
     const uint8_t *avail;
     const float *h_in;
@@ -84,11 +86,14 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
 #pragma unroll
     for (int c = 0; c < NC; ++c) {
         if constexpr (ACT) {
-            row[c] = ((group_id * kFrontWaves + wave) * NC + c) * 32 + col;
-            valid[c] = row[c] < args.rows;
-            e[c] = valid[c] ? row[c] / N : 0;
-            n[c] = valid[c] ? row[c] % N : 0;
-            obs_row[c] = args.obs + (valid[c] ? (size_t)row[c] * D : 0);     // rows past the end read row 0, unused
+            // position in the list of rows to serve -> (environment, agent) -> row of the arrays
+            const int at = ((group_id * kFrontWaves + wave) * NC + c) * 32 + col;
+            valid[c] = at < args.rows;
+            const int listed = valid[c] ? at / N : 0;
+            n[c] = valid[c] ? at % N : 0;
+            e[c] = args.env_index ? min(max(args.env_index[listed], 0), args.n_envs - 1) : listed;
+            row[c] = valid[c] ? e[c] * N + n[c] : 0;                         // positions past the end read row 0, unused
+            obs_row[c] = args.obs + (size_t)row[c] * D;
         } else {
             const int rows = args.B * N, S = args.T + 1, ntiles = (rows + 31) / 32, ngroups = (ntiles + NC - 1) / NC;
             const long work = (long)group_id * kFrontWaves + wave;        // (group of NC row tiles, slot)
@@ -420,14 +425,15 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
 namespace {
 
 template <int H, int P>
-hipError_t act_dispatch(const NetFrags &net, int rows, const float *obs, const uint8_t *avail, const float *h_in,
+hipError_t act_dispatch(const NetFrags &net, int rows, const int32_t *env_index, int n_envs, const float *obs,
+                        const uint8_t *avail, const float *h_in,
                         const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
                         int32_t *action, float *q_out, hipStream_t stream)
 {
     constexpr int RPW = 32 * front_col_blocks(H, P) * kFrontWaves;     // rows per workgroup
     FrontArgs a{};
     a.net[0] = net;
-    a.rows = rows; a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
+    a.rows = rows; a.env_index = env_index; a.n_envs = n_envs; a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
     a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out; a.nets = 1;
     const dim3 grid((unsigned)((rows + RPW - 1) / RPW)), block(kFrontThreads);
     if (net.mb2 == 1) hipLaunchKernelGGL((front_kernel<H, P, 1, true>), grid, block, 0, stream, a);
@@ -474,13 +480,14 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
 
 }  // namespace
 
-hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const uint8_t *avail, const float *h_in,
+hipError_t launch_act_step(const NetFrags &net, int E, const int32_t *env_index, int n_listed, const float *obs,
+                           const uint8_t *avail, const float *h_in,
                            const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
                            int32_t *action, float *q_out, hipStream_t stream)
 {
-    const int rows = E * net.N;
+    const int rows = (env_index ? n_listed : E) * net.N;
 #define MARL_ACT(HH, PP) \
-    return act_dispatch<HH, PP>(net, rows, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream)
+    return act_dispatch<HH, PP>(net, rows, env_index, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream)
     if (net.H == 64 && net.planes == 2) MARL_ACT(64, 2);
     if (net.H == 64 && net.planes == 1) MARL_ACT(64, 1);
     if (net.H == 128 && net.planes == 2) MARL_ACT(128, 2);

@@ -249,8 +249,25 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
     if (takes_fused_path(q, false))
         MARL_HIP(marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
     else
-        MARL_HIP(marl::launch_act_step(q->net, E, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
+        MARL_HIP(marl::launch_act_step(q->net, E, nullptr, 0, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
     if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
+    return MARL_OK;
+}
+
+int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int32_t n_listed, const float *obs,
+                          const uint8_t *avail, const float *h_in, const uint8_t *reset, const int32_t *step_t,
+                          float epsilon, uint64_t seed, float *h_out, int32_t *action, float *q_out, void *hip_stream)
+{
+    if (!q) return MARL_ERR_NULL;
+    if (E < 0 || (int64_t)E * q->desc.n_agents > (int64_t)1 << 30 || n_listed < 0 || n_listed > E) return MARL_ERR_BAD_DIM;
+    if (!unit_interval(epsilon)) return MARL_ERR_BAD_ARG;
+    if (n_listed == 0) return MARL_OK;
+    if (!env_index || !obs || !avail || !h_in || !step_t || !h_out || !action) return MARL_ERR_NULL;
+    if (!aligned16(h_in) || !aligned16(h_out)) return MARL_ERR_BAD_ARG;
+    DeviceGuard guard(q->desc.device);
+    if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    MARL_HIP(marl::launch_act_step(q->net, E, env_index, n_listed, obs, avail, h_in, reset, step_t, epsilon, seed, h_out,
+                                   action, q_out, static_cast<hipStream_t>(hip_stream)));
     return MARL_OK;
 }
 

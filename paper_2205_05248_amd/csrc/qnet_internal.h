@@ -91,7 +91,10 @@ void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_
 int report_device_error(hipError_t err, const char *what);
 
 // Launchers (kernels.hip).  All enqueue on `stream` and return the HIP status.
-hipError_t launch_act_step(const NetFrags &net, int E, const float *obs, const uint8_t *avail, const float *h_in,
+// env_index (device, n_listed entries) null: all E environments; else only the listed ones, whose
+// rows of the E-environment arrays are read and written.
+hipError_t launch_act_step(const NetFrags &net, int E, const int32_t *env_index, int n_listed, const float *obs,
+                           const uint8_t *avail, const float *h_in,
                            const uint8_t *reset, const int32_t *step_t, float epsilon, uint64_t seed, float *h_out,
                            int32_t *action, float *q_out, hipStream_t stream);
 

@@ -453,3 +453,40 @@ def test_calls_replay_from_a_hip_graph(path):
             got = {"h_out": replayed[0].cpu().numpy(), "action": replayed[1].cpu().numpy(), "q": replayed[2].cpu().numpy()}
             pu.compare_act(cfg, ai, got, oracle_act(cfg, w, ai), tol)
     net.close(); target.close()
+
+
+# ------------------------------------------------------------------ asynchronous sub-batch
+@pytest.mark.parametrize("ci,n_listed", [(0, 3), (1, 100), (3, 1), (3, 777), (4, 50)])
+def test_indexed_decision_step_serves_only_the_listed_environments(ci, n_listed):
+    """A random subset of the environments, in random order: their rows get exactly what the oracle
+    gives them in a step over all environments (same random-number key, which uses the environment's
+    own index), every other row of every output keeps its previous contents, and the hidden-state
+    table may be updated in place."""
+    cfg = dict(wl.config(ci))
+    cfg["E"] = min(cfg["E"], 1024)
+    tol = pu.TOL[cfg["dtype"]]
+    N, D, A, H = wl.dims(cfg)
+    net, w = make_net(cfg)
+    inp = wl.make_act_inputs(cfg)
+    E = cfg["E"]
+    listed = np.random.default_rng(ci).permutation(E)[:n_listed].astype(np.int32)
+    ref = oracle_act(cfg, w, inp)
+    d = pu.to_dev(inp, ["obs", "avail", "h_in", "reset", "step_t"])
+    idx = torch.from_numpy(listed).cuda()
+    h_table = d["h_in"].clone()                       # updated in place
+    action = torch.full((E, N), -7, dtype=torch.int32, device="cuda")
+    q = torch.full((E, N, A), -123.0, device="cuda")
+    net.act_step_indexed(idx, d["obs"], d["avail"], h_table, d["reset"], d["step_t"], inp["epsilon"], inp["seed"],
+                         h_table, action, q)
+    torch.cuda.synchronize()
+    served = np.zeros(E, bool); served[listed] = True
+    got = {"h_out": h_table.cpu().numpy(), "action": action.cpu().numpy(), "q": q.cpu().numpy()}
+    sub = lambda x: {k: v[served] for k, v in x.items()}
+    pu.compare_act(cfg, {k: (inp[k][served] if isinstance(inp[k], np.ndarray) else inp[k]) for k in inp}, sub(got),
+                   {k: v[served] for k, v in ref.items()}, tol)
+    np.testing.assert_array_equal(got["h_out"][~served], inp["h_in"][~served])
+    assert (got["action"][~served] == -7).all() and (got["q"][~served] == -123.0).all()
+    with pytest.raises(binding.MarlError) as err:
+        binding.check(binding.load().marl_act_step_indexed(net.handle, E, None, E + 1, *([None] * 5), 0.0, 0, None, None, None, None))
+    assert err.value.status == -2
+    net.close()
