@@ -191,6 +191,28 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
                    float *q_taken, float *next_max, float *td_target, float *q_all,
                    void *hip_stream);
 
+/*
+ * The same unroll with its inputs read in place from a larger pool of episodes (the learner's
+ * experience replay pool, from which Alg. 3 samples B episodes at random): no packed copy of
+ * the batch is made.
+ *   pool_episodes               episodes the input arrays hold
+ *   episode_index dev [B] i32   pool episode of each batch position, each in [0, pool_episodes);
+ *                               repeats are allowed (sampling with replacement)
+ *   obs, avail, actions, reward, terminated, filled: as above with leading dimension
+ *                               pool_episodes instead of B
+ *   outputs: as above, leading dimension B (batch position)
+ * An index outside the range is clamped into it (the call cannot check device data).  Served by
+ * the fused16 kernels only: MARL_ERR_BAD_DIM when the handle's unroll takes the tile32 kernels,
+ * when pool_episodes < 1, or when pool_episodes (T+1) N max(D, A) >= 2^30.  Otherwise errors as
+ * marl_unroll_td.
+ */
+int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_episodes,
+                           const int32_t *episode_index, int32_t B, int32_t T,
+                           const float *obs, const uint8_t *avail, const int32_t *actions,
+                           const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                           float gamma, float *q_taken, float *next_max, float *td_target,
+                           float *q_all, void *hip_stream);
+
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*

@@ -298,10 +298,13 @@ int marl_qnet_set_kernels(marl_qnet *q, int32_t path)
     return MARL_OK;
 }
 
-int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const float *obs,
-                   const uint8_t *avail, const int32_t *actions, const float *reward,
-                   const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
-                   float *next_max, float *td_target, float *q_all, void *hip_stream)
+}  // extern "C"
+
+namespace {
+int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const int32_t *episode_index,
+                int32_t pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
+                const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
+                float *next_max, float *td_target, float *q_all, void *hip_stream)
 {
     if (!online || !target) return MARL_ERR_NULL;
     const marl_qnet_desc &a = online->desc, &b = target->desc;
@@ -311,9 +314,11 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     if (B < 0 || T < 1 || (int64_t)T > (int64_t)1 << 20) return MARL_ERR_BAD_DIM;
     {   // every array is indexed with 32-bit element offsets
         const int64_t widest = a.obs_dim > a.n_actions ? a.obs_dim : a.n_actions;
-        if ((int64_t)B * (T + 1) * a.n_agents * widest >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+        const int64_t episodes = episode_index ? (pool_episodes > B ? pool_episodes : B) : B;
+        if (episodes * (T + 1) * a.n_agents * widest >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
     }
     if (!unit_interval(gamma)) return MARL_ERR_BAD_ARG;
+    if (episode_index && pool_episodes < 1) return MARL_ERR_BAD_DIM;
     if (B == 0) return MARL_OK;
     if (!obs || !avail || !actions || !reward || !terminated || !filled || !q_taken || !next_max || !td_target)
         return MARL_ERR_NULL;
@@ -322,6 +327,7 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     const bool two = online != target;
     const bool fused = takes_fused_path(online, true);
+    if (episode_index && !fused) return MARL_ERR_BAD_DIM;       // the pool is read in place by the fused kernel only
     int rc = MARL_OK;
     if (!fused) {
         const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
@@ -339,7 +345,7 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
     if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
     if (fused) {
         if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
-        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, obs, avail, actions, reward, terminated,
+        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
                                            filled, gamma, q_taken, next_max, td_target, q_all, stream));
         if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
         return MARL_OK;
@@ -349,6 +355,28 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
                                     stream, ev ? ev[1] : nullptr));
     if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
     return MARL_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const float *obs,
+                   const uint8_t *avail, const int32_t *actions, const float *reward, const uint8_t *terminated,
+                   const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
+                   float *q_all, void *hip_stream)
+{
+    return unroll_call(online, target, B, T, nullptr, B, obs, avail, actions, reward, terminated, filled, gamma,
+                       q_taken, next_max, td_target, q_all, hip_stream);
+}
+
+int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_episodes, const int32_t *episode_index,
+                           int32_t B, int32_t T, const float *obs, const uint8_t *avail, const int32_t *actions,
+                           const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
+                           float *q_taken, float *next_max, float *td_target, float *q_all, void *hip_stream)
+{
+    if (B > 0 && !episode_index) return MARL_ERR_NULL;
+    return unroll_call(online, target, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                       filled, gamma, q_taken, next_max, td_target, q_all, hip_stream);
 }
 
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable)

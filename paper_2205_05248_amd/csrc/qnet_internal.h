@@ -116,8 +116,10 @@ hipError_t launch_act_fused(const NetFrags &net, int E, int groups_hint, const f
 // Fused unroll (unroll_fused.hip): no scratch buffer.  `fits` tells whether the network's shape
 // fits the kernel's LDS and register budgets; otherwise the two-kernel path above is used.
 bool unroll_fused_fits(const NetFrags &net);
+// episode_index (device, B entries) null: the input arrays hold the batch itself; else they hold
+// pool_episodes episodes and batch position b reads episode episode_index[b].
 hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
-                               const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
+                               const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream);
 

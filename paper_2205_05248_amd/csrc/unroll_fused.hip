@@ -38,7 +38,8 @@ namespace marl {
 
 template <int H, int P, int AB, bool QALL>
 __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
-    NetFrags online, NetFrags target, int two_nets, int B, int T, const float *__restrict__ obs,
+    NetFrags online, NetFrags target, int two_nets, int B, int T, const int32_t *__restrict__ episode_index,
+    int pool_episodes, const float *__restrict__ obs,
     const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions, const float *__restrict__ reward,
     const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled, float gamma,
     float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target, float *__restrict__ q_all)
@@ -67,7 +68,9 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     const int ks1 = (D + 31) / 32;
     const int row = rt * 16 + c;
     const bool valid = row < rows;                     // rows past the end compute on row 0's inputs; results dropped
-    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+    const int b = valid ? row / N : 0, n = valid ? row % N : 0;         // position in the batch: outputs
+    // episode of the input arrays: the batch position itself, or the listed episode of a larger pool
+    const int bi = episode_index ? min(max(episode_index[b], 0), pool_episodes - 1) : b;
 
     // W_ih -> LDS, all waves.  Its first readers start after kFusedLead barriers.
     {
@@ -108,15 +111,17 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             for (int ks = 0; ks < KS; ++ks) w2[ab][ks] = load_wfrag<P>(net.w2_16 + ((size_t)(ab * KS + ks) * P) * 64 + lane);
         if (lane < 16 * AB) b2_lds[lane] = lane < A ? net.b2[lane] : 0.0f;
         // 32-bit element offsets (the host bounds every array to 2^30 elements)
-        const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // actions / outputs: + t N
-        const uint32_t av0 = ((uint32_t)(b * S) * N + n) * A;     // avail / q_all:     + t N A
-        const uint32_t bt0 = (uint32_t)(b * T);                   // per-episode flags: + t
+        const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // outputs [B, T, N]:       + t N
+        const uint32_t qa0 = ((uint32_t)(b * S) * N + n) * A;     // q_all [B, T+1, N, A]:    + t N A
+        const uint32_t act0 = (uint32_t)(bi * T) * N + n;         // actions of the episode:  + t N
+        const uint32_t av0 = ((uint32_t)(bi * S) * N + n) * A;    // avail of the episode:    + t N A
+        const uint32_t bt0 = (uint32_t)(bi * T);                  // per-episode flags:       + t
         struct SlotIn { int u; uint32_t avail_raw[AB]; float reward; uint8_t on_filled, terminated, tg_filled; };
         auto fetch_slot = [&](int t) {          // inputs of slot t, requested one step before they are used
             SlotIn in{};
             if (t > T) return in;
             if (emit_online && t < T) {
-                in.u = valid ? actions[btn0 + (uint32_t)t * N] : 0;
+                in.u = valid ? actions[act0 + (uint32_t)t * N] : 0;
                 in.on_filled = valid ? filled[bt0 + t] : 0;
             }
             if (emit_target && t >= 1) {
@@ -147,7 +152,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                 }
                 if (emit_online) {
                     if constexpr (QALL) {
-                        if (valid) store_q_row16<AB>(q_all + (av0 + (uint32_t)t * N * A), qv, A, q4);
+                        if (valid) store_q_row16<AB>(q_all + (qa0 + (uint32_t)t * N * A), qv, A, q4);
                     }
                     if (t < T) {
                         const int u = min(max(in.u, 0), A - 1);
@@ -173,7 +178,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         }
     } else if (wave == Sh::kLoader) {
         // ---------------------------------------------------------------- loader wave
-        const float *base = obs + ((size_t)b * S * N + n) * D + 8 * q4;      // the lane's row at slot 0
+        const float *base = obs + ((size_t)bi * S * N + n) * D + 8 * q4;     // the lane's row at slot 0
         const size_t slot_stride = (size_t)N * D;
         ObsStage<H, P> st;
         st.init(D, ks1, q4);
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         fc1.load(net, f, ks1, lane);
         f32x4 b1v[Sh::NBF];
         Fc1Wave<H, P>::load_bias(net, f, n, q4, b1v);
-        const float *touch_row = obs + ((size_t)b * S * N + n) * D;
+        const float *touch_row = obs + ((size_t)bi * S * N + n) * D;
         ObsTouch<H, P, 0> tch;
         tch.init(D, q4);
         auto touch = [&](int c, int s) {             // the slot the loader will load kTouchAhead steps from now
@@ -226,7 +231,7 @@ namespace {
 
 template <int H, int P>
 hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
-                          const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
+                          const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                           const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                           float *next_max, float *td_target, float *q_all, hipStream_t stream)
 {
@@ -241,7 +246,8 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
         auto kernel = unroll_fused_kernel<H, P, ABLK, QA>;                                                          \
         hipError_t err = allow_large_lds<unroll_fused_kernel<H, P, ABLK, QA>>(kLdsLimit);                           \
         if (err != hipSuccess) return err;                                                                          \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, obs, avail, actions,        \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, episode_index, pool_episodes, \
+                           obs, avail, actions,                                                                      \
                            reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);                 \
     } while (0)
 #define MARL_FUSED_Q(ABLK) do { if (q_all) MARL_FUSED(ABLK, true); else MARL_FUSED(ABLK, false); } while (0)
@@ -275,12 +281,12 @@ bool unroll_fused_fits(const NetFrags &net)
 }
 
 hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
-                               const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
+                               const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream)
 {
 #define MARL_GO(HH, PP)                                                                                             \
-    return fused_dispatch<HH, PP>(online, target, two_nets, B, T, obs, avail, actions, reward, terminated, filled,  \
+    return fused_dispatch<HH, PP>(online, target, two_nets, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated, filled,  \
                                   gamma, q_taken, next_max, td_target, q_all, stream)
     if (online.H == 64 && online.planes == 2) MARL_GO(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_GO(64, 1);

@@ -490,3 +490,40 @@ def test_indexed_decision_step_serves_only_the_listed_environments(ci, n_listed)
         binding.check(binding.load().marl_act_step_indexed(net.handle, E, None, E + 1, *([None] * 5), 0.0, 0, None, None, None, None))
     assert err.value.status == -2
     net.close()
+
+
+# ------------------------------------------------------------------ replay pool read in place
+@pytest.mark.parametrize("ci,pool,B", [(0, 9, 4), (1, 40, 24), (3, 50, 70), (4, 12, 7)])
+def test_indexed_unroll_reads_the_batch_from_a_pool(ci, pool, B):
+    """B episodes drawn with replacement from a pool of episodes: the call that reads the pool in place
+    gives, per batch position, exactly what the oracle gives on the gathered batch (and bit for bit
+    what the library's own packed-batch call gives)."""
+    cfg = dict(wl.config(ci), T=min(wl.config(ci)["T"], 25))
+    tol = pu.TOL[cfg["dtype"]]
+    N, D, A, H = wl.dims(cfg)
+    T = cfg["T"]
+    net, w = make_net(cfg)
+    target, w_tg = make_net(cfg, 1)
+    assert net.kernels_in_use(binding.ENTRY_UNROLL_TD) == binding.KERNELS_FUSED16
+    u = wl.make_unroll_inputs(cfg, B=pool)
+    pick = np.random.default_rng(ci + 10).integers(0, pool, B).astype(np.int32)
+    keys = ["obs", "avail", "actions", "reward", "terminated", "filled"]
+    packed = dict(u, **{k: np.ascontiguousarray(u[k][pick]) for k in keys})
+    d = pu.to_dev(u, keys)
+    outs = {k: torch.full((B, T, N), float("nan"), device="cuda") for k in ("q_taken", "next_max", "td_target")}
+    q_all = torch.full((B, T + 1, N, A), float("nan"), device="cuda")
+    net.unroll_td_indexed(target, torch.from_numpy(pick).cuda(), d["obs"], d["avail"], d["actions"], d["reward"],
+                          d["terminated"], d["filled"], u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in outs.items()}
+    got["q_all"] = q_all.cpu().numpy()
+    pu.compare_unroll(got, oracle_unroll(cfg, w, w_tg, packed), tol)
+    same = pu.gpu_unroll(net, target, cfg, packed)
+    for k in got:
+        np.testing.assert_array_equal(got[k], same[k])
+    net.set_kernels(binding.KERNELS_TILE32)
+    with pytest.raises(binding.MarlError) as err:
+        net.unroll_td_indexed(target, torch.from_numpy(pick).cuda(), d["obs"], d["avail"], d["actions"], d["reward"],
+                              d["terminated"], d["filled"], u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
+    assert err.value.status == -2
+    net.close(); target.close()
