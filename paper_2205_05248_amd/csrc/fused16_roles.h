@@ -72,10 +72,12 @@ template <int H, int P> struct GruWave {
                                          const bf16x8 (*x_src)[P][64], f32x4 (&hv)[NBC]) const
     {
         const float *gb = reinterpret_cast<const float *>(lds + Sh::oGBias);
-        // The per-lane offsets are made opaque once per item: otherwise the compiler precomputes
-        // one address register per fragment and keeps them across the loop.  Two bases because
-        // an LDS access encodes at most 64 KB of constant offset.
-        uint32_t lane_off = lane * 16, lane_off_hi = lane * 16 + 65536;
+        // W_ih fragments of this wave: two per-lane base addresses (an LDS access encodes at most
+        // 64 KB of constant offset, the matrix may be larger) that already contain the wave's own
+        // offset, so that every fragment is base + compile-time constant and costs no address
+        // arithmetic.  The bases are made opaque once per item: otherwise the compiler precomputes
+        // one address register per fragment and keeps them all across the loop.
+        uint32_t lane_off = lane * 16 + (NBC * w * KS) * Sh::kFrag, lane_off_hi = lane_off + 65536;
         asm volatile("" : "+v"(lane_off), "+v"(lane_off_hi));
         const char *wih_lane = lds + Sh::oWih + lane_off, *wih_lane_hi = lds + Sh::oWih + lane_off_hi;
         WFrag<P> wi[2][3][NBC];              // W_ih fragments of two k-steps in rotation
@@ -84,7 +86,7 @@ template <int H, int P> struct GruWave {
             for (int gate = 0; gate < 3; ++gate)
 #pragma unroll
                 for (int j = 0; j < NBC; ++j) {
-                    const int off = ((gate * FBK + NBC * w + j) * KS + ks) * Sh::kFrag;
+                    const int off = ((gate * FBK + j) * KS + ks) * Sh::kFrag;      // beyond the wave's own offset
                     wi[ks % 2][gate][j] = load_wfrag<P>(reinterpret_cast<const bf16x8 *>(
                         off + Sh::kFrag <= 65536 ? wih_lane + off : wih_lane_hi + (off - 65536)));
                 }
