@@ -197,11 +197,15 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         f32x4 b1v[Sh::NBF];
         Fc1Wave<H, P>::load_bias(net, f, n, q4, b1v);
         const float *touch_row = obs + ((size_t)bi * S * N + n) * D;
-        ObsTouch<H, P, 0> tch;
+        ObsTouch<H, P, 2> tch;
         tch.init(D, q4);
         auto touch = [&](int c, int s) {             // the slot the loader will load kTouchAhead steps from now
+            const int slot = min(max(s + 3 + kTouchAhead, 0), T);                            // ends: touched twice
             tch.consume(c);
-            tch.touch(c, touch_row + (size_t)min(max(s + 3 + kTouchAhead, 0), T) * N * D);   // ends: touched twice
+            tch.touch(c, touch_row + (size_t)slot * N * D);
+            // and what the epilogues will read for that slot: the row's availability and action
+            tch.set[c][tch.TLO] = avail[(((size_t)bi * S + slot) * N + n) * A];
+            tch.set[c][tch.TLO + 1] = (uint32_t)actions[((size_t)bi * T + min(slot, T - 1)) * N + n];
         };
         auto fc1_step = [&](int s) {
             const int slot = s + 1;
