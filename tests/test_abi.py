@@ -72,6 +72,9 @@ def test_create_rejects_bad_descriptions_before_using_a_device(lib):
 def test_calls_reject_null_handles(lib):
     assert lib.marl_act_step(None, 4, None, None, None, None, None, 0.0, 0, None, None, None, None) == -1
     assert lib.marl_unroll_td(None, None, 1, 1, None, None, None, None, None, None, 0.9, None, None, None, None, None) == -1
+    assert lib.marl_act_step_indexed(None, 4, None, 2, None, None, None, None, None, 0.0, 0, None, None, None, None) == -1
+    assert lib.marl_unroll_td_indexed(None, None, 8, None, 1, 1, None, None, None, None, None, None, 0.9, None, None, None,
+                                      None, None) == -1
     assert lib.marl_qnet_reserve_unroll(None, 1, 1) == -1
     assert lib.marl_qnet_get_desc(None, None) == -1
     assert lib.marl_destroy(None) == 0

@@ -1,6 +1,8 @@
 """GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by
 element on the same seeded inputs.  Tolerances: max abs error 1e-4 with fp32 weights, 2e-2
 with bf16 weights (fp32 accumulation); integer outputs exact outside near-ties."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -521,6 +523,16 @@ def test_indexed_unroll_reads_the_batch_from_a_pool(ci, pool, B):
     same = pu.gpu_unroll(net, target, cfg, packed)
     for k in got:
         np.testing.assert_array_equal(got[k], same[k])
+    lib, vp = binding.load(), ctypes.c_void_p
+    args = lambda pool_n, index, b: (vp(net.handle), vp(target.handle), pool_n, index, b, T, vp(d["obs"].data_ptr()),
+                                     vp(d["avail"].data_ptr()), vp(d["actions"].data_ptr()), vp(d["reward"].data_ptr()),
+                                     vp(d["terminated"].data_ptr()), vp(d["filled"].data_ptr()), 0.9, vp(outs["q_taken"].data_ptr()),
+                                     vp(outs["next_max"].data_ptr()), vp(outs["td_target"].data_ptr()), None, None)
+    index_ptr = vp(torch.from_numpy(pick).cuda().data_ptr())
+    assert lib.marl_unroll_td_indexed(*args(pool, index_ptr, 0)) == 0         # empty batch: nothing to do
+    assert lib.marl_unroll_td_indexed(*args(0, index_ptr, B)) == -2           # empty pool
+    assert lib.marl_unroll_td_indexed(*args(pool, None, B)) == -1             # no index
+    torch.cuda.synchronize()
     net.set_kernels(binding.KERNELS_TILE32)
     with pytest.raises(binding.MarlError) as err:
         net.unroll_td_indexed(target, torch.from_numpy(pick).cuda(), d["obs"], d["avail"], d["actions"], d["reward"],
