@@ -1,9 +1,10 @@
-"""ctypes binding of libmarl_qnet.so (include/marl_qnet.h), same entry-point names.
+"""ctypes binding of libmarl_qnet.so (include/marl_qnet.h and include/marl_mixer.h), same
+entry-point names.
 
 Argument marshalling only: tensors are checked for dtype, shape, contiguity and
 device, and their addresses handed to the C ABI together with torch's current
-HIP stream.  Every step of the network, the action rule and the TD targets run
-in the library's kernels.  There is no CPU fallback: if the library is not
+HIP stream.  Every step of the network, the action rule, the TD targets and the
+mixing network run in the library's kernels.  There is no CPU fallback: if the library is not
 built, or a call fails, an exception is raised.
 """
 import ctypes
