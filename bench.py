@@ -155,6 +155,40 @@ class Bench:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
+    def cache_resident_act(self, n=100):
+        """The same launch on one buffer over and over: inputs stay in the memory-side cache."""
+        torch = self.torch
+        a0 = self.act_in[0]
+        call = lambda: self.online.act_step(a0["obs"], a0["avail"], a0["h_in"], a0["reset"], a0["step_t"],
+                                            self.act_meta["epsilon"], self.act_meta["seed"], self.h_out[0], self.action, self.q[0])
+        for _ in range(5):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
+    def single_net_unroll(self, n=10):
+        """target == online: one network's unroll instead of two."""
+        torch = self.torch
+        u = self.u
+        call = lambda: self.online.unroll_td(None, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
+                                             u["filled"], self.u_host["gamma"], *self.u_out)
+        for _ in range(2):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
     def close(self):
         self.online.close()
         if self.target is not None:
@@ -270,6 +304,8 @@ def main():
     E, B, T = cfg["E"], cfg["B"], cfg["T"]
     wall, k = b.run(args.steps, args.warmup)
     act_b2b_ms = b.back_to_back_act()
+    act_cached_ms = b.cache_resident_act()
+    single_net_ms = b.single_net_unroll()
     b.close()
 
     ms_per_step = wall * 1e3 / args.steps
@@ -332,11 +368,12 @@ def main():
                                "unroll_td": "fused16" if b.fused else "tile32"},
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
         "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
-                     "kernel_ms_back_to_back": act_b2b_ms, "hbm_GBs": kernels["act_step"]["GBs"],
+                     "kernel_ms_back_to_back": act_b2b_ms, "kernel_ms_cache_resident_inputs": act_cached_ms, "hbm_GBs": kernels["act_step"]["GBs"],
                      "hbm_frac": kernels["act_step"]["hbm_frac"], "mfma_frac": kernels["act_step"]["mfma_frac"],
                      "input_pool_bytes": b.pool * kernels["act_step"]["bytes"]},
         "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),
                       "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "kernels_ms": unroll_ms,
+                      "single_network_ms": single_net_ms,
                       "kernels": {n: {"ms": v["ms"], "TFLOPs": v["TFLOPs"], "mfma_frac": v["mfma_frac"],
                                       "GBs": v["GBs"], "hbm_frac": v["hbm_frac"]}
                                   for n, v in kernels.items() if n != "act_step"}},
