@@ -201,10 +201,9 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
  *   obs, avail, actions, reward, terminated, filled: as above with leading dimension
  *                               pool_episodes instead of B
  *   outputs: as above, leading dimension B (batch position)
- * An index outside the range is clamped into it (the call cannot check device data).  Served by
- * the fused16 kernels only: MARL_ERR_BAD_DIM when the handle's unroll takes the tile32 kernels,
- * when pool_episodes < 1, or when pool_episodes (T+1) N max(D, A) >= 2^30.  Otherwise errors as
- * marl_unroll_td.
+ * An index outside the range is clamped into it (the call cannot check device data).
+ * MARL_ERR_BAD_DIM when pool_episodes < 1 or pool_episodes (T+1) N max(D, A) >= 2^30.  Otherwise
+ * errors, kernel families and scratch as marl_unroll_td (the scratch is sized by B, not by the pool).
  */
 int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_episodes,
                            const int32_t *episode_index, int32_t B, int32_t T,

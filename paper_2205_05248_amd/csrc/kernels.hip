@@ -46,6 +46,8 @@ struct FrontArgs {
     // input projection
     char *gi[2];
     int B, T;
+    const int32_t *episode_index;   // null, or the pool episode of each batch position
+    int pool_episodes;
     unsigned nets;              // 1 or 2
 };
 
@@ -103,8 +105,9 @@ __global__ __launch_bounds__(kFrontThreads, 1) void front_kernel(const FrontArgs
             row[c] = rt * 32 + col;
             valid[c] = tile_ok && row[c] < rows;
             const int b = valid[c] ? row[c] / N : 0;
+            const int bi = args.episode_index ? min(max(args.episode_index[b], 0), args.pool_episodes - 1) : b;
             n[c] = valid[c] ? row[c] % N : 0;
-            obs_row[c] = args.obs + (valid[c] ? (((size_t)b * S + t) * N + n[c]) * D : 0);
+            obs_row[c] = args.obs + (valid[c] ? (((size_t)bi * S + t) * N + n[c]) * D : 0);
             gi_dst[c] = tile_ok ? args.gi[net_id] + ((size_t)rt * S + t) * (3 * FB * GiLayout<P>::kBlockBytes) : nullptr;
         }
     }
@@ -367,7 +370,8 @@ template <int H, int P> struct RecurrentShape {
 template <int H, int P, int MB2, bool QALL>
 __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kernel(
     NetFrags online, NetFrags target, const char *__restrict__ gi_online, const char *__restrict__ gi_target,
-    int two_nets, int B, int T, const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
+    int two_nets, int B, int T, const int32_t *__restrict__ episode_index, int pool_episodes,
+    const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
     const float *__restrict__ reward, const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled,
     float gamma, float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target,
     float *__restrict__ q_all)
@@ -390,7 +394,7 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
     if (wave < Shape::kCompute) {
         compute_role<H, P>(net, wave, lane, T, 1, &gi_lds[0][0], h_lds);
     } else if (wave == Shape::kCompute) {
-        const TdArrays td{avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all};
+        const TdArrays td{episode_index, pool_episodes, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all};
         epilogue_role<H, P, MB2, QALL>(net, td, !is_target, is_target || !two_nets, rt, lane, B, T, 1, h_lds, b2_lds);
     } else {
         // ---------------------------------------------------------------- prefetch wave
@@ -443,7 +447,7 @@ hipError_t act_dispatch(const NetFrags &net, int rows, const int32_t *env_index,
 
 template <int H, int P>
 hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, char *gi_on, char *gi_tg,
-                           int B, int T, const float *obs, const uint8_t *avail, const int32_t *actions,
+                           int B, int T, const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
                            const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
                            float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream,
                            hipEvent_t between)
@@ -456,7 +460,7 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
         FrontArgs a{};
         a.net[0] = online; a.net[1] = target;
         a.gi[0] = gi_on; a.gi[1] = gi_tg;
-        a.B = B; a.T = T; a.obs = obs; a.nets = nets;
+        a.B = B; a.T = T; a.episode_index = episode_index; a.pool_episodes = pool_episodes; a.obs = obs; a.nets = nets;
         const dim3 grid((unsigned)((groups + kFrontWaves - 1) / kFrontWaves) * nets), block(kFrontThreads);
         // the fc2 block count does not enter the projection; one instantiation serves both
         hipLaunchKernelGGL((front_kernel<H, P, 1, false>), grid, block, 0, stream, a);
@@ -471,7 +475,8 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
     const int two = two_nets ? 1 : 0;
 #define MARL_REC(MB, QA)                                                                                             \
     hipLaunchKernelGGL((recurrent_td_kernel<H, P, MB, QA>), grid, block, 0, stream, online, target, gi_on, gi_tg, two,  \
-                       B, T, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all)
+                       B, T, episode_index, pool_episodes, avail, actions, reward, terminated, filled, gamma, q_taken,      \
+                       next_max, td_target, q_all)
     if (online.mb2 == 1) { if (q_all) MARL_REC(1, true); else MARL_REC(1, false); }
     else                 { if (q_all) MARL_REC(2, true); else MARL_REC(2, false); }
 #undef MARL_REC
@@ -504,14 +509,16 @@ size_t unroll_scratch_bytes(const NetFrags &net, int B, int T)
 }
 
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
-                            void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
+                            void *scratch_target, int B, int T, const int32_t *episode_index, int pool_episodes,
+                            const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
                             float *q_all, hipStream_t stream, hipEvent_t between)
 {
     char *gi_on = static_cast<char *>(scratch_online), *gi_tg = static_cast<char *>(scratch_target);
 #define MARL_UNROLL(HH, PP)                                                                                        \
-    return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, obs, avail, actions, reward,      \
+    return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, episode_index, pool_episodes, obs, \
+                                   avail, actions, reward,                                                         \
                                    terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream, between)
     if (online.H == 64 && online.planes == 2) MARL_UNROLL(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_UNROLL(64, 1);

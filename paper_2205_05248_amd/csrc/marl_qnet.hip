@@ -327,7 +327,6 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     const bool two = online != target;
     const bool fused = takes_fused_path(online, true);
-    if (episode_index && !fused) return MARL_ERR_BAD_DIM;       // the pool is read in place by the fused kernel only
     int rc = MARL_OK;
     if (!fused) {
         const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
@@ -350,7 +349,8 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
         if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
         return MARL_OK;
     }
-    MARL_HIP(marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, obs, avail,
+    MARL_HIP(marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, episode_index,
+                                    pool_episodes, obs, avail,
                                     actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
                                     stream, ev ? ev[1] : nullptr));
     if (ev) MARL_HIP(hipEventRecord(ev[2], stream));

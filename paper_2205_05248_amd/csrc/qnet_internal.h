@@ -101,7 +101,8 @@ hipError_t launch_act_step(const NetFrags &net, int E, const int32_t *env_index,
 size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
 
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
-                            void *scratch_target, int B, int T, const float *obs, const uint8_t *avail,
+                            void *scratch_target, int B, int T, const int32_t *episode_index, int pool_episodes,
+                            const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
                             float *q_all, hipStream_t stream, hipEvent_t between);

@@ -83,6 +83,8 @@ __device__ __forceinline__ void compute_role(const NetFrags &net, int fb, int la
 
 // Arrays of the TD step as the epilogue sees them.
 struct TdArrays {
+    const int32_t *episode_index;   // null: the input arrays hold the batch; else batch position b reads episode episode_index[b]
+    int pool_episodes;              // episodes the input arrays hold (listed indices are clamped into it)
     const uint8_t *avail;
     const int32_t *actions;
     const float *reward;
@@ -122,15 +124,18 @@ __device__ __forceinline__ void epilogue_role(const NetFrags &net, const TdArray
     // behind the other waves' work.
     // 32-bit element offsets (the host bounds every array to 2^30 elements): uniform base
     // pointer + per-lane offset + per-slot stride.
-    const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // actions / outputs: + t N
-    const uint32_t av0 = ((uint32_t)(b * S) * N + n) * A;     // avail / q_all:     + t N A
-    const uint32_t bt0 = (uint32_t)(b * T);                   // per-episode flags: + t
+    const int bi = td.episode_index ? min(max(td.episode_index[b], 0), td.pool_episodes - 1) : b;     // episode of the inputs
+    const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // outputs [B, T, N]:       + t N
+    const uint32_t qa0 = ((uint32_t)(b * S) * N + n) * A;     // q_all [B, T+1, N, A]:    + t N A
+    const uint32_t act0 = (uint32_t)(bi * T) * N + n;         // actions of the episode:  + t N
+    const uint32_t av0 = ((uint32_t)(bi * S) * N + n) * A;    // avail of the episode:    + t N A
+    const uint32_t bt0 = (uint32_t)(bi * T);                  // per-episode flags:       + t
     struct SlotIn { int u; uint32_t avail_raw[MB2 * 4]; float reward; uint8_t on_filled, terminated, tg_filled; };
     auto fetch_slot = [&](int t) {
         SlotIn in{};
         if (t > T) return in;
         if (emit_online && t < T) {
-            in.u = valid ? td.actions[btn0 + (uint32_t)t * N] : 0;
+            in.u = valid ? td.actions[act0 + (uint32_t)t * N] : 0;
             in.on_filled = valid ? td.filled[bt0 + t] : 0;
         }
         if (emit_target && t >= 1) {
@@ -167,7 +172,7 @@ __device__ __forceinline__ void epilogue_role(const NetFrags &net, const TdArray
             }
             if (emit_online) {
                 if constexpr (QALL) {
-                    if (valid) store_q_row<MB2>(td.q_all + (av0 + (uint32_t)t * N * A), q, A, lane);
+                    if (valid) store_q_row<MB2>(td.q_all + (qa0 + (uint32_t)t * N * A), q, A, lane);
                 }
                 if (t < T) {
                     const int u = min(max(in.u, 0), A - 1);

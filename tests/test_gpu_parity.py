@@ -533,9 +533,14 @@ def test_indexed_unroll_reads_the_batch_from_a_pool(ci, pool, B):
     assert lib.marl_unroll_td_indexed(*args(0, index_ptr, B)) == -2           # empty pool
     assert lib.marl_unroll_td_indexed(*args(pool, None, B)) == -1             # no index
     torch.cuda.synchronize()
+    # the two-kernel family reads the pool in place as well
     net.set_kernels(binding.KERNELS_TILE32)
-    with pytest.raises(binding.MarlError) as err:
-        net.unroll_td_indexed(target, torch.from_numpy(pick).cuda(), d["obs"], d["avail"], d["actions"], d["reward"],
-                              d["terminated"], d["filled"], u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
-    assert err.value.status == -2
+    for t in list(outs.values()) + [q_all]:
+        t.fill_(float("nan"))
+    net.unroll_td_indexed(target, torch.from_numpy(pick).cuda(), d["obs"], d["avail"], d["actions"], d["reward"],
+                          d["terminated"], d["filled"], u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
+    torch.cuda.synchronize()
+    got32 = {k: v.cpu().numpy() for k, v in outs.items()}
+    got32["q_all"] = q_all.cpu().numpy()
+    pu.compare_unroll(got32, oracle_unroll(cfg, w, w_tg, packed), tol)
     net.close(); target.close()
