@@ -65,6 +65,16 @@ size_t marl_mixer_param_count(const marl_mixer_desc *desc);
  * _MISMATCH (n_weights != parameter count) / _NOMEM / _DEVICE. */
 int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, size_t n_weights, marl_mixer **out);
 
+/*
+ * Replaces the parameters in place (the target mixer taking over the online mixer's parameters, or the
+ * learner publishing an update; Alg. 3, last step).  host_weights: the packed layout and count of
+ * create.  The call repacks on the host into a pinned staging buffer the handle owns and enqueues one
+ * host-to-device copy on hip_stream, so it is ordered like a kernel on that stream: marl_mixer_td calls
+ * enqueued earlier use the old parameters, later ones the new.  A second call waits on the host until
+ * the previous call's copy has left the staging buffer.  host_weights may be reused on return.
+ */
+int marl_mixer_set_weights(marl_mixer *m, const float *host_weights, size_t n_weights, void *hip_stream);
+
 /* Frees the handle after the device has finished with it (synchronises).  NULL is a no-op. */
 void marl_mixer_destroy(marl_mixer *m);
 

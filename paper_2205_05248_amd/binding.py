@@ -24,7 +24,8 @@ EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_a
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
-MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td"]
+MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td",
+                 "marl_mixer_set_weights"]
 
 
 class MarlError(RuntimeError):
@@ -96,6 +97,8 @@ def load():
         lib.marl_mixer_param_count.argtypes = [ctypes.POINTER(MixerDesc)]
         lib.marl_mixer_create.restype = ctypes.c_int
         lib.marl_mixer_create.argtypes = [ctypes.POINTER(MixerDesc), vp, ctypes.c_size_t, ctypes.POINTER(vp)]
+        lib.marl_mixer_set_weights.restype = ctypes.c_int
+        lib.marl_mixer_set_weights.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.marl_mixer_destroy.restype = None
         lib.marl_mixer_destroy.argtypes = [vp]
         lib.marl_mixer_td.restype = ctypes.c_int
@@ -317,6 +320,12 @@ def marl_mixer_create(n_agents, embed, state_dim, weight_dtype, device, host_wei
     return out.value
 
 
+def marl_mixer_set_weights(handle, host_weights):
+    """Stream-ordered in-place parameter refresh on torch's current stream."""
+    w = np.ascontiguousarray(host_weights, dtype=np.float32)
+    check(load().marl_mixer_set_weights(ctypes.c_void_p(handle), w.ctypes.data_as(ctypes.c_void_p), w.size, _stream()))
+
+
 def marl_mixer_destroy(handle):
     load().marl_mixer_destroy(ctypes.c_void_p(handle))
 
@@ -340,6 +349,9 @@ class Mixer:
     def __init__(self, dims, weights, dtype="fp32", device=0):
         self.dims = tuple(int(v) for v in dims)
         self.handle = marl_mixer_create(*self.dims, DTYPES[dtype], device, weights)
+
+    def set_weights(self, weights):
+        marl_mixer_set_weights(self.handle, weights)
 
     def td(self, target, state, q_taken, next_max, reward, terminated, filled, gamma, q_total, y_total, td_err):
         marl_mixer_td(self.handle, None if target is None else target.handle, self.dims, state, q_taken, next_max,

@@ -35,7 +35,10 @@ struct marl_mixer {
     const marl::bf16x8 *frags;   // [(N + 3) M / 16][ks][planes][64]
     const float *bias;           // [(N + 3) M]: hb1 | hbb1 | hb2 | c1
     const float *v2;             // [M]
-    float c2;
+    const float *c2;             // [1]
+    size_t bytes;                // of the image
+    void *staging;               // pinned host copy of the image for marl_mixer_set_weights (lazily allocated)
+    hipEvent_t staging_done;     // the last upload from it
 };
 
 namespace marl {
@@ -47,7 +50,7 @@ constexpr int kAhead = 4;             // blocks between asking for a block's fra
 struct MixerArgs {
     const bf16x8 *frags[2];
     const float *bias[2], *v2[2];
-    float c2[2];
+    const float *c2[2];
     int N, S, ks, rows, T;                 // ks: padded k-steps of the packed fragments
     const float *state, *q[2], *reward;
     const uint8_t *terminated, *filled;
@@ -198,7 +201,7 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         }
         total += __shfl_xor(total, 16);
         total += __shfl_xor(total, 32);
-        mixed[pass] = total + a.c2[pass];
+        mixed[pass] = total + a.c2[pass][0];
     }
     if (valid && q4 == 0) {
         const float y = a.reward[row] + a.gamma * (a.terminated[row] ? 0.0f : 1.0f) * mixed[1];
@@ -294,6 +297,48 @@ size_t marl_mixer_param_count(const marl_mixer_desc *desc)
     return marl::mixer_params(desc);
 }
 
+}  // extern "C"
+
+namespace marl {
+namespace {
+// The device image of a mixer: fragments of the four state matrices in the order the kernel walks
+// them (W1 rows agent-major, b1, w2, offset layer), then the fp32 tables hb1 | hbb1 | hb2 | c1, v2, c2.
+// Returns a calloc'ed host copy (caller frees) or null.
+char *pack_mixer_image(const marl_mixer_desc &d, const float *w, size_t *bytes, size_t *frag_bytes)
+{
+    const int N = d.n_agents, M = d.embed, S = d.state_dim;
+    const int planes = d.weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
+    const int ks = padded_ksteps(S), F = (N + 3) * M;
+    const float *Hw1 = w, *hb1 = Hw1 + (size_t)N * M * S, *Hb1 = hb1 + (size_t)N * M, *hbb1 = Hb1 + (size_t)M * S;
+    const float *Hw2 = hbb1 + M, *hb2 = Hw2 + (size_t)M * S, *V1 = hb2 + M, *c1 = V1 + (size_t)M * S, *v2 = c1 + M, *c2 = v2 + M;
+    *frag_bytes = (size_t)(F / 16) * ks * planes * 1024;
+    *bytes = *frag_bytes + sizeof(float) * (F + M + 4);
+    char *host = static_cast<char *>(std::calloc(1, *bytes));
+    if (!host) return nullptr;
+    uint16_t *frags = reinterpret_cast<uint16_t *>(host);
+    const size_t per_block = (size_t)ks * planes * 512;
+    auto pack_rows = [&](int first_block, const float *W, int n_rows) {      // blocks of 16 rows, ks k-steps each (zero past S)
+        for (int fb = 0; fb < n_rows / 16; ++fb)
+            pack_frags16(frags + (size_t)(first_block + fb) * per_block, W + (size_t)16 * fb * S, 16, S, S, false, planes);
+    };
+    pack_rows(0, Hw1, N * M);
+    pack_rows(N * M / 16, Hb1, M);
+    pack_rows((N + 1) * M / 16, Hw2, M);
+    pack_rows((N + 2) * M / 16, V1, M);
+    float *bias = reinterpret_cast<float *>(host + *frag_bytes);
+    std::memcpy(bias, hb1, sizeof(float) * N * M);
+    std::memcpy(bias + (size_t)N * M, hbb1, sizeof(float) * M);
+    std::memcpy(bias + (size_t)(N + 1) * M, hb2, sizeof(float) * M);
+    std::memcpy(bias + (size_t)(N + 2) * M, c1, sizeof(float) * M);
+    std::memcpy(bias + F, v2, sizeof(float) * M);
+    bias[F + M] = c2[0];
+    return host;
+}
+}  // namespace
+}  // namespace marl
+
+extern "C" {
+
 int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, size_t n_weights, marl_mixer **out)
 {
     if (!desc || !host_weights || !out) return MARL_ERR_NULL;
@@ -301,37 +346,16 @@ int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, si
     int why;
     if (!marl::mixer_desc_valid(desc, &why)) return why;
     if (n_weights != marl::mixer_params(desc)) return MARL_ERR_MISMATCH;
-    const int N = desc->n_agents, M = desc->embed, S = desc->state_dim;
-    const int planes = desc->weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
-    const int ks = marl::padded_ksteps(S), F = (N + 3) * M;
-    const float *Hw1 = host_weights, *hb1 = Hw1 + (size_t)N * M * S, *Hb1 = hb1 + (size_t)N * M, *hbb1 = Hb1 + (size_t)M * S;
-    const float *Hw2 = hbb1 + M, *hb2 = Hw2 + (size_t)M * S, *V1 = hb2 + M, *c1 = V1 + (size_t)M * S, *v2 = c1 + M, *c2 = v2 + M;
-
-    const size_t frag_bytes = (size_t)(F / 16) * ks * planes * 1024;
-    const size_t bytes = frag_bytes + sizeof(float) * (F + M);
-    char *host = static_cast<char *>(std::calloc(1, bytes));
+    size_t bytes, frag_bytes;
+    char *host = marl::pack_mixer_image(*desc, host_weights, &bytes, &frag_bytes);
     if (!host) return MARL_ERR_NOMEM;
-    // generated quantities in the order the kernel walks them: W1 rows (agent-major), b1, w2, offset layer
-    uint16_t *frags = reinterpret_cast<uint16_t *>(host);
-    const size_t per_block = (size_t)ks * planes * 512;
-    auto pack_rows = [&](int first_block, const float *W, int n_rows) {      // blocks of 16 rows, ks k-steps each (zero past S)
-        for (int fb = 0; fb < n_rows / 16; ++fb)
-            marl::pack_frags16(frags + (size_t)(first_block + fb) * per_block, W + (size_t)16 * fb * S, 16, S, S, false, planes);
-    };
-    pack_rows(0, Hw1, N * M);
-    pack_rows(N * M / 16, Hb1, M);
-    pack_rows((N + 1) * M / 16, Hw2, M);
-    pack_rows((N + 2) * M / 16, V1, M);
-    float *bias = reinterpret_cast<float *>(host + frag_bytes);
-    std::memcpy(bias, hb1, sizeof(float) * N * M);
-    std::memcpy(bias + (size_t)N * M, hbb1, sizeof(float) * M);
-    std::memcpy(bias + (size_t)(N + 1) * M, hb2, sizeof(float) * M);
-    std::memcpy(bias + (size_t)(N + 2) * M, c1, sizeof(float) * M);
-    std::memcpy(bias + F, v2, sizeof(float) * M);
-
     marl_mixer *m = new (std::nothrow) marl_mixer();
     if (!m) { std::free(host); return MARL_ERR_NOMEM; }
-    m->desc = *desc; m->planes = planes; m->ks = ks; m->c2 = c2[0]; m->image = nullptr;
+    const int F = (desc->n_agents + 3) * desc->embed;
+    m->desc = *desc;
+    m->planes = desc->weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
+    m->ks = marl::padded_ksteps(desc->state_dim);
+    m->image = nullptr; m->bytes = bytes; m->staging = nullptr; m->staging_done = nullptr;
     marl::MixerDeviceGuard guard(desc->device);
     hipError_t err = guard.ok ? hipMalloc(&m->image, bytes) : hipErrorInvalidDevice;
     if (err == hipSuccess) err = hipMemcpy(m->image, host, bytes, hipMemcpyHostToDevice);
@@ -344,7 +368,36 @@ int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, si
     m->frags = static_cast<const marl::bf16x8 *>(m->image);
     m->bias = reinterpret_cast<const float *>(static_cast<char *>(m->image) + frag_bytes);
     m->v2 = m->bias + F;
+    m->c2 = m->v2 + desc->embed;
     *out = m;
+    return MARL_OK;
+}
+
+int marl_mixer_set_weights(marl_mixer *m, const float *host_weights, size_t n_weights, void *hip_stream)
+{
+    if (!m || !host_weights) return MARL_ERR_NULL;
+    if (n_weights != marl::mixer_params(&m->desc)) return MARL_ERR_MISMATCH;
+    size_t bytes, frag_bytes;
+    char *host = marl::pack_mixer_image(m->desc, host_weights, &bytes, &frag_bytes);
+    if (!host) return MARL_ERR_NOMEM;
+    struct FreeHost { void *p; ~FreeHost() { std::free(p); } } free_host{host};
+    marl::MixerDeviceGuard guard(m->desc.device);
+    if (!guard.ok) return marl::report_device_error(hipErrorInvalidDevice, "hipSetDevice");
+    hipError_t err;
+    if (!m->staging) {
+        err = hipHostMalloc(&m->staging, bytes, hipHostMallocDefault);
+        if (err != hipSuccess) { m->staging = nullptr; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : marl::report_device_error(err, "hipHostMalloc"); }
+        err = hipEventCreateWithFlags(&m->staging_done, hipEventDisableTiming);
+        if (err != hipSuccess) { (void)hipHostFree(m->staging); m->staging = nullptr; m->staging_done = nullptr; return marl::report_device_error(err, "hipEventCreate"); }
+    } else {
+        err = hipEventSynchronize(m->staging_done);                      // the previous upload still reads the buffer
+        if (err != hipSuccess) return marl::report_device_error(err, "hipEventSynchronize");
+    }
+    std::memcpy(m->staging, host, bytes);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    err = hipMemcpyAsync(m->image, m->staging, bytes, hipMemcpyHostToDevice, stream);
+    if (err == hipSuccess) err = hipEventRecord(m->staging_done, stream);
+    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_set_weights");
     return MARL_OK;
 }
 
@@ -352,7 +405,9 @@ void marl_mixer_destroy(marl_mixer *m)
 {
     if (!m) return;
     marl::MixerDeviceGuard guard(m->desc.device);
-    if (m->image) (void)hipFree(m->image);
+    if (m->image) (void)hipFree(m->image);              // synchronises the device
+    if (m->staging) (void)hipHostFree(m->staging);
+    if (m->staging_done) (void)hipEventDestroy(m->staging_done);
     delete m;
 }
 

@@ -170,3 +170,32 @@ def test_mixer_is_monotone_on_the_device():
         up["q_taken"][..., n] += 1.5
         assert (gpu_td(mixer, None, up)["q_total"] >= base - 1e-4).all()
     mixer.close()
+
+
+def test_mixer_set_weights_is_ordered_on_the_stream():
+    """Parameters replaced in place, with no synchronisation in between: a call enqueued before the
+    refresh sees the old mixer, calls after it the new one (the offset constant included, which is
+    part of the uploaded image); a second refresh right behind the first does not disturb it."""
+    cfg = dict(wl.config(2), B=6, T=13)
+    dims = wl.mixer_dims(cfg)
+    w0, w1, w2 = (wl.make_mixer_weights(cfg, s) for s in (0, 1, 2))
+    for w in (w1, w2):
+        w[-1] += 3.0                                # c2: a visible change of the constant
+    mixer = binding.Mixer(dims, w0, "fp32")
+    m = wl.make_mixer_inputs(cfg)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    d = {k: dev(m[k]) for k in ("state", "q_taken", "next_max", "reward", "terminated", "filled")}
+    outs = []
+    for w in (None, w1, w2):
+        if w is not None:
+            mixer.set_weights(w)
+        o = [torch.empty(cfg["B"], cfg["T"], device="cuda") for _ in range(3)]
+        mixer.td(None, d["state"], d["q_taken"], d["next_max"], d["reward"], d["terminated"], d["filled"], m["gamma"], *o)
+        outs.append(o)
+    torch.cuda.synchronize()
+    for o, w in zip(outs, (w0, w1, w2)):
+        ref = mxo.td(dims, w, None, m["state"], m["q_taken"], m["next_max"], m["reward"], m["terminated"], m["filled"], m["gamma"])
+        check({k: t.cpu().numpy() for k, t in zip(("q_total", "y_total", "td_err"), o)}, ref, TOL["fp32"])
+    with pytest.raises(binding.MarlError):
+        mixer.set_weights(w0[:-1])
+    mixer.close()
