@@ -10,6 +10,8 @@
  *   q_total[b,t] = Mix(theta;  q_taken[b,t,:], state[b,t])
  *   y_total[b,t] = reward[b,t] + gamma (1 - terminated[b,t]) Mix(theta-; next_max[b,t,:], state[b,t+1])
  *   td_err[b,t]  = filled[b,t] ? y_total[b,t] - q_total[b,t] : 0
+ *   loss         = ( sum_{b,t} td_err[b,t]^2 ,  number of filled transitions )
+ * (the masked mean-squared TD loss the gradient of Alg. 3 descends is loss[0] / loss[1])
  *
  * The paper names the mixer (its experiments train Qmix variants) but prints no
  * equations for it; Mix is the monotonic-mixing definition, in this concrete form
@@ -87,14 +89,17 @@ void marl_mixer_destroy(marl_mixer *m);
  *   terminated [B, T]      u8      nonzero: no bootstrap
  *   filled     [B, T]      u8      zero: padding, td_err = 0
  *   q_total, y_total, td_err [B, T] f32 outputs; any of them may be NULL (not written)
+ *   loss       [2] f32 output or NULL: sum of squared td_err and number of filled transitions, reduced by
+ *              one small second kernel in a fixed order (same bits on every run); needs td_err
  * `target` may equal `online` (or be NULL: the same).  Both handles must have the same
  * descriptor (MARL_ERR_MISMATCH otherwise).  MARL_ERR_BAD_DIM for B < 0, T < 1 or B T >= 2^30;
- * MARL_ERR_BAD_ARG for gamma outside [0, 1]; B = 0 is a no-op.
+ * MARL_ERR_BAD_ARG for gamma outside [0, 1]; MARL_ERR_NULL for loss without td_err; B = 0 is a no-op
+ * (loss is then left unwritten).
  */
 int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, const float *state,
                   const float *q_taken, const float *next_max, const float *reward, const uint8_t *terminated,
                   const uint8_t *filled, float gamma, float *q_total, float *y_total, float *td_err,
-                  void *hip_stream);
+                  float *loss, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -105,13 +105,17 @@ void mixer_forward(int N, int M, int S, const float *w, long R, const double *q,
  *   q_total = Mix(theta;  q_taken[b, t, :], state[b, t])
  *   y_total = reward + gamma (1 - terminated) Mix(theta-; next_max[b, t, :], state[b, t + 1])
  *   td_err  = filled ? y_total - q_total : 0
- * state [B, T+1, S]; q_taken, next_max [B, T, N] doubles; outputs [B, T] doubles.
+ * and over the batch  loss[0] = sum td_err^2,  loss[1] = number of filled transitions
+ * (the masked mean-squared TD loss is loss[0] / loss[1]).
+ * state [B, T+1, S]; q_taken, next_max [B, T, N] doubles; outputs [B, T] doubles, loss [2].
  */
 void mixer_td(int N, int M, int S, const float *w_online, const float *w_target, int B, int T,
               const float *state, const double *q_taken, const double *next_max, const float *reward,
               const uint8_t *terminated, const uint8_t *filled, float gamma,
-              double *q_total, double *y_total, double *td_err)
+              double *q_total, double *y_total, double *td_err, double *loss)
 {
+    loss[0] = 0.0;
+    loss[1] = 0.0;
     mixer_t on, tg;
     mixer_bind(&on, N, M, S, w_online);
     mixer_bind(&tg, N, M, S, w_target);
@@ -126,5 +130,7 @@ void mixer_td(int N, int M, int S, const float *w_online, const float *w_target,
             q_total[i] = qt;
             y_total[i] = y;
             td_err[i] = filled[i] ? y - qt : 0.0;
+            loss[0] += td_err[i] * td_err[i];
+            loss[1] += filled[i] ? 1.0 : 0.0;
         }
 }

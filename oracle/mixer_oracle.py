@@ -58,7 +58,8 @@ def forward(dims, w, q, state):
 
 
 def td(dims, w_online, w_target, state, q_taken, next_max, reward, terminated, filled, gamma):
-    """dict(q_total, y_total, td_err) [B, T] f64.  w_target=None means target == online."""
+    """dict(q_total, y_total, td_err [B, T] f64, loss [2] = (sum of squared errors, filled count)).
+    w_target=None means target == online."""
     N, M, S = (int(v) for v in dims)
     w_online = _c(w_online, np.float32)
     w_target = w_online if w_target is None else _c(w_target, np.float32)
@@ -71,8 +72,8 @@ def td(dims, w_online, w_target, state, q_taken, next_max, reward, terminated, f
     reward = _c(reward, np.float32); assert reward.shape == (B, T)
     terminated = _c(terminated, np.uint8); assert terminated.shape == (B, T)
     filled = _c(filled, np.uint8); assert filled.shape == (B, T)
-    out = dict(q_total=np.zeros((B, T)), y_total=np.zeros((B, T)), td_err=np.zeros((B, T)))
+    out = dict(q_total=np.zeros((B, T)), y_total=np.zeros((B, T)), td_err=np.zeros((B, T)), loss=np.zeros(2))
     _load().mixer_td(N, M, S, _p(w_online), _p(w_target), B, T, _p(state), _p(q_taken), _p(next_max), _p(reward),
                      _p(terminated), _p(filled), ctypes.c_float(float(np.float32(gamma))),
-                     _p(out["q_total"]), _p(out["y_total"]), _p(out["td_err"]))
+                     _p(out["q_total"]), _p(out["y_total"]), _p(out["td_err"]), _p(out["loss"]))
     return out

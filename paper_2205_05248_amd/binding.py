@@ -102,7 +102,7 @@ def load():
         lib.marl_mixer_destroy.restype = None
         lib.marl_mixer_destroy.argtypes = [vp]
         lib.marl_mixer_td.restype = ctypes.c_int
-        lib.marl_mixer_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp]
+        lib.marl_mixer_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         _lib = lib
     return _lib
 
@@ -331,7 +331,7 @@ def marl_mixer_destroy(handle):
 
 
 def marl_mixer_td(online, target, dims, state, q_taken, next_max, reward, terminated, filled, gamma,
-                  q_total, y_total, td_err):
+                  q_total, y_total, td_err, loss=None):
     N, M, S = dims
     B, T = int(state.shape[0]), int(state.shape[1]) - 1
     check(load().marl_mixer_td(
@@ -340,7 +340,7 @@ def marl_mixer_td(online, target, dims, state, q_taken, next_max, reward, termin
         _dev(next_max, "f32", (B, T, N), "next_max"), _dev(reward, "f32", (B, T), "reward"),
         _dev(terminated, "u8", (B, T), "terminated"), _dev(filled, "u8", (B, T), "filled"), float(gamma),
         _dev(q_total, "f32", (B, T), "q_total", optional=True), _dev(y_total, "f32", (B, T), "y_total", optional=True),
-        _dev(td_err, "f32", (B, T), "td_err", optional=True), _stream()))
+        _dev(td_err, "f32", (B, T), "td_err", optional=True), _dev(loss, "f32", (2,), "loss", optional=True), _stream()))
 
 
 class Mixer:
@@ -353,9 +353,10 @@ class Mixer:
     def set_weights(self, weights):
         marl_mixer_set_weights(self.handle, weights)
 
-    def td(self, target, state, q_taken, next_max, reward, terminated, filled, gamma, q_total, y_total, td_err):
+    def td(self, target, state, q_taken, next_max, reward, terminated, filled, gamma, q_total, y_total, td_err,
+           loss=None):
         marl_mixer_td(self.handle, None if target is None else target.handle, self.dims, state, q_taken, next_max,
-                      reward, terminated, filled, gamma, q_total, y_total, td_err)
+                      reward, terminated, filled, gamma, q_total, y_total, td_err, loss)
 
     def close(self):
         if self.handle:

@@ -211,6 +211,35 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
     }
 }
 
+// loss[0] = sum of the squared errors, loss[1] = number of filled transitions.  One workgroup, each
+// thread a strided partial sum, then a tree over LDS: the summation order is fixed, so the result is
+// the same on every run.
+__global__ __launch_bounds__(256) void mixer_loss_kernel(const float *__restrict__ td_err, const uint8_t *__restrict__ filled,
+                                                        int rows, float *__restrict__ loss)
+{
+    __shared__ float sq[256], cnt[256];
+    float s = 0.0f, n = 0.0f;
+    for (int i = threadIdx.x; i < rows; i += 256) {
+        const float e = td_err[i];
+        s = fmaf(e, e, s);
+        n += filled[i] ? 1.0f : 0.0f;
+    }
+    sq[threadIdx.x] = s;
+    cnt[threadIdx.x] = n;
+    __syncthreads();
+    for (int half = 128; half >= 1; half >>= 1) {
+        if ((int)threadIdx.x < half) {
+            sq[threadIdx.x] += sq[threadIdx.x + half];
+            cnt[threadIdx.x] += cnt[threadIdx.x + half];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        loss[0] = sq[0];
+        loss[1] = cnt[0];
+    }
+}
+
 template <int MB, int P, int KS>
 hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
 {
@@ -413,10 +442,11 @@ void marl_mixer_destroy(marl_mixer *m)
 
 int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, const float *state,
                   const float *q_taken, const float *next_max, const float *reward, const uint8_t *terminated,
-                  const uint8_t *filled, float gamma, float *q_total, float *y_total, float *td_err,
+                  const uint8_t *filled, float gamma, float *q_total, float *y_total, float *td_err, float *loss,
                   void *hip_stream)
 {
     if (!online) return MARL_ERR_NULL;
+    if (loss && !td_err) return MARL_ERR_NULL;             // the loss is reduced from td_err
     if (!target) target = online;
     if (std::memcmp(&online->desc, &target->desc, sizeof(marl_mixer_desc)) != 0) return MARL_ERR_MISMATCH;
     if (B < 0 || T < 1 || (int64_t)B * T >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
@@ -439,6 +469,11 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
     if (online->planes == 2) err = marl::mixer_dispatch_ks<2>(a.ks, mb, a, stream);
     else err = marl::mixer_dispatch_ks<1>(a.ks, mb, a, stream);
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td launch");
+    if (loss) {
+        hipLaunchKernelGGL(marl::mixer_loss_kernel, dim3(1), dim3(256), 0, stream, td_err, filled, a.rows, loss);
+        err = hipGetLastError();
+        if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td loss launch");
+    }
     return MARL_OK;
 }
 

@@ -104,6 +104,6 @@ def test_mixer_rejects_bad_arguments_before_using_a_device(lib):
     assert create(ctypes.byref(mk(state_dim=0)), wp, w.size, ctypes.byref(out)) == -2
     assert create(ctypes.byref(mk(weight_dtype=5)), wp, w.size, ctypes.byref(out)) == -3
     assert create(ctypes.byref(mk()), wp, w.size - 1, ctypes.byref(out)) == -4
-    assert lib.marl_mixer_td(None, None, 1, 1, None, None, None, None, None, None, 0.5, None, None, None, None) == -1
+    assert lib.marl_mixer_td(None, None, 1, 1, None, None, None, None, None, None, 0.5, None, None, None, None, None) == -1
     assert lib.marl_mixer_set_weights(None, wp, w.size, None) == -1
     lib.marl_mixer_destroy(None)

@@ -34,8 +34,9 @@ def gpu_td(online, target, m, outputs=("q_total", "y_total", "td_err")):
     B, T = m["reward"].shape
     out = {k: (torch.full((B, T), float("nan"), device="cuda") if k in outputs else None)
            for k in ("q_total", "y_total", "td_err")}
+    out["loss"] = torch.full((2,), float("nan"), device="cuda") if "td_err" in outputs else None
     online.td(target, dev(m["state"]), dev(m["q_taken"]), dev(m["next_max"]), dev(m["reward"]), dev(m["terminated"]),
-              dev(m["filled"]), m["gamma"], out["q_total"], out["y_total"], out["td_err"])
+              dev(m["filled"]), m["gamma"], out["q_total"], out["y_total"], out["td_err"], out["loss"])
     torch.cuda.synchronize()
     return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
 
@@ -50,6 +51,11 @@ def check(got, ref, tol):
         err = float(np.abs(got[k] - ref[k]).max()) / scale
         assert err <= tol, f"{k}: max error {err:.3g} of scale {scale:.3g}"
         worst = max(worst, err)
+    if got.get("loss") is not None and "loss" in ref:
+        # sum of squares: each term carries twice the relative error of its td_err, fp32 summation on top
+        scale = max(1.0, float(np.abs(ref["td_err"]).max()))
+        assert got["loss"][1] == ref["loss"][1], "filled count"
+        assert abs(got["loss"][0] - ref["loss"][0]) <= 4 * tol * scale * max(1.0, float(np.abs(ref["td_err"]).sum())), "loss sum"
     return worst
 
 

@@ -144,6 +144,9 @@ def test_td_targets_by_hand():
     np.testing.assert_allclose(out["y_total"], y, atol=1e-6)
     np.testing.assert_allclose(out["td_err"], (y - q_tot) * filled, atol=1e-6)
     assert out["y_total"][0, 2] == reward[0, 2] and out["td_err"][1, 2] == 0.0
+    # the loss terms: sum of the squared errors of the five filled transitions, and their number
+    by_hand = sum(float((y[b, t] - q_tot[b, t]) ** 2) for b, t in [(0, 0), (0, 1), (0, 2), (1, 0), (1, 1)])
+    assert abs(out["loss"][0] - by_hand) < 1e-5 and out["loss"][1] == 5.0
     assert abs(out["y_total"][0, 0] - (1.0 + 0.5 * (-2.0 + 2.0 + 2.0))) < 1e-6   # next slot's state 0.2
     same = mxo.td(dims, w_on, None, state, q_taken, next_max, reward, terminated, filled, gamma)
     np.testing.assert_allclose(same["y_total"], reward + gamma * (1 - terminated) * (1.0 + next_max.sum(-1)), atol=1e-6)
