@@ -195,7 +195,7 @@ class Bench:
             self.target.close()
 
 
-def cpu_baseline(ci, budget_rows=1024):
+def cpu_baseline(ci, budget_rows=4096):
     """The oracle as it stands, timed on this host's cores on a bounded sample of the workload."""
     from oracle import marl_oracle as orc
     from paper_2205_05248_amd import workloads as wl
