@@ -251,6 +251,8 @@ typedef struct {
     const uint8_t *terminated, *filled; float gamma;
     double *q_taken, *next_max, *td_target, *q_all;
     const int32_t *row_list; /* optional list of (b*N+n) rows to evaluate */
+    int double_q;            /* the next action is chosen by the online network, valued by the target */
+    int32_t *next_action;    /* optional [B,T,N]: index of the action whose target value is bootstrapped */
 } unroll_ctx;
 
 static void unroll_row(const unroll_ctx *c, int b, int n)
@@ -278,7 +280,10 @@ static void unroll_row(const unroll_ctx *c, int b, int n)
         double f = c->filled[bt] ? 1.0 : 0.0;
         int u = c->actions[out];
         const uint8_t *av = c->avail + (((size_t)b * S + (t + 1)) * N + n) * A;
-        int best = masked_argmax(qt + (size_t)(t + 1) * A, av, A);
+        /* plain target: the target network's own best available action at t+1;
+         * double estimator: the online network's best available action at t+1 */
+        int best = masked_argmax((c->double_q ? qo : qt) + (size_t)(t + 1) * A, av, A);
+        if (c->next_action) c->next_action[out] = best;
         double nm = best < 0 ? 0.0 : qt[(size_t)(t + 1) * A + best];
         double y = (double)c->reward[bt] + (double)c->gamma * (c->terminated[bt] ? 0.0 : 1.0) * nm;
         c->q_taken[out] = f * qo[(size_t)t * A + u];
@@ -320,6 +325,32 @@ void oracle_unroll_td(int N, int D, int A, int H, const float *w_online, const f
     c.terminated = terminated; c.filled = filled; c.gamma = gamma;
     c.q_taken = q_taken; c.next_max = next_max; c.td_target = td_target; c.q_all = q_all;
     c.row_list = rows;
+    c.double_q = 0; c.next_action = NULL;
     if (rows) for_each(unroll_listed, &c, n_rows, nthreads);
     else      for_each(unroll_episode, &c, B, nthreads);
+}
+
+/* The double-estimator variant of the TD target.  Alg. 3 writes y^total without
+ * defining it; besides the plain reading above (the target network both picks
+ * and values the next action) the common alternative is
+ *   a* = argmax_{a available at t+1} Q_online(t+1, a)      (lowest index on ties)
+ *   next value = Q_target(t+1, a*),   y = r + gamma (1 - terminated) next value
+ * Same arrays as oracle_unroll_td; next_max holds the next value and
+ * next_action [B,T,N] (optional) the index a*, -1 if no action is available. */
+void oracle_unroll_td_double(int N, int D, int A, int H, const float *w_online, const float *w_target,
+                             int B, int T, const float *obs, const uint8_t *avail, const int32_t *actions,
+                             const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                             float gamma, double *q_taken, double *next_max, double *td_target,
+                             double *q_all, int32_t *next_action, int nthreads)
+{
+    unroll_ctx c;
+    net_bind(&c.online, N, D, A, H, w_online);
+    net_bind(&c.target, N, D, A, H, w_target);
+    c.same = (w_online == w_target);
+    c.B = B; c.T = T; c.obs = obs; c.avail = avail; c.actions = actions; c.reward = reward;
+    c.terminated = terminated; c.filled = filled; c.gamma = gamma;
+    c.q_taken = q_taken; c.next_max = next_max; c.td_target = td_target; c.q_all = q_all;
+    c.row_list = NULL;
+    c.double_q = 1; c.next_action = next_action;
+    for_each(unroll_episode, &c, B, nthreads);
 }

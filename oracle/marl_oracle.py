@@ -130,3 +130,33 @@ def unroll_td(dims, w_online, w_target, obs, avail, actions, reward, terminated,
         _p(out["q_taken"]), _p(out["next_max"]), _p(out["td_target"]), _p(out["q_all"]),
         _p(rows_a), 0 if rows_a is None else int(rows_a.size), int(nthreads or default_threads()))
     return out
+
+
+def unroll_td_double(dims, w_online, w_target, obs, avail, actions, reward, terminated, filled, gamma,
+                     want_q_all=True, nthreads=None):
+    """The double-estimator TD target: the online network picks the next action, the target values it.
+
+    Returns dict(q_taken, next_max, td_target [B,T,N] f64, next_action [B,T,N] i32,
+    q_all [B,T+1,N,A] f64 or None (online network)).
+    """
+    N, D, A, H = (int(v) for v in dims)
+    w_online = _c(w_online, np.float32)
+    w_target = w_online if w_target is None else _c(w_target, np.float32)
+    assert w_online.size == w_target.size == param_count(N, D, A, H)
+    obs = _c(obs, np.float32)
+    B, T = obs.shape[0], obs.shape[1] - 1
+    assert obs.shape == (B, T + 1, N, D)
+    avail = _c(avail, np.uint8); assert avail.shape == (B, T + 1, N, A)
+    actions = _c(actions, np.int32); assert actions.shape == (B, T, N)
+    reward = _c(reward, np.float32); assert reward.shape == (B, T)
+    terminated = _c(terminated, np.uint8); assert terminated.shape == (B, T)
+    filled = _c(filled, np.uint8); assert filled.shape == (B, T)
+    out = dict(q_taken=np.zeros((B, T, N)), next_max=np.zeros((B, T, N)), td_target=np.zeros((B, T, N)),
+               next_action=np.zeros((B, T, N), np.int32),
+               q_all=np.zeros((B, T + 1, N, A)) if want_q_all else None)
+    _load().oracle_unroll_td_double(
+        N, D, A, H, _p(w_online), _p(w_target), B, T, _p(obs), _p(avail), _p(actions), _p(reward),
+        _p(terminated), _p(filled), ctypes.c_float(float(np.float32(gamma))),
+        _p(out["q_taken"]), _p(out["next_max"]), _p(out["td_target"]), _p(out["q_all"]),
+        _p(out["next_action"]), int(nthreads or default_threads()))
+    return out

@@ -456,3 +456,90 @@ def test_generator_shapes_match_scenario_table():
         assert (u["filled"].sum(1) == L).all()
         assert (np.take_along_axis(u["avail"][:, :c["T"]], u["actions"][..., None].astype(np.int64), -1) == 1).all()
         assert orc.param_count(*wl.dims(c)) == wl.param_count(*wl.dims(c)) == wl.make_weights(c).size
+
+
+# ---------------------------------------------------------------- double-estimator target
+def _double(cfg, w_on, w_tg, inp):
+    return orc.unroll_td_double(wl.dims(cfg), w_on, w_tg, inp["obs"], inp["avail"], inp["actions"], inp["reward"],
+                                inp["terminated"], inp["filled"], inp["gamma"])
+
+
+def test_double_target_brute_force_from_library_q():
+    """Pick with the online network's library Q, value with the target's, written out in loops."""
+    cfg = wl.config(0)
+    dims = wl.dims(cfg)
+    N, D, A, H = dims
+    w_on, w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
+    B, T = 3, 12
+    inp = wl.make_unroll_inputs(cfg, B=B, T=T)
+    out = _double(cfg, w_on, w_tg, inp)
+    qs = {}
+    for key, w in (("on", w_on), ("tg", w_tg)):
+        step = torch_net(dims, w)
+        h = torch.zeros(B, N, H, dtype=torch.float64)
+        q_t = []
+        for t in range(T + 1):
+            h, q = step(inp["obs"][:, t], h)
+            q_t.append(q.numpy())
+        qs[key] = np.stack(q_t, 1)
+    g = float(np.float32(inp["gamma"]))
+    differs = 0
+    for b in range(B):
+        for t in range(T):
+            for n in range(N):
+                f = float(inp["filled"][b, t])
+                allowed = [a for a in range(A) if inp["avail"][b, t + 1, n, a]]
+                pick = max(allowed, key=lambda a: (qs["on"][b, t + 1, n, a], -a))
+                value = qs["tg"][b, t + 1, n, pick]
+                differs += value != max(qs["tg"][b, t + 1, n, a] for a in allowed)
+                y = float(inp["reward"][b, t]) + g * (1.0 - float(inp["terminated"][b, t])) * value
+                assert out["next_action"][b, t, n] == pick
+                assert abs(out["next_max"][b, t, n] - f * value) < 1e-12
+                assert abs(out["td_target"][b, t, n] - f * y) < 1e-12
+                assert abs(out["q_taken"][b, t, n] - f * qs["on"][b, t, n, inp["actions"][b, t, n]]) < 1e-12
+    assert differs > 0, "the case must tell the two estimators apart"
+    np.testing.assert_allclose(out["q_all"], qs["on"], rtol=0, atol=1e-12)
+
+
+def test_double_target_reduces_to_plain_target_when_networks_coincide():
+    cfg = wl.config(1)
+    dims = wl.dims(cfg)
+    w = wl.make_weights(cfg, 0)
+    inp = wl.make_unroll_inputs(cfg, B=2, T=9)
+    plain = orc.unroll_td(dims, w, None, inp["obs"], inp["avail"], inp["actions"], inp["reward"],
+                          inp["terminated"], inp["filled"], inp["gamma"])
+    both = _double(cfg, w, None, inp)
+    for k in ("q_taken", "next_max", "td_target"):
+        np.testing.assert_array_equal(both[k], plain[k])
+    # and never above the plain target's bootstrap when the networks differ (max is an upper bound)
+    w2 = wl.make_weights(cfg, 1)
+    plain2 = orc.unroll_td(dims, w, w2, inp["obs"], inp["avail"], inp["actions"], inp["reward"],
+                           inp["terminated"], inp["filled"], inp["gamma"])
+    both2 = _double(cfg, w, w2, inp)
+    assert (both2["next_max"] <= plain2["next_max"] + 1e-15).all()
+    assert (both2["next_max"] < plain2["next_max"]).any()
+
+
+def test_double_target_hand_set_q_ties_and_masks():
+    """Q = b2 for both networks: the online b2 decides the index, the target b2 gives the value."""
+    cfg = small_cfg(N=2, D=3, A=4, H=4)
+    dims = wl.dims(cfg)
+    parts_on, parts_tg = zero_parts(dims), zero_parts(dims)
+    parts_on["b2"] = np.array([1.0, 3.0, 3.0, 2.0])          # tie between actions 1 and 2: lowest index
+    parts_tg["b2"] = np.array([10.0, 20.0, 30.0, 40.0])
+    w_on, w_tg = wl.pack_weights(dims, parts_on), wl.pack_weights(dims, parts_tg)
+    B, T = 1, 3
+    inp = wl.make_unroll_inputs(cfg, B=B, T=T)
+    inp["avail"][:] = 1
+    inp["avail"][0, 2, 0, 1] = 0                             # agent 0 at slot 2: action 1 unavailable -> 2
+    inp["avail"][0, 3, 1, 1:3] = 0                           # agent 1 at slot 3: only {0, 3} -> 3
+    inp["filled"][:] = 1
+    inp["terminated"][:] = 0
+    inp["terminated"][0, 2] = 1
+    inp["reward"][:] = np.array([[0.5, -1.0, 2.0]], np.float32)
+    out = _double(cfg, w_on, w_tg, inp)
+    np.testing.assert_array_equal(out["next_action"][0], [[1, 1], [2, 1], [1, 3]])
+    np.testing.assert_array_equal(out["next_max"][0], [[20.0, 20.0], [30.0, 20.0], [20.0, 40.0]])
+    g = float(np.float32(inp["gamma"]))
+    expect = np.array([[0.5 + g * 20, 0.5 + g * 20], [-1 + g * 30, -1 + g * 20], [2.0, 2.0]])
+    np.testing.assert_allclose(out["td_target"][0], expect, rtol=0, atol=1e-12)
