@@ -172,12 +172,19 @@ class Bench:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
-    def single_net_unroll(self, n=10):
-        """target == online: one network's unroll instead of two."""
+    def single_net_unroll(self, n=10, double=False):
+        """target == online: one network's unroll instead of two; double: the double-estimator
+        target (the two networks one after the other, the second valuing the first's choice)."""
         torch = self.torch
         u = self.u
-        call = lambda: self.online.unroll_td(None, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
-                                             u["filled"], self.u_host["gamma"], *self.u_out)
+        if double:
+            nxt = torch.empty(self.u_out[0].shape, dtype=torch.int32, device="cuda")
+            call = lambda: self.online.unroll_td_double(self.target, u["obs"], u["avail"], u["actions"], u["reward"],
+                                                        u["terminated"], u["filled"], self.u_host["gamma"],
+                                                        *self.u_out, nxt)
+        else:
+            call = lambda: self.online.unroll_td(None, u["obs"], u["avail"], u["actions"], u["reward"],
+                                                 u["terminated"], u["filled"], self.u_host["gamma"], *self.u_out)
         for _ in range(2):
             call()
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -306,6 +313,7 @@ def main():
     act_b2b_ms = b.back_to_back_act()
     act_cached_ms = b.cache_resident_act()
     single_net_ms = b.single_net_unroll()
+    double_ms = b.single_net_unroll(double=True)
     b.close()
 
     ms_per_step = wall * 1e3 / args.steps
@@ -374,6 +382,7 @@ def main():
         "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),
                       "agent_steps_per_s": steps_unroll / (unroll_ms * 1e-3), "kernels_ms": unroll_ms,
                       "single_network_ms": single_net_ms,
+                      "double_estimator_target_ms": double_ms,
                       "kernels": {n: {"ms": v["ms"], "TFLOPs": v["TFLOPs"], "mfma_frac": v["mfma_frac"],
                                       "GBs": v["GBs"], "hbm_frac": v["hbm_frac"]}
                                   for n, v in kernels.items() if n != "act_step"}},

@@ -212,6 +212,31 @@ int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_ep
                            float gamma, float *q_taken, float *next_max, float *td_target,
                            float *q_all, void *hip_stream);
 
+/*
+ * The unroll with the double-estimator TD target.  Alg. 3 uses y^total without defining it;
+ * marl_unroll_td takes the target network's own maximum, this call lets the online network
+ * choose the next action and the target network value it:
+ *   a*[b,t,n]  = lowest-index maximiser over available a of Q_online(t+1)[a]   (-1 if none)
+ *   next_max   = filled * Q_target(t+1)[a*]                                    (0 if none)
+ *   td_target  = filled * (reward + gamma * (1 - terminated) * Q_target(t+1)[a*])
+ *   q_taken, q_all: as marl_unroll_td
+ *   next_action dev [B,T,N] i32, required: receives a* (written for padding steps too)
+ *   episode_index NULL: the input arrays hold the batch itself (pool_episodes is ignored);
+ *   else as marl_unroll_td_indexed.
+ * The networks run one after the other on the stream (two launches of the single-network
+ * kernels, the second reading next_action), in either kernel family; `online` and `target` may
+ * be the same handle, and the result then equals marl_unroll_td's.  The choice of a* is made in
+ * fp32 on the library's Q values: where two available actions are within rounding of each other
+ * another evaluation order may choose the other one.
+ * Errors as marl_unroll_td, plus MARL_ERR_NULL for a missing next_action.
+ */
+int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_episodes,
+                          const int32_t *episode_index, int32_t B, int32_t T,
+                          const float *obs, const uint8_t *avail, const int32_t *actions,
+                          const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                          float gamma, float *q_taken, float *next_max, float *td_target,
+                          int32_t *next_action, float *q_all, void *hip_stream);
+
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*

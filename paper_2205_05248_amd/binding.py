@@ -20,6 +20,7 @@ MARL_DTYPE_BF16 = 1
 DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
+           "marl_unroll_td_double",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
@@ -76,6 +77,8 @@ def load():
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_unroll_td_indexed.restype = ctypes.c_int
         lib.marl_unroll_td_indexed.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        lib.marl_unroll_td_double.restype = ctypes.c_int
+        lib.marl_unroll_td_double.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
         lib.marl_qnet_kernels_in_use.restype = ctypes.c_int
@@ -251,6 +254,23 @@ def marl_unroll_td_indexed(online, target, dims, episode_index, obs, avail, acti
         _stream()))
 
 
+def marl_unroll_td_double(online, target, dims, obs, avail, actions, reward, terminated, filled, gamma,
+                          q_taken, next_max, td_target, next_action, q_all=None, episode_index=None):
+    """Double-estimator target; with episode_index the inputs are pool arrays as in marl_unroll_td_indexed."""
+    N, D, A, H = dims
+    pool, T = obs.shape[0], obs.shape[1] - 1
+    B = pool if episode_index is None else int(episode_index.shape[0])
+    check(load().marl_unroll_td_double(
+        ctypes.c_void_p(online), ctypes.c_void_p(target), pool,
+        _dev(episode_index, "i32", (B,), "episode_index", optional=True), B, T,
+        _dev(obs, "f32", (pool, T + 1, N, D), "obs"), _dev(avail, "u8", (pool, T + 1, N, A), "avail"),
+        _dev(actions, "i32", (pool, T, N), "actions"), _dev(reward, "f32", (pool, T), "reward"),
+        _dev(terminated, "u8", (pool, T), "terminated"), _dev(filled, "u8", (pool, T), "filled"), float(gamma),
+        _dev(q_taken, "f32", (B, T, N), "q_taken"), _dev(next_max, "f32", (B, T, N), "next_max"),
+        _dev(td_target, "f32", (B, T, N), "td_target"), _dev(next_action, "i32", (B, T, N), "next_action"),
+        _dev(q_all, "f32", (B, T + 1, N, A), "q_all", optional=True), _stream()))
+
+
 class QNet:
     """Convenience owner of one handle (create on init, destroy on close)."""
 
@@ -268,6 +288,12 @@ class QNet:
         tgt = self if target is None else target
         marl_unroll_td_indexed(self.handle, tgt.handle, self.dims, episode_index, obs, avail, actions, reward,
                                terminated, filled, gamma, q_taken, next_max, td_target, q_all)
+
+    def unroll_td_double(self, target, obs, avail, actions, reward, terminated, filled, gamma,
+                         q_taken, next_max, td_target, next_action, q_all=None, episode_index=None):
+        tgt = self if target is None else target
+        marl_unroll_td_double(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
+                              gamma, q_taken, next_max, td_target, next_action, q_all, episode_index)
 
     def act_step_indexed(self, env_index, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
         marl_act_step_indexed(self.handle, self.dims, env_index, obs, avail, h_in, reset, step_t, epsilon, seed,

@@ -49,31 +49,6 @@ struct ActFusedArgs {
     float *q_out;               // may be null
 };
 
-// Masked argmax of a row whose Q values are split over the four lanes c, c + 16, c + 32, c + 48;
-// lowest index on ties; idx = -1 when nothing is available.
-template <int AB>
-__device__ __forceinline__ void masked_argmax16(const f32x4 (&qv)[AB], uint32_t slots, int q, float &best_q, int &best_idx)
-{
-    best_q = 0.0f; best_idx = -1;
-#pragma unroll
-    for (int ab = 0; ab < AB; ++ab)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const bool ok = (slots >> (4 * ab + r)) & 1u;
-            if (ok && (best_idx < 0 || qv[ab][r] > best_q)) { best_q = qv[ab][r]; best_idx = 16 * ab + 4 * q + r; }
-        }
-    auto better = [](float qa, int ia, float qb, int ib, float &q_out, int &i_out) {      // a: the lower quarter
-        const bool take_b = ib >= 0 && (ia < 0 || qb > qa || (qb == qa && ib < ia));
-        q_out = take_b ? qb : qa;
-        i_out = take_b ? ib : ia;
-    };
-    LanePair pq = halves16(__float_as_uint(best_q)), pi = halves16((uint32_t)best_idx);
-    better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
-    pq = halves32(__float_as_uint(best_q));
-    pi = halves32((uint32_t)best_idx);
-    better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
-}
-
 // Availability bits of the whole row (bit a = action a) from the four lanes' slot masks.
 template <int AB>
 __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)

@@ -374,7 +374,7 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
     const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions,
     const float *__restrict__ reward, const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled,
     float gamma, float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target,
-    float *__restrict__ q_all)
+    float *__restrict__ q_all, int mode, int32_t *__restrict__ next_action)
 {
     using Shape = RecurrentShape<H, P>;
     constexpr int KCH = H / 16;
@@ -394,7 +394,8 @@ __global__ __launch_bounds__(64 * recurrent_waves(H), 2) void recurrent_td_kerne
     if (wave < Shape::kCompute) {
         compute_role<H, P>(net, wave, lane, T, 1, &gi_lds[0][0], h_lds);
     } else if (wave == Shape::kCompute) {
-        const TdArrays td{episode_index, pool_episodes, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all};
+        const TdArrays td{episode_index, pool_episodes, avail, actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
+                          mode, next_action};
         epilogue_role<H, P, MB2, QALL>(net, td, !is_target, is_target || !two_nets, rt, lane, B, T, 1, h_lds, b2_lds);
     } else {
         // ---------------------------------------------------------------- prefetch wave
@@ -450,7 +451,7 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
                            int B, int T, const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
                            const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
                            float *q_taken, float *next_max, float *td_target, float *q_all, hipStream_t stream,
-                           hipEvent_t between)
+                           hipEvent_t between, TdMode mode, int32_t *next_action)
 {
     const int rows = B * online.N, tiles = (rows + 31) / 32;
     const unsigned nets = two_nets ? 2u : 1u;
@@ -476,7 +477,7 @@ hipError_t unroll_dispatch(const NetFrags &online, const NetFrags &target, bool 
 #define MARL_REC(MB, QA)                                                                                             \
     hipLaunchKernelGGL((recurrent_td_kernel<H, P, MB, QA>), grid, block, 0, stream, online, target, gi_on, gi_tg, two,  \
                        B, T, episode_index, pool_episodes, avail, actions, reward, terminated, filled, gamma, q_taken,      \
-                       next_max, td_target, q_all)
+                       next_max, td_target, q_all, (int)mode, next_action)
     if (online.mb2 == 1) { if (q_all) MARL_REC(1, true); else MARL_REC(1, false); }
     else                 { if (q_all) MARL_REC(2, true); else MARL_REC(2, false); }
 #undef MARL_REC
@@ -513,13 +514,15 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
                             const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
-                            float *q_all, hipStream_t stream, hipEvent_t between)
+                            float *q_all, hipStream_t stream, hipEvent_t between, TdMode mode, int32_t *next_action)
 {
+    if (mode != kTdPlain && (two_nets || !next_action)) return hipErrorInvalidValue;
     char *gi_on = static_cast<char *>(scratch_online), *gi_tg = static_cast<char *>(scratch_target);
 #define MARL_UNROLL(HH, PP)                                                                                        \
     return unroll_dispatch<HH, PP>(online, target, two_nets, gi_on, gi_tg, B, T, episode_index, pool_episodes, obs, \
                                    avail, actions, reward,                                                         \
-                                   terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream, between)
+                                   terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream, between,  \
+                                   mode, next_action)
     if (online.H == 64 && online.planes == 2) MARL_UNROLL(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_UNROLL(64, 1);
     if (online.H == 128 && online.planes == 2) MARL_UNROLL(128, 2);

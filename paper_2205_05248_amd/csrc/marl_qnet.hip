@@ -304,7 +304,8 @@ namespace {
 int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const int32_t *episode_index,
                 int32_t pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
                 const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
-                float *next_max, float *td_target, float *q_all, void *hip_stream)
+                float *next_max, float *td_target, float *q_all, void *hip_stream, bool double_q = false,
+                int32_t *next_action = nullptr)
 {
     if (!online || !target) return MARL_ERR_NULL;
     const marl_qnet_desc &a = online->desc, &b = target->desc;
@@ -322,16 +323,17 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
     if (B == 0) return MARL_OK;
     if (!obs || !avail || !actions || !reward || !terminated || !filled || !q_taken || !next_max || !td_target)
         return MARL_ERR_NULL;
+    if (double_q && !next_action) return MARL_ERR_NULL;
 
     DeviceGuard guard(a.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
-    const bool two = online != target;
+    const bool two = online != target && !double_q;      // the double-estimator target runs the networks one after the other
     const bool fused = takes_fused_path(online, true);
     int rc = MARL_OK;
     if (!fused) {
         const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
         rc = ensure_scratch(online, need);
-        if (rc == MARL_OK && two) rc = ensure_scratch(target, need);
+        if (rc == MARL_OK && online != target) rc = ensure_scratch(target, need);
         if (rc != MARL_OK) return rc;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -342,6 +344,30 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
         if (rc != MARL_OK) return rc;
     }
     if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
+    if (double_q) {
+        // Selection by the online network (q_taken, q_all, next_action), then valuation by the target
+        // network (next_max, td_target); the stream orders the second launch after the first.
+        if (fused) {
+            if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
+            MARL_HIP(marl::launch_unroll_fused(online->net, online->net, false, B, T, episode_index, pool_episodes, obs,
+                                               avail, actions, reward, terminated, filled, gamma, q_taken, nullptr,
+                                               nullptr, q_all, stream, marl::kTdSelect, next_action));
+            MARL_HIP(marl::launch_unroll_fused(target->net, target->net, false, B, T, episode_index, pool_episodes, obs,
+                                               avail, actions, reward, terminated, filled, gamma, nullptr, next_max,
+                                               td_target, nullptr, stream, marl::kTdValue, next_action));
+        } else {
+            MARL_HIP(marl::launch_unroll_td(online->net, online->net, false, online->scratch, online->scratch, B, T,
+                                            episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                                            filled, gamma, q_taken, nullptr, nullptr, q_all, stream,
+                                            ev ? ev[1] : nullptr, marl::kTdSelect, next_action));
+            MARL_HIP(marl::launch_unroll_td(target->net, target->net, false, target->scratch, target->scratch, B, T,
+                                            episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                                            filled, gamma, nullptr, next_max, td_target, nullptr, stream, nullptr,
+                                            marl::kTdValue, next_action));
+        }
+        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
+        return MARL_OK;
+    }
     if (fused) {
         if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
         MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
@@ -377,6 +403,17 @@ int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_ep
     if (B > 0 && !episode_index) return MARL_ERR_NULL;
     return unroll_call(online, target, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
                        filled, gamma, q_taken, next_max, td_target, q_all, hip_stream);
+}
+
+int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_episodes, const int32_t *episode_index,
+                          int32_t B, int32_t T, const float *obs, const uint8_t *avail, const int32_t *actions,
+                          const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma,
+                          float *q_taken, float *next_max, float *td_target, int32_t *next_action, float *q_all,
+                          void *hip_stream)
+{
+    return unroll_call(online, target, B, T, episode_index, episode_index ? pool_episodes : B, obs, avail, actions,
+                       reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, hip_stream, true,
+                       next_action);
 }
 
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable)

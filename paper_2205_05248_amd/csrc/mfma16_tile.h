@@ -112,6 +112,41 @@ __device__ __forceinline__ uint32_t or_quarters(uint32_t x)
     return p.lower | p.upper;
 }
 
+// Masked argmax of a row whose Q values are split over the four lanes c, c + 16, c + 32, c + 48;
+// lowest index on ties; idx = -1 when nothing is available.  The quarters are combined with lane
+// swaps (vector instructions), or with LDS shuffles when VIA_LDS (see masked_max16 for when).
+template <int AB, bool VIA_LDS = false>
+__device__ __forceinline__ void masked_argmax16(const f32x4 (&qv)[AB], uint32_t slots, int q, float &best_q, int &best_idx)
+{
+    best_q = 0.0f; best_idx = -1;
+#pragma unroll
+    for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool ok = (slots >> (4 * ab + r)) & 1u;
+            if (ok && (best_idx < 0 || qv[ab][r] > best_q)) { best_q = qv[ab][r]; best_idx = 16 * ab + 4 * q + r; }
+        }
+    auto better = [](float qa, int ia, float qb, int ib, float &q_out, int &i_out) {      // ties: the lower index
+        const bool take_b = ib >= 0 && (ia < 0 || qb > qa || (qb == qa && ib < ia));
+        q_out = take_b ? qb : qa;
+        i_out = take_b ? ib : ia;
+    };
+    if constexpr (VIA_LDS) {
+#pragma unroll
+        for (int d = 16; d <= 32; d *= 2) {
+            const float oq = __shfl_xor(best_q, d);
+            const int oi = __shfl_xor(best_idx, d);
+            better(best_q, best_idx, oq, oi, best_q, best_idx);
+        }
+    } else {
+        LanePair pq = halves16(__float_as_uint(best_q)), pi = halves16((uint32_t)best_idx);
+        better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
+        pq = halves32(__float_as_uint(best_q));
+        pi = halves32((uint32_t)best_idx);
+        better(__uint_as_float(pq.lower), (int)pi.lower, __uint_as_float(pq.upper), (int)pi.upper, best_q, best_idx);
+    }
+}
+
 // The unroll's per-slot reductions below go through LDS shuffles instead: they cost the wave a
 // wait but no vector issue slots, which it shares with a compute wave; and with their cost off
 // the SIMD the online and the target workgroup of a tile keep the same pace, so the second of them

@@ -100,12 +100,21 @@ hipError_t launch_act_step(const NetFrags &net, int E, const int32_t *env_index,
 
 size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
 
+// What an unroll launch does with the value of the next slot.  kTdPlain: the masked maximum of the
+// evaluating network (next_max, td_target).  The double-estimator target takes two single-network
+// launches: kTdSelect with the online network stores, besides q_taken, the index of its best
+// available action of slot t + 1 into next_action[b, t, n] (-1: none available) and leaves
+// next_max / td_target alone; kTdValue with the target network reads those indices and writes
+// next_max / td_target from its own value of that action, and leaves q_taken / q_all alone.
+enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2 };
+
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
                             void *scratch_target, int B, int T, const int32_t *episode_index, int pool_episodes,
                             const float *obs, const uint8_t *avail,
                             const int32_t *actions, const float *reward, const uint8_t *terminated,
                             const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
-                            float *q_all, hipStream_t stream, hipEvent_t between);
+                            float *q_all, hipStream_t stream, hipEvent_t between, TdMode mode = kTdPlain,
+                            int32_t *next_action = nullptr);
 
 // Fused decision step (act_fused.hip).  `fits` as below; groups_hint = workgroups to spread the
 // tiles over (0: one per compute unit).
@@ -122,6 +131,7 @@ bool unroll_fused_fits(const NetFrags &net);
 hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
                                const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
-                               float *next_max, float *td_target, float *q_all, hipStream_t stream);
+                               float *next_max, float *td_target, float *q_all, hipStream_t stream,
+                               TdMode mode = kTdPlain, int32_t *next_action = nullptr);
 
 }  // namespace marl

@@ -92,6 +92,8 @@ struct TdArrays {
     const uint8_t *filled;
     float gamma;
     float *q_taken, *next_max, *td_target, *q_all;
+    int mode;                       // TdMode
+    int32_t *next_action;           // written under kTdSelect, read under kTdValue, unused otherwise
 };
 
 // emit_online: q_taken (and q_all); emit_target: next_max and td_target.  b2_lds: 32 MB2 floats
@@ -104,6 +106,8 @@ __device__ __forceinline__ void epilogue_role(const NetFrags &net, const TdArray
     constexpr int KCH = H / 16;
     const int g = lane >> 5, col = lane & 31;
     const int N = net.N, A = net.A, S = T + 1;
+    const bool select = td.mode == kTdSelect, value = td.mode == kTdValue;
+    emit_online = emit_online && !value;
     const int rows = B * N;
     const int row = rt * 32 + col;
     const bool valid = row < rows;
@@ -139,7 +143,8 @@ __device__ __forceinline__ void epilogue_role(const NetFrags &net, const TdArray
             in.on_filled = valid ? td.filled[bt0 + t] : 0;
         }
         if (emit_target && t >= 1) {
-            if (A >= 4) issue_avail_loads<MB2>(td.avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, in.avail_raw);
+            if (value) in.u = valid ? td.next_action[btn0 + (uint32_t)(t - 1) * N] : -1;
+            else if (A >= 4) issue_avail_loads<MB2>(td.avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, in.avail_raw);
             in.reward = valid ? td.reward[bt0 + t - 1] : 0.0f;
             in.terminated = valid ? td.terminated[bt0 + t - 1] : 0;
             in.tg_filled = valid ? td.filled[bt0 + t - 1] : 0;
@@ -181,12 +186,24 @@ __device__ __forceinline__ void epilogue_role(const NetFrags &net, const TdArray
                 }
             }
             if (emit_target && t >= 1) {
-                const uint32_t slots =
-                    A >= 4 ? avail_mask_from_raw<MB2>(in.avail_raw, A, lane, valid)
-                           : avail_mask_small(td.avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, valid);
-                const float best_q = masked_max_slots<MB2>(q, slots);
-                if (valid && g == 0) {
-                    const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
+                const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
+                float best_q;
+                if (value) {                       // the value of the action the other network chose
+                    const float picked = pick_action_value<MB2>(q, min(max(in.u, 0), A - 1), lane);
+                    best_q = in.u >= 0 ? picked : 0.0f;
+                } else {
+                    const uint32_t slots =
+                        A >= 4 ? avail_mask_from_raw<MB2>(in.avail_raw, A, lane, valid)
+                               : avail_mask_small(td.avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, lane, valid);
+                    if (select) {
+                        int best;
+                        masked_argmax_slots<MB2>(q, slots, lane, best_q, best);
+                        if (valid && g == 0) td.next_action[o] = best;
+                    } else {
+                        best_q = masked_max_slots<MB2>(q, slots);
+                    }
+                }
+                if (!select && valid && g == 0) {
                     const float keep = in.terminated ? 0.0f : 1.0f;
                     const float y = in.reward + td.gamma * keep * best_q;
                     td.next_max[o] = in.tg_filled ? best_q : 0.0f;

@@ -36,13 +36,14 @@
 
 namespace marl {
 
-template <int H, int P, int AB, bool QALL>
+template <int H, int P, int AB, bool QALL, int MODE>
 __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     NetFrags online, NetFrags target, int two_nets, int B, int T, const int32_t *__restrict__ episode_index,
     int pool_episodes, const float *__restrict__ obs,
     const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions, const float *__restrict__ reward,
     const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled, float gamma,
-    float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target, float *__restrict__ q_all)
+    float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target, float *__restrict__ q_all,
+    int32_t *__restrict__ next_action)
 {
     using Sh = Fused16<H, P>;
     constexpr int FBK = Sh::FBK, KS = Sh::KS, LEAD = kFusedLead;
@@ -102,7 +103,9 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         }
     } else if (wave == Sh::kEpilogue) {
         // ---------------------------------------------------------------- epilogue wave
-        const bool emit_online = !is_target, emit_target = is_target || !two_nets;
+        // kSelect / kValue: the two single-network launches of the double-estimator target
+        constexpr bool kSelect = MODE == kTdSelect, kValue = MODE == kTdValue;
+        const bool emit_online = !is_target && !kValue, emit_target = is_target || !two_nets;
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
         WFrag<P> w2[AB][KS];
 #pragma unroll
@@ -125,7 +128,8 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                 in.on_filled = valid ? filled[bt0 + t] : 0;
             }
             if (emit_target && t >= 1) {
-                if (A >= 4) issue_avail_loads16<AB>(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, in.avail_raw);
+                if constexpr (kValue) in.u = valid ? next_action[btn0 + (uint32_t)(t - 1) * N] : -1;
+                else if (A >= 4) issue_avail_loads16<AB>(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, in.avail_raw);
                 in.reward = valid ? reward[bt0 + t - 1] : 0.0f;
                 in.terminated = valid ? terminated[bt0 + t - 1] : 0;
                 in.tg_filled = valid ? filled[bt0 + t - 1] : 0;
@@ -161,12 +165,24 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                     }
                 }
                 if (emit_target && t >= 1) {
-                    const uint32_t slots =
-                        A >= 4 ? avail_mask16<AB>(in.avail_raw, A, q4, valid)
-                               : avail_mask_small16(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, valid);
-                    const float best_q = masked_max16<AB>(qv, slots);
-                    if (valid && q4 == 0) {
-                        const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
+                    const uint32_t o = btn0 + (uint32_t)(t - 1) * N;
+                    float best_q;
+                    if constexpr (kValue) {               // the value of the action the other network chose
+                        const float picked = pick_action_value16<AB>(qv, min(max(in.u, 0), A - 1), q4);
+                        best_q = in.u >= 0 ? picked : 0.0f;
+                    } else {
+                        const uint32_t slots =
+                            A >= 4 ? avail_mask16<AB>(in.avail_raw, A, q4, valid)
+                                   : avail_mask_small16(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, valid);
+                        if constexpr (kSelect) {
+                            int best;
+                            masked_argmax16<AB, true>(qv, slots, q4, best_q, best);
+                            if (valid && q4 == 0) next_action[o] = best;
+                        } else {
+                            best_q = masked_max16<AB>(qv, slots);
+                        }
+                    }
+                    if (!kSelect && valid && q4 == 0) {
                         const float keep = in.terminated ? 0.0f : 1.0f;
                         const float y = in.reward + gamma * keep * best_q;
                         next_max[o] = in.tg_filled ? best_q : 0.0f;
@@ -237,7 +253,8 @@ template <int H, int P>
 hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
                           const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                           const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
-                          float *next_max, float *td_target, float *q_all, hipStream_t stream)
+                          float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
+                          int32_t *next_action)
 {
     using Sh = Fused16<H, P>;
     const int tiles = (B * online.N + 15) / 16;
@@ -245,16 +262,22 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
     const size_t lds = Sh::lds_bytes((online.D + 31) / 32);
     const int two = two_nets ? 1 : 0;
     const int ab = (online.A + 15) / 16;
-#define MARL_FUSED(ABLK, QA)                                                                                        \
+#define MARL_FUSED(ABLK, QA, MD)                                                                                    \
     do {                                                                                                            \
-        auto kernel = unroll_fused_kernel<H, P, ABLK, QA>;                                                          \
-        hipError_t err = allow_large_lds<unroll_fused_kernel<H, P, ABLK, QA>>(kLdsLimit);                           \
+        auto kernel = unroll_fused_kernel<H, P, ABLK, QA, MD>;                                                      \
+        hipError_t err = allow_large_lds<unroll_fused_kernel<H, P, ABLK, QA, MD>>(kLdsLimit);                       \
         if (err != hipSuccess) return err;                                                                          \
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, episode_index, pool_episodes, \
                            obs, avail, actions,                                                                      \
-                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all);                 \
+                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, next_action);    \
     } while (0)
-#define MARL_FUSED_Q(ABLK) do { if (q_all) MARL_FUSED(ABLK, true); else MARL_FUSED(ABLK, false); } while (0)
+#define MARL_FUSED_Q(ABLK)                                                                                          \
+    do {                                                                                                            \
+        if (mode == kTdValue) MARL_FUSED(ABLK, false, kTdValue);                                                    \
+        else if (mode == kTdSelect) { if (q_all) MARL_FUSED(ABLK, true, kTdSelect); else MARL_FUSED(ABLK, false, kTdSelect); } \
+        else if (q_all) MARL_FUSED(ABLK, true, kTdPlain);                                                           \
+        else MARL_FUSED(ABLK, false, kTdPlain);                                                                     \
+    } while (0)
     switch (ab) {
     case 1: MARL_FUSED_Q(1); break;
     case 2: MARL_FUSED_Q(2); break;
@@ -287,11 +310,13 @@ bool unroll_fused_fits(const NetFrags &net)
 hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, bool two_nets, int B, int T,
                                const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
-                               float *next_max, float *td_target, float *q_all, hipStream_t stream)
+                               float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
+                               int32_t *next_action)
 {
+    if (mode != kTdPlain && (two_nets || !next_action)) return hipErrorInvalidValue;
 #define MARL_GO(HH, PP)                                                                                             \
     return fused_dispatch<HH, PP>(online, target, two_nets, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated, filled,  \
-                                  gamma, q_taken, next_max, td_target, q_all, stream)
+                                  gamma, q_taken, next_max, td_target, q_all, stream, mode, next_action)
     if (online.H == 64 && online.planes == 2) MARL_GO(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_GO(64, 1);
     if (online.H == 128 && online.planes == 1) MARL_GO(128, 1);

@@ -75,6 +75,8 @@ def test_calls_reject_null_handles(lib):
     assert lib.marl_act_step_indexed(None, 4, None, 2, None, None, None, None, None, 0.0, 0, None, None, None, None) == -1
     assert lib.marl_unroll_td_indexed(None, None, 8, None, 1, 1, None, None, None, None, None, None, 0.9, None, None, None,
                                       None, None) == -1
+    assert lib.marl_unroll_td_double(None, None, 8, None, 1, 1, None, None, None, None, None, None, 0.9, None, None, None,
+                                     None, None, None) == -1
     assert lib.marl_qnet_reserve_unroll(None, 1, 1) == -1
     assert lib.marl_qnet_get_desc(None, None) == -1
     assert lib.marl_destroy(None) == 0

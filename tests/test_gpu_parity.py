@@ -544,3 +544,101 @@ def test_indexed_unroll_reads_the_batch_from_a_pool(ci, pool, B):
     got32["q_all"] = q_all.cpu().numpy()
     pu.compare_unroll(got32, oracle_unroll(cfg, w, w_tg, packed), tol)
     net.close(); target.close()
+
+
+# ------------------------------------------------------------------ double-estimator target
+def run_double(net, target, cfg, u, d, index=None, want_q_all=True):
+    N, D, A, H = wl.dims(cfg)
+    T = u["actions"].shape[1]
+    B = u["actions"].shape[0] if index is None else index.shape[0]
+    outs = {k: torch.full((B, T, N), float("nan"), device="cuda") for k in ("q_taken", "next_max", "td_target")}
+    nxt = torch.full((B, T, N), -9, dtype=torch.int32, device="cuda")
+    q_all = torch.full((B, T + 1, N, A), float("nan"), device="cuda") if want_q_all else None
+    net.unroll_td_double(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                         u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], nxt, q_all,
+                         None if index is None else torch.from_numpy(index).cuda())
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in outs.items()}
+    got["next_action"] = nxt.cpu().numpy()
+    got["q_all"] = None if q_all is None else q_all.cpu().numpy()
+    return got
+
+
+def compare_double(cfg, u, got, w_on, w_tg, tol):
+    """u: the batch as the oracle sees it.  The index is exact wherever the online network's best
+    available value at t+1 leads by more than tol; inside a near-tie any available action within
+    tol of the best passes.  The values are those of the target network at the index returned."""
+    dims = wl.dims(cfg)
+    ref = orc.unroll_td_double(dims, w_on, w_tg, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
+                               u["filled"], u["gamma"])
+    q_tg = orc.unroll_td(dims, w_tg, None, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
+                         u["filled"], u["gamma"])["q_all"]
+    assert np.abs(got["q_taken"] - ref["q_taken"]).max() <= tol
+    if got["q_all"] is not None:
+        assert np.abs(got["q_all"] - ref["q_all"]).max() <= tol
+    avail = u["avail"][:, 1:] != 0
+    masked = np.where(avail, ref["q_all"][:, 1:], -np.inf)
+    top = np.sort(masked, -1)
+    best = top[..., -1]
+    second = top[..., -2] if masked.shape[-1] > 1 else np.full(best.shape, -np.inf)
+    none = ~avail.any(-1)
+    with np.errstate(invalid="ignore"):
+        clear = ((best - second) > tol) | none
+    a = got["next_action"]
+    assert (a[clear] == ref["next_action"][clear]).all(), "index mismatch outside near-ties"
+    assert (a[none] == -1).all()
+    tie = ~clear
+    if tie.any():
+        chosen = np.take_along_axis(masked[tie], a[tie].astype(np.int64)[:, None], -1)[:, 0]
+        assert (chosen >= best[tie] - tol).all(), "near-tie index is not one of the leaders"
+    value = np.take_along_axis(q_tg[:, 1:], np.maximum(a, 0).astype(np.int64)[..., None], -1)[..., 0]
+    value = np.where(none, 0.0, value)
+    f = (u["filled"] != 0).astype(np.float64)[..., None]
+    keep = 1.0 - (u["terminated"] != 0).astype(np.float64)[..., None]
+    y = u["reward"].astype(np.float64)[..., None] + float(np.float32(u["gamma"])) * keep * value
+    assert np.abs(got["next_max"] - f * value).max() <= tol
+    assert np.abs(got["td_target"] - f * y).max() <= tol
+    assert (a[clear] == ref["next_action"][clear]).mean() == 1.0
+    return int(tie.sum())
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("ci,B,T", [(0, 32, 25), (1, 13, 9), (2, 7, 12), (3, 33, 5), (4, 5, 11)])
+def test_double_estimator_target(ci, B, T, path):
+    cfg = dict(wl.config(ci), B=B, T=T)
+    tol = pu.TOL[cfg["dtype"]]
+    net, w = make_net(cfg, kernels=path)
+    target, w_tg = make_net(cfg, 1, kernels=path)
+    assert net.kernels_in_use(binding.ENTRY_UNROLL_TD) == path
+    keys = ["obs", "avail", "actions", "reward", "terminated", "filled"]
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    u["avail"][0, 2, 0, :] = 0                                 # a row with nothing available: index -1, value 0
+    d = pu.to_dev(u, keys)
+    got = run_double(net, target, cfg, u, d)
+    ties = compare_double(cfg, u, got, w, w_tg, tol)
+    assert ties < (0.05 if cfg["dtype"] == "fp32" else 0.25) * got["next_action"].size     # the exact check covers the rest
+    # it is not the plain target: somewhere the target network prefers another action
+    plain = pu.gpu_unroll(net, target, cfg, u)
+    assert (got["next_max"] <= plain["next_max"] + 2 * tol).all() and (got["next_max"] < plain["next_max"]).any()
+    np.testing.assert_array_equal(got["q_taken"], plain["q_taken"])
+    np.testing.assert_array_equal(got["q_all"], plain["q_all"])
+    # one handle on both sides: the plain target's numbers, bit for bit
+    one = run_double(net, None, cfg, u, d, want_q_all=False)
+    plain_one = pu.gpu_unroll(net, None, cfg, u, want_q_all=False)
+    for k in ("q_taken", "next_max", "td_target"):
+        np.testing.assert_array_equal(one[k], plain_one[k])
+    # the batch read in place from a pool
+    pick = np.random.default_rng(ci + 20).integers(0, B, 6).astype(np.int32)
+    packed = dict(u, **{k: np.ascontiguousarray(u[k][pick]) for k in keys})
+    pooled = run_double(net, target, cfg, u, d, index=pick)
+    compare_double(cfg, packed, pooled, w, w_tg, tol)
+    for k in ("q_taken", "next_max", "td_target", "next_action", "q_all"):
+        np.testing.assert_array_equal(pooled[k], got[k][pick])
+    # a missing index array is refused before anything is launched
+    lib, vp = binding.load(), ctypes.c_void_p
+    rc = lib.marl_unroll_td_double(vp(net.handle), vp(target.handle), B, None, B, T, vp(d["obs"].data_ptr()),
+                                   vp(d["avail"].data_ptr()), vp(d["actions"].data_ptr()), vp(d["reward"].data_ptr()),
+                                   vp(d["terminated"].data_ptr()), vp(d["filled"].data_ptr()), 0.9,
+                                   vp(d["obs"].data_ptr()), vp(d["obs"].data_ptr()), vp(d["obs"].data_ptr()), None, None, None)
+    assert rc == -1
+    net.close(); target.close()
