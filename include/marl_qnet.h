@@ -240,6 +240,36 @@ int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_epi
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*
+ * Backward half of the learner step (Alg. 3: "calculate the gradient"): back-propagation through
+ * time over the network `q` for a batch of B episodes of T steps.  With q_taken as marl_unroll_td
+ * returns it (q_taken[b,t,n] = filled[b,t] * Q(t)[actions[b,t,n]]) and the caller's
+ * grad_q_taken[b,t,n] = dL/dq_taken[b,t,n] (for the mixing network: dL/dQ_total times the mixer's
+ * derivative with respect to the agent's value),
+ *   grad_weights[p] = sum over b,t,n of grad_q_taken[b,t,n] * d q_taken[b,t,n] / d weights[p]
+ * for every entry of the packed parameter vector, in the order of marl_qnet_create's weights.
+ *   obs           dev [B,T+1,N,D] f32
+ *   actions       dev [B,T,N] i32     clamped into [0,A)
+ *   filled        dev [B,T] u8        unfilled steps contribute nothing
+ *   grad_q_taken  dev [B,T,N] f32
+ *   workspace     dev, 256-byte aligned, at least marl_qnet_grad_workspace_bytes(q, B, T) bytes:
+ *                 the saved activations, the adjoints and the partial sums; the caller owns it,
+ *                 the call allocates nothing, the contents afterwards are unspecified
+ *   grad_weights  dev [marl_param_count] f32, overwritten
+ * The call enqueues a forward pass that keeps the activations, the time-reversed pass and the
+ * weight-gradient products on the stream.  Sums run in a fixed order: the same inputs give the
+ * same bits.  Arithmetic: bf16 MFMA products with fp32 accumulation; fp32 networks split every
+ * operand into two bf16 parts, bf16 networks round the adjoints inside the recurrence to bf16.
+ * Only networks that run on the fused16 kernels are served (see marl_qnet_set_kernels), with
+ * D + N <= 384: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^32, or a
+ * workspace that is too small; MARL_ERR_BAD_ARG for a misaligned workspace.
+ */
+int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, size_t *bytes);
+int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T,
+                   const float *obs, const int32_t *actions, const uint8_t *filled,
+                   const float *grad_q_taken, void *workspace, size_t workspace_bytes,
+                   float *grad_weights, void *hip_stream);
+
+/*
  * Choice of the kernel family for calls on this handle (for marl_unroll_td: the `online` handle).
  * Two families compute the same functions:
  *   fused16  tiles of 16 rows, every weight resident on chip, one kernel per call; serves the

@@ -22,6 +22,16 @@
  * Reverse mode, written out: for t = T-1 .. 0 the adjoint of h'_t is the sum
  * of what flows from Q_t and from step t+1.
  *
+ * The ReLU of the first layer makes the gradient of W1 and b1 discontinuous in
+ * the forward values: a unit whose pre-activation is within an implementation's
+ * forward error of zero may be switched on in one implementation and off in the
+ * other, and each is then the exact derivative of what that implementation
+ * computed.  For comparing against such an implementation the oracle can also
+ * return, per entry of W1 and b1, the ambiguity budget
+ *     amb[p] = sum over samples whose pre-activation of that unit lies in
+ *              [-delta, delta] of |contribution of the sample to grad[p]|
+ * (zero for every other tensor: the switch does not reach them).
+ *
  * Pinned by tests that do not call this file for their expected values: a
  * tensor library's automatic differentiation of an independently written
  * forward pass, central finite differences of the forward oracle, closed forms
@@ -58,10 +68,11 @@ static double sigmoid(double v) { return 1.0 / (1.0 + exp(-v)); }
 typedef struct {
     layout_t L; const float *w; int B, T;
     const float *obs; const int32_t *actions; const uint8_t *filled; const double *g;
+    double delta;            /* half-width of the band of first-layer pre-activations counted as ambiguous */
 } job_t;
 
 /* One (episode, agent) row: forward over slots 0..T-1 keeping every intermediate, then backward. */
-static void row_grad(const job_t *J, int b, int n, double *grad)
+static void row_grad(const job_t *J, int b, int n, double *grad, double *amb)
 {
     const layout_t *L = &J->L;
     const int H = L->H, D = L->D, Din = L->Din, T = J->T, N = L->N;
@@ -69,19 +80,20 @@ static void row_grad(const job_t *J, int b, int n, double *grad)
     const float *W1 = w + L->oW1, *b1 = w + L->ob1, *Wih = w + L->oWih, *Whh = w + L->oWhh;
     const float *bih = w + L->obih, *bhh = w + L->obhh, *W2 = w + L->oW2;
     const size_t S = (size_t)T + 1;
-    /* per step: x_in [Din], x [H], h_prev [H], r, z, nn, ghn [H each], h_new [H] */
-    const size_t per = (size_t)Din + 7 * H;
+    /* per step: x_in [Din], x [H], h_prev [H], r, z, nn, ghn [H each], h_new [H], pre [H] */
+    const size_t per = (size_t)Din + 8 * H;
     double *tape = malloc(sizeof(double) * per * T);
     double *h = calloc(H, sizeof(double));
     for (int t = 0; t < T; ++t) {
         double *x_in = tape + per * t, *x = x_in + Din, *hp = x + H, *r = hp + H, *z = r + H, *nn = z + H,
-               *ghn = nn + H, *hn = ghn + H;
+               *ghn = nn + H, *hn = ghn + H, *pre = hn + H;
         const float *o = J->obs + (((size_t)b * S + t) * N + n) * D;
         for (int d = 0; d < D; ++d) x_in[d] = (double)o[d];
         for (int m = 0; m < N; ++m) x_in[D + m] = (m == n) ? 1.0 : 0.0;
         for (int j = 0; j < H; ++j) {
             double s = (double)b1[j];
             for (int d = 0; d < Din; ++d) s += (double)W1[(size_t)j * Din + d] * x_in[d];
+            pre[j] = s;
             x[j] = s > 0.0 ? s : 0.0;
         }
         memcpy(hp, h, sizeof(double) * H);
@@ -110,7 +122,7 @@ static void row_grad(const job_t *J, int b, int n, double *grad)
     double *dx = malloc(sizeof(double) * H);
     for (int t = T - 1; t >= 0; --t) {
         const double *x_in = tape + per * t, *x = x_in + Din, *hp = x + H, *r = hp + H, *z = r + H, *nn = z + H,
-                     *ghn = nn + H, *hn = ghn + H;
+                     *ghn = nn + H, *hn = ghn + H, *pre = hn + H;
         const size_t bt = (size_t)b * T + t;
         const int u = J->actions[bt * N + n];
         const double gq = J->filled[bt] ? J->g[bt * N + n] : 0.0;        /* adjoint of Q_t[u] */
@@ -151,18 +163,22 @@ static void row_grad(const job_t *J, int b, int n, double *grad)
             const double dp = x[j] > 0.0 ? dx[j] : 0.0;
             grad[L->ob1 + j] += dp;
             for (int d = 0; d < Din; ++d) grad[L->oW1 + (size_t)j * Din + d] += dp * x_in[d];
+            if (amb && fabs(pre[j]) <= J->delta) {
+                amb[L->ob1 + j] += fabs(dx[j]);
+                for (int d = 0; d < Din; ++d) amb[L->oW1 + (size_t)j * Din + d] += fabs(dx[j] * x_in[d]);
+            }
         }
         memcpy(dh, dh_prev, sizeof(double) * H);
     }
     free(dx); free(da); free(dh_prev); free(dh); free(h); free(tape);
 }
 
-typedef struct { const job_t *J; int lo, hi; double *grad; } span_t;
+typedef struct { const job_t *J; int lo, hi; double *grad, *amb; } span_t;
 static void *span_run(void *p)
 {
     span_t *s = (span_t *)p;
     for (int b = s->lo; b < s->hi; ++b)
-        for (int n = 0; n < s->J->L.N; ++n) row_grad(s->J, b, n, s->grad);
+        for (int n = 0; n < s->J->L.N; ++n) row_grad(s->J, b, n, s->grad, s->amb);
     return NULL;
 }
 
@@ -173,15 +189,18 @@ long bptt_param_count(int N, int D, int A, int H)
     return L.count;
 }
 
-/* obs [B,T+1,N,D] f32, actions [B,T,N] i32, filled [B,T] u8, g [B,T,N] f64 -> grad [param count] f64.
+/* obs [B,T+1,N,D] f32, actions [B,T,N] i32, filled [B,T] u8, g [B,T,N] f64 -> grad [param count] f64,
+ * and, if amb != NULL, the ambiguity budget [param count] f64 for the band |pre-activation| <= delta.
  * Episodes are split over threads; each thread sums its rows in order, the threads' sums are
  * added in thread order. */
 void bptt_qnet_grad(int N, int D, int A, int H, const float *weights, int B, int T, const float *obs,
-                    const int32_t *actions, const uint8_t *filled, const double *g, double *grad, int nthreads)
+                    const int32_t *actions, const uint8_t *filled, const double *g, double *grad,
+                    double delta, double *amb, int nthreads)
 {
     job_t J;
     layout(&J.L, N, D, A, H);
     J.w = weights; J.B = B; J.T = T; J.obs = obs; J.actions = actions; J.filled = filled; J.g = g;
+    J.delta = delta;
     if (nthreads < 1) nthreads = 1;
     if (nthreads > B) nthreads = B > 0 ? B : 1;
     span_t *spans = malloc(sizeof(span_t) * nthreads);
@@ -191,13 +210,16 @@ void bptt_qnet_grad(int N, int D, int A, int H, const float *weights, int B, int
         spans[i].lo = (int)((long)B * i / nthreads);
         spans[i].hi = (int)((long)B * (i + 1) / nthreads);
         spans[i].grad = calloc(J.L.count, sizeof(double));
+        spans[i].amb = amb ? calloc(J.L.count, sizeof(double)) : NULL;
         pthread_create(&th[i], NULL, span_run, &spans[i]);
     }
     memset(grad, 0, sizeof(double) * J.L.count);
+    if (amb) memset(amb, 0, sizeof(double) * J.L.count);
     for (int i = 0; i < nthreads; ++i) {
         pthread_join(th[i], NULL);
         for (long p = 0; p < J.L.count; ++p) grad[p] += spans[i].grad[p];
-        free(spans[i].grad);
+        if (amb) for (long p = 0; p < J.L.count; ++p) amb[p] += spans[i].amb[p];
+        free(spans[i].grad); free(spans[i].amb);
     }
     free(th); free(spans);
 }

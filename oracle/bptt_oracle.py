@@ -49,10 +49,12 @@ def default_threads():
     return max(1, min(os.cpu_count() or 1, 16))
 
 
-def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None):
+def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None, relu_band=None):
     """grad [param count] f64 of sum(g * q_taken) with respect to the packed weights.
 
     obs [B,T+1,N,D], actions [B,T,N], filled [B,T], g [B,T,N] = dL/dq_taken.
+    relu_band = delta: returns (grad, amb), amb the ambiguity budget of the first layer's entries for
+    pre-activations within delta of zero.
     """
     N, D, A, H = (int(v) for v in dims)
     weights = _c(weights, np.float32)
@@ -66,6 +68,8 @@ def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None):
     filled = _c(filled, np.uint8); assert filled.shape == (B, T)
     g = _c(g, np.float64); assert g.shape == (B, T, N)
     grad = np.zeros(count)
+    amb = None if relu_band is None else np.zeros(count)
     _load().bptt_qnet_grad(N, D, A, H, _p(weights), B, T, _p(obs), _p(actions), _p(filled), _p(g), _p(grad),
-                           int(nthreads or default_threads()))
-    return grad
+                           ctypes.c_double(0.0 if relu_band is None else float(relu_band)),
+                           None if amb is None else _p(amb), int(nthreads or default_threads()))
+    return grad if amb is None else (grad, amb)

@@ -20,7 +20,7 @@ MARL_DTYPE_BF16 = 1
 DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
-           "marl_unroll_td_double",
+           "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
@@ -79,6 +79,10 @@ def load():
         lib.marl_unroll_td_indexed.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_unroll_td_double.restype = ctypes.c_int
         lib.marl_unroll_td_double.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, vp]
+        lib.marl_qnet_grad_workspace_bytes.restype = ctypes.c_int
+        lib.marl_qnet_grad_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        lib.marl_qnet_grad.restype = ctypes.c_int
+        lib.marl_qnet_grad.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
         lib.marl_qnet_reserve_unroll.argtypes = [vp, i32, i32]
         lib.marl_qnet_kernels_in_use.restype = ctypes.c_int
@@ -271,6 +275,24 @@ def marl_unroll_td_double(online, target, dims, obs, avail, actions, reward, ter
         _dev(q_all, "f32", (B, T + 1, N, A), "q_all", optional=True), _stream()))
 
 
+def marl_qnet_grad_workspace_bytes(handle, B, T):
+    n = ctypes.c_size_t(0)
+    check(load().marl_qnet_grad_workspace_bytes(ctypes.c_void_p(handle), int(B), int(T), ctypes.byref(n)))
+    return int(n.value)
+
+
+def marl_qnet_grad(handle, dims, obs, actions, filled, grad_q_taken, workspace, grad_weights):
+    """workspace: a device uint8 tensor of at least marl_qnet_grad_workspace_bytes bytes."""
+    N, D, A, H = dims
+    B, T = obs.shape[0], obs.shape[1] - 1
+    n_params = (D + N) * H + H + 6 * H * H + 6 * H + A * H + A
+    check(load().marl_qnet_grad(
+        ctypes.c_void_p(handle), B, T, _dev(obs, "f32", (B, T + 1, N, D), "obs"),
+        _dev(actions, "i32", (B, T, N), "actions"), _dev(filled, "u8", (B, T), "filled"),
+        _dev(grad_q_taken, "f32", (B, T, N), "grad_q_taken"), _dev(workspace, "u8", (workspace.numel(),), "workspace"),
+        int(workspace.numel()), _dev(grad_weights, "f32", (n_params,), "grad_weights"), _stream()))
+
+
 class QNet:
     """Convenience owner of one handle (create on init, destroy on close)."""
 
@@ -294,6 +316,12 @@ class QNet:
         tgt = self if target is None else target
         marl_unroll_td_double(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                               gamma, q_taken, next_max, td_target, next_action, q_all, episode_index)
+
+    def grad_workspace_bytes(self, B, T):
+        return marl_qnet_grad_workspace_bytes(self.handle, B, T)
+
+    def grad(self, obs, actions, filled, grad_q_taken, workspace, grad_weights):
+        marl_qnet_grad(self.handle, self.dims, obs, actions, filled, grad_q_taken, workspace, grad_weights)
 
     def act_step_indexed(self, env_index, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
         marl_act_step_indexed(self.handle, self.dims, env_index, obs, avail, h_in, reset, step_t, epsilon, seed,

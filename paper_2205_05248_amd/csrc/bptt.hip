@@ -1,0 +1,532 @@
+// Backward half of the learner step for the recurrent Q-network: the gradient of
+// sum(g * q_taken) with respect to every parameter, g = dL/dq_taken handed in by the caller.
+//
+//   unroll_fused_kernel<.., kTdSave>   (unroll_fused.hip) forward pass of the online network that keeps x and
+//                                      h of every slot in global memory, fp32, [B, T+1, N, H]
+//   bptt_back_kernel                   one workgroup per 16 (episode, agent) rows walks the slots backwards.
+//                                      Per slot it recomputes the gates from x_t and h_{t-1} (two MFMA
+//                                      products, as the forward pass), forms the adjoints of the four gate
+//                                      pre-activations, and carries dL/dh back through W_hh^T; W_ih^T gives
+//                                      the adjoint of x and, through the ReLU, of fc1's pre-activation.  All
+//                                      four GRU matrices stay on chip: W_hh, W_hh^T and W_ih^T as operand
+//                                      fragments in registers (four waves, one per SIMD, up to 512 registers
+//                                      each), W_ih in LDS.  The adjoints go to global memory.
+//   tn_gemm_kernel                     the weight gradients are sums over all (row, slot) samples of outer
+//                                      products adjoint x activation: C[p][q] = sum_m A[m][p] B[m][q], four
+//                                      times (W_ih, W_hh, W1, W2).  The samples are split into chunks over
+//                                      the grid, a workgroup stages 32 samples at a time through LDS (the
+//                                      contraction index has to become the fragments' k), and writes its
+//                                      partial sum; extra columns of B made up on the fly (a column of ones,
+//                                      or the one-hot agent id) yield the bias gradients in the same product.
+//   tn_reduce_kernel                   adds the chunks' partial sums in a fixed order and writes the result
+//                                      into the packed gradient vector.
+// The precision follows the network's: fp32 networks split every operand into two bf16 planes (three MFMAs per
+// product), bf16 networks round the adjoints that enter the recurrent products to bf16; the weight-gradient
+// products always use the split.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "fused16_roles.h"
+
+namespace marl {
+
+struct BpttArgs {
+    NetFrags net;
+    int B, T, a16;
+    const int32_t *actions;      // [B, T, N]
+    const uint8_t *filled;       // [B, T]
+    const float *grad_q;         // [B, T, N]   dL/dq_taken
+    const float *h_all, *x_all;  // [B, T+1, N, H]   h_all[b, s] = state before slot s
+    float *da;                   // [B, T, N, 4H]   adjoints of the gate pre-activations: n (input side), r, z, n (hidden side)
+    float *dpre1;                // [B, T, N, H]    adjoint of fc1's pre-activation
+    float *dq;                   // [B, T, N, a16]  adjoint of Q, dense (one non-zero per row)
+};
+
+template <int H, int P> struct BpttShape {
+    using Sh = Fused16<H, P>;
+    static constexpr int KS = Sh::KS, FBK = Sh::FBK, NBC = Sh::NBC;
+    // LDS: W_ih, one buffer of h and x fragments and the gate biases where the forward kernel has them;
+    // the adjoint fragments (r, z, n: 3 KS k-steps; n hidden side: KS) where it keeps the observations
+    static constexpr int oDa = Sh::oObs, oDhn = oDa + 3 * KS * Sh::kFrag, kBytes = oDhn + KS * Sh::kFrag;
+};
+
+template <int H, int P>
+__global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
+{
+    using Sh = Fused16<H, P>;
+    using Bs = BpttShape<H, P>;
+    constexpr int KS = Sh::KS, FBK = Sh::FBK, NBC = Sh::NBC;
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    typedef bf16x8 (*FragBuf)[P][64];
+    const FragBuf hf = reinterpret_cast<FragBuf>(lds + Sh::oH), xf = reinterpret_cast<FragBuf>(lds + Sh::oX);
+    const FragBuf daf = reinterpret_cast<FragBuf>(lds + Bs::oDa), dhf = reinterpret_cast<FragBuf>(lds + Bs::oDhn);
+    bf16x8 *const wih_lds = reinterpret_cast<bf16x8 *>(lds + Sh::oWih);
+    const float *gb = reinterpret_cast<const float *>(lds + Sh::oGBias);
+
+    const NetFrags &net = a.net;
+    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = net.N, A = net.A, T = a.T, S = T + 1;
+    const int rows = a.B * N;
+    const int row = blockIdx.x * 16 + c;
+    const bool valid = row < rows;
+    const int b = valid ? row / N : 0, n = valid ? row % N : 0;
+
+    {
+        constexpr int kVecs = 3 * FBK * KS * P * 64;
+        for (int i = threadIdx.x; i < kVecs; i += 256) wih_lds[i] = net.wih_16[i];
+    }
+    if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
+
+    // this wave's hidden units: blocks NBC w + j; forward W_hh rows of the three gates, and the rows of
+    // W_hh^T and W_ih^T that produce its units of dL/dh and dL/dx
+    WFrag<P> whh[3][NBC][KS], whhT[NBC][3 * KS], wihT[NBC][3 * KS];
+    f32x4 bias_hn[NBC];
+#pragma unroll
+    for (int j = 0; j < NBC; ++j) {
+        const int blk = NBC * w + j;
+#pragma unroll
+        for (int gate = 0; gate < 3; ++gate)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                whh[gate][j][ks] = load_wfrag<P>(net.whh_16 + ((size_t)((gate * FBK + blk) * KS + ks) * P) * 64 + lane);
+#pragma unroll
+        for (int ks = 0; ks < 3 * KS; ++ks) {
+            whhT[j][ks] = load_wfrag<P>(net.whhT_16 + ((size_t)(blk * 3 * KS + ks) * P) * 64 + lane);
+            wihT[j][ks] = load_wfrag<P>(net.wihT_16 + ((size_t)(blk * 3 * KS + ks) * P) * 64 + lane);
+        }
+        bias_hn[j] = load_feature4(net.bias_hn, blk, q4);
+    }
+
+    const int unit0 = 16 * NBC * w + 4 * q4;                       // + 16 j: the lane's four units of block j
+    const size_t slot_stride = (size_t)N * H;
+    const float *h_row = a.h_all + ((size_t)b * S * N + n) * H + unit0;
+    const float *x_row = a.x_all + ((size_t)b * S * N + n) * H + unit0;
+
+    struct StepIn { f32x4 hp[NBC], xv[NBC], w2[NBC]; float gq; int u; };
+    auto fetch = [&](int t) {
+        StepIn in;
+        const size_t bt = (size_t)b * T + t;
+        in.u = min(max(a.actions[bt * N + n], 0), A - 1);
+        in.gq = (valid && a.filled[bt]) ? a.grad_q[bt * N + n] : 0.0f;
+#pragma unroll
+        for (int j = 0; j < NBC; ++j) {
+            in.hp[j] = *reinterpret_cast<const f32x4 *>(h_row + (size_t)t * slot_stride + 16 * j);
+            in.xv[j] = *reinterpret_cast<const f32x4 *>(x_row + (size_t)t * slot_stride + 16 * j);
+            in.w2[j] = *reinterpret_cast<const f32x4 *>(net.w2_plain + (size_t)in.u * H + unit0 + 16 * j);
+        }
+        return in;
+    };
+
+    f32x4 dh[NBC];                                                 // dL/dh flowing into the state after slot t
+#pragma unroll
+    for (int j = 0; j < NBC; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dh[j][r] = 0.0f;
+
+    StepIn nxt = fetch(T - 1);
+    lds_barrier();                                                 // W_ih and the biases are in LDS
+    for (int t = T - 1; t >= 0; --t) {
+        const StepIn in = nxt;
+        if (t > 0) nxt = fetch(t - 1);
+        GruWave<H, P>::publish(hf, w, lane, in.hp);
+        GruWave<H, P>::publish(xf, w, lane, in.xv);
+        lds_barrier();
+
+        // the gates of slot t again
+        f32x4 acc_r[NBC], acc_z[NBC], acc_in[NBC], acc_hn[NBC];
+#pragma unroll
+        for (int j = 0; j < NBC; ++j) {
+            acc_r[j] = load_feature4(gb, 0 * FBK + NBC * w + j, q4);
+            acc_z[j] = load_feature4(gb, 1 * FBK + NBC * w + j, q4);
+            acc_in[j] = load_feature4(gb, 2 * FBK + NBC * w + j, q4);
+            acc_hn[j] = bias_hn[j];
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag<P> hb, xb;
+            hb.hi = hf[ks][0][lane];
+            xb.hi = xf[ks][0][lane];
+            if constexpr (P == 2) { hb.lo = hf[ks][1][lane]; xb.lo = xf[ks][1][lane]; }
+#pragma unroll
+            for (int j = 0; j < NBC; ++j) {
+                const int blk = NBC * w + j;
+                mma16<P>(acc_r[j], whh[0][j][ks], hb);
+                mma16<P>(acc_z[j], whh[1][j][ks], hb);
+                mma16<P>(acc_hn[j], whh[2][j][ks], hb);
+                mma16<P>(acc_r[j], load_wfrag<P>(wih_lds + ((size_t)((0 * FBK + blk) * KS + ks) * P) * 64 + lane), xb);
+                mma16<P>(acc_z[j], load_wfrag<P>(wih_lds + ((size_t)((1 * FBK + blk) * KS + ks) * P) * 64 + lane), xb);
+                mma16<P>(acc_in[j], load_wfrag<P>(wih_lds + ((size_t)((2 * FBK + blk) * KS + ks) * P) * 64 + lane), xb);
+            }
+        }
+
+        // adjoints of the pre-activations
+        f32x4 dar[NBC], daz[NBC], dan[NBC], dahn[NBC], carry[NBC];
+#pragma unroll
+        for (int j = 0; j < NBC; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float rr = sigmoidf_fast(acc_r[j][r]), zz = sigmoidf_fast(acc_z[j][r]);
+                const float nn = tanhf_fast(acc_in[j][r] + rr * acc_hn[j][r]);
+                const float dht = dh[j][r] + in.gq * in.w2[j][r];             // Q_t[u] = W2[u] . h_t + b2[u]
+                const float dn = dht * (1.0f - zz) * (1.0f - nn * nn);
+                dan[j][r] = dn;
+                dahn[j][r] = dn * rr;
+                dar[j][r] = dn * acc_hn[j][r] * rr * (1.0f - rr);
+                daz[j][r] = dht * (in.hp[j][r] - nn) * zz * (1.0f - zz);
+                carry[j][r] = dht * zz;
+            }
+        const size_t m = ((size_t)b * T + t) * N + n;
+        if (valid) {
+            float *da_row = a.da + m * 4 * H + unit0;
+#pragma unroll
+            for (int j = 0; j < NBC; ++j) {
+                *reinterpret_cast<f32x4 *>(da_row + 0 * H + 16 * j) = dan[j];
+                *reinterpret_cast<f32x4 *>(da_row + 1 * H + 16 * j) = dar[j];
+                *reinterpret_cast<f32x4 *>(da_row + 2 * H + 16 * j) = daz[j];
+                *reinterpret_cast<f32x4 *>(da_row + 3 * H + 16 * j) = dahn[j];
+            }
+            if (w == 0) {                                          // the adjoint of Q_t, one wave writes the row
+                float *dq_row = a.dq + m * a.a16;
+                for (int ab = 0; 16 * ab < a.a16; ++ab) {
+                    f32x4 v;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v[r] = (16 * ab + 4 * q4 + r == in.u) ? in.gq : 0.0f;
+                    *reinterpret_cast<f32x4 *>(dq_row + 16 * ab + 4 * q4) = v;
+                }
+            }
+        }
+        GruWave<H, P>::publish(daf + 0 * KS, w, lane, dar);
+        GruWave<H, P>::publish(daf + 1 * KS, w, lane, daz);
+        GruWave<H, P>::publish(daf + 2 * KS, w, lane, dan);
+        GruWave<H, P>::publish(dhf, w, lane, dahn);
+        lds_barrier();
+
+        // back through the two products: dL/dh_{t-1} and dL/dx_t for this wave's units
+        f32x4 accx[NBC];
+#pragma unroll
+        for (int j = 0; j < NBC; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) accx[j][r] = 0.0f;
+#pragma unroll
+        for (int ks = 0; ks < 3 * KS; ++ks) {
+            Frag<P> di, dhid;
+            di.hi = daf[ks][0][lane];
+            if constexpr (P == 2) di.lo = daf[ks][1][lane];
+            if (ks < 2 * KS) {
+                dhid = di;
+            } else {
+                dhid.hi = dhf[ks - 2 * KS][0][lane];
+                if constexpr (P == 2) dhid.lo = dhf[ks - 2 * KS][1][lane];
+            }
+#pragma unroll
+            for (int j = 0; j < NBC; ++j) {
+                mma16<P>(carry[j], whhT[j][ks], dhid);
+                mma16<P>(accx[j], wihT[j][ks], di);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NBC; ++j) {
+            dh[j] = carry[j];
+            f32x4 dp;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) dp[r] = in.xv[j][r] > 0.0f ? accx[j][r] : 0.0f;
+            if (valid) *reinterpret_cast<f32x4 *>(a.dpre1 + m * H + unit0 + 16 * j) = dp;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ weight gradients
+// Row m of an operand lives at base + (m / rows_per_group) * group_stride + (m % rows_per_group) * ld.
+struct RowMap {
+    const float *base;
+    long group_stride;
+    int rows_per_group, ld;
+};
+
+enum ExtraCols : int { kExtraOnes = 1, kExtraAgent = 2 };
+
+struct TnGemmArgs {
+    RowMap a, b;
+    int M;              // samples
+    int P, Q;           // columns of A and of B taken
+    int extra_mode;     // columns appended to B: kExtraOnes (one column of ones), kExtraAgent (N one-hot columns of m % N)
+    int n_extra, N;
+    int qp;             // Q + n_extra rounded up to 16: row pitch of the result
+    int chunk;          // samples per workgroup along the contraction, a multiple of 32
+    float *partial;     // [chunks][P rounded up to 64][qp]
+};
+
+constexpr int kTnMaxQBlocks = 24, kTnQPerWave = kTnMaxQBlocks / 4;      // at most 384 columns of B
+
+__global__ __launch_bounds__(256, 1) void tn_gemm_kernel(TnGemmArgs g)
+{
+    extern __shared__ __attribute__((aligned(16))) float stage[];
+    constexpr int kPitchA = 64 + 2;
+    const int pitch_b = g.qp + 2;
+    float *const As = stage, *const Bs = stage + 32 * kPitchA;
+    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int p0 = blockIdx.x * 64;
+    const int n_qb = g.qp / 16;
+    const int m_begin = (int)blockIdx.y * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
+
+    f32x4 acc[4][kTnQPerWave];
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+        for (int j = 0; j < kTnQPerWave; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[pb][j][r] = 0.0f;
+
+    float ra[8], rb[8][kTnQPerWave];
+    auto fetch = [&](int m0) {                   // this wave's eight rows of the next 32 samples -> registers
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int m = m0 + 8 * w + r;
+            const bool live = m < m_end;
+            const unsigned ms = live ? (unsigned)m : 0u;
+            const float *arow = g.a.base + (long)(ms / (unsigned)g.a.rows_per_group) * g.a.group_stride +
+                                (long)(ms % (unsigned)g.a.rows_per_group) * g.a.ld;
+            const float *brow = g.b.base + (long)(ms / (unsigned)g.b.rows_per_group) * g.b.group_stride +
+                                (long)(ms % (unsigned)g.b.rows_per_group) * g.b.ld;
+            ra[r] = (live && p0 + lane < g.P) ? arow[p0 + lane] : 0.0f;
+            const int agent = (int)(ms % (unsigned)g.N);
+#pragma unroll
+            for (int i = 0; i < kTnQPerWave; ++i) {
+                const int col = lane + 64 * i;
+                float v = 0.0f;
+                if (live && col < g.Q) v = brow[col];
+                else if (live && col < g.Q + g.n_extra) v = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == agent ? 1.0f : 0.0f);
+                rb[r][i] = v;
+            }
+        }
+    };
+    auto deposit = [&]() {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            As[(8 * w + r) * kPitchA + lane] = ra[r];
+#pragma unroll
+            for (int i = 0; i < kTnQPerWave; ++i)
+                if (lane + 64 * i < g.qp) Bs[(8 * w + r) * pitch_b + lane + 64 * i] = rb[r][i];
+        }
+    };
+
+    fetch(m_begin);
+    for (int m0 = m_begin; m0 < m_end; m0 += 32) {
+        __syncthreads();                         // the previous step's fragments have been read
+        deposit();
+        __syncthreads();
+        if (m0 + 32 < m_end) fetch(m0 + 32);
+        // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
+        WFrag<2> af[4];
+#pragma unroll
+        for (int pb = 0; pb < 4; ++pb) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = As[(8 * q4 + i) * kPitchA + 16 * pb + c];
+            const Frag<2> f = to_frag<2>(v);
+            af[pb].hi = f.hi;
+            af[pb].lo = f.lo;
+        }
+#pragma unroll
+        for (int j = 0; j < kTnQPerWave; ++j) {
+            const int qb = w + 4 * j;
+            if (qb < n_qb) {
+                float v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) v[i] = Bs[(8 * q4 + i) * pitch_b + 16 * qb + c];
+                const Frag<2> bf = to_frag<2>(v);
+#pragma unroll
+                for (int pb = 0; pb < 4; ++pb) mma16<2>(acc[pb][j], af[pb], bf);
+            }
+        }
+    }
+
+    // C layout: lane (c, q4) holds result[p0 + 16 pb + 4 q4 + r][16 qb + c]
+    const int p_pad = (g.P + 63) / 64 * 64;
+    float *out = g.partial + (size_t)blockIdx.y * p_pad * g.qp;
+#pragma unroll
+    for (int pb = 0; pb < 4; ++pb)
+#pragma unroll
+        for (int j = 0; j < kTnQPerWave; ++j) {
+            const int qb = w + 4 * j;
+            if (qb < n_qb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) out[(size_t)(p0 + 16 * pb + 4 * q4 + r) * g.qp + 16 * qb + c] = acc[pb][j][r];
+        }
+}
+
+// Sum of the chunks, in order, into the packed gradient vector.  Result row p goes to row
+// (p + row_shift) % P of the destination matrix (the adjoint array lists the gates as n, r, z, the
+// parameters as r, z, n); columns < w_cols go to dst_w[row * ld_w + column]; the appended columns
+// go to dst_b[row] (kExtraOnes: the one column; kExtraAgent: the sum of the N columns).
+struct TnReduceArgs {
+    const float *partial;
+    int chunks, P, p_pad, qp;
+    int Q, n_extra, extra_mode;
+    int row_shift, w_cols, ld_w;
+    float *dst_w, *dst_b;
+};
+
+__global__ void tn_reduce_kernel(TnReduceArgs g)
+{
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int total = g.P * (g.Q + 1);
+    if (idx >= total) return;
+    const int p = idx / (g.Q + 1), q = idx % (g.Q + 1);
+    const int row = (p + g.row_shift) % g.P;
+    auto column = [&](int col) {
+        float s = 0.0f;
+        for (int ch = 0; ch < g.chunks; ++ch) s += g.partial[((size_t)ch * g.p_pad + p) * g.qp + col];
+        return s;
+    };
+    if (q < g.Q) {
+        g.dst_w[(size_t)row * g.ld_w + q] = column(q);
+        return;
+    }
+    if (g.extra_mode == kExtraOnes) {
+        g.dst_b[row] = column(g.Q);
+    } else {
+        float s = 0.0f;
+        for (int e = 0; e < g.n_extra; ++e) {
+            const float v = column(g.Q + e);
+            g.dst_w[(size_t)row * g.ld_w + g.Q + e] = v;
+            s += v;
+        }
+        g.dst_b[row] = s;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ host side
+namespace {
+
+size_t align_up(size_t v) { return (v + 255) / 256 * 256; }
+
+struct Plan {
+    size_t off_h, off_x, off_da, off_dpre1, off_dq, off_partial, bytes;
+    int a16, chunks, chunk;
+};
+
+Plan make_plan(const NetFrags &net, int B, int T)
+{
+    Plan p{};
+    const size_t R = (size_t)B * net.N, S = (size_t)T + 1, H = net.H;
+    p.a16 = (net.A + 15) / 16 * 16;
+    const long M = (long)R * T;
+    p.chunks = (int)std::min<long>(256, (M + 31) / 32);
+    if (p.chunks < 1) p.chunks = 1;
+    p.chunk = (int)(((M + p.chunks - 1) / p.chunks + 31) / 32 * 32);
+    size_t off = 0;
+    p.off_h = off;      off = align_up(off + R * S * H * 4);
+    p.off_x = off;      off = align_up(off + R * S * H * 4);
+    p.off_da = off;     off = align_up(off + R * T * 4 * H * 4);
+    p.off_dpre1 = off;  off = align_up(off + R * T * H * 4);
+    p.off_dq = off;     off = align_up(off + R * T * p.a16 * 4);
+    // the largest of the four products' partial results
+    auto part = [&](size_t P, size_t Qt) { return (size_t)p.chunks * ((P + 63) / 64 * 64) * ((Qt + 15) / 16 * 16) * 4; };
+    size_t need = part(3 * H, H + 1);
+    need = std::max(need, part(H, (size_t)net.D + net.N));
+    need = std::max(need, part(p.a16, H + 1));
+    p.off_partial = off; off = align_up(off + need);
+    p.bytes = off;
+    return p;
+}
+
+hipError_t run_product(const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra, int N,
+                       const Plan &plan, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
+                       hipStream_t stream)
+{
+    TnGemmArgs g{};
+    g.a = a; g.b = b; g.M = (int)M; g.P = P; g.Q = Q; g.extra_mode = extra_mode; g.n_extra = n_extra; g.N = N;
+    g.qp = (Q + n_extra + 15) / 16 * 16;
+    g.chunk = plan.chunk;
+    g.partial = partial;
+    if (g.qp > 16 * kTnMaxQBlocks) return hipErrorInvalidValue;
+    const int p_tiles = (P + 63) / 64, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
+    const size_t lds = (size_t)32 * (66 + g.qp + 2) * sizeof(float);
+    hipError_t err = allow_large_lds<tn_gemm_kernel>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(tn_gemm_kernel, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    TnReduceArgs r{};
+    r.partial = partial; r.chunks = chunks; r.P = P; r.p_pad = p_tiles * 64; r.qp = g.qp;
+    r.Q = Q; r.n_extra = n_extra; r.extra_mode = extra_mode;
+    r.row_shift = row_shift; r.w_cols = Q; r.ld_w = ld_w; r.dst_w = dst_w; r.dst_b = dst_b;
+    const int total = P * (Q + 1);
+    hipLaunchKernelGGL(tn_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, r);
+    return hipGetLastError();
+}
+
+template <int H, int P>
+hipError_t back_dispatch(const BpttArgs &a, hipStream_t stream)
+{
+    const int tiles = (a.B * a.net.N + 15) / 16;
+    hipError_t err = allow_large_lds<bptt_back_kernel<H, P>>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    constexpr size_t kLds = BpttShape<H, P>::kBytes;
+    hipLaunchKernelGGL((bptt_back_kernel<H, P>), dim3(tiles), dim3(256), kLds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool qnet_grad_fits(const NetFrags &net)
+{
+    return unroll_fused_fits(net) && net.D + net.N <= 16 * kTnMaxQBlocks && net.H + 1 <= 16 * kTnMaxQBlocks;
+}
+
+size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T) { return make_plan(net, B, T).bytes; }
+
+// grad: packed like the weights (W1, b1, W_ih, W_hh, b_ih, b_hh, W2, b2), device, fully overwritten.
+hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
+                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream)
+{
+    const Plan plan = make_plan(net, B, T);
+    char *ws = static_cast<char *>(workspace);
+    float *h_all = reinterpret_cast<float *>(ws + plan.off_h), *x_all = reinterpret_cast<float *>(ws + plan.off_x);
+    float *da = reinterpret_cast<float *>(ws + plan.off_da), *dpre1 = reinterpret_cast<float *>(ws + plan.off_dpre1);
+    float *dq = reinterpret_cast<float *>(ws + plan.off_dq), *partial = reinterpret_cast<float *>(ws + plan.off_partial);
+    const int N = net.N, D = net.D, A = net.A, H = net.H, S = T + 1;
+
+    // forward pass that keeps x and h
+    hipError_t err = launch_unroll_fused(net, net, false, B, T, nullptr, B, obs, nullptr, actions, nullptr, nullptr, filled,
+                                         0.0f, nullptr, nullptr, nullptr, nullptr, stream, kTdSave, nullptr, h_all, x_all);
+    if (err != hipSuccess) return err;
+
+    BpttArgs a{};
+    a.net = net; a.B = B; a.T = T; a.a16 = plan.a16; a.actions = actions; a.filled = filled; a.grad_q = grad_q;
+    a.h_all = h_all; a.x_all = x_all; a.da = da; a.dpre1 = dpre1; a.dq = dq;
+    if (H == 64 && net.planes == 2) err = back_dispatch<64, 2>(a, stream);
+    else if (H == 64 && net.planes == 1) err = back_dispatch<64, 1>(a, stream);
+    else if (H == 128 && net.planes == 1) err = back_dispatch<128, 1>(a, stream);
+    else err = hipErrorInvalidValue;
+    if (err != hipSuccess) return err;
+
+    // offsets of the tensors in the packed vector
+    float *gW1 = grad, *gb1 = gW1 + (size_t)H * (D + N), *gWih = gb1 + H, *gWhh = gWih + (size_t)3 * H * H;
+    float *gbih = gWhh + (size_t)3 * H * H, *gbhh = gbih + 3 * H, *gW2 = gbhh + 3 * H, *gb2 = gW2 + (size_t)A * H;
+    const long M = (long)B * N * T;
+    const int TN = T * N;
+    const RowMap plain_da{da, 0, (int)std::min<long>(M, 1 << 30), 4 * H};
+    const RowMap da_i = plain_da;                                        // columns n, r, z
+    RowMap da_h = plain_da; da_h.base = da + H;                          // columns r, z, n (hidden side)
+    const RowMap x_rows{x_all, (long)S * N * H, TN, H};
+    const RowMap h_prev{h_all, (long)S * N * H, TN, H};
+    const RowMap h_new{h_all + (size_t)N * H, (long)S * N * H, TN, H};
+    const RowMap pre_rows{dpre1, 0, (int)std::min<long>(M, 1 << 30), H};
+    const RowMap obs_rows{obs, (long)S * N * D, TN, D};
+    const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16};
+    // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
+    err = run_product(da_i, x_rows, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 2 * H, gWih, H, gbih, stream);
+    if (err != hipSuccess) return err;
+    err = run_product(da_h, h_prev, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 0, gWhh, H, gbhh, stream);
+    if (err != hipSuccess) return err;
+    err = run_product(pre_rows, obs_rows, M, H, D, kExtraAgent, N, N, plan, partial, 0, gW1, D + N, gb1, stream);
+    if (err != hipSuccess) return err;
+    return run_product(dq_rows, h_new, M, A, H, kExtraOnes, 1, N, plan, partial, 0, gW2, H, gb2, stream);
+}
+
+}  // namespace marl

@@ -192,8 +192,10 @@ template <int H, int P> struct Fc1Wave {
     }
 
     // One item: observation fragments obs_src[ks] (LDS) -> x fragments of this wave's blocks in x_dst.
+    // SAVE: x also goes, in fp32, to x_row[16 block + 0..3] (the caller has added the lane's 4 q; null: no store).
+    template <bool SAVE = false>
     __device__ __forceinline__ void step(const bf16x8 *obs_src, int ks1, int f, int lane, const f32x4 (&b1v)[NBF],
-                                         bf16x8 (*x_dst)[P][64]) const
+                                         bf16x8 (*x_dst)[P][64], float *x_row = nullptr) const
     {
         auto obs_frag = [&](int ks) {
             const bf16x8 *src = obs_src + (size_t)(ks * P) * 64 + lane;
@@ -222,6 +224,11 @@ template <int H, int P> struct Fc1Wave {
         for (int j = 0; j < NBF; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[j][r] = fmaxf(acc[j][r] + b1v[j][r], 0.0f);
+        if constexpr (SAVE) {
+            if (x_row)
+#pragma unroll
+                for (int j = 0; j < NBF; ++j) *reinterpret_cast<f32x4 *>(x_row + 16 * (f * NBF + j)) = acc[j];
+        }
 #pragma unroll
         for (int jj = 0; jj < NBF / 2; ++jj) {
             const Frag<P> fr = frag_of_pair<P>(acc[2 * jj], acc[2 * jj + 1]);

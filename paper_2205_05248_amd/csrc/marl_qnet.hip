@@ -169,6 +169,9 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.wih_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih_16);
     n.whh_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh_16);
     n.w2_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2_16);
+    n.wihT_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wihT_16);
+    n.whhT_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whhT_16);
+    n.w2_plain = reinterpret_cast<const float *>(base + img.off_w2_plain);
     n.bias1 = reinterpret_cast<const float *>(base + img.off_bias1);
     n.bias_r = reinterpret_cast<const float *>(base + img.off_bias_r);
     n.bias_z = reinterpret_cast<const float *>(base + img.off_bias_z);
@@ -414,6 +417,39 @@ int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_epi
     return unroll_call(online, target, B, T, episode_index, episode_index ? pool_episodes : B, obs, avail, actions,
                        reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, hip_stream, true,
                        next_action);
+}
+
+int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, size_t *bytes)
+{
+    if (!q || !bytes) return MARL_ERR_NULL;
+    if (B < 1 || T < 1 || (int64_t)B * q->desc.n_agents * ((int64_t)T + 1) * 4 * q->desc.hidden >= (int64_t)1 << 32)
+        return MARL_ERR_BAD_DIM;
+    if (!marl::qnet_grad_fits(q->net)) return MARL_ERR_BAD_DIM;
+    *bytes = marl::qnet_grad_workspace_bytes(q->net, B, T);
+    return MARL_OK;
+}
+
+int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T, const float *obs, const int32_t *actions, const uint8_t *filled,
+                   const float *grad_q_taken, void *workspace, size_t workspace_bytes, float *grad_weights,
+                   void *hip_stream)
+{
+    if (!q) return MARL_ERR_NULL;
+    size_t need = 0;
+    const int rc = marl_qnet_grad_workspace_bytes(q, B, T, &need);
+    if (rc != MARL_OK) return rc;
+    {
+        const marl_qnet_desc &a = q->desc;
+        const int64_t widest = a.obs_dim > a.n_actions ? a.obs_dim : a.n_actions;
+        if ((int64_t)B * (T + 1) * a.n_agents * widest >= (int64_t)1 << 30 || (int64_t)T > (int64_t)1 << 20) return MARL_ERR_BAD_DIM;
+    }
+    if (!obs || !actions || !filled || !grad_q_taken || !workspace || !grad_weights) return MARL_ERR_NULL;
+    if (workspace_bytes < need) return MARL_ERR_BAD_DIM;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MARL_ERR_BAD_ARG;
+    DeviceGuard guard(q->desc.device);
+    if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    MARL_HIP(marl::launch_qnet_grad(q->net, B, T, obs, actions, filled, grad_q_taken, workspace, grad_weights,
+                                    static_cast<hipStream_t>(hip_stream)));
+    return MARL_OK;
 }
 
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable)

@@ -115,6 +115,9 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     out->off_wih_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
     out->off_whh_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
     out->off_w2_16 = off;   off = align256(off + (size_t)ab * KS * frag_bytes);
+    out->off_wihT_16 = off; off = align256(off + (size_t)FBK * 3 * KS * frag_bytes);
+    out->off_whhT_16 = off; off = align256(off + (size_t)FBK * 3 * KS * frag_bytes);
+    out->off_w2_plain = off; off = align256(off + sizeof(float) * (size_t)A * H);
     out->off_bias1 = off;   off = align256(off + sizeof(float) * (size_t)N * H);
     out->off_bias_r = off;  off = align256(off + sizeof(float) * H);
     out->off_bias_z = off;  off = align256(off + sizeof(float) * H);
@@ -183,6 +186,20 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
                          Whh + (size_t)gate * H * H, H, H, H, true, planes);
         }
         pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_w2_16), W2, A, H, H, true, planes);
+    }
+
+    // Backward pass: W_ih^T and W_hh^T as [H, 3H] matrices (row k, column gate H + j), and fc2 as it is.
+    {
+        std::vector<float> wt((size_t)H * 3 * H);
+        for (int which = 0; which < 2; ++which) {
+            const float *W = which ? Whh : Wih;
+            for (int g = 0; g < 3 * H; ++g)
+                for (int k = 0; k < H; ++k) wt[(size_t)k * 3 * H + g] = W[(size_t)g * H + k];
+            pack_frags16(reinterpret_cast<uint16_t *>(img + (which ? out->off_whhT_16 : out->off_wihT_16)), wt.data(), H,
+                         3 * H, 3 * H, true, planes);
+        }
+        float *w2p = reinterpret_cast<float *>(img + out->off_w2_plain);
+        for (size_t i = 0; i < (size_t)A * H; ++i) w2p[i] = planes == 1 ? bf16_value(bf16_bits(W2[i])) : W2[i];
     }
 
     // The agent-id column of W1 is a per-agent bias.  A bf16 network uses the rounded weight.

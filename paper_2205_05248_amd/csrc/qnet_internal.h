@@ -35,6 +35,11 @@ struct NetFrags {
     const bf16x8 *wih_16;   // [3][H/16][H/32][P][64]
     const bf16x8 *whh_16;   // [3][H/16][H/32][P][64]
     const bf16x8 *w2_16;    // [ceil(A/16)][H/32][P][64]
+    // backward pass: the transposed GRU matrices (H output rows, contraction over the 3H stacked gate
+    // units r, z, n) as 16x16x32 fragments [H/16][3H/32][P][64], and fc2 as plain fp32 [A][H]
+    const bf16x8 *wihT_16;
+    const bf16x8 *whhT_16;
+    const float *w2_plain;
     const float *bias1;   // [N][H]   b1 + W1[:, D + n]
     const float *bias_r;  // [H]      b_ir + b_hr
     const float *bias_z;  // [H]      b_iz + b_hz
@@ -76,7 +81,7 @@ namespace marl {
 struct PackedImage {
     void *host;        // malloc'ed image, caller frees
     size_t bytes;
-    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_wihT_16, off_whhT_16, off_w2_plain, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
     int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
@@ -106,7 +111,10 @@ size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
 // available action of slot t + 1 into next_action[b, t, n] (-1: none available) and leaves
 // next_max / td_target alone; kTdValue with the target network reads those indices and writes
 // next_max / td_target from its own value of that action, and leaves q_taken / q_all alone.
-enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2 };
+// kTdSave (fused kernels, one network): no TD output at all; the fc1 output x and the hidden state of
+// every slot go to x_save / h_save [B, T+1, N, H] fp32 for the backward pass: x_save[b, s] = x of slot s,
+// h_save[b, 0] = 0 and h_save[b, s + 1] = the state after slot s (s < T).
+enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2, kTdSave = 3 };
 
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
                             void *scratch_target, int B, int T, const int32_t *episode_index, int pool_episodes,
@@ -132,6 +140,14 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
                                const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream,
-                               TdMode mode = kTdPlain, int32_t *next_action = nullptr);
+                               TdMode mode = kTdPlain, int32_t *next_action = nullptr, float *h_save = nullptr,
+                               float *x_save = nullptr);
+
+// Backward pass (bptt.hip): the gradient of sum(grad_q * q_taken) with respect to the packed parameters.
+// `fits`: the network runs on the fused unroll kernel and its widest layer fits the gradient product.
+bool qnet_grad_fits(const NetFrags &net);
+size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T);
+hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
+                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream);
 
 }  // namespace marl

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions, const float *__restrict__ reward,
     const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled, float gamma,
     float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target, float *__restrict__ q_all,
-    int32_t *__restrict__ next_action)
+    int32_t *__restrict__ next_action, float *__restrict__ h_save, float *__restrict__ x_save)
 {
     using Sh = Fused16<H, P>;
     constexpr int FBK = Sh::FBK, KS = Sh::KS, LEAD = kFusedLead;
@@ -92,20 +92,34 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[j][r] = 0.0f;
         GruWave<H, P>::publish(h_lds[0], w, lane, hv);
+        // kTdSave: this lane's units of its row's state, slot by slot
+        float *h_row = nullptr;
+        if constexpr (MODE == kTdSave) {
+            h_row = h_save + ((size_t)b * S * N + n) * H + 16 * Sh::NBC * w + 4 * q4;
+            if (valid)
+#pragma unroll
+                for (int j = 0; j < Sh::NBC; ++j) *reinterpret_cast<f32x4 *>(h_row + 16 * j) = hv[j];
+        }
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it <= T) {
                 const int cur = it & 1;
                 gru.step(lds, w, lane, q4, h_lds[cur], x_lds[cur], hv);
                 GruWave<H, P>::publish(h_lds[cur ^ 1], w, lane, hv);
+                if constexpr (MODE == kTdSave) {
+                    if (valid && it < T)
+#pragma unroll
+                        for (int j = 0; j < Sh::NBC; ++j)
+                            *reinterpret_cast<f32x4 *>(h_row + (size_t)(it + 1) * N * H + 16 * j) = hv[j];
+                }
             }
             lds_barrier();
         }
     } else if (wave == Sh::kEpilogue) {
         // ---------------------------------------------------------------- epilogue wave
         // kSelect / kValue: the two single-network launches of the double-estimator target
-        constexpr bool kSelect = MODE == kTdSelect, kValue = MODE == kTdValue;
-        const bool emit_online = !is_target && !kValue, emit_target = is_target || !two_nets;
+        constexpr bool kSelect = MODE == kTdSelect, kValue = MODE == kTdValue, kSave = MODE == kTdSave;
+        const bool emit_online = !is_target && !kValue && !kSave, emit_target = (is_target || !two_nets) && !kSave;
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
         WFrag<P> w2[AB][KS];
 #pragma unroll
@@ -220,13 +234,20 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             tch.consume(c);
             tch.touch(c, touch_row + (size_t)slot * N * D);
             // and what the epilogues will read for that slot: the row's availability and action
-            tch.set[c][tch.TLO] = avail[(((size_t)bi * S + slot) * N + n) * A];
-            tch.set[c][tch.TLO + 1] = (uint32_t)actions[((size_t)bi * T + min(slot, T - 1)) * N + n];
+            if constexpr (MODE != kTdSave) {
+                tch.set[c][tch.TLO] = avail[(((size_t)bi * S + slot) * N + n) * A];
+                tch.set[c][tch.TLO + 1] = (uint32_t)actions[((size_t)bi * T + min(slot, T - 1)) * N + n];
+            }
         };
         auto fc1_step = [&](int s) {
             const int slot = s + 1;
-            if (slot >= 0 && slot <= T)
-                fc1.step(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1]);
+            if (slot >= 0 && slot <= T) {
+                if constexpr (MODE == kTdSave)
+                    fc1.template step<true>(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1],
+                                            valid ? x_save + (((size_t)b * S + slot) * N + n) * H + 4 * q4 : nullptr);
+                else
+                    fc1.step(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1]);
+            }
             lds_barrier();
         };
         int s = -LEAD;
@@ -254,7 +275,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
                           const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                           const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                           float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
-                          int32_t *next_action)
+                          int32_t *next_action, float *h_save, float *x_save)
 {
     using Sh = Fused16<H, P>;
     const int tiles = (B * online.N + 15) / 16;
@@ -269,11 +290,13 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
         if (err != hipSuccess) return err;                                                                          \
         hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, episode_index, pool_episodes, \
                            obs, avail, actions,                                                                      \
-                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, next_action);    \
+                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, next_action,     \
+                           h_save, x_save);                                                                         \
     } while (0)
 #define MARL_FUSED_Q(ABLK)                                                                                          \
     do {                                                                                                            \
-        if (mode == kTdValue) MARL_FUSED(ABLK, false, kTdValue);                                                    \
+        if (mode == kTdSave) MARL_FUSED(ABLK, false, kTdSave);                                                      \
+        else if (mode == kTdValue) MARL_FUSED(ABLK, false, kTdValue);                                               \
         else if (mode == kTdSelect) { if (q_all) MARL_FUSED(ABLK, true, kTdSelect); else MARL_FUSED(ABLK, false, kTdSelect); } \
         else if (q_all) MARL_FUSED(ABLK, true, kTdPlain);                                                           \
         else MARL_FUSED(ABLK, false, kTdPlain);                                                                     \
@@ -311,12 +334,13 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
                                const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
-                               int32_t *next_action)
+                               int32_t *next_action, float *h_save, float *x_save)
 {
-    if (mode != kTdPlain && (two_nets || !next_action)) return hipErrorInvalidValue;
+    if ((mode == kTdSelect || mode == kTdValue) && (two_nets || !next_action)) return hipErrorInvalidValue;
+    if (mode == kTdSave && (two_nets || !h_save || !x_save)) return hipErrorInvalidValue;
 #define MARL_GO(HH, PP)                                                                                             \
     return fused_dispatch<HH, PP>(online, target, two_nets, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated, filled,  \
-                                  gamma, q_taken, next_max, td_target, q_all, stream, mode, next_action)
+                                  gamma, q_taken, next_max, td_target, q_all, stream, mode, next_action, h_save, x_save)
     if (online.H == 64 && online.planes == 2) MARL_GO(64, 2);
     if (online.H == 64 && online.planes == 1) MARL_GO(64, 1);
     if (online.H == 128 && online.planes == 1) MARL_GO(128, 1);

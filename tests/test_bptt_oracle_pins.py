@@ -19,8 +19,9 @@ def case(ci=0, B=3, T=7, seed=3):
     return cfg, dims, w, u, g
 
 
-def autograd_grad(dims, w, u, g):
-    """sum(g * q_taken) differentiated by the library; the forward pass is written with its ops."""
+def autograd_grad(dims, w, u, g, relu_band=None):
+    """sum(g * q_taken) differentiated by the library; the forward pass is written with its ops.
+    relu_band: also the ambiguity budget of W1 and b1, from the library's adjoint of x."""
     N, D, A, H = dims
     wt = torch.tensor(np.asarray(w, np.float64), requires_grad=True)
     sl = wl.weight_slices(*dims)
@@ -33,8 +34,13 @@ def autograd_grad(dims, w, u, g):
     act = torch.from_numpy(u["actions"].astype(np.int64))
     f = torch.from_numpy(u["filled"].astype(np.float64))
     gt = torch.from_numpy(g)
+    kept = []
     for t in range(T):
-        x = torch.relu(torch.cat([obs[:, t], eye], -1) @ p["W1"].T + p["b1"])
+        x_in = torch.cat([obs[:, t], eye], -1)
+        pre = x_in @ p["W1"].T + p["b1"]
+        x = torch.relu(pre)
+        x.retain_grad()
+        kept.append((x_in, pre, x))
         gi = x @ p["W_ih"].T + p["b_ih"]
         gh = h @ p["W_hh"].T + p["b_hh"]
         r = torch.sigmoid(gi[..., :H] + gh[..., :H])
@@ -44,7 +50,17 @@ def autograd_grad(dims, w, u, g):
         q = h @ p["W2"].T + p["b2"]
         total = total + (gt[:, t] * f[:, t, None] * q.gather(-1, act[:, t, :, None])[..., 0]).sum()
     total.backward()
-    return wt.grad.numpy()
+    if relu_band is None:
+        return wt.grad.numpy()
+    amb = np.zeros(wt.numel())
+    a1, b1_, shp = sl["W1"]
+    ab, bb, _ = sl["b1"]
+    for x_in, pre, x in kept:
+        near = (pre.detach().abs() <= relu_band).double()
+        dx = x.grad.abs() * near                                       # [B, N, H]
+        amb[ab:bb] += dx.sum((0, 1)).numpy()
+        amb[a1:b1_] += torch.einsum("bnj,bnd->jd", dx, x_in.abs()).reshape(-1).numpy()
+    return wt.grad.numpy(), amb
 
 
 @pytest.mark.parametrize("ci", [0, 1])
@@ -131,3 +147,20 @@ def test_one_step_scalar_network_by_hand():
                      gq * h, gq])                                 # W2, b2
     assert x > 0
     np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
+
+
+def test_relu_ambiguity_budget_matches_the_library_adjoints():
+    cfg, dims, w, u, g = case(1, B=2, T=6)
+    band = 0.05
+    got, amb = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g, relu_band=band)
+    want, want_amb = autograd_grad(dims, w, u, g, relu_band=band)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-11 * max(1.0, np.abs(want).max()))
+    np.testing.assert_allclose(amb, want_amb, rtol=0, atol=1e-11 * max(1.0, want_amb.max()))
+    sl = wl.weight_slices(*dims)
+    assert amb[sl["W1"][0]:sl["W1"][1]].max() > 0 and amb[sl["b1"][1]:].max() == 0        # only the first layer
+    # an empty band has an empty budget; a band that holds everything bounds the gradient itself
+    _, none = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g, relu_band=-1.0)
+    assert none.max() == 0
+    _, all_of_it = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g, relu_band=1e9)
+    a, b, _ = sl["W1"]
+    assert (np.abs(got[a:b]) <= all_of_it[a:b] + 1e-12).all()
