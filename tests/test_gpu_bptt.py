@@ -84,3 +84,68 @@ def test_gradient_matches_the_oracle(ci, B, T, over):
     again = gpu_grad(net, cfg, u, g)
     np.testing.assert_array_equal(again, got)
     net.close()
+
+
+def test_full_size_launch_on_a_few_live_episodes():
+    """The workload's full batch in the launch configuration the benchmark times; the upstream gradient is
+    non-zero for three episodes only, so the oracle has to walk just those (the sum is linear in it), while
+    every tile, chunk and reduction of the full-size launch takes part."""
+    cfg = wl.config(4)
+    dims = wl.dims(cfg)
+    B, T = cfg["B"], cfg["T"]
+    w = wl.make_weights(cfg, 0)
+    net = binding.QNet(dims, w, cfg["dtype"])
+    u = wl.make_unroll_inputs(cfg)
+    live = [0, 37, B - 1]
+    g = np.zeros((B, T, dims[0]), np.float32)
+    g[live] = np.random.default_rng(5).normal(size=(len(live), T, dims[0])).astype(np.float32)
+    got = gpu_grad(net, cfg, u, g)
+    sub = {k: np.ascontiguousarray(u[k][live]) for k in ("obs", "actions", "filled")}
+    want, amb = bpo.qnet_grad(dims, pu.oracle_weights(cfg, w), sub["obs"], sub["actions"], sub["filled"],
+                              g[live].astype(np.float64), relu_band=RELU_BAND[cfg["dtype"]])
+    compare(cfg, got, want, amb)
+    net.close()
+
+
+def test_edge_shapes_and_argument_errors():
+    cfg = dict(wl.config(1), B=1, T=1)
+    dims = wl.dims(cfg)
+    w = wl.make_weights(cfg, 0)
+    net = binding.QNet(dims, w, cfg["dtype"])
+    # one episode of one step, unfilled steps, and an all-zero upstream gradient
+    u = wl.make_unroll_inputs(cfg, B=1, T=1)
+    u["filled"][:] = 1
+    g = np.ones((1, 1, dims[0]), np.float32)
+    want, amb = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g.astype(np.float64), relu_band=1e-4)
+    compare(cfg, gpu_grad(net, cfg, u, g), want, amb)
+    u["filled"][:] = 0
+    assert np.abs(gpu_grad(net, cfg, u, g)).max() == 0
+    u2 = wl.make_unroll_inputs(cfg, B=3, T=4)
+    assert np.abs(gpu_grad(net, cfg, u2, np.zeros((3, 4, dims[0]), np.float32))).max() == 0
+    # arguments
+    lib, vp = binding.load(), ctypes.c_void_p
+    need = ctypes.c_size_t(0)
+    assert lib.marl_qnet_grad_workspace_bytes(vp(net.handle), 3, 4, ctypes.byref(need)) == 0 and need.value > 0
+    assert lib.marl_qnet_grad_workspace_bytes(vp(net.handle), 0, 4, ctypes.byref(need)) == -2
+    assert lib.marl_qnet_grad_workspace_bytes(vp(net.handle), 3, 0, ctypes.byref(need)) == -2
+    assert lib.marl_qnet_grad_workspace_bytes(None, 3, 4, ctypes.byref(need)) == -1
+    d = pu.to_dev(u2, ["obs", "actions", "filled"])
+    gq = torch.zeros(3, 4, dims[0], device="cuda")
+    bytes_needed = net.grad_workspace_bytes(3, 4)
+    ws = torch.empty(bytes_needed + 256, dtype=torch.uint8, device="cuda")
+    out = torch.zeros(wl.param_count(*dims), device="cuda")
+    call = lambda ws_ptr, ws_bytes, out_ptr: lib.marl_qnet_grad(
+        vp(net.handle), 3, 4, vp(d["obs"].data_ptr()), vp(d["actions"].data_ptr()), vp(d["filled"].data_ptr()),
+        vp(gq.data_ptr()), ws_ptr, ws_bytes, out_ptr, None)
+    assert call(vp(ws.data_ptr()), bytes_needed - 1, vp(out.data_ptr())) == -2        # workspace too small
+    assert call(vp(ws.data_ptr() + 4), bytes_needed, vp(out.data_ptr())) == -5        # misaligned
+    assert call(None, bytes_needed, vp(out.data_ptr())) == -1
+    assert call(vp(ws.data_ptr()), bytes_needed, None) == -1
+    assert call(vp(ws.data_ptr()), bytes_needed, vp(out.data_ptr())) == 0
+    torch.cuda.synchronize()
+    net.close()
+    # a network the fused kernels do not hold is refused, not served some other way
+    big = dict(wl.config(4), dtype="fp32")
+    net = binding.QNet(wl.dims(big), wl.make_weights(big, 0), "fp32")
+    assert lib.marl_qnet_grad_workspace_bytes(vp(net.handle), 3, 4, ctypes.byref(need)) == -2
+    net.close()
