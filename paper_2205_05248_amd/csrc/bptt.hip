@@ -258,10 +258,13 @@ struct TnGemmArgs {
     float *partial;     // [chunks][P rounded up to 64][qp]
 };
 
-constexpr int kTnMaxQBlocks = 24, kTnQPerWave = kTnMaxQBlocks / 4;      // at most 384 columns of B
+constexpr int kTnMaxQBlocks = 24;      // at most 384 columns of B
 
-__global__ __launch_bounds__(256, 1) void tn_gemm_kernel(TnGemmArgs g)
+// QPW: column blocks of the result per wave (4 QPW blocks of 16 columns per workgroup).
+template <int QPW>
+__global__ __launch_bounds__(256, QPW > 3 ? 1 : 2) void tn_gemm_kernel(TnGemmArgs g)
 {
+    constexpr int kTnQPerWave = QPW;
     extern __shared__ __attribute__((aligned(16))) float stage[];
     constexpr int kPitchA = 64 + 2;
     const int pitch_b = g.qp + 2;
@@ -282,24 +285,30 @@ __global__ __launch_bounds__(256, 1) void tn_gemm_kernel(TnGemmArgs g)
 
     float ra[8], rb[8][kTnQPerWave];
     auto fetch = [&](int m0) {                   // this wave's eight rows of the next 32 samples -> registers
+        // (group, row in group) of the wave's first row by division, of the following rows by stepping
+        const unsigned first = (unsigned)min(m0 + 8 * w, g.M - 1);
+        unsigned ga = first / (unsigned)g.a.rows_per_group, ia = first % (unsigned)g.a.rows_per_group;
+        unsigned gb = first / (unsigned)g.b.rows_per_group, ib = first % (unsigned)g.b.rows_per_group;
+        unsigned agent = first % (unsigned)g.N;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int m = m0 + 8 * w + r;
             const bool live = m < m_end;
-            const unsigned ms = live ? (unsigned)m : 0u;
-            const float *arow = g.a.base + (long)(ms / (unsigned)g.a.rows_per_group) * g.a.group_stride +
-                                (long)(ms % (unsigned)g.a.rows_per_group) * g.a.ld;
-            const float *brow = g.b.base + (long)(ms / (unsigned)g.b.rows_per_group) * g.b.group_stride +
-                                (long)(ms % (unsigned)g.b.rows_per_group) * g.b.ld;
+            const float *arow = g.a.base + (long)ga * g.a.group_stride + (long)ia * g.a.ld;
+            const float *brow = g.b.base + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
             ra[r] = (live && p0 + lane < g.P) ? arow[p0 + lane] : 0.0f;
-            const int agent = (int)(ms % (unsigned)g.N);
 #pragma unroll
             for (int i = 0; i < kTnQPerWave; ++i) {
                 const int col = lane + 64 * i;
                 float v = 0.0f;
                 if (live && col < g.Q) v = brow[col];
-                else if (live && col < g.Q + g.n_extra) v = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == agent ? 1.0f : 0.0f);
+                else if (live && col < g.Q + g.n_extra) v = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == (int)agent ? 1.0f : 0.0f);
                 rb[r][i] = v;
+            }
+            if (m + 1 < g.M) {                    // the next row; past the end the last row is kept (and not used)
+                if (++ia == (unsigned)g.a.rows_per_group) { ia = 0; ++ga; }
+                if (++ib == (unsigned)g.b.rows_per_group) { ib = 0; ++gb; }
+                if (++agent == (unsigned)g.N) agent = 0;
             }
         }
     };
@@ -358,10 +367,10 @@ __global__ __launch_bounds__(256, 1) void tn_gemm_kernel(TnGemmArgs g)
         }
 }
 
-// Sum of the chunks, in order, into the packed gradient vector.  Result row p goes to row
+// Sum of the chunks, in a fixed order, into the packed gradient vector.  Result row p goes to row
 // (p + row_shift) % P of the destination matrix (the adjoint array lists the gates as n, r, z, the
-// parameters as r, z, n); columns < w_cols go to dst_w[row * ld_w + column]; the appended columns
-// go to dst_b[row] (kExtraOnes: the one column; kExtraAgent: the sum of the N columns).
+// parameters as r, z, n); columns < Q go to dst_w[row * ld_w + column]; the appended column of ones
+// goes to dst_b[row]; appended agent columns continue the row of dst_w (they are W1's id columns).
 struct TnReduceArgs {
     const float *partial;
     int chunks, P, p_pad, qp;
@@ -372,31 +381,37 @@ struct TnReduceArgs {
 
 __global__ void tn_reduce_kernel(TnReduceArgs g)
 {
+    const int cols = g.Q + g.n_extra;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
-    const int total = g.P * (g.Q + 1);
-    if (idx >= total) return;
-    const int p = idx / (g.Q + 1), q = idx % (g.Q + 1);
+    if (idx >= g.P * cols) return;
+    const int p = idx / cols, q = idx % cols;
     const int row = (p + g.row_shift) % g.P;
-    auto column = [&](int col) {
-        float s = 0.0f;
-        for (int ch = 0; ch < g.chunks; ++ch) s += g.partial[((size_t)ch * g.p_pad + p) * g.qp + col];
-        return s;
-    };
-    if (q < g.Q) {
-        g.dst_w[(size_t)row * g.ld_w + q] = column(q);
-        return;
+    // four running sums over interleaved chunks keep sixteen loads in flight; the order is fixed
+    const float *src = g.partial + (size_t)p * g.qp + q;
+    const size_t step = (size_t)g.p_pad * g.qp;
+    float s[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    int ch = 0;
+    for (; ch + 16 <= g.chunks; ch += 16) {
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = src[(size_t)(ch + i) * step];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s[i & 3] += v[i];
     }
-    if (g.extra_mode == kExtraOnes) {
-        g.dst_b[row] = column(g.Q);
-    } else {
-        float s = 0.0f;
-        for (int e = 0; e < g.n_extra; ++e) {
-            const float v = column(g.Q + e);
-            g.dst_w[(size_t)row * g.ld_w + g.Q + e] = v;
-            s += v;
-        }
-        g.dst_b[row] = s;
-    }
+    for (; ch < g.chunks; ++ch) s[ch & 3] += src[(size_t)ch * step];
+    const float total = (s[0] + s[1]) + (s[2] + s[3]);
+    if (q < g.Q || g.extra_mode == kExtraAgent) g.dst_w[(size_t)row * g.ld_w + q] = total;
+    else g.dst_b[row] = total;
+}
+
+// kExtraAgent: the bias gradient is the sum of the agent columns just written.
+__global__ void bias_from_columns_kernel(const float *w, int rows, int ld, int first, int count, float *dst)
+{
+    const int row = blockIdx.x * blockDim.x + threadIdx.x;
+    if (row >= rows) return;
+    float s = 0.0f;
+    for (int e = 0; e < count; ++e) s += w[(size_t)row * ld + first + e];
+    dst[row] = s;
 }
 
 // ------------------------------------------------------------------------------------------ host side
@@ -446,17 +461,27 @@ hipError_t run_product(const RowMap &a, const RowMap &b, long M, int P, int Q, i
     if (g.qp > 16 * kTnMaxQBlocks) return hipErrorInvalidValue;
     const int p_tiles = (P + 63) / 64, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
     const size_t lds = (size_t)32 * (66 + g.qp + 2) * sizeof(float);
-    hipError_t err = allow_large_lds<tn_gemm_kernel>(kLdsLimit);
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(tn_gemm_kernel, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
+    hipError_t err;
+    if (g.qp <= 16 * 4 * 3) {
+        err = allow_large_lds<tn_gemm_kernel<3>>(kLdsLimit);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(tn_gemm_kernel<3>, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
+    } else {
+        err = allow_large_lds<tn_gemm_kernel<6>>(kLdsLimit);
+        if (err != hipSuccess) return err;
+        hipLaunchKernelGGL(tn_gemm_kernel<6>, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
+    }
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     TnReduceArgs r{};
     r.partial = partial; r.chunks = chunks; r.P = P; r.p_pad = p_tiles * 64; r.qp = g.qp;
     r.Q = Q; r.n_extra = n_extra; r.extra_mode = extra_mode;
     r.row_shift = row_shift; r.w_cols = Q; r.ld_w = ld_w; r.dst_w = dst_w; r.dst_b = dst_b;
-    const int total = P * (Q + 1);
+    const int total = P * (Q + n_extra);
     hipLaunchKernelGGL(tn_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, r);
+    err = hipGetLastError();
+    if (err != hipSuccess || extra_mode != kExtraAgent) return err;
+    hipLaunchKernelGGL(bias_from_columns_kernel, dim3((P + 255) / 256), dim3(256), 0, stream, dst_w, P, ld_w, Q, n_extra, dst_b);
     return hipGetLastError();
 }
 
