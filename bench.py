@@ -285,6 +285,60 @@ def mixer_section(ci, with_cpu, launches=20):
     return out
 
 
+def grad_section(ci, with_cpu, launches=10):
+    """The backward pass of the learner step on the same workload's batch (marl_qnet_grad: forward pass that
+    keeps activations, time-reversed pass, weight-gradient products; not part of the timed step above):
+    time per call from events on the launch stream, and the back-propagation oracle on a bounded sample."""
+    import torch
+    from paper_2205_05248_amd import binding, workloads as wl
+    cfg = wl.config(ci)
+    dims = N, D, A, H = wl.dims(cfg)
+    B, T = cfg["B"], cfg["T"]
+    w = wl.make_weights(cfg, 0)
+    net = binding.QNet(dims, w, cfg["dtype"])
+    u = wl.make_unroll_inputs(cfg)
+    try:
+        need = net.grad_workspace_bytes(B, T)
+    except binding.MarlError:
+        net.close()
+        return {"kernel": "qnet_grad", "ms": None, "note": "the network does not fit the fused kernels the backward pass builds on"}
+    d = {k: torch.from_numpy(np.ascontiguousarray(u[k])).cuda() for k in ("obs", "actions", "filled")}
+    g_host = np.random.default_rng(1).normal(size=(B, T, N)).astype(np.float32)
+    g = torch.from_numpy(g_host).cuda()
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    out_grad = torch.empty(wl.param_count(*dims), device="cuda")
+    call = lambda: net.grad(d["obs"], d["actions"], d["filled"], g, ws, out_grad)
+    for _ in range(2):
+        call()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(launches):
+        call()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / launches
+    net.close()
+    rows = B * N
+    fwd = rows * (T + 1) * (2 * D * H + 12 * H * H + 2 * H * A)        # the forward pass again, activations kept
+    back = rows * T * (12 * H * H + 12 * H * H)                        # the gates again + the two transposed products
+    wgrad = rows * T * (2 * 2 * 3 * H * (H + 1) + 2 * H * (D + N) + 2 * A * (H + 1))
+    flops = fwd + back + wgrad
+    out = {"kernel": "qnet_grad (4 kernels)", "ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "bound": "mfma",
+           "TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK["bf16_TFs"],
+           "workspace_bytes": need, "config": {"B": B, "T": T, "rows": rows, "parameters": int(out_grad.numel())}}
+    if with_cpu:
+        from oracle import bptt_oracle as bpo
+        sample_b = max(1, min(B, 2))
+        t0 = time.perf_counter()
+        bpo.qnet_grad(dims, w, u["obs"][:sample_b], u["actions"][:sample_b], u["filled"][:sample_b],
+                      g_host[:sample_b].astype(np.float64))
+        sec = time.perf_counter() - t0
+        out["cpu_oracle"] = {"transitions_per_s": sample_b * T / sec, "cores": min(sample_b, bpo.default_threads()),
+                             "sample": f"first {sample_b} of {B} episodes, all {T} transitions"}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -389,6 +443,7 @@ def main():
         "roofline": roofline,
     }
     out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
+    out["qnet_grad"] = grad_section(args.config, not args.no_cpu_baseline)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

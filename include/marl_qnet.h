@@ -260,7 +260,7 @@ int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
  * same bits.  Arithmetic: bf16 MFMA products with fp32 accumulation; fp32 networks split every
  * operand into two bf16 parts, bf16 networks round the adjoints inside the recurrence to bf16.
  * Only networks that run on the fused16 kernels are served (see marl_qnet_set_kernels), with
- * D + N <= 384: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^32, or a
+ * D + N <= 384: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^30, or a
  * workspace that is too small; MARL_ERR_BAD_ARG for a misaligned workspace.
  */
 int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, size_t *bytes);

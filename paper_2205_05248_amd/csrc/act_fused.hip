@@ -61,7 +61,6 @@ __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)
 
 constexpr int kActLead = 2;          // steps before item 0 enters the GRU
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-constexpr int kRawBuffer = 0x00020000;       // descriptor word 3: untyped 32-bit data, no swizzle, offsets checked against the size
 
 template <int H, int P, int AB>
 __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const ActFusedArgs args)

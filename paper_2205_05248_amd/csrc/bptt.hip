@@ -104,12 +104,16 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
     const float *h_row = a.h_all + ((size_t)b * S * N + n) * H + unit0;
     const float *x_row = a.x_all + ((size_t)b * S * N + n) * H + unit0;
 
-    struct StepIn { f32x4 hp[NBC], xv[NBC], w2[NBC]; float gq; int u; };
-    auto fetch = [&](int t) {
+    // The inputs of a slot are asked for one iteration before it; the chosen action, whose row of W2 is one
+    // of those inputs, one iteration earlier still.  Nothing here is conditional (rows past the end read row 0).
+    struct StepIn { f32x4 hp[NBC], xv[NBC], w2[NBC]; float gq_raw; uint8_t fil; int u; };
+    auto load_action = [&](int t) { return a.actions[((size_t)b * T + t) * N + n]; };
+    auto fetch = [&](int t, int u_raw) {
         StepIn in;
         const size_t bt = (size_t)b * T + t;
-        in.u = min(max(a.actions[bt * N + n], 0), A - 1);
-        in.gq = (valid && a.filled[bt]) ? a.grad_q[bt * N + n] : 0.0f;
+        in.u = min(max(u_raw, 0), A - 1);
+        in.fil = a.filled[bt];
+        in.gq_raw = a.grad_q[bt * N + n];
 #pragma unroll
         for (int j = 0; j < NBC; ++j) {
             in.hp[j] = *reinterpret_cast<const f32x4 *>(h_row + (size_t)t * slot_stride + 16 * j);
@@ -125,11 +129,35 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
 #pragma unroll
         for (int r = 0; r < 4; ++r) dh[j][r] = 0.0f;
 
-    StepIn nxt = fetch(T - 1);
+    // Every global access inside the loop is unconditional, so that the loop body is straight-line code and
+    // the waits for the prefetched inputs count exactly the stores issued after them: rows past the end
+    // store through buffer descriptors at an offset beyond the descriptor, which the hardware drops.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr uint32_t kDrop = 0xFFFFFFF0u;
+    const size_t samples = (size_t)rows * T;
+    const __amdgpu_buffer_rsrc_t da_buf = __builtin_amdgcn_make_buffer_rsrc(a.da, 0, (int)(uint32_t)(samples * 4 * H * 4), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t pre_buf = __builtin_amdgcn_make_buffer_rsrc(a.dpre1, 0, (int)(uint32_t)(samples * H * 4), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t dq_buf = __builtin_amdgcn_make_buffer_rsrc(a.dq, 0, (int)(uint32_t)(samples * a.a16 * 4), kRawBuffer);
+    uint32_t drop = valid ? 0u : kDrop;
+    asm volatile("" : "+v"(drop));
+    const uint32_t drop_dq = (16 * w < a.a16) ? drop : kDrop;      // wave w writes block w of the row's dQ
+
+    StepIn nxt = fetch(T - 1, load_action(T - 1));
+    int u_ahead = load_action(max(T - 2, 0));
+    // Nothing may be in flight when the loop is entered: the waits inside it are then the ones of the loop
+    // itself (the entry would otherwise add its own, stricter ones, which make every iteration wait for the
+    // previous iteration's stores).
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int j = 0; j < NBC; ++j) asm volatile("" : "+v"(nxt.hp[j]), "+v"(nxt.xv[j]), "+v"(nxt.w2[j]));
+    asm volatile("" : "+v"(nxt.gq_raw), "+v"(u_ahead));
     lds_barrier();                                                 // W_ih and the biases are in LDS
     for (int t = T - 1; t >= 0; --t) {
         const StepIn in = nxt;
-        if (t > 0) nxt = fetch(t - 1);
+        const int u_next = u_ahead;
+        u_ahead = load_action(max(t - 2, 0));
+        nxt = fetch(max(t - 1, 0), u_next);
+        const float gq = (valid && in.fil) ? in.gq_raw : 0.0f;
         GruWave<H, P>::publish(hf, w, lane, in.hp);
         GruWave<H, P>::publish(xf, w, lane, in.xv);
         lds_barrier();
@@ -169,7 +197,7 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
             for (int r = 0; r < 4; ++r) {
                 const float rr = sigmoidf_fast(acc_r[j][r]), zz = sigmoidf_fast(acc_z[j][r]);
                 const float nn = tanhf_fast(acc_in[j][r] + rr * acc_hn[j][r]);
-                const float dht = dh[j][r] + in.gq * in.w2[j][r];             // Q_t[u] = W2[u] . h_t + b2[u]
+                const float dht = dh[j][r] + gq * in.w2[j][r];             // Q_t[u] = W2[u] . h_t + b2[u]
                 const float dn = dht * (1.0f - zz) * (1.0f - nn * nn);
                 dan[j][r] = dn;
                 dahn[j][r] = dn * rr;
@@ -177,25 +205,21 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
                 daz[j][r] = dht * (in.hp[j][r] - nn) * zz * (1.0f - zz);
                 carry[j][r] = dht * zz;
             }
-        const size_t m = ((size_t)b * T + t) * N + n;
-        if (valid) {
-            float *da_row = a.da + m * 4 * H + unit0;
+        const uint32_t m = (uint32_t)((b * T + t) * N + n);          // sample index; the host bounds 4 H samples to 2^30
+        {
+            const uint32_t da_at = (m * 4 * H + unit0) * 4u;
 #pragma unroll
             for (int j = 0; j < NBC; ++j) {
-                *reinterpret_cast<f32x4 *>(da_row + 0 * H + 16 * j) = dan[j];
-                *reinterpret_cast<f32x4 *>(da_row + 1 * H + 16 * j) = dar[j];
-                *reinterpret_cast<f32x4 *>(da_row + 2 * H + 16 * j) = daz[j];
-                *reinterpret_cast<f32x4 *>(da_row + 3 * H + 16 * j) = dahn[j];
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dan[j]), da_buf, (da_at + (0 * H + 16 * j) * 4u) | drop, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dar[j]), da_buf, (da_at + (1 * H + 16 * j) * 4u) | drop, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, daz[j]), da_buf, (da_at + (2 * H + 16 * j) * 4u) | drop, 0, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dahn[j]), da_buf, (da_at + (3 * H + 16 * j) * 4u) | drop, 0, 0);
             }
-            if (w == 0) {                                          // the adjoint of Q_t, one wave writes the row
-                float *dq_row = a.dq + m * a.a16;
-                for (int ab = 0; 16 * ab < a.a16; ++ab) {
-                    f32x4 v;
+            // the adjoint of Q_t, dense: wave w writes action block w of every row
+            f32x4 v;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v[r] = (16 * ab + 4 * q4 + r == in.u) ? in.gq : 0.0f;
-                    *reinterpret_cast<f32x4 *>(dq_row + 16 * ab + 4 * q4) = v;
-                }
-            }
+            for (int r = 0; r < 4; ++r) v[r] = (16 * w + 4 * q4 + r == in.u) ? gq : 0.0f;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dq_buf, ((m * a.a16 + 16 * w + 4 * q4) * 4u) | drop_dq, 0, 0);
         }
         GruWave<H, P>::publish(daf + 0 * KS, w, lane, dar);
         GruWave<H, P>::publish(daf + 1 * KS, w, lane, daz);
@@ -232,7 +256,7 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
             f32x4 dp;
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp[r] = in.xv[j][r] > 0.0f ? accx[j][r] : 0.0f;
-            if (valid) *reinterpret_cast<f32x4 *>(a.dpre1 + m * H + unit0 + 16 * j) = dp;
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dp), pre_buf, ((m * H + unit0 + 16 * j) * 4u) | drop, 0, 0);
         }
     }
 }

@@ -27,6 +27,7 @@ hipError_t allow_large_lds(int bytes)
 
 constexpr int kFusedLead = 3;         // steps before slot 0 enters the recurrence
 constexpr int kLdsLimit = 160 * 1024;
+constexpr int kRawBuffer = 0x00020000;       // descriptor word 3: untyped 32-bit data, no swizzle, offsets checked against the size
 
 template <int H, int P> struct Fused16 {
     static constexpr int FBK = H / 16;                 // feature blocks of the hidden layer

@@ -422,7 +422,7 @@ int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_epi
 int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, size_t *bytes)
 {
     if (!q || !bytes) return MARL_ERR_NULL;
-    if (B < 1 || T < 1 || (int64_t)B * q->desc.n_agents * ((int64_t)T + 1) * 4 * q->desc.hidden >= (int64_t)1 << 32)
+    if (B < 1 || T < 1 || (int64_t)B * q->desc.n_agents * ((int64_t)T + 1) * 4 * q->desc.hidden >= (int64_t)1 << 30)
         return MARL_ERR_BAD_DIM;
     if (!marl::qnet_grad_fits(q->net)) return MARL_ERR_BAD_DIM;
     *bytes = marl::qnet_grad_workspace_bytes(q->net, B, T);
