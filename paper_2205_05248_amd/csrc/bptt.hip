@@ -289,10 +289,12 @@ template <int QPW>
 __global__ __launch_bounds__(256, QPW > 3 ? 1 : 2) void tn_gemm_kernel(TnGemmArgs g)
 {
     constexpr int kTnQPerWave = QPW;
-    extern __shared__ __attribute__((aligned(16))) float stage[];
-    constexpr int kPitchA = 64 + 2;
-    const int pitch_b = g.qp + 2;
-    float *const As = stage, *const Bs = stage + 32 * kPitchA;
+    // LDS: two buffers (even and odd steps) of two planes (bf16 high part, bf16 of the remainder), each plane
+    // column-major: column c of the staged 32 samples is 64 bytes, the lane's eight samples of a fragment 16.
+    // Columns 0..63 are the workgroup's columns of A, then B's.
+    extern __shared__ __attribute__((aligned(16))) char stage[];
+    constexpr int kPitch = 80;                                     // bytes per column: 64 + 16 against bank conflicts
+    const int plane_bytes = (64 + g.qp) * kPitch;
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int p0 = blockIdx.x * 64;
@@ -307,8 +309,14 @@ __global__ __launch_bounds__(256, QPW > 3 ? 1 : 2) void tn_gemm_kernel(TnGemmArg
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[pb][j][r] = 0.0f;
 
-    float ra[8], rb[8][kTnQPerWave];
-    auto fetch = [&](int m0) {                   // this wave's eight rows of the next 32 samples -> registers
+    // Inputs are asked for kDepth steps before they are used, into kDepth register sets that the unrolled
+    // loop addresses statically.  Every load is unconditional (addresses clamped into the arrays, the value
+    // replaced afterwards where it does not count), so the loop is straight-line code and each wait covers
+    // exactly the set it needs.
+    constexpr int kDepth = 2;
+    float ra[kDepth][8], rb[kDepth][8][kTnQPerWave], rm[kDepth][8][kTnQPerWave];
+    const int a_col = p0 + lane < g.P ? p0 + lane : 0;
+    auto fetch = [&](float (&fa)[8], float (&fb)[8][kTnQPerWave], float (&fm)[8][kTnQPerWave], int m0) {      // this wave's eight rows of 32 samples
         // (group, row in group) of the wave's first row by division, of the following rows by stepping
         const unsigned first = (unsigned)min(m0 + 8 * w, g.M - 1);
         unsigned ga = first / (unsigned)g.a.rows_per_group, ia = first % (unsigned)g.a.rows_per_group;
@@ -320,59 +328,86 @@ __global__ __launch_bounds__(256, QPW > 3 ? 1 : 2) void tn_gemm_kernel(TnGemmArg
             const bool live = m < m_end;
             const float *arow = g.a.base + (long)ga * g.a.group_stride + (long)ia * g.a.ld;
             const float *brow = g.b.base + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
-            ra[r] = (live && p0 + lane < g.P) ? arow[p0 + lane] : 0.0f;
+            fa[r] = arow[a_col];                  // raw: what does not count is replaced in `deposit`
 #pragma unroll
             for (int i = 0; i < kTnQPerWave; ++i) {
                 const int col = lane + 64 * i;
-                float v = 0.0f;
-                if (live && col < g.Q) v = brow[col];
-                else if (live && col < g.Q + g.n_extra) v = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == (int)agent ? 1.0f : 0.0f);
-                rb[r][i] = v;
+                float made = 0.0f;                // the appended columns, or zero for padding and rows past the end
+                if (live && col >= g.Q && col < g.Q + g.n_extra)
+                    made = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == (int)agent ? 1.0f : 0.0f);
+                fb[r][i] = brow[col < g.Q ? col : 0];
+                fm[r][i] = made;
             }
-            if (m + 1 < g.M) {                    // the next row; past the end the last row is kept (and not used)
-                if (++ia == (unsigned)g.a.rows_per_group) { ia = 0; ++ga; }
-                if (++ib == (unsigned)g.b.rows_per_group) { ib = 0; ++gb; }
-                if (++agent == (unsigned)g.N) agent = 0;
-            }
+            // the next row, without a branch (a branch between two loads would make every wait a full one);
+            // past the end the last row is kept (and not used)
+            const unsigned go = m + 1 < g.M ? 1u : 0u;
+            ia += go; ib += go; agent += go;
+            const unsigned wa = ia == (unsigned)g.a.rows_per_group ? 1u : 0u, wb = ib == (unsigned)g.b.rows_per_group ? 1u : 0u;
+            ga += wa; ia = wa ? 0u : ia;
+            gb += wb; ib = wb ? 0u : ib;
+            agent = agent == (unsigned)g.N ? 0u : agent;
         }
     };
-    auto deposit = [&]() {
+    // The wave's eight samples of a column are samples 8 w + 0..7 of the step: as bf16 they are exactly the 16
+    // bytes that lane quarter w of a fragment of that column reads.  Converted once here, not by every reader.
+    // A loaded value is first passed through an empty asm: that is where the wait for it goes, and it keeps the
+    // compiler from turning "loaded value or zero" into a branch around the load.
+    auto deposit = [&](char *buf, float (&fa)[8], float (&fb)[8][kTnQPerWave], const float (&fm)[8][kTnQPerWave], int m0) {
+        auto put = [&](int col, const float (&v)[8]) {
+            const Frag<2> f = to_frag<2>(v);
+            *reinterpret_cast<bf16x8 *>(buf + col * kPitch + 16 * w) = f.hi;
+            *reinterpret_cast<bf16x8 *>(buf + plane_bytes + col * kPitch + 16 * w) = f.lo;
+        };
+        float va[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            As[(8 * w + r) * kPitchA + lane] = ra[r];
-#pragma unroll
-            for (int i = 0; i < kTnQPerWave; ++i)
-                if (lane + 64 * i < g.qp) Bs[(8 * w + r) * pitch_b + lane + 64 * i] = rb[r][i];
+            asm volatile("" : "+v"(fa[r]));
+            va[r] = (m0 + 8 * w + r < m_end && p0 + lane < g.P) ? fa[r] : 0.0f;
         }
-    };
-
-    fetch(m_begin);
-    for (int m0 = m_begin; m0 < m_end; m0 += 32) {
-        __syncthreads();                         // the previous step's fragments have been read
-        deposit();
-        __syncthreads();
-        if (m0 + 32 < m_end) fetch(m0 + 32);
-        // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
-        WFrag<2> af[4];
+        put(lane, va);
 #pragma unroll
-        for (int pb = 0; pb < 4; ++pb) {
-            float v[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) v[i] = As[(8 * q4 + i) * kPitchA + 16 * pb + c];
-            const Frag<2> f = to_frag<2>(v);
-            af[pb].hi = f.hi;
-            af[pb].lo = f.lo;
-        }
-#pragma unroll
-        for (int j = 0; j < kTnQPerWave; ++j) {
-            const int qb = w + 4 * j;
-            if (qb < n_qb) {
+        for (int i = 0; i < kTnQPerWave; ++i)
+            if (lane + 64 * i < g.qp) {
                 float v[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) v[i] = Bs[(8 * q4 + i) * pitch_b + 16 * qb + c];
-                const Frag<2> bf = to_frag<2>(v);
+                for (int r = 0; r < 8; ++r) {
+                    asm volatile("" : "+v"(fb[r][i]));
+                    v[r] = (m0 + 8 * w + r < m_end && lane + 64 * i < g.Q) ? fb[r][i] : fm[r][i];
+                }
+                put(64 + lane + 64 * i, v);
+            }
+    };
+
 #pragma unroll
-                for (int pb = 0; pb < 4; ++pb) mma16<2>(acc[pb][j], af[pb], bf);
+    for (int d = 0; d < kDepth; ++d) fetch(ra[d], rb[d], rm[d], m_begin + 32 * d);
+    // Rounds of kDepth steps; steps past the end of the chunk add zeros.
+    for (int m0 = m_begin; m0 < m_end; m0 += 32 * kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            // One barrier per step: the buffer written now was last read two steps ago, and every wave has
+            // passed the previous step's barrier since.
+            char *buf = stage + (d & 1) * 2 * plane_bytes;
+            deposit(buf, ra[d], rb[d], rm[d], m0 + 32 * d);
+            __syncthreads();
+            fetch(ra[d], rb[d], rm[d], m0 + 32 * (d + kDepth));
+            // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
+            const char *mine = buf + c * kPitch + 16 * q4;
+            WFrag<2> af[4];
+#pragma unroll
+            for (int pb = 0; pb < 4; ++pb) {
+                af[pb].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * pb * kPitch);
+                af[pb].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * pb * kPitch);
+            }
+#pragma unroll
+            for (int j = 0; j < kTnQPerWave; ++j) {
+                const int qb = w + 4 * j;
+                if (qb < n_qb) {
+                    Frag<2> bf;
+                    bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (64 + 16 * qb) * kPitch);
+                    bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (64 + 16 * qb) * kPitch);
+#pragma unroll
+                    for (int pb = 0; pb < 4; ++pb) mma16<2>(acc[pb][j], af[pb], bf);
+                }
             }
         }
     }
@@ -484,7 +519,7 @@ hipError_t run_product(const RowMap &a, const RowMap &b, long M, int P, int Q, i
     g.partial = partial;
     if (g.qp > 16 * kTnMaxQBlocks) return hipErrorInvalidValue;
     const int p_tiles = (P + 63) / 64, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
-    const size_t lds = (size_t)32 * (66 + g.qp + 2) * sizeof(float);
+    const size_t lds = (size_t)4 * (64 + g.qp) * 80;            // two buffers of two planes, 80 bytes per column
     hipError_t err;
     if (g.qp <= 16 * 4 * 3) {
         err = allow_large_lds<tn_gemm_kernel<3>>(kLdsLimit);
