@@ -318,6 +318,16 @@ def grad_section(ci, with_cpu, launches=10):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / launches
+    # the parameter update that follows it: weights -= lr * gradient, image rebuilt on the device
+    master = torch.from_numpy(w.copy()).cuda()
+    net.sgd_step(master, out_grad, 0.0)                   # the first call builds the map
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(launches):
+        net.sgd_step(master, out_grad, 0.0)
+    b.record()
+    torch.cuda.synchronize()
+    sgd_ms = a.elapsed_time(b) / launches
     net.close()
     rows = B * N
     fwd = rows * (T + 1) * (2 * D * H + 12 * H * H + 2 * H * A)        # the forward pass again, activations kept
@@ -326,7 +336,8 @@ def grad_section(ci, with_cpu, launches=10):
     flops = fwd + back + wgrad
     out = {"kernel": "qnet_grad (4 kernels)", "ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "bound": "mfma",
            "TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK["bf16_TFs"],
-           "workspace_bytes": need, "config": {"B": B, "T": T, "rows": rows, "parameters": int(out_grad.numel())}}
+           "sgd_step_ms": sgd_ms, "workspace_bytes": need,
+           "config": {"B": B, "T": T, "rows": rows, "parameters": int(out_grad.numel())}}
     if with_cpu:
         from oracle import bptt_oracle as bpo
         sample_b = max(1, min(B, 2))

@@ -240,6 +240,34 @@ int marl_unroll_td_double(marl_qnet *online, marl_qnet *target, int32_t pool_epi
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T);
 
 /*
+ * The learner's parameter update (Alg. 3: theta <- theta + d theta, here d theta = -lr * gradient) on
+ * the device:
+ *   weights[p] <- weights[p] - lr * grad_weights[p]      (fp32: the product is rounded, then the difference)
+ * and then the network `q` computes with the new weights: its resident image (operand fragments, bias
+ * tables) is rebuilt from them by kernels on the stream, with the same rounding as marl_qnet_create, so
+ * that `q` afterwards behaves bit for bit like a network created from the new weights.
+ *   weights       dev [marl_param_count] f32, in and out: the caller's copy of the parameters, in the
+ *                 order of marl_qnet_create (the handle itself keeps no fp32 copy)
+ *   grad_weights  dev [marl_param_count] f32, e.g. from marl_qnet_grad
+ *   lr            finite; MARL_ERR_BAD_ARG otherwise
+ * Stream-ordered like marl_qnet_set_weights: calls enqueued before it see the old weights, calls after
+ * it the new ones.  Nothing crosses to the host.  The first call on a handle builds a map of the image
+ * on the host and allocates and fills its device copy (synchronous, a few MB); later calls allocate
+ * nothing.  To hand the same update to other networks (the actors' copies, a target network), copy
+ * `weights` to the host and use marl_qnet_set_weights, or call this on each handle with its own copy.
+ */
+int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, float lr,
+                       void *hip_stream);
+
+/*
+ * Host-only self-check of the map marl_qnet_sgd_step rebuilds the image with: applied to
+ * host_weights with the device kernel's arithmetic it must reproduce, bit for bit, the fragment part of
+ * the image marl_qnet_create would build.  Touches no GPU.  MARL_OK, MARL_ERR_MISMATCH if it does not
+ * (or n_weights is wrong), MARL_ERR_NULL / the descriptor's error otherwise.
+ */
+int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_weights, size_t n_weights);
+
+/*
  * Backward half of the learner step (Alg. 3: "calculate the gradient"): back-propagation through
  * time over the network `q` for a batch of B episodes of T steps.  With q_taken as marl_unroll_td
  * returns it (q_taken[b,t,n] = filled[b,t] * Q(t)[actions[b,t,n]]) and the caller's

@@ -146,6 +146,8 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     q->staging_done = nullptr;
     q->scratch = nullptr;
     q->scratch_bytes = 0;
+    q->repack_map = nullptr;
+    q->repack_elems = 0;
     q->kernels = MARL_KERNELS_AUTO;
     {
         int n_cu = 0;
@@ -452,6 +454,37 @@ int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T, const float *obs, const i
     return MARL_OK;
 }
 
+int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_weights, size_t n_weights)
+{
+    if (!desc || !host_weights) return MARL_ERR_NULL;
+    int why;
+    if (!desc_valid(desc, &why)) return why;
+    if (n_weights != param_count(desc)) return MARL_ERR_MISMATCH;
+    return marl::repack_map_reproduces_packer(*desc, host_weights, n_weights) ? MARL_OK : MARL_ERR_MISMATCH;
+}
+
+int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, float lr, void *hip_stream)
+{
+    if (!q || !weights || !grad_weights) return MARL_ERR_NULL;
+    if (!(lr == lr) || lr - lr != 0.0f) return MARL_ERR_BAD_ARG;                 // NaN or infinite
+    DeviceGuard guard(q->desc.device);
+    if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
+    if (!q->repack_map) {
+        std::vector<int32_t> map;
+        if (!marl::build_repack_map(q->desc, q->n_params, &map, &q->layout)) return MARL_ERR_NOMEM;
+        int32_t *dev = nullptr;
+        hipError_t err = hipMalloc(&dev, map.size() * sizeof(int32_t));
+        if (err != hipSuccess) return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipMalloc");
+        err = hipMemcpy(dev, map.data(), map.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (err != hipSuccess) { (void)hipFree(dev); return device_fail(err, "hipMemcpy"); }
+        q->repack_map = dev;
+        q->repack_elems = map.size();
+    }
+    MARL_HIP(marl::launch_sgd_step(q->desc, q->layout, q->net.planes, q->repack_map, q->repack_elems, q->dev_weights, weights,
+                                   grad_weights, q->n_params, lr, static_cast<hipStream_t>(hip_stream)));
+    return MARL_OK;
+}
+
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable)
 {
     if (!q) return MARL_ERR_NULL;
@@ -496,7 +529,7 @@ int marl_destroy(marl_qnet *q)
     {
         DeviceGuard guard(q->desc.device);
         for (hipEvent_t e : q->ev_pool) (void)hipEventDestroy(e);
-        for (void *p : {q->dev_weights, q->scratch}) {
+        for (void *p : {q->dev_weights, q->scratch, static_cast<void *>(q->repack_map)}) {
             if (!p) continue;
             hipError_t err = hipFree(p);
             if (err != hipSuccess) rc = device_fail(err, "hipFree");        // hipFree waits for the device

@@ -54,6 +54,15 @@ struct NetFrags {
     int planes;           // P
 };
 
+// Host: build the device image of a network from packed fp32 weights.
+// Returns bytes; fills `image` (host) and offsets into `net` relative to base 0.
+struct PackedImage {
+    void *host;        // malloc'ed image, caller frees
+    size_t bytes;
+    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_wihT_16, off_whhT_16, off_w2_plain, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
+};
+
 }  // namespace marl
 
 struct marl_qnet {
@@ -72,18 +81,14 @@ struct marl_qnet {
     std::vector<hipEvent_t> ev_pool;   // events created so far (reused after a read)
     size_t ev_used;                    // events handed out since the last read
     std::vector<int> timed_calls;      // per recorded call: 2 = decision step (2 events), 3 = unroll (3 events)
+    // device-side refresh of the image (marl_qnet_sgd_step), built on first use
+    int32_t *repack_map;               // device: source parameter of every 16-bit element of the fragment part
+    size_t repack_elems;
+    marl::PackedImage layout;          // offsets of the image's arrays (host pointer unused)
 };
 
 namespace marl {
 
-// Host: build the device image of a network from packed fp32 weights.
-// Returns bytes; fills `image` (host) and offsets into `net` relative to base 0.
-struct PackedImage {
-    void *host;        // malloc'ed image, caller frees
-    size_t bytes;
-    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_wihT_16, off_whhT_16, off_w2_plain, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
-    int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
-};
 bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedImage *out);
 
 // W [M rows, K columns, leading dimension ld] -> 16x16x32 A-operand fragments
@@ -149,5 +154,13 @@ bool qnet_grad_fits(const NetFrags &net);
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T);
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
                             const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream);
+
+// Device-side parameter update (repack.hip).  build_repack_map (host): for every 16-bit element of the image's
+// fragment part, the parameter it holds; launch_sgd_step: weights -= lr * grad, then the image rebuilt from them.
+bool build_repack_map(const marl_qnet_desc &desc, size_t n_params, std::vector<int32_t> *map, PackedImage *layout);
+bool repack_map_reproduces_packer(const marl_qnet_desc &desc, const float *weights, size_t n_params);
+hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout, int planes, const int32_t *map_dev,
+                           size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
+                           hipStream_t stream);
 
 }  // namespace marl

@@ -111,3 +111,20 @@ def test_mixer_rejects_bad_arguments_before_using_a_device(lib):
     assert lib.marl_mixer_td(None, None, 1, 1, None, None, None, None, None, None, 0.5, None, None, None, None, None) == -1
     assert lib.marl_mixer_set_weights(None, wp, w.size, None) == -1
     lib.marl_mixer_destroy(None)
+
+
+@pytest.mark.parametrize("ci,dtype", [(0, "fp32"), (1, "fp32"), (3, "bf16"), (4, "bf16"), (4, "fp32")])
+def test_refresh_map_reproduces_the_packer_on_the_host(lib, ci, dtype):
+    """The device-side weight refresh rebuilds the image through a map found by probing the packer; applied
+    on the host to random weights (extreme magnitudes included) it must give the packer's own bytes."""
+    cfg = wl.config(ci)
+    N, D, A, H = wl.dims(cfg)
+    w = wl.make_weights(cfg, 3).copy()
+    rng = np.random.default_rng(ci)
+    w[rng.integers(0, w.size, 50)] *= np.float32(1e6)
+    w[rng.integers(0, w.size, 50)] *= np.float32(1e-20)
+    w[rng.integers(0, w.size, 20)] = 0.0
+    d = binding.Desc(N, D, A, H, binding.DTYPES[dtype], 0)
+    assert lib.marl_qnet_check_refresh_map(ctypes.byref(d), w.ctypes.data_as(ctypes.c_void_p), w.size) == 0
+    assert lib.marl_qnet_check_refresh_map(ctypes.byref(d), w.ctypes.data_as(ctypes.c_void_p), w.size - 1) == -4
+    assert lib.marl_qnet_check_refresh_map(None, w.ctypes.data_as(ctypes.c_void_p), w.size) == -1

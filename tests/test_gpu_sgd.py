@@ -1,0 +1,140 @@
+"""GPU: the device-side parameter update.  After marl_qnet_sgd_step a network must behave bit for bit like
+one created from the updated weights (every kernel family, every entry point reads another part of the
+rebuilt image), the update itself is the fp32 expression the header states, and a few learner iterations
+(unroll, TD error, backward pass, update) on a fixed batch bring the TD loss down."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2205_05248_amd import binding, workloads as wl
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    binding.load()
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU in this container")
+
+
+def all_outputs(net, cfg, inp, u, g, kernels):
+    net.set_kernels(kernels)
+    out = {}
+    a = pu.gpu_act(net, cfg, inp)
+    out.update({"act_" + k: v for k, v in a.items()})
+    r = pu.gpu_unroll(net, None, cfg, u)
+    out.update({"unroll_" + k: v for k, v in r.items()})
+    return out
+
+
+@pytest.mark.parametrize("ci,dtype", [(0, "fp32"), (1, "fp32"), (1, "bf16"), (3, "fp32"), (4, "bf16")])
+def test_updated_network_equals_one_created_from_the_updated_weights(ci, dtype):
+    cfg = dict(wl.config(ci), dtype=dtype, T=min(wl.config(ci)["T"], 12), B=min(wl.config(ci)["B"], 6))
+    dims = wl.dims(cfg)
+    w = wl.make_weights(cfg, 0)
+    rng = np.random.default_rng(ci)
+    g = rng.normal(size=w.shape).astype(np.float32)
+    lr = 0.03
+    net = binding.QNet(dims, w, dtype)
+    master = torch.from_numpy(w.copy()).cuda()
+    net.sgd_step(master, torch.from_numpy(g).cuda(), lr)
+    torch.cuda.synchronize()
+    want = w - np.float32(lr) * g                                   # fp32: product rounded, then the difference
+    np.testing.assert_array_equal(master.cpu().numpy(), want)
+    fresh = binding.QNet(dims, want, dtype)
+    inp = wl.make_act_inputs(cfg, E=7)
+    u = wl.make_unroll_inputs(cfg, B=cfg["B"], T=cfg["T"])
+    gq = rng.normal(size=(cfg["B"], cfg["T"], dims[0])).astype(np.float32)
+    families = [binding.KERNELS_TILE32]
+    if dtype == "bf16" or dims[3] == 64:
+        families.append(binding.KERNELS_FUSED16)
+    for kernels in families:
+        got, ref = all_outputs(net, cfg, inp, u, gq, kernels), all_outputs(fresh, cfg, inp, u, gq, kernels)
+        for k in ref:
+            np.testing.assert_array_equal(got[k], ref[k], err_msg=f"{k} (kernels {kernels})")
+    # the backward pass reads the transposed matrices and the plain copy of fc2
+    net.set_kernels(binding.KERNELS_AUTO); fresh.set_kernels(binding.KERNELS_AUTO)
+    d = pu.to_dev(u, ["obs", "actions", "filled"])
+    grads = []
+    for q in (net, fresh):
+        ws = torch.empty(q.grad_workspace_bytes(cfg["B"], cfg["T"]), dtype=torch.uint8, device="cuda")
+        out = torch.empty(w.size, device="cuda")
+        q.grad(d["obs"], d["actions"], d["filled"], torch.from_numpy(gq).cuda(), ws, out)
+        torch.cuda.synchronize()
+        grads.append(out.cpu().numpy())
+    np.testing.assert_array_equal(grads[0], grads[1])
+    # a second update on the same handle (the map is reused), and argument checks
+    net.sgd_step(master, torch.from_numpy(g).cuda(), -lr)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(master.cpu().numpy(), want - np.float32(-lr) * g)
+    import ctypes
+    lib, vp = binding.load(), ctypes.c_void_p
+    assert lib.marl_qnet_sgd_step(vp(net.handle), None, vp(master.data_ptr()), 0.1, None) == -1
+    assert lib.marl_qnet_sgd_step(vp(net.handle), vp(master.data_ptr()), vp(master.data_ptr()), float("nan"), None) == -5
+    assert lib.marl_qnet_sgd_step(None, vp(master.data_ptr()), vp(master.data_ptr()), 0.1, None) == -1
+    net.close(); fresh.close()
+
+
+def test_update_is_ordered_on_the_stream():
+    """A decision step enqueued before the update computes with the old weights, one enqueued after it with
+    the new ones, with no synchronisation in between."""
+    cfg = wl.config(1)
+    dims = wl.dims(cfg)
+    N, D, A, H = dims
+    w = wl.make_weights(cfg, 0)
+    g = np.random.default_rng(2).normal(size=w.shape).astype(np.float32)
+    net, old, new = binding.QNet(dims, w), binding.QNet(dims, w), binding.QNet(dims, w - np.float32(0.5) * g)
+    inp = wl.make_act_inputs(cfg)
+    ref_old, ref_new = pu.gpu_act(old, cfg, inp), pu.gpu_act(new, cfg, inp)
+    d = pu.to_dev(inp, ["obs", "avail", "h_in", "reset", "step_t"])
+    E = inp["obs"].shape[0]
+    master, gd = torch.from_numpy(w.copy()).cuda(), torch.from_numpy(g).cuda()
+    net.sgd_step(master, gd, 0.0)                                   # builds the map (synchronous) ahead of the timed part
+    outs = [(torch.empty(E, N, H, device="cuda"), torch.empty(E, N, dtype=torch.int32, device="cuda"),
+             torch.empty(E, N, A, device="cuda")) for _ in range(2)]
+    torch.cuda.synchronize()
+    net.act_step(d["obs"], d["avail"], d["h_in"], d["reset"], d["step_t"], inp["epsilon"], inp["seed"], *outs[0])
+    net.sgd_step(master, gd, 0.5)
+    net.act_step(d["obs"], d["avail"], d["h_in"], d["reset"], d["step_t"], inp["epsilon"], inp["seed"], *outs[1])
+    torch.cuda.synchronize()
+    for (h, a, q), ref in zip(outs, (ref_old, ref_new)):
+        np.testing.assert_array_equal(q.cpu().numpy(), ref["q"])
+        np.testing.assert_array_equal(h.cpu().numpy(), ref["h_out"])
+        np.testing.assert_array_equal(a.cpu().numpy(), ref["action"])
+    assert np.abs(ref_old["q"] - ref_new["q"]).max() > 1e-3
+    for q in (net, old, new):
+        q.close()
+
+
+def test_learner_iterations_reduce_the_td_loss():
+    """Unroll (online and a frozen target), per-agent TD error, backward pass, update: fifteen iterations on one
+    batch.  The loss must fall, and every step runs in the library's kernels (the TD error in between is
+    three element-wise tensor operations of the test)."""
+    cfg = dict(wl.config(1), B=16, T=20)
+    dims = wl.dims(cfg)
+    N = dims[0]
+    w = wl.make_weights(cfg, 0)
+    online, target = binding.QNet(dims, w), binding.QNet(dims, wl.make_weights(cfg, 1))
+    u = wl.make_unroll_inputs(cfg, B=16, T=20)
+    d = pu.to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
+    B, T = 16, 20
+    q_taken, next_max, y = (torch.empty(B, T, N, device="cuda") for _ in range(3))
+    master = torch.from_numpy(w.copy()).cuda()
+    grad = torch.empty(w.size, device="cuda")
+    ws = torch.empty(online.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    count = float(u["filled"].sum()) * N
+    losses = []
+    for it in range(15):
+        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                         u["gamma"], q_taken, next_max, y)
+        td = y - q_taken                                            # both already carry the filled factor
+        losses.append(float((td * td).sum() / count))
+        online.grad(d["obs"], d["actions"], d["filled"], (-2.0 / count) * td, ws, grad)
+        online.sgd_step(master, grad, 0.05)
+    torch.cuda.synchronize()
+    assert np.isfinite(losses).all()
+    assert losses[-1] < 0.8 * losses[0], losses
+    assert all(b <= a * 1.02 for a, b in zip(losses, losses[1:])), losses
+    online.close(); target.close()
