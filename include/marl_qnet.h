@@ -286,9 +286,9 @@ int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_we
  * The call enqueues a forward pass that keeps the activations, the time-reversed pass and the
  * weight-gradient products on the stream.  Sums run in a fixed order: the same inputs give the
  * same bits.  Arithmetic: bf16 MFMA products with fp32 accumulation; fp32 networks split every
- * operand into two bf16 parts, bf16 networks round the adjoints inside the recurrence to bf16.
+ * operand into two bf16 parts, bf16 networks round the operands of every product (adjoints, activations) to bf16.
  * Only networks that run on the fused16 kernels are served (see marl_qnet_set_kernels), with
- * D + N <= 384: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^30, or a
+ * D + N <= 336: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^30, or a
  * workspace that is too small; MARL_ERR_BAD_ARG for a misaligned workspace.
  */
 int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, size_t *bytes);

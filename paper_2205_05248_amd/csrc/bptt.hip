@@ -13,16 +13,17 @@
 //                                      each), W_ih in LDS.  The adjoints go to global memory.
 //   tn_gemm_kernel                     the weight gradients are sums over all (row, slot) samples of outer
 //                                      products adjoint x activation: C[p][q] = sum_m A[m][p] B[m][q], four
-//                                      times (W_ih, W_hh, W1, W2).  The samples are split into chunks over
-//                                      the grid, a workgroup stages 32 samples at a time through LDS (the
-//                                      contraction index has to become the fragments' k), and writes its
-//                                      partial sum; extra columns of B made up on the fly (a column of ones,
-//                                      or the one-hot agent id) yield the bias gradients in the same product.
+//                                      times (W_ih, W_hh, W1, W2).  The samples are split into chunks, one
+//                                      workgroup each, which computes the whole (small) result for its chunk:
+//                                      it stages 32 samples at a time through LDS (the contraction index has
+//                                      to become the fragments' k), every element read from memory once, and
+//                                      writes its partial sum; extra columns of B made up on the fly (a column
+//                                      of ones, or the one-hot agent id) yield the bias gradients in the same
+//                                      product.
 //   tn_reduce_kernel                   adds the chunks' partial sums in a fixed order and writes the result
 //                                      into the packed gradient vector.
-// The precision follows the network's: fp32 networks split every operand into two bf16 planes (three MFMAs per
-// product), bf16 networks round the adjoints that enter the recurrent products to bf16; the weight-gradient
-// products always use the split.
+// The precision follows the network's, in every product of the pass: fp32 networks split every operand into two
+// bf16 planes (three MFMAs per product), bf16 networks round the operands (adjoints, activations) to bf16.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -279,151 +280,153 @@ struct TnGemmArgs {
     int n_extra, N;
     int qp;             // Q + n_extra rounded up to 16: row pitch of the result
     int chunk;          // samples per workgroup along the contraction, a multiple of 32
-    float *partial;     // [chunks][P rounded up to 64][qp]
+    float *partial;     // [chunks][128 or 384 rows][qp]
 };
 
-constexpr int kTnMaxQBlocks = 24;      // at most 384 columns of B
+constexpr int kTnThreads = 512;        // eight waves: two per SIMD
 
-// QPW: column blocks of the result per wave (4 QPW blocks of 16 columns per workgroup).
-template <int QPW>
-__global__ __launch_bounds__(256, QPW > 3 ? 1 : 2) void tn_gemm_kernel(TnGemmArgs g)
+// One workgroup per chunk of samples computes the whole result, so that every operand element is read from
+// memory once.  Wave w owns result row blocks w, w + 8, .. (PBW of them) and all QBN column blocks.  P: bf16
+// planes per operand, the network's own: 2 = every value as bf16 high part + bf16 of the remainder, three MFMAs
+// per product; 1 = values rounded to bf16, one MFMA.
+template <int PBW, int QBN, int P>
+__global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(TnGemmArgs g)
 {
-    constexpr int kTnQPerWave = QPW;
-    // LDS: two buffers (even and odd steps) of two planes (bf16 high part, bf16 of the remainder), each plane
-    // column-major: column c of the staged 32 samples is 64 bytes, the lane's eight samples of a fragment 16.
-    // Columns 0..63 are the workgroup's columns of A, then B's.
-    extern __shared__ __attribute__((aligned(16))) char stage[];
+    constexpr int kPp = 16 * 8 * PBW;                              // result rows, padded = columns of A staged
+    constexpr int kSets = (kPp + 16 * QBN + 63) / 64;              // sets of 64 staged columns (A's, then B's)
+    constexpr int kSetsPerWave = (kSets + 1) / 2;
+    constexpr bool kTwoBuffers = P == 1;                           // a second staging buffer where it fits
     constexpr int kPitch = 80;                                     // bytes per column: 64 + 16 against bank conflicts
-    const int plane_bytes = (64 + g.qp) * kPitch;
+    // LDS: P planes (bf16 high part, bf16 of the remainder), each column-major: column c of the staged 32
+    // samples is 64 bytes, the lane's eight samples of a fragment 16.
+    extern __shared__ __attribute__((aligned(16))) char stage[];
+    const int cols = kPp + g.qp;
+    const int plane_bytes = cols * kPitch;
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int p0 = blockIdx.x * 64;
+    const int sg = w & 3, half = w >> 2;                           // the wave stages samples 8 sg + 0..7 of every other column set
     const int n_qb = g.qp / 16;
-    const int m_begin = (int)blockIdx.y * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
+    const int m_begin = (int)blockIdx.x * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
 
-    f32x4 acc[4][kTnQPerWave];
+    f32x4 acc[PBW][QBN];
 #pragma unroll
-    for (int pb = 0; pb < 4; ++pb)
+    for (int k = 0; k < PBW; ++k)
 #pragma unroll
-        for (int j = 0; j < kTnQPerWave; ++j)
+        for (int j = 0; j < QBN; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[pb][j][r] = 0.0f;
+            for (int r = 0; r < 4; ++r) acc[k][j][r] = 0.0f;
 
     // Inputs are asked for kDepth steps before they are used, into kDepth register sets that the unrolled
     // loop addresses statically.  Every load is unconditional (addresses clamped into the arrays, the value
     // replaced afterwards where it does not count), so the loop is straight-line code and each wait covers
     // exactly the set it needs.
     constexpr int kDepth = 2;
-    float ra[kDepth][8], rb[kDepth][8][kTnQPerWave], rm[kDepth][8][kTnQPerWave];
-    const int a_col = p0 + lane < g.P ? p0 + lane : 0;
-    auto fetch = [&](float (&fa)[8], float (&fb)[8][kTnQPerWave], float (&fm)[8][kTnQPerWave], int m0) {      // this wave's eight rows of 32 samples
+    float rv[kDepth][kSetsPerWave][8];
+    // per column set of this wave: which operand, and the lane's (clamped) column in it
+    bool set_is_a[kSetsPerWave];
+    int set_col[kSetsPerWave];
+#pragma unroll
+    for (int i = 0; i < kSetsPerWave; ++i) {
+        const int col = lane + 64 * (2 * i + half);
+        set_is_a[i] = 64 * (2 * i + half) < kPp;                   // kPp is a multiple of 64: a set never straddles
+        set_col[i] = set_is_a[i] ? (col < g.P ? col : 0) : (col - kPp < g.Q ? col - kPp : 0);
+    }
+    auto fetch = [&](float (&f)[kSetsPerWave][8], int m0) {         // this wave's eight rows of 32 samples
         // (group, row in group) of the wave's first row by division, of the following rows by stepping
-        const unsigned first = (unsigned)min(m0 + 8 * w, g.M - 1);
+        const unsigned first = (unsigned)min(m0 + 8 * sg, g.M - 1);
         unsigned ga = first / (unsigned)g.a.rows_per_group, ia = first % (unsigned)g.a.rows_per_group;
         unsigned gb = first / (unsigned)g.b.rows_per_group, ib = first % (unsigned)g.b.rows_per_group;
-        unsigned agent = first % (unsigned)g.N;
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
-            const int m = m0 + 8 * w + r;
-            const bool live = m < m_end;
+            const int m = m0 + 8 * sg + r;
             const float *arow = g.a.base + (long)ga * g.a.group_stride + (long)ia * g.a.ld;
             const float *brow = g.b.base + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
-            fa[r] = arow[a_col];                  // raw: what does not count is replaced in `deposit`
 #pragma unroll
-            for (int i = 0; i < kTnQPerWave; ++i) {
-                const int col = lane + 64 * i;
-                float made = 0.0f;                // the appended columns, or zero for padding and rows past the end
-                if (live && col >= g.Q && col < g.Q + g.n_extra)
-                    made = g.extra_mode == kExtraOnes ? 1.0f : (col - g.Q == (int)agent ? 1.0f : 0.0f);
-                fb[r][i] = brow[col < g.Q ? col : 0];
-                fm[r][i] = made;
-            }
+            for (int i = 0; i < kSetsPerWave; ++i) f[i][r] = (set_is_a[i] ? arow : brow)[set_col[i]];      // raw
             // the next row, without a branch (a branch between two loads would make every wait a full one);
             // past the end the last row is kept (and not used)
             const unsigned go = m + 1 < g.M ? 1u : 0u;
-            ia += go; ib += go; agent += go;
+            ia += go; ib += go;
             const unsigned wa = ia == (unsigned)g.a.rows_per_group ? 1u : 0u, wb = ib == (unsigned)g.b.rows_per_group ? 1u : 0u;
             ga += wa; ia = wa ? 0u : ia;
             gb += wb; ib = wb ? 0u : ib;
-            agent = agent == (unsigned)g.N ? 0u : agent;
         }
     };
-    // The wave's eight samples of a column are samples 8 w + 0..7 of the step: as bf16 they are exactly the 16
-    // bytes that lane quarter w of a fragment of that column reads.  Converted once here, not by every reader.
+    // The wave's eight samples of a column are samples 8 sg + 0..7 of the step: as bf16 they are exactly the 16
+    // bytes that lane quarter sg of a fragment of that column reads.  Converted once here, not by every reader.
     // A loaded value is first passed through an empty asm: that is where the wait for it goes, and it keeps the
     // compiler from turning "loaded value or zero" into a branch around the load.
-    auto deposit = [&](char *buf, float (&fa)[8], float (&fb)[8][kTnQPerWave], const float (&fm)[8][kTnQPerWave], int m0) {
-        auto put = [&](int col, const float (&v)[8]) {
-            const Frag<2> f = to_frag<2>(v);
-            *reinterpret_cast<bf16x8 *>(buf + col * kPitch + 16 * w) = f.hi;
-            *reinterpret_cast<bf16x8 *>(buf + plane_bytes + col * kPitch + 16 * w) = f.lo;
-        };
-        float va[8];
+    unsigned agent0 = (unsigned)(m_begin + 8 * sg) % (unsigned)g.N;       // agent of the wave's first row of the step
+    const unsigned agent_step = 32u % (unsigned)g.N;
+    auto deposit = [&](char *buf, float (&f)[kSetsPerWave][8], int m0) {
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            asm volatile("" : "+v"(fa[r]));
-            va[r] = (m0 + 8 * w + r < m_end && p0 + lane < g.P) ? fa[r] : 0.0f;
-        }
-        put(lane, va);
+        for (int i = 0; i < kSetsPerWave; ++i) {
+            const int col = lane + 64 * (2 * i + half);
+            float v[8];
+            unsigned agent = agent0;
 #pragma unroll
-        for (int i = 0; i < kTnQPerWave; ++i)
-            if (lane + 64 * i < g.qp) {
-                float v[8];
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    asm volatile("" : "+v"(fb[r][i]));
-                    v[r] = (m0 + 8 * w + r < m_end && lane + 64 * i < g.Q) ? fb[r][i] : fm[r][i];
-                }
-                put(64 + lane + 64 * i, v);
+            for (int r = 0; r < 8; ++r) {
+                asm volatile("" : "+v"(f[i][r]));
+                const bool live = m0 + 8 * sg + r < m_end;
+                const int cb = col - kPp;                          // column of B (with its appended columns)
+                float made = 0.0f;
+                if (cb >= g.Q && cb < g.Q + g.n_extra) made = g.extra_mode == kExtraOnes ? 1.0f : (cb - g.Q == (int)agent ? 1.0f : 0.0f);
+                const bool real = set_is_a[i] ? col < g.P : cb < g.Q;
+                v[r] = live ? (real ? f[i][r] : (set_is_a[i] ? 0.0f : made)) : 0.0f;
+                agent = agent + 1 == (unsigned)g.N ? 0u : agent + 1;
             }
+            if (col < cols) {
+                const Frag<P> fr = to_frag<P>(v);
+                *reinterpret_cast<bf16x8 *>(buf + col * kPitch + 16 * sg) = fr.hi;
+                if constexpr (P == 2) *reinterpret_cast<bf16x8 *>(buf + plane_bytes + col * kPitch + 16 * sg) = fr.lo;
+            }
+        }
+        agent0 += agent_step;
+        agent0 = agent0 >= (unsigned)g.N ? agent0 - (unsigned)g.N : agent0;
     };
 
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) fetch(ra[d], rb[d], rm[d], m_begin + 32 * d);
+    for (int d = 0; d < kDepth; ++d) fetch(rv[d], m_begin + 32 * d);
     // Rounds of kDepth steps; steps past the end of the chunk add zeros.
     for (int m0 = m_begin; m0 < m_end; m0 += 32 * kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
-            // One barrier per step: the buffer written now was last read two steps ago, and every wave has
-            // passed the previous step's barrier since.
-            char *buf = stage + (d & 1) * 2 * plane_bytes;
-            deposit(buf, ra[d], rb[d], rm[d], m0 + 32 * d);
+            // Two buffers: one barrier per step (the buffer written now was last read two steps ago, and every
+            // wave has passed the previous step's barrier since).  One buffer: a barrier before writing too.
+            char *buf = stage + (kTwoBuffers ? (d & 1) * P * plane_bytes : 0);
+            if constexpr (!kTwoBuffers) __syncthreads();
+            deposit(buf, rv[d], m0 + 32 * d);
             __syncthreads();
-            fetch(ra[d], rb[d], rm[d], m0 + 32 * (d + kDepth));
+            fetch(rv[d], m0 + 32 * (d + kDepth));
             // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
             const char *mine = buf + c * kPitch + 16 * q4;
-            WFrag<2> af[4];
+            WFrag<P> af[PBW];
 #pragma unroll
-            for (int pb = 0; pb < 4; ++pb) {
-                af[pb].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * pb * kPitch);
-                af[pb].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * pb * kPitch);
+            for (int k = 0; k < PBW; ++k) {
+                af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
+                if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
             }
 #pragma unroll
-            for (int j = 0; j < kTnQPerWave; ++j) {
-                const int qb = w + 4 * j;
-                if (qb < n_qb) {
-                    Frag<2> bf;
-                    bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (64 + 16 * qb) * kPitch);
-                    bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (64 + 16 * qb) * kPitch);
+            for (int j = 0; j < QBN; ++j)
+                if (j < n_qb) {
+                    Frag<P> bf;
+                    bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (kPp + 16 * j) * kPitch);
+                    if constexpr (P == 2) bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (kPp + 16 * j) * kPitch);
 #pragma unroll
-                    for (int pb = 0; pb < 4; ++pb) mma16<2>(acc[pb][j], af[pb], bf);
+                    for (int k = 0; k < PBW; ++k) mma16<P>(acc[k][j], af[k], bf);
                 }
-            }
         }
     }
 
-    // C layout: lane (c, q4) holds result[p0 + 16 pb + 4 q4 + r][16 qb + c]
-    const int p_pad = (g.P + 63) / 64 * 64;
-    float *out = g.partial + (size_t)blockIdx.y * p_pad * g.qp;
+    // C layout: lane (c, q4) holds result[16 block + 4 q4 + r][16 j + c]
+    float *out = g.partial + (size_t)blockIdx.x * kPp * g.qp;
 #pragma unroll
-    for (int pb = 0; pb < 4; ++pb)
+    for (int k = 0; k < PBW; ++k)
 #pragma unroll
-        for (int j = 0; j < kTnQPerWave; ++j) {
-            const int qb = w + 4 * j;
-            if (qb < n_qb)
+        for (int j = 0; j < QBN; ++j)
+            if (j < n_qb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) out[(size_t)(p0 + 16 * pb + 4 * q4 + r) * g.qp + 16 * qb + c] = acc[pb][j][r];
-        }
+                for (int r = 0; r < 4; ++r) out[(size_t)(16 * (w + 8 * k) + 4 * q4 + r) * g.qp + 16 * j + c] = acc[k][j][r];
 }
 
 // Sum of the chunks, in a fixed order, into the packed gradient vector.  Result row p goes to row
@@ -499,7 +502,7 @@ Plan make_plan(const NetFrags &net, int B, int T)
     p.off_dpre1 = off;  off = align_up(off + R * T * H * 4);
     p.off_dq = off;     off = align_up(off + R * T * p.a16 * 4);
     // the largest of the four products' partial results
-    auto part = [&](size_t P, size_t Qt) { return (size_t)p.chunks * ((P + 63) / 64 * 64) * ((Qt + 15) / 16 * 16) * 4; };
+    auto part = [&](size_t P, size_t Qt) { return (size_t)p.chunks * (P > 128 ? 384 : 128) * ((Qt + 15) / 16 * 16) * 4; };
     size_t need = part(3 * H, H + 1);
     need = std::max(need, part(H, (size_t)net.D + net.N));
     need = std::max(need, part(p.a16, H + 1));
@@ -508,7 +511,7 @@ Plan make_plan(const NetFrags &net, int B, int T)
     return p;
 }
 
-hipError_t run_product(const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra, int N,
+hipError_t run_product(int planes, const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra, int N,
                        const Plan &plan, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
                        hipStream_t stream)
 {
@@ -517,23 +520,25 @@ hipError_t run_product(const RowMap &a, const RowMap &b, long M, int P, int Q, i
     g.qp = (Q + n_extra + 15) / 16 * 16;
     g.chunk = plan.chunk;
     g.partial = partial;
-    if (g.qp > 16 * kTnMaxQBlocks) return hipErrorInvalidValue;
-    const int p_tiles = (P + 63) / 64, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
-    const size_t lds = (size_t)4 * (64 + g.qp) * 80;            // two buffers of two planes, 80 bytes per column
-    hipError_t err;
-    if (g.qp <= 16 * 4 * 3) {
-        err = allow_large_lds<tn_gemm_kernel<3>>(kLdsLimit);
-        if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(tn_gemm_kernel<3>, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
-    } else {
-        err = allow_large_lds<tn_gemm_kernel<6>>(kLdsLimit);
-        if (err != hipSuccess) return err;
-        hipLaunchKernelGGL(tn_gemm_kernel<6>, dim3(p_tiles, chunks), dim3(256), lds, stream, g);
-    }
+    // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
+    const bool wide_rows = P > 128;
+    if ((wide_rows && (P > 384 || g.qp > 144)) || (!wide_rows && g.qp > 336)) return hipErrorInvalidValue;
+    const int p_pad = wide_rows ? 384 : 128, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
+    const size_t lds = (size_t)(planes == 1 ? 2 : 1) * planes * (p_pad + g.qp) * 80;     // 80 bytes per staged column and plane
+    hipError_t err = hipErrorInvalidValue;
+#define MARL_TN(PBW, QBN, PL)                                                                            \
+    do {                                                                                                 \
+        err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL>>(kLdsLimit);                                  \
+        if (err != hipSuccess) return err;                                                               \
+        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL>), dim3(chunks), dim3(kTnThreads), lds, stream, g); \
+    } while (0)
+    if (wide_rows) { if (planes == 2) MARL_TN(3, 9, 2); else MARL_TN(3, 9, 1); }
+    else           { if (planes == 2) MARL_TN(1, 21, 2); else MARL_TN(1, 21, 1); }
+#undef MARL_TN
     err = hipGetLastError();
     if (err != hipSuccess) return err;
     TnReduceArgs r{};
-    r.partial = partial; r.chunks = chunks; r.P = P; r.p_pad = p_tiles * 64; r.qp = g.qp;
+    r.partial = partial; r.chunks = chunks; r.P = P; r.p_pad = p_pad; r.qp = g.qp;
     r.Q = Q; r.n_extra = n_extra; r.extra_mode = extra_mode;
     r.row_shift = row_shift; r.w_cols = Q; r.ld_w = ld_w; r.dst_w = dst_w; r.dst_b = dst_b;
     const int total = P * (Q + n_extra);
@@ -559,7 +564,7 @@ hipError_t back_dispatch(const BpttArgs &a, hipStream_t stream)
 
 bool qnet_grad_fits(const NetFrags &net)
 {
-    return unroll_fused_fits(net) && net.D + net.N <= 16 * kTnMaxQBlocks && net.H + 1 <= 16 * kTnMaxQBlocks;
+    return unroll_fused_fits(net) && net.D + net.N <= 336;        // the widest product the gradient kernel stages
 }
 
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T) { return make_plan(net, B, T).bytes; }
@@ -604,13 +609,13 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     const RowMap obs_rows{obs, (long)S * N * D, TN, D};
     const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16};
     // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
-    err = run_product(da_i, x_rows, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 2 * H, gWih, H, gbih, stream);
+    err = run_product(net.planes, da_i, x_rows, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 2 * H, gWih, H, gbih, stream);
     if (err != hipSuccess) return err;
-    err = run_product(da_h, h_prev, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 0, gWhh, H, gbhh, stream);
+    err = run_product(net.planes, da_h, h_prev, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 0, gWhh, H, gbhh, stream);
     if (err != hipSuccess) return err;
-    err = run_product(pre_rows, obs_rows, M, H, D, kExtraAgent, N, N, plan, partial, 0, gW1, D + N, gb1, stream);
+    err = run_product(net.planes, pre_rows, obs_rows, M, H, D, kExtraAgent, N, N, plan, partial, 0, gW1, D + N, gb1, stream);
     if (err != hipSuccess) return err;
-    return run_product(dq_rows, h_new, M, A, H, kExtraOnes, 1, N, plan, partial, 0, gW2, H, gb2, stream);
+    return run_product(net.planes, dq_rows, h_new, M, A, H, kExtraOnes, 1, N, plan, partial, 0, gW2, H, gb2, stream);
 }
 
 }  // namespace marl
