@@ -52,12 +52,38 @@ template <int H, int P> struct BpttShape {
     static constexpr int oDa = Sh::oObs, oDhn = oDa + 3 * KS * Sh::kFrag, kBytes = oDhn + KS * Sh::kFrag;
 };
 
-template <int H, int P>
-__global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
+// The wave's blocks of 16 units as operand fragments in LDS: two adjacent blocks make one k-step.  A wave with
+// two blocks writes a whole fragment, a wave with one block its half of every lane's 16 bytes.
+template <int P, int NBC>
+__device__ __forceinline__ void publish_blocks(bf16x8 (*dst)[P][64], int w, int lane, const f32x4 (&v)[NBC])
+{
+    if constexpr (NBC == 2) {
+        const Frag<P> f = frag_of_pair<P>(v[0], v[1]);
+        dst[w][0][lane] = f.hi;
+        if constexpr (P == 2) dst[w][1][lane] = f.lo;
+    } else {
+        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+        bf16x4 hi, lo;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            hi[r] = (__bf16)v[0][r];
+            lo[r] = (__bf16)(v[0][r] - (float)hi[r]);
+        }
+        char *at = reinterpret_cast<char *>(&dst[w / 2][0][lane]) + (w & 1) * 8;
+        *reinterpret_cast<bf16x4 *>(at) = hi;
+        if constexpr (P == 2) *reinterpret_cast<bf16x4 *>(at + 1024) = lo;
+    }
+}
+
+// NW waves share the H / 16 blocks of hidden units: four waves (one per SIMD, up to 512 registers) or eight
+// (two per SIMD, one block each, so that one wave's waits are another's work).
+template <int H, int P, int NW>
+__global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
 {
     using Sh = Fused16<H, P>;
     using Bs = BpttShape<H, P>;
-    constexpr int KS = Sh::KS, FBK = Sh::FBK, NBC = Sh::NBC;
+    constexpr int KS = Sh::KS, FBK = Sh::FBK, NBC = FBK / NW;
+    static_assert(NBC == 1 || NBC == 2, "one or two blocks of hidden units per wave");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     typedef bf16x8 (*FragBuf)[P][64];
     const FragBuf hf = reinterpret_cast<FragBuf>(lds + Sh::oH), xf = reinterpret_cast<FragBuf>(lds + Sh::oX);
@@ -76,7 +102,7 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
 
     {
         constexpr int kVecs = 3 * FBK * KS * P * 64;
-        for (int i = threadIdx.x; i < kVecs; i += 256) wih_lds[i] = net.wih_16[i];
+        for (int i = threadIdx.x; i < kVecs; i += 64 * NW) wih_lds[i] = net.wih_16[i];
     }
     if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
 
@@ -159,8 +185,8 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
         u_ahead = load_action(max(t - 2, 0));
         nxt = fetch(max(t - 1, 0), u_next);
         const float gq = (valid && in.fil) ? in.gq_raw : 0.0f;
-        GruWave<H, P>::publish(hf, w, lane, in.hp);
-        GruWave<H, P>::publish(xf, w, lane, in.xv);
+        publish_blocks<P, NBC>(hf, w, lane, in.hp);
+        publish_blocks<P, NBC>(xf, w, lane, in.xv);
         lds_barrier();
 
         // the gates of slot t again
@@ -222,10 +248,10 @@ __global__ __launch_bounds__(256, 1) void bptt_back_kernel(BpttArgs a)
             for (int r = 0; r < 4; ++r) v[r] = (16 * w + 4 * q4 + r == in.u) ? gq : 0.0f;
             __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dq_buf, ((m * a.a16 + 16 * w + 4 * q4) * 4u) | drop_dq, 0, 0);
         }
-        GruWave<H, P>::publish(daf + 0 * KS, w, lane, dar);
-        GruWave<H, P>::publish(daf + 1 * KS, w, lane, daz);
-        GruWave<H, P>::publish(daf + 2 * KS, w, lane, dan);
-        GruWave<H, P>::publish(dhf, w, lane, dahn);
+        publish_blocks<P, NBC>(daf + 0 * KS, w, lane, dar);
+        publish_blocks<P, NBC>(daf + 1 * KS, w, lane, daz);
+        publish_blocks<P, NBC>(daf + 2 * KS, w, lane, dan);
+        publish_blocks<P, NBC>(dhf, w, lane, dahn);
         lds_barrier();
 
         // back through the two products: dL/dh_{t-1} and dL/dx_t for this wave's units
@@ -549,14 +575,14 @@ hipError_t run_product(int planes, const RowMap &a, const RowMap &b, long M, int
     return hipGetLastError();
 }
 
-template <int H, int P>
+template <int H, int P, int NW>
 hipError_t back_dispatch(const BpttArgs &a, hipStream_t stream)
 {
     const int tiles = (a.B * a.net.N + 15) / 16;
-    hipError_t err = allow_large_lds<bptt_back_kernel<H, P>>(kLdsLimit);
+    hipError_t err = allow_large_lds<bptt_back_kernel<H, P, NW>>(kLdsLimit);
     if (err != hipSuccess) return err;
     constexpr size_t kLds = BpttShape<H, P>::kBytes;
-    hipLaunchKernelGGL((bptt_back_kernel<H, P>), dim3(tiles), dim3(256), kLds, stream, a);
+    hipLaunchKernelGGL((bptt_back_kernel<H, P, NW>), dim3(tiles), dim3(64 * NW), kLds, stream, a);
     return hipGetLastError();
 }
 
@@ -588,9 +614,9 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     BpttArgs a{};
     a.net = net; a.B = B; a.T = T; a.a16 = plan.a16; a.actions = actions; a.filled = filled; a.grad_q = grad_q;
     a.h_all = h_all; a.x_all = x_all; a.da = da; a.dpre1 = dpre1; a.dq = dq;
-    if (H == 64 && net.planes == 2) err = back_dispatch<64, 2>(a, stream);
-    else if (H == 64 && net.planes == 1) err = back_dispatch<64, 1>(a, stream);
-    else if (H == 128 && net.planes == 1) err = back_dispatch<128, 1>(a, stream);
+    if (H == 64 && net.planes == 2) err = back_dispatch<64, 2, 4>(a, stream);
+    else if (H == 64 && net.planes == 1) err = back_dispatch<64, 1, 4>(a, stream);
+    else if (H == 128 && net.planes == 1) err = back_dispatch<128, 1, 8>(a, stream);
     else err = hipErrorInvalidValue;
     if (err != hipSuccess) return err;
 
