@@ -134,3 +134,66 @@ void mixer_td(int N, int M, int S, const float *w_online, const float *w_target,
             loss[1] += filled[i] ? 1.0 : 0.0;
         }
 }
+
+/*
+ * Backward pass of the mixing network (Alg. 3: "calculate the gradient"): with an upstream array
+ * e[i] = dL/dQ_total[i] handed in by the caller (for the masked mean-squared TD loss: -2 td_err / count),
+ *     grad_w[p]    = sum_i e[i] * d Q_total[i] / d w[p]        for every packed parameter p
+ *     grad_q[i][n] = e[i] * d Q_total[i] / d q[i][n]           (what flows on into the agents' networks)
+ * for the R = B T transitions i = (b, t) with values q [B, T, N] and state[b, t] of state [B, T+1, S].
+ * Reverse mode of the definition above, written out per transition; d|x|/dx = sign(x) (0 at 0),
+ * elu'(x) = 1 for x > 0, exp(x) otherwise, relu'(x) = [x > 0].
+ */
+void mixer_grad(int N, int M, int S, const float *w, int B, int T, const float *state, const double *q,
+                const double *e, double *grad_q, double *grad_w)
+{
+    mixer_t mx;
+    mixer_bind(&mx, N, M, S, w);
+    const long count = mixer_param_count(N, M, S);
+    for (long p = 0; p < count; ++p) grad_w[p] = 0.0;
+    /* the same binding on the gradient vector */
+    double *gHw1 = grad_w, *ghb1 = gHw1 + (long)N * M * S, *gHb1 = ghb1 + (long)N * M, *ghbb1 = gHb1 + (long)M * S;
+    double *gHw2 = ghbb1 + M, *ghb2 = gHw2 + (long)M * S, *gV1 = ghb2 + M, *gc1 = gV1 + (long)M * S;
+    double *gv2 = gc1 + M, *gc2 = gv2 + M;
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t) {
+            const long i = (long)b * T + t;
+            const float *s = state + ((long)b * (T + 1) + t) * S;
+            const double *qi = q + i * N;
+            const double ei = e[i];
+            for (int m = 0; m < M; ++m) {
+                /* forward for hidden unit m */
+                double pre = dot_state(mx.Hb1 + (long)m * S, s, S) + (double)mx.hbb1[m];
+                for (int n = 0; n < N; ++n) {
+                    const long f = (long)n * M + m;
+                    pre += qi[n] * fabs(dot_state(mx.Hw1 + f * S, s, S) + (double)mx.hb1[f]);
+                }
+                const double hid = pre > 0.0 ? pre : exp(pre) - 1.0;
+                const double gen2 = dot_state(mx.Hw2 + (long)m * S, s, S) + (double)mx.hb2[m];
+                const double a = dot_state(mx.V1 + (long)m * S, s, S) + (double)mx.c1[m];
+                /* backward */
+                const double d_gen2 = ei * hid * (gen2 > 0.0 ? 1.0 : gen2 < 0.0 ? -1.0 : 0.0);
+                const double d_pre = ei * fabs(gen2) * (pre > 0.0 ? 1.0 : exp(pre));
+                const double d_a = ei * (double)mx.v2[m] * (a > 0.0 ? 1.0 : 0.0);
+                gv2[m] += ei * (a > 0.0 ? a : 0.0);
+                ghb2[m] += d_gen2;
+                ghbb1[m] += d_pre;
+                gc1[m] += d_a;
+                for (int k = 0; k < S; ++k) {
+                    gHw2[(long)m * S + k] += d_gen2 * (double)s[k];
+                    gHb1[(long)m * S + k] += d_pre * (double)s[k];
+                    gV1[(long)m * S + k] += d_a * (double)s[k];
+                }
+                for (int n = 0; n < N; ++n) {
+                    const long f = (long)n * M + m;
+                    const double gen1 = dot_state(mx.Hw1 + f * S, s, S) + (double)mx.hb1[f];
+                    const double d_gen1 = d_pre * qi[n] * (gen1 > 0.0 ? 1.0 : gen1 < 0.0 ? -1.0 : 0.0);
+                    ghb1[f] += d_gen1;
+                    for (int k = 0; k < S; ++k) gHw1[f * S + k] += d_gen1 * (double)s[k];
+                    if (m == 0) grad_q[i * N + n] = 0.0;
+                    grad_q[i * N + n] += d_pre * fabs(gen1);
+                }
+            }
+            gc2[0] += ei;
+        }
+}

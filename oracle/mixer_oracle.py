@@ -77,3 +77,19 @@ def td(dims, w_online, w_target, state, q_taken, next_max, reward, terminated, f
                      _p(terminated), _p(filled), ctypes.c_float(float(np.float32(gamma))),
                      _p(out["q_total"]), _p(out["y_total"]), _p(out["td_err"]), _p(out["loss"]))
     return out
+
+
+def grad(dims, w, state, q, e):
+    """Backward pass: returns (grad_q [B,T,N], grad_w [param count]) for upstream e [B,T] = dL/dQ_total."""
+    N, M, S = (int(v) for v in dims)
+    w = _c(w, np.float32)
+    assert w.size == param_count(N, M, S)
+    state = _c(state, np.float32)
+    B, T = state.shape[0], state.shape[1] - 1
+    assert state.shape == (B, T + 1, S)
+    q = _c(q, np.float64); assert q.shape == (B, T, N)
+    e = _c(e, np.float64); assert e.shape == (B, T)
+    grad_q = np.zeros((B, T, N))
+    grad_w = np.zeros(w.size)
+    _load().mixer_grad(N, M, S, _p(w), B, T, _p(state), _p(q), _p(e), _p(grad_q), _p(grad_w))
+    return grad_q, grad_w

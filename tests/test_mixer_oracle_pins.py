@@ -150,3 +150,75 @@ def test_td_targets_by_hand():
     assert abs(out["y_total"][0, 0] - (1.0 + 0.5 * (-2.0 + 2.0 + 2.0))) < 1e-6   # next slot's state 0.2
     same = mxo.td(dims, w_on, None, state, q_taken, next_max, reward, terminated, filled, gamma)
     np.testing.assert_allclose(same["y_total"], reward + gamma * (1 - terminated) * (1.0 + next_max.sum(-1)), atol=1e-6)
+
+
+# ---------------------------------------------------------------- backward pass
+def _library_grads(dims, w, state, q, e):
+    """sum(e * Q_total) differentiated by a tensor library; the forward is written with its ops."""
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    N, M, S = dims
+    B, T = q.shape[:2]
+    wt = torch.tensor(np.asarray(w, np.float64), requires_grad=True)
+    t = {k: wt[a:b].reshape(shp) for k, (a, b, shp) in wl.mixer_slices(*dims).items()}
+    ts = torch.from_numpy(state[:, :T].astype(np.float64)).reshape(B * T, S)
+    tq = torch.tensor(q.reshape(B * T, N), requires_grad=True)
+    R = B * T
+    W1 = torch.abs(F.linear(ts, t["Hw1"], t["hb1"])).view(R, N, M)
+    hid = F.elu(torch.bmm(tq.view(R, 1, N), W1).view(R, M) + F.linear(ts, t["Hb1"], t["hbb1"]))
+    w2 = torch.abs(F.linear(ts, t["Hw2"], t["hb2"]))
+    v = F.relu(F.linear(ts, t["V1"], t["c1"])) @ t["v2"] + t["c2"]
+    total = (((hid * w2).sum(-1) + v) * torch.from_numpy(e.reshape(R))).sum()
+    total.backward()
+    return tq.grad.numpy().reshape(B, T, N), wt.grad.numpy()
+
+
+@pytest.mark.parametrize("ci", [0, 1, 3])
+def test_gradient_against_library_autodiff(ci):
+    cfg = wl.config(ci)
+    dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    m = wl.make_mixer_inputs(cfg, B=3, T=7)
+    e = np.random.default_rng(ci).normal(size=(3, 7))
+    q = m["q_taken"].astype(np.float64)
+    got_q, got_w = mxo.grad(dims, w, m["state"], q, e)
+    want_q, want_w = _library_grads(dims, w, m["state"], q, e)
+    np.testing.assert_allclose(got_q, want_q, rtol=0, atol=1e-11 * max(1.0, np.abs(want_q).max()))
+    np.testing.assert_allclose(got_w, want_w, rtol=0, atol=1e-11 * max(1.0, np.abs(want_w).max()))
+    for name, (a, b, _) in wl.mixer_slices(*dims).items():          # every tensor receives a gradient
+        assert np.abs(want_w[a:b]).max() > 0, name
+
+
+def test_gradient_against_finite_differences_and_closed_forms():
+    cfg = wl.config(0)
+    N, M, S = dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    m = wl.make_mixer_inputs(cfg, B=2, T=4)
+    q = m["q_taken"].astype(np.float64)
+    e = np.random.default_rng(3).normal(size=(2, 4))
+    got_q, got_w = mxo.grad(dims, w, m["state"], q, e)
+    flat_state = m["state"][:, :4].reshape(8, S)
+
+    def objective(wv, qv):
+        return float((mxo.forward(dims, wv, qv.reshape(8, N), flat_state) * e.reshape(8)).sum())
+
+    rng = np.random.default_rng(0)
+    for name, (a, b, _) in wl.mixer_slices(*dims).items():
+        for p in rng.choice(np.arange(a, b), size=min(3, b - a), replace=False):
+            lo, hi = np.array(w), np.array(w)
+            lo[p] = np.float32(w[p] - 1e-3); hi[p] = np.float32(w[p] + 1e-3)
+            slope = (objective(hi, q) - objective(lo, q)) / (float(hi[p]) - float(lo[p]))
+            assert abs(slope - got_w[p]) <= 2e-4 * max(1.0, abs(got_w[p])), (name, p, slope, got_w[p])
+    for idx in [(0, 0, 0), (1, 3, N - 1)]:
+        lo, hi = q.copy(), q.copy()
+        lo[idx] -= 1e-5; hi[idx] += 1e-5
+        slope = (objective(w, hi) - objective(w, lo)) / 2e-5
+        assert abs(slope - got_q[idx]) <= 1e-6 * max(1.0, abs(got_q[idx]))
+    # the offset's last bias collects e itself; the derivative with respect to a value is never negative
+    # (monotonic mixing) once divided by e; linear in e
+    a, b, _ = wl.mixer_slices(*dims)["c2"]
+    assert abs(got_w[a] - e.sum()) < 1e-12
+    assert ((got_q / e[..., None]) >= 0).all()
+    q2, w2 = mxo.grad(dims, w, m["state"], q, -3.0 * e)
+    np.testing.assert_allclose(q2, -3.0 * got_q, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(w2, -3.0 * got_w, rtol=0, atol=1e-10)
