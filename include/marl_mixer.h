@@ -101,6 +101,29 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
                   const uint8_t *filled, float gamma, float *q_total, float *y_total, float *td_err,
                   float *loss, void *hip_stream);
 
+/*
+ * Backward pass of the mixing network (Alg. 3: "calculate the gradient").  With the caller's
+ * grad_q_total[b,t] = dL/dQ_total[b,t] (for the masked mean-squared TD loss of marl_mixer_td:
+ * -2 td_err / number of filled transitions; y_total is a constant of the target network),
+ *   grad_weights[p]     = sum over b,t of grad_q_total[b,t] * d Q_total[b,t] / d weights[p]
+ *   grad_q_taken[b,t,n] = grad_q_total[b,t] * d Q_total[b,t] / d q_taken[b,t,n]
+ * the second being what marl_qnet_grad takes as its upstream gradient.  d|x|/dx = sign(x) (0 at 0).
+ *   state          dev [B,T+1,S] f32   (slot t of each episode is used)
+ *   q_taken        dev [B,T,N] f32
+ *   grad_q_total   dev [B,T] f32
+ *   workspace      dev, 256-byte aligned, at least marl_mixer_grad_workspace_bytes(m, B, T) bytes; the
+ *                  caller owns it, the call allocates nothing
+ *   grad_q_taken   dev [B,T,N] f32, overwritten
+ *   grad_weights   dev [marl_mixer_param_count] f32, overwritten, packed like the weights
+ * Sums run in a fixed order.  Arithmetic as the forward pass (bf16 MFMA products, fp32 accumulation; fp32
+ * mixers split operands into two bf16 parts).  MARL_ERR_BAD_DIM for B < 1, T < 1, (N + 3) embed > 1536, a
+ * workspace that is too small; MARL_ERR_BAD_ARG for a misaligned workspace.
+ */
+int marl_mixer_grad_workspace_bytes(const marl_mixer *m, int32_t B, int32_t T, size_t *bytes);
+int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, const float *q_taken,
+                    const float *grad_q_total, void *workspace, size_t workspace_bytes,
+                    float *grad_q_taken, float *grad_weights, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

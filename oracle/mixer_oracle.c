@@ -143,14 +143,23 @@ void mixer_td(int N, int M, int S, const float *w_online, const float *w_target,
  * for the R = B T transitions i = (b, t) with values q [B, T, N] and state[b, t] of state [B, T+1, S].
  * Reverse mode of the definition above, written out per transition; d|x|/dx = sign(x) (0 at 0),
  * elu'(x) = 1 for x > 0, exp(x) otherwise, relu'(x) = [x > 0].
+ *
+ * sign and the relu step are discontinuous in the forward values: where a generated weight or an offset
+ * unit is within an implementation's forward error of zero, two implementations may switch differently and
+ * each is the exact derivative of what it computed.  If amb != NULL it receives, per parameter, the summed
+ * magnitude by which the gradient can differ through such switches for values in [-delta, delta] (twice the
+ * term for a sign, once for a step); it is zero for v2, c2, and grad_q is continuous.
  */
 void mixer_grad(int N, int M, int S, const float *w, int B, int T, const float *state, const double *q,
-                const double *e, double *grad_q, double *grad_w)
+                const double *e, double *grad_q, double *grad_w, double delta, double *amb)
 {
     mixer_t mx;
     mixer_bind(&mx, N, M, S, w);
     const long count = mixer_param_count(N, M, S);
     for (long p = 0; p < count; ++p) grad_w[p] = 0.0;
+    if (amb) for (long p = 0; p < count; ++p) amb[p] = 0.0;
+    const long oHw1 = 0, ohb1 = oHw1 + (long)N * M * S, oHb1 = ohb1 + (long)N * M, ohbb1 = oHb1 + (long)M * S;
+    const long oHw2 = ohbb1 + M, ohb2 = oHw2 + (long)M * S, oV1 = ohb2 + M, oc1 = oV1 + (long)M * S;
     /* the same binding on the gradient vector */
     double *gHw1 = grad_w, *ghb1 = gHw1 + (long)N * M * S, *gHb1 = ghb1 + (long)N * M, *ghbb1 = gHb1 + (long)M * S;
     double *gHw2 = ghbb1 + M, *ghb2 = gHw2 + (long)M * S, *gV1 = ghb2 + M, *gc1 = gV1 + (long)M * S;
@@ -184,12 +193,24 @@ void mixer_grad(int N, int M, int S, const float *w, int B, int T, const float *
                     gHb1[(long)m * S + k] += d_pre * (double)s[k];
                     gV1[(long)m * S + k] += d_a * (double)s[k];
                 }
+                if (amb && fabs(gen2) <= delta) {
+                    amb[ohb2 + m] += 2.0 * fabs(ei * hid);
+                    for (int k = 0; k < S; ++k) amb[oHw2 + (long)m * S + k] += 2.0 * fabs(ei * hid * (double)s[k]);
+                }
+                if (amb && fabs(a) <= delta) {
+                    amb[oc1 + m] += fabs(ei * (double)mx.v2[m]);
+                    for (int k = 0; k < S; ++k) amb[oV1 + (long)m * S + k] += fabs(ei * (double)mx.v2[m] * (double)s[k]);
+                }
                 for (int n = 0; n < N; ++n) {
                     const long f = (long)n * M + m;
                     const double gen1 = dot_state(mx.Hw1 + f * S, s, S) + (double)mx.hb1[f];
                     const double d_gen1 = d_pre * qi[n] * (gen1 > 0.0 ? 1.0 : gen1 < 0.0 ? -1.0 : 0.0);
                     ghb1[f] += d_gen1;
                     for (int k = 0; k < S; ++k) gHw1[f * S + k] += d_gen1 * (double)s[k];
+                    if (amb && fabs(gen1) <= delta) {
+                        amb[ohb1 + f] += 2.0 * fabs(d_pre * qi[n]);
+                        for (int k = 0; k < S; ++k) amb[oHw1 + f * S + k] += 2.0 * fabs(d_pre * qi[n] * (double)s[k]);
+                    }
                     if (m == 0) grad_q[i * N + n] = 0.0;
                     grad_q[i * N + n] += d_pre * fabs(gen1);
                 }

@@ -79,8 +79,9 @@ def td(dims, w_online, w_target, state, q_taken, next_max, reward, terminated, f
     return out
 
 
-def grad(dims, w, state, q, e):
-    """Backward pass: returns (grad_q [B,T,N], grad_w [param count]) for upstream e [B,T] = dL/dQ_total."""
+def grad(dims, w, state, q, e, switch_band=None):
+    """Backward pass: returns (grad_q [B,T,N], grad_w [param count]) for upstream e [B,T] = dL/dQ_total;
+    with switch_band = delta also the ambiguity budget [param count] of the sign / step switches."""
     N, M, S = (int(v) for v in dims)
     w = _c(w, np.float32)
     assert w.size == param_count(N, M, S)
@@ -91,5 +92,8 @@ def grad(dims, w, state, q, e):
     e = _c(e, np.float64); assert e.shape == (B, T)
     grad_q = np.zeros((B, T, N))
     grad_w = np.zeros(w.size)
-    _load().mixer_grad(N, M, S, _p(w), B, T, _p(state), _p(q), _p(e), _p(grad_q), _p(grad_w))
-    return grad_q, grad_w
+    amb = None if switch_band is None else np.zeros(w.size)
+    _load().mixer_grad(N, M, S, _p(w), B, T, _p(state), _p(q), _p(e), _p(grad_q), _p(grad_w),
+                       ctypes.c_double(0.0 if switch_band is None else float(switch_band)),
+                       None if amb is None else _p(amb))
+    return (grad_q, grad_w) if amb is None else (grad_q, grad_w, amb)

@@ -26,7 +26,7 @@ EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_a
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
 MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td",
-                 "marl_mixer_set_weights"]
+                 "marl_mixer_set_weights", "marl_mixer_grad_workspace_bytes", "marl_mixer_grad"]
 
 
 class MarlError(RuntimeError):
@@ -112,6 +112,10 @@ def load():
         lib.marl_mixer_set_weights.argtypes = [vp, vp, ctypes.c_size_t, vp]
         lib.marl_mixer_destroy.restype = None
         lib.marl_mixer_destroy.argtypes = [vp]
+        lib.marl_mixer_grad_workspace_bytes.restype = ctypes.c_int
+        lib.marl_mixer_grad_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
+        lib.marl_mixer_grad.restype = ctypes.c_int
+        lib.marl_mixer_grad.argtypes = [vp, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
         lib.marl_mixer_td.restype = ctypes.c_int
         lib.marl_mixer_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         _lib = lib
@@ -415,6 +419,22 @@ class Mixer:
 
     def set_weights(self, weights):
         marl_mixer_set_weights(self.handle, weights)
+
+    def grad_workspace_bytes(self, B, T):
+        n = ctypes.c_size_t(0)
+        check(load().marl_mixer_grad_workspace_bytes(ctypes.c_void_p(self.handle), int(B), int(T), ctypes.byref(n)))
+        return int(n.value)
+
+    def grad(self, state, q_taken, grad_q_total, workspace, grad_q_taken, grad_weights):
+        N, M, S = self.dims
+        B, T = q_taken.shape[0], q_taken.shape[1]
+        n_params = (N * M + 3 * M) * (S + 1) + M + 1
+        check(load().marl_mixer_grad(
+            ctypes.c_void_p(self.handle), B, T, _dev(state, "f32", (B, T + 1, S), "state"),
+            _dev(q_taken, "f32", (B, T, N), "q_taken"), _dev(grad_q_total, "f32", (B, T), "grad_q_total"),
+            _dev(workspace, "u8", (workspace.numel(),), "workspace"), int(workspace.numel()),
+            _dev(grad_q_taken, "f32", (B, T, N), "grad_q_taken"), _dev(grad_weights, "f32", (n_params,), "grad_weights"),
+            _stream()))
 
     def td(self, target, state, q_taken, next_max, reward, terminated, filled, gamma, q_total, y_total, td_err,
            loss=None):

@@ -289,15 +289,6 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
 }
 
 // ------------------------------------------------------------------------------------------ weight gradients
-// Row m of an operand lives at base + (m / rows_per_group) * group_stride + (m % rows_per_group) * ld.
-struct RowMap {
-    const float *base;
-    long group_stride;
-    int rows_per_group, ld;
-};
-
-enum ExtraCols : int { kExtraOnes = 1, kExtraAgent = 2 };
-
 struct TnGemmArgs {
     RowMap a, b;
     int M;              // samples
@@ -541,15 +532,41 @@ hipError_t run_product(int planes, const RowMap &a, const RowMap &b, long M, int
                        const Plan &plan, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
                        hipStream_t stream)
 {
+    return launch_tn_product(planes, a, b, M, P, Q, extra_mode, n_extra, N, plan.chunk, partial, row_shift, dst_w, ld_w, dst_b, stream);
+}
+
+template <int H, int P, int NW>
+hipError_t back_dispatch(const BpttArgs &a, hipStream_t stream)
+{
+    const int tiles = (a.B * a.net.N + 15) / 16;
+    hipError_t err = allow_large_lds<bptt_back_kernel<H, P, NW>>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    constexpr size_t kLds = BpttShape<H, P>::kBytes;
+    hipLaunchKernelGGL((bptt_back_kernel<H, P, NW>), dim3(tiles), dim3(64 * NW), kLds, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+size_t tn_partial_bytes(long M, int chunk, int P, int q_total)
+{
+    const size_t chunks = (size_t)((M + chunk - 1) / chunk);
+    return chunks * (P > 128 ? 384 : 128) * (size_t)((q_total + 15) / 16 * 16) * sizeof(float);
+}
+
+hipError_t launch_tn_product(int planes, const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra,
+                             int N, int chunk, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
+                             hipStream_t stream)
+{
     TnGemmArgs g{};
     g.a = a; g.b = b; g.M = (int)M; g.P = P; g.Q = Q; g.extra_mode = extra_mode; g.n_extra = n_extra; g.N = N;
     g.qp = (Q + n_extra + 15) / 16 * 16;
-    g.chunk = plan.chunk;
+    g.chunk = chunk;
     g.partial = partial;
     // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
     const bool wide_rows = P > 128;
     if ((wide_rows && (P > 384 || g.qp > 144)) || (!wide_rows && g.qp > 336)) return hipErrorInvalidValue;
-    const int p_pad = wide_rows ? 384 : 128, chunks = (int)((M + plan.chunk - 1) / plan.chunk);
+    const int p_pad = wide_rows ? 384 : 128, chunks = (int)((M + chunk - 1) / chunk);
     const size_t lds = (size_t)(planes == 1 ? 2 : 1) * planes * (p_pad + g.qp) * 80;     // 80 bytes per staged column and plane
     hipError_t err = hipErrorInvalidValue;
 #define MARL_TN(PBW, QBN, PL)                                                                            \
@@ -575,18 +592,6 @@ hipError_t run_product(int planes, const RowMap &a, const RowMap &b, long M, int
     return hipGetLastError();
 }
 
-template <int H, int P, int NW>
-hipError_t back_dispatch(const BpttArgs &a, hipStream_t stream)
-{
-    const int tiles = (a.B * a.net.N + 15) / 16;
-    hipError_t err = allow_large_lds<bptt_back_kernel<H, P, NW>>(kLdsLimit);
-    if (err != hipSuccess) return err;
-    constexpr size_t kLds = BpttShape<H, P>::kBytes;
-    hipLaunchKernelGGL((bptt_back_kernel<H, P, NW>), dim3(tiles), dim3(64 * NW), kLds, stream, a);
-    return hipGetLastError();
-}
-
-}  // namespace
 
 bool qnet_grad_fits(const NetFrags &net)
 {

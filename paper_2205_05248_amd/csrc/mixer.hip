@@ -478,3 +478,232 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
 }
 
 }  // extern "C"
+
+// ------------------------------------------------------------------------------------------ backward pass
+// Gradient of sum_i e[i] Q_total[i] (e = dL/dQ_total, the caller's) with respect to the mixer's parameters and
+// to the agents' values.  Two stages:
+//   mixer_back_kernel   a workgroup takes 16 transitions: all (N + 3) M generated quantities again (the same
+//                       MFMA contraction as the forward pass, fragments read from L2, results to LDS), the
+//                       mix, and then the adjoint of every generated quantity, written to the workspace as a
+//                       matrix [transitions, (N + 3) M + M + 1] (the last M + 1 columns: e relu(offset unit), e),
+//                       and dL/dq for the agents' networks;
+//   launch_tn_product   every state matrix's gradient is (adjoint columns)^T [state | 1] summed over the
+//                       transitions: the sample-contraction product of the Q-network's backward pass, cut into
+//                       slices of rows and state columns that fit its two shapes.
+namespace marl {
+namespace {
+
+struct MixerBackArgs {
+    const bf16x8 *frags;
+    const float *bias, *v2;
+    int N, M, S, ks, rows, T, F, ldd;
+    const float *state, *q, *e;
+    float *dgen;        // [rows, ldd]
+    float *grad_q;      // [rows, N]
+};
+
+constexpr int kMixBackGenMax = 1536;       // generated quantities per transition whose values fit LDS
+
+template <int P>
+__global__ __launch_bounds__(256) void mixer_back_kernel(const MixerBackArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int N = a.N, M = a.M, S = a.S, T = a.T, F = a.F, KS = a.ks;
+    const int row0 = blockIdx.x * 16;
+    // LDS: the tile's states as operand fragments [KS][P][64], every generated quantity [16][F + 4], the
+    // tile's agent values [16][N], adjoints of the hidden units [16][M], and e [16]
+    typedef bf16x8 (*FragBuf)[P][64];
+    const FragBuf stf = reinterpret_cast<FragBuf>(lds);
+    const int gp = F + 4;
+    float *const gen = reinterpret_cast<float *>(lds + (size_t)KS * P * 1024);
+    float *const q_lds = gen + 16 * gp;
+    float *const dpre = q_lds + 16 * N;
+    float *const e_lds = dpre + 16 * M;
+
+    // states: lane (row c, quarter q4) holds values 32 ks + 8 q4 + 0..7 of its transition's state; zero past S
+    {
+        const int row = min(row0 + c, a.rows - 1);
+        const float *srow = a.state + ((size_t)(row / T) * (T + 1) + row % T) * S;
+        for (int ks = wave; ks < KS; ks += 4) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = 32 * ks + 8 * q4 + i;
+                v[i] = k < S ? srow[k] : 0.0f;
+            }
+            const Frag<P> f = to_frag<P>(v);
+            stf[ks][0][lane] = f.hi;
+            if constexpr (P == 2) stf[ks][1][lane] = f.lo;
+        }
+        for (int i = threadIdx.x; i < 16 * N; i += 256) q_lds[i] = a.q[(size_t)min(row0 + i / N, a.rows - 1) * N + i % N];
+        if (threadIdx.x < 16) e_lds[threadIdx.x] = row0 + (int)threadIdx.x < a.rows ? a.e[row0 + threadIdx.x] : 0.0f;
+    }
+    __syncthreads();
+    // generated quantities: block fb of 16, lane (transition c, quantities 16 fb + 4 q4 + 0..3)
+    for (int fb = wave; fb < F / 16; fb += 4) {
+        f32x4 acc = load_feature4(a.bias, fb, q4);
+        const bf16x8 *blk = a.frags + (size_t)fb * KS * P * 64 + lane;
+        for (int ks = 0; ks < KS; ++ks) {
+            Frag<P> st;
+            st.hi = stf[ks][0][lane];
+            if constexpr (P == 2) st.lo = stf[ks][1][lane];
+            mma16<P>(acc, load_wfrag<P>(blk + (size_t)ks * P * 64), st);
+        }
+        *reinterpret_cast<f32x4 *>(gen + c * gp + 16 * fb + 4 * q4) = acc;
+    }
+    __syncthreads();
+    // per (transition, hidden unit): the mix forward, then the adjoints that do not depend on the agent
+    for (int idx = threadIdx.x; idx < 16 * M; idx += 256) {
+        const int tr = idx / M, m = idx % M;
+        const float *g = gen + tr * gp;
+        float pre = g[N * M + m];
+        for (int n = 0; n < N; ++n) pre += q_lds[tr * N + n] * fabsf(g[n * M + m]);
+        const float hid = pre > 0.0f ? pre : expm1f(pre);
+        const float gen2 = g[(N + 1) * M + m], off = g[(N + 2) * M + m];
+        const float e = e_lds[tr];
+        const float d_pre = e * fabsf(gen2) * (pre > 0.0f ? 1.0f : expf(pre));
+        const float d_gen2 = e * hid * (gen2 > 0.0f ? 1.0f : gen2 < 0.0f ? -1.0f : 0.0f);
+        const float d_off = off > 0.0f ? e * a.v2[m] : 0.0f;
+        dpre[tr * M + m] = d_pre;
+        if (row0 + tr < a.rows) {
+            float *d = a.dgen + (size_t)(row0 + tr) * a.ldd;
+            d[N * M + m] = d_pre;
+            d[(N + 1) * M + m] = d_gen2;
+            d[(N + 2) * M + m] = d_off;
+            d[F + m] = e * fmaxf(off, 0.0f);
+            if (m == 0) d[F + M] = e;
+        }
+    }
+    __syncthreads();
+    // adjoints of the per-agent weights, and what flows on to the agents' values
+    for (int idx = threadIdx.x; idx < 16 * N * M; idx += 256) {
+        const int tr = idx / (N * M), f = idx % (N * M);
+        const float g1 = gen[tr * gp + f];
+        const float v = dpre[tr * M + f % M] * q_lds[tr * N + f / M] * (g1 > 0.0f ? 1.0f : g1 < 0.0f ? -1.0f : 0.0f);
+        if (row0 + tr < a.rows) a.dgen[(size_t)(row0 + tr) * a.ldd + f] = v;
+    }
+    for (int idx = threadIdx.x; idx < 16 * N; idx += 256) {
+        const int tr = idx / N, n = idx % N;
+        float s = 0.0f;
+        for (int m = 0; m < M; ++m) s += dpre[tr * M + m] * fabsf(gen[tr * gp + n * M + m]);
+        if (row0 + tr < a.rows) a.grad_q[(size_t)(row0 + tr) * N + n] = s;
+    }
+}
+
+struct MixerGradPlan {
+    int ldd, chunk;
+    size_t off_dgen, off_partial, bytes;
+};
+
+MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
+{
+    MixerGradPlan p{};
+    const long R = (long)B * T;
+    const int F = (d.n_agents + 3) * d.embed;
+    p.ldd = (F + d.embed + 1 + 3) / 4 * 4;
+    const long chunks = std::min<long>(256, (R + 31) / 32);
+    p.chunk = (int)(((R + chunks - 1) / chunks + 31) / 32 * 32);
+    size_t off = 0;
+    p.off_dgen = off;    off = (off + (size_t)R * p.ldd * 4 + 255) / 256 * 256;
+    p.off_partial = off; off = (off + tn_partial_bytes(R, p.chunk, 384, 144) + 255) / 256 * 256;      // the larger of the two shapes' needs
+    p.bytes = off;
+    return p;
+}
+
+size_t mixer_back_lds(const marl_mixer *m)
+{
+    const int F = (m->desc.n_agents + 3) * m->desc.embed;
+    return (size_t)m->ks * m->planes * 1024 + sizeof(float) * (16 * (F + 4) + 16 * m->desc.n_agents + 16 * m->desc.embed + 16);
+}
+
+}  // namespace
+}  // namespace marl
+
+extern "C" {
+
+int marl_mixer_grad_workspace_bytes(const marl_mixer *m, int32_t B, int32_t T, size_t *bytes)
+{
+    if (!m || !bytes) return MARL_ERR_NULL;
+    const int F = (m->desc.n_agents + 3) * m->desc.embed;
+    if (B < 1 || T < 1 || (int64_t)B * T * (F + m->desc.embed + 4) >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+    if (F > marl::kMixBackGenMax || marl::mixer_back_lds(m) > (size_t)marl::kLdsLimit) return MARL_ERR_BAD_DIM;
+    *bytes = marl::mixer_grad_plan(m->desc, B, T).bytes;
+    return MARL_OK;
+}
+
+int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, const float *q_taken,
+                    const float *grad_q_total, void *workspace, size_t workspace_bytes, float *grad_q_taken,
+                    float *grad_weights, void *hip_stream)
+{
+    if (!m) return MARL_ERR_NULL;
+    size_t need = 0;
+    const int rc = marl_mixer_grad_workspace_bytes(m, B, T, &need);
+    if (rc != MARL_OK) return rc;
+    if (!state || !q_taken || !grad_q_total || !workspace || !grad_q_taken || !grad_weights) return MARL_ERR_NULL;
+    if (workspace_bytes < need) return MARL_ERR_BAD_DIM;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MARL_ERR_BAD_ARG;
+    marl::MixerDeviceGuard guard(m->desc.device);
+    if (!guard.ok) return marl::report_device_error(hipErrorInvalidDevice, "hipSetDevice");
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const marl::MixerGradPlan plan = marl::mixer_grad_plan(m->desc, B, T);
+    const int N = m->desc.n_agents, M = m->desc.embed, S = m->desc.state_dim, F = (N + 3) * M;
+    const long R = (long)B * T;
+    float *dgen = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_dgen);
+    float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_partial);
+
+    marl::MixerBackArgs a{};
+    a.frags = m->frags; a.bias = m->bias; a.v2 = m->v2;
+    a.N = N; a.M = M; a.S = S; a.ks = m->ks; a.rows = (int)R; a.T = T; a.F = F; a.ldd = plan.ldd;
+    a.state = state; a.q = q_taken; a.e = grad_q_total; a.dgen = dgen; a.grad_q = grad_q_taken;
+    const size_t lds = marl::mixer_back_lds(m);
+    hipError_t err;
+    if (m->planes == 2) {
+        err = marl::allow_large_lds<marl::mixer_back_kernel<2>>(marl::kLdsLimit);
+        if (err == hipSuccess) hipLaunchKernelGGL(marl::mixer_back_kernel<2>, dim3((unsigned)((R + 15) / 16)), dim3(256), lds, stream, a);
+    } else {
+        err = marl::allow_large_lds<marl::mixer_back_kernel<1>>(marl::kLdsLimit);
+        if (err == hipSuccess) hipLaunchKernelGGL(marl::mixer_back_kernel<1>, dim3((unsigned)((R + 15) / 16)), dim3(256), lds, stream, a);
+    }
+    if (err == hipSuccess) err = hipGetLastError();
+    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad launch");
+
+    // parameter gradients: packed order Hw1 [N M, S], hb1, Hb1 [M, S], hbb1, Hw2 [M, S], hb2, V1 [M, S], c1, v2, c2
+    float *gHw1 = grad_weights, *ghb1 = gHw1 + (size_t)N * M * S, *gHb1 = ghb1 + (size_t)N * M, *ghbb1 = gHb1 + (size_t)M * S;
+    float *gHw2 = ghbb1 + M, *ghb2 = gHw2 + (size_t)M * S, *gV1 = ghb2 + M, *gc1 = gV1 + (size_t)M * S, *gv2 = gc1 + M;
+    const marl::RowMap plain{dgen, 0, (int)R, plan.ldd};
+    const marl::RowMap states{state, (long)(T + 1) * S, T, S};
+    // one matrix: rows [r0, r0 + P) of it are adjoint columns [col0 + r0, ..); state columns in slices, the
+    // column of ones (the bias) rides with the last slice
+    auto matrix = [&](int col0, int rows_total, float *dst_w, float *dst_b) -> hipError_t {
+        const bool wide = rows_total > 128;
+        const int p_step = wide ? 384 : 128, q_step = wide ? 128 : 320;
+        for (int r0 = 0; r0 < rows_total; r0 += p_step)
+            for (int k0 = 0; k0 < S; k0 += q_step) {
+                const int P = std::min(p_step, rows_total - r0), Q = std::min(q_step, S - k0);
+                const bool last = k0 + q_step >= S;
+                marl::RowMap ar = plain, br = states;
+                ar.base = dgen + col0 + r0;
+                br.base = state + k0;
+                const hipError_t e2 = marl::launch_tn_product(m->planes, ar, br, R, P, Q, last ? marl::kExtraOnes : marl::kExtraNone,
+                                                              last ? 1 : 0, 1, plan.chunk, partial, 0, dst_w + (size_t)r0 * S + k0, S,
+                                                              dst_b + r0, stream);
+                if (e2 != hipSuccess) return e2;
+            }
+        return hipSuccess;
+    };
+    err = matrix(0, N * M, gHw1, ghb1);
+    if (err == hipSuccess) err = matrix(N * M, M, gHb1, ghbb1);
+    if (err == hipSuccess) err = matrix((N + 1) * M, M, gHw2, ghb2);
+    if (err == hipSuccess) err = matrix((N + 2) * M, M, gV1, gc1);
+    if (err == hipSuccess) {        // v2 and c2: the last M + 1 adjoint columns against the column of ones alone
+        marl::RowMap ar = plain;
+        ar.base = dgen + F;
+        err = marl::launch_tn_product(m->planes, ar, states, R, M + 1, 0, marl::kExtraOnes, 1, 1, plan.chunk, partial, 0, gv2, 1, gv2, stream);
+    }
+    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad products");
+    return MARL_OK;
+}
+
+}  // extern "C"

@@ -205,3 +205,70 @@ def test_mixer_set_weights_is_ordered_on_the_stream():
     with pytest.raises(binding.MarlError):
         mixer.set_weights(w0[:-1])
     mixer.close()
+
+
+# ------------------------------------------------------------------ backward pass
+GRAD_REL = {"fp32": 1e-3, "bf16": 3e-2}
+# forward error of a generated quantity: fp32 mixers the forward tolerance; bf16 mixers round every state entry
+# to bf16 (relative 2^-9) before a product over up to 512 of them
+SWITCH_BAND = {"fp32": 1e-4, "bf16": 5e-3}
+
+
+def _gpu_mixer_grad(mixer, dims, m, e):
+    N, M, S = dims
+    B, T = m["q_taken"].shape[:2]
+    d = {k: torch.from_numpy(np.ascontiguousarray(m[k])).cuda() for k in ("state", "q_taken")}
+    ws = torch.empty(mixer.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    gq = torch.full((B, T, N), float("nan"), device="cuda")
+    gw = torch.full((wl.mixer_param_count(*dims),), float("nan"), device="cuda")
+    mixer.grad(d["state"], d["q_taken"], torch.from_numpy(e.astype(np.float32)).cuda(), ws, gq, gw)
+    torch.cuda.synchronize()
+    return gq.cpu().numpy(), gw.cpu().numpy()
+
+
+@pytest.mark.parametrize("ci,B,T,dtype", [(0, 3, 7, "fp32"), (1, 5, 9, "fp32"), (2, 7, 12, "fp32"), (3, 33, 5, "fp32"),
+                                          (4, 3, 11, "bf16"), (4, 2, 5, "fp32"), (1, 6, 8, "bf16")])
+def test_mixer_gradient_matches_the_oracle(ci, B, T, dtype):
+    """Every entry of every parameter tensor, and dL/dq, within REL of the tensor's largest reference value.
+    The absolute values and the offset's relu are switches set by forward values: where a generated weight or an
+    offset unit is within the forward error of zero (SWITCH_BAND) the two sides may set them differently, and the
+    oracle's ambiguity budget for exactly those terms is added to the bar of the entries they reach (zero for
+    dL/dq, v2, c2, Hb1, hbb1, which the test checks)."""
+    cfg = dict(wl.config(ci), dtype=dtype)
+    dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    mixer = binding.Mixer(dims, w, dtype)
+    m = wl.make_mixer_inputs(cfg, B=B, T=T)
+    e = np.random.default_rng(ci).normal(size=(B, T)).astype(np.float32)
+    got_q, got_w = _gpu_mixer_grad(mixer, dims, m, e)
+    w_ref = w
+    if dtype == "bf16":
+        from oracle import marl_oracle as orc
+        w_ref = np.array(w, np.float32)
+        for name, (a, b, shp) in wl.mixer_slices(*dims).items():
+            if len(shp) == 2:
+                w_ref[a:b] = orc.round_bf16(w_ref[a:b])
+    want_q, want_w, amb = mxo.grad(dims, w_ref, m["state"], m["q_taken"].astype(np.float64), e.astype(np.float64),
+                                   switch_band=SWITCH_BAND[dtype])
+    rel = GRAD_REL[dtype]
+    assert np.isfinite(got_q).all() and np.isfinite(got_w).all()
+    bad, worst = [], {}
+    err_q = np.abs(got_q - want_q).max() / np.abs(want_q).max()
+    worst["dq"] = err_q
+    if err_q > rel:
+        bad.append(("dq", err_q))
+    for name, (a, b, _) in wl.mixer_slices(*dims).items():
+        scale = np.abs(want_w[a:b]).max()
+        diff = np.abs(got_w[a:b] - want_w[a:b])
+        worst[name] = diff.max() / max(scale, 1e-30)
+        if name in ("Hb1", "hbb1", "v2", "c2"):
+            assert amb[a:b].max() == 0
+        if (diff - (rel * scale + 1e-6 + amb[a:b])).max() > 0:
+            bad.append((name, worst[name], amb[a:b].max() / max(scale, 1e-30)))
+    print(cfg["name"], dtype, {k: f"{v:.1e}" for k, v in worst.items()})
+    assert not bad, bad
+    again_q, again_w = _gpu_mixer_grad(mixer, dims, m, e)
+    np.testing.assert_array_equal(again_w, got_w)
+    np.testing.assert_array_equal(again_q, got_q)
+    mixer.close()

@@ -222,3 +222,41 @@ def test_gradient_against_finite_differences_and_closed_forms():
     q2, w2 = mxo.grad(dims, w, m["state"], q, -3.0 * e)
     np.testing.assert_allclose(q2, -3.0 * got_q, rtol=0, atol=1e-12)
     np.testing.assert_allclose(w2, -3.0 * got_w, rtol=0, atol=1e-10)
+
+
+def test_switch_ambiguity_budget_against_library_adjoints():
+    torch = pytest.importorskip("torch")
+    F = torch.nn.functional
+    cfg = wl.config(1)
+    N, M, S = dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    B, T = 2, 5
+    m = wl.make_mixer_inputs(cfg, B=B, T=T)
+    e = np.random.default_rng(4).normal(size=(B, T))
+    q = m["q_taken"].astype(np.float64)
+    band = 0.05
+    _, got_w, amb = mxo.grad(dims, w, m["state"], q, e, switch_band=band)
+    # the library's adjoints of the three switched quantities
+    t = {k: torch.from_numpy(w[a:b].reshape(shp).astype(np.float64)) for k, (a, b, shp) in wl.mixer_slices(*dims).items()}
+    R = B * T
+    ts = torch.from_numpy(m["state"][:, :T].astype(np.float64)).reshape(R, S)
+    tq, te = torch.from_numpy(q.reshape(R, N)), torch.from_numpy(e.reshape(R))
+    g1 = F.linear(ts, t["Hw1"], t["hb1"]).requires_grad_(True)
+    g2 = F.linear(ts, t["Hw2"], t["hb2"]).requires_grad_(True)
+    off = F.linear(ts, t["V1"], t["c1"])
+    hid = F.elu(torch.bmm(tq.view(R, 1, N), torch.abs(g1).view(R, N, M)).view(R, M) + F.linear(ts, t["Hb1"], t["hbb1"]))
+    (((hid * torch.abs(g2)).sum(-1)) * te).sum().backward()
+    sl = wl.mixer_slices(*dims)
+    want = np.zeros(w.size)
+    near1 = (g1.detach().abs() <= band).double() * 2.0 * g1.grad.abs()
+    near2 = (g2.detach().abs() <= band).double() * 2.0 * g2.grad.abs()
+    near3 = (off.abs() <= band).double() * (te[:, None] * t["v2"][None, :]).abs()
+    for name_w, name_b, near in (("Hw1", "hb1", near1), ("Hw2", "hb2", near2), ("V1", "c1", near3)):
+        a, b, _ = sl[name_b]
+        want[a:b] = near.sum(0).numpy()
+        a, b, _ = sl[name_w]
+        want[a:b] = torch.einsum("rf,rk->fk", near, ts.abs()).reshape(-1).numpy()
+    np.testing.assert_allclose(amb, want, rtol=0, atol=1e-11 * max(1.0, want.max()))
+    assert amb[sl["Hw1"][0]:sl["Hw1"][1]].max() > 0 and amb[sl["v2"][0]:].max() == 0 and amb[sl["Hb1"][0]:sl["hbb1"][1]].max() == 0
+    _, _, none = mxo.grad(dims, w, m["state"], q, e, switch_band=-1.0)
+    assert none.max() == 0
