@@ -138,3 +138,48 @@ def test_learner_iterations_reduce_the_td_loss():
     assert losses[-1] < 0.8 * losses[0], losses
     assert all(b <= a * 1.02 for a, b in zip(losses, losses[1:])), losses
     online.close(); target.close()
+
+
+def test_qmix_learner_iterations_reduce_the_loss():
+    """The whole learner step of Alg. 3 with the mixing network, every stage in the library's kernels: unroll
+    (online, frozen target), mixer forward + TD loss, mixer backward (parameter gradients and dL/dq_taken),
+    Q-network backward, parameter updates.  The mixer's update goes through its stream-ordered weight refresh.
+    Twelve iterations on one batch: the masked mean-squared TD loss must fall."""
+    cfg = dict(wl.config(1), B=16, T=20)
+    dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
+    N = dims[0]
+    B, T = 16, 20
+    w, mw = wl.make_weights(cfg, 0), wl.make_mixer_weights(cfg, 0)
+    online, target = binding.QNet(dims, w), binding.QNet(dims, wl.make_weights(cfg, 1))
+    mixer, mixer_tg = binding.Mixer(mdims, mw), binding.Mixer(mdims, wl.make_mixer_weights(cfg, 1))
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    m = wl.make_mixer_inputs(cfg, B=B, T=T)
+    d = pu.to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
+    state = torch.from_numpy(m["state"]).cuda()
+    q_taken, next_max, y = (torch.empty(B, T, N, device="cuda") for _ in range(3))
+    q_total, y_total, td = (torch.empty(B, T, device="cuda") for _ in range(3))
+    loss2 = torch.empty(2, device="cuda")
+    master, grad = torch.from_numpy(w.copy()).cuda(), torch.empty(w.size, device="cuda")
+    mmaster, mgrad = torch.from_numpy(mw.copy()).cuda(), torch.empty(mw.size, device="cuda")
+    gq = torch.empty(B, T, N, device="cuda")
+    ws = torch.empty(online.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    mws = torch.empty(mixer.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    losses = []
+    for it in range(12):
+        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                         u["gamma"], q_taken, next_max, y)
+        mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
+                 q_total, y_total, td, loss2)
+        sq, count = (float(v) for v in loss2.cpu())
+        losses.append(sq / count)
+        mixer.grad(state, q_taken, (-2.0 / count) * td, mws, gq, mgrad)          # td_err = filled (y_total - Q_total)
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
+        online.sgd_step(master, grad, 0.0005)
+        mmaster -= 0.0005 * mgrad
+        mixer.set_weights(mmaster.cpu().numpy())
+    torch.cuda.synchronize()
+    assert np.isfinite(losses).all(), losses
+    assert losses[-1] < 0.8 * losses[0], losses
+    assert all(b <= a * 1.05 for a, b in zip(losses, losses[1:])), losses
+    for h in (online, target, mixer, mixer_tg):
+        h.close()
