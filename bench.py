@@ -266,12 +266,32 @@ def mixer_section(ci, with_cpu, launches=20):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / launches
+    # the mixer's backward pass on the same batch (parameter gradients and dL/dq_taken for an upstream dL/dQ_total)
+    grad_ms = None
+    try:
+        need = online.grad_workspace_bytes(B, T)
+        ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+        gq = torch.empty(B, T, N, device="cuda")
+        gw = torch.empty(wl.mixer_param_count(*dims), device="cuda")
+        gcall = lambda: online.grad(d["state"], d["q_taken"], outs[2], ws, gq, gw)
+        for _ in range(2):
+            gcall()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(launches):
+            gcall()
+        b.record()
+        torch.cuda.synchronize()
+        grad_ms = a.elapsed_time(b) / launches
+    except binding.MarlError:
+        pass
     online.close(); target.close()
     flops = 2 * B * T * 2 * (N * M + 3 * M) * S                  # two mixers, one multiply-add per generated quantity and state value
     io_bytes = B * (T + 1) * S * 4 + 2 * B * T * N * 4 + B * T * (4 + 2 + 12)
     out = {"kernel": "mixer_td", "ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "bound": "mfma",
            "TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK["bf16_TFs"],
            "GBs": io_bytes / (ms * 1e-3) / 1e9, "hbm_frac": io_bytes / (ms * 1e-3) / 1e9 / PEAK["hbm_GBs"],
+           "grad_ms": grad_ms,
            "config": {"n_agents": N, "embed": M, "state_dim": S, "B": B, "T": T, "mixers": "online + target"}}
     if with_cpu:
         from oracle import mixer_oracle as mxo

@@ -504,13 +504,15 @@ struct MixerBackArgs {
 
 constexpr int kMixBackGenMax = 1536;       // generated quantities per transition whose values fit LDS
 
-template <int P>
+// KS: k-steps of 32 over the state, a template parameter so that a block's fragment loads are all issued
+// before its first product (a loop over a run-time count would take them from L2 one round trip at a time).
+template <int P, int KS>
 __global__ __launch_bounds__(256) void mixer_back_kernel(const MixerBackArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int N = a.N, M = a.M, S = a.S, T = a.T, F = a.F, KS = a.ks;
+    const int N = a.N, M = a.M, S = a.S, T = a.T, F = a.F;
     const int row0 = blockIdx.x * 16;
     // LDS: the tile's states as operand fragments [KS][P][64], every generated quantity [16][F + 4], the
     // tile's agent values [16][N], adjoints of the hidden units [16][M], and e [16]
@@ -545,11 +547,15 @@ __global__ __launch_bounds__(256) void mixer_back_kernel(const MixerBackArgs a)
     for (int fb = wave; fb < F / 16; fb += 4) {
         f32x4 acc = load_feature4(a.bias, fb, q4);
         const bf16x8 *blk = a.frags + (size_t)fb * KS * P * 64 + lane;
+        WFrag<P> wf[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) wf[ks] = load_wfrag<P>(blk + (size_t)ks * P * 64);
+#pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             Frag<P> st;
             st.hi = stf[ks][0][lane];
             if constexpr (P == 2) st.lo = stf[ks][1][lane];
-            mma16<P>(acc, load_wfrag<P>(blk + (size_t)ks * P * 64), st);
+            mma16<P>(acc, wf[ks], st);
         }
         *reinterpret_cast<f32x4 *>(gen + c * gp + 16 * fb + 4 * q4) = acc;
     }
@@ -658,14 +664,26 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     a.N = N; a.M = M; a.S = S; a.ks = m->ks; a.rows = (int)R; a.T = T; a.F = F; a.ldd = plan.ldd;
     a.state = state; a.q = q_taken; a.e = grad_q_total; a.dgen = dgen; a.grad_q = grad_q_taken;
     const size_t lds = marl::mixer_back_lds(m);
-    hipError_t err;
-    if (m->planes == 2) {
-        err = marl::allow_large_lds<marl::mixer_back_kernel<2>>(marl::kLdsLimit);
-        if (err == hipSuccess) hipLaunchKernelGGL(marl::mixer_back_kernel<2>, dim3((unsigned)((R + 15) / 16)), dim3(256), lds, stream, a);
-    } else {
-        err = marl::allow_large_lds<marl::mixer_back_kernel<1>>(marl::kLdsLimit);
-        if (err == hipSuccess) hipLaunchKernelGGL(marl::mixer_back_kernel<1>, dim3((unsigned)((R + 15) / 16)), dim3(256), lds, stream, a);
+    hipError_t err = hipErrorInvalidValue;
+    const dim3 grid((unsigned)((R + 15) / 16));
+#define MARL_MIXBACK(PL, KSTEPS)                                                                          \
+    do {                                                                                                  \
+        err = marl::allow_large_lds<marl::mixer_back_kernel<PL, KSTEPS>>(marl::kLdsLimit);                \
+        if (err == hipSuccess) hipLaunchKernelGGL((marl::mixer_back_kernel<PL, KSTEPS>), grid, dim3(256), lds, stream, a); \
+    } while (0)
+#define MARL_MIXBACK_KS(PL)                                                                               \
+    switch (m->ks) {                                                                                      \
+    case 2: MARL_MIXBACK(PL, 2); break;                                                                   \
+    case 4: MARL_MIXBACK(PL, 4); break;                                                                   \
+    case 6: MARL_MIXBACK(PL, 6); break;                                                                   \
+    case 8: MARL_MIXBACK(PL, 8); break;                                                                   \
+    case 16: MARL_MIXBACK(PL, 16); break;                                                                 \
+    case 32: MARL_MIXBACK(PL, 32); break;                                                                 \
+    default: break;                                                                                       \
     }
+    if (m->planes == 2) { MARL_MIXBACK_KS(2); } else { MARL_MIXBACK_KS(1); }
+#undef MARL_MIXBACK_KS
+#undef MARL_MIXBACK
     if (err == hipSuccess) err = hipGetLastError();
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad launch");
 
