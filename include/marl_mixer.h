@@ -124,6 +124,19 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
                     const float *grad_q_total, void *workspace, size_t workspace_bytes,
                     float *grad_q_taken, float *grad_weights, void *hip_stream);
 
+/*
+ * The learner's parameter update for the mixer on the device, the counterpart of marl_qnet_sgd_step:
+ *   weights[p] <- weights[p] - lr * grad_weights[p]      (fp32: the product is rounded, then the difference)
+ * and the mixer's resident image is rebuilt from the new weights by kernels on the stream, with the rounding
+ * of marl_mixer_create, so that `m` afterwards behaves bit for bit like a mixer created from them.
+ *   weights       dev [marl_mixer_param_count] f32, in and out (the caller's copy of the parameters)
+ *   grad_weights  dev [marl_mixer_param_count] f32, e.g. from marl_mixer_grad
+ *   lr            finite; MARL_ERR_BAD_ARG otherwise
+ * Stream-ordered; nothing crosses to the host.  The first call on a handle builds the image's map on the host
+ * and allocates and fills its device copy (synchronous); later calls allocate nothing.
+ */
+int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights, float lr, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

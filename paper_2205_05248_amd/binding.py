@@ -26,7 +26,7 @@ EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_a
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
 MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td",
-                 "marl_mixer_set_weights", "marl_mixer_grad_workspace_bytes", "marl_mixer_grad"]
+                 "marl_mixer_set_weights", "marl_mixer_grad_workspace_bytes", "marl_mixer_grad", "marl_mixer_sgd_step"]
 
 
 class MarlError(RuntimeError):
@@ -116,6 +116,8 @@ def load():
         lib.marl_mixer_grad_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         lib.marl_mixer_grad.restype = ctypes.c_int
         lib.marl_mixer_grad.argtypes = [vp, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp, vp, vp]
+        lib.marl_mixer_sgd_step.restype = ctypes.c_int
+        lib.marl_mixer_sgd_step.argtypes = [vp, vp, vp, f32, vp]
         lib.marl_mixer_td.restype = ctypes.c_int
         lib.marl_mixer_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         _lib = lib
@@ -419,6 +421,11 @@ class Mixer:
 
     def set_weights(self, weights):
         marl_mixer_set_weights(self.handle, weights)
+
+    def sgd_step(self, weights, grad_weights, lr):
+        n = weights.numel()
+        check(load().marl_mixer_sgd_step(ctypes.c_void_p(self.handle), _dev(weights, "f32", (n,), "weights"),
+                                         _dev(grad_weights, "f32", (n,), "grad_weights"), float(lr), _stream()))
 
     def grad_workspace_bytes(self, B, T):
         n = ctypes.c_size_t(0)

@@ -22,6 +22,7 @@
 #include <cstring>
 #include <new>
 #include <type_traits>
+#include <vector>
 
 #include "../../include/marl_mixer.h"
 #include "fused16.h"
@@ -39,6 +40,10 @@ struct marl_mixer {
     size_t bytes;                // of the image
     void *staging;               // pinned host copy of the image for marl_mixer_set_weights (lazily allocated)
     hipEvent_t staging_done;     // the last upload from it
+    // device-side refresh (marl_mixer_sgd_step), built on first use: source parameter of every 16-bit element
+    // of the fragments, then of every fp32 table entry
+    int32_t *repack_map;
+    size_t frag_elems, table_entries;
 };
 
 namespace marl {
@@ -385,6 +390,7 @@ int marl_mixer_create(const marl_mixer_desc *desc, const float *host_weights, si
     m->planes = desc->weight_dtype == MARL_DTYPE_BF16 ? 1 : 2;
     m->ks = marl::padded_ksteps(desc->state_dim);
     m->image = nullptr; m->bytes = bytes; m->staging = nullptr; m->staging_done = nullptr;
+    m->repack_map = nullptr; m->frag_elems = 0; m->table_entries = 0;
     marl::MixerDeviceGuard guard(desc->device);
     hipError_t err = guard.ok ? hipMalloc(&m->image, bytes) : hipErrorInvalidDevice;
     if (err == hipSuccess) err = hipMemcpy(m->image, host, bytes, hipMemcpyHostToDevice);
@@ -435,6 +441,7 @@ void marl_mixer_destroy(marl_mixer *m)
     if (!m) return;
     marl::MixerDeviceGuard guard(m->desc.device);
     if (m->image) (void)hipFree(m->image);              // synchronises the device
+    if (m->repack_map) (void)hipFree(m->repack_map);
     if (m->staging) (void)hipHostFree(m->staging);
     if (m->staging_done) (void)hipEventDestroy(m->staging_done);
     delete m;
@@ -721,6 +728,60 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
         err = marl::launch_tn_product(m->planes, ar, states, R, M + 1, 0, marl::kExtraOnes, 1, 1, plan.chunk, partial, 0, gv2, 1, gv2, stream);
     }
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad products");
+    return MARL_OK;
+}
+
+int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights, float lr, void *hip_stream)
+{
+    if (!m || !weights || !grad_weights) return MARL_ERR_NULL;
+    if (!(lr == lr) || lr - lr != 0.0f) return MARL_ERR_BAD_ARG;
+    marl::MixerDeviceGuard guard(m->desc.device);
+    if (!guard.ok) return marl::report_device_error(hipErrorInvalidDevice, "hipSetDevice");
+    const size_t n_params = marl::mixer_params(&m->desc);
+    const size_t N = m->desc.n_agents, M = m->desc.embed, S = m->desc.state_dim, F = (N + 3) * M;
+    if (!m->repack_map) {
+        size_t bytes = 0, frag_bytes = 0;
+        {
+            std::vector<float> zeros(n_params, 0.0f);
+            char *host = marl::pack_mixer_image(m->desc, zeros.data(), &bytes, &frag_bytes);
+            if (!host) return MARL_ERR_NOMEM;
+            std::free(host);
+        }
+        std::vector<int32_t> map;
+        const size_t frag_elems = frag_bytes / 2;
+        const bool ok = marl::probe_fragment_map(n_params, frag_elems, [&](const float *w, uint16_t *out) {
+            size_t b2, f2;
+            char *host = marl::pack_mixer_image(m->desc, w, &b2, &f2);
+            if (!host) return false;
+            std::memcpy(out, host, frag_elems * 2);
+            std::free(host);
+            return true;
+        }, &map);
+        if (!ok) return MARL_ERR_NOMEM;
+        // the tables are copies: hb1 | hbb1 | hb2 | c1, then v2, then c2 (packed order of the parameters:
+        // Hw1, hb1, Hb1, hbb1, Hw2, hb2, V1, c1, v2, c2)
+        const size_t o_hb1 = N * M * S, o_hbb1 = o_hb1 + N * M + M * S, o_hb2 = o_hbb1 + M + M * S, o_c1 = o_hb2 + M + M * S;
+        const size_t o_v2 = o_c1 + M, o_c2 = o_v2 + M;
+        for (size_t i = 0; i < N * M; ++i) map.push_back((int32_t)(o_hb1 + i));
+        for (size_t i = 0; i < M; ++i) map.push_back((int32_t)(o_hbb1 + i));
+        for (size_t i = 0; i < M; ++i) map.push_back((int32_t)(o_hb2 + i));
+        for (size_t i = 0; i < M; ++i) map.push_back((int32_t)(o_c1 + i));
+        for (size_t i = 0; i < M; ++i) map.push_back((int32_t)(o_v2 + i));
+        map.push_back((int32_t)o_c2);
+        int32_t *dev = nullptr;
+        hipError_t err = hipMalloc(&dev, map.size() * sizeof(int32_t));
+        if (err != hipSuccess) return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : marl::report_device_error(err, "hipMalloc");
+        err = hipMemcpy(dev, map.data(), map.size() * sizeof(int32_t), hipMemcpyHostToDevice);
+        if (err != hipSuccess) { (void)hipFree(dev); return marl::report_device_error(err, "hipMemcpy"); }
+        m->repack_map = dev;
+        m->frag_elems = frag_elems;
+        m->table_entries = F + M + 1;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    hipError_t err = marl::launch_sgd_and_fragments(weights, grad_weights, lr, n_params, m->repack_map, m->frag_elems, m->image, stream);
+    if (err == hipSuccess)
+        err = marl::launch_copy_refresh(weights, m->repack_map + m->frag_elems, m->table_entries, const_cast<float *>(m->bias), stream);
+    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_sgd_step launch");
     return MARL_OK;
 }
 

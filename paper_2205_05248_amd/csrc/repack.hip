@@ -64,6 +64,13 @@ __global__ void repack_frag_kernel(const float *w, const int32_t *map, uint16_t 
     image[e] = (uint16_t)out;
 }
 
+// fp32 tables that are plain copies of parameters: dst[i] = w[src[i]]
+__global__ void copy_map_kernel(const float *w, const int32_t *src, float *dst, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = w[src[i]];
+}
+
 struct TableArgs {
     const float *w;
     char *image;
@@ -94,27 +101,23 @@ __global__ void repack_tables_kernel(TableArgs t)
 
 }  // namespace
 
-// Host: map[e] for every 16-bit element e of the fragment part of the image (bytes [0, off_w2_plain)).
-bool build_repack_map(const marl_qnet_desc &desc, size_t n_params, std::vector<int32_t> *map, PackedImage *layout)
+// Host: map[e] for every 16-bit element e of an image's fragment part, found by running its packer on the probe
+// vectors described at the top of this file.  pack(w, out) writes the frag_elems elements packed from w.
+bool probe_fragment_map(size_t n_params, size_t frag_elems, const FragPacker &pack, std::vector<int32_t> *map)
 {
     if (n_params >= (size_t)128 * 128 * 128) return false;
     std::vector<float> probe(n_params);
     std::vector<uint16_t> images[3];
-    size_t elems = 0;
     for (int k = 0; k < 3; ++k) {
         for (size_t i = 0; i < n_params; ++i) {
             const int digit = (int)((i >> (7 * k)) & 127);
             probe[i] = (float)(digit + 1) * (1.0f + 1.0f / 512.0f);
         }
-        PackedImage img{};
-        if (!pack_network(desc, probe.data(), &img)) return false;
-        elems = img.off_w2_plain / 2;
-        images[k].assign(reinterpret_cast<uint16_t *>(img.host), reinterpret_cast<uint16_t *>(img.host) + elems);
-        if (k == 0) { *layout = img; layout->host = nullptr; }
-        std::free(img.host);
+        images[k].assign(frag_elems, 0);
+        if (!pack(probe.data(), images[k].data())) return false;
     }
-    map->assign(elems, kNoSource);
-    for (size_t e = 0; e < elems; ++e) {
+    map->assign(frag_elems, kNoSource);
+    for (size_t e = 0; e < frag_elems; ++e) {
         if (!images[0][e] && !images[1][e] && !images[2][e]) continue;
         int32_t index = 0, plane = -1;
         for (int k = 0; k < 3; ++k) {
@@ -130,6 +133,25 @@ bool build_repack_map(const marl_qnet_desc &desc, size_t n_params, std::vector<i
         (*map)[e] = index | (plane ? kLowPlane : 0);
     }
     return true;
+}
+
+// The Q-network's image: fragments in bytes [0, off_w2_plain); also returns the image's layout.
+bool build_repack_map(const marl_qnet_desc &desc, size_t n_params, std::vector<int32_t> *map, PackedImage *layout)
+{
+    std::vector<float> zeros(n_params, 0.0f);
+    PackedImage first{};
+    if (!pack_network(desc, zeros.data(), &first)) return false;
+    std::free(first.host);
+    *layout = first;
+    layout->host = nullptr;
+    const size_t elems = first.off_w2_plain / 2;
+    return probe_fragment_map(n_params, elems, [&](const float *w, uint16_t *out) {
+        PackedImage img{};
+        if (!pack_network(desc, w, &img)) return false;
+        std::memcpy(out, img.host, elems * 2);
+        std::free(img.host);
+        return true;
+    }, map);
 }
 
 // Host: the map applied to `weights` with the kernel's arithmetic must give the packer's own image of them.
@@ -161,16 +183,28 @@ bool repack_map_reproduces_packer(const marl_qnet_desc &desc, const float *weigh
     return same;
 }
 
-hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout, int planes, const int32_t *map_dev,
-                           size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
-                           hipStream_t stream)
+hipError_t launch_sgd_and_fragments(float *weights, const float *grad, float lr, size_t n_params, const int32_t *map_dev,
+                                    size_t map_elems, void *image_dev, hipStream_t stream)
 {
     hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)((n_params + 255) / 256)), dim3(256), 0, stream, weights, grad, lr, n_params);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(repack_frag_kernel, dim3((unsigned)((map_elems + 255) / 256)), dim3(256), 0, stream, weights, map_dev,
                        static_cast<uint16_t *>(image_dev), map_elems);
-    err = hipGetLastError();
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_refresh(const float *weights, const int32_t *src_dev, size_t n, float *dst, hipStream_t stream)
+{
+    hipLaunchKernelGGL(copy_map_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, weights, src_dev, dst, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout, int planes, const int32_t *map_dev,
+                           size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
+                           hipStream_t stream)
+{
+    hipError_t err = launch_sgd_and_fragments(weights, grad, lr, n_params, map_dev, map_elems, image_dev, stream);
     if (err != hipSuccess) return err;
     TableArgs t{};
     t.w = weights; t.image = static_cast<char *>(image_dev);

@@ -79,6 +79,7 @@ def test_calls_reject_null_handles(lib):
                                      None, None, None) == -1
     assert lib.marl_qnet_grad_workspace_bytes(None, 1, 1, None) == -1
     assert lib.marl_mixer_grad_workspace_bytes(None, 1, 1, None) == -1
+    assert lib.marl_mixer_sgd_step(None, None, None, 0.1, None) == -1
     assert lib.marl_mixer_grad(None, 1, 1, None, None, None, None, 0, None, None, None) == -1
     assert lib.marl_qnet_grad(None, 1, 1, None, None, None, None, None, 0, None, None) == -1
     assert lib.marl_qnet_reserve_unroll(None, 1, 1) == -1

@@ -143,8 +143,8 @@ def test_learner_iterations_reduce_the_td_loss():
 def test_qmix_learner_iterations_reduce_the_loss():
     """The whole learner step of Alg. 3 with the mixing network, every stage in the library's kernels: unroll
     (online, frozen target), mixer forward + TD loss, mixer backward (parameter gradients and dL/dq_taken),
-    Q-network backward, parameter updates.  The mixer's update goes through its stream-ordered weight refresh.
-    Twelve iterations on one batch: the masked mean-squared TD loss must fall."""
+    Q-network backward, both parameter updates on the device.  Twelve iterations on one batch: the masked
+    mean-squared TD loss must fall."""
     cfg = dict(wl.config(1), B=16, T=20)
     dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
     N = dims[0]
@@ -175,11 +175,49 @@ def test_qmix_learner_iterations_reduce_the_loss():
         mixer.grad(state, q_taken, (-2.0 / count) * td, mws, gq, mgrad)          # td_err = filled (y_total - Q_total)
         online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
         online.sgd_step(master, grad, 0.0005)
-        mmaster -= 0.0005 * mgrad
-        mixer.set_weights(mmaster.cpu().numpy())
+        mixer.sgd_step(mmaster, mgrad, 0.0005)
     torch.cuda.synchronize()
     assert np.isfinite(losses).all(), losses
     assert losses[-1] < 0.8 * losses[0], losses
     assert all(b <= a * 1.05 for a, b in zip(losses, losses[1:])), losses
     for h in (online, target, mixer, mixer_tg):
         h.close()
+
+
+@pytest.mark.parametrize("ci,dtype", [(0, "fp32"), (1, "bf16"), (4, "bf16"), (4, "fp32")])
+def test_updated_mixer_equals_one_created_from_the_updated_weights(ci, dtype):
+    cfg = dict(wl.config(ci), dtype=dtype)
+    dims = wl.mixer_dims(cfg)
+    N = dims[0]
+    mw = wl.make_mixer_weights(cfg, 0)
+    rng = np.random.default_rng(ci)
+    g = rng.normal(size=mw.shape).astype(np.float32)
+    lr = 0.02
+    mixer = binding.Mixer(dims, mw, dtype)
+    master = torch.from_numpy(mw.copy()).cuda()
+    mixer.sgd_step(master, torch.from_numpy(g).cuda(), lr)
+    torch.cuda.synchronize()
+    want = mw - np.float32(lr) * g
+    np.testing.assert_array_equal(master.cpu().numpy(), want)
+    fresh = binding.Mixer(dims, want, dtype)
+    B, T = 5, 9
+    m = wl.make_mixer_inputs(cfg, B=B, T=T)
+    d = {k: torch.from_numpy(np.ascontiguousarray(m[k])).cuda()
+         for k in ("state", "q_taken", "next_max", "reward", "terminated", "filled")}
+    e = torch.from_numpy(rng.normal(size=(B, T)).astype(np.float32)).cuda()
+    results = []
+    for mx in (mixer, fresh):
+        outs = [torch.empty(B, T, device="cuda") for _ in range(3)]
+        mx.td(None, d["state"], d["q_taken"], d["next_max"], d["reward"], d["terminated"], d["filled"], m["gamma"], *outs)
+        ws = torch.empty(mx.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+        gq, gw = torch.empty(B, T, N, device="cuda"), torch.empty(mw.size, device="cuda")
+        mx.grad(d["state"], d["q_taken"], e, ws, gq, gw)
+        torch.cuda.synchronize()
+        results.append([o.cpu().numpy() for o in outs] + [gq.cpu().numpy(), gw.cpu().numpy()])
+    for a, b in zip(*results):
+        np.testing.assert_array_equal(a, b)
+    import ctypes
+    lib, vp = binding.load(), ctypes.c_void_p
+    assert lib.marl_mixer_sgd_step(vp(mixer.handle), vp(master.data_ptr()), vp(master.data_ptr()), float("inf"), None) == -5
+    assert lib.marl_mixer_sgd_step(vp(mixer.handle), None, vp(master.data_ptr()), 0.1, None) == -1
+    mixer.close(); fresh.close()
