@@ -377,6 +377,67 @@ def grad_section(ci, with_cpu, launches=10):
     return out
 
 
+def learner_section(ci, launches=10):
+    """One whole learner iteration of Alg. 3 on the workload's batch, every stage in the library's kernels and
+    chained on one stream with no host round trip: unroll (online + target), mixer forward with the TD loss, mixer
+    backward, Q-network backward, both parameter updates (lr = 0: the weights stay put while timing).  The only
+    work outside the library is one element-wise tensor operation, dL/dQ_total = -2 td_err / count."""
+    import torch
+    from paper_2205_05248_amd import binding, workloads as wl
+    cfg = wl.config(ci)
+    dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
+    N = dims[0]
+    B, T = cfg["B"], cfg["T"]
+    w, mw = wl.make_weights(cfg, 0), wl.make_mixer_weights(cfg, 0)
+    online, target = binding.QNet(dims, w, cfg["dtype"]), binding.QNet(dims, wl.make_weights(cfg, 1), cfg["dtype"])
+    mixer, mixer_tg = binding.Mixer(mdims, mw, cfg["dtype"]), binding.Mixer(mdims, wl.make_mixer_weights(cfg, 1), cfg["dtype"])
+    try:
+        need, mneed = online.grad_workspace_bytes(B, T), mixer.grad_workspace_bytes(B, T)
+    except binding.MarlError:
+        for h in (online, target, mixer, mixer_tg):
+            h.close()
+        return {"ms": None, "note": "the backward passes do not serve this shape"}
+    u = wl.make_unroll_inputs(cfg)
+    d = {k: torch.from_numpy(np.ascontiguousarray(u[k])).cuda()
+         for k in ("obs", "avail", "actions", "reward", "terminated", "filled")}
+    state = torch.from_numpy(wl.make_mixer_inputs(cfg)["state"]).cuda()
+    q_taken, next_max, y = (torch.empty(B, T, N, device="cuda") for _ in range(3))
+    q_total, y_total, td = (torch.empty(B, T, device="cuda") for _ in range(3))
+    loss2 = torch.empty(2, device="cuda")
+    master, grad = torch.from_numpy(w.copy()).cuda(), torch.empty(w.size, device="cuda")
+    mmaster, mgrad = torch.from_numpy(mw.copy()).cuda(), torch.empty(mw.size, device="cuda")
+    gq = torch.empty(B, T, N, device="cuda")
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    mws = torch.empty(mneed, dtype=torch.uint8, device="cuda")
+
+    def iteration():
+        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                         u["gamma"], q_taken, next_max, y)
+        mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
+                 q_total, y_total, td, loss2)
+        e = td * (-2.0 / loss2[1])
+        mixer.grad(state, q_taken, e, mws, gq, mgrad)
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
+        online.sgd_step(master, grad, 0.0)
+        mixer.sgd_step(mmaster, mgrad, 0.0)
+
+    for _ in range(2):
+        iteration()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(launches):
+        iteration()
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / launches
+    for h in (online, target, mixer, mixer_tg):
+        h.close()
+    return {"ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "agent_steps_per_s": B * T * N / (ms * 1e-3),
+            "stages": "unroll_td (2 networks) + mixer_td + mixer_grad + qnet_grad + qnet_sgd_step + mixer_sgd_step",
+            "config": {"B": B, "T": T, "n_agents": N}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -482,6 +543,7 @@ def main():
     }
     out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
     out["qnet_grad"] = grad_section(args.config, not args.no_cpu_baseline)
+    out["learner_iteration"] = learner_section(args.config)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(args.config)
     print(json.dumps(out))

@@ -301,14 +301,17 @@ struct TnGemmArgs {
 };
 
 constexpr int kTnThreads = 512;        // eight waves: two per SIMD
+constexpr int kTnBatchMax = 16;        // products of one shape launched together (blockIdx.y picks one)
+struct TnGemmBatch { TnGemmArgs g[kTnBatchMax]; };
 
 // One workgroup per chunk of samples computes the whole result, so that every operand element is read from
 // memory once.  Wave w owns result row blocks w, w + 8, .. (PBW of them) and all QBN column blocks.  P: bf16
 // planes per operand, the network's own: 2 = every value as bf16 high part + bf16 of the remainder, three MFMAs
 // per product; 1 = values rounded to bf16, one MFMA.
 template <int PBW, int QBN, int P>
-__global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(TnGemmArgs g)
+__global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatch batch)
 {
+    const TnGemmArgs g = batch.g[blockIdx.y];
     constexpr int kPp = 16 * 8 * PBW;                              // result rows, padded = columns of A staged
     constexpr int kSets = (kPp + 16 * QBN + 63) / 64;              // sets of 64 staged columns (A's, then B's)
     constexpr int kSetsPerWave = (kSets + 1) / 2;
@@ -457,9 +460,11 @@ struct TnReduceArgs {
     int row_shift, w_cols, ld_w;
     float *dst_w, *dst_b;
 };
+struct TnReduceBatch { TnReduceArgs r[kTnBatchMax]; };
 
-__global__ void tn_reduce_kernel(TnReduceArgs g)
+__global__ void tn_reduce_kernel(const TnReduceBatch batch)
 {
+    const TnReduceArgs g = batch.r[blockIdx.y];
     const int cols = g.Q + g.n_extra;
     const int idx = blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= g.P * cols) return;
@@ -499,7 +504,7 @@ namespace {
 size_t align_up(size_t v) { return (v + 255) / 256 * 256; }
 
 struct Plan {
-    size_t off_h, off_x, off_da, off_dpre1, off_dq, off_partial, bytes;
+    size_t off_h, off_x, off_da, off_dpre1, off_dq, off_partial, partial_bytes, bytes;
     int a16, chunks, chunk;
 };
 
@@ -518,21 +523,14 @@ Plan make_plan(const NetFrags &net, int B, int T)
     p.off_da = off;     off = align_up(off + R * T * 4 * H * 4);
     p.off_dpre1 = off;  off = align_up(off + R * T * H * 4);
     p.off_dq = off;     off = align_up(off + R * T * p.a16 * 4);
-    // the largest of the four products' partial results
-    auto part = [&](size_t P, size_t Qt) { return (size_t)p.chunks * (P > 128 ? 384 : 128) * ((Qt + 15) / 16 * 16) * 4; };
-    size_t need = part(3 * H, H + 1);
-    need = std::max(need, part(H, (size_t)net.D + net.N));
-    need = std::max(need, part(p.a16, H + 1));
+    // the four products run together: room for all their partial results
+    const long chunks_real = (M + p.chunk - 1) / p.chunk;
+    auto part = [&](size_t P, size_t Qt) { return (size_t)chunks_real * (P > 128 ? 384 : 128) * ((Qt + 15) / 16 * 16) * 4; };
+    const size_t need = 2 * part(3 * H, H + 1) + part(H, (size_t)net.D + net.N) + part(net.A, H + 1);
+    p.partial_bytes = need;
     p.off_partial = off; off = align_up(off + need);
     p.bytes = off;
     return p;
-}
-
-hipError_t run_product(int planes, const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra, int N,
-                       const Plan &plan, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
-                       hipStream_t stream)
-{
-    return launch_tn_product(planes, a, b, M, P, Q, extra_mode, n_extra, N, plan.chunk, partial, row_shift, dst_w, ld_w, dst_b, stream);
 }
 
 template <int H, int P, int NW>
@@ -554,42 +552,70 @@ size_t tn_partial_bytes(long M, int chunk, int P, int q_total)
     return chunks * (P > 128 ? 384 : 128) * (size_t)((q_total + 15) / 16 * 16) * sizeof(float);
 }
 
-hipError_t launch_tn_product(int planes, const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra,
-                             int N, int chunk, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
-                             hipStream_t stream)
+// Launches the products of `list` (all over the same M samples, chunks of `chunk`): those of one shape go
+// together in one launch (up to kTnBatchMax), then their partial sums are reduced, again in one launch.
+hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long M, int chunk, float *partial,
+                              size_t partial_bytes, hipStream_t stream)
 {
-    TnGemmArgs g{};
-    g.a = a; g.b = b; g.M = (int)M; g.P = P; g.Q = Q; g.extra_mode = extra_mode; g.n_extra = n_extra; g.N = N;
-    g.qp = (Q + n_extra + 15) / 16 * 16;
-    g.chunk = chunk;
-    g.partial = partial;
-    // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
-    const bool wide_rows = P > 128;
-    if ((wide_rows && (P > 384 || g.qp > 144)) || (!wide_rows && g.qp > 336)) return hipErrorInvalidValue;
-    const int p_pad = wide_rows ? 384 : 128, chunks = (int)((M + chunk - 1) / chunk);
-    const size_t lds = (size_t)(planes == 1 ? 2 : 1) * planes * (p_pad + g.qp) * 80;     // 80 bytes per staged column and plane
-    hipError_t err = hipErrorInvalidValue;
-#define MARL_TN(PBW, QBN, PL)                                                                            \
+    const int chunks = (int)((M + chunk - 1) / chunk);
+    int done = 0;
+    while (done < count) {
+        TnGemmBatch wide{}, narrow{};
+        TnReduceBatch red{};
+        int n_wide = 0, n_narrow = 0, n_red = 0, max_q_wide = 0, max_q_narrow = 0, max_total = 0;
+        size_t used = 0;
+        int taken = done;
+        for (; taken < count; ++taken) {
+            const TnProduct &t = list[taken];
+            TnGemmArgs g{};
+            g.a = t.a; g.b = t.b; g.M = (int)M; g.P = t.P; g.Q = t.Q; g.extra_mode = t.extra_mode; g.n_extra = t.n_extra;
+            g.N = t.N > 0 ? t.N : 1;
+            g.qp = (t.Q + t.n_extra + 15) / 16 * 16;
+            g.chunk = chunk;
+            // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
+            const bool is_wide = t.P > 128;
+            if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;
+            const size_t bytes = tn_partial_bytes(M, chunk, t.P, t.Q + t.n_extra);
+            if (bytes > partial_bytes) return hipErrorInvalidValue;
+            if (used + bytes > partial_bytes || (is_wide ? n_wide : n_narrow) == kTnBatchMax || n_red == kTnBatchMax) break;
+            g.partial = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + used);
+            used += bytes;
+            if (is_wide) { wide.g[n_wide++] = g; max_q_wide = std::max(max_q_wide, g.qp); }
+            else         { narrow.g[n_narrow++] = g; max_q_narrow = std::max(max_q_narrow, g.qp); }
+            TnReduceArgs r{};
+            r.partial = g.partial; r.chunks = chunks; r.P = t.P; r.p_pad = is_wide ? 384 : 128; r.qp = g.qp;
+            r.Q = t.Q; r.n_extra = t.n_extra; r.extra_mode = t.extra_mode;
+            r.row_shift = t.row_shift; r.w_cols = t.Q; r.ld_w = t.ld_w; r.dst_w = t.dst_w; r.dst_b = t.dst_b;
+            red.r[n_red++] = r;
+            max_total = std::max(max_total, t.P * (t.Q + t.n_extra));
+        }
+        hipError_t err = hipSuccess;
+#define MARL_TN(PBW, QBN, PL, BATCH, COUNT, PPAD, MAXQ)                                                  \
     do {                                                                                                 \
+        const size_t lds = (size_t)(PL == 1 ? 2 : 1) * PL * (PPAD + MAXQ) * 80;      /* 80 bytes per staged column and plane */ \
         err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL>>(kLdsLimit);                                  \
         if (err != hipSuccess) return err;                                                               \
-        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL>), dim3(chunks), dim3(kTnThreads), lds, stream, g); \
+        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL>), dim3(chunks, COUNT), dim3(kTnThreads), lds, stream, BATCH); \
+        err = hipGetLastError();                                                                         \
+        if (err != hipSuccess) return err;                                                               \
     } while (0)
-    if (wide_rows) { if (planes == 2) MARL_TN(3, 9, 2); else MARL_TN(3, 9, 1); }
-    else           { if (planes == 2) MARL_TN(1, 21, 2); else MARL_TN(1, 21, 1); }
+        if (n_wide) { if (planes == 2) MARL_TN(3, 9, 2, wide, n_wide, 384, max_q_wide); else MARL_TN(3, 9, 1, wide, n_wide, 384, max_q_wide); }
+        if (n_narrow) { if (planes == 2) MARL_TN(1, 21, 2, narrow, n_narrow, 128, max_q_narrow); else MARL_TN(1, 21, 1, narrow, n_narrow, 128, max_q_narrow); }
 #undef MARL_TN
-    err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    TnReduceArgs r{};
-    r.partial = partial; r.chunks = chunks; r.P = P; r.p_pad = p_pad; r.qp = g.qp;
-    r.Q = Q; r.n_extra = n_extra; r.extra_mode = extra_mode;
-    r.row_shift = row_shift; r.w_cols = Q; r.ld_w = ld_w; r.dst_w = dst_w; r.dst_b = dst_b;
-    const int total = P * (Q + n_extra);
-    hipLaunchKernelGGL(tn_reduce_kernel, dim3((total + 255) / 256), dim3(256), 0, stream, r);
-    err = hipGetLastError();
-    if (err != hipSuccess || extra_mode != kExtraAgent) return err;
-    hipLaunchKernelGGL(bias_from_columns_kernel, dim3((P + 255) / 256), dim3(256), 0, stream, dst_w, P, ld_w, Q, n_extra, dst_b);
-    return hipGetLastError();
+        hipLaunchKernelGGL(tn_reduce_kernel, dim3((max_total + 255) / 256, n_red), dim3(256), 0, stream, red);
+        err = hipGetLastError();
+        if (err != hipSuccess) return err;
+        for (int i = done; i < taken; ++i)
+            if (list[i].extra_mode == kExtraAgent) {
+                const TnProduct &t = list[i];
+                hipLaunchKernelGGL(bias_from_columns_kernel, dim3((t.P + 255) / 256), dim3(256), 0, stream, t.dst_w, t.P, t.ld_w, t.Q,
+                                   t.n_extra, t.dst_b);
+                err = hipGetLastError();
+                if (err != hipSuccess) return err;
+            }
+        done = taken;
+    }
+    return hipSuccess;
 }
 
 
@@ -640,13 +666,13 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     const RowMap obs_rows{obs, (long)S * N * D, TN, D};
     const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16};
     // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
-    err = run_product(net.planes, da_i, x_rows, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 2 * H, gWih, H, gbih, stream);
-    if (err != hipSuccess) return err;
-    err = run_product(net.planes, da_h, h_prev, M, 3 * H, H, kExtraOnes, 1, N, plan, partial, 0, gWhh, H, gbhh, stream);
-    if (err != hipSuccess) return err;
-    err = run_product(net.planes, pre_rows, obs_rows, M, H, D, kExtraAgent, N, N, plan, partial, 0, gW1, D + N, gb1, stream);
-    if (err != hipSuccess) return err;
-    return run_product(net.planes, dq_rows, h_new, M, A, H, kExtraOnes, 1, N, plan, partial, 0, gW2, H, gb2, stream);
+    const TnProduct products[4] = {
+        {da_i, x_rows, 3 * H, H, kExtraOnes, 1, N, 2 * H, H, gWih, gbih},
+        {da_h, h_prev, 3 * H, H, kExtraOnes, 1, N, 0, H, gWhh, gbhh},
+        {pre_rows, obs_rows, H, D, kExtraAgent, N, N, 0, D + N, gW1, gb1},
+        {dq_rows, h_new, A, H, kExtraOnes, 1, N, 0, H, gW2, gb2},
+    };
+    return launch_tn_products(net.planes, products, 4, M, plan.chunk, partial, plan.partial_bytes, stream);
 }
 
 }  // namespace marl

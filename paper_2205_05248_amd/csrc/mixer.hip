@@ -607,7 +607,7 @@ __global__ __launch_bounds__(256) void mixer_back_kernel(const MixerBackArgs a)
 
 struct MixerGradPlan {
     int ldd, chunk;
-    size_t off_dgen, off_partial, bytes;
+    size_t off_dgen, off_partial, partial_bytes, bytes;
 };
 
 MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
@@ -616,11 +616,14 @@ MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
     const long R = (long)B * T;
     const int F = (d.n_agents + 3) * d.embed;
     p.ldd = (F + d.embed + 1 + 3) / 4 * 4;
-    const long chunks = std::min<long>(256, (R + 31) / 32);
+    // few samples (B T, not B T N) and many products that run side by side: chunks of about 256 transitions
+    const long chunks = std::max<long>(1, std::min<long>(256, R / 256));
     p.chunk = (int)(((R + chunks - 1) / chunks + 31) / 32 * 32);
     size_t off = 0;
     p.off_dgen = off;    off = (off + (size_t)R * p.ldd * 4 + 255) / 256 * 256;
-    p.off_partial = off; off = (off + tn_partial_bytes(R, p.chunk, 384, 144) + 255) / 256 * 256;      // the larger of the two shapes' needs
+    // room for sixteen of the largest partial results: the products run sixteen at a time
+    p.partial_bytes = 16 * tn_partial_bytes(R, p.chunk, 384, 144);
+    p.off_partial = off; off = (off + p.partial_bytes + 255) / 256 * 256;
     p.bytes = off;
     return p;
 }
@@ -701,7 +704,8 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     const marl::RowMap states{state, (long)(T + 1) * S, T, S};
     // one matrix: rows [r0, r0 + P) of it are adjoint columns [col0 + r0, ..); state columns in slices, the
     // column of ones (the bias) rides with the last slice
-    auto matrix = [&](int col0, int rows_total, float *dst_w, float *dst_b) -> hipError_t {
+    std::vector<marl::TnProduct> products;
+    auto matrix = [&](int col0, int rows_total, float *dst_w, float *dst_b) {
         const bool wide = rows_total > 128;
         const int p_step = wide ? 384 : 128, q_step = wide ? 128 : 320;
         for (int r0 = 0; r0 < rows_total; r0 += p_step)
@@ -711,22 +715,20 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
                 marl::RowMap ar = plain, br = states;
                 ar.base = dgen + col0 + r0;
                 br.base = state + k0;
-                const hipError_t e2 = marl::launch_tn_product(m->planes, ar, br, R, P, Q, last ? marl::kExtraOnes : marl::kExtraNone,
-                                                              last ? 1 : 0, 1, plan.chunk, partial, 0, dst_w + (size_t)r0 * S + k0, S,
-                                                              dst_b + r0, stream);
-                if (e2 != hipSuccess) return e2;
+                products.push_back({ar, br, P, Q, last ? marl::kExtraOnes : marl::kExtraNone, last ? 1 : 0, 1, 0, S,
+                                    dst_w + (size_t)r0 * S + k0, dst_b + r0});
             }
-        return hipSuccess;
     };
-    err = matrix(0, N * M, gHw1, ghb1);
-    if (err == hipSuccess) err = matrix(N * M, M, gHb1, ghbb1);
-    if (err == hipSuccess) err = matrix((N + 1) * M, M, gHw2, ghb2);
-    if (err == hipSuccess) err = matrix((N + 2) * M, M, gV1, gc1);
-    if (err == hipSuccess) {        // v2 and c2: the last M + 1 adjoint columns against the column of ones alone
+    matrix(0, N * M, gHw1, ghb1);
+    matrix(N * M, M, gHb1, ghbb1);
+    matrix((N + 1) * M, M, gHw2, ghb2);
+    matrix((N + 2) * M, M, gV1, gc1);
+    {        // v2 and c2: the last M + 1 adjoint columns against the column of ones alone
         marl::RowMap ar = plain;
         ar.base = dgen + F;
-        err = marl::launch_tn_product(m->planes, ar, states, R, M + 1, 0, marl::kExtraOnes, 1, 1, plan.chunk, partial, 0, gv2, 1, gv2, stream);
+        products.push_back({ar, states, M + 1, 0, marl::kExtraOnes, 1, 1, 0, 1, gv2, gv2});
     }
+    err = marl::launch_tn_products(m->planes, products.data(), (int)products.size(), R, plan.chunk, partial, plan.partial_bytes, stream);
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad products");
     return MARL_OK;
 }

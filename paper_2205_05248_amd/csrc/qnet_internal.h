@@ -158,15 +158,20 @@ struct RowMap {
 };
 // Columns appended to B on the fly: one column of ones, or N one-hot columns of (m % N).
 enum ExtraCols : int { kExtraNone = 0, kExtraOnes = 1, kExtraAgent = 2 };
-// The samples are cut into chunks of `chunk` (a multiple of 32), one workgroup each; `partial` holds
-// tn_partial_bytes.  Shapes served: P <= 384 with Q + extra <= 144, or P <= 128 with Q + extra <= 336.
-// planes: 2 = operands as bf16 pairs (three MFMAs per product), 1 = rounded to bf16.  The sum of the chunks
-// goes to dst_w[((p + row_shift) % P) * ld_w + q] for q < Q (and the agent columns, which continue the row),
-// the column of ones to dst_b[(p + row_shift) % P].
+// The samples are cut into chunks of `chunk` (a multiple of 32), one workgroup each and product.  Shapes served:
+// P <= 384 with Q + extra <= 144, or P <= 128 with Q + extra <= 336.  planes: 2 = operands as bf16 pairs (three
+// MFMAs per product), 1 = rounded to bf16.  The sum of the chunks goes to dst_w[((p + row_shift) % P) * ld_w + q]
+// for q < Q (and the agent columns, which continue the row), the column of ones to dst_b[(p + row_shift) % P].
+struct TnProduct {
+    RowMap a, b;
+    int P, Q, extra_mode, n_extra, N, row_shift, ld_w;
+    float *dst_w, *dst_b;
+};
+// tn_partial_bytes: what one product needs of `partial`; launch_tn_products runs the list (same M and chunk for
+// all), as many at a time as `partial` holds.
 size_t tn_partial_bytes(long M, int chunk, int P, int q_total);
-hipError_t launch_tn_product(int planes, const RowMap &a, const RowMap &b, long M, int P, int Q, int extra_mode, int n_extra,
-                             int N, int chunk, float *partial, int row_shift, float *dst_w, int ld_w, float *dst_b,
-                             hipStream_t stream);
+hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long M, int chunk, float *partial,
+                              size_t partial_bytes, hipStream_t stream);
 
 // Backward pass (bptt.hip): the gradient of sum(grad_q * q_taken) with respect to the packed parameters.
 // `fits`: the network runs on the fused unroll kernel and its widest layer fits the gradient product.
