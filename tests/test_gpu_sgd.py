@@ -221,3 +221,71 @@ def test_updated_mixer_equals_one_created_from_the_updated_weights(ci, dtype):
     assert lib.marl_mixer_sgd_step(vp(mixer.handle), vp(master.data_ptr()), vp(master.data_ptr()), float("inf"), None) == -5
     assert lib.marl_mixer_sgd_step(vp(mixer.handle), None, vp(master.data_ptr()), 0.1, None) == -1
     mixer.close(); fresh.close()
+
+
+def test_learner_iteration_replays_from_a_hip_graph():
+    """The whole learner iteration captured into a HIP graph after two eager iterations (which build the update
+    maps and set the launch attributes), then replayed: four replays, with eager work and synchronisation in
+    between, leave exactly the weights that four eager iterations leave (the iteration reads and updates the
+    weights, so any replay that went wrong shows in every later one)."""
+    cfg = dict(wl.config(1), B=8, T=15)
+    dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
+    N = dims[0]
+    B, T = 8, 15
+    w, mw = wl.make_weights(cfg, 0), wl.make_mixer_weights(cfg, 0)
+    online, target = binding.QNet(dims, w), binding.QNet(dims, wl.make_weights(cfg, 1))
+    mixer, mixer_tg = binding.Mixer(mdims, mw), binding.Mixer(mdims, wl.make_mixer_weights(cfg, 1))
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    d = pu.to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
+    state = torch.from_numpy(wl.make_mixer_inputs(cfg, B=B, T=T)["state"]).cuda()
+    q_taken, next_max, y = (torch.empty(B, T, N, device="cuda") for _ in range(3))
+    q_total, y_total, td = (torch.empty(B, T, device="cuda") for _ in range(3))
+    loss2, e = torch.empty(2, device="cuda"), torch.empty(B, T, device="cuda")
+    master, grad = torch.from_numpy(w.copy()).cuda(), torch.empty(w.size, device="cuda")
+    mmaster, mgrad = torch.from_numpy(mw.copy()).cuda(), torch.empty(mw.size, device="cuda")
+    gq = torch.empty(B, T, N, device="cuda")
+    ws = torch.empty(online.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    mws = torch.empty(mixer.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+
+    def iteration():
+        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                         u["gamma"], q_taken, next_max, y)
+        mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
+                 q_total, y_total, td, loss2)
+        torch.mul(td, -2.0 / (B * T), out=e)
+        mixer.grad(state, q_taken, e, mws, gq, mgrad)
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
+        online.sgd_step(master, grad, 0.0005)
+        mixer.sgd_step(mmaster, mgrad, 0.0005)
+
+    def reset():
+        master.copy_(torch.from_numpy(w)); mmaster.copy_(torch.from_numpy(mw))
+        online.set_weights(w); mixer.set_weights(mw)
+        torch.cuda.synchronize()
+
+    for _ in range(2):
+        iteration()
+    reset()
+    for _ in range(4):
+        iteration()
+    torch.cuda.synchronize()
+    eager = (master.clone(), mmaster.clone(), grad.clone(), mgrad.clone())
+    reset()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            iteration()
+    torch.cuda.synchronize()
+    reset()                                               # capture does not run anything, but start from the same state anyway
+    scratch = torch.empty(1 << 20, device="cuda")
+    for _ in range(4):
+        graph.replay()
+        scratch.normal_()                                 # eager work of the program between the replays
+        torch.cuda.synchronize()
+    for a, b in zip(eager, (master, mmaster, grad, mgrad)):
+        assert torch.equal(a, b)
+    assert not torch.equal(master, torch.from_numpy(w).cuda())
+    for h in (online, target, mixer, mixer_tg):
+        h.close()
