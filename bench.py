@@ -431,9 +431,28 @@ def learner_section(ci, launches=10):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / launches
+    # the same iteration replayed from a HIP graph (the calls allocate nothing and record no memset)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            iteration()
+    torch.cuda.synchronize()
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(launches):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    ms_graph = a.elapsed_time(b) / launches
+    del graph
     for h in (online, target, mixer, mixer_tg):
         h.close()
-    return {"ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "agent_steps_per_s": B * T * N / (ms * 1e-3),
+    return {"ms": ms, "ms_graph_replay": ms_graph, "transitions_per_s": B * T / (ms * 1e-3),
+            "agent_steps_per_s": B * T * N / (ms * 1e-3),
             "stages": "unroll_td (2 networks) + mixer_td + mixer_grad + qnet_grad + qnet_sgd_step + mixer_sgd_step",
             "config": {"B": B, "T": T, "n_agents": N}}
 
