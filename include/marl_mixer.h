@@ -137,6 +137,10 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
  */
 int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights, float lr, void *hip_stream);
 
+/* RMSprop in place of plain descent; arguments and arithmetic as marl_qnet_rmsprop_step. */
+int marl_mixer_rmsprop_step(marl_mixer *m, float *weights, const float *grad_weights, float *sq_avg,
+                            float lr, float alpha, float eps, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

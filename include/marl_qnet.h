@@ -260,6 +260,18 @@ int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, 
                        void *hip_stream);
 
 /*
+ * The same with RMSprop in place of plain descent:
+ *   sq_avg[p]  <- alpha * sq_avg[p] + (1 - alpha) * grad[p]^2
+ *   weights[p] <- weights[p] - lr * grad[p] / (sqrt(sq_avg[p]) + eps)
+ * every operation rounded to fp32 on its own, in the order written (products before sums), so that a host
+ * reference reproduces it bit for bit.  sq_avg: dev [marl_param_count] f32, in and out, the caller's (start it
+ * at zero).  alpha in [0,1], eps > 0 and finite, lr finite: MARL_ERR_BAD_ARG otherwise.  Everything else as
+ * marl_qnet_sgd_step.
+ */
+int marl_qnet_rmsprop_step(marl_qnet *q, float *weights, const float *grad_weights, float *sq_avg,
+                           float lr, float alpha, float eps, void *hip_stream);
+
+/*
  * Host-only self-check of the map marl_qnet_sgd_step rebuilds the image with: applied to
  * host_weights with the device kernel's arithmetic it must reproduce, bit for bit, the fragment part of
  * the image marl_qnet_create would build.  Touches no GPU.  MARL_OK, MARL_ERR_MISMATCH if it does not

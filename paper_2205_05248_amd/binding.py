@@ -20,13 +20,13 @@ MARL_DTYPE_BF16 = 1
 DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
-           "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_sgd_step", "marl_qnet_check_refresh_map",
+           "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_sgd_step", "marl_qnet_rmsprop_step", "marl_qnet_check_refresh_map",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
 MIXER_EXPORTS = ["marl_mixer_param_count", "marl_mixer_create", "marl_mixer_destroy", "marl_mixer_td",
-                 "marl_mixer_set_weights", "marl_mixer_grad_workspace_bytes", "marl_mixer_grad", "marl_mixer_sgd_step"]
+                 "marl_mixer_set_weights", "marl_mixer_grad_workspace_bytes", "marl_mixer_grad", "marl_mixer_sgd_step", "marl_mixer_rmsprop_step"]
 
 
 class MarlError(RuntimeError):
@@ -85,6 +85,10 @@ def load():
         lib.marl_qnet_grad.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
         lib.marl_qnet_check_refresh_map.restype = ctypes.c_int
         lib.marl_qnet_check_refresh_map.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t]
+        lib.marl_qnet_rmsprop_step.restype = ctypes.c_int
+        lib.marl_qnet_rmsprop_step.argtypes = [vp, vp, vp, vp, f32, f32, f32, vp]
+        lib.marl_mixer_rmsprop_step.restype = ctypes.c_int
+        lib.marl_mixer_rmsprop_step.argtypes = [vp, vp, vp, vp, f32, f32, f32, vp]
         lib.marl_qnet_sgd_step.restype = ctypes.c_int
         lib.marl_qnet_sgd_step.argtypes = [vp, vp, vp, f32, vp]
         lib.marl_qnet_reserve_unroll.restype = ctypes.c_int
@@ -327,6 +331,12 @@ class QNet:
         marl_unroll_td_double(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
                               gamma, q_taken, next_max, td_target, next_action, q_all, episode_index)
 
+    def rmsprop_step(self, weights, grad_weights, sq_avg, lr, alpha=0.99, eps=1e-5):
+        n = weights.numel()
+        check(load().marl_qnet_rmsprop_step(ctypes.c_void_p(self.handle), _dev(weights, "f32", (n,), "weights"),
+                                            _dev(grad_weights, "f32", (n,), "grad_weights"), _dev(sq_avg, "f32", (n,), "sq_avg"),
+                                            float(lr), float(alpha), float(eps), _stream()))
+
     def sgd_step(self, weights, grad_weights, lr):
         n = weights.numel()
         check(load().marl_qnet_sgd_step(ctypes.c_void_p(self.handle), _dev(weights, "f32", (n,), "weights"),
@@ -421,6 +431,12 @@ class Mixer:
 
     def set_weights(self, weights):
         marl_mixer_set_weights(self.handle, weights)
+
+    def rmsprop_step(self, weights, grad_weights, sq_avg, lr, alpha=0.99, eps=1e-5):
+        n = weights.numel()
+        check(load().marl_mixer_rmsprop_step(ctypes.c_void_p(self.handle), _dev(weights, "f32", (n,), "weights"),
+                                             _dev(grad_weights, "f32", (n,), "grad_weights"), _dev(sq_avg, "f32", (n,), "sq_avg"),
+                                             float(lr), float(alpha), float(eps), _stream()))
 
     def sgd_step(self, weights, grad_weights, lr):
         n = weights.numel()

@@ -463,10 +463,11 @@ int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_we
     return marl::repack_map_reproduces_packer(*desc, host_weights, n_weights) ? MARL_OK : MARL_ERR_MISMATCH;
 }
 
-int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, float lr, void *hip_stream)
+namespace {
+bool is_finite(float v) { return v == v && v - v == 0.0f; }
+
+int qnet_update(marl_qnet *q, float *weights, const float *grad_weights, float lr, const marl::UpdateRule &rule, void *hip_stream)
 {
-    if (!q || !weights || !grad_weights) return MARL_ERR_NULL;
-    if (!(lr == lr) || lr - lr != 0.0f) return MARL_ERR_BAD_ARG;                 // NaN or infinite
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     if (!q->repack_map) {
@@ -481,8 +482,26 @@ int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, 
         q->repack_elems = map.size();
     }
     MARL_HIP(marl::launch_sgd_step(q->desc, q->layout, q->net.planes, q->repack_map, q->repack_elems, q->dev_weights, weights,
-                                   grad_weights, q->n_params, lr, static_cast<hipStream_t>(hip_stream)));
+                                   grad_weights, q->n_params, lr, static_cast<hipStream_t>(hip_stream), rule));
     return MARL_OK;
+}
+}  // namespace
+
+int marl_qnet_sgd_step(marl_qnet *q, float *weights, const float *grad_weights, float lr, void *hip_stream)
+{
+    if (!q || !weights || !grad_weights) return MARL_ERR_NULL;
+    if (!is_finite(lr)) return MARL_ERR_BAD_ARG;
+    return qnet_update(q, weights, grad_weights, lr, marl::UpdateRule(), hip_stream);
+}
+
+int marl_qnet_rmsprop_step(marl_qnet *q, float *weights, const float *grad_weights, float *sq_avg, float lr, float alpha,
+                           float eps, void *hip_stream)
+{
+    if (!q || !weights || !grad_weights || !sq_avg) return MARL_ERR_NULL;
+    if (!is_finite(lr) || !(alpha >= 0.0f && alpha <= 1.0f) || !(eps > 0.0f) || !is_finite(eps)) return MARL_ERR_BAD_ARG;
+    marl::UpdateRule rule;
+    rule.sq_avg = sq_avg; rule.alpha = alpha; rule.eps = eps;
+    return qnet_update(q, weights, grad_weights, lr, rule, hip_stream);
 }
 
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable)

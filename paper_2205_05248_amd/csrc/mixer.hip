@@ -733,10 +733,9 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     return MARL_OK;
 }
 
-int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights, float lr, void *hip_stream)
+namespace {
+int mixer_update(marl_mixer *m, float *weights, const float *grad_weights, float lr, const marl::UpdateRule &rule, void *hip_stream)
 {
-    if (!m || !weights || !grad_weights) return MARL_ERR_NULL;
-    if (!(lr == lr) || lr - lr != 0.0f) return MARL_ERR_BAD_ARG;
     marl::MixerDeviceGuard guard(m->desc.device);
     if (!guard.ok) return marl::report_device_error(hipErrorInvalidDevice, "hipSetDevice");
     const size_t n_params = marl::mixer_params(&m->desc);
@@ -780,11 +779,30 @@ int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights
         m->table_entries = F + M + 1;
     }
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-    hipError_t err = marl::launch_sgd_and_fragments(weights, grad_weights, lr, n_params, m->repack_map, m->frag_elems, m->image, stream);
+    hipError_t err = marl::launch_sgd_and_fragments(weights, grad_weights, lr, n_params, m->repack_map, m->frag_elems, m->image, stream, rule);
     if (err == hipSuccess)
         err = marl::launch_copy_refresh(weights, m->repack_map + m->frag_elems, m->table_entries, const_cast<float *>(m->bias), stream);
-    if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_sgd_step launch");
+    if (err != hipSuccess) return marl::report_device_error(err, "mixer update launch");
     return MARL_OK;
+}
+bool finite_value(float v) { return v == v && v - v == 0.0f; }
+}  // namespace
+
+int marl_mixer_sgd_step(marl_mixer *m, float *weights, const float *grad_weights, float lr, void *hip_stream)
+{
+    if (!m || !weights || !grad_weights) return MARL_ERR_NULL;
+    if (!finite_value(lr)) return MARL_ERR_BAD_ARG;
+    return mixer_update(m, weights, grad_weights, lr, marl::UpdateRule(), hip_stream);
+}
+
+int marl_mixer_rmsprop_step(marl_mixer *m, float *weights, const float *grad_weights, float *sq_avg, float lr, float alpha,
+                            float eps, void *hip_stream)
+{
+    if (!m || !weights || !grad_weights || !sq_avg) return MARL_ERR_NULL;
+    if (!finite_value(lr) || !(alpha >= 0.0f && alpha <= 1.0f) || !(eps > 0.0f) || !finite_value(eps)) return MARL_ERR_BAD_ARG;
+    marl::UpdateRule rule;
+    rule.sq_avg = sq_avg; rule.alpha = alpha; rule.eps = eps;
+    return mixer_update(m, weights, grad_weights, lr, rule, hip_stream);
 }
 
 }  // extern "C"

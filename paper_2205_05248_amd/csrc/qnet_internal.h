@@ -184,15 +184,20 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
 // fragment part, the parameter it holds; launch_sgd_step: weights -= lr * grad, then the image rebuilt from them.
 // probe_fragment_map: the same for any image whose packer is handed in (pack(w, out): the frag_elems 16-bit
 // elements of the fragment part packed from w); launch_sgd_and_fragments / launch_copy_refresh: the kernels.
+// How the weights move: plain gradient descent (sq_avg null) or RMSprop with the running mean of squares sq_avg.
+struct UpdateRule {
+    float *sq_avg = nullptr;
+    float alpha = 0.0f, eps = 0.0f;
+};
 using FragPacker = std::function<bool(const float *, uint16_t *)>;
 bool probe_fragment_map(size_t n_params, size_t frag_elems, const FragPacker &pack, std::vector<int32_t> *map);
 hipError_t launch_sgd_and_fragments(float *weights, const float *grad, float lr, size_t n_params, const int32_t *map_dev,
-                                    size_t map_elems, void *image_dev, hipStream_t stream);
+                                    size_t map_elems, void *image_dev, hipStream_t stream, const UpdateRule &rule = UpdateRule());
 hipError_t launch_copy_refresh(const float *weights, const int32_t *src_dev, size_t n, float *dst, hipStream_t stream);
 bool build_repack_map(const marl_qnet_desc &desc, size_t n_params, std::vector<int32_t> *map, PackedImage *layout);
 bool repack_map_reproduces_packer(const marl_qnet_desc &desc, const float *weights, size_t n_params);
 hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout, int planes, const int32_t *map_dev,
                            size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
-                           hipStream_t stream);
+                           hipStream_t stream, const UpdateRule &rule = UpdateRule());
 
 }  // namespace marl

@@ -50,6 +50,29 @@ __global__ void sgd_kernel(float *w, const float *g, float lr, size_t n)
     }
 }
 
+// RMSprop: v <- alpha v + (1 - alpha) g^2;  w <- w - lr g / (sqrt(v) + eps).  Every operation is rounded on its
+// own, in this order (no fused multiply-add), so that a host reference in fp32 reproduces it bit for bit.
+__global__ void rmsprop_kernel(float *w, const float *g, float *v, float lr, float alpha, float eps, size_t n)
+{
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float gi = g[i];
+    float keep = alpha * v[i];
+    asm volatile("" : "+v"(keep));
+    float sq = gi * gi;
+    asm volatile("" : "+v"(sq));
+    float fresh = (1.0f - alpha) * sq;
+    asm volatile("" : "+v"(fresh));
+    const float vi = keep + fresh;
+    v[i] = vi;
+    const float denom = sqrtf(vi) + eps;          // sqrtf and / are correctly rounded (the compiler's default for HIP)
+    float ratio = gi / denom;
+    asm volatile("" : "+v"(ratio));
+    float step = lr * ratio;
+    asm volatile("" : "+v"(step));
+    w[i] = w[i] - step;
+}
+
 __global__ void repack_frag_kernel(const float *w, const int32_t *map, uint16_t *image, size_t n)
 {
     const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -184,9 +207,11 @@ bool repack_map_reproduces_packer(const marl_qnet_desc &desc, const float *weigh
 }
 
 hipError_t launch_sgd_and_fragments(float *weights, const float *grad, float lr, size_t n_params, const int32_t *map_dev,
-                                    size_t map_elems, void *image_dev, hipStream_t stream)
+                                    size_t map_elems, void *image_dev, hipStream_t stream, const UpdateRule &rule)
 {
-    hipLaunchKernelGGL(sgd_kernel, dim3((unsigned)((n_params + 255) / 256)), dim3(256), 0, stream, weights, grad, lr, n_params);
+    const dim3 grid((unsigned)((n_params + 255) / 256));
+    if (rule.sq_avg) hipLaunchKernelGGL(rmsprop_kernel, grid, dim3(256), 0, stream, weights, grad, rule.sq_avg, lr, rule.alpha, rule.eps, n_params);
+    else hipLaunchKernelGGL(sgd_kernel, grid, dim3(256), 0, stream, weights, grad, lr, n_params);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(repack_frag_kernel, dim3((unsigned)((map_elems + 255) / 256)), dim3(256), 0, stream, weights, map_dev,
@@ -202,9 +227,9 @@ hipError_t launch_copy_refresh(const float *weights, const int32_t *src_dev, siz
 
 hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout, int planes, const int32_t *map_dev,
                            size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
-                           hipStream_t stream)
+                           hipStream_t stream, const UpdateRule &rule)
 {
-    hipError_t err = launch_sgd_and_fragments(weights, grad, lr, n_params, map_dev, map_elems, image_dev, stream);
+    hipError_t err = launch_sgd_and_fragments(weights, grad, lr, n_params, map_dev, map_elems, image_dev, stream, rule);
     if (err != hipSuccess) return err;
     TableArgs t{};
     t.w = weights; t.image = static_cast<char *>(image_dev);

@@ -80,6 +80,8 @@ def test_calls_reject_null_handles(lib):
     assert lib.marl_qnet_grad_workspace_bytes(None, 1, 1, None) == -1
     assert lib.marl_mixer_grad_workspace_bytes(None, 1, 1, None) == -1
     assert lib.marl_mixer_sgd_step(None, None, None, 0.1, None) == -1
+    assert lib.marl_mixer_rmsprop_step(None, None, None, None, 0.1, 0.9, 1e-5, None) == -1
+    assert lib.marl_qnet_rmsprop_step(None, None, None, None, 0.1, 0.9, 1e-5, None) == -1
     assert lib.marl_mixer_grad(None, 1, 1, None, None, None, None, 0, None, None, None) == -1
     assert lib.marl_qnet_grad(None, 1, 1, None, None, None, None, None, 0, None, None) == -1
     assert lib.marl_qnet_reserve_unroll(None, 1, 1) == -1

@@ -289,3 +289,51 @@ def test_learner_iteration_replays_from_a_hip_graph():
     assert not torch.equal(master, torch.from_numpy(w).cuda())
     for h in (online, target, mixer, mixer_tg):
         h.close()
+
+
+def test_rmsprop_update_matches_a_host_reference_bit_for_bit():
+    """Three RMSprop steps on the Q-network and on the mixer: weights and running squares equal the fp32 host
+    sequence exactly, and the handles compute with the new weights."""
+    cfg = wl.config(1)
+    dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
+    rng = np.random.default_rng(8)
+    lr, alpha, eps = np.float32(0.01), np.float32(0.99), np.float32(1e-5)
+    for make, w in ((lambda wv: binding.QNet(dims, wv), wl.make_weights(cfg, 0)),
+                    (lambda wv: binding.Mixer(mdims, wv), wl.make_mixer_weights(cfg, 0))):
+        h = make(w)
+        master, sq = torch.from_numpy(w.copy()).cuda(), torch.zeros(w.size, device="cuda")
+        ref_w, ref_v = w.copy(), np.zeros_like(w)
+        for step in range(3):
+            g = rng.normal(size=w.shape).astype(np.float32) * np.float32(10.0 ** (step - 1))
+            h.rmsprop_step(master, torch.from_numpy(g).cuda(), sq, float(lr), float(alpha), float(eps))
+            ref_v = (alpha * ref_v) + ((np.float32(1.0) - alpha) * (g * g))
+            ref_w = ref_w - lr * (g / (np.sqrt(ref_v) + eps))
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(sq.cpu().numpy(), ref_v)
+        np.testing.assert_array_equal(master.cpu().numpy(), ref_w)
+        fresh = make(ref_w)
+        if isinstance(h, binding.QNet):
+            inp = wl.make_act_inputs(cfg, E=5)
+            a, b = pu.gpu_act(h, cfg, inp), pu.gpu_act(fresh, cfg, inp)
+            for k in a:
+                np.testing.assert_array_equal(a[k], b[k])
+        else:
+            m = wl.make_mixer_inputs(cfg, B=3, T=4)
+            d = {k: torch.from_numpy(np.ascontiguousarray(m[k])).cuda()
+                 for k in ("state", "q_taken", "next_max", "reward", "terminated", "filled")}
+            res = []
+            for mx in (h, fresh):
+                outs = [torch.empty(3, 4, device="cuda") for _ in range(3)]
+                mx.td(None, d["state"], d["q_taken"], d["next_max"], d["reward"], d["terminated"], d["filled"], m["gamma"], *outs)
+                torch.cuda.synchronize()
+                res.append([o.cpu().numpy() for o in outs])
+            for x, y2 in zip(*res):
+                np.testing.assert_array_equal(x, y2)
+        import ctypes
+        lib, vp = binding.load(), ctypes.c_void_p
+        fn = lib.marl_qnet_rmsprop_step if isinstance(h, binding.QNet) else lib.marl_mixer_rmsprop_step
+        p = vp(master.data_ptr())
+        assert fn(vp(h.handle), p, p, p, 0.1, 1.5, 1e-5, None) == -5
+        assert fn(vp(h.handle), p, p, p, 0.1, 0.9, 0.0, None) == -5
+        assert fn(vp(h.handle), p, p, None, 0.1, 0.9, 1e-5, None) == -1
+        h.close(); fresh.close()
