@@ -411,13 +411,13 @@ def learner_section(ci, launches=10):
     mws = torch.empty(mneed, dtype=torch.uint8, device="cuda")
 
     def iteration():
-        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
-                         u["gamma"], q_taken, next_max, y)
+        online.unroll_td_keep(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                              u["gamma"], q_taken, next_max, y, ws)          # leaves x and h for the backward pass
         mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
                  q_total, y_total, td, loss2)
         e = td * (-2.0 / loss2[1])
         mixer.grad(state, q_taken, e, mws, gq, mgrad)
-        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad, kept=True)
         online.sgd_step(master, grad, 0.0)
         mixer.sgd_step(mmaster, mgrad, 0.0)
 
@@ -453,7 +453,7 @@ def learner_section(ci, launches=10):
         h.close()
     return {"ms": ms, "ms_graph_replay": ms_graph, "transitions_per_s": B * T / (ms * 1e-3),
             "agent_steps_per_s": B * T * N / (ms * 1e-3),
-            "stages": "unroll_td (2 networks) + mixer_td + mixer_grad + qnet_grad + qnet_sgd_step + mixer_sgd_step",
+            "stages": "unroll_td_keep (2 networks) + mixer_td + mixer_grad + qnet_grad_kept + qnet_sgd_step + mixer_sgd_step",
             "config": {"B": B, "T": T, "n_agents": N}}
 
 

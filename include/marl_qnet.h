@@ -310,6 +310,26 @@ int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T,
                    float *grad_weights, void *hip_stream);
 
 /*
+ * The learner runs the unroll and then the backward pass on the same batch with the same weights; the pair
+ * below lets the unroll leave its activations for the backward pass, which then skips its own forward pass.
+ *   marl_unroll_td_keep   marl_unroll_td (same arguments, same outputs, bit for bit) whose online network
+ *                         also writes x and h of every slot into `workspace` (sized and aligned as for
+ *                         marl_qnet_grad with the same B, T); fused16 kernels only (MARL_ERR_BAD_DIM else)
+ *   marl_qnet_grad_kept   marl_qnet_grad (same arguments, same result, bit for bit) that trusts `workspace`
+ *                         to hold what marl_unroll_td_keep wrote for this q, B, T, obs, with no change of
+ *                         q's weights and no other use of the workspace in between (stream order counts)
+ */
+int marl_unroll_td_keep(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
+                        const float *obs, const uint8_t *avail, const int32_t *actions,
+                        const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                        float gamma, float *q_taken, float *next_max, float *td_target, float *q_all,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+int marl_qnet_grad_kept(marl_qnet *q, int32_t B, int32_t T,
+                        const float *obs, const int32_t *actions, const uint8_t *filled,
+                        const float *grad_q_taken, void *workspace, size_t workspace_bytes,
+                        float *grad_weights, void *hip_stream);
+
+/*
  * Choice of the kernel family for calls on this handle (for marl_unroll_td: the `online` handle).
  * Two families compute the same functions:
  *   fused16  tiles of 16 rows, every weight resident on chip, one kernel per call; serves the

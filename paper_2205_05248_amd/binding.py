@@ -20,7 +20,7 @@ MARL_DTYPE_BF16 = 1
 DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
-           "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_sgd_step", "marl_qnet_rmsprop_step", "marl_qnet_check_refresh_map",
+           "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_grad_kept", "marl_unroll_td_keep", "marl_qnet_sgd_step", "marl_qnet_rmsprop_step", "marl_qnet_check_refresh_map",
            "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
@@ -83,6 +83,10 @@ def load():
         lib.marl_qnet_grad_workspace_bytes.argtypes = [vp, i32, i32, ctypes.POINTER(ctypes.c_size_t)]
         lib.marl_qnet_grad.restype = ctypes.c_int
         lib.marl_qnet_grad.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.marl_qnet_grad_kept.restype = ctypes.c_int
+        lib.marl_qnet_grad_kept.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp, vp]
+        lib.marl_unroll_td_keep.restype = ctypes.c_int
+        lib.marl_unroll_td_keep.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.marl_qnet_check_refresh_map.restype = ctypes.c_int
         lib.marl_qnet_check_refresh_map.argtypes = [ctypes.POINTER(Desc), vp, ctypes.c_size_t]
         lib.marl_qnet_rmsprop_step.restype = ctypes.c_int
@@ -295,12 +299,14 @@ def marl_qnet_grad_workspace_bytes(handle, B, T):
     return int(n.value)
 
 
-def marl_qnet_grad(handle, dims, obs, actions, filled, grad_q_taken, workspace, grad_weights):
-    """workspace: a device uint8 tensor of at least marl_qnet_grad_workspace_bytes bytes."""
+def marl_qnet_grad(handle, dims, obs, actions, filled, grad_q_taken, workspace, grad_weights, kept=False):
+    """workspace: a device uint8 tensor of at least marl_qnet_grad_workspace_bytes bytes.
+    kept: the workspace holds the activations marl_unroll_td_keep left there."""
     N, D, A, H = dims
     B, T = obs.shape[0], obs.shape[1] - 1
     n_params = (D + N) * H + H + 6 * H * H + 6 * H + A * H + A
-    check(load().marl_qnet_grad(
+    fn = load().marl_qnet_grad_kept if kept else load().marl_qnet_grad
+    check(fn(
         ctypes.c_void_p(handle), B, T, _dev(obs, "f32", (B, T + 1, N, D), "obs"),
         _dev(actions, "i32", (B, T, N), "actions"), _dev(filled, "u8", (B, T), "filled"),
         _dev(grad_q_taken, "f32", (B, T, N), "grad_q_taken"), _dev(workspace, "u8", (workspace.numel(),), "workspace"),
@@ -345,8 +351,22 @@ class QNet:
     def grad_workspace_bytes(self, B, T):
         return marl_qnet_grad_workspace_bytes(self.handle, B, T)
 
-    def grad(self, obs, actions, filled, grad_q_taken, workspace, grad_weights):
-        marl_qnet_grad(self.handle, self.dims, obs, actions, filled, grad_q_taken, workspace, grad_weights)
+    def grad(self, obs, actions, filled, grad_q_taken, workspace, grad_weights, kept=False):
+        marl_qnet_grad(self.handle, self.dims, obs, actions, filled, grad_q_taken, workspace, grad_weights, kept)
+
+    def unroll_td_keep(self, target, obs, avail, actions, reward, terminated, filled, gamma,
+                       q_taken, next_max, td_target, workspace, q_all=None):
+        N, D, A, H = self.dims
+        B, T = obs.shape[0], obs.shape[1] - 1
+        tgt = self if target is None else target
+        check(load().marl_unroll_td_keep(
+            ctypes.c_void_p(self.handle), ctypes.c_void_p(tgt.handle), B, T, _dev(obs, "f32", (B, T + 1, N, D), "obs"),
+            _dev(avail, "u8", (B, T + 1, N, A), "avail"), _dev(actions, "i32", (B, T, N), "actions"),
+            _dev(reward, "f32", (B, T), "reward"), _dev(terminated, "u8", (B, T), "terminated"),
+            _dev(filled, "u8", (B, T), "filled"), float(gamma), _dev(q_taken, "f32", (B, T, N), "q_taken"),
+            _dev(next_max, "f32", (B, T, N), "next_max"), _dev(td_target, "f32", (B, T, N), "td_target"),
+            _dev(q_all, "f32", (B, T + 1, N, A), "q_all", optional=True),
+            _dev(workspace, "u8", (workspace.numel(),), "workspace"), int(workspace.numel()), _stream()))
 
     def act_step_indexed(self, env_index, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out=None):
         marl_act_step_indexed(self.handle, self.dims, env_index, obs, avail, h_in, reset, step_t, epsilon, seed,

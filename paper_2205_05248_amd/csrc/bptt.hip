@@ -627,8 +627,16 @@ bool qnet_grad_fits(const NetFrags &net)
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T) { return make_plan(net, B, T).bytes; }
 
 // grad: packed like the weights (W1, b1, W_ih, W_hh, b_ih, b_hh, W2, b2), device, fully overwritten.
+void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, float **x_all)
+{
+    const Plan plan = make_plan(net, B, T);
+    *h_all = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_h);
+    *x_all = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_x);
+}
+
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
-                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream)
+                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream,
+                            bool activations_kept)
 {
     const Plan plan = make_plan(net, B, T);
     char *ws = static_cast<char *>(workspace);
@@ -637,9 +645,11 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     float *dq = reinterpret_cast<float *>(ws + plan.off_dq), *partial = reinterpret_cast<float *>(ws + plan.off_partial);
     const int N = net.N, D = net.D, A = net.A, H = net.H, S = T + 1;
 
-    // forward pass that keeps x and h
-    hipError_t err = launch_unroll_fused(net, net, false, B, T, nullptr, B, obs, nullptr, actions, nullptr, nullptr, filled,
-                                         0.0f, nullptr, nullptr, nullptr, nullptr, stream, kTdSave, nullptr, h_all, x_all);
+    // forward pass that keeps x and h, unless the caller's unroll has left them in the workspace
+    hipError_t err = hipSuccess;
+    if (!activations_kept)
+        err = launch_unroll_fused(net, net, false, B, T, nullptr, B, obs, nullptr, actions, nullptr, nullptr, filled,
+                                  0.0f, nullptr, nullptr, nullptr, nullptr, stream, kTdSave, nullptr, h_all, x_all);
     if (err != hipSuccess) return err;
 
     BpttArgs a{};

@@ -310,7 +310,7 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
                 int32_t pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
                 const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                 float *next_max, float *td_target, float *q_all, void *hip_stream, bool double_q = false,
-                int32_t *next_action = nullptr)
+                int32_t *next_action = nullptr, void *keep_workspace = nullptr)
 {
     if (!online || !target) return MARL_ERR_NULL;
     const marl_qnet_desc &a = online->desc, &b = target->desc;
@@ -373,6 +373,17 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
         if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
         return MARL_OK;
     }
+    if (keep_workspace) {
+        if (!fused) return MARL_ERR_BAD_DIM;
+        float *h_all, *x_all;
+        marl::qnet_grad_activation_slots(online->net, B, T, keep_workspace, &h_all, &x_all);
+        if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
+        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions,
+                                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream,
+                                           marl::kTdKeep, nullptr, h_all, x_all));
+        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
+        return MARL_OK;
+    }
     if (fused) {
         if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
         MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
@@ -431,9 +442,10 @@ int marl_qnet_grad_workspace_bytes(const marl_qnet *q, int32_t B, int32_t T, siz
     return MARL_OK;
 }
 
-int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T, const float *obs, const int32_t *actions, const uint8_t *filled,
+namespace {
+int qnet_grad_call(marl_qnet *q, int32_t B, int32_t T, const float *obs, const int32_t *actions, const uint8_t *filled,
                    const float *grad_q_taken, void *workspace, size_t workspace_bytes, float *grad_weights,
-                   void *hip_stream)
+                   void *hip_stream, bool activations_kept)
 {
     if (!q) return MARL_ERR_NULL;
     size_t need = 0;
@@ -450,8 +462,38 @@ int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T, const float *obs, const i
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     MARL_HIP(marl::launch_qnet_grad(q->net, B, T, obs, actions, filled, grad_q_taken, workspace, grad_weights,
-                                    static_cast<hipStream_t>(hip_stream)));
+                                    static_cast<hipStream_t>(hip_stream), activations_kept));
     return MARL_OK;
+}
+}  // namespace
+
+int marl_qnet_grad(marl_qnet *q, int32_t B, int32_t T, const float *obs, const int32_t *actions, const uint8_t *filled,
+                   const float *grad_q_taken, void *workspace, size_t workspace_bytes, float *grad_weights,
+                   void *hip_stream)
+{
+    return qnet_grad_call(q, B, T, obs, actions, filled, grad_q_taken, workspace, workspace_bytes, grad_weights, hip_stream, false);
+}
+
+int marl_qnet_grad_kept(marl_qnet *q, int32_t B, int32_t T, const float *obs, const int32_t *actions, const uint8_t *filled,
+                        const float *grad_q_taken, void *workspace, size_t workspace_bytes, float *grad_weights,
+                        void *hip_stream)
+{
+    return qnet_grad_call(q, B, T, obs, actions, filled, grad_q_taken, workspace, workspace_bytes, grad_weights, hip_stream, true);
+}
+
+int marl_unroll_td_keep(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const float *obs,
+                        const uint8_t *avail, const int32_t *actions, const float *reward, const uint8_t *terminated,
+                        const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
+                        float *q_all, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    if (!online || !workspace) return MARL_ERR_NULL;
+    size_t need = 0;
+    const int rc = marl_qnet_grad_workspace_bytes(online, B, T, &need);
+    if (rc != MARL_OK) return rc;
+    if (workspace_bytes < need) return MARL_ERR_BAD_DIM;
+    if (reinterpret_cast<uintptr_t>(workspace) % 256 != 0) return MARL_ERR_BAD_ARG;
+    return unroll_call(online, target, B, T, nullptr, B, obs, avail, actions, reward, terminated, filled, gamma, q_taken,
+                       next_max, td_target, q_all, hip_stream, false, nullptr, workspace);
 }
 
 int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_weights, size_t n_weights)

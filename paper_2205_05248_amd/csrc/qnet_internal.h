@@ -120,7 +120,8 @@ size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
 // kTdSave (fused kernels, one network): no TD output at all; the fc1 output x and the hidden state of
 // every slot go to x_save / h_save [B, T+1, N, H] fp32 for the backward pass: x_save[b, s] = x of slot s,
 // h_save[b, 0] = 0 and h_save[b, s + 1] = the state after slot s (s < T).
-enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2, kTdSave = 3 };
+// kTdKeep: kTdPlain (one or two networks, all TD outputs) whose online network also stores x_save / h_save.
+enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2, kTdSave = 3, kTdKeep = 4 };
 
 hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool two_nets, void *scratch_online,
                             void *scratch_target, int B, int T, const int32_t *episode_index, int pool_episodes,
@@ -177,8 +178,12 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
 // `fits`: the network runs on the fused unroll kernel and its widest layer fits the gradient product.
 bool qnet_grad_fits(const NetFrags &net);
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T);
+// activations_kept: the workspace already holds x and h of this batch (an unroll in kTdKeep mode wrote them to the
+// places qnet_grad_activation_slots names); otherwise the call runs its own forward pass first.
+void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, float **x_all);
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
-                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream);
+                            const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream,
+                            bool activations_kept = false);
 
 // Device-side parameter update (repack.hip).  build_repack_map (host): for every 16-bit element of the image's
 // fragment part, the parameter it holds; launch_sgd_step: weights -= lr * grad, then the image rebuilt from them.

@@ -92,11 +92,13 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
             for (int r = 0; r < 4; ++r) hv[j][r] = 0.0f;
         GruWave<H, P>::publish(h_lds[0], w, lane, hv);
-        // kTdSave: this lane's units of its row's state, slot by slot
+        // kTdSave / kTdKeep: this lane's units of its row's state, slot by slot (the online network's)
+        constexpr bool kStores = MODE == kTdSave || MODE == kTdKeep;
+        const bool stores = kStores && !is_target;
         float *h_row = nullptr;
-        if constexpr (MODE == kTdSave) {
+        if constexpr (kStores) {
             h_row = h_save + ((size_t)b * S * N + n) * H + 16 * Sh::NBC * w + 4 * q4;
-            if (valid)
+            if (valid && stores)
 #pragma unroll
                 for (int j = 0; j < Sh::NBC; ++j) *reinterpret_cast<f32x4 *>(h_row + 16 * j) = hv[j];
         }
@@ -106,8 +108,8 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                 const int cur = it & 1;
                 gru.step(lds, w, lane, q4, h_lds[cur], x_lds[cur], hv);
                 GruWave<H, P>::publish(h_lds[cur ^ 1], w, lane, hv);
-                if constexpr (MODE == kTdSave) {
-                    if (valid && it < T)
+                if constexpr (kStores) {
+                    if (valid && stores && it < T)
 #pragma unroll
                         for (int j = 0; j < Sh::NBC; ++j)
                             *reinterpret_cast<f32x4 *>(h_row + (size_t)(it + 1) * N * H + 16 * j) = hv[j];
@@ -242,9 +244,9 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         auto fc1_step = [&](int s) {
             const int slot = s + 1;
             if (slot >= 0 && slot <= T) {
-                if constexpr (MODE == kTdSave)
+                if constexpr (MODE == kTdSave || MODE == kTdKeep)
                     fc1.template step<true>(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1],
-                                            valid ? x_save + (((size_t)b * S + slot) * N + n) * H + 4 * q4 : nullptr);
+                                            valid && !is_target ? x_save + (((size_t)b * S + slot) * N + n) * H + 4 * q4 : nullptr);
                 else
                     fc1.step(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1]);
             }
@@ -296,6 +298,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
 #define MARL_FUSED_Q(ABLK)                                                                                          \
     do {                                                                                                            \
         if (mode == kTdSave) MARL_FUSED(ABLK, false, kTdSave);                                                      \
+        else if (mode == kTdKeep) { if (q_all) MARL_FUSED(ABLK, true, kTdKeep); else MARL_FUSED(ABLK, false, kTdKeep); } \
         else if (mode == kTdValue) MARL_FUSED(ABLK, false, kTdValue);                                               \
         else if (mode == kTdSelect) { if (q_all) MARL_FUSED(ABLK, true, kTdSelect); else MARL_FUSED(ABLK, false, kTdSelect); } \
         else if (q_all) MARL_FUSED(ABLK, true, kTdPlain);                                                           \
@@ -338,6 +341,7 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
 {
     if ((mode == kTdSelect || mode == kTdValue) && (two_nets || !next_action)) return hipErrorInvalidValue;
     if (mode == kTdSave && (two_nets || !h_save || !x_save)) return hipErrorInvalidValue;
+    if (mode == kTdKeep && (!h_save || !x_save)) return hipErrorInvalidValue;
 #define MARL_GO(HH, PP)                                                                                             \
     return fused_dispatch<HH, PP>(online, target, two_nets, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated, filled,  \
                                   gamma, q_taken, next_max, td_target, q_all, stream, mode, next_action, h_save, x_save)

@@ -84,6 +84,8 @@ def test_calls_reject_null_handles(lib):
     assert lib.marl_qnet_rmsprop_step(None, None, None, None, 0.1, 0.9, 1e-5, None) == -1
     assert lib.marl_mixer_grad(None, 1, 1, None, None, None, None, 0, None, None, None) == -1
     assert lib.marl_qnet_grad(None, 1, 1, None, None, None, None, None, 0, None, None) == -1
+    assert lib.marl_qnet_grad_kept(None, 1, 1, None, None, None, None, None, 0, None, None) == -1
+    assert lib.marl_unroll_td_keep(None, None, 1, 1, None, None, None, None, None, None, 0.9, None, None, None, None, None, 0, None) == -1
     assert lib.marl_qnet_reserve_unroll(None, 1, 1) == -1
     assert lib.marl_qnet_get_desc(None, None) == -1
     assert lib.marl_destroy(None) == 0

@@ -149,3 +149,46 @@ def test_edge_shapes_and_argument_errors():
     net = binding.QNet(wl.dims(big), wl.make_weights(big, 0), "fp32")
     assert lib.marl_qnet_grad_workspace_bytes(vp(net.handle), 3, 4, ctypes.byref(need)) == -2
     net.close()
+
+
+@pytest.mark.parametrize("ci,B,T,two", [(0, 5, 9, True), (1, 6, 8, False), (4, 3, 11, True)])
+def test_unroll_that_keeps_activations_feeds_the_backward_pass(ci, B, T, two):
+    """marl_unroll_td_keep returns what marl_unroll_td returns and leaves the activations; marl_qnet_grad_kept on
+    them returns what marl_qnet_grad returns.  Both bit for bit."""
+    cfg = dict(wl.config(ci), B=B, T=T)
+    dims = wl.dims(cfg)
+    N, D, A, H = dims
+    net = binding.QNet(dims, wl.make_weights(cfg, 0), cfg["dtype"])
+    target = binding.QNet(dims, wl.make_weights(cfg, 1), cfg["dtype"]) if two else None
+    u = wl.make_unroll_inputs(cfg, B=B, T=T)
+    d = pu.to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
+    g = torch.from_numpy(np.random.default_rng(ci).normal(size=(B, T, N)).astype(np.float32)).cuda()
+    ws = torch.empty(net.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
+    n_params = wl.param_count(*dims)
+    plain = pu.gpu_unroll(net, target, cfg, u)
+    ws.fill_(0xFF)
+    ref = torch.full((n_params,), float("nan"), device="cuda")
+    net.grad(d["obs"], d["actions"], d["filled"], g, ws, ref)
+    torch.cuda.synchronize()
+    ws.fill_(0xFF)
+    outs = [torch.full((B, T, N), float("nan"), device="cuda") for _ in range(3)]
+    q_all = torch.full((B, T + 1, N, A), float("nan"), device="cuda")
+    net.unroll_td_keep(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"], u["gamma"],
+                       *outs, ws, q_all)
+    got = torch.full((n_params,), float("nan"), device="cuda")
+    net.grad(d["obs"], d["actions"], d["filled"], g, ws, got, kept=True)
+    torch.cuda.synchronize()
+    for o, k in zip(outs + [q_all], ("q_taken", "next_max", "td_target", "q_all")):
+        np.testing.assert_array_equal(o.cpu().numpy(), plain[k])
+    assert torch.equal(got, ref)
+    lib, vp = binding.load(), ctypes.c_void_p
+    args = (vp(net.handle), vp(net.handle), B, T, vp(d["obs"].data_ptr()), vp(d["avail"].data_ptr()), vp(d["actions"].data_ptr()),
+            vp(d["reward"].data_ptr()), vp(d["terminated"].data_ptr()), vp(d["filled"].data_ptr()), 0.9,
+            vp(outs[0].data_ptr()), vp(outs[1].data_ptr()), vp(outs[2].data_ptr()), None)
+    assert lib.marl_unroll_td_keep(*args, vp(ws.data_ptr()), ws.numel() - 1, None) == -2
+    assert lib.marl_unroll_td_keep(*args, None, ws.numel(), None) == -1
+    net.set_kernels(binding.KERNELS_TILE32)
+    assert lib.marl_unroll_td_keep(*args, vp(ws.data_ptr()), ws.numel(), None) == -2          # the two-kernel family keeps nothing
+    net.close()
+    if target is not None:
+        target.close()

@@ -248,13 +248,13 @@ def test_learner_iteration_replays_from_a_hip_graph():
     mws = torch.empty(mixer.grad_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
 
     def iteration():
-        online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
-                         u["gamma"], q_taken, next_max, y)
+        online.unroll_td_keep(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                              u["gamma"], q_taken, next_max, y, ws)
         mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
                  q_total, y_total, td, loss2)
         torch.mul(td, -2.0 / (B * T), out=e)
         mixer.grad(state, q_taken, e, mws, gq, mgrad)
-        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad)
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad, kept=True)
         online.sgd_step(master, grad, 0.0005)
         mixer.sgd_step(mmaster, mgrad, 0.0005)
 
