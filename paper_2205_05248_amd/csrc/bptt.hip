@@ -39,9 +39,11 @@ struct BpttArgs {
     const uint8_t *filled;       // [B, T]
     const float *grad_q;         // [B, T, N]   dL/dq_taken
     const float *h_all, *x_all;  // [B, T+1, N, H]   h_all[b, s] = state before slot s
-    float *da;                   // [B, T, N, 4H]   adjoints of the gate pre-activations: n (input side), r, z, n (hidden side)
-    float *dpre1;                // [B, T, N, H]    adjoint of fc1's pre-activation
-    float *dq;                   // [B, T, N, a16]  adjoint of Q, dense (one non-zero per row)
+    // The adjoints, fp32 for fp32 networks and bf16 for bf16 networks (whose products round them to bf16 anyway:
+    // stored rounded, they cost half the traffic to write here and to read in the weight-gradient products)
+    void *da;                    // [B, T, N, 4H]   adjoints of the gate pre-activations: n (input side), r, z, n (hidden side)
+    void *dpre1;                 // [B, T, N, H]    adjoint of fc1's pre-activation
+    void *dq;                    // [B, T, N, a16]  adjoint of Q, dense (one non-zero per row)
 };
 
 template <int H, int P> struct BpttShape {
@@ -162,9 +164,23 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     constexpr uint32_t kDrop = 0xFFFFFFF0u;
     const size_t samples = (size_t)rows * T;
-    const __amdgpu_buffer_rsrc_t da_buf = __builtin_amdgcn_make_buffer_rsrc(a.da, 0, (int)(uint32_t)(samples * 4 * H * 4), kRawBuffer);
-    const __amdgpu_buffer_rsrc_t pre_buf = __builtin_amdgcn_make_buffer_rsrc(a.dpre1, 0, (int)(uint32_t)(samples * H * 4), kRawBuffer);
-    const __amdgpu_buffer_rsrc_t dq_buf = __builtin_amdgcn_make_buffer_rsrc(a.dq, 0, (int)(uint32_t)(samples * a.a16 * 4), kRawBuffer);
+    constexpr uint32_t kElem = P == 1 ? 2u : 4u;                   // bytes per stored adjoint
+    const __amdgpu_buffer_rsrc_t da_buf = __builtin_amdgcn_make_buffer_rsrc(a.da, 0, (int)(uint32_t)(samples * 4 * H * kElem), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t pre_buf = __builtin_amdgcn_make_buffer_rsrc(a.dpre1, 0, (int)(uint32_t)(samples * H * kElem), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t dq_buf = __builtin_amdgcn_make_buffer_rsrc(a.dq, 0, (int)(uint32_t)(samples * a.a16 * kElem), kRawBuffer);
+    // four adjoints of one lane -> element offset `at` of the array behind `buf` (dropped for rows past the end)
+    auto store4 = [&](const f32x4 &v, const __amdgpu_buffer_rsrc_t &buf, uint32_t at, uint32_t drop_mask) {
+        if constexpr (P == 1) {
+            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            bf16x4 r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (__bf16)v[i];
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, r), buf, (at * 2u) | drop_mask, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), buf, (at * 4u) | drop_mask, 0, 0);
+        }
+    };
     uint32_t drop = valid ? 0u : kDrop;
     asm volatile("" : "+v"(drop));
     const uint32_t drop_dq = (16 * w < a.a16) ? drop : kDrop;      // wave w writes block w of the row's dQ
@@ -234,19 +250,19 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
             }
         const uint32_t m = (uint32_t)((b * T + t) * N + n);          // sample index; the host bounds 4 H samples to 2^30
         {
-            const uint32_t da_at = (m * 4 * H + unit0) * 4u;
+            const uint32_t da_at = m * 4 * H + unit0;
 #pragma unroll
             for (int j = 0; j < NBC; ++j) {
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dan[j]), da_buf, (da_at + (0 * H + 16 * j) * 4u) | drop, 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dar[j]), da_buf, (da_at + (1 * H + 16 * j) * 4u) | drop, 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, daz[j]), da_buf, (da_at + (2 * H + 16 * j) * 4u) | drop, 0, 0);
-                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dahn[j]), da_buf, (da_at + (3 * H + 16 * j) * 4u) | drop, 0, 0);
+                store4(dan[j], da_buf, da_at + 0 * H + 16 * j, drop);
+                store4(dar[j], da_buf, da_at + 1 * H + 16 * j, drop);
+                store4(daz[j], da_buf, da_at + 2 * H + 16 * j, drop);
+                store4(dahn[j], da_buf, da_at + 3 * H + 16 * j, drop);
             }
             // the adjoint of Q_t, dense: wave w writes action block w of every row
             f32x4 v;
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = (16 * w + 4 * q4 + r == in.u) ? gq : 0.0f;
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dq_buf, ((m * a.a16 + 16 * w + 4 * q4) * 4u) | drop_dq, 0, 0);
+            store4(v, dq_buf, m * a.a16 + 16 * w + 4 * q4, drop_dq);
         }
         publish_blocks<P, NBC>(daf + 0 * KS, w, lane, dar);
         publish_blocks<P, NBC>(daf + 1 * KS, w, lane, daz);
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
             f32x4 dp;
 #pragma unroll
             for (int r = 0; r < 4; ++r) dp[r] = in.xv[j][r] > 0.0f ? accx[j][r] : 0.0f;
-            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, dp), pre_buf, ((m * H + unit0 + 16 * j) * 4u) | drop, 0, 0);
+            store4(dp, pre_buf, m * H + unit0 + 16 * j, drop);
         }
     }
 }
@@ -308,7 +324,8 @@ struct TnGemmBatch { TnGemmArgs g[kTnBatchMax]; };
 // memory once.  Wave w owns result row blocks w, w + 8, .. (PBW of them) and all QBN column blocks.  P: bf16
 // planes per operand, the network's own: 2 = every value as bf16 high part + bf16 of the remainder, three MFMAs
 // per product; 1 = values rounded to bf16, one MFMA.
-template <int PBW, int QBN, int P>
+// ABF: A's elements are bf16 (the adjoints of a bf16 network), else fp32; B's are fp32.
+template <int PBW, int QBN, int P, bool ABF>
 __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatch batch)
 {
     const TnGemmArgs g = batch.g[blockIdx.y];
@@ -343,13 +360,15 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     constexpr int kDepth = 2;
     float rv[kDepth][kSetsPerWave][8];
     // per column set of this wave: which operand, and the lane's (clamped) column in it
-    bool set_is_a[kSetsPerWave];
+    // kPp is a multiple of 128, so set i of either half of the waves is one of A's exactly for i < kPp / 128:
+    // known at compile time, and with it the element type, so that a load is one instruction with no branch
+    constexpr int kSetsOfA = kPp / 128;
+    static_assert(kPp % 128 == 0, "the column sets of A split evenly between the two halves of the waves");
     int set_col[kSetsPerWave];
 #pragma unroll
     for (int i = 0; i < kSetsPerWave; ++i) {
         const int col = lane + 64 * (2 * i + half);
-        set_is_a[i] = 64 * (2 * i + half) < kPp;                   // kPp is a multiple of 64: a set never straddles
-        set_col[i] = set_is_a[i] ? (col < g.P ? col : 0) : (col - kPp < g.Q ? col - kPp : 0);
+        set_col[i] = i < kSetsOfA ? (col < g.P ? col : 0) : (col - kPp < g.Q ? col - kPp : 0);
     }
     auto fetch = [&](float (&f)[kSetsPerWave][8], int m0) {         // this wave's eight rows of 32 samples
         // (group, row in group) of the wave's first row by division, of the following rows by stepping
@@ -359,10 +378,19 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
             const int m = m0 + 8 * sg + r;
-            const float *arow = g.a.base + (long)ga * g.a.group_stride + (long)ia * g.a.ld;
-            const float *brow = g.b.base + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
+            const char *arow = static_cast<const char *>(g.a.base) + ((long)ga * g.a.group_stride + (long)ia * g.a.ld) * (ABF ? 2 : 4);
+            const float *brow = static_cast<const float *>(g.b.base) + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
 #pragma unroll
-            for (int i = 0; i < kSetsPerWave; ++i) f[i][r] = (set_is_a[i] ? arow : brow)[set_col[i]];      // raw
+            for (int i = 0; i < kSetsPerWave; ++i) {
+                if constexpr (ABF) {
+                    if (i < kSetsOfA) {      // a bf16 element, widened (bf16 is the upper half of an fp32)
+                        const uint16_t e = reinterpret_cast<const uint16_t *>(arow)[set_col[i]];
+                        f[i][r] = __uint_as_float((uint32_t)e << 16);
+                        continue;
+                    }
+                }
+                f[i][r] = i < kSetsOfA ? reinterpret_cast<const float *>(arow)[set_col[i]] : brow[set_col[i]];      // raw
+            }
             // the next row, without a branch (a branch between two loads would make every wait a full one);
             // past the end the last row is kept (and not used)
             const unsigned go = m + 1 < g.M ? 1u : 0u;
@@ -391,8 +419,8 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
                 const int cb = col - kPp;                          // column of B (with its appended columns)
                 float made = 0.0f;
                 if (cb >= g.Q && cb < g.Q + g.n_extra) made = g.extra_mode == kExtraOnes ? 1.0f : (cb - g.Q == (int)agent ? 1.0f : 0.0f);
-                const bool real = set_is_a[i] ? col < g.P : cb < g.Q;
-                v[r] = live ? (real ? f[i][r] : (set_is_a[i] ? 0.0f : made)) : 0.0f;
+                const bool real = i < kSetsOfA ? col < g.P : cb < g.Q;
+                v[r] = live ? (real ? f[i][r] : (i < kSetsOfA ? 0.0f : made)) : 0.0f;
                 agent = agent + 1 == (unsigned)g.N ? 0u : agent + 1;
             }
             if (col < cols) {
@@ -511,6 +539,7 @@ struct Plan {
 Plan make_plan(const NetFrags &net, int B, int T)
 {
     Plan p{};
+    const size_t adj = net.planes == 1 ? 2 : 4;                    // bytes per stored adjoint
     const size_t R = (size_t)B * net.N, S = (size_t)T + 1, H = net.H;
     p.a16 = (net.A + 15) / 16 * 16;
     const long M = (long)R * T;
@@ -520,9 +549,9 @@ Plan make_plan(const NetFrags &net, int B, int T)
     size_t off = 0;
     p.off_h = off;      off = align_up(off + R * S * H * 4);
     p.off_x = off;      off = align_up(off + R * S * H * 4);
-    p.off_da = off;     off = align_up(off + R * T * 4 * H * 4);
-    p.off_dpre1 = off;  off = align_up(off + R * T * H * 4);
-    p.off_dq = off;     off = align_up(off + R * T * p.a16 * 4);
+    p.off_da = off;     off = align_up(off + R * T * 4 * H * adj + 4);
+    p.off_dpre1 = off;  off = align_up(off + R * T * H * adj + 4);
+    p.off_dq = off;     off = align_up(off + R * T * p.a16 * adj + 4);
     // the four products run together: room for all their partial results
     const long chunks_real = (M + p.chunk - 1) / p.chunk;
     auto part = [&](size_t P, size_t Qt) { return (size_t)chunks_real * (P > 128 ? 384 : 128) * ((Qt + 15) / 16 * 16) * 4; };
@@ -575,6 +604,7 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
             const bool is_wide = t.P > 128;
             if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;
+            if (t.b.bf16 || (t.a.bf16 != 0) != (list[0].a.bf16 != 0) || (t.a.bf16 && planes != 1)) return hipErrorInvalidValue;
             const size_t bytes = tn_partial_bytes(M, chunk, t.P, t.Q + t.n_extra);
             if (bytes > partial_bytes) return hipErrorInvalidValue;
             if (used + bytes > partial_bytes || (is_wide ? n_wide : n_narrow) == kTnBatchMax || n_red == kTnBatchMax) break;
@@ -590,17 +620,27 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             max_total = std::max(max_total, t.P * (t.Q + t.n_extra));
         }
         hipError_t err = hipSuccess;
-#define MARL_TN(PBW, QBN, PL, BATCH, COUNT, PPAD, MAXQ)                                                  \
+#define MARL_TN(PBW, QBN, PL, ABF, BATCH, COUNT, PPAD, MAXQ)                                             \
     do {                                                                                                 \
         const size_t lds = (size_t)(PL == 1 ? 2 : 1) * PL * (PPAD + MAXQ) * 80;      /* 80 bytes per staged column and plane */ \
-        err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL>>(kLdsLimit);                                  \
+        err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL, ABF>>(kLdsLimit);                             \
         if (err != hipSuccess) return err;                                                               \
-        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL>), dim3(chunks, COUNT), dim3(kTnThreads), lds, stream, BATCH); \
+        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL, ABF>), dim3(chunks, COUNT), dim3(kTnThreads), lds, stream, BATCH); \
         err = hipGetLastError();                                                                         \
         if (err != hipSuccess) return err;                                                               \
     } while (0)
-        if (n_wide) { if (planes == 2) MARL_TN(3, 9, 2, wide, n_wide, 384, max_q_wide); else MARL_TN(3, 9, 1, wide, n_wide, 384, max_q_wide); }
-        if (n_narrow) { if (planes == 2) MARL_TN(1, 21, 2, narrow, n_narrow, 128, max_q_narrow); else MARL_TN(1, 21, 1, narrow, n_narrow, 128, max_q_narrow); }
+        // the element type of A is the same for every product of a call (bf16 adjoints only with one plane)
+        const bool a_bf16 = list[done].a.bf16 != 0;
+        if (n_wide) {
+            if (planes == 2) MARL_TN(3, 9, 2, false, wide, n_wide, 384, max_q_wide);
+            else if (a_bf16) MARL_TN(3, 9, 1, true, wide, n_wide, 384, max_q_wide);
+            else MARL_TN(3, 9, 1, false, wide, n_wide, 384, max_q_wide);
+        }
+        if (n_narrow) {
+            if (planes == 2) MARL_TN(1, 21, 2, false, narrow, n_narrow, 128, max_q_narrow);
+            else if (a_bf16) MARL_TN(1, 21, 1, true, narrow, n_narrow, 128, max_q_narrow);
+            else MARL_TN(1, 21, 1, false, narrow, n_narrow, 128, max_q_narrow);
+        }
 #undef MARL_TN
         hipLaunchKernelGGL(tn_reduce_kernel, dim3((max_total + 255) / 256, n_red), dim3(256), 0, stream, red);
         err = hipGetLastError();
@@ -641,8 +681,9 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     const Plan plan = make_plan(net, B, T);
     char *ws = static_cast<char *>(workspace);
     float *h_all = reinterpret_cast<float *>(ws + plan.off_h), *x_all = reinterpret_cast<float *>(ws + plan.off_x);
-    float *da = reinterpret_cast<float *>(ws + plan.off_da), *dpre1 = reinterpret_cast<float *>(ws + plan.off_dpre1);
-    float *dq = reinterpret_cast<float *>(ws + plan.off_dq), *partial = reinterpret_cast<float *>(ws + plan.off_partial);
+    char *da = ws + plan.off_da, *dpre1 = ws + plan.off_dpre1, *dq = ws + plan.off_dq;
+    float *partial = reinterpret_cast<float *>(ws + plan.off_partial);
+    const int adj_bf16 = net.planes == 1 ? 1 : 0, adj_bytes = adj_bf16 ? 2 : 4;
     const int N = net.N, D = net.D, A = net.A, H = net.H, S = T + 1;
 
     // forward pass that keeps x and h, unless the caller's unroll has left them in the workspace
@@ -666,15 +707,15 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     float *gbih = gWhh + (size_t)3 * H * H, *gbhh = gbih + 3 * H, *gW2 = gbhh + 3 * H, *gb2 = gW2 + (size_t)A * H;
     const long M = (long)B * N * T;
     const int TN = T * N;
-    const RowMap plain_da{da, 0, (int)std::min<long>(M, 1 << 30), 4 * H};
+    const RowMap plain_da{da, 0, (int)std::min<long>(M, 1 << 30), 4 * H, adj_bf16};
     const RowMap da_i = plain_da;                                        // columns n, r, z
-    RowMap da_h = plain_da; da_h.base = da + H;                          // columns r, z, n (hidden side)
-    const RowMap x_rows{x_all, (long)S * N * H, TN, H};
-    const RowMap h_prev{h_all, (long)S * N * H, TN, H};
-    const RowMap h_new{h_all + (size_t)N * H, (long)S * N * H, TN, H};
-    const RowMap pre_rows{dpre1, 0, (int)std::min<long>(M, 1 << 30), H};
-    const RowMap obs_rows{obs, (long)S * N * D, TN, D};
-    const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16};
+    RowMap da_h = plain_da; da_h.base = da + (size_t)H * adj_bytes;      // columns r, z, n (hidden side)
+    const RowMap x_rows{x_all, (long)S * N * H, TN, H, 0};
+    const RowMap h_prev{h_all, (long)S * N * H, TN, H, 0};
+    const RowMap h_new{h_all + (size_t)N * H, (long)S * N * H, TN, H, 0};
+    const RowMap pre_rows{dpre1, 0, (int)std::min<long>(M, 1 << 30), H, adj_bf16};
+    const RowMap obs_rows{obs, (long)S * N * D, TN, D, 0};
+    const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16, adj_bf16};
     // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
     const TnProduct products[4] = {
         {da_i, x_rows, 3 * H, H, kExtraOnes, 1, N, 2 * H, H, gWih, gbih},

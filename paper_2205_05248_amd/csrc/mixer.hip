@@ -700,8 +700,8 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     // parameter gradients: packed order Hw1 [N M, S], hb1, Hb1 [M, S], hbb1, Hw2 [M, S], hb2, V1 [M, S], c1, v2, c2
     float *gHw1 = grad_weights, *ghb1 = gHw1 + (size_t)N * M * S, *gHb1 = ghb1 + (size_t)N * M, *ghbb1 = gHb1 + (size_t)M * S;
     float *gHw2 = ghbb1 + M, *ghb2 = gHw2 + (size_t)M * S, *gV1 = ghb2 + M, *gc1 = gV1 + (size_t)M * S, *gv2 = gc1 + M;
-    const marl::RowMap plain{dgen, 0, (int)R, plan.ldd};
-    const marl::RowMap states{state, (long)(T + 1) * S, T, S};
+    const marl::RowMap plain{dgen, 0, (int)R, plan.ldd, 0};
+    const marl::RowMap states{state, (long)(T + 1) * S, T, S, 0};
     // one matrix: rows [r0, r0 + P) of it are adjoint columns [col0 + r0, ..); state columns in slices, the
     // column of ones (the bias) rides with the last slice
     std::vector<marl::TnProduct> products;

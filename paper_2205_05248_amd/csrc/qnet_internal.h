@@ -152,10 +152,13 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
 
 // Products over samples, C[p][q] = sum_m A[m][p] B[m][q] with fp32 operands in global memory (bptt.hip).
 // Row m of an operand lives at base + (m / rows_per_group) * group_stride + (m % rows_per_group) * ld.
+// Elements are fp32, or bf16 (bf16 != 0: the left operand A of a one-plane product only, the same for every product
+// of a call); group_stride and ld count elements either way.
 struct RowMap {
-    const float *base;
+    const void *base;
     long group_stride;
     int rows_per_group, ld;
+    int bf16;
 };
 // Columns appended to B on the fly: one column of ones, or N one-hot columns of (m % N).
 enum ExtraCols : int { kExtraNone = 0, kExtraOnes = 1, kExtraAgent = 2 };
