@@ -65,7 +65,10 @@ def compare(cfg, got, want, amb):
 
 CASES = [(0, 4, 6, {}), (0, 32, 25, {}), (1, 5, 9, {}), (2, 7, 12, {}), (3, 33, 5, {}), (4, 3, 11, {}),
          # the widest first layer and more than sixteen agents with fp32 weights; a bf16 network with H = 64
-         (4, 3, 7, dict(H=64, D=150, dtype="fp32")), (1, 6, 8, dict(dtype="bf16"))]
+         (4, 3, 7, dict(H=64, D=150, dtype="fp32")), (1, 6, 8, dict(dtype="bf16")),
+         # odd shapes: one agent, odd observation and action counts, the most actions, a hidden-128 network with few inputs
+         (0, 5, 13, dict(N=1, D=7, A=5)), (0, 3, 6, dict(N=17, D=33, A=64, dtype="bf16")),
+         (4, 4, 9, dict(N=2, D=160, A=4)), (1, 1, 40, dict(N=3, D=1, A=7))]
 
 
 @pytest.mark.parametrize("ci,B,T,over", CASES, ids=lambda v: str(v).replace(" ", ""))

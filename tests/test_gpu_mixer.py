@@ -228,7 +228,7 @@ def _gpu_mixer_grad(mixer, dims, m, e):
 
 
 @pytest.mark.parametrize("ci,B,T,dtype", [(0, 3, 7, "fp32"), (1, 5, 9, "fp32"), (2, 7, 12, "fp32"), (3, 33, 5, "fp32"),
-                                          (4, 3, 11, "bf16"), (4, 2, 5, "fp32"), (1, 6, 8, "bf16")])
+                                          (4, 3, 11, "bf16"), (4, 2, 5, "fp32"), (1, 6, 8, "bf16"), (3, 1, 2, "fp32"), (2, 40, 33, "bf16")])
 def test_mixer_gradient_matches_the_oracle(ci, B, T, dtype):
     """Every entry of every parameter tensor, and dL/dq, within REL of the tensor's largest reference value.
     The absolute values and the offset's relu are switches set by forward values: where a generated weight or an
