@@ -432,6 +432,35 @@ def learner_section(ci, launches=10):
     b.record()
     torch.cuda.synchronize()
     ms = a.elapsed_time(b) / launches
+    # where the time goes: the same calls with an event after every stage
+    stage_names = ["unroll_td_keep", "mixer_td", "dL/dQ_total (tensor op)", "mixer_grad", "qnet_grad_kept", "qnet_sgd_step", "mixer_sgd_step"]
+    stage_ms = [0.0] * len(stage_names)
+
+    def staged():
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(stage_names) + 1)]
+        ev[0].record()
+        online.unroll_td_keep(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
+                              u["gamma"], q_taken, next_max, y, ws)
+        ev[1].record()
+        mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
+                 q_total, y_total, td, loss2)
+        ev[2].record()
+        e = td * (-2.0 / loss2[1])
+        ev[3].record()
+        mixer.grad(state, q_taken, e, mws, gq, mgrad)
+        ev[4].record()
+        online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad, kept=True)
+        ev[5].record()
+        online.sgd_step(master, grad, 0.0)
+        ev[6].record()
+        mixer.sgd_step(mmaster, mgrad, 0.0)
+        ev[7].record()
+        torch.cuda.synchronize()
+        for i in range(len(stage_names)):
+            stage_ms[i] += ev[i].elapsed_time(ev[i + 1]) / launches
+
+    for _ in range(launches):
+        staged()
     # the same iteration replayed from a HIP graph (the calls allocate nothing and record no memset)
     graph = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
@@ -454,6 +483,7 @@ def learner_section(ci, launches=10):
         h.close()
     return {"ms": ms, "ms_graph_replay": ms_graph, "transitions_per_s": B * T / (ms * 1e-3),
             "agent_steps_per_s": B * T * N / (ms * 1e-3),
+            "stage_ms": {k: round(v, 4) for k, v in zip(stage_names, stage_ms)},
             "stages": "unroll_td_keep (2 networks) + mixer_td + mixer_grad + qnet_grad_kept + qnet_sgd_step + mixer_sgd_step",
             "config": {"B": B, "T": T, "n_agents": N}}
 
