@@ -302,6 +302,14 @@ def mixer_section(ci, with_cpu, launches=20):
         sec = time.perf_counter() - t0
         out["cpu_oracle"] = {"transitions_per_s": sample_b * T / sec, "cores": 1,
                              "sample": f"first {sample_b} of {B} episodes, all {T} transitions"}
+        if grad_ms is not None:
+            gb = max(1, min(B, 1024 // T))
+            e = np.random.default_rng(2).normal(size=(gb, T))
+            t0 = time.perf_counter()
+            mxo.grad(dims, w_on, m["state"][:gb], m["q_taken"][:gb].astype(np.float64), e)
+            sec = time.perf_counter() - t0
+            out["grad_cpu_oracle"] = {"transitions_per_s": gb * T / sec, "cores": 1,
+                                      "sample": f"first {gb} of {B} episodes, all {T} transitions"}
     return out
 
 
