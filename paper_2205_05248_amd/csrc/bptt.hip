@@ -24,6 +24,7 @@
 //                                      into the packed gradient vector.
 // The precision follows the network's, in every product of the pass: fp32 networks split every operand into two
 // bf16 planes (three MFMAs per product), bf16 networks round the operands (adjoints, activations) to bf16.
+#include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -313,6 +314,8 @@ struct TnGemmArgs {
     int n_extra, N;
     int qp;             // Q + n_extra rounded up to 16: row pitch of the result
     int chunk;          // samples per workgroup along the contraction, a multiple of 32
+    // elements from a row to the next: inside a group, and from a group's last row to the next group's first
+    unsigned next_a, wrap_a, next_b, wrap_b;
     float *partial;     // [chunks][128 or 384 rows][qp]
 };
 
@@ -344,6 +347,11 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     const int sg = w & 3, half = w >> 2;                           // the wave stages samples 8 sg + 0..7 of every other column set
     const int n_qb = g.qp / 16;
     const int m_begin = (int)blockIdx.x * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
+    // The 32 samples of a step are eight consecutive ones from each quarter of the chunk: wave group sg walks
+    // through its own quarter, so that the rows it reads follow one another from the first step to the last and
+    // their addresses are stepped, never recomputed.
+    const int n_steps = (m_end - m_begin + 31) / 32;
+    const int wave_begin = m_begin + 8 * n_steps * sg, wave_end = min(m_end, wave_begin + 8 * n_steps);
 
     f32x4 acc[PBW][QBN];
 #pragma unroll
@@ -354,117 +362,163 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
             for (int r = 0; r < 4; ++r) acc[k][j][r] = 0.0f;
 
     // Inputs are asked for kDepth steps before they are used, into kDepth register sets that the unrolled
-    // loop addresses statically.  Every load is unconditional (addresses clamped into the arrays, the value
-    // replaced afterwards where it does not count), so the loop is straight-line code and each wait covers
-    // exactly the set it needs.
+    // loop addresses statically.  Every load is unconditional (rows past the end of the arrays repeat the last
+    // row, columns past an operand's width repeat its first), so the loop is straight-line code and each wait
+    // covers exactly the set it needs.
     constexpr int kDepth = 2;
     float rv[kDepth][kSetsPerWave][8];
-    // per column set of this wave: which operand, and the lane's (clamped) column in it
     // kPp is a multiple of 128, so set i of either half of the waves is one of A's exactly for i < kPp / 128:
     // known at compile time, and with it the element type, so that a load is one instruction with no branch
     constexpr int kSetsOfA = kPp / 128;
     static_assert(kPp % 128 == 0, "the column sets of A split evenly between the two halves of the waves");
-    int set_col[kSetsPerWave];
+    // Per column set of this wave: the lane's (clamped) column in its operand's rows, and for B's sets what the lane's
+    // column is made of: -2 a column of B itself (or one past everything, whose results nobody reads), -1 the
+    // appended column of ones, n >= 0 the appended one-hot column of agent n.
+    int set_col[kSetsPerWave], made_of[kSetsPerWave];
 #pragma unroll
     for (int i = 0; i < kSetsPerWave; ++i) {
-        const int col = lane + 64 * (2 * i + half);
-        set_col[i] = i < kSetsOfA ? (col < g.P ? col : 0) : (col - kPp < g.Q ? col - kPp : 0);
+        const int col = lane + 64 * (2 * i + half), cb = col - kPp;
+        set_col[i] = i < kSetsOfA ? (col < g.P ? col : 0) : (cb < g.Q ? cb : 0);
+        made_of[i] = (i >= kSetsOfA && cb >= g.Q && cb < g.Q + g.n_extra) ? (g.extra_mode == kExtraOnes ? -1 : cb - g.Q) : -2;
     }
-    auto fetch = [&](float (&f)[kSetsPerWave][8], int m0) {         // this wave's eight rows of 32 samples
-        // (group, row in group) of the wave's first row by division, of the following rows by stepping
-        const unsigned first = (unsigned)min(m0 + 8 * sg, g.M - 1);
-        unsigned ga = first / (unsigned)g.a.rows_per_group, ia = first % (unsigned)g.a.rows_per_group;
-        unsigned gb = first / (unsigned)g.b.rows_per_group, ib = first % (unsigned)g.b.rows_per_group;
+    // A column past an operand's width is staged with the values of the operand's first column: it only reaches
+    // rows or columns of the result that the reduction never reads, and costs no instruction here.
+
+    // The row the next load takes, as addresses in A and B; (group, row in group) by division once, then by
+    // stepping: a row further in the group, or from a group's last row to the next group's first.  All of it
+    // is the same in every lane and is kept in scalar registers (said so where the compiler cannot tell).
+    const unsigned row0 = (unsigned)min(wave_begin, g.M - 1);
+    const unsigned ga0 = __builtin_amdgcn_readfirstlane(row0 / (unsigned)g.a.rows_per_group);
+    const unsigned gb0 = __builtin_amdgcn_readfirstlane(row0 / (unsigned)g.b.rows_per_group);
+    const unsigned ia0 = row0 - ga0 * (unsigned)g.a.rows_per_group, ib0 = row0 - gb0 * (unsigned)g.b.rows_per_group;
+    long off_a = (long)ga0 * g.a.group_stride + (long)ia0 * g.a.ld;          // in elements
+    long off_b = (long)gb0 * g.b.group_stride + (long)ib0 * g.b.ld;
+    unsigned a_left = (unsigned)g.a.rows_per_group - ia0, b_left = (unsigned)g.b.rows_per_group - ib0;   // rows to the group's end
+    unsigned rows_left = (unsigned)(g.M - 1) - row0;                  // steps that stay inside the arrays
+    int sample = wave_begin;                                          // first sample of the step being staged
+    unsigned agent0 = (unsigned)wave_begin % (unsigned)g.N;          // its agent, where rows are (.., agent) samples
+    const unsigned agent_step = 8u % (unsigned)g.N;
+
+    // The loop comes twice.  ENDS = false: every row the workgroup touches, those fetched ahead included, exists
+    // and every sample of every step counts - all chunks but the last one or two.  ENDS = true: past the last
+    // sample the last row is fetched again (and not used), and samples past the wave's share are cleared (A's
+    // values are; B's may stay).
+    auto run = [&](auto ends_tag) {
+        constexpr bool ENDS = decltype(ends_tag)::value;
+        auto fetch = [&](float (&f)[kSetsPerWave][8]) {             // this wave's next eight rows
 #pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int m = m0 + 8 * sg + r;
-            const char *arow = static_cast<const char *>(g.a.base) + ((long)ga * g.a.group_stride + (long)ia * g.a.ld) * (ABF ? 2 : 4);
-            const float *brow = static_cast<const float *>(g.b.base) + (long)gb * g.b.group_stride + (long)ib * g.b.ld;
+            for (int r = 0; r < 8; ++r) {
+                const char *arow = static_cast<const char *>(g.a.base) + off_a * (ABF ? 2 : 4);
+                const float *brow = static_cast<const float *>(g.b.base) + off_b;
+#pragma unroll
+                for (int i = 0; i < kSetsPerWave; ++i) {
+                    if constexpr (ABF) {
+                        if (i < kSetsOfA) {      // bf16 elements stay as they are, two rows to a register (even row: lower half)
+                            const uint32_t e = reinterpret_cast<const uint16_t *>(arow)[set_col[i]];
+                            f[i][r / 2] = __uint_as_float(r % 2 ? (__float_as_uint(f[i][r / 2]) | (e << 16)) : e);
+                            continue;
+                        }
+                    }
+                    f[i][r] = i < kSetsOfA ? reinterpret_cast<const float *>(arow)[set_col[i]] : brow[set_col[i]];
+                }
+                // the next row, without a branch (a branch between two loads would make every wait a full one)
+                unsigned go = 1u;
+                if constexpr (ENDS) { go = rows_left ? 1u : 0u; rows_left -= go; }
+                a_left -= go; b_left -= go;
+                const bool wa = a_left == 0u, wb = b_left == 0u;
+                unsigned sa = wa ? g.wrap_a : g.next_a, sb = wb ? g.wrap_b : g.next_b;
+                if constexpr (ENDS) { sa = go ? sa : 0u; sb = go ? sb : 0u; }
+                off_a += sa; off_b += sb;
+                a_left = wa ? (unsigned)g.a.rows_per_group : a_left;
+                b_left = wb ? (unsigned)g.b.rows_per_group : b_left;
+            }
+        };
+        // The wave's eight samples of a column are samples 8 sg + 0..7 of the step: as bf16 they are exactly the
+        // 16 bytes that lane quarter sg of a fragment of that column reads.  Converted once here, not by every
+        // reader.  A loaded value is first passed through an empty asm: that is where the wait for it goes, and
+        // it keeps the compiler from turning "loaded value or zero" into a branch around the load.
+        auto deposit = [&](char *buf, float (&f)[kSetsPerWave][8]) {
 #pragma unroll
             for (int i = 0; i < kSetsPerWave; ++i) {
+                const int col = lane + 64 * (2 * i + half);
                 if constexpr (ABF) {
-                    if (i < kSetsOfA) {      // a bf16 element, widened (bf16 is the upper half of an fp32)
-                        const uint16_t e = reinterpret_cast<const uint16_t *>(arow)[set_col[i]];
-                        f[i][r] = __uint_as_float((uint32_t)e << 16);
+                    if (i < kSetsOfA) {       // the four registers are the fragment already
+                        uint32_t word[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            asm volatile("" : "+v"(f[i][j]));
+                            word[j] = __float_as_uint(f[i][j]);
+                            if constexpr (ENDS)
+                                word[j] &= sample + 2 * j + 1 < wave_end ? 0xFFFFFFFFu : (sample + 2 * j < wave_end ? 0x0000FFFFu : 0u);
+                        }
+                        if (col < cols) *reinterpret_cast<uint4 *>(buf + col * kPitch + 16 * sg) = make_uint4(word[0], word[1], word[2], word[3]);
                         continue;
                     }
                 }
-                f[i][r] = i < kSetsOfA ? reinterpret_cast<const float *>(arow)[set_col[i]] : brow[set_col[i]];      // raw
-            }
-            // the next row, without a branch (a branch between two loads would make every wait a full one);
-            // past the end the last row is kept (and not used)
-            const unsigned go = m + 1 < g.M ? 1u : 0u;
-            ia += go; ib += go;
-            const unsigned wa = ia == (unsigned)g.a.rows_per_group ? 1u : 0u, wb = ib == (unsigned)g.b.rows_per_group ? 1u : 0u;
-            ga += wa; ia = wa ? 0u : ia;
-            gb += wb; ib = wb ? 0u : ib;
-        }
-    };
-    // The wave's eight samples of a column are samples 8 sg + 0..7 of the step: as bf16 they are exactly the 16
-    // bytes that lane quarter sg of a fragment of that column reads.  Converted once here, not by every reader.
-    // A loaded value is first passed through an empty asm: that is where the wait for it goes, and it keeps the
-    // compiler from turning "loaded value or zero" into a branch around the load.
-    unsigned agent0 = (unsigned)(m_begin + 8 * sg) % (unsigned)g.N;       // agent of the wave's first row of the step
-    const unsigned agent_step = 32u % (unsigned)g.N;
-    auto deposit = [&](char *buf, float (&f)[kSetsPerWave][8], int m0) {
+                float v[8];
+                unsigned agent = agent0;
 #pragma unroll
-        for (int i = 0; i < kSetsPerWave; ++i) {
-            const int col = lane + 64 * (2 * i + half);
-            float v[8];
-            unsigned agent = agent0;
-#pragma unroll
-            for (int r = 0; r < 8; ++r) {
-                asm volatile("" : "+v"(f[i][r]));
-                const bool live = m0 + 8 * sg + r < m_end;
-                const int cb = col - kPp;                          // column of B (with its appended columns)
-                float made = 0.0f;
-                if (cb >= g.Q && cb < g.Q + g.n_extra) made = g.extra_mode == kExtraOnes ? 1.0f : (cb - g.Q == (int)agent ? 1.0f : 0.0f);
-                const bool real = i < kSetsOfA ? col < g.P : cb < g.Q;
-                v[r] = live ? (real ? f[i][r] : (i < kSetsOfA ? 0.0f : made)) : 0.0f;
-                agent = agent + 1 == (unsigned)g.N ? 0u : agent + 1;
+                for (int r = 0; r < 8; ++r) {
+                    asm volatile("" : "+v"(f[i][r]));
+                    if (i < kSetsOfA) {
+                        v[r] = (!ENDS || sample + r < wave_end) ? f[i][r] : 0.0f;
+                    } else {
+                        const int which = g.extra_mode == kExtraOnes ? -1 : (int)agent;
+                        v[r] = made_of[i] == which ? 1.0f : (made_of[i] == -2 ? f[i][r] : 0.0f);
+                        agent = agent + 1 == (unsigned)g.N ? 0u : agent + 1;
+                    }
+                }
+                if (col < cols) {
+                    const Frag<P> fr = to_frag<P>(v);
+                    *reinterpret_cast<bf16x8 *>(buf + col * kPitch + 16 * sg) = fr.hi;
+                    if constexpr (P == 2) *reinterpret_cast<bf16x8 *>(buf + plane_bytes + col * kPitch + 16 * sg) = fr.lo;
+                }
             }
-            if (col < cols) {
-                const Frag<P> fr = to_frag<P>(v);
-                *reinterpret_cast<bf16x8 *>(buf + col * kPitch + 16 * sg) = fr.hi;
-                if constexpr (P == 2) *reinterpret_cast<bf16x8 *>(buf + plane_bytes + col * kPitch + 16 * sg) = fr.lo;
-            }
-        }
-        agent0 += agent_step;
-        agent0 = agent0 >= (unsigned)g.N ? agent0 - (unsigned)g.N : agent0;
-    };
+            sample += 8;
+            agent0 += agent_step;
+            agent0 = agent0 >= (unsigned)g.N ? agent0 - (unsigned)g.N : agent0;
+        };
 
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) fetch(rv[d], m_begin + 32 * d);
-    // Rounds of kDepth steps; steps past the end of the chunk add zeros.
-    for (int m0 = m_begin; m0 < m_end; m0 += 32 * kDepth) {
+        for (int d = 0; d < kDepth; ++d) fetch(rv[d]);
+        // Rounds of kDepth steps; steps past the end of the chunk add zeros.
+        for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
 #pragma unroll
-        for (int d = 0; d < kDepth; ++d) {
-            // Two buffers: one barrier per step (the buffer written now was last read two steps ago, and every
-            // wave has passed the previous step's barrier since).  One buffer: a barrier before writing too.
-            char *buf = stage + (kTwoBuffers ? (d & 1) * P * plane_bytes : 0);
-            if constexpr (!kTwoBuffers) __syncthreads();
-            deposit(buf, rv[d], m0 + 32 * d);
-            __syncthreads();
-            fetch(rv[d], m0 + 32 * (d + kDepth));
-            // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
-            const char *mine = buf + c * kPitch + 16 * q4;
-            WFrag<P> af[PBW];
+            for (int d = 0; d < kDepth; ++d) {
+                // Two buffers: one barrier per step (the buffer written now was last read two steps ago, and
+                // every wave has passed the previous step's barrier since).  One buffer: a barrier before writing too.
+                char *buf = stage + (kTwoBuffers ? (d & 1) * P * plane_bytes : 0);
+                if constexpr (!kTwoBuffers) __syncthreads();
+                deposit(buf, rv[d]);
+                __syncthreads();
+                fetch(rv[d]);
+                // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
+                const char *mine = buf + c * kPitch + 16 * q4;
+                WFrag<P> af[PBW];
 #pragma unroll
-            for (int k = 0; k < PBW; ++k) {
-                af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
-                if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
-            }
-#pragma unroll
-            for (int j = 0; j < QBN; ++j)
-                if (j < n_qb) {
-                    Frag<P> bf;
-                    bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (kPp + 16 * j) * kPitch);
-                    if constexpr (P == 2) bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (kPp + 16 * j) * kPitch);
-#pragma unroll
-                    for (int k = 0; k < PBW; ++k) mma16<P>(acc[k][j], af[k], bf);
+                for (int k = 0; k < PBW; ++k) {
+                    af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
+                    if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
                 }
+#pragma unroll
+                for (int j = 0; j < QBN; ++j)
+                    if (j < n_qb) {
+                        Frag<P> bf;
+                        bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (kPp + 16 * j) * kPitch);
+                        if constexpr (P == 2) bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (kPp + 16 * j) * kPitch);
+#pragma unroll
+                        for (int k = 0; k < PBW; ++k) mma16<P>(acc[k][j], af[k], bf);
+                    }
+            }
         }
-    }
+    };
+    // Rows touched: the last quarter's, plus what is fetched ahead of the last step (the loop runs whole rounds).
+    const int rounds_end = (n_steps + kDepth - 1) / kDepth * kDepth;
+    const bool all_inside = m_begin + 8 * (3 * n_steps + rounds_end + kDepth) <= g.M
+                            && rounds_end == n_steps && m_end - m_begin == 32 * n_steps;
+    // (two planes: the one general loop only - twice over, the loop did not fit the registers)
+    if (P == 1 && all_inside) run(std::integral_constant<bool, P != 1>{});
+    else run(std::true_type{});
 
     // C layout: lane (c, q4) holds result[16 block + 4 q4 + r][16 j + c]
     float *out = g.partial + (size_t)blockIdx.x * kPp * g.qp;
@@ -545,7 +599,7 @@ Plan make_plan(const NetFrags &net, int B, int T)
     const long M = (long)R * T;
     p.chunks = (int)std::min<long>(256, (M + 31) / 32);
     if (p.chunks < 1) p.chunks = 1;
-    p.chunk = (int)(((M + p.chunks - 1) / p.chunks + 31) / 32 * 32);
+    p.chunk = (int)(((M + p.chunks - 1) / p.chunks + 63) / 64 * 64);      // whole rounds of two steps of 32 samples
     size_t off = 0;
     p.off_h = off;      off = align_up(off + R * S * H * 4);
     p.off_x = off;      off = align_up(off + R * S * H * 4);
@@ -601,6 +655,15 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             g.N = t.N > 0 ? t.N : 1;
             g.qp = (t.Q + t.n_extra + 15) / 16 * 16;
             g.chunk = chunk;
+            // steps from row to row in elements, 32 bits each; an operand that is one group never takes the second
+            auto steps = [&](const RowMap &m, unsigned *next, unsigned *wrap) {
+                const long n = (long)m.ld;
+                const long w = m.rows_per_group >= M ? n : m.group_stride - (long)(m.rows_per_group - 1) * m.ld;
+                if (n < 0 || w < 0 || n >= (1L << 31) || w >= (1L << 31)) return false;
+                *next = (unsigned)n; *wrap = (unsigned)w;
+                return true;
+            };
+            if (!steps(t.a, &g.next_a, &g.wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
             const bool is_wide = t.P > 128;
             if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;

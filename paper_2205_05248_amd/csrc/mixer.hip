@@ -618,7 +618,7 @@ MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
     p.ldd = (F + d.embed + 1 + 3) / 4 * 4;
     // few samples (B T, not B T N) and many products that run side by side: chunks of about 256 transitions
     const long chunks = std::max<long>(1, std::min<long>(256, R / 256));
-    p.chunk = (int)(((R + chunks - 1) / chunks + 31) / 32 * 32);
+    p.chunk = (int)(((R + chunks - 1) / chunks + 63) / 64 * 64);
     size_t off = 0;
     p.off_dgen = off;    off = (off + (size_t)R * p.ldd * 4 + 255) / 256 * 256;
     // room for sixteen of the largest partial results: the products run sixteen at a time
