@@ -315,7 +315,8 @@ struct TnGemmArgs {
     int qp;             // Q + n_extra rounded up to 16: row pitch of the result
     int chunk;          // samples per workgroup along the contraction, a multiple of 32
     // elements from a row to the next: inside a group, and from a group's last row to the next group's first
-    unsigned next_a, wrap_a, next_b, wrap_b;
+    // (A's rows are one group: the adjoint arrays are)
+    unsigned next_a, next_b, wrap_b;
     float *partial;     // [chunks][128 or 384 rows][qp]
 };
 
@@ -388,12 +389,11 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     // stepping: a row further in the group, or from a group's last row to the next group's first.  All of it
     // is the same in every lane and is kept in scalar registers (said so where the compiler cannot tell).
     const unsigned row0 = (unsigned)min(wave_begin, g.M - 1);
-    const unsigned ga0 = __builtin_amdgcn_readfirstlane(row0 / (unsigned)g.a.rows_per_group);
     const unsigned gb0 = __builtin_amdgcn_readfirstlane(row0 / (unsigned)g.b.rows_per_group);
-    const unsigned ia0 = row0 - ga0 * (unsigned)g.a.rows_per_group, ib0 = row0 - gb0 * (unsigned)g.b.rows_per_group;
-    long off_a = (long)ga0 * g.a.group_stride + (long)ia0 * g.a.ld;          // in elements
+    const unsigned ib0 = row0 - gb0 * (unsigned)g.b.rows_per_group;
+    long off_a = (long)row0 * g.a.ld;                                        // in elements; A's rows follow one another
     long off_b = (long)gb0 * g.b.group_stride + (long)ib0 * g.b.ld;
-    unsigned a_left = (unsigned)g.a.rows_per_group - ia0, b_left = (unsigned)g.b.rows_per_group - ib0;   // rows to the group's end
+    unsigned b_left = (unsigned)g.b.rows_per_group - ib0;            // rows to the end of B's group
     unsigned rows_left = (unsigned)(g.M - 1) - row0;                  // steps that stay inside the arrays
     int sample = wave_begin;                                          // first sample of the step being staged
     unsigned agent0 = (unsigned)wave_begin % (unsigned)g.N;          // its agent, where rows are (.., agent) samples
@@ -413,9 +413,8 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
 #pragma unroll
                 for (int i = 0; i < kSetsPerWave; ++i) {
                     if constexpr (ABF) {
-                        if (i < kSetsOfA) {      // bf16 elements stay as they are, two rows to a register (even row: lower half)
-                            const uint32_t e = reinterpret_cast<const uint16_t *>(arow)[set_col[i]];
-                            f[i][r / 2] = __uint_as_float(r % 2 ? (__float_as_uint(f[i][r / 2]) | (e << 16)) : e);
+                        if (i < kSetsOfA) {      // a bf16 element stays as it is (nothing here may need the value: that would be a wait)
+                            f[i][r] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(arow)[set_col[i]]);
                             continue;
                         }
                     }
@@ -424,12 +423,12 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
                 // the next row, without a branch (a branch between two loads would make every wait a full one)
                 unsigned go = 1u;
                 if constexpr (ENDS) { go = rows_left ? 1u : 0u; rows_left -= go; }
-                a_left -= go; b_left -= go;
-                const bool wa = a_left == 0u, wb = b_left == 0u;
-                unsigned sa = wa ? g.wrap_a : g.next_a, sb = wb ? g.wrap_b : g.next_b;
+                b_left -= go;
+                const bool wb = b_left == 0u;
+                unsigned sa = g.next_a, sb = wb ? g.wrap_b : g.next_b;      // A's rows are one group (the launcher checks)
                 if constexpr (ENDS) { sa = go ? sa : 0u; sb = go ? sb : 0u; }
                 off_a += sa; off_b += sb;
-                a_left = wa ? (unsigned)g.a.rows_per_group : a_left;
+                asm volatile("" : "+s"(off_a));      // kept as one running scalar, not turned into a vector address per row
                 b_left = wb ? (unsigned)g.b.rows_per_group : b_left;
             }
         };
@@ -442,12 +441,12 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
             for (int i = 0; i < kSetsPerWave; ++i) {
                 const int col = lane + 64 * (2 * i + half);
                 if constexpr (ABF) {
-                    if (i < kSetsOfA) {       // the four registers are the fragment already
+                    if (i < kSetsOfA) {       // two bf16 values to a word, the earlier sample in the lower half: the fragment
                         uint32_t word[4];
 #pragma unroll
                         for (int j = 0; j < 4; ++j) {
-                            asm volatile("" : "+v"(f[i][j]));
-                            word[j] = __float_as_uint(f[i][j]);
+                            asm volatile("" : "+v"(f[i][2 * j]), "+v"(f[i][2 * j + 1]));
+                            word[j] = __float_as_uint(f[i][2 * j]) | (__float_as_uint(f[i][2 * j + 1]) << 16);
                             if constexpr (ENDS)
                                 word[j] &= sample + 2 * j + 1 < wave_end ? 0xFFFFFFFFu : (sample + 2 * j < wave_end ? 0x0000FFFFu : 0u);
                         }
@@ -481,34 +480,50 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
 
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) fetch(rv[d]);
-        // Rounds of kDepth steps; steps past the end of the chunk add zeros.
-        for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
+        // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
+        auto multiply = [&](const char *buf) {
+            const char *mine = buf + c * kPitch + 16 * q4;
+            WFrag<P> af[PBW];
 #pragma unroll
-            for (int d = 0; d < kDepth; ++d) {
-                // Two buffers: one barrier per step (the buffer written now was last read two steps ago, and
-                // every wave has passed the previous step's barrier since).  One buffer: a barrier before writing too.
-                char *buf = stage + (kTwoBuffers ? (d & 1) * P * plane_bytes : 0);
-                if constexpr (!kTwoBuffers) __syncthreads();
-                deposit(buf, rv[d]);
-                __syncthreads();
-                fetch(rv[d]);
-                // fragments: lane (c, q4) takes samples 8 q4 + 0..7 of column 16 block + c
-                const char *mine = buf + c * kPitch + 16 * q4;
-                WFrag<P> af[PBW];
+            for (int k = 0; k < PBW; ++k) {
+                af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
+                if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
+            }
 #pragma unroll
-                for (int k = 0; k < PBW; ++k) {
-                    af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
-                    if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
+            for (int j = 0; j < QBN; ++j)
+                if (j < n_qb) {
+                    Frag<P> bf;
+                    bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (kPp + 16 * j) * kPitch);
+                    if constexpr (P == 2) bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (kPp + 16 * j) * kPitch);
+#pragma unroll
+                    for (int k = 0; k < PBW; ++k) mma16<P>(acc[k][j], af[k], bf);
                 }
+        };
+        // Rounds of kDepth steps; steps past the end of the chunk add zeros.  The compiler's wait at the head of
+        // the loop is for everything asked for so far, whatever the order of the round.  Where two staging
+        // buffers fit, the round is therefore: stage both steps, ask for the next two, multiply both - every
+        // load has both multiplications to arrive in.
+        for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
+            if constexpr (kTwoBuffers) {
+                static_assert(kDepth == 2, "one staging buffer per step of a round");
+                char *second = stage + P * plane_bytes;
+                deposit(stage, rv[0]);
+                deposit(second, rv[1]);
+                fetch(rv[0]);
+                fetch(rv[1]);
+                __syncthreads();
+                multiply(stage);
+                multiply(second);
+                __syncthreads();               // every wave is done reading before the next round writes
+            } else {
 #pragma unroll
-                for (int j = 0; j < QBN; ++j)
-                    if (j < n_qb) {
-                        Frag<P> bf;
-                        bf.hi = *reinterpret_cast<const bf16x8 *>(mine + (kPp + 16 * j) * kPitch);
-                        if constexpr (P == 2) bf.lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + (kPp + 16 * j) * kPitch);
-#pragma unroll
-                        for (int k = 0; k < PBW; ++k) mma16<P>(acc[k][j], af[k], bf);
-                    }
+                for (int d = 0; d < kDepth; ++d) {
+                    __syncthreads();           // one buffer: the previous step has been read by every wave
+                    deposit(stage, rv[d]);
+                    fetch(rv[d]);              // asked for before the barrier, so that the wait at it is not idle time for memory
+                    __syncthreads();
+                    multiply(stage);
+                }
             }
         }
     };
@@ -663,7 +678,8 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
                 *next = (unsigned)n; *wrap = (unsigned)w;
                 return true;
             };
-            if (!steps(t.a, &g.next_a, &g.wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
+            unsigned wrap_a = 0;
+            if (t.a.rows_per_group < M || !steps(t.a, &g.next_a, &wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
             const bool is_wide = t.P > 128;
             if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;
