@@ -153,7 +153,8 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
 // Products over samples, C[p][q] = sum_m A[m][p] B[m][q] with fp32 operands in global memory (bptt.hip).
 // Row m of an operand lives at base + (m / rows_per_group) * group_stride + (m % rows_per_group) * ld.
 // Elements are fp32, or bf16 (bf16 != 0: the left operand A of a one-plane product only, the same for every product
-// of a call); group_stride and ld count elements either way.
+// of a call); group_stride and ld count elements either way.  A's rows must be one group (rows_per_group >= M), and
+// the steps from one row to the next (ld; from a group's last row to the next group's first) must lie in [0, 2^31).
 struct RowMap {
     const void *base;
     long group_stride;
