@@ -39,7 +39,8 @@ struct BpttArgs {
     const int32_t *actions;      // [B, T, N]
     const uint8_t *filled;       // [B, T]
     const float *grad_q;         // [B, T, N]   dL/dq_taken
-    const float *h_all, *x_all;  // [B, T+1, N, H]   h_all[b, s] = state before slot s
+    const float *h_all;          // [B, T+1, N, H]   h_all[b, s] = state before slot s
+    const void *x_all;           // [B, T+1, N, H]   x of slot s; fp32, or bf16 for a one-plane network
     // The adjoints, fp32 for fp32 networks and bf16 for bf16 networks (whose products round them to bf16 anyway:
     // stored rounded, they cost half the traffic to write here and to read in the weight-gradient products)
     void *da;                    // [B, T, N, 4H]   adjoints of the gate pre-activations: n (input side), r, z, n (hidden side)
@@ -132,7 +133,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
     const int unit0 = 16 * NBC * w + 4 * q4;                       // + 16 j: the lane's four units of block j
     const size_t slot_stride = (size_t)N * H;
     const float *h_row = a.h_all + ((size_t)b * S * N + n) * H + unit0;
-    const float *x_row = a.x_all + ((size_t)b * S * N + n) * H + unit0;
+    constexpr int kBytesX = P == 1 ? 2 : 4;
+    const char *x_row = static_cast<const char *>(a.x_all) + (((size_t)b * S * N + n) * H + unit0) * kBytesX;
 
     // The inputs of a slot are asked for one iteration before it; the chosen action, whose row of W2 is one
     // of those inputs, one iteration earlier still.  Nothing here is conditional (rows past the end read row 0).
@@ -147,7 +149,14 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
 #pragma unroll
         for (int j = 0; j < NBC; ++j) {
             in.hp[j] = *reinterpret_cast<const f32x4 *>(h_row + (size_t)t * slot_stride + 16 * j);
-            in.xv[j] = *reinterpret_cast<const f32x4 *>(x_row + (size_t)t * slot_stride + 16 * j);
+            const char *xp = x_row + ((size_t)t * slot_stride + 16 * j) * kBytesX;
+            if constexpr (P == 1) {      // four bf16 values, widened (bf16 is the upper half of an fp32)
+                const uint2 raw = *reinterpret_cast<const uint2 *>(xp);
+                in.xv[j][0] = __uint_as_float(raw.x << 16); in.xv[j][1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                in.xv[j][2] = __uint_as_float(raw.y << 16); in.xv[j][3] = __uint_as_float(raw.y & 0xFFFF0000u);
+            } else {
+                in.xv[j] = *reinterpret_cast<const f32x4 *>(xp);
+            }
             in.w2[j] = *reinterpret_cast<const f32x4 *>(net.w2_plain + (size_t)in.u * H + unit0 + 16 * j);
         }
         return in;
@@ -328,8 +337,8 @@ struct TnGemmBatch { TnGemmArgs g[kTnBatchMax]; };
 // memory once.  Wave w owns result row blocks w, w + 8, .. (PBW of them) and all QBN column blocks.  P: bf16
 // planes per operand, the network's own: 2 = every value as bf16 high part + bf16 of the remainder, three MFMAs
 // per product; 1 = values rounded to bf16, one MFMA.
-// ABF: A's elements are bf16 (the adjoints of a bf16 network), else fp32; B's are fp32.
-template <int PBW, int QBN, int P, bool ABF>
+// ABF: A's elements are bf16 (the adjoints of a bf16 network), else fp32.  BBF: the same for B's (its saved x).
+template <int PBW, int QBN, int P, bool ABF, bool BBF = false>
 __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatch batch)
 {
     const TnGemmArgs g = batch.g[blockIdx.y];
@@ -409,7 +418,7 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const char *arow = static_cast<const char *>(g.a.base) + off_a * (ABF ? 2 : 4);
-                const float *brow = static_cast<const float *>(g.b.base) + off_b;
+                const char *brow = static_cast<const char *>(g.b.base) + off_b * (BBF ? 2 : 4);
 #pragma unroll
                 for (int i = 0; i < kSetsPerWave; ++i) {
                     if constexpr (ABF) {
@@ -418,7 +427,13 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
                             continue;
                         }
                     }
-                    f[i][r] = i < kSetsOfA ? reinterpret_cast<const float *>(arow)[set_col[i]] : brow[set_col[i]];
+                    if constexpr (BBF) {
+                        if (i >= kSetsOfA) {
+                            f[i][r] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(brow)[set_col[i]]);
+                            continue;
+                        }
+                    }
+                    f[i][r] = i < kSetsOfA ? reinterpret_cast<const float *>(arow)[set_col[i]] : reinterpret_cast<const float *>(brow)[set_col[i]];
                 }
                 // the next row, without a branch (a branch between two loads would make every wait a full one)
                 unsigned go = 1u;
@@ -449,6 +464,26 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
                             word[j] = __float_as_uint(f[i][2 * j]) | (__float_as_uint(f[i][2 * j + 1]) << 16);
                             if constexpr (ENDS)
                                 word[j] &= sample + 2 * j + 1 < wave_end ? 0xFFFFFFFFu : (sample + 2 * j < wave_end ? 0x0000FFFFu : 0u);
+                        }
+                        if (col < cols) *reinterpret_cast<uint4 *>(buf + col * kPitch + 16 * sg) = make_uint4(word[0], word[1], word[2], word[3]);
+                        continue;
+                    }
+                }
+                if constexpr (BBF) {
+                    if (i >= kSetsOfA) {      // bf16 values of B, or the bf16 of an appended column's 1 or 0
+                        uint32_t word[4];
+                        unsigned agent = agent0;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            asm volatile("" : "+v"(f[i][2 * j]), "+v"(f[i][2 * j + 1]));
+                            uint32_t e[2];
+#pragma unroll
+                            for (int k = 0; k < 2; ++k) {
+                                const int which = g.extra_mode == kExtraOnes ? -1 : (int)agent;
+                                e[k] = made_of[i] == which ? 0x3F80u : (made_of[i] == -2 ? __float_as_uint(f[i][2 * j + k]) : 0u);
+                                agent = agent + 1 == (unsigned)g.N ? 0u : agent + 1;
+                            }
+                            word[j] = e[0] | (e[1] << 16);
                         }
                         if (col < cols) *reinterpret_cast<uint4 *>(buf + col * kPitch + 16 * sg) = make_uint4(word[0], word[1], word[2], word[3]);
                         continue;
@@ -617,7 +652,7 @@ Plan make_plan(const NetFrags &net, int B, int T)
     p.chunk = (int)(((M + p.chunks - 1) / p.chunks + 63) / 64 * 64);      // whole rounds of two steps of 32 samples
     size_t off = 0;
     p.off_h = off;      off = align_up(off + R * S * H * 4);
-    p.off_x = off;      off = align_up(off + R * S * H * 4);
+    p.off_x = off;      off = align_up(off + R * S * H * adj + 4);         // x: bf16 for a one-plane network
     p.off_da = off;     off = align_up(off + R * T * 4 * H * adj + 4);
     p.off_dpre1 = off;  off = align_up(off + R * T * H * adj + 4);
     p.off_dq = off;     off = align_up(off + R * T * p.a16 * adj + 4);
@@ -683,7 +718,10 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
             const bool is_wide = t.P > 128;
             if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;
-            if (t.b.bf16 || (t.a.bf16 != 0) != (list[0].a.bf16 != 0) || (t.a.bf16 && planes != 1)) return hipErrorInvalidValue;
+            if ((t.a.bf16 != 0) != (list[0].a.bf16 != 0) || (t.a.bf16 && planes != 1)) return hipErrorInvalidValue;
+            // B in bf16: the wide shape of a one-plane network with bf16 adjoints only; such products go in launches of their own
+            if (t.b.bf16 && !(is_wide && t.a.bf16)) return hipErrorInvalidValue;
+            if ((t.b.bf16 != 0) != (list[done].b.bf16 != 0)) break;
             const size_t bytes = tn_partial_bytes(M, chunk, t.P, t.Q + t.n_extra);
             if (bytes > partial_bytes) return hipErrorInvalidValue;
             if (used + bytes > partial_bytes || (is_wide ? n_wide : n_narrow) == kTnBatchMax || n_red == kTnBatchMax) break;
@@ -699,12 +737,13 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             max_total = std::max(max_total, t.P * (t.Q + t.n_extra));
         }
         hipError_t err = hipSuccess;
-#define MARL_TN(PBW, QBN, PL, ABF, BATCH, COUNT, PPAD, MAXQ)                                             \
+#define MARL_TN(PBW, QBN, PL, ABF, BATCH, COUNT, PPAD, MAXQ) MARL_TN2(PBW, QBN, PL, ABF, false, BATCH, COUNT, PPAD, MAXQ)
+#define MARL_TN2(PBW, QBN, PL, ABF, BBF, BATCH, COUNT, PPAD, MAXQ)                                       \
     do {                                                                                                 \
         const size_t lds = (size_t)(PL == 1 ? 2 : 1) * PL * (PPAD + MAXQ) * 80;      /* 80 bytes per staged column and plane */ \
-        err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL, ABF>>(kLdsLimit);                             \
+        err = allow_large_lds<tn_gemm_kernel<PBW, QBN, PL, ABF, BBF>>(kLdsLimit);                        \
         if (err != hipSuccess) return err;                                                               \
-        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL, ABF>), dim3(chunks, COUNT), dim3(kTnThreads), lds, stream, BATCH); \
+        hipLaunchKernelGGL((tn_gemm_kernel<PBW, QBN, PL, ABF, BBF>), dim3(chunks, COUNT), dim3(kTnThreads), lds, stream, BATCH); \
         err = hipGetLastError();                                                                         \
         if (err != hipSuccess) return err;                                                               \
     } while (0)
@@ -712,6 +751,7 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
         const bool a_bf16 = list[done].a.bf16 != 0;
         if (n_wide) {
             if (planes == 2) MARL_TN(3, 9, 2, false, wide, n_wide, 384, max_q_wide);
+            else if (a_bf16 && list[done].b.bf16) MARL_TN2(3, 9, 1, true, true, wide, n_wide, 384, max_q_wide);
             else if (a_bf16) MARL_TN(3, 9, 1, true, wide, n_wide, 384, max_q_wide);
             else MARL_TN(3, 9, 1, false, wide, n_wide, 384, max_q_wide);
         }
@@ -721,6 +761,7 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             else MARL_TN(1, 21, 1, false, narrow, n_narrow, 128, max_q_narrow);
         }
 #undef MARL_TN
+#undef MARL_TN2
         hipLaunchKernelGGL(tn_reduce_kernel, dim3((max_total + 255) / 256, n_red), dim3(256), 0, stream, red);
         err = hipGetLastError();
         if (err != hipSuccess) return err;
@@ -746,11 +787,11 @@ bool qnet_grad_fits(const NetFrags &net)
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T) { return make_plan(net, B, T).bytes; }
 
 // grad: packed like the weights (W1, b1, W_ih, W_hh, b_ih, b_hh, W2, b2), device, fully overwritten.
-void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, float **x_all)
+void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, void **x_all)
 {
     const Plan plan = make_plan(net, B, T);
     *h_all = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_h);
-    *x_all = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_x);
+    *x_all = static_cast<char *>(workspace) + plan.off_x;
 }
 
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
@@ -759,7 +800,8 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
 {
     const Plan plan = make_plan(net, B, T);
     char *ws = static_cast<char *>(workspace);
-    float *h_all = reinterpret_cast<float *>(ws + plan.off_h), *x_all = reinterpret_cast<float *>(ws + plan.off_x);
+    float *h_all = reinterpret_cast<float *>(ws + plan.off_h);
+    void *x_all = ws + plan.off_x;
     char *da = ws + plan.off_da, *dpre1 = ws + plan.off_dpre1, *dq = ws + plan.off_dq;
     float *partial = reinterpret_cast<float *>(ws + plan.off_partial);
     const int adj_bf16 = net.planes == 1 ? 1 : 0, adj_bytes = adj_bf16 ? 2 : 4;
@@ -789,7 +831,7 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     const RowMap plain_da{da, 0, (int)std::min<long>(M, 1 << 30), 4 * H, adj_bf16};
     const RowMap da_i = plain_da;                                        // columns n, r, z
     RowMap da_h = plain_da; da_h.base = da + (size_t)H * adj_bytes;      // columns r, z, n (hidden side)
-    const RowMap x_rows{x_all, (long)S * N * H, TN, H, 0};
+    const RowMap x_rows{x_all, (long)S * N * H, TN, H, adj_bf16};      // stored as the adjoints are
     const RowMap h_prev{h_all, (long)S * N * H, TN, H, 0};
     const RowMap h_new{h_all + (size_t)N * H, (long)S * N * H, TN, H, 0};
     const RowMap pre_rows{dpre1, 0, (int)std::min<long>(M, 1 << 30), H, adj_bf16};

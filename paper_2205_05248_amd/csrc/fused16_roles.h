@@ -192,10 +192,11 @@ template <int H, int P> struct Fc1Wave {
     }
 
     // One item: observation fragments obs_src[ks] (LDS) -> x fragments of this wave's blocks in x_dst.
-    // SAVE: x also goes, in fp32, to x_row[16 block + 0..3] (the caller has added the lane's 4 q; null: no store).
+    // SAVE: x also goes to elements 16 block + 0..3 of x_row (the caller has added the lane's 4 q; null: no store):
+    // fp32 for a two-plane network, bf16 for a one-plane network (the rounding every reader of x applies anyway).
     template <bool SAVE = false>
     __device__ __forceinline__ void step(const bf16x8 *obs_src, int ks1, int f, int lane, const f32x4 (&b1v)[NBF],
-                                         bf16x8 (*x_dst)[P][64], float *x_row = nullptr) const
+                                         bf16x8 (*x_dst)[P][64], void *x_row = nullptr) const
     {
         auto obs_frag = [&](int ks) {
             const bf16x8 *src = obs_src + (size_t)(ks * P) * 64 + lane;
@@ -227,7 +228,17 @@ template <int H, int P> struct Fc1Wave {
         if constexpr (SAVE) {
             if (x_row)
 #pragma unroll
-                for (int j = 0; j < NBF; ++j) *reinterpret_cast<f32x4 *>(x_row + 16 * (f * NBF + j)) = acc[j];
+                for (int j = 0; j < NBF; ++j) {
+                    if constexpr (P == 1) {
+                        typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                        bf16x4 v;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[r] = (__bf16)acc[j][r];
+                        *reinterpret_cast<bf16x4 *>(static_cast<__bf16 *>(x_row) + 16 * (f * NBF + j)) = v;
+                    } else {
+                        *reinterpret_cast<f32x4 *>(static_cast<float *>(x_row) + 16 * (f * NBF + j)) = acc[j];
+                    }
+                }
         }
 #pragma unroll
         for (int jj = 0; jj < NBF / 2; ++jj) {

@@ -375,7 +375,8 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
     }
     if (keep_workspace) {
         if (!fused) return MARL_ERR_BAD_DIM;
-        float *h_all, *x_all;
+        float *h_all;
+        void *x_all;
         marl::qnet_grad_activation_slots(online->net, B, T, keep_workspace, &h_all, &x_all);
         if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
         MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions,

@@ -118,7 +118,8 @@ size_t unroll_scratch_bytes(const NetFrags &net, int B, int T);
 // next_max / td_target alone; kTdValue with the target network reads those indices and writes
 // next_max / td_target from its own value of that action, and leaves q_taken / q_all alone.
 // kTdSave (fused kernels, one network): no TD output at all; the fc1 output x and the hidden state of
-// every slot go to x_save / h_save [B, T+1, N, H] fp32 for the backward pass: x_save[b, s] = x of slot s,
+// every slot go to x_save / h_save [B, T+1, N, H] for the backward pass (h fp32; x fp32, or bf16 for a one-plane
+// network, whose every use of x rounds it to bf16 anyway): x_save[b, s] = x of slot s,
 // h_save[b, 0] = 0 and h_save[b, s + 1] = the state after slot s (s < T).
 // kTdKeep: kTdPlain (one or two networks, all TD outputs) whose online network also stores x_save / h_save.
 enum TdMode : int { kTdPlain = 0, kTdSelect = 1, kTdValue = 2, kTdSave = 3, kTdKeep = 4 };
@@ -148,7 +149,7 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream,
                                TdMode mode = kTdPlain, int32_t *next_action = nullptr, float *h_save = nullptr,
-                               float *x_save = nullptr);
+                               void *x_save = nullptr);
 
 // Products over samples, C[p][q] = sum_m A[m][p] B[m][q] with fp32 operands in global memory (bptt.hip).
 // Row m of an operand lives at base + (m / rows_per_group) * group_stride + (m % rows_per_group) * ld.
@@ -184,7 +185,7 @@ bool qnet_grad_fits(const NetFrags &net);
 size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T);
 // activations_kept: the workspace already holds x and h of this batch (an unroll in kTdKeep mode wrote them to the
 // places qnet_grad_activation_slots names); otherwise the call runs its own forward pass first.
-void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, float **x_all);
+void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, void **x_all);
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
                             const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream,
                             bool activations_kept = false);

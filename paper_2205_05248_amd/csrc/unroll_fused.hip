@@ -43,7 +43,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     const uint8_t *__restrict__ avail, const int32_t *__restrict__ actions, const float *__restrict__ reward,
     const uint8_t *__restrict__ terminated, const uint8_t *__restrict__ filled, float gamma,
     float *__restrict__ q_taken, float *__restrict__ next_max, float *__restrict__ td_target, float *__restrict__ q_all,
-    int32_t *__restrict__ next_action, float *__restrict__ h_save, float *__restrict__ x_save)
+    int32_t *__restrict__ next_action, float *__restrict__ h_save, void *__restrict__ x_save)
 {
     using Sh = Fused16<H, P>;
     constexpr int FBK = Sh::FBK, KS = Sh::KS, LEAD = kFusedLead;
@@ -246,7 +246,8 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
             if (slot >= 0 && slot <= T) {
                 if constexpr (MODE == kTdSave || MODE == kTdKeep)
                     fc1.template step<true>(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1],
-                                            valid && !is_target ? x_save + (((size_t)b * S + slot) * N + n) * H + 4 * q4 : nullptr);
+                                            valid && !is_target ? static_cast<char *>(x_save) + ((((size_t)b * S + slot) * N + n) * H + 4 * q4) * (P == 1 ? 2 : 4)
+                                                                : nullptr);
                 else
                     fc1.step(obuf + (size_t)((slot & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[slot & 1]);
             }
@@ -277,7 +278,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
                           const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                           const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                           float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
-                          int32_t *next_action, float *h_save, float *x_save)
+                          int32_t *next_action, float *h_save, void *x_save)
 {
     using Sh = Fused16<H, P>;
     const int tiles = (B * online.N + 15) / 16;
@@ -337,7 +338,7 @@ hipError_t launch_unroll_fused(const NetFrags &online, const NetFrags &target, b
                                const int32_t *episode_index, int pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions, const float *reward,
                                const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                                float *next_max, float *td_target, float *q_all, hipStream_t stream, TdMode mode,
-                               int32_t *next_action, float *h_save, float *x_save)
+                               int32_t *next_action, float *h_save, void *x_save)
 {
     if ((mode == kTdSelect || mode == kTdValue) && (two_nets || !next_action)) return hipErrorInvalidValue;
     if (mode == kTdSave && (two_nets || !h_save || !x_save)) return hipErrorInvalidValue;
