@@ -362,13 +362,13 @@ def grad_section(ci, with_cpu, launches=10):
     back = rows * T * (12 * H * H + 12 * H * H)                        # the gates again + the two transposed products
     wgrad = rows * T * (2 * 2 * 3 * H * (H + 1) + 2 * H * (D + N) + 2 * A * (H + 1))
     flops = fwd + back + wgrad
-    # bytes the four stages move by design (fp32 activations and adjoints kept in the workspace): the forward pass
+    # bytes the four stages move by design (activations and adjoints kept in the workspace): the forward pass
     # reads the observations and writes x and h; the reverse pass reads x and h and writes the adjoints; each
     # product reads its two operands once
     a16 = (A + 15) // 16 * 16
-    adj = 2 if cfg["dtype"] == "bf16" else 4                  # bytes per stored adjoint (bf16 networks keep them as bf16)
-    io_bytes = (rows * (T + 1) * (4 * D + 8 * H) + rows * T * (8 * H + adj * (5 * H + a16))
-                + rows * T * (2 * (adj * 3 * H + 4 * H) + (adj * H + 4 * D) + (adj * a16 + 4 * H)))
+    adj = 2 if cfg["dtype"] == "bf16" else 4                  # bytes per stored adjoint and per saved x (bf16 networks keep both as bf16)
+    io_bytes = (rows * (T + 1) * (4 * D + 4 * H + adj * H) + rows * T * (4 * H + adj * H + adj * (5 * H + a16))
+                + rows * T * ((adj * 3 * H + adj * H) + (adj * 3 * H + 4 * H) + (adj * H + 4 * D) + (adj * a16 + 4 * H)))
     out = {"kernel": "qnet_grad (4 kernels)", "ms": ms, "transitions_per_s": B * T / (ms * 1e-3), "bound": "hbm",
            "GBs": io_bytes / (ms * 1e-3) / 1e9, "hbm_frac": io_bytes / (ms * 1e-3) / 1e9 / PEAK["hbm_GBs"],
            "TFLOPs": flops / (ms * 1e-3) / 1e12, "mfma_frac": flops / (ms * 1e-3) / 1e12 / PEAK["bf16_TFs"],
