@@ -2,7 +2,8 @@
 // sum(g * q_taken) with respect to every parameter, g = dL/dq_taken handed in by the caller.
 //
 //   unroll_fused_kernel<.., kTdSave>   (unroll_fused.hip) forward pass of the online network that keeps x and
-//                                      h of every slot in global memory, fp32, [B, T+1, N, H]
+//                                      h of every slot in global memory, [B, T+1, N, H]: h in fp32, x in fp32
+//                                      or, for a bf16 network, in bf16 (what every reader rounds it to)
 //   bptt_back_kernel                   one workgroup per 16 (episode, agent) rows walks the slots backwards.
 //                                      Per slot it recomputes the gates from x_t and h_{t-1} (two MFMA
 //                                      products, as the forward pass), forms the adjoints of the four gate
@@ -373,8 +374,7 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
 
     // Inputs are asked for kDepth steps before they are used, into kDepth register sets that the unrolled
     // loop addresses statically.  Every load is unconditional (rows past the end of the arrays repeat the last
-    // row, columns past an operand's width repeat its first), so the loop is straight-line code and each wait
-    // covers exactly the set it needs.
+    // row, columns past an operand's width repeat its first), so the loop is straight-line code.
     constexpr int kDepth = 2;
     float rv[kDepth][kSetsPerWave][8];
     // kPp is a multiple of 128, so set i of either half of the waves is one of A's exactly for i < kPp / 128:
