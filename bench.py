@@ -70,7 +70,7 @@ def unroll_bytes_per_agent_step(N, D, A, H):
     return 4 * D + A + 16
 
 
-KERNELS = {"auto": 0, "tile32": 1, "fused16": 2}
+KERNELS = {"auto": 0, "tile32": 1, "fused16": 2, "stream16": 3}
 
 
 class Bench:

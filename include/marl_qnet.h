@@ -337,19 +337,29 @@ int marl_qnet_grad_kept(marl_qnet *q, int32_t B, int32_t T,
  *            hidden = 64 and obs_dim <= 160; for marl_act_step also n_actions >= 4)
  *   tile32   tiles of 32 rows, weights streamed; the unroll is two kernels with a scratch buffer
  *            between them; serves every network
+ *   stream16 a second decision-step kernel on tiles of 16 rows (marl_unroll_td runs fused16 with this choice):
+ *            every wavefront holds one block of 16 hidden units of all three weight matrices, inputs travel
+ *            from global memory into LDS without passing through registers, and tiles are dealt round-robin
+ *            over the workgroups.  It serves bf16 weights with obs_dim + n_agents <= 384 and fp32 weights
+ *            with hidden = 64 and obs_dim + n_agents <= 192, for batches whose arrays stay below 2^30 bytes
+ *            and are 16-byte aligned; a call it cannot serve runs on fused16 / tile32 as under AUTO.  Measured
+ *            slower than fused16 on all five workloads, hence not what AUTO picks.
  *   MARL_KERNELS_AUTO     per entry point, fused16 when the network fits it, else tile32 (the default)
  *   MARL_KERNELS_TILE32   always tile32
  *   MARL_KERNELS_FUSED16  always fused16; MARL_ERR_BAD_DIM if the network does not fit it for both
  *                         entry points
+ *   MARL_KERNELS_STREAM16 stream16 for marl_act_step, fused16 for the unroll; MARL_ERR_BAD_DIM if the network
+ *                         fits neither
  * Returns MARL_ERR_BAD_ARG for any other value.
  */
 #define MARL_KERNELS_AUTO 0
 #define MARL_KERNELS_TILE32 1
 #define MARL_KERNELS_FUSED16 2
+#define MARL_KERNELS_STREAM16 3
 int marl_qnet_set_kernels(marl_qnet *q, int32_t which);
 
-/* The family an entry point uses for this handle as things stand: MARL_KERNELS_TILE32 or
- * MARL_KERNELS_FUSED16 (never AUTO).  Negative status for a null handle or an unknown entry. */
+/* The family an entry point uses for this handle as things stand: MARL_KERNELS_TILE32,
+ * MARL_KERNELS_FUSED16 or MARL_KERNELS_STREAM16 (never AUTO).  Negative status for a null handle or an unknown entry. */
 #define MARL_ENTRY_ACT_STEP 0
 #define MARL_ENTRY_UNROLL_TD 1
 int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry);

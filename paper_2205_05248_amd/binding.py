@@ -229,7 +229,7 @@ def marl_qnet_reserve_unroll(handle, B, T):
     check(load().marl_qnet_reserve_unroll(ctypes.c_void_p(handle), B, T))
 
 
-KERNELS_AUTO, KERNELS_TILE32, KERNELS_FUSED16 = 0, 1, 2
+KERNELS_AUTO, KERNELS_TILE32, KERNELS_FUSED16, KERNELS_STREAM16 = 0, 1, 2, 3
 
 
 def marl_qnet_set_kernels(handle, path):

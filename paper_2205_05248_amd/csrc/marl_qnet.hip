@@ -171,10 +171,12 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     n.wih_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wih_16);
     n.whh_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whh_16);
     n.w2_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w2_16);
+    n.w1x_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_w1x_16);
     n.wihT_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_wihT_16);
     n.whhT_16 = reinterpret_cast<const marl::bf16x8 *>(base + img.off_whhT_16);
     n.w2_plain = reinterpret_cast<const float *>(base + img.off_w2_plain);
     n.bias1 = reinterpret_cast<const float *>(base + img.off_bias1);
+    n.b1_plain = reinterpret_cast<const float *>(base + img.off_b1_plain);
     n.bias_r = reinterpret_cast<const float *>(base + img.off_bias_r);
     n.bias_z = reinterpret_cast<const float *>(base + img.off_bias_z);
     n.bias_in = reinterpret_cast<const float *>(base + img.off_bias_in);
@@ -227,6 +229,13 @@ bool takes_fused_path(const marl_qnet *q, bool for_unroll)
     if (q->kernels == MARL_KERNELS_TILE32) return false;
     return for_unroll ? marl::unroll_fused_fits(q->net) : marl::act_fused_fits(q->net);
 }
+// The streaming decision step: on request only (slower than fused16 on every workload measured), when the
+// network and the batch fit it.
+bool takes_stream_path(const marl_qnet *q, int E)
+{
+    if (q->kernels != MARL_KERNELS_STREAM16) return false;
+    return marl::act_stream_fits(q->net, E);
+}
 }  // namespace
 
 int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avail, const float *h_in,
@@ -251,7 +260,10 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
         if (rc != MARL_OK) return rc;
     }
     if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
-    if (takes_fused_path(q, false))
+    const bool all_aligned = aligned16(obs) && aligned16(avail) && aligned16(step_t) && (!q_out || aligned16(q_out)) && aligned16(action);
+    if (takes_stream_path(q, E) && all_aligned)
+        MARL_HIP(marl::launch_act_stream(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
+    else if (takes_fused_path(q, false))
         MARL_HIP(marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
     else
         MARL_HIP(marl::launch_act_step(q->net, E, nullptr, 0, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
@@ -291,14 +303,16 @@ int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry)
 {
     if (!q) return MARL_ERR_NULL;
     if (entry != MARL_ENTRY_ACT_STEP && entry != MARL_ENTRY_UNROLL_TD) return MARL_ERR_BAD_ARG;
+    if (entry == MARL_ENTRY_ACT_STEP && takes_stream_path(q, 1)) return MARL_KERNELS_STREAM16;
     return takes_fused_path(q, entry == MARL_ENTRY_UNROLL_TD) ? MARL_KERNELS_FUSED16 : MARL_KERNELS_TILE32;
 }
 
 int marl_qnet_set_kernels(marl_qnet *q, int32_t path)
 {
     if (!q) return MARL_ERR_NULL;
-    if (path != MARL_KERNELS_AUTO && path != MARL_KERNELS_TILE32 && path != MARL_KERNELS_FUSED16) return MARL_ERR_BAD_ARG;
+    if (path != MARL_KERNELS_AUTO && path != MARL_KERNELS_TILE32 && path != MARL_KERNELS_FUSED16 && path != MARL_KERNELS_STREAM16) return MARL_ERR_BAD_ARG;
     if (path == MARL_KERNELS_FUSED16 && !(marl::unroll_fused_fits(q->net) && marl::act_fused_fits(q->net))) return MARL_ERR_BAD_DIM;
+    if (path == MARL_KERNELS_STREAM16 && !(marl::unroll_fused_fits(q->net) && marl::act_stream_fits(q->net, 1))) return MARL_ERR_BAD_DIM;
     q->kernels = path;
     return MARL_OK;
 }

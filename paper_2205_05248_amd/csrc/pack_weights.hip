@@ -115,10 +115,13 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
     out->off_wih_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
     out->off_whh_16 = off;  off = align256(off + (size_t)3 * FBK * KS * frag_bytes);
     out->off_w2_16 = off;   off = align256(off + (size_t)ab * KS * frag_bytes);
+    const int ks1x = (Din + 31) / 32;
+    out->off_w1x_16 = off;  off = align256(off + (size_t)FBK * ks1x * frag_bytes);
     out->off_wihT_16 = off; off = align256(off + (size_t)FBK * 3 * KS * frag_bytes);
     out->off_whhT_16 = off; off = align256(off + (size_t)FBK * 3 * KS * frag_bytes);
     out->off_w2_plain = off; off = align256(off + sizeof(float) * (size_t)A * H);
     out->off_bias1 = off;   off = align256(off + sizeof(float) * (size_t)N * H);
+    out->off_b1_plain = off; off = align256(off + sizeof(float) * H);
     out->off_bias_r = off;  off = align256(off + sizeof(float) * H);
     out->off_bias_z = off;  off = align256(off + sizeof(float) * H);
     out->off_bias_in = off; off = align256(off + sizeof(float) * H);
@@ -186,6 +189,8 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
                          Whh + (size_t)gate * H * H, H, H, H, true, planes);
         }
         pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_w2_16), W2, A, H, H, true, planes);
+        // the same first layer with the agent-id columns kept in the product (streaming decision step)
+        pack_frags16(reinterpret_cast<uint16_t *>(img + out->off_w1x_16), W1, H, Din, Din, false, planes);
     }
 
     // Backward pass: W_ih^T and W_hh^T as [H, 3H] matrices (row k, column gate H + j), and fc2 as it is.
@@ -210,6 +215,7 @@ bool pack_network(const marl_qnet_desc &d, const float *w, PackedImage *out)
             if (planes == 1) col = bf16_value(bf16_bits(col));
             bias1[(size_t)n * H + j] = b1[j] + col;
         }
+    std::memcpy(img + out->off_b1_plain, b1, sizeof(float) * H);
     float *br = reinterpret_cast<float *>(img + out->off_bias_r), *bz = reinterpret_cast<float *>(img + out->off_bias_z);
     float *bin = reinterpret_cast<float *>(img + out->off_bias_in), *bhn = reinterpret_cast<float *>(img + out->off_bias_hn);
     for (int j = 0; j < H; ++j) {

@@ -36,12 +36,15 @@ struct NetFrags {
     const bf16x8 *wih_16;   // [3][H/16][H/32][P][64]
     const bf16x8 *whh_16;   // [3][H/16][H/32][P][64]
     const bf16x8 *w2_16;    // [ceil(A/16)][H/32][P][64]
+    // streaming decision step: W1 with the agent-id columns as part of the product, [H/16][ceil((D+N)/32)][P][64]
+    const bf16x8 *w1x_16;
     // backward pass: the transposed GRU matrices (H output rows, contraction over the 3H stacked gate
     // units r, z, n) as 16x16x32 fragments [H/16][3H/32][P][64], and fc2 as plain fp32 [A][H]
     const bf16x8 *wihT_16;
     const bf16x8 *whhT_16;
     const float *w2_plain;
     const float *bias1;   // [N][H]   b1 + W1[:, D + n]
+    const float *b1_plain; // [H]     b1
     const float *bias_r;  // [H]      b_ir + b_hr
     const float *bias_z;  // [H]      b_iz + b_hz
     const float *bias_in; // [H]
@@ -60,7 +63,7 @@ struct NetFrags {
 struct PackedImage {
     void *host;        // malloc'ed image, caller frees
     size_t bytes;
-    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_wihT_16, off_whhT_16, off_w2_plain, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    size_t off_act, off_proj, off_whh, off_w2, off_w1_16, off_wih_16, off_whh_16, off_w2_16, off_w1x_16, off_wihT_16, off_whhT_16, off_w2_plain, off_bias1, off_b1_plain, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
     int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 
@@ -138,6 +141,13 @@ bool act_fused_fits(const NetFrags &net);
 hipError_t launch_act_fused(const NetFrags &net, int E, int groups_hint, const float *obs, const uint8_t *avail,
                             const float *h_in, const uint8_t *reset, const int32_t *step_t, float epsilon,
                             uint64_t seed, float *h_out, int32_t *action, float *q_out, hipStream_t stream);
+
+// Streaming decision step (act_stream.hip): `fits` for this network and batch; n_cu = compute units of the device.
+// Every array must be 16-byte aligned.
+bool act_stream_fits(const NetFrags &net, int E);
+hipError_t launch_act_stream(const NetFrags &net, int E, int n_cu, const float *obs, const uint8_t *avail,
+                             const float *h_in, const uint8_t *reset, const int32_t *step_t, float epsilon,
+                             uint64_t seed, float *h_out, int32_t *action, float *q_out, hipStream_t stream);
 
 // Fused unroll (unroll_fused.hip): no scratch buffer.  `fits` tells whether the network's shape
 // fits the kernel's LDS and register budgets; otherwise the two-kernel path above is used.

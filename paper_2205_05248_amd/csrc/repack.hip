@@ -97,7 +97,7 @@ __global__ void copy_map_kernel(const float *w, const int32_t *src, float *dst, 
 struct TableArgs {
     const float *w;
     char *image;
-    size_t off_w2_plain, off_bias1, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
+    size_t off_w2_plain, off_bias1, off_b1_plain, off_bias_r, off_bias_z, off_bias_in, off_bias_hn, off_b2;
     int N, D, A, H, planes;
 };
 
@@ -114,6 +114,7 @@ __global__ void repack_tables_kernel(TableArgs t)
         reinterpret_cast<float *>(t.image + t.off_bias1)[i] = __fadd_rn(b1[j], as_stored(W1[(size_t)j * Din + D + n]));
     }
     if (i < H) {
+        reinterpret_cast<float *>(t.image + t.off_b1_plain)[i] = b1[i];
         reinterpret_cast<float *>(t.image + t.off_bias_r)[i] = __fadd_rn(bih[i], bhh[i]);
         reinterpret_cast<float *>(t.image + t.off_bias_z)[i] = __fadd_rn(bih[H + i], bhh[H + i]);
         reinterpret_cast<float *>(t.image + t.off_bias_in)[i] = bih[2 * H + i];
@@ -233,7 +234,7 @@ hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout
     if (err != hipSuccess) return err;
     TableArgs t{};
     t.w = weights; t.image = static_cast<char *>(image_dev);
-    t.off_w2_plain = layout.off_w2_plain; t.off_bias1 = layout.off_bias1; t.off_bias_r = layout.off_bias_r;
+    t.off_w2_plain = layout.off_w2_plain; t.off_bias1 = layout.off_bias1; t.off_b1_plain = layout.off_b1_plain; t.off_bias_r = layout.off_bias_r;
     t.off_bias_z = layout.off_bias_z; t.off_bias_in = layout.off_bias_in; t.off_bias_hn = layout.off_bias_hn;
     t.off_b2 = layout.off_b2;
     t.N = desc.n_agents; t.D = desc.obs_dim; t.A = desc.n_actions; t.H = desc.hidden; t.planes = planes;

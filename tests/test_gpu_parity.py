@@ -42,10 +42,13 @@ def oracle_unroll(cfg, w_on, w_tg, u, rows=None):
 # Both kernel families are held to the same bar.
 PATHS = [binding.KERNELS_TILE32, binding.KERNELS_FUSED16]
 PATH_IDS = ["tile32", "fused16"]
+# the decision step has a third implementation (the default where it fits)
+ACT_PATHS = PATHS + [binding.KERNELS_STREAM16]
+ACT_PATH_IDS = PATH_IDS + ["stream16"]
 
 
 # ------------------------------------------------------------------ act-step
-@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("path", ACT_PATHS, ids=ACT_PATH_IDS)
 @pytest.mark.parametrize("ci", [0, 1, 2, 3, 4])
 def test_act_step_full_config(ci, path):
     cfg = wl.config(ci)
@@ -65,7 +68,7 @@ def test_act_step_full_config(ci, path):
     net.close()
 
 
-@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("path", ACT_PATHS, ids=ACT_PATH_IDS)
 @pytest.mark.parametrize("ci,E", [(0, 1), (0, 5), (0, 11), (1, 3), (1, 37), (3, 13), (3, 203), (3, 1000), (4, 1), (4, 9)])
 def test_act_step_ragged_sizes(ci, E, path):
     cfg = wl.config(ci)
