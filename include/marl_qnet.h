@@ -94,7 +94,6 @@ size_t marl_param_count(const marl_qnet_desc *desc);
 int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size_t n_weights,
                      marl_qnet **out);
 
-/* Copy of the description the handle was created with. */
 /*
  * Replace the weights of a network in place (the learner publishing new parameters to the
  * worker's copy; Sec. "Learner" and Alg. 3, the periodic parameter copy).  host_weights: the same
@@ -107,6 +106,7 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
  */
 int marl_qnet_set_weights(marl_qnet *q, const float *host_weights, size_t n_weights, void *hip_stream);
 
+/* Copy of the description the handle was created with. */
 int marl_qnet_get_desc(const marl_qnet *q, marl_qnet_desc *out);
 
 /*
@@ -366,9 +366,11 @@ int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry);
 
 /*
  * Kernel timing for benchmarks.  While timing is enabled on a handle, marl_act_step and
- * marl_unroll_td (the `online` handle's setting counts) record HIP events on the caller's
- * stream around each kernel they launch, for up to MARL_TIMING_MAX_CALLS calls (later calls
- * run untimed).  marl_qnet_timing_read waits for the recorded events, returns the mean
+ * marl_unroll_td (the `online` handle's setting counts) time each kernel they launch with HIP
+ * events on the caller's stream, for up to MARL_TIMING_MAX_CALLS calls (later calls run untimed).
+ * The one-kernel paths (fused16, stream16) launch their kernel with a start and a stop event of its
+ * own, so the interval is the kernel's duration alone; the tile32 path records events before,
+ * between and after its kernels, which also counts the gaps between them.  marl_qnet_timing_read waits for the recorded events, returns the mean
  * duration in milliseconds of each kernel over the recorded calls, and clears the record:
  *   act_ms      decision-step kernel, over *act_calls calls
  *   unroll_ms   two-kernel path: [0] input-projection kernel, [1] recurrent TD kernel;

@@ -343,7 +343,7 @@ hipError_t act_dispatch(const ActFusedArgs &a, hipStream_t stream)
         auto kernel = act_fused_kernel<H, P, ABLK>;                                                                 \
         hipError_t err = allow_large_lds<act_fused_kernel<H, P, ABLK>>(kLdsLimit);                                  \
         if (err != hipSuccess) return err;                                                                          \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, a);                                                    \
+        launch_kernel(kernel, grid, block, lds, stream, a);                                                         \
     } while (0)
     switch ((a.net.A + 15) / 16) {
     case 1: MARL_ACTF(1); break;

@@ -579,7 +579,7 @@ hipError_t stream_launch_one(const ActStreamArgs &a, int groups, hipStream_t str
         allowed.fetch_or(1ull << (dev & 63), std::memory_order_release);
     }
     const size_t lds_bytes = StreamLds<H, P>::total(a.net.D);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(64 * (H / 16)), lds_bytes, stream, a);
+    launch_kernel(kernel, dim3((unsigned)groups), dim3(64 * (H / 16)), lds_bytes, stream, a);
     return hipGetLastError();
 }
 

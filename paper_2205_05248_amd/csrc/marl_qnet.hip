@@ -100,10 +100,18 @@ hipEvent_t *take_events(marl_qnet *q, int count, int *rc)
     return ev;
 }
 
+// Takes back the events of the call recorded last (its launch failed).
+void drop_events(marl_qnet *q, int count)
+{
+    q->timed_calls.pop_back();
+    q->ev_used -= count;
+}
+
 }  // namespace
 
 namespace marl {
 int report_device_error(hipError_t err, const char *what) { return device_fail(err, what); }
+thread_local const KernelTimer *g_kernel_timer = nullptr;
 }  // namespace marl
 
 extern "C" {
@@ -243,7 +251,7 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
                   float *h_out, int32_t *action, float *q_out, void *hip_stream)
 {
     if (!q) return MARL_ERR_NULL;
-    if (E < 0 || (int64_t)E * q->desc.n_agents > (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+    if (E < 0 || (int64_t)E * q->desc.n_agents >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
     if (!unit_interval(epsilon)) return MARL_ERR_BAD_ARG;
     if (E == 0) return MARL_OK;
     if (!obs || !avail || !h_in || !step_t || !h_out || !action) return MARL_ERR_NULL;
@@ -252,6 +260,8 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool all_aligned = aligned16(obs) && aligned16(avail) && aligned16(step_t) && (!q_out || aligned16(q_out)) && aligned16(action);
+    const bool stream_path = takes_stream_path(q, E) && all_aligned, fused_path = takes_fused_path(q, false);
     hipEvent_t *ev = nullptr;
     if (q->timing) {
         q->ev_pool.reserve(3 * MARL_TIMING_MAX_CALLS);      // keeps handed-out pointers stable
@@ -259,15 +269,27 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
         ev = take_events(q, 2, &rc);
         if (rc != MARL_OK) return rc;
     }
-    if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
-    const bool all_aligned = aligned16(obs) && aligned16(avail) && aligned16(step_t) && (!q_out || aligned16(q_out)) && aligned16(action);
-    if (takes_stream_path(q, E) && all_aligned)
-        MARL_HIP(marl::launch_act_stream(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
-    else if (takes_fused_path(q, false))
-        MARL_HIP(marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
-    else
-        MARL_HIP(marl::launch_act_step(q->net, E, nullptr, 0, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream));
-    if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
+    // one-kernel paths: the events take the kernel's own start and end; the tile32 path records them around its launches
+    marl::KernelTimer timer{};
+    if (ev && (stream_path || fused_path)) {
+        timer = {ev[0], ev[1]};
+        marl::g_kernel_timer = &timer;
+    }
+    hipError_t err = hipSuccess;
+    if (stream_path) {
+        err = marl::launch_act_stream(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
+    } else if (fused_path) {
+        err = marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
+    } else {
+        if (ev) err = hipEventRecord(ev[0], stream);
+        if (err == hipSuccess) err = marl::launch_act_step(q->net, E, nullptr, 0, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
+        if (err == hipSuccess && ev) err = hipEventRecord(ev[1], stream);
+    }
+    marl::g_kernel_timer = nullptr;
+    if (err != hipSuccess) {
+        if (ev) drop_events(q, 2);                         // the record must not keep events that were never recorded
+        return device_fail(err, "marl_act_step launch");
+    }
     return MARL_OK;
 }
 
@@ -276,7 +298,7 @@ int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int
                           float epsilon, uint64_t seed, float *h_out, int32_t *action, float *q_out, void *hip_stream)
 {
     if (!q) return MARL_ERR_NULL;
-    if (E < 0 || (int64_t)E * q->desc.n_agents > (int64_t)1 << 30 || n_listed < 0 || n_listed > E) return MARL_ERR_BAD_DIM;
+    if (E < 0 || (int64_t)E * q->desc.n_agents >= (int64_t)1 << 30 || n_listed < 0 || n_listed > E) return MARL_ERR_BAD_DIM;
     if (!unit_interval(epsilon)) return MARL_ERR_BAD_ARG;
     if (n_listed == 0) return MARL_OK;
     if (!env_index || !obs || !avail || !h_in || !step_t || !h_out || !action) return MARL_ERR_NULL;
@@ -291,7 +313,7 @@ int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int
 int marl_qnet_reserve_unroll(marl_qnet *q, int32_t B, int32_t T)
 {
     if (!q) return MARL_ERR_NULL;
-    if (B < 0 || T < 1 || (int64_t)B * q->desc.n_agents > (int64_t)1 << 30 || (int64_t)T > (int64_t)1 << 20)
+    if (B < 0 || T < 1 || (int64_t)B * q->desc.n_agents >= (int64_t)1 << 30 || (int64_t)T > (int64_t)1 << 20)
         return MARL_ERR_BAD_DIM;
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
@@ -355,6 +377,7 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
         if (rc == MARL_OK && online != target) rc = ensure_scratch(target, need);
         if (rc != MARL_OK) return rc;
     }
+    if (keep_workspace && !fused) return MARL_ERR_BAD_DIM;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipEvent_t *ev = nullptr;
     if (online->timing) {
@@ -362,55 +385,70 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
         ev = take_events(online, 3, &rc);
         if (rc != MARL_OK) return rc;
     }
-    if (ev) MARL_HIP(hipEventRecord(ev[0], stream));
-    if (double_q) {
-        // Selection by the online network (q_taken, q_all, next_action), then valuation by the target
-        // network (next_max, td_target); the stream orders the second launch after the first.
-        if (fused) {
-            if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
-            MARL_HIP(marl::launch_unroll_fused(online->net, online->net, false, B, T, episode_index, pool_episodes, obs,
-                                               avail, actions, reward, terminated, filled, gamma, q_taken, nullptr,
-                                               nullptr, q_all, stream, marl::kTdSelect, next_action));
-            MARL_HIP(marl::launch_unroll_fused(target->net, target->net, false, B, T, episode_index, pool_episodes, obs,
-                                               avail, actions, reward, terminated, filled, gamma, nullptr, next_max,
-                                               td_target, nullptr, stream, marl::kTdValue, next_action));
-        } else {
-            MARL_HIP(marl::launch_unroll_td(online->net, online->net, false, online->scratch, online->scratch, B, T,
-                                            episode_index, pool_episodes, obs, avail, actions, reward, terminated,
-                                            filled, gamma, q_taken, nullptr, nullptr, q_all, stream,
-                                            ev ? ev[1] : nullptr, marl::kTdSelect, next_action));
-            MARL_HIP(marl::launch_unroll_td(target->net, target->net, false, target->scratch, target->scratch, B, T,
-                                            episode_index, pool_episodes, obs, avail, actions, reward, terminated,
-                                            filled, gamma, nullptr, next_max, td_target, nullptr, stream, nullptr,
-                                            marl::kTdValue, next_action));
+    // Events of a timed call: [0] before anything, [1] between the input projection and the recurrence (tile32) or the
+    // start of the last kernel (fused16: its own start, by an extended launch), [2] the end.
+    marl::KernelTimer timer{};
+    auto time_next_kernel = [&]() {
+        if (!ev) return;
+        timer = {ev[1], ev[2]};
+        marl::g_kernel_timer = &timer;
+    };
+    auto run = [&]() -> hipError_t {
+        hipError_t err = hipSuccess;
+        if (ev) err = hipEventRecord(ev[0], stream);
+        if (err != hipSuccess) return err;
+        if (double_q) {
+            // Selection by the online network (q_taken, q_all, next_action), then valuation by the target
+            // network (next_max, td_target); the stream orders the second launch after the first.
+            if (fused) {
+                err = marl::launch_unroll_fused(online->net, online->net, false, B, T, episode_index, pool_episodes, obs,
+                                                avail, actions, reward, terminated, filled, gamma, q_taken, nullptr,
+                                                nullptr, q_all, stream, marl::kTdSelect, next_action);
+                if (err != hipSuccess) return err;
+                time_next_kernel();
+                return marl::launch_unroll_fused(target->net, target->net, false, B, T, episode_index, pool_episodes, obs,
+                                                 avail, actions, reward, terminated, filled, gamma, nullptr, next_max,
+                                                 td_target, nullptr, stream, marl::kTdValue, next_action);
+            }
+            err = marl::launch_unroll_td(online->net, online->net, false, online->scratch, online->scratch, B, T,
+                                         episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                                         filled, gamma, q_taken, nullptr, nullptr, q_all, stream,
+                                         ev ? ev[1] : nullptr, marl::kTdSelect, next_action);
+            if (err != hipSuccess) return err;
+            err = marl::launch_unroll_td(target->net, target->net, false, target->scratch, target->scratch, B, T,
+                                         episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                                         filled, gamma, nullptr, next_max, td_target, nullptr, stream, nullptr,
+                                         marl::kTdValue, next_action);
+            if (err == hipSuccess && ev) err = hipEventRecord(ev[2], stream);
+            return err;
         }
-        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
-        return MARL_OK;
+        if (keep_workspace) {
+            float *h_all;
+            void *x_all;
+            marl::qnet_grad_activation_slots(online->net, B, T, keep_workspace, &h_all, &x_all);
+            time_next_kernel();
+            return marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions,
+                                             reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream,
+                                             marl::kTdKeep, nullptr, h_all, x_all);
+        }
+        if (fused) {
+            time_next_kernel();
+            return marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
+                                             filled, gamma, q_taken, next_max, td_target, q_all, stream);
+        }
+        err = marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, episode_index,
+                                     pool_episodes, obs, avail,
+                                     actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
+                                     stream, ev ? ev[1] : nullptr);
+        if (err == hipSuccess && ev) err = hipEventRecord(ev[2], stream);
+        return err;
+    };
+    const hipError_t err = run();
+    marl::g_kernel_timer = nullptr;
+    if (err != hipSuccess) {
+        if (ev) drop_events(online, 3);                    // the record must not keep events that were never recorded
+        return device_fail(err, "unroll launch");
     }
-    if (keep_workspace) {
-        if (!fused) return MARL_ERR_BAD_DIM;
-        float *h_all;
-        void *x_all;
-        marl::qnet_grad_activation_slots(online->net, B, T, keep_workspace, &h_all, &x_all);
-        if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
-        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions,
-                                           reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, stream,
-                                           marl::kTdKeep, nullptr, h_all, x_all));
-        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
-        return MARL_OK;
-    }
-    if (fused) {
-        if (ev) MARL_HIP(hipEventRecord(ev[1], stream));
-        MARL_HIP(marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
-                                           filled, gamma, q_taken, next_max, td_target, q_all, stream));
-        if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
-        return MARL_OK;
-    }
-    MARL_HIP(marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, episode_index,
-                                    pool_episodes, obs, avail,
-                                    actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
-                                    stream, ev ? ev[1] : nullptr));
-    if (ev) MARL_HIP(hipEventRecord(ev[2], stream));
     return MARL_OK;
 }
 }  // namespace
@@ -578,15 +616,22 @@ int marl_qnet_timing_read(marl_qnet *q, float *act_ms, int32_t *act_calls, float
     double act = 0.0, proj = 0.0, rec = 0.0;
     int n_act = 0, n_unroll = 0;
     size_t at = 0;
+    hipError_t err = hipSuccess;
     for (int count : q->timed_calls) {
         hipEvent_t *ev = &q->ev_pool[at];
         at += count;
-        MARL_HIP(hipEventSynchronize(ev[count - 1]));
         float a = 0.0f, b = 0.0f;
-        MARL_HIP(hipEventElapsedTime(&a, ev[0], ev[1]));
+        err = hipEventSynchronize(ev[count - 1]);
+        if (err == hipSuccess) err = hipEventElapsedTime(&a, ev[0], ev[1]);
+        if (err == hipSuccess && count == 3) err = hipEventElapsedTime(&b, ev[1], ev[2]);
+        if (err != hipSuccess) break;
         if (count == 2) { act += a; ++n_act; continue; }
-        MARL_HIP(hipEventElapsedTime(&b, ev[1], ev[2]));
         proj += a; rec += b; ++n_unroll;
+    }
+    if (err != hipSuccess) {                               // the record is cleared either way: a later read starts afresh
+        q->ev_used = 0;
+        q->timed_calls.clear();
+        return device_fail(err, "marl_qnet_timing_read");
     }
     *act_ms = n_act ? (float)(act / n_act) : 0.0f;
     *act_calls = n_act;

@@ -3,6 +3,7 @@
 // network whose matrices are stored as MFMA operand fragments.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -99,6 +100,24 @@ bool pack_network(const marl_qnet_desc &desc, const float *host_weights, PackedI
 // [ceil(M/16)][ceil(K/32)][planes][64 lanes][8] bf16, zero padded; plane 1 holds the bf16 remainder.
 // use_perm: k order in which a pair of accumulators is the next operand (see mfma16_tile.h).
 void pack_frags16(uint16_t *out, const float *W, int M, int K, int ld, bool use_perm, int planes);
+
+// Kernel timing for benchmarks.  While the calling thread has a timer set, the next single-kernel launch made
+// through launch_kernel records the kernel's own start and end in the timer's events (an extended launch), so
+// that the interval is the kernel's duration and nothing of what precedes it on the stream.
+struct KernelTimer { hipEvent_t start, stop; };
+extern thread_local const KernelTimer *g_kernel_timer;
+
+template <typename Kernel, typename... Args>
+void launch_kernel(Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream, Args... args)
+{
+    if (g_kernel_timer) {
+        const KernelTimer t = *g_kernel_timer;
+        g_kernel_timer = nullptr;
+        hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds_bytes, stream, t.start, t.stop, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, stream, args...);
+    }
+}
 
 // Shared by the C-ABI source files: records the text marl_last_device_error() returns and
 // yields MARL_ERR_DEVICE.

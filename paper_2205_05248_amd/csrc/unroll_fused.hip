@@ -291,7 +291,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
         auto kernel = unroll_fused_kernel<H, P, ABLK, QA, MD>;                                                      \
         hipError_t err = allow_large_lds<unroll_fused_kernel<H, P, ABLK, QA, MD>>(kLdsLimit);                       \
         if (err != hipSuccess) return err;                                                                          \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, online, target, two, B, T, episode_index, pool_episodes, \
+        launch_kernel(kernel, grid, block, lds, stream, online, target, two, B, T, episode_index, pool_episodes,      \
                            obs, avail, actions,                                                                      \
                            reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all, next_action,     \
                            h_save, x_save);                                                                         \
