@@ -49,12 +49,15 @@ def default_threads():
     return max(1, min(os.cpu_count() or 1, 16))
 
 
-def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None, relu_band=None):
+def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None, relu_band=None, inputs_as_bf16=False):
     """grad [param count] f64 of sum(g * q_taken) with respect to the packed weights.
 
     obs [B,T+1,N,D], actions [B,T,N], filled [B,T], g [B,T,N] = dL/dq_taken.
     relu_band = delta: returns (grad, amb), amb the ambiguity budget of the first layer's entries for
     pre-activations within delta of zero.
+    inputs_as_bf16: diagnostic mode for a network held in bf16, whose first layer takes every observation
+    entry rounded to bf16 (nearest, ties to even): the gradient of that network, so that the first layer's
+    yes/no decisions are taken on the values an implementation in that precision sees.
     """
     N, D, A, H = (int(v) for v in dims)
     weights = _c(weights, np.float32)
@@ -63,6 +66,9 @@ def qnet_grad(dims, weights, obs, actions, filled, g, nthreads=None, relu_band=N
     obs = _c(obs, np.float32)
     B, T = obs.shape[0], obs.shape[1] - 1
     assert obs.shape == (B, T + 1, N, D)
+    if inputs_as_bf16:
+        from oracle import marl_oracle
+        obs = marl_oracle.round_bf16(obs).reshape(obs.shape)
     actions = _c(actions, np.int32); assert actions.shape == (B, T, N)
     assert actions.min(initial=0) >= 0 and actions.max(initial=0) < A
     filled = _c(filled, np.uint8); assert filled.shape == (B, T)

@@ -79,15 +79,21 @@ def td(dims, w_online, w_target, state, q_taken, next_max, reward, terminated, f
     return out
 
 
-def grad(dims, w, state, q, e, switch_band=None):
+def grad(dims, w, state, q, e, switch_band=None, inputs_as_bf16=False):
     """Backward pass: returns (grad_q [B,T,N], grad_w [param count]) for upstream e [B,T] = dL/dQ_total;
-    with switch_band = delta also the ambiguity budget [param count] of the sign / step switches."""
+    with switch_band = delta also the ambiguity budget [param count] of the sign / step switches.
+    inputs_as_bf16: diagnostic mode for a mixer held in bf16, whose generating layers take every state entry
+    rounded to bf16 (nearest, ties to even): the gradient of that mixer, so that the switches are set on the
+    values an implementation in that precision sees."""
     N, M, S = (int(v) for v in dims)
     w = _c(w, np.float32)
     assert w.size == param_count(N, M, S)
     state = _c(state, np.float32)
     B, T = state.shape[0], state.shape[1] - 1
     assert state.shape == (B, T + 1, S)
+    if inputs_as_bf16:
+        from oracle import marl_oracle
+        state = marl_oracle.round_bf16(state).reshape(state.shape)
     q = _c(q, np.float64); assert q.shape == (B, T, N)
     e = _c(e, np.float64); assert e.shape == (B, T)
     grad_q = np.zeros((B, T, N))
