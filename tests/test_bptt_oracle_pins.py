@@ -63,6 +63,19 @@ def autograd_grad(dims, w, u, g, relu_band=None):
     return wt.grad.numpy(), amb
 
 
+def test_bf16_input_mode_is_the_gradient_on_library_cast_observations():
+    """The diagnostic mode rounds the observation entries, and nothing else, the way a library's bfloat16 cast
+    does: its result is the library's gradient at the cast observations, not the one at the raw ones."""
+    cfg, dims, w, u, g = case(1, B=2, T=5)
+    cast = dict(u, obs=torch.from_numpy(u["obs"]).to(torch.bfloat16).to(torch.float32).numpy())
+    assert (cast["obs"] != u["obs"]).any()
+    got = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g, inputs_as_bf16=True)
+    want = autograd_grad(dims, w, cast, g)
+    np.testing.assert_allclose(got, want, rtol=0, atol=1e-10 * max(1.0, np.abs(want).max()))
+    raw = bpo.qnet_grad(dims, w, u["obs"], u["actions"], u["filled"], g)
+    assert np.abs(raw - got).max() > 1e-6 * np.abs(raw).max()
+
+
 @pytest.mark.parametrize("ci", [0, 1])
 def test_gradient_matches_library_autodiff(ci):
     cfg, dims, w, u, g = case(ci)

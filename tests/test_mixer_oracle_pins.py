@@ -189,6 +189,26 @@ def test_gradient_against_library_autodiff(ci):
         assert np.abs(want_w[a:b]).max() > 0, name
 
 
+def test_bf16_input_mode_is_the_gradient_on_library_cast_states():
+    """The diagnostic mode rounds the state entries, and nothing else, the way a library's bfloat16 cast does:
+    its result is the library's gradient at the cast states, and differs from the gradient at the raw ones."""
+    import torch
+    cfg = wl.config(1)
+    dims = wl.mixer_dims(cfg)
+    w = wl.make_mixer_weights(cfg)
+    m = wl.make_mixer_inputs(cfg, B=3, T=7)
+    e = np.random.default_rng(9).normal(size=(3, 7))
+    q = m["q_taken"].astype(np.float64)
+    cast = torch.from_numpy(m["state"]).to(torch.bfloat16).to(torch.float32).numpy()
+    assert (cast != m["state"]).any()
+    got_q, got_w = mxo.grad(dims, w, m["state"], q, e, inputs_as_bf16=True)
+    want_q, want_w = _library_grads(dims, w, cast, q, e)
+    np.testing.assert_allclose(got_q, want_q, rtol=0, atol=1e-11 * max(1.0, np.abs(want_q).max()))
+    np.testing.assert_allclose(got_w, want_w, rtol=0, atol=1e-11 * max(1.0, np.abs(want_w).max()))
+    raw_q, raw_w = mxo.grad(dims, w, m["state"], q, e)
+    assert np.abs(raw_w - got_w).max() > 1e-6 * np.abs(raw_w).max()
+
+
 def test_gradient_against_finite_differences_and_closed_forms():
     cfg = wl.config(0)
     N, M, S = dims = wl.mixer_dims(cfg)
