@@ -192,6 +192,36 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
                    void *hip_stream);
 
 /*
+ * marl_unroll_td for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs and checks as marl_unroll_td.  It always runs the tile32
+ * kernels (whatever marl_qnet_set_kernels chose), whose scratch - the input half
+ * of the GRU gates of every slot, for both networks - lies in a static device
+ * array of MARL_STATIC_SCRATCH_BYTES that is part of the library's image on each
+ * GPU and stays there until the process ends.  The call itself allocates
+ * nothing and frees nothing, on the device or through any library: it launches
+ * the two kernels and returns.  It records no timing (marl_qnet_set_timing does
+ * not apply to it).
+ *   MARL_ERR_BAD_DIM (and a message naming both sizes in marl_last_device_error,
+ *   which this call clears on entry) when the batch needs more than the array
+ *   holds: per network
+ *   ceil(B N / 32) (T+1) 3 (hidden/32) x 2048 bytes (bf16 weights) or 4096 (fp32),
+ *   rounded up to 256; twice that when target != online.
+ * Every call on a GPU, from any handle, uses that GPU's one array: calls that may
+ * overlap in time (different streams, different threads) race and must be
+ * ordered by the caller.  Nothing in the array has to start at zero: the first
+ * kernel writes every block the second one reads, so the contents left by an
+ * earlier, larger call do not matter.
+ */
+#define MARL_STATIC_SCRATCH_BYTES (64u << 20)
+int marl_unroll_td_static(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T,
+                          const float *obs, const uint8_t *avail, const int32_t *actions,
+                          const float *reward, const uint8_t *terminated, const uint8_t *filled,
+                          float gamma,
+                          float *q_taken, float *next_max, float *td_target, float *q_all,
+                          void *hip_stream);
+
+/*
  * The same unroll with its inputs read in place from a larger pool of episodes (the learner's
  * experience replay pool, from which Alg. 3 samples B episodes at random): no packed copy of
  * the batch is made.

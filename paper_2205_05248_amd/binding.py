@@ -21,7 +21,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
            "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_grad_kept", "marl_unroll_td_keep", "marl_qnet_sgd_step", "marl_qnet_rmsprop_step", "marl_qnet_check_refresh_map",
-           "marl_unroll_td", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
+           "marl_unroll_td", "marl_unroll_td_static", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
@@ -75,6 +75,8 @@ def load():
         lib.marl_act_step_indexed.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, f32, u64, vp, vp, vp, vp]
         lib.marl_unroll_td.restype = ctypes.c_int
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        lib.marl_unroll_td_static.restype = ctypes.c_int
+        lib.marl_unroll_td_static.argtypes = lib.marl_unroll_td.argtypes
         lib.marl_unroll_td_indexed.restype = ctypes.c_int
         lib.marl_unroll_td_indexed.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
         lib.marl_unroll_td_double.restype = ctypes.c_int
@@ -132,12 +134,14 @@ def load():
     return _lib
 
 
-def check(status):
+def check(status, detail=False):
+    """detail: the call clears the thread's message on entry, so whatever is there afterwards is its own."""
     if status != 0:
         lib = load()
         text = lib.marl_strerror(status).decode()
-        if status == -6:
-            text += " (" + lib.marl_last_device_error().decode() + ")"
+        message = lib.marl_last_device_error().decode()
+        if status == -6 or (detail and message):
+            text += " (" + message + ")"
         raise MarlError(status, text)
 
 
@@ -211,18 +215,23 @@ def marl_act_step_indexed(handle, dims, env_index, obs, avail, h_in, reset, step
         _dev(q_out, "f32", (E, N, A), "q_out", optional=True), _stream()))
 
 
+STATIC_SCRATCH_BYTES = 64 << 20          # MARL_STATIC_SCRATCH_BYTES
+
+
 def marl_unroll_td(online, target, dims, obs, avail, actions, reward, terminated, filled, gamma,
-                   q_taken, next_max, td_target, q_all=None):
+                   q_taken, next_max, td_target, q_all=None, static=False):
+    """static: marl_unroll_td_static, the variant that allocates nothing (same arguments)."""
     N, D, A, H = dims
     B, T = obs.shape[0], obs.shape[1] - 1
-    check(load().marl_unroll_td(
+    entry = load().marl_unroll_td_static if static else load().marl_unroll_td
+    check(entry(
         ctypes.c_void_p(online), ctypes.c_void_p(target), B, T,
         _dev(obs, "f32", (B, T + 1, N, D), "obs"), _dev(avail, "u8", (B, T + 1, N, A), "avail"),
         _dev(actions, "i32", (B, T, N), "actions"), _dev(reward, "f32", (B, T), "reward"),
         _dev(terminated, "u8", (B, T), "terminated"), _dev(filled, "u8", (B, T), "filled"), float(gamma),
         _dev(q_taken, "f32", (B, T, N), "q_taken"), _dev(next_max, "f32", (B, T, N), "next_max"),
         _dev(td_target, "f32", (B, T, N), "td_target"), _dev(q_all, "f32", (B, T + 1, N, A), "q_all", optional=True),
-        _stream()))
+        _stream()), detail=static)
 
 
 def marl_qnet_reserve_unroll(handle, B, T):
@@ -373,10 +382,10 @@ class QNet:
                               h_out, action, q_out)
 
     def unroll_td(self, target, obs, avail, actions, reward, terminated, filled, gamma,
-                  q_taken, next_max, td_target, q_all=None):
+                  q_taken, next_max, td_target, q_all=None, static=False):
         tgt = self if target is None else target
         marl_unroll_td(self.handle, tgt.handle, self.dims, obs, avail, actions, reward, terminated, filled,
-                       gamma, q_taken, next_max, td_target, q_all)
+                       gamma, q_taken, next_max, td_target, q_all, static=static)
 
     def set_weights(self, weights):
         marl_qnet_set_weights(self.handle, weights)

@@ -7,9 +7,15 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "qnet_internal.h"
+
+// Input-projection buffer of marl_unroll_td_static: device memory that exists from the moment the library is loaded
+// on a device, so that the call allocates nothing.  The name stands for the array in host code only as a symbol to
+// look up; the address on each device comes from static_scratch_of() below.
+static __device__ __align__(256) unsigned char scratch[MARL_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -59,6 +65,30 @@ struct DeviceGuard {
         if (ok && prev >= 0) (void)hipSetDevice(prev);
     }
 };
+
+// The device address of `scratch` on the current device (each device holds its own copy of the array), looked up
+// once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_static_scratch_lock;
+void *g_static_scratch[kMaxDevices] = {};
+
+int static_scratch_of(int device, void **out)
+{
+    if (device < 0 || device >= kMaxDevices) {
+        std::snprintf(g_last_error, sizeof(g_last_error), "device %d beyond the %d devices the static scratch serves", device, kMaxDevices);
+        return MARL_ERR_DEVICE;
+    }
+    std::lock_guard<std::mutex> hold(g_static_scratch_lock);
+    if (!g_static_scratch[device]) {
+        void *ptr = nullptr;
+        const hipError_t err = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return device_fail(err, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return device_fail(hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        g_static_scratch[device] = ptr;
+    }
+    *out = g_static_scratch[device];
+    return MARL_OK;
+}
 
 bool unit_interval(float v) { return std::isfinite(v) && v >= 0.0f && v <= 1.0f; }
 
@@ -164,6 +194,11 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
     }
     q->timing = false;
     q->ev_used = 0;
+    q->static_scratch = nullptr;
+    {
+        const int rc = static_scratch_of(desc->device, &q->static_scratch);      // the handle's device is current here
+        if (rc != MARL_OK) { delete q; return rc; }
+    }
     err = hipMalloc(&q->dev_weights, img.bytes);
     if (err != hipSuccess) { delete q; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipMalloc"); }
     err = hipMemcpy(q->dev_weights, img.host, img.bytes, hipMemcpyHostToDevice);
@@ -346,8 +381,9 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
                 int32_t pool_episodes, const float *obs, const uint8_t *avail, const int32_t *actions,
                 const float *reward, const uint8_t *terminated, const uint8_t *filled, float gamma, float *q_taken,
                 float *next_max, float *td_target, float *q_all, void *hip_stream, bool double_q = false,
-                int32_t *next_action = nullptr, void *keep_workspace = nullptr)
+                int32_t *next_action = nullptr, void *keep_workspace = nullptr, bool no_alloc = false)
 {
+    if (no_alloc) g_last_error[0] = '\0';                // whatever this call leaves there is its own
     if (!online || !target) return MARL_ERR_NULL;
     const marl_qnet_desc &a = online->desc, &b = target->desc;
     if (a.n_agents != b.n_agents || a.obs_dim != b.obs_dim || a.n_actions != b.n_actions || a.hidden != b.hidden ||
@@ -369,18 +405,33 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
     DeviceGuard guard(a.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     const bool two = online != target && !double_q;      // the double-estimator target runs the networks one after the other
-    const bool fused = takes_fused_path(online, true);
+    // no_alloc: the tiled kernels, with both networks' projections in the device's static array
+    const bool fused = !no_alloc && takes_fused_path(online, true);
     int rc = MARL_OK;
-    if (!fused) {
+    void *scratch_on = nullptr, *scratch_tg = nullptr;
+    if (no_alloc) {
+        const size_t need = (marl::unroll_scratch_bytes(online->net, B, T) + 255) & ~(size_t)255;
+        const size_t total = online != target ? 2 * need : need;
+        if (total > (size_t)MARL_STATIC_SCRATCH_BYTES) {
+            std::snprintf(g_last_error, sizeof(g_last_error),
+                          "marl_unroll_td_static: B = %d, T = %d needs %zu bytes of scratch, the static buffer holds %zu", B, T,
+                          total, (size_t)MARL_STATIC_SCRATCH_BYTES);
+            return MARL_ERR_BAD_DIM;
+        }
+        scratch_on = online->static_scratch;
+        scratch_tg = online != target ? static_cast<char *>(online->static_scratch) + need : scratch_on;
+    } else if (!fused) {
         const size_t need = marl::unroll_scratch_bytes(online->net, B, T);
         rc = ensure_scratch(online, need);
         if (rc == MARL_OK && online != target) rc = ensure_scratch(target, need);
         if (rc != MARL_OK) return rc;
+        scratch_on = online->scratch;
+        scratch_tg = target->scratch;
     }
     if (keep_workspace && !fused) return MARL_ERR_BAD_DIM;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     hipEvent_t *ev = nullptr;
-    if (online->timing) {
+    if (online->timing && !no_alloc) {                    // (creating events allocates)
         online->ev_pool.reserve(3 * MARL_TIMING_MAX_CALLS);
         ev = take_events(online, 3, &rc);
         if (rc != MARL_OK) return rc;
@@ -410,12 +461,12 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
                                                  avail, actions, reward, terminated, filled, gamma, nullptr, next_max,
                                                  td_target, nullptr, stream, marl::kTdValue, next_action);
             }
-            err = marl::launch_unroll_td(online->net, online->net, false, online->scratch, online->scratch, B, T,
+            err = marl::launch_unroll_td(online->net, online->net, false, scratch_on, scratch_on, B, T,
                                          episode_index, pool_episodes, obs, avail, actions, reward, terminated,
                                          filled, gamma, q_taken, nullptr, nullptr, q_all, stream,
                                          ev ? ev[1] : nullptr, marl::kTdSelect, next_action);
             if (err != hipSuccess) return err;
-            err = marl::launch_unroll_td(target->net, target->net, false, target->scratch, target->scratch, B, T,
+            err = marl::launch_unroll_td(target->net, target->net, false, scratch_tg, scratch_tg, B, T,
                                          episode_index, pool_episodes, obs, avail, actions, reward, terminated,
                                          filled, gamma, nullptr, next_max, td_target, nullptr, stream, nullptr,
                                          marl::kTdValue, next_action);
@@ -436,7 +487,7 @@ int unroll_call(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, cons
             return marl::launch_unroll_fused(online->net, target->net, two, B, T, episode_index, pool_episodes, obs, avail, actions, reward, terminated,
                                              filled, gamma, q_taken, next_max, td_target, q_all, stream);
         }
-        err = marl::launch_unroll_td(online->net, target->net, two, online->scratch, target->scratch, B, T, episode_index,
+        err = marl::launch_unroll_td(online->net, target->net, two, scratch_on, scratch_tg, B, T, episode_index,
                                      pool_episodes, obs, avail,
                                      actions, reward, terminated, filled, gamma, q_taken, next_max, td_target, q_all,
                                      stream, ev ? ev[1] : nullptr);
@@ -462,6 +513,15 @@ int marl_unroll_td(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, c
 {
     return unroll_call(online, target, B, T, nullptr, B, obs, avail, actions, reward, terminated, filled, gamma,
                        q_taken, next_max, td_target, q_all, hip_stream);
+}
+
+int marl_unroll_td_static(marl_qnet *online, marl_qnet *target, int32_t B, int32_t T, const float *obs,
+                          const uint8_t *avail, const int32_t *actions, const float *reward, const uint8_t *terminated,
+                          const uint8_t *filled, float gamma, float *q_taken, float *next_max, float *td_target,
+                          float *q_all, void *hip_stream)
+{
+    return unroll_call(online, target, B, T, nullptr, B, obs, avail, actions, reward, terminated, filled, gamma,
+                       q_taken, next_max, td_target, q_all, hip_stream, false, nullptr, nullptr, true);
 }
 
 int marl_unroll_td_indexed(marl_qnet *online, marl_qnet *target, int32_t pool_episodes, const int32_t *episode_index,

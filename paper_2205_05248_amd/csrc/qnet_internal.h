@@ -80,6 +80,7 @@ struct marl_qnet {
     hipEvent_t staging_done;  // recorded after the last upload from `staging`
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
+    void *static_scratch;     // this device's address of the library's static buffer (marl_unroll_td_static)
     int n_cu;                          // compute units of the device
     int kernels;                       // MARL_KERNELS_AUTO / MARL_KERNELS_TILE32
     bool timing;                       // record events around the kernels of each call

@@ -64,7 +64,7 @@ def compare_act(cfg, inp, got, ref, tol):
     return int(tie.sum())
 
 
-def gpu_unroll(online, target, cfg, u, want_q_all=True):
+def gpu_unroll(online, target, cfg, u, want_q_all=True, static=False):
     import torch
     N, D, A, H = wl.dims(cfg)
     d = to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
@@ -72,7 +72,7 @@ def gpu_unroll(online, target, cfg, u, want_q_all=True):
     outs = {k: torch.full((B, T, N), float("nan"), device="cuda") for k in ("q_taken", "next_max", "td_target")}
     q_all = torch.full((B, T + 1, N, A), float("nan"), device="cuda") if want_q_all else None
     online.unroll_td(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
-                     u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all)
+                     u["gamma"], outs["q_taken"], outs["next_max"], outs["td_target"], q_all, static=static)
     torch.cuda.synchronize()
     res = {k: v.cpu().numpy() for k, v in outs.items()}
     res["q_all"] = None if q_all is None else q_all.cpu().numpy()
