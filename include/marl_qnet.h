@@ -106,7 +106,7 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
  */
 int marl_qnet_set_weights(marl_qnet *q, const float *host_weights, size_t n_weights, void *hip_stream);
 
-/* Copy of the description the handle was created with. */
+/* Writes to *out (host) a copy of the description the handle was created with.  MARL_ERR_NULL for a null argument. */
 int marl_qnet_get_desc(const marl_qnet *q, marl_qnet_desc *out);
 
 /*

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import optim_oracle as opo
 from paper_2205_05248_amd import binding, workloads as wl
 import parity_util as pu
 
@@ -41,7 +42,7 @@ def test_updated_network_equals_one_created_from_the_updated_weights(ci, dtype):
     master = torch.from_numpy(w.copy()).cuda()
     net.sgd_step(master, torch.from_numpy(g).cuda(), lr)
     torch.cuda.synchronize()
-    want = w - np.float32(lr) * g                                   # fp32: product rounded, then the difference
+    want = opo.sgd_step(w, g, lr)                                   # fp32: product rounded, then the difference
     np.testing.assert_array_equal(master.cpu().numpy(), want)
     fresh = binding.QNet(dims, want, dtype)
     inp = wl.make_act_inputs(cfg, E=7)
@@ -68,7 +69,7 @@ def test_updated_network_equals_one_created_from_the_updated_weights(ci, dtype):
     # a second update on the same handle (the map is reused), and argument checks
     net.sgd_step(master, torch.from_numpy(g).cuda(), -lr)
     torch.cuda.synchronize()
-    np.testing.assert_array_equal(master.cpu().numpy(), want - np.float32(-lr) * g)
+    np.testing.assert_array_equal(master.cpu().numpy(), opo.sgd_step(want, g, -lr))
     import ctypes
     lib, vp = binding.load(), ctypes.c_void_p
     assert lib.marl_qnet_sgd_step(vp(net.handle), None, vp(master.data_ptr()), 0.1, None) == -1
@@ -85,7 +86,7 @@ def test_update_is_ordered_on_the_stream():
     N, D, A, H = dims
     w = wl.make_weights(cfg, 0)
     g = np.random.default_rng(2).normal(size=w.shape).astype(np.float32)
-    net, old, new = binding.QNet(dims, w), binding.QNet(dims, w), binding.QNet(dims, w - np.float32(0.5) * g)
+    net, old, new = binding.QNet(dims, w), binding.QNet(dims, w), binding.QNet(dims, opo.sgd_step(w, g, 0.5))
     inp = wl.make_act_inputs(cfg)
     ref_old, ref_new = pu.gpu_act(old, cfg, inp), pu.gpu_act(new, cfg, inp)
     d = pu.to_dev(inp, ["obs", "avail", "h_in", "reset", "step_t"])
@@ -197,7 +198,7 @@ def test_updated_mixer_equals_one_created_from_the_updated_weights(ci, dtype):
     master = torch.from_numpy(mw.copy()).cuda()
     mixer.sgd_step(master, torch.from_numpy(g).cuda(), lr)
     torch.cuda.synchronize()
-    want = mw - np.float32(lr) * g
+    want = opo.sgd_step(mw, g, lr)
     np.testing.assert_array_equal(master.cpu().numpy(), want)
     fresh = binding.Mixer(dims, want, dtype)
     B, T = 5, 9
@@ -306,8 +307,7 @@ def test_rmsprop_update_matches_a_host_reference_bit_for_bit():
         for step in range(3):
             g = rng.normal(size=w.shape).astype(np.float32) * np.float32(10.0 ** (step - 1))
             h.rmsprop_step(master, torch.from_numpy(g).cuda(), sq, float(lr), float(alpha), float(eps))
-            ref_v = (alpha * ref_v) + ((np.float32(1.0) - alpha) * (g * g))
-            ref_w = ref_w - lr * (g / (np.sqrt(ref_v) + eps))
+            ref_w, ref_v = opo.rmsprop_step(ref_w, g, ref_v, lr, alpha, eps)
         torch.cuda.synchronize()
         np.testing.assert_array_equal(sq.cpu().numpy(), ref_v)
         np.testing.assert_array_equal(master.cpu().numpy(), ref_w)
