@@ -196,47 +196,159 @@ class Bench:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
+    def act_outputs(self, seed):
+        """The decision step on input set 0 (the one the oracle leg regenerates), copied to the host."""
+        torch = self.torch
+        a0 = self.act_in[0]
+        self.online.act_step(a0["obs"], a0["avail"], a0["h_in"], a0["reset"], a0["step_t"], self.act_meta["epsilon"], seed,
+                             self.h_out[0], self.action, self.q[0])
+        torch.cuda.synchronize()
+        return {"seed": seed, "h_out": self.h_out[0].cpu().numpy(), "action": self.action.cpu().numpy(),
+                "q": self.q[0].cpu().numpy()}
+
+    def unroll_outputs(self):
+        """The unroll the timed region runs, with every slot's Q values as well, copied to the host."""
+        torch = self.torch
+        u = self.u
+        B, T = self.cfg["B"], self.cfg["T"]
+        N, D, A, H = self.dims
+        q_all = torch.empty(B, T + 1, N, A, device="cuda")
+        self.online.unroll_td(self.target, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"],
+                              u["filled"], self.u_host["gamma"], *self.u_out, q_all)
+        torch.cuda.synchronize()
+        out = {k: v.cpu().numpy() for k, v in zip(("q_taken", "next_max", "td_target"), self.u_out)}
+        out["q_all"] = q_all.cpu().numpy()
+        return out
+
     def close(self):
         self.online.close()
         if self.target is not None:
             self.target.close()
 
 
-def cpu_baseline(ci, budget_rows=4096):
-    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload."""
+def _median_time(fn, reps):
+    times = []
+    for _ in range(reps):
+        t0 = time.perf_counter()
+        fn()
+        times.append(time.perf_counter() - t0)
+    return float(np.median(times))
+
+
+def cpu_baseline(ci, gpu_act=None, gpu_unroll=None):
+    """The oracle as it stands, timed on this host's cores on a bounded sample of the workload: medians over
+    repetitions, with all cores and with one thread.  Its outputs for the benchmarked inputs are also what the GPU
+    results (gpu_act: the decision step on input set 0, gpu_unroll: the unroll's outputs) are compared with."""
     from oracle import marl_oracle as orc
     from paper_2205_05248_amd import workloads as wl
     cfg = wl.config(ci)
     dims = wl.dims(cfg)
-    N = cfg["N"]
-    w_on, w_tg = wl.make_weights(cfg, 0), wl.make_weights(cfg, 1)
-    inp = wl.make_act_inputs(cfg)
+    N, E, B, T = cfg["N"], cfg["E"], cfg["B"], cfg["T"]
+    tol = 2e-2 if cfg["dtype"] == "bf16" else 1e-4
+    rounded = lambda w: w if cfg["dtype"] != "bf16" else _bf16_matrices(orc, wl, dims, w)
+    w_on, w_tg = rounded(wl.make_weights(cfg, 0)), rounded(wl.make_weights(cfg, 1))
+    inp = wl.make_act_inputs(cfg, stream=0)
     threads = orc.default_threads()
-    orc.act_step(dims, w_on, inp["obs"][:8], inp["avail"][:8], inp["h_in"][:8], inp["reset"][:8], inp["step_t"][:8],
-                 0.0, 1)                                           # build / page in
-    t0 = time.perf_counter()
-    reps = 3
-    for _ in range(reps):
-        orc.act_step(dims, w_on, inp["obs"], inp["avail"], inp["h_in"], inp["reset"], inp["step_t"],
-                     inp["epsilon"], inp["seed"], nthreads=threads)
-    t_act = (time.perf_counter() - t0) / reps
+    act = lambda n_env, nthreads, seed: orc.act_step(
+        dims, w_on, inp["obs"][:n_env], inp["avail"][:n_env], inp["h_in"][:n_env], inp["reset"][:n_env],
+        inp["step_t"][:n_env], inp["epsilon"], seed, nthreads=nthreads)
+    act(min(E, 8), threads, 1)                                     # build / page in
+    act_reps = 5
+    t_act = _median_time(lambda: act(E, threads, inp["seed"]), act_reps)
+    e_one = max(1, E // 16)
+    t_act_one = _median_time(lambda: act(e_one, 1, inp["seed"]), act_reps) * E / e_one
     u = wl.make_unroll_inputs(cfg)
-    rows_total = cfg["B"] * N
-    rows = np.arange(min(rows_total, budget_rows), dtype=np.int32)
-    t0 = time.perf_counter()
-    orc.unroll_td(dims, w_on, w_tg, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"], u["filled"],
-                  u["gamma"], want_q_all=False, rows=rows, nthreads=threads)
-    t_unroll = (time.perf_counter() - t0) * rows_total / rows.size       # scaled to the whole batch
-    steps_act = cfg["E"] * N
-    steps_unroll = cfg["B"] * cfg["T"] * N
-    return {
+    rows_total = B * N
+    unroll = lambda rows, nthreads, q_all: orc.unroll_td(
+        dims, w_on, w_tg, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"], u["filled"], u["gamma"],
+        want_q_all=q_all, rows=rows, nthreads=nthreads)
+    unroll_reps = 3
+    t_unroll = _median_time(lambda: unroll(None, threads, False), unroll_reps)
+    rows_one = np.arange(min(rows_total, 64), dtype=np.int32)
+    t_unroll_one = _median_time(lambda: unroll(rows_one, 1, False), unroll_reps) * rows_total / rows_one.size
+    steps_act, steps_unroll = E * N, B * T * N
+    out = {
         "value": (steps_act + steps_unroll) / (t_act + t_unroll), "unit": "agent-steps/s", "cores": threads,
         "kind": "oracle",
-        "sample": f"act-step: all {steps_act} rows x{reps}; unroll+TD (two networks): first {rows.size} of "
-                  f"{rows_total} (episode, agent) rows over all T+1 slots, time scaled to the full batch",
+        "sample": f"act-step: all {steps_act} rows, median of {act_reps}; unroll+TD (two networks): all {rows_total} "
+                  f"(episode, agent) rows over all T+1 slots, median of {unroll_reps}; single-thread figures: "
+                  f"{e_one} environments / {rows_one.size} rows, scaled to the whole batch",
         "act_agent_steps_per_s": steps_act / t_act,
-        "unroll_episode_steps_per_s": cfg["B"] * cfg["T"] / t_unroll,
+        "unroll_episode_steps_per_s": B * T / t_unroll,
+        "single_thread": {"value": (steps_act + steps_unroll) / (t_act_one + t_unroll_one),
+                          "act_agent_steps_per_s": steps_act / t_act_one,
+                          "unroll_episode_steps_per_s": B * T / t_unroll_one},
+        "seconds": {"act_all_cores": t_act, "unroll_all_cores": t_unroll, "act_one_thread_scaled": t_act_one,
+                    "unroll_one_thread_scaled": t_unroll_one},
     }
+    parity = {"tolerance": tol}
+    if gpu_act is not None:
+        ref = act(E, threads, gpu_act["seed"])
+        # a near-tie: a greedy row whose two best available Q values lie within the tolerance of each other
+        near = (ref["explored"] == 0) & (_top2_margin(ref["q"], inp["avail"]) <= tol)
+        differ = gpu_act["action"] != ref["action"]
+        parity["act_step"] = {
+            "rows": steps_act, "max_abs_err_q": float(np.abs(gpu_act["q"] - ref["q"]).max()),
+            "max_abs_err_h": float(np.abs(gpu_act["h_out"] - ref["h_out"]).max()),
+            "near_ties": int(near.sum()),
+            "actions_differing": int(differ.sum()),
+            "actions_differing_outside_near_ties": int((differ & ~near).sum())}
+    if gpu_unroll is not None:
+        ref = unroll(None, threads, True)
+        parity["unroll_td"] = {"rows": rows_total}
+        for k in ("q_taken", "next_max", "td_target", "q_all"):
+            if gpu_unroll.get(k) is not None:
+                parity["unroll_td"]["max_abs_err_" + k] = float(np.abs(gpu_unroll[k] - ref[k]).max())
+    return out, parity
+
+
+def _bf16_matrices(orc, wl, dims, w):
+    """A bf16 network's weights as the network holds them: the matrices rounded to bf16, the biases as given."""
+    w = np.array(w, np.float32)
+    for name, (a, b, shp) in wl.weight_slices(*dims).items():
+        if len(shp) == 2:
+            w[a:b] = orc.round_bf16(w[a:b])
+    return w
+
+
+def _top2_margin(q, avail):
+    """Gap between the best and second-best available Q value of each row (inf with fewer than two)."""
+    masked = np.where(avail != 0, q.astype(np.float64), -np.inf)
+    top = np.sort(masked, axis=-1)[..., -2:]
+    gap = top[..., 1] - top[..., 0]
+    return np.where(np.isfinite(gap), gap, np.inf)
+
+
+def measured_peaks():
+    """What this GPU reaches on plain kernels, next to the nominal peaks: the library's streaming probe over 1 GiB
+    (read only; copy, bytes read plus bytes written) and its probe of dependency-free bf16 matrix instructions."""
+    import torch
+    from paper_2205_05248_amd import binding
+
+    def timed(fn, n):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / n
+    src = torch.ones((1 << 30) // 4, device="cuda")
+    dst = torch.empty_like(src)
+    sink = torch.zeros(1, device="cuda")
+    t_read = timed(lambda: binding.marl_probe_stream(src, None, sink), 20)
+    t_copy = timed(lambda: binding.marl_probe_stream(src, dst, sink), 20)
+    assert torch.equal(dst[-4096:], src[-4096:]) and float(sink) == 0.0
+    del src, dst
+    torch.cuda.empty_cache()
+    flops = binding.marl_probe_mfma(20000, sink)
+    t_mfma = timed(lambda: binding.marl_probe_mfma(20000, sink), 5)
+    return {"stream_read_GBs": (1 << 30) / t_read / 1e9, "stream_copy_GBs": 2 * (1 << 30) / t_copy / 1e9,
+            "mfma_bf16_TFLOPs": flops / t_mfma / 1e12,
+            "nominal": {"hbm_GBs": PEAK["hbm_GBs"], "bf16_TFLOPs": PEAK["bf16_TFs"]}}
 
 
 def mixer_section(ci, with_cpu, launches=20):
@@ -496,13 +608,36 @@ def learner_section(ci, launches=10):
             "config": {"B": B, "T": T, "n_agents": N}}
 
 
+def other_config(ci, kernels, steps=50, warmup=5):
+    """(workload name, compact figures) of one of the paper-scenario configurations: the same step, timed the same way."""
+    b = Bench(ci, kernels=kernels)
+    cfg = b.cfg
+    N, D, A, H = b.dims
+    E, B, T = cfg["E"], cfg["B"], cfg["T"]
+    wall, k = b.run(steps, warmup)
+    act_b2b_ms = b.back_to_back_act()
+    b.close()
+    steps_act, steps_unroll, slots = E * N, B * T * N, B * (T + 1) * N
+    act_s, unroll_s = k["act_ms"] * 1e-3, (k["input_proj_ms"] if not b.fused else 0.0) * 1e-3 + k["recurrent_ms"] * 1e-3
+    return cfg["name"], {
+        "ms_per_step": wall * 1e3 / steps, "agent_steps_per_s": (steps_act + steps_unroll) / (wall / steps),
+        "act_step": {"kernel_ms": k["act_ms"], "kernel_ms_back_to_back": act_b2b_ms,
+                     "agent_steps_per_s": steps_act / act_s,
+                     "hbm_frac": steps_act * act_bytes_per_agent_step(*b.dims) / act_s / 1e9 / PEAK["hbm_GBs"]},
+        "unroll_td": {"kernels_ms": unroll_s * 1e3, "episode_steps_per_s": B * T / unroll_s,
+                      "mfma_frac": 2 * slots * flops_per_agent_step(*b.dims) / unroll_s / 1e12 / PEAK["bf16_TFs"]},
+        "dtype": cfg["dtype"], "steps": steps}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=4, help="workload index 0..4")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle's timing and the comparison with it")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline step: no mixer / gradient / learner sections, no other configurations")
     ap.add_argument("--single-net", action="store_true", help="target == online in the unroll")
     ap.add_argument("--kernels", choices=sorted(KERNELS), default="auto",
                     help="kernel family (auto: the library's choice)")
@@ -525,6 +660,12 @@ def main():
     act_cached_ms = b.cache_resident_act()
     single_net_ms = b.single_net_unroll()
     double_ms = b.single_net_unroll(double=True)
+    gpu_act = gpu_unroll = None
+    if not args.no_cpu_baseline and not args.single_net:
+        gpu_act, gpu_unroll = b.act_outputs(b.act_meta["seed"]), b.unroll_outputs()
+    names = {binding.KERNELS_TILE32: "tile32", binding.KERNELS_FUSED16: "fused16", binding.KERNELS_STREAM16: "stream16"}
+    kernel_names = {"act_step": names[b.online.kernels_in_use(binding.ENTRY_ACT_STEP)],
+                    "unroll_td": names[b.online.kernels_in_use(binding.ENTRY_UNROLL_TD)]}
     b.close()
 
     ms_per_step = wall * 1e3 / args.steps
@@ -583,8 +724,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg["name"], "E": E, "N": N, "obs_dim": D, "n_actions": A, "hidden": H,
                    "B": B, "T": T, "target_network": "distinct" if nets == 2 else "same",
-                   "kernels": {"act_step": "fused16" if b.act_fused else "tile32",
-                               "unroll_td": "fused16" if b.fused else "tile32"},
+                   "kernels": kernel_names,
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
         "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
                      "kernel_ms_back_to_back": act_b2b_ms, "kernel_ms_cache_resident_inputs": act_cached_ms, "hbm_GBs": kernels["act_step"]["GBs"],
@@ -599,11 +739,14 @@ def main():
                                   for n, v in kernels.items() if n != "act_step"}},
         "roofline": roofline,
     }
-    out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
-    out["qnet_grad"] = grad_section(args.config, not args.no_cpu_baseline)
-    out["learner_iteration"] = learner_section(args.config)
+    out["measured_peaks"] = measured_peaks()
+    if not args.no_extras:
+        out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
+        out["qnet_grad"] = grad_section(args.config, not args.no_cpu_baseline)
+        out["learner_iteration"] = learner_section(args.config)
+        out["all_configs"] = {wl_name: v for wl_name, v in (other_config(ci, args.kernels) for ci in range(4) if ci != args.config)}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(args.config)
+        out["cpu_baseline"], out["parity_vs_oracle"] = cpu_baseline(args.config, gpu_act, gpu_unroll)
     print(json.dumps(out))
 
 

@@ -412,6 +412,21 @@ int marl_qnet_kernels_in_use(const marl_qnet *q, int32_t entry);
 int marl_qnet_set_timing(marl_qnet *q, int32_t enable);
 int marl_qnet_timing_read(marl_qnet *q, float *act_ms, int32_t *act_calls, float unroll_ms[2], int32_t *unroll_calls);
 
+/*
+ * Measurement aids for benchmarks: what the current device reaches on two plain kernels, to set next to
+ * its nominal peaks.  Not part of the network's path; each call enqueues one kernel and returns.
+ *   marl_probe_stream  streams `bytes` (a multiple of 16) from src (dev, 16-byte aligned) with 16-byte loads from
+ *                      32 workgroups per compute unit; dst (dev, 16-byte aligned, `bytes` long) non-NULL: copies
+ *                      them there (bytes read + bytes written = 2 * bytes); NULL: only reads and sums them.
+ *                      sink: dev [1] f32, left alone (it keeps the loads alive).
+ *   marl_probe_mfma    two workgroups of four waves per compute unit, each wave issuing iters * 8 independent
+ *                      16x16x32 bf16 matrix instructions; *flops (host) receives the floating-point operations the
+ *                      launch performs (2 * 16 * 16 * 32 per instruction and wave).
+ * MARL_ERR_NULL / MARL_ERR_BAD_DIM (bytes, iters out of range) / MARL_ERR_BAD_ARG (alignment).
+ */
+int marl_probe_stream(const void *src, void *dst, size_t bytes, float *sink, void *hip_stream);
+int marl_probe_mfma(int32_t iters, float *sink, double *flops, void *hip_stream);
+
 /* Free the handle, its weights and scratch.  Synchronises the device.  NULL is allowed. */
 int marl_destroy(marl_qnet *q);
 

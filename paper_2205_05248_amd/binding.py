@@ -21,7 +21,7 @@ DTYPES = {"fp32": MARL_DTYPE_F32, "bf16": MARL_DTYPE_BF16}
 
 EXPORTS = ["marl_param_count", "marl_qnet_create", "marl_qnet_get_desc", "marl_act_step", "marl_act_step_indexed", "marl_unroll_td_indexed",
            "marl_unroll_td_double", "marl_qnet_grad_workspace_bytes", "marl_qnet_grad", "marl_qnet_grad_kept", "marl_unroll_td_keep", "marl_qnet_sgd_step", "marl_qnet_rmsprop_step", "marl_qnet_check_refresh_map",
-           "marl_unroll_td", "marl_unroll_td_static", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
+           "marl_unroll_td", "marl_unroll_td_static", "marl_probe_stream", "marl_probe_mfma", "marl_qnet_reserve_unroll", "marl_destroy", "marl_strerror",
            "marl_last_device_error", "marl_qnet_set_timing", "marl_qnet_timing_read",
            "marl_qnet_set_kernels", "marl_qnet_kernels_in_use", "marl_qnet_set_weights"]
 # include/marl_mixer.h
@@ -75,6 +75,10 @@ def load():
         lib.marl_act_step_indexed.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp, vp, f32, u64, vp, vp, vp, vp]
         lib.marl_unroll_td.restype = ctypes.c_int
         lib.marl_unroll_td.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp, vp, vp, f32, vp, vp, vp, vp, vp]
+        lib.marl_probe_stream.restype = ctypes.c_int
+        lib.marl_probe_stream.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
+        lib.marl_probe_mfma.restype = ctypes.c_int
+        lib.marl_probe_mfma.argtypes = [i32, vp, ctypes.POINTER(ctypes.c_double), vp]
         lib.marl_unroll_td_static.restype = ctypes.c_int
         lib.marl_unroll_td_static.argtypes = lib.marl_unroll_td.argtypes
         lib.marl_unroll_td_indexed.restype = ctypes.c_int
@@ -213,6 +217,21 @@ def marl_act_step_indexed(handle, dims, env_index, obs, avail, h_in, reset, step
         _dev(step_t, "i32", (E,), "step_t"), float(epsilon), int(seed) & 0xFFFFFFFFFFFFFFFF,
         _dev(h_out, "f32", (E, N, H), "h_out"), _dev(action, "i32", (E, N), "action"),
         _dev(q_out, "f32", (E, N, A), "q_out", optional=True), _stream()))
+
+
+def marl_probe_stream(src, dst, sink):
+    """One streaming pass over src (a read, or a copy into dst when dst is given)."""
+    nbytes = src.numel() * src.element_size()
+    check(load().marl_probe_stream(ctypes.c_void_p(src.data_ptr()), ctypes.c_void_p(dst.data_ptr()) if dst is not None else None,
+                                   nbytes, ctypes.c_void_p(sink.data_ptr()), _stream()))
+    return nbytes * (2 if dst is not None else 1)
+
+
+def marl_probe_mfma(iters, sink):
+    """One launch of dependency-free bf16 matrix instructions; returns its floating-point operations."""
+    flops = ctypes.c_double(0.0)
+    check(load().marl_probe_mfma(int(iters), ctypes.c_void_p(sink.data_ptr()), ctypes.byref(flops), _stream()))
+    return flops.value
 
 
 STATIC_SCRATCH_BYTES = 64 << 20          # MARL_STATIC_SCRATCH_BYTES

@@ -694,3 +694,24 @@ def test_double_estimator_target(ci, B, T, path):
                                    vp(d["obs"].data_ptr()), vp(d["obs"].data_ptr()), vp(d["obs"].data_ptr()), None, None, None)
     assert rc == -1
     net.close(); target.close()
+
+
+# ------------------------------------------------------------------ measurement aids
+def test_probes_copy_what_they_read_and_check_their_arguments():
+    lib, vp = binding.load(), ctypes.c_void_p
+    src = torch.arange(4 * 100003, dtype=torch.float32, device="cuda")      # a vector count no grid stride divides
+    dst = torch.zeros_like(src)
+    sink = torch.zeros(1, device="cuda")
+    assert binding.marl_probe_stream(src, dst, sink) == 2 * src.numel() * 4
+    assert binding.marl_probe_stream(src, None, sink) == src.numel() * 4
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src) and float(sink) == 0.0
+    flops = binding.marl_probe_mfma(10, sink)
+    torch.cuda.synchronize()
+    assert flops == torch.cuda.get_device_properties(0).multi_processor_count * 2 * 4 * 10 * 8 * 2 * 16 * 16 * 32
+    assert float(sink) == 0.0
+    p = vp(src.data_ptr())
+    assert lib.marl_probe_stream(p, None, 24, vp(sink.data_ptr()), None) == -2          # not a multiple of 16
+    assert lib.marl_probe_stream(vp(src.data_ptr() + 4), None, 32, vp(sink.data_ptr()), None) == -5
+    assert lib.marl_probe_stream(None, None, 32, vp(sink.data_ptr()), None) == -1
+    assert lib.marl_probe_mfma(0, vp(sink.data_ptr()), ctypes.byref(ctypes.c_double()), None) == -2
