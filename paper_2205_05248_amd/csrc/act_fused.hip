@@ -216,8 +216,16 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
                 asm volatile("" : "+v"(dead));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
+                    {
+                        f32x4 *accs[AB];
+                        const WFrag<P> *wf[AB];
 #pragma unroll
-                    for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb[ks]);
+                        for (int ab = 0; ab < AB; ++ab) {
+                            accs[ab] = &qv[ab];
+                            wf[ab] = &w2[ab][ks];
+                        }
+                        mma16_across<P, AB>(accs, wf, hb[ks]);
+                    }
                 if ((A & 3) == 0) {                          // a lane's four actions of a block: 16 aligned bytes
 #pragma unroll
                     for (int ab = 0; ab < AB; ++ab) {

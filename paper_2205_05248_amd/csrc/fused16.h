@@ -34,10 +34,10 @@ template <int H, int P> struct Fused16 {
     static constexpr int KS = H / 32;                  // k-steps over the hidden layer
     static constexpr int NC = 4;                       // compute waves
     static constexpr int NBC = FBK / NC;               // feature blocks per compute wave (2 or 1)
-    static constexpr int NF = H == 128 ? 2 : 1;        // fc1 waves
+    static constexpr int NF = 2;                       // fc1 waves
     static constexpr int kEpilogue = NC, kLoader = NC + 1, kFc1 = NC + 2, kWaves = NC + 2 + NF;
     static constexpr int NBF = FBK / NF;               // fc1 feature blocks per fc1 wave
-    static constexpr int kKs1Max = 40 / (NBF * P);     // observation k-steps whose W1 fragments fit 160 registers
+    static constexpr int kKs1Max = 10 / P;             // observation k-steps: W1 fragments of an fc1 wave within 160 registers (H = 128), 80 (H = 64)
     static constexpr int kFrag = P * 1024;             // bytes of one fragment (all planes)
     // LDS layout (byte offsets)
     static constexpr int oWih = 0;                                  // [3 FBK][KS][P][64] bf16x8
@@ -60,6 +60,6 @@ template <int H, int P> struct Fused16 {
     static constexpr size_t lds_bytes_act(int ks1) { return greedy_offset(ks1) + 8 * 16; }
 };
 
-constexpr int fused_threads(int H) { return 64 * (4 + 2 + (H == 128 ? 2 : 1)); }
+constexpr int fused_threads(int) { return 64 * (4 + 2 + 2); }
 
 }  // namespace marl

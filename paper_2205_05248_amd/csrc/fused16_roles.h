@@ -120,15 +120,15 @@ template <int H, int P> struct GruWave {
         for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
             for (int j = 0; j < NBC; ++j) {
-                mma16<P>(acc_r[j], whh[0][j][ks], hb[ks]);
-                mma16<P>(acc_z[j], whh[1][j][ks], hb[ks]);
-                mma16<P>(acc_hn[j], whh[2][j][ks], hb[ks]);
+                f32x4 *const acc[3] = {&acc_r[j], &acc_z[j], &acc_hn[j]};
+                const WFrag<P> *const wf[3] = {&whh[0][j][ks], &whh[1][j][ks], &whh[2][j][ks]};
+                mma16_across<P, 3>(acc, wf, hb[ks]);
             }
 #pragma unroll
             for (int j = 0; j < NBC; ++j) {
-                mma16<P>(acc_r[j], wi[ks % 2][0][j], x[ks]);
-                mma16<P>(acc_z[j], wi[ks % 2][1][j], x[ks]);
-                mma16<P>(acc_in[j], wi[ks % 2][2][j], x[ks]);
+                f32x4 *const acc[3] = {&acc_r[j], &acc_z[j], &acc_in[j]};
+                const WFrag<P> *const wf[3] = {&wi[ks % 2][0][j], &wi[ks % 2][1][j], &wi[ks % 2][2][j]};
+                mma16_across<P, 3>(acc, wf, x[ks]);
             }
             __builtin_amdgcn_sched_barrier(0);
             if (ks + 2 < KS) request(ks + 2);
@@ -218,8 +218,16 @@ template <int H, int P> struct Fc1Wave {
         for (int ks = 0; ks < KM; ++ks)
             if (ks < ks1) {
                 bq[(ks + 2) % 3] = obs_frag(min(ks + 2, ks1 - 1));
+                {
+                    f32x4 *accs[NBF];
+                    const WFrag<P> *wf[NBF];
 #pragma unroll
-                for (int j = 0; j < NBF; ++j) mma16<P>(acc[j], w1[j][ks], bq[ks % 3]);
+                    for (int j = 0; j < NBF; ++j) {
+                        accs[j] = &acc[j];
+                        wf[j] = &w1[j][ks];
+                    }
+                    mma16_across<P, NBF>(accs, wf, bq[ks % 3]);
+                }
             }
 #pragma unroll
         for (int j = 0; j < NBF; ++j)

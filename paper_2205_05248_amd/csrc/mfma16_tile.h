@@ -22,6 +22,23 @@ __device__ __forceinline__ void mma16(f32x4 &acc, const WFrag<P> &w, const Frag<
     acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w.hi, b.hi, acc, 0, 0, 0);
 }
 
+// The same for N accumulators that share the B operand.  With two planes the three products of one accumulator
+// depend on each other, and a matrix instruction issued right behind the one it depends on waits out the depth
+// of the pipeline; taking each kind of product across all accumulators first keeps dependent instructions N
+// apart.  Every accumulator still receives lo.hi, hi.lo, hi.hi in that order: the same bits as N calls of mma16.
+template <int P, int N>
+__device__ __forceinline__ void mma16_across(f32x4 *const (&acc)[N], const WFrag<P> *const (&w)[N], const Frag<P> &b)
+{
+    if constexpr (P == 2) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) *acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[i]->lo, b.hi, *acc[i], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) *acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[i]->hi, b.lo, *acc[i], 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < N; ++i) *acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[i]->hi, b.hi, *acc[i], 0, 0, 0);
+}
+
 // Feature blocks 2 j and 2 j + 1 of a result -> k-step j of the next operand.
 template <int P>
 __device__ __forceinline__ Frag<P> frag_of_pair(const f32x4 &even, const f32x4 &odd)

@@ -32,9 +32,15 @@
 // step s was last read in step s-1 and is first read in step s+1.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "fused16_roles.h"
 
 namespace marl {
+
+
+// LDS of a launch: the shared layout, then the staging area of the epilogue's inputs, [2][8][64] words.
+template <int H, int P> constexpr size_t unroll_lds_bytes(int ks1) { return Fused16<H, P>::lds_bytes(ks1) + 2 * 8 * 64 * 4; }
 
 template <int H, int P, int AB, bool QALL, int MODE>
 __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
@@ -73,6 +79,56 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     // episode of the input arrays: the batch position itself, or the listed episode of a larger pool
     const int bi = episode_index ? min(max(episode_index[b], 0), pool_episodes - 1) : b;
 
+    // ---- the epilogue's per-slot inputs: the taken action, the flags, the reward and the availability bytes
+    // kSelect / kValue: the two single-network launches of the double-estimator target
+    constexpr bool kSelect = MODE == kTdSelect, kValue = MODE == kTdValue, kSave = MODE == kTdSave;
+    // 32-bit element offsets (the host bounds every array to 2^30 elements)
+    const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // outputs [B, T, N]:       + t N
+    const uint32_t qa0 = ((uint32_t)(b * S) * N + n) * A;     // q_all [B, T+1, N, A]:    + t N A
+    const uint32_t act0 = (uint32_t)(bi * T) * N + n;         // actions of the episode:  + t N
+    const uint32_t av0 = ((uint32_t)(bi * S) * N + n) * A;    // avail of the episode:    + t N A
+    const uint32_t bt0 = (uint32_t)(bi * T);                  // per-episode flags:       + t
+    // They are global loads whose latency is longer than a step, and the epilogue's own instruction stream cannot
+    // hide it: its stores and loads are conditional, so any wait it needs covers everything in flight.  The loader
+    // wave fetches them instead, beside the observations and a step earlier, the same number of loads every step
+    // (positions clamped into the arrays, rows past the end read row 0), and hands them over in LDS:
+    // epi[slot & 1][word][lane], words: 0 action, 1 flags (filled(t) | terminated(t-1) << 8 | filled(t-1) << 16),
+    // 2 reward(t-1), 3.. the raw availability words of slot t.
+    struct SlotIn { int u; uint32_t flags; float reward; uint32_t avail_raw[AB]; };
+    constexpr int kEpiWords = 8;
+    static_assert(3 + AB <= kEpiWords, "the staging area holds eight words per lane");
+    uint32_t *const epi = reinterpret_cast<uint32_t *>(lds + Sh::lds_bytes(ks1));
+    auto fetch_slot = [&](int t, auto wide) {        // t in 0 .. T
+        SlotIn in{};
+        if constexpr (!kSave) {
+            const uint32_t tq = (uint32_t)min(t, T - 1), tp = (uint32_t)max(t - 1, 0);
+            if constexpr (kValue) in.u = next_action[btn0 + tp * N];
+            else in.u = actions[act0 + tq * N];
+            in.flags = (uint32_t)filled[bt0 + tq] | (uint32_t)terminated[bt0 + tp] << 8 | (uint32_t)filled[bt0 + tp] << 16;
+            in.reward = reward[bt0 + tp];
+            if constexpr (decltype(wide)::value) issue_avail_loads16<AB>(avail + (av0 + (uint32_t)t * N * A), A, q4, in.avail_raw);
+        }
+        return in;
+    };
+    auto stage_slot = [&](const SlotIn &in, int t) {
+        uint32_t *at = epi + (size_t)(t & 1) * kEpiWords * 64 + lane;
+        at[0] = (uint32_t)in.u;
+        at[64] = in.flags;
+        at[128] = __builtin_bit_cast(uint32_t, in.reward);
+#pragma unroll
+        for (int ab = 0; ab < AB; ++ab) at[(3 + ab) * 64] = in.avail_raw[ab];
+    };
+    auto staged_slot = [&](int t) {
+        const uint32_t *at = epi + (size_t)(t & 1) * kEpiWords * 64 + lane;
+        SlotIn in;
+        in.u = (int)at[0];
+        in.flags = at[64];
+        in.reward = __builtin_bit_cast(float, at[128]);
+#pragma unroll
+        for (int ab = 0; ab < AB; ++ab) in.avail_raw[ab] = at[(3 + ab) * 64];
+        return in;
+    };
+
     // W_ih -> LDS, all waves.  Its first readers start after kFusedLead barriers.
     {
         constexpr int kVecs = 3 * FBK * KS * P * 64;
@@ -102,6 +158,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
                 for (int j = 0; j < Sh::NBC; ++j) *reinterpret_cast<f32x4 *>(h_row + 16 * j) = hv[j];
         }
+        gru.settle_weights();
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it <= T) {
@@ -119,8 +176,6 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         }
     } else if (wave == Sh::kEpilogue) {
         // ---------------------------------------------------------------- epilogue wave
-        // kSelect / kValue: the two single-network launches of the double-estimator target
-        constexpr bool kSelect = MODE == kTdSelect, kValue = MODE == kTdValue, kSave = MODE == kTdSave;
         const bool emit_online = !is_target && !kValue && !kSave, emit_target = (is_target || !two_nets) && !kSave;
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
         WFrag<P> w2[AB][KS];
@@ -129,36 +184,17 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) w2[ab][ks] = load_wfrag<P>(net.w2_16 + ((size_t)(ab * KS + ks) * P) * 64 + lane);
         if (lane < 16 * AB) b2_lds[lane] = lane < A ? net.b2[lane] : 0.0f;
-        // 32-bit element offsets (the host bounds every array to 2^30 elements)
-        const uint32_t btn0 = (uint32_t)(b * T) * N + n;          // outputs [B, T, N]:       + t N
-        const uint32_t qa0 = ((uint32_t)(b * S) * N + n) * A;     // q_all [B, T+1, N, A]:    + t N A
-        const uint32_t act0 = (uint32_t)(bi * T) * N + n;         // actions of the episode:  + t N
-        const uint32_t av0 = ((uint32_t)(bi * S) * N + n) * A;    // avail of the episode:    + t N A
-        const uint32_t bt0 = (uint32_t)(bi * T);                  // per-episode flags:       + t
-        struct SlotIn { int u; uint32_t avail_raw[AB]; float reward; uint8_t on_filled, terminated, tg_filled; };
-        auto fetch_slot = [&](int t) {          // inputs of slot t, requested one step before they are used
-            SlotIn in{};
-            if (t > T) return in;
-            if (emit_online && t < T) {
-                in.u = valid ? actions[act0 + (uint32_t)t * N] : 0;
-                in.on_filled = valid ? filled[bt0 + t] : 0;
-            }
-            if (emit_target && t >= 1) {
-                if constexpr (kValue) in.u = valid ? next_action[btn0 + (uint32_t)(t - 1) * N] : -1;
-                else if (A >= 4) issue_avail_loads16<AB>(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, in.avail_raw);
-                in.reward = valid ? reward[bt0 + t - 1] : 0.0f;
-                in.terminated = valid ? terminated[bt0 + t - 1] : 0;
-                in.tg_filled = valid ? filled[bt0 + t - 1] : 0;
-            }
-            return in;
-        };
-        SlotIn nxt = fetch_slot(0);
+        // the weights have arrived before the loop starts: a wait for them inside it would also cover the loop's own loads
+#pragma unroll
+        for (int ab = 0; ab < AB; ++ab)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) settle(w2[ab][ks]);
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int it = 0; it <= T + 1; ++it) {
             if (it >= 1) {
                 const int t = it - 1, cur = it & 1;          // h_t was published during iteration t
-                const SlotIn in = nxt;
-                nxt = fetch_slot(t + 1);
+                const SlotIn in = staged_slot(t);
+                const bool on_filled = (in.flags & 0xFFu) != 0, terminated_prev = (in.flags >> 8 & 0xFFu) != 0, tg_filled = (in.flags >> 16 & 0xFFu) != 0;
                 f32x4 qv[AB];
 #pragma unroll
                 for (int ab = 0; ab < AB; ++ab) qv[ab] = load_feature4(b2_lds, ab, q4);
@@ -167,8 +203,16 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                     Frag<P> hb;
                     hb.hi = h_lds[cur][ks][0][lane];
                     if constexpr (P == 2) hb.lo = h_lds[cur][ks][1][lane];
+                    {
+                        f32x4 *accs[AB];
+                        const WFrag<P> *wf[AB];
 #pragma unroll
-                    for (int ab = 0; ab < AB; ++ab) mma16<P>(qv[ab], w2[ab][ks], hb);
+                        for (int ab = 0; ab < AB; ++ab) {
+                            accs[ab] = &qv[ab];
+                            wf[ab] = &w2[ab][ks];
+                        }
+                        mma16_across<P, AB>(accs, wf, hb);
+                    }
                 }
                 if (emit_online) {
                     if constexpr (QALL) {
@@ -177,7 +221,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                     if (t < T) {
                         const int u = min(max(in.u, 0), A - 1);
                         const float qu = pick_action_value16<AB>(qv, u, q4);
-                        if (valid && q4 == 0) q_taken[btn0 + (uint32_t)t * N] = in.on_filled ? qu : 0.0f;
+                        if (valid && q4 == 0) q_taken[btn0 + (uint32_t)t * N] = on_filled ? qu : 0.0f;
                     }
                 }
                 if (emit_target && t >= 1) {
@@ -185,7 +229,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                     float best_q;
                     if constexpr (kValue) {               // the value of the action the other network chose
                         const float picked = pick_action_value16<AB>(qv, min(max(in.u, 0), A - 1), q4);
-                        best_q = in.u >= 0 ? picked : 0.0f;
+                        best_q = in.u >= 0 ? picked : 0.0f;      // -1: the other network found no action available
                     } else {
                         const uint32_t slots =
                             A >= 4 ? avail_mask16<AB>(in.avail_raw, A, q4, valid)
@@ -199,10 +243,10 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                         }
                     }
                     if (!kSelect && valid && q4 == 0) {
-                        const float keep = in.terminated ? 0.0f : 1.0f;
+                        const float keep = terminated_prev ? 0.0f : 1.0f;
                         const float y = in.reward + gamma * keep * best_q;
-                        next_max[o] = in.tg_filled ? best_q : 0.0f;
-                        td_target[o] = in.tg_filled ? y : 0.0f;
+                        next_max[o] = tg_filled ? best_q : 0.0f;
+                        td_target[o] = tg_filled ? y : 0.0f;
                     }
                 }
             }
@@ -214,13 +258,29 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         const size_t slot_stride = (size_t)N * D;
         ObsStage<H, P> st;
         st.init(D, ks1, q4);
-        ObsRegs<H, P> regs;
-        for (int s = -LEAD; s <= T + 1; ++s) {
-            const int ws = s + 2, ls = s + 3;
-            if (ws >= 0 && ws <= T) st.write(regs, obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
-            if (ls >= 0 && ls <= T) st.load(regs, base + (size_t)ls * slot_stride);                      // issue the loads
+        // Two register sets in turn: a step first issues the loads of the slot it will write in the next step, into
+        // the set that step will read, then converts the set loaded a step ago.  The loads have a whole step to arrive.
+        ObsRegs<H, P> set_a, set_b;
+        SlotIn epi_a{}, epi_b{};                     // the epilogue's inputs of a slot, in turn like the observation sets
+        auto loader_step = [&](const ObsRegs<H, P> &ready, ObsRegs<H, P> &refill, const SlotIn &epi_ready, SlotIn &epi_refill,
+                               int s, auto wide) {
+            const int ws = s + 2, ls = ws + 1;
+            st.load(refill, base + (size_t)min(max(ls, 0), T) * slot_stride);       // every step the same number of loads (the ends load a slot again)
+            epi_refill = fetch_slot(min(max(s + 1, 0), T), wide);                   // slot s + 1: staged in the next step, read by the epilogue in step s + 2
+            if (ws >= 0 && ws <= T) st.write(ready, obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
+            if (s >= 0 && s <= T) stage_slot(epi_ready, s);
             lds_barrier();
-        }
+        };
+        auto loader_loop = [&](auto wide) {
+            int s = -LEAD;
+            for (; s + 1 <= T + 1; s += 2) {
+                loader_step(set_a, set_b, epi_a, epi_b, s, wide);
+                loader_step(set_b, set_a, epi_b, epi_a, s + 1, wide);
+            }
+            if (s <= T + 1) loader_step(set_a, set_b, epi_a, epi_b, s, wide);
+        };
+        if (A >= 4) loader_loop(std::true_type{});
+        else loader_loop(std::false_type{});
     } else {
         // ---------------------------------------------------------------- fc1 wave
         const int f = wave - Sh::kFc1;
@@ -228,6 +288,9 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         fc1.load(net, f, ks1, lane);
         f32x4 b1v[Sh::NBF];
         Fc1Wave<H, P>::load_bias(net, f, n, q4, b1v);
+        fc1.settle_weights(ks1);
+#pragma unroll
+        for (int j = 0; j < Sh::NBF; ++j) asm volatile("" ::"v"(b1v[j]));
         const float *touch_row = obs + ((size_t)bi * S * N + n) * D;
         ObsTouch<H, P, 2> tch;
         tch.init(D, q4);
@@ -283,7 +346,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
     using Sh = Fused16<H, P>;
     const int tiles = (B * online.N + 15) / 16;
     const dim3 grid(two_nets ? (unsigned)((tiles + 7) / 8) * 16u : (unsigned)tiles), block(fused_threads(H));
-    const size_t lds = Sh::lds_bytes((online.D + 31) / 32);
+    const size_t lds = unroll_lds_bytes<H, P>((online.D + 31) / 32);
     const int two = two_nets ? 1 : 0;
     const int ab = (online.A + 15) / 16;
 #define MARL_FUSED(ABLK, QA, MD)                                                                                    \
@@ -320,7 +383,7 @@ hipError_t fused_dispatch(const NetFrags &online, const NetFrags &target, bool t
 template <int H, int P> bool fits(const NetFrags &net)
 {
     const int ks1 = (net.D + 31) / 32;
-    return ks1 <= Fused16<H, P>::kKs1Max && Fused16<H, P>::lds_bytes(ks1) <= (size_t)kLdsLimit;
+    return ks1 <= Fused16<H, P>::kKs1Max && unroll_lds_bytes<H, P>(ks1) <= (size_t)kLdsLimit;
 }
 
 }  // namespace
