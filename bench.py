@@ -155,6 +155,28 @@ class Bench:
         torch.cuda.synchronize()
         return a.elapsed_time(b) / n
 
+    def back_to_back_act_indexed(self, n=200):
+        """The decision step through marl_act_step_indexed with every environment listed, in a random order."""
+        torch = self.torch
+        E = self.cfg["E"]
+        order = torch.from_numpy(np.random.default_rng(0).permutation(E).astype(np.int32)).cuda()
+        def call():
+            i = self.n_act % self.pool
+            self.n_act += 1
+            a = self.act_in[i]
+            self.online.act_step_indexed(order, a["obs"], a["avail"], a["h_in"], a["reset"], a["step_t"], self.act_meta["epsilon"],
+                                         self.act_meta["seed"] + self.n_act, self.h_out[i], self.action, self.q[i])
+        for _ in range(5):
+            call()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(n):
+            call()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+
     def cache_resident_act(self, n=100):
         """The same launch on one buffer over and over: inputs stay in the memory-side cache."""
         torch = self.torch
@@ -657,6 +679,7 @@ def main():
     E, B, T = cfg["E"], cfg["B"], cfg["T"]
     wall, k = b.run(args.steps, args.warmup)
     act_b2b_ms = b.back_to_back_act()
+    act_indexed_ms = b.back_to_back_act_indexed()
     act_cached_ms = b.cache_resident_act()
     single_net_ms = b.single_net_unroll()
     double_ms = b.single_net_unroll(double=True)
@@ -727,7 +750,8 @@ def main():
                    "kernels": kernel_names,
                    "step": "1 act-step call (E*N rows, Q written) + 1 unroll+TD call (B*T transitions)"},
         "act_step": {"agent_steps_per_s": steps_act / (act_ms * 1e-3), "kernel_ms": act_ms,
-                     "kernel_ms_back_to_back": act_b2b_ms, "kernel_ms_cache_resident_inputs": act_cached_ms, "hbm_GBs": kernels["act_step"]["GBs"],
+                     "kernel_ms_back_to_back": act_b2b_ms, "kernel_ms_back_to_back_indexed_all_envs_shuffled": act_indexed_ms,
+                     "kernel_ms_cache_resident_inputs": act_cached_ms, "hbm_GBs": kernels["act_step"]["GBs"],
                      "hbm_frac": kernels["act_step"]["hbm_frac"], "mfma_frac": kernels["act_step"]["mfma_frac"],
                      "input_pool_bytes": b.pool * kernels["act_step"]["bytes"]},
         "unroll_td": {"episode_steps_per_s": B * T / (unroll_ms * 1e-3), "episodes_per_s": B / (unroll_ms * 1e-3),

@@ -147,8 +147,9 @@ int marl_act_step(marl_qnet *q, int32_t E,
  * environment's own index e, so a listed environment gets exactly the action marl_act_step over
  * all E environments would give it.  An index outside [0, E) is clamped into the range (the call
  * cannot check device data); duplicates make the duplicated rows' outputs unspecified.
- * n_listed = 0 is a no-op.  Runs on the tile32 kernels.  Errors as marl_act_step, plus
- * MARL_ERR_BAD_DIM for n_listed < 0 or n_listed > E.
+ * n_listed = 0 is a no-op.  Kernel family as marl_act_step chooses it (fused16 where the network
+ * fits and E N n_actions 4 < 2^31, else tile32; the streaming kernel serves the dense call only).
+ * Errors as marl_act_step, plus MARL_ERR_BAD_DIM for n_listed < 0 or n_listed > E.
  */
 int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int32_t n_listed,
                           const float *obs, const uint8_t *avail, const float *h_in,

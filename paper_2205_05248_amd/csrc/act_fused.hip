@@ -35,7 +35,10 @@ namespace marl {
 
 struct ActFusedArgs {
     NetFrags net;
-    int rows;                   // E * N
+    int rows;                   // rows to serve: (listed) environments x agents
+    const int32_t *env_index;   // indexed call: the environments to serve, in any order (entries clamped into 0 .. n_envs - 1)
+    int n_envs;                 // environments the arrays hold
+    uint32_t n_magic;           // ceil(2^32 / N): floor(p / N) = high word of p * n_magic for p < 2^26 (N >= 2)
     int tiles_per_group;        // consecutive tiles of 16 rows per workgroup
     const float *obs;
     const uint8_t *avail;
@@ -62,7 +65,9 @@ __device__ __forceinline__ uint64_t row_avail_bits16(uint32_t slots, int q)
 constexpr int kActLead = 2;          // steps before item 0 enters the GRU
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int H, int P, int AB>
+// IDX: the rows to serve are those of a list of environments; position p of the list's rows maps to row
+// env_index[p / N] N + p % N of the arrays, which every load and store is addressed by.
+template <int H, int P, int AB, bool IDX>
 __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const ActFusedArgs args)
 {
     using Sh = Fused16<H, P>;
@@ -94,8 +99,27 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
     const int last = count + 1;                                       // the last step
     // item k (0 <= k < count) is tile first + k; items past the run re-use its last tile (reads only),
     // rows past the end row 0
-    auto item_row = [&](int k) { return (first + min(max(k, 0), count - 1)) * 16 + c; };
-    auto read_row = [&](int k) { const int row = item_row(k); return row < rows ? row : 0; };
+    auto item_row = [&](int k) { return (first + min(max(k, 0), count - 1)) * 16 + c; };       // position among the rows to serve
+    // A position p is agent p % N of the p / N-th environment served; the division is a multiplication by a
+    // constant of the launch.  The indexed call then looks the environment up in the list: a global load, which a
+    // wave issues one step before it needs the result (EnvAhead) so that no address ever waits for it.
+    struct Served { int env, n; };
+    auto served_at = [&](int k) {                                                              // item k -> (p / N, p % N)
+        int pos = item_row(k);
+        pos = pos < rows ? pos : 0;
+        const int listed = N == 1 ? pos : (int)__umulhi((uint32_t)pos, args.n_magic);
+        return Served{listed, pos - listed * N};
+    };
+    auto env_of = [&](int k) {                                                                 // the environment of item k's row
+        const int listed = served_at(k).env;
+        if constexpr (IDX) return min(max(args.env_index[listed], 0), args.n_envs - 1);
+        else return listed;
+    };
+    auto row_in = [&](int env, int k) { return env * N + served_at(k).n; };                    // row of the arrays
+    struct EnvAhead {                      // env_of(item) for the item of the next call, asked for during this one
+        int next;
+        __device__ __forceinline__ int take(int upcoming) { const int now = next; next = upcoming; return now; }
+    };
     // Steps run s = -LEAD .. count + 1, one barrier at the end of each: LEAD + count + 2 barriers per wave.
     // Step s = s0 + u of the unrolled loops has the parity of u.
 
@@ -113,12 +137,14 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         gru.load(net, w, lane, q4);
         if (w == 0) GruWave<H, P>::stage_gate_biases(lds, net, lane);
         gru.settle_weights();
+        EnvAhead ahead{env_of(0)};
         for (int i = 0; i < LEAD; ++i) lds_barrier();
         for (int s = 0; s <= last; ++s) {
+            const int env = ahead.take(env_of(s + 1));
             if (s < count) {
                 const int cur = s & 1;
-                const int row = item_row(s);
-                const bool valid = row < rows;
+                const bool valid = item_row(s) < rows;
+                const int row = row_in(env, s);
                 f32x4 hv[NBC];           // this wave's own units of the old state in fp32, for the blend
 #pragma unroll
                 for (int j = 0; j < NBC; ++j) hv[j] = hf_lds[cur][NBC * w + j][lane];
@@ -144,19 +170,20 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         const bool has_reset = args.reset != nullptr;
         // without reset flags the byte is read from step_t instead and ignored
         const uint8_t *const flag_src = has_reset ? args.reset : reinterpret_cast<const uint8_t *>(args.step_t);
-        auto fetch_state = [&](int k) {
+        auto fetch_state = [&](int k, int env) {
             StateIn st;
-            const int rr = read_row(k);
+            const int rr = row_in(env, k);
             const float *r = args.h_in + (size_t)rr * H + 4 * q4;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
                 st.a[ks] = *reinterpret_cast<const f32x4 *>(r + 32 * ks);
                 st.b[ks] = *reinterpret_cast<const f32x4 *>(r + 32 * ks + 16);
             }
-            st.flag = flag_src[rr / N];
+            st.flag = flag_src[env];
             return st;
         };
-        StateIn state[2] = {fetch_state(0), fetch_state(1)};
+        StateIn state[2] = {fetch_state(0, env_of(0)), fetch_state(1, env_of(1))};
+        EnvAhead state_ahead{env_of(-LEAD + 3)}, out_ahead{env_of(-LEAD - 1)};
         stage_wih();
         float *const b2_lds = reinterpret_cast<float *>(lds + Sh::oB2);
         WFrag<P> w2[AB][KS];
@@ -170,9 +197,11 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) settle(w2[ab][ks]);
         // outputs of this workgroup's run of tiles, addressed by row within the run
+        // (indexed call: of the whole array, addressed by array row; the host has checked that it fits 32-bit offsets)
         const int run_rows = min(count * 16, rows - first * 16);
         const __amdgpu_buffer_rsrc_t q_buf = __builtin_amdgcn_make_buffer_rsrc(
-            args.q_out + (size_t)first * 16 * A, 0, args.q_out ? run_rows * A * 4 : 0, kRawBuffer);
+            args.q_out + (IDX ? (size_t)0 : (size_t)first * 16 * A), 0,
+            args.q_out ? (IDX ? args.n_envs * N : run_rows) * A * 4 : 0, kRawBuffer);
         constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
         auto step = [&](auto set, int s) {
             constexpr int p = 1 - decltype(set)::value;      // parity of items s - 1, s + 1, s + 3
@@ -207,12 +236,14 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
                     hf_lds[nb][2 * ks][lane] = a;
                     hf_lds[nb][2 * ks + 1][lane] = b;
                 }
-                state[p] = fetch_state(s + 3);
+                state[p] = fetch_state(s + 3, state_ahead.take(env_of(s + 4)));
             }
             __builtin_amdgcn_sched_barrier(0);
             {   // item s - 1: Q, mask, choice
-                const int lr = k * 16 + c;                   // row within the run
-                uint32_t dead = k >= 0 ? 0u : kDrop;         // in a vector register: the step must not fork on it
+                const int out_env = out_ahead.take(env_of(s));           // item k of this step; item s - 1 + 1 for the next
+                const int lr = IDX ? row_in(out_env, k) : k * 16 + c;    // row within the run (indexed call: of the array)
+                // (the run-relative addresses of the dense call fall outside the descriptor for items past the run)
+                uint32_t dead = k >= 0 && (!IDX || (k < count && item_row(k) < rows)) ? 0u : kDrop;      // in a vector register: the step must not fork on it
                 asm volatile("" : "+v"(dead));
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
@@ -265,32 +296,36 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         st.init(D, ks1, q4);
         ObsRegs<H, P> regs[2];
         struct ItemIn { uint32_t avail_raw[AB]; int step; };
-        auto obs_row8 = [&](int k) { return args.obs + (size_t)read_row(k) * D + 8 * q4; };
-        auto fetch_item = [&](int k) {
+        auto obs_row8 = [&](int k, int env) { return args.obs + (size_t)row_in(env, k) * D + 8 * q4; };
+        auto fetch_item = [&](int k, int env) {
             ItemIn in;
-            const int rr = read_row(k);
-            issue_avail_loads16<AB>(args.avail + (size_t)rr * A, A, q4, in.avail_raw);
-            in.step = args.step_t[rr / N];
+            issue_avail_loads16<AB>(args.avail + (size_t)row_in(env, k) * A, A, q4, in.avail_raw);
+            in.step = args.step_t[env];
             return in;
         };
-        st.load(regs[0], obs_row8(0));
-        st.load(regs[1], obs_row8(1));
-        ItemIn in[2] = {fetch_item(0), fetch_item(1)};
+        st.load(regs[0], obs_row8(0, env_of(0)));
+        st.load(regs[1], obs_row8(1, env_of(1)));
+        ItemIn in[2] = {fetch_item(0, env_of(0)), fetch_item(1, env_of(1))};
+        // three lookups a step, each asked for one step early: the items whose observations and availability are
+        // fetched next, and the item whose action is drawn next
+        auto pick_item = [&](int s) { return ((s - 2) & ~3) + q4; };
+        EnvAhead obs_ahead{env_of(-LEAD + 4)}, item_ahead{env_of(-LEAD + 2)}, pick_ahead{env_of(pick_item(-LEAD))};
         stage_wih();
         // actions of this workgroup's run of tiles, addressed by row within the run
         const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(
-            args.action + (size_t)first * 16, 0, min(count * 16, rows - first * 16) * 4, kRawBuffer);
+            args.action + (IDX ? (size_t)0 : (size_t)first * 16), 0,
+            (IDX ? args.n_envs * N : min(count * 16, rows - first * 16)) * 4, kRawBuffer);
         constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
         auto step = [&](auto set, int s) {
             constexpr int u = decltype(set)::value;          // parity of items s, s + 2, s + 4
             st.write(regs[u], obuf + (size_t)((s & 1) * ks1) * P * 64 + lane);
-            st.load(regs[u], obs_row8(s + 4));
+            st.load(regs[u], obs_row8(s + 4, obs_ahead.take(env_of(s + 5))));
             {   // availability of item s: slot masks for the epilogue's argmax, the row's bits for the draw
                 const uint32_t slots = avail_mask16<AB>(in[u].avail_raw, A, q4, true);
                 slots_lds[s & 1][lane] = slots;
                 const uint64_t bits = row_avail_bits16<AB>(slots, q4);
                 choice_lds[s & 7][c] = {(uint32_t)bits, (uint32_t)(bits >> 32), in[u].step};      // the four lanes of a row agree
-                in[u] = fetch_item(s + 2);
+                in[u] = fetch_item(s + 2, item_ahead.take(env_of(s + 3)));
             }
             // The draw is the same work for one lane or sixty-four, so it waits until four items
             // have their greedy action (or the run ends) and is then made for their 64 rows at
@@ -299,14 +334,16 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
             const int k = s - 2;
             int pick = 0;
             uint32_t pick_at = kDrop;
+            const int pick_env = pick_ahead.take(env_of(pick_item(s + 1)));
             if ((k & 3) == 3 || k == count - 1) {
                 const int kk = (k & ~3) + q4;
                 const RowChoice ch = choice_lds[kk & 7][c];
                 const int greedy = greedy_lds[kk & 7][c];
-                const int rr = read_row(kk);
+                const int rr = row_in(pick_env, kk);
                 pick = eps_greedy_pick(greedy, ((uint64_t)ch.bits_hi << 32) | ch.bits_lo, args.epsilon, args.seed,
-                                       (uint32_t)(rr / N), (uint32_t)(rr % N), (uint32_t)ch.step);
-                pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
+                                       (uint32_t)pick_env, (uint32_t)served_at(kk).n, (uint32_t)ch.step);
+                if constexpr (IDX) pick_at = kk >= 0 && kk <= k && item_row(kk) < rows ? (uint32_t)rr * 4u : kDrop;
+                else pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
             }
             __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
             lds_barrier();
@@ -328,7 +365,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
             const int item = s + 1;
             if (item >= 0 && item < count) {
                 f32x4 b1v[Sh::NBF];
-                Fc1Wave<H, P>::load_bias(net, f, read_row(item) % N, q4, b1v);
+                Fc1Wave<H, P>::load_bias(net, f, served_at(item).n, q4, b1v);
                 fc1.step(obuf + (size_t)((item & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[item & 1]);
             }
             lds_barrier();
@@ -339,7 +376,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
 // ------------------------------------------------------------------------------------------ host side
 namespace {
 
-template <int H, int P>
+template <int H, int P, bool IDX>
 hipError_t act_dispatch(const ActFusedArgs &a, hipStream_t stream)
 {
     using Sh = Fused16<H, P>;
@@ -348,8 +385,8 @@ hipError_t act_dispatch(const ActFusedArgs &a, hipStream_t stream)
     const size_t lds = Sh::lds_bytes_act((a.net.D + 31) / 32);
 #define MARL_ACTF(ABLK)                                                                                             \
     do {                                                                                                            \
-        auto kernel = act_fused_kernel<H, P, ABLK>;                                                                 \
-        hipError_t err = allow_large_lds<act_fused_kernel<H, P, ABLK>>(kLdsLimit);                                  \
+        auto kernel = act_fused_kernel<H, P, ABLK, IDX>;                                                            \
+        hipError_t err = allow_large_lds<act_fused_kernel<H, P, ABLK, IDX>>(kLdsLimit);                             \
         if (err != hipSuccess) return err;                                                                          \
         launch_kernel(kernel, grid, block, lds, stream, a);                                                         \
     } while (0)
@@ -381,22 +418,40 @@ bool act_fused_fits(const NetFrags &net)
     return false;
 }
 
-hipError_t launch_act_fused(const NetFrags &net, int E, int n_groups_hint, const float *obs, const uint8_t *avail,
+hipError_t launch_act_fused(const NetFrags &net, int E, const int32_t *env_index, int n_listed, int n_groups_hint,
+                            const float *obs, const uint8_t *avail,
                             const float *h_in, const uint8_t *reset, const int32_t *step_t, float epsilon,
                             uint64_t seed, float *h_out, int32_t *action, float *q_out, hipStream_t stream)
 {
     ActFusedArgs a{};
     a.net = net;
-    a.rows = E * net.N;
+    a.rows = (env_index ? n_listed : E) * net.N;
+    a.env_index = env_index;
+    a.n_envs = E;
+    a.n_magic = net.N == 1 ? 0u : (uint32_t)(((1ull << 32) + net.N - 1) / net.N);
     const int tiles = (a.rows + 15) / 16;
     const int groups = n_groups_hint > 0 ? n_groups_hint : 256;       // one workgroup per compute unit
     a.tiles_per_group = (tiles + groups - 1) / groups;
     a.obs = obs; a.avail = avail; a.h_in = h_in; a.reset = reset; a.step_t = step_t;
     a.epsilon = epsilon; a.seed = seed; a.h_out = h_out; a.action = action; a.q_out = q_out;
-    if (net.H == 64 && net.planes == 2) return act_dispatch<64, 2>(a, stream);
-    if (net.H == 64 && net.planes == 1) return act_dispatch<64, 1>(a, stream);
-    if (net.H == 128 && net.planes == 1) return act_dispatch<128, 1>(a, stream);
+#define MARL_GO(HH, PP) return env_index ? act_dispatch<HH, PP, true>(a, stream) : act_dispatch<HH, PP, false>(a, stream)
+    if (net.H == 64 && net.planes == 2) MARL_GO(64, 2);
+    if (net.H == 64 && net.planes == 1) MARL_GO(64, 1);
+    if (net.H == 128 && net.planes == 1) MARL_GO(128, 1);
+#undef MARL_GO
     return hipErrorInvalidValue;
+}
+
+// The indexed call addresses Q values and actions of the whole arrays with 32-bit byte offsets.
+bool act_fused_indexed_fits(const NetFrags &net, int E)
+{
+    return act_fused_rows_fit(net, E) && (long)E * net.N * net.A * 4 < (1l << 31);
+}
+
+// Rows are split into (environment, agent) by a multiplication that is exact below 2^26 rows.
+bool act_fused_rows_fit(const NetFrags &net, int E)
+{
+    return act_fused_fits(net) && (long)E * net.N < (1l << 26);
 }
 
 }  // namespace marl

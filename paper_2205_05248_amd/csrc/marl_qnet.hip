@@ -296,7 +296,8 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const bool all_aligned = aligned16(obs) && aligned16(avail) && aligned16(step_t) && (!q_out || aligned16(q_out)) && aligned16(action);
-    const bool stream_path = takes_stream_path(q, E) && all_aligned, fused_path = takes_fused_path(q, false);
+    const bool stream_path = takes_stream_path(q, E) && all_aligned;
+    const bool fused_path = takes_fused_path(q, false) && marl::act_fused_rows_fit(q->net, E);
     hipEvent_t *ev = nullptr;
     if (q->timing) {
         q->ev_pool.reserve(3 * MARL_TIMING_MAX_CALLS);      // keeps handed-out pointers stable
@@ -314,7 +315,7 @@ int marl_act_step(marl_qnet *q, int32_t E, const float *obs, const uint8_t *avai
     if (stream_path) {
         err = marl::launch_act_stream(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
     } else if (fused_path) {
-        err = marl::launch_act_fused(q->net, E, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
+        err = marl::launch_act_fused(q->net, E, nullptr, 0, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
     } else {
         if (ev) err = hipEventRecord(ev[0], stream);
         if (err == hipSuccess) err = marl::launch_act_step(q->net, E, nullptr, 0, obs, avail, h_in, reset, step_t, epsilon, seed, h_out, action, q_out, stream);
@@ -340,8 +341,14 @@ int marl_act_step_indexed(marl_qnet *q, int32_t E, const int32_t *env_index, int
     if (!aligned16(h_in) || !aligned16(h_out)) return MARL_ERR_BAD_ARG;
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
-    MARL_HIP(marl::launch_act_step(q->net, E, env_index, n_listed, obs, avail, h_in, reset, step_t, epsilon, seed, h_out,
-                                   action, q_out, static_cast<hipStream_t>(hip_stream)));
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    // the fused kernel where the network and the arrays fit it (the tiled one on request or otherwise)
+    if (takes_fused_path(q, false) && marl::act_fused_indexed_fits(q->net, E) && (!q_out || aligned16(q_out)))
+        MARL_HIP(marl::launch_act_fused(q->net, E, env_index, n_listed, q->n_cu, obs, avail, h_in, reset, step_t, epsilon, seed,
+                                        h_out, action, q_out, stream));
+    else
+        MARL_HIP(marl::launch_act_step(q->net, E, env_index, n_listed, obs, avail, h_in, reset, step_t, epsilon, seed, h_out,
+                                       action, q_out, stream));
     return MARL_OK;
 }
 

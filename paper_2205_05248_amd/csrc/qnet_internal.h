@@ -158,9 +158,14 @@ hipError_t launch_unroll_td(const NetFrags &online, const NetFrags &target, bool
 // Fused decision step (act_fused.hip).  `fits` as below; groups_hint = workgroups to spread the
 // tiles over (0: one per compute unit).
 bool act_fused_fits(const NetFrags &net);
-hipError_t launch_act_fused(const NetFrags &net, int E, int groups_hint, const float *obs, const uint8_t *avail,
+hipError_t launch_act_fused(const NetFrags &net, int E, const int32_t *env_index, int n_listed, int groups_hint,
+                            const float *obs, const uint8_t *avail,
                             const float *h_in, const uint8_t *reset, const int32_t *step_t, float epsilon,
                             uint64_t seed, float *h_out, int32_t *action, float *q_out, hipStream_t stream);
+// env_index non-null (the indexed call): also the output arrays must fit 32-bit byte offsets.
+bool act_fused_indexed_fits(const NetFrags &net, int E);
+// and the batch: E N below 2^26 rows (dense and indexed calls)
+bool act_fused_rows_fit(const NetFrags &net, int E);
 
 // Streaming decision step (act_stream.hip): `fits` for this network and batch; n_cu = compute units of the device.
 // Every array must be 16-byte aligned.

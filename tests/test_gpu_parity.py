@@ -510,8 +510,9 @@ def test_calls_replay_from_a_hip_graph(path):
 
 
 # ------------------------------------------------------------------ asynchronous sub-batch
-@pytest.mark.parametrize("ci,n_listed", [(0, 3), (1, 100), (3, 1), (3, 777), (4, 50)])
-def test_indexed_decision_step_serves_only_the_listed_environments(ci, n_listed):
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("ci,n_listed", [(0, 3), (1, 100), (3, 1), (3, 777), (4, 50), (4, 1024), (2, 512)])
+def test_indexed_decision_step_serves_only_the_listed_environments(ci, n_listed, path):
     """A random subset of the environments, in random order: their rows get exactly what the oracle
     gives them in a step over all environments (same random-number key, which uses the environment's
     own index), every other row of every output keeps its previous contents, and the hidden-state
@@ -520,7 +521,7 @@ def test_indexed_decision_step_serves_only_the_listed_environments(ci, n_listed)
     cfg["E"] = min(cfg["E"], 1024)
     tol = pu.TOL[cfg["dtype"]]
     N, D, A, H = wl.dims(cfg)
-    net, w = make_net(cfg)
+    net, w = make_net(cfg, kernels=path)
     inp = wl.make_act_inputs(cfg)
     E = cfg["E"]
     listed = np.random.default_rng(ci).permutation(E)[:n_listed].astype(np.int32)
