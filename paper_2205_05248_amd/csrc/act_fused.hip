@@ -295,57 +295,15 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         ObsStage<H, P> st;
         st.init(D, ks1, q4);
         ObsRegs<H, P> regs[2];
-        struct ItemIn { uint32_t avail_raw[AB]; int step; };
         auto obs_row8 = [&](int k, int env) { return args.obs + (size_t)row_in(env, k) * D + 8 * q4; };
-        auto fetch_item = [&](int k, int env) {
-            ItemIn in;
-            issue_avail_loads16<AB>(args.avail + (size_t)row_in(env, k) * A, A, q4, in.avail_raw);
-            in.step = args.step_t[env];
-            return in;
-        };
         st.load(regs[0], obs_row8(0, env_of(0)));
         st.load(regs[1], obs_row8(1, env_of(1)));
-        ItemIn in[2] = {fetch_item(0, env_of(0)), fetch_item(1, env_of(1))};
-        // three lookups a step, each asked for one step early: the items whose observations and availability are
-        // fetched next, and the item whose action is drawn next
-        auto pick_item = [&](int s) { return ((s - 2) & ~3) + q4; };
-        EnvAhead obs_ahead{env_of(-LEAD + 4)}, item_ahead{env_of(-LEAD + 2)}, pick_ahead{env_of(pick_item(-LEAD))};
+        EnvAhead obs_ahead{env_of(-LEAD + 4)};       // the item whose observations are fetched next, looked up a step early
         stage_wih();
-        // actions of this workgroup's run of tiles, addressed by row within the run
-        const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(
-            args.action + (IDX ? (size_t)0 : (size_t)first * 16), 0,
-            (IDX ? args.n_envs * N : min(count * 16, rows - first * 16)) * 4, kRawBuffer);
-        constexpr uint32_t kDrop = 0xFFFFFFF0u;              // beyond any descriptor
         auto step = [&](auto set, int s) {
             constexpr int u = decltype(set)::value;          // parity of items s, s + 2, s + 4
             st.write(regs[u], obuf + (size_t)((s & 1) * ks1) * P * 64 + lane);
             st.load(regs[u], obs_row8(s + 4, obs_ahead.take(env_of(s + 5))));
-            {   // availability of item s: slot masks for the epilogue's argmax, the row's bits for the draw
-                const uint32_t slots = avail_mask16<AB>(in[u].avail_raw, A, q4, true);
-                slots_lds[s & 1][lane] = slots;
-                const uint64_t bits = row_avail_bits16<AB>(slots, q4);
-                choice_lds[s & 7][c] = {(uint32_t)bits, (uint32_t)(bits >> 32), in[u].step};      // the four lanes of a row agree
-                in[u] = fetch_item(s + 2, item_ahead.take(env_of(s + 3)));
-            }
-            // The draw is the same work for one lane or sixty-four, so it waits until four items
-            // have their greedy action (or the run ends) and is then made for their 64 rows at
-            // once: lane quarter q takes item 4 i + q.  Item s - 2 got its greedy action in the
-            // previous step.
-            const int k = s - 2;
-            int pick = 0;
-            uint32_t pick_at = kDrop;
-            const int pick_env = pick_ahead.take(env_of(pick_item(s + 1)));
-            if ((k & 3) == 3 || k == count - 1) {
-                const int kk = (k & ~3) + q4;
-                const RowChoice ch = choice_lds[kk & 7][c];
-                const int greedy = greedy_lds[kk & 7][c];
-                const int rr = row_in(pick_env, kk);
-                pick = eps_greedy_pick(greedy, ((uint64_t)ch.bits_hi << 32) | ch.bits_lo, args.epsilon, args.seed,
-                                       (uint32_t)pick_env, (uint32_t)served_at(kk).n, (uint32_t)ch.step);
-                if constexpr (IDX) pick_at = kk >= 0 && kk <= k && item_row(kk) < rows ? (uint32_t)rr * 4u : kDrop;
-                else pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
-            }
-            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
             lds_barrier();
         };
         int s = -LEAD;
@@ -356,19 +314,79 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
         if (s <= last) step(std::integral_constant<int, 0>{}, s);
     } else {
         // ---------------------------------------------------------------- fc1 wave
+        // Besides x, each of the two takes one side job of the choice of action off the loader (which is the wave
+        // with the most to do in a step): the first the availability of item s (slot masks for the epilogue's
+        // argmax, the row's bits and step number for the draw), the second the draw itself.
         const int f = wave - Sh::kFc1;
         stage_wih();
         Fc1Wave<H, P> fc1;
         fc1.load(net, f, ks1, lane);
         fc1.settle_weights(ks1);
-        for (int s = -LEAD; s <= last; ++s) {
+        struct ItemIn { uint32_t avail_raw[AB]; int step; };
+        auto fetch_item = [&](int k, int env) {
+            ItemIn in;
+            issue_avail_loads16<AB>(args.avail + (size_t)row_in(env, k) * A, A, q4, in.avail_raw);
+            in.step = args.step_t[env];
+            return in;
+        };
+        auto fc1_item = [&](int s) {
             const int item = s + 1;
             if (item >= 0 && item < count) {
                 f32x4 b1v[Sh::NBF];
                 Fc1Wave<H, P>::load_bias(net, f, served_at(item).n, q4, b1v);
                 fc1.step(obuf + (size_t)((item & 1) * ks1) * P * 64, ks1, f, lane, b1v, x_lds[item & 1]);
             }
-            lds_barrier();
+        };
+        if (f == 0) {
+            ItemIn in[2] = {fetch_item(0, env_of(0)), fetch_item(1, env_of(1))};
+            EnvAhead item_ahead{env_of(-LEAD + 2)};      // the item whose availability is fetched next, looked up a step early
+            auto step = [&](auto set, int s) {
+                constexpr int u = decltype(set)::value;      // parity of items s, s + 2
+                fc1_item(s);
+                const uint32_t slots = avail_mask16<AB>(in[u].avail_raw, A, q4, true);
+                slots_lds[s & 1][lane] = slots;
+                const uint64_t bits = row_avail_bits16<AB>(slots, q4);
+                choice_lds[s & 7][c] = {(uint32_t)bits, (uint32_t)(bits >> 32), in[u].step};      // the four lanes of a row agree
+                in[u] = fetch_item(s + 2, item_ahead.take(env_of(s + 3)));
+                lds_barrier();
+            };
+            int s = -LEAD;
+            for (; s + 1 <= last; s += 2) {
+                step(std::integral_constant<int, 0>{}, s);
+                step(std::integral_constant<int, 1>{}, s + 1);
+            }
+            if (s <= last) step(std::integral_constant<int, 0>{}, s);
+        } else {
+            // actions of this workgroup's run of tiles, addressed by row within the run
+            const __amdgpu_buffer_rsrc_t action_buf = __builtin_amdgcn_make_buffer_rsrc(
+                args.action + (IDX ? (size_t)0 : (size_t)first * 16), 0,
+                (IDX ? args.n_envs * N : min(count * 16, rows - first * 16)) * 4, kRawBuffer);
+            constexpr uint32_t kDrop = 0xFFFFFFF0u;          // beyond any descriptor
+            auto pick_item = [&](int s) { return ((s - 2) & ~3) + q4; };
+            EnvAhead pick_ahead{env_of(pick_item(-LEAD))};   // the item whose action is drawn next, looked up a step early
+            for (int s = -LEAD; s <= last; ++s) {
+                fc1_item(s);
+                // The draw is the same work for one lane or sixty-four, so it waits until four items
+                // have their greedy action (or the run ends) and is then made for their 64 rows at
+                // once: lane quarter q takes item 4 i + q.  Item s - 2 got its greedy action in the
+                // previous step.
+                const int k = s - 2;
+                int pick = 0;
+                uint32_t pick_at = kDrop;
+                const int pick_env = pick_ahead.take(env_of(pick_item(s + 1)));
+                if ((k & 3) == 3 || k == count - 1) {
+                    const int kk = (k & ~3) + q4;
+                    const RowChoice ch = choice_lds[kk & 7][c];
+                    const int greedy = greedy_lds[kk & 7][c];
+                    const int rr = row_in(pick_env, kk);
+                    pick = eps_greedy_pick(greedy, ((uint64_t)ch.bits_hi << 32) | ch.bits_lo, args.epsilon, args.seed,
+                                           (uint32_t)pick_env, (uint32_t)served_at(kk).n, (uint32_t)ch.step);
+                    if constexpr (IDX) pick_at = kk >= 0 && kk <= k && item_row(kk) < rows ? (uint32_t)rr * 4u : kDrop;
+                    else pick_at = kk >= 0 && kk <= k ? (uint32_t)(kk * 16 + c) * 4u : kDrop;
+                }
+                __builtin_amdgcn_raw_buffer_store_b32((uint32_t)pick, action_buf, pick_at, 0, 0);
+                lds_barrier();
+            }
         }
     }
 }
