@@ -660,6 +660,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle's timing and the comparison with it")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline step: no mixer / gradient / learner sections, no other configurations")
+    ap.add_argument("--only-this-config", action="store_true", help="leave the other configurations' figures out")
     ap.add_argument("--single-net", action="store_true", help="target == online in the unroll")
     ap.add_argument("--kernels", choices=sorted(KERNELS), default="auto",
                     help="kernel family (auto: the library's choice)")
@@ -768,7 +769,8 @@ def main():
         out["mixer_td"] = mixer_section(args.config, not args.no_cpu_baseline)
         out["qnet_grad"] = grad_section(args.config, not args.no_cpu_baseline)
         out["learner_iteration"] = learner_section(args.config)
-        out["all_configs"] = {wl_name: v for wl_name, v in (other_config(ci, args.kernels) for ci in range(4) if ci != args.config)}
+        if not args.only_this_config:
+            out["all_configs"] = {wl_name: v for wl_name, v in (other_config(ci, args.kernels) for ci in range(4) if ci != args.config)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"], out["parity_vs_oracle"] = cpu_baseline(args.config, gpu_act, gpu_unroll)
     print(json.dumps(out))
