@@ -39,8 +39,8 @@
 namespace marl {
 
 
-// LDS of a launch: the shared layout, then the staging area of the epilogue's inputs, [2][8][64] words.
-template <int H, int P> constexpr size_t unroll_lds_bytes(int ks1) { return Fused16<H, P>::lds_bytes(ks1) + 2 * 8 * 64 * 4; }
+// LDS of a launch: the shared layout, then the staging area of the epilogue's inputs, [2][4][64] words.
+template <int H, int P> constexpr size_t unroll_lds_bytes(int ks1) { return Fused16<H, P>::lds_bytes(ks1) + 2 * 4 * 64 * 4; }
 
 template <int H, int P, int AB, bool QALL, int MODE>
 __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
@@ -93,30 +93,38 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
     // wave fetches them instead, beside the observations and a step earlier, the same number of loads every step
     // (positions clamped into the arrays, rows past the end read row 0), and hands them over in LDS:
     // epi[slot & 1][word][lane], words: 0 action, 1 flags (filled(t) | terminated(t-1) << 8 | filled(t-1) << 16),
-    // 2 reward(t-1), 3.. the raw availability words of slot t.
-    struct SlotIn { int u; uint32_t flags; float reward; uint32_t avail_raw[AB]; };
-    constexpr int kEpiWords = 8;
-    static_assert(3 + AB <= kEpiWords, "the staging area holds eight words per lane");
+    // 2 reward(t-1), 3 the lane's availability slots of slot t (avail_mask16, formed by the loader).
+    // With two networks each workgroup's epilogue uses one half only - the online one the action and filled(t),
+    // the target one the rest - and its loader fetches just that half (WANT_ONLINE / WANT_TARGET).
+    struct SlotIn { int u; uint32_t flags; float reward; uint32_t slots; };
+    struct SlotRaw { int u; uint32_t flags; float reward; uint32_t avail_raw[AB]; };
+    constexpr int kEpiWords = 4;
     uint32_t *const epi = reinterpret_cast<uint32_t *>(lds + Sh::lds_bytes(ks1));
-    auto fetch_slot = [&](int t, auto wide) {        // t in 0 .. T
-        SlotIn in{};
+    auto fetch_slot = [&](int t, auto wide, auto want_online, auto want_target) {        // t in 0 .. T
+        constexpr bool kOn = decltype(want_online)::value, kTg = decltype(want_target)::value;
+        SlotRaw in{};
         if constexpr (!kSave) {
             const uint32_t tq = (uint32_t)min(t, T - 1), tp = (uint32_t)max(t - 1, 0);
             if constexpr (kValue) in.u = next_action[btn0 + tp * N];
-            else in.u = actions[act0 + tq * N];
-            in.flags = (uint32_t)filled[bt0 + tq] | (uint32_t)terminated[bt0 + tp] << 8 | (uint32_t)filled[bt0 + tp] << 16;
-            in.reward = reward[bt0 + tp];
-            if constexpr (decltype(wide)::value) issue_avail_loads16<AB>(avail + (av0 + (uint32_t)t * N * A), A, q4, in.avail_raw);
+            else if constexpr (kOn) in.u = actions[act0 + tq * N];
+            if constexpr (kOn) in.flags = (uint32_t)filled[bt0 + tq];
+            if constexpr (kTg) {
+                in.flags |= (uint32_t)terminated[bt0 + tp] << 8 | (uint32_t)filled[bt0 + tp] << 16;
+                in.reward = reward[bt0 + tp];
+                if constexpr (decltype(wide)::value && !kValue)
+                    issue_avail_loads16<AB>(avail + (av0 + (uint32_t)t * N * A), A, q4, in.avail_raw);
+            }
         }
         return in;
     };
-    auto stage_slot = [&](const SlotIn &in, int t) {
+    auto stage_slot = [&](const SlotRaw &in, int t, auto wide, auto want_target) {
         uint32_t *at = epi + (size_t)(t & 1) * kEpiWords * 64 + lane;
         at[0] = (uint32_t)in.u;
         at[64] = in.flags;
-        at[128] = __builtin_bit_cast(uint32_t, in.reward);
-#pragma unroll
-        for (int ab = 0; ab < AB; ++ab) at[(3 + ab) * 64] = in.avail_raw[ab];
+        if constexpr (decltype(want_target)::value) {
+            at[128] = __builtin_bit_cast(uint32_t, in.reward);
+            if constexpr (decltype(wide)::value && !kValue && !kSave) at[192] = avail_mask16<AB>(in.avail_raw, A, q4, valid);
+        }
     };
     auto staged_slot = [&](int t) {
         const uint32_t *at = epi + (size_t)(t & 1) * kEpiWords * 64 + lane;
@@ -124,8 +132,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         in.u = (int)at[0];
         in.flags = at[64];
         in.reward = __builtin_bit_cast(float, at[128]);
-#pragma unroll
-        for (int ab = 0; ab < AB; ++ab) in.avail_raw[ab] = at[(3 + ab) * 64];
+        in.slots = at[192];
         return in;
     };
 
@@ -232,7 +239,7 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
                         best_q = in.u >= 0 ? picked : 0.0f;      // -1: the other network found no action available
                     } else {
                         const uint32_t slots =
-                            A >= 4 ? avail_mask16<AB>(in.avail_raw, A, q4, valid)
+                            A >= 4 ? in.slots
                                    : avail_mask_small16(avail + (valid ? av0 + (uint32_t)t * N * A : 0u), A, q4, valid);
                         if constexpr (kSelect) {
                             int best;
@@ -261,26 +268,37 @@ __global__ __launch_bounds__(fused_threads(H), 2) void unroll_fused_kernel(
         // Two register sets in turn: a step first issues the loads of the slot it will write in the next step, into
         // the set that step will read, then converts the set loaded a step ago.  The loads have a whole step to arrive.
         ObsRegs<H, P> set_a, set_b;
-        SlotIn epi_a{}, epi_b{};                     // the epilogue's inputs of a slot, in turn like the observation sets
-        auto loader_step = [&](const ObsRegs<H, P> &ready, ObsRegs<H, P> &refill, const SlotIn &epi_ready, SlotIn &epi_refill,
-                               int s, auto wide) {
+        SlotRaw epi_a{}, epi_b{};                    // the epilogue's inputs of a slot, in turn like the observation sets
+        auto loader_step = [&](const ObsRegs<H, P> &ready, ObsRegs<H, P> &refill, const SlotRaw &epi_ready, SlotRaw &epi_refill,
+                               int s, auto wide, auto want_online, auto want_target) {
             const int ws = s + 2, ls = ws + 1;
             st.load(refill, base + (size_t)min(max(ls, 0), T) * slot_stride);       // every step the same number of loads (the ends load a slot again)
-            epi_refill = fetch_slot(min(max(s + 1, 0), T), wide);                   // slot s + 1: staged in the next step, read by the epilogue in step s + 2
+            epi_refill = fetch_slot(min(max(s + 1, 0), T), wide, want_online, want_target);     // slot s + 1: staged in the next step, read by the epilogue in step s + 2
             if (ws >= 0 && ws <= T) st.write(ready, obuf + (size_t)((ws & 1) * ks1) * P * 64 + lane);     // registers -> LDS
-            if (s >= 0 && s <= T) stage_slot(epi_ready, s);
+            if (s >= 0 && s <= T) stage_slot(epi_ready, s, wide, want_target);
             lds_barrier();
         };
-        auto loader_loop = [&](auto wide) {
+        auto loader_loop = [&](auto wide, auto want_online, auto want_target) {
             int s = -LEAD;
             for (; s + 1 <= T + 1; s += 2) {
-                loader_step(set_a, set_b, epi_a, epi_b, s, wide);
-                loader_step(set_b, set_a, epi_b, epi_a, s + 1, wide);
+                loader_step(set_a, set_b, epi_a, epi_b, s, wide, want_online, want_target);
+                loader_step(set_b, set_a, epi_b, epi_a, s + 1, wide, want_online, want_target);
             }
-            if (s <= T + 1) loader_step(set_a, set_b, epi_a, epi_b, s, wide);
+            if (s <= T + 1) loader_step(set_a, set_b, epi_a, epi_b, s, wide, want_online, want_target);
         };
-        if (A >= 4) loader_loop(std::true_type{});
-        else loader_loop(std::false_type{});
+        using Yes = std::true_type;
+        using No = std::false_type;
+        // which half the workgroup's epilogue uses (see emit_online / emit_target there)
+        const bool need_online = !is_target && !kValue, need_target = is_target || !two_nets;
+        if (A >= 4) {
+            if (need_online && need_target) loader_loop(Yes{}, Yes{}, Yes{});
+            else if (need_online) loader_loop(Yes{}, Yes{}, No{});
+            else loader_loop(Yes{}, No{}, Yes{});
+        } else {
+            if (need_online && need_target) loader_loop(No{}, Yes{}, Yes{});
+            else if (need_online) loader_loop(No{}, Yes{}, No{});
+            else loader_loop(No{}, No{}, Yes{});
+        }
     } else {
         // ---------------------------------------------------------------- fc1 wave
         const int f = wave - Sh::kFc1;
