@@ -106,3 +106,44 @@ def test_static_unroll_takes_no_device_memory_and_refuses_what_does_not_fit():
                          u1["gamma"], *outs1, static=True)
     assert err.value.status == -2
     online.close(); target.close()
+
+
+def test_static_unroll_replays_from_a_hip_graph():
+    """What the entry point is for: captured into a HIP graph (after one eager call, so that the kernels are loaded)
+    and replayed on fresh input values with eager work between the replays; every replay equals the eager call."""
+    cfg = dict(wl.config(1), B=6, T=11)
+    N, D, A, H = wl.dims(cfg)
+    online, target, w_on, w_tg = nets(cfg)
+    keys = ["obs", "avail", "actions", "reward", "terminated", "filled"]
+    batches = [wl.make_unroll_inputs(cfg, stream=s) for s in range(3)]
+    u = pu.to_dev(batches[0], keys)
+    B, T = cfg["B"], cfg["T"]
+    outs = [torch.empty(B, T, N, device="cuda") for _ in range(3)]
+    call = lambda: online.unroll_td(target, u["obs"], u["avail"], u["actions"], u["reward"], u["terminated"], u["filled"],
+                                    batches[0]["gamma"], *outs, static=True)
+    call()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            call()
+    torch.cuda.synchronize()
+    for r, batch in enumerate(batches):
+        for k in keys:
+            u[k].copy_(torch.from_numpy(np.ascontiguousarray(batch[k])))
+        call()
+        torch.cuda.synchronize()
+        eager = [o.clone() for o in outs]
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for e, o in zip(eager, outs):
+            assert torch.equal(e, o), f"replay {r} differs from the eager call"
+        if r == 0:
+            got = dict(zip(("q_taken", "next_max", "td_target"), (o.cpu().numpy() for o in outs)), q_all=None)
+            pu.compare_unroll(got, oracle_unroll(cfg, w_on, w_tg, batch), pu.TOL[cfg["dtype"]])
+    online.close(); target.close()
