@@ -124,8 +124,18 @@ __global__ __launch_bounds__(fused_threads(H), 2) void act_fused_kernel(const Ac
     // Step s = s0 + u of the unrolled loops has the parity of u.
 
     auto stage_wih = [&]() {             // every wave's share of W_ih -> LDS
-        constexpr int kVecs = 3 * FBK * KS * P * 64;
-        for (int i = threadIdx.x; i < kVecs; i += fused_threads(H)) wih_lds[i] = net.wih_16[i];
+        constexpr int kVecs = 3 * FBK * KS * P * 64, kRounds = kVecs / fused_threads(H);
+        static_assert(kVecs % fused_threads(H) == 0, "whole rounds");
+        // every workgroup copies the same bytes at the same time: each starts at another round, so that at any
+        // moment the compute units ask different L2 channels
+        const int first_round = blockIdx.x % kRounds;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            int round = first_round + r;
+            round = round >= kRounds ? round - kRounds : round;
+            const int i = round * fused_threads(H) + threadIdx.x;
+            wih_lds[i] = net.wih_16[i];
+        }
     };
 
     if (wave < Sh::NC) {
