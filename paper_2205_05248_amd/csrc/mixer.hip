@@ -63,68 +63,76 @@ struct MixerArgs {
     float *q_total, *y_total, *td_err;
 };
 
+// Two tiles per wave: when a block's fragments fit two register sets and the state is long enough
+// for the fragment traffic to matter.
+template <int P, int KS> constexpr bool mixer_two_tiles_fit() { return KS * P <= 16 && KS >= 8; }
+
+// One pass of one group of 64 TPW transitions: blockIdx.y = 0 is the online mixer on the chosen
+// values and the slot's state (Q_total), 1 the target mixer on the bootstrap values and the next
+// slot's state (y_total).  td_err = filled ? y_total - Q_total : 0 is formed by both passes adding
+// their term to an array cleared beforehand: the two orders give the same bits (0 + x = x, and
+// -Q + y and y + (-Q) round alike).
 // KS: k-steps of 32 over the state (the packed fragments are zero past the state's end).
-template <int MB, int P, int KS>
+// TPW: tiles of 16 transitions per wave; each fragment read from LDS then feeds TPW products.
+template <int MB, int P, int KS, int TPW>
 __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int pass = blockIdx.y;
     const int N = a.N, S = a.S, T = a.T;
-    const int tile_row0 = (blockIdx.x * kMixWaves + wave) * 16;
-    const int row = tile_row0 + c;                                 // transition b T + t
-    const bool valid = row < a.rows;
-    const int rr = valid ? row : a.rows - 1;                       // rows past the end re-read the last one
-    const int b = rr / T, t = rr % T;
     const int n_blocks = (N + 3) * MB, F = n_blocks * 16;
     constexpr int kChunk = KS * P * 64;                            // 16-byte vectors of one block
     constexpr int kStage = (kChunk + kMixThreads - 1) / kMixThreads;      // vectors per thread and block
-    // LDS: two block buffers, the pass's bias table, the tiles' agent values [wave][agent][row]
+    constexpr bool kReadAhead = KS * P <= 16;                      // two register sets of a block's fragments fit
+    static_assert(TPW == 1 || kReadAhead, "two tiles per wave come with the read-ahead loop");
+    // LDS: two block buffers, the pass's bias table, the tiles' agent values [wave][tile][agent][row]
     bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);
     float *const bias_lds = reinterpret_cast<float *>(lds + (size_t)2 * kChunk * 16);
-    float *const q_lds = bias_lds + F + (size_t)wave * N * 16;
+    float *const q_lds = bias_lds + F + (size_t)wave * TPW * N * 16;
 
-    float mixed[2];
+    const bf16x8 *frags = a.frags[pass];
+    // Fragments travel global -> registers -> LDS.  A block is asked for kAhead blocks before it
+    // is multiplied (an L2 round trip is several blocks long) into one of kAhead register sets,
+    // indexed by block % kAhead with the loop unrolled over them so that a wait covers only that
+    // set.  Blocks past the last one re-read it and contribute nothing, which keeps every step the
+    // same straight-line code with no other global access in it (biases and agent values come
+    // from LDS).
+    bf16x8 stage[kAhead][kStage];
+    auto fetch = [&](int set, int blk) {       // the block's fragments, this thread's share
+        const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
-        // pass 0: online mixer, chosen values, state of the slot; pass 1: target mixer,
-        // bootstrap values, state of the next slot
-        const bf16x8 *frags = a.frags[pass];
-        const float *srow = a.state + ((size_t)b * (T + 1) + t + pass) * S;
-        // Fragments travel global -> registers -> LDS.  A block is asked for kAhead blocks before
-        // it is multiplied (an L2 round trip is several blocks long) into one of kAhead register
-        // sets, indexed by block % kAhead with the loop unrolled over them so that a wait covers
-        // only that set; it moves to LDS one block ahead of its use.  Blocks past the last one
-        // re-read it and contribute nothing, which keeps every step the same straight-line code
-        // with no other global access in it (biases and agent values come from LDS).
-        bf16x8 stage[kAhead][kStage];
-        auto fetch = [&](int set, int blk) {       // the block's fragments, this thread's share
-            const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
+        for (int i = 0; i < kStage; ++i) stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
+    };
+    auto stash = [&](int set, int blk) {
+        bf16x8 *dst = buf + (size_t)(blk & 1) * kChunk;
 #pragma unroll
-            for (int i = 0; i < kStage; ++i) stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
-        };
-        auto stash = [&](int set, int blk) {
-            bf16x8 *dst = buf + (size_t)(blk & 1) * kChunk;
-#pragma unroll
-            for (int i = 0; i < kStage; ++i) {
-                const int at = i * kMixThreads + threadIdx.x;
-                if (at < kChunk) dst[at] = stage[set][i];
-            }
-        };
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) fetch(u, u);
-        lds_barrier();                             // the previous pass has finished with LDS
-        for (int i = threadIdx.x; i < F; i += kMixThreads) bias_lds[i] = a.bias[pass][i];
-        for (int i = lane; i < 16 * N; i += 64) {  // this wave's tile: rows are consecutive in memory
-            const int r = i / N, n = i % N;
-            q_lds[n * 16 + r] = a.q[pass][(size_t)min(tile_row0 + r, a.rows - 1) * N + n];
+        for (int i = 0; i < kStage; ++i) {
+            const int at = i * kMixThreads + threadIdx.x;
+            if (at < kChunk) dst[at] = stage[set][i];
         }
-        // The tile's states as B operands: lane (row c, quarter q) holds values 32 ks + 8 q + 0..7.
-        // K-steps wholly inside the row are two 16-byte loads (only 4-byte alignment is assumed);
-        // a partial one is read element by element from positions clamped into the row and
-        // zeroed past its end.
-        const int nfull = S / 32;
-        Frag<P> st[KS];
+    };
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) fetch(u, u);
+    for (int i = threadIdx.x; i < F; i += kMixThreads) bias_lds[i] = a.bias[pass][i];
+    // The tiles' states as B operands: lane (row c, quarter q) holds values 32 ks + 8 q + 0..7.
+    // K-steps wholly inside the row are two 16-byte loads (only 4-byte alignment is assumed); a
+    // partial one is read element by element from positions clamped into the row and zeroed past
+    // its end.  Rows past the end re-read the last one.
+    const int nfull = S / 32;
+    Frag<P> st[TPW][KS];
+    int row[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tile_row0 = ((blockIdx.x * kMixWaves + wave) * TPW + i) * 16;
+        row[i] = tile_row0 + c;
+        const int rr = min(row[i], a.rows - 1);
+        const float *srow = a.state + ((size_t)(rr / T) * (T + 1) + rr % T + pass) * S;
+        for (int k = lane; k < 16 * N; k += 64) {  // the tile's agent values: its rows are consecutive in memory
+            const int r = k / N, n = k % N;
+            q_lds[(i * N + n) * 16 + r] = a.q[pass][(size_t)min(tile_row0 + r, a.rows - 1) * N + n];
+        }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             float v[8];
@@ -133,34 +141,120 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
                 __builtin_memcpy(&lo4, srow + 32 * ks + 8 * q4, 16);
                 __builtin_memcpy(&hi4, srow + 32 * ks + 8 * q4 + 4, 16);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { v[i] = lo4[i]; v[4 + i] = hi4[i]; }
+                for (int e = 0; e < 4; ++e) { v[e] = lo4[e]; v[4 + e] = hi4[e]; }
             } else {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int at = 32 * ks + 8 * q4 + i;
+                for (int e = 0; e < 8; ++e) {
+                    const int at = 32 * ks + 8 * q4 + e;
                     const float x = srow[min(at, S - 1)];
-                    v[i] = at < S ? x : 0.0f;
+                    v[e] = at < S ? x : 0.0f;
                 }
             }
-            st[ks] = to_frag<P>(v);
+            st[i][ks] = to_frag<P>(v);
         }
-        f32x4 gain[MB];                            // v2, this lane's units
+    }
+    f32x4 gain[MB];                            // v2, this lane's units
 #pragma unroll
-        for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2[pass], j, q4);
-        stash(0, 0);
-        lds_barrier();
-        f32x4 hidden[MB];
+    for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2[pass], j, q4);
+    f32x4 hidden[TPW][MB];
+    float total[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        total[i] = 0.0f;
 #pragma unroll
         for (int j = 0; j < MB; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) hidden[j][r] = 0.0f;
-        float total = 0.0f;
+            for (int r = 0; r < 4; ++r) hidden[i][j][r] = 0.0f;
+    }
+    // A block's 16 x 16 result of tile i, folded into the tile's running mix
+    auto fold = [&](int i, int blk, const f32x4 &acc, float qn) {
+        const int group = blk / MB, j = blk % MB;                  // group: agents 0 .. N-1, then b1, w2, offset
+        if (group < N) {
+#pragma unroll
+            for (int jj = 0; jj < MB; ++jj)
+                if (jj == j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) hidden[i][jj][r] = fmaf(qn, fabsf(acc[r]), hidden[i][jj][r]);
+        } else if (group == N) {
+#pragma unroll
+            for (int jj = 0; jj < MB; ++jj)
+                if (jj == j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) hidden[i][jj][r] += acc[r];
+        } else if (group == N + 1) {
+#pragma unroll
+            for (int jj = 0; jj < MB; ++jj)
+                if (jj == j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const float x = hidden[i][jj][r];
+                        total[i] = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total[i]);
+                    }
+        } else if (group == N + 2) {
+#pragma unroll
+            for (int jj = 0; jj < MB; ++jj)
+                if (jj == j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) total[i] = fmaf(gain[jj][r], fmaxf(acc[r], 0.0f), total[i]);
+        }
+    };
+    if constexpr (kReadAhead) {
+        // A block's fragments are read from LDS into registers while the previous block is being
+        // multiplied (two register sets by the block's parity), so that the waves' LDS reads
+        // (64 KB per block) and their products run side by side instead of in turns.  The small
+        // reads of the step (bias, agent value) are issued before them: LDS answers in order, and
+        // the products need those first.  Block b + 2 goes to LDS while block b is multiplied: its
+        // buffer held block b, whose reads every wave finished before the barrier that ended the
+        // previous step.
+        WFrag<P> w[2][KS];
+        auto read = [&](int set, int blk) {
+            const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                w[set][ks].hi = src[(ks * P) * 64];
+                if constexpr (P == 2) w[set][ks].lo = src[(ks * P + 1) * 64];
+            }
+        };
+        stash(0, 0);
+        stash(1, 1);
+        fetch(0, kAhead);
+        lds_barrier();
+        read(0, 0);
+        lds_barrier();                         // every wave holds block 0 before its buffer is written again
+        for (int base = 0; base < n_blocks; base += kAhead) {
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int blk = base + u;
+                const f32x4 bias4 = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
+                f32x4 acc[TPW];
+                float qn[TPW];
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) {
+                    acc[i] = bias4;
+                    qn[i] = q_lds[(i * N + min(blk / MB, N - 1)) * 16 + c];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                read((u + 1) & 1, blk + 1);
+                __builtin_amdgcn_sched_barrier(0);                 // the reads stay ahead of the products
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) mma16<P>(acc[i], w[u & 1][ks], st[i][ks]);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) fold(i, blk, acc[i], qn[i]);
+                fetch((u + 1) % kAhead, blk + kAhead + 1);         // that set held block blk + 1, in LDS since the last step
+                stash((u + 2) % kAhead, blk + 2);
+                lds_barrier();
+            }
+        }
+    } else {
+        stash(0, 0);
+        lds_barrier();
         for (int base = 0; base < n_blocks; base += kAhead) {
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
                 const int blk = base + u;
                 fetch(u, blk + kAhead);                            // this set held block blk, already in LDS
-                const int group = blk / MB, j = blk % MB;          // group: agents 0 .. N-1, then b1, w2, offset
                 const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
                 WFrag<P> w[KS];
 #pragma unroll
@@ -169,51 +263,39 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
                     if constexpr (P == 2) w[ks].lo = src[(ks * P + 1) * 64];
                 }
                 f32x4 acc = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
-                const float qn = q_lds[min(group, N - 1) * 16 + c];
+                const float qn = q_lds[min(blk / MB, N - 1) * 16 + c];
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[ks]);
-                if (group < N) {
-#pragma unroll
-                    for (int jj = 0; jj < MB; ++jj)
-                        if (jj == j)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) hidden[jj][r] = fmaf(qn, fabsf(acc[r]), hidden[jj][r]);
-                } else if (group == N) {
-#pragma unroll
-                    for (int jj = 0; jj < MB; ++jj)
-                        if (jj == j)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) hidden[jj][r] += acc[r];
-                } else if (group == N + 1) {
-#pragma unroll
-                    for (int jj = 0; jj < MB; ++jj)
-                        if (jj == j)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                const float x = hidden[jj][r];
-                                total = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total);
-                            }
-                } else if (group == N + 2) {
-#pragma unroll
-                    for (int jj = 0; jj < MB; ++jj)
-                        if (jj == j)
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) total = fmaf(gain[jj][r], fmaxf(acc[r], 0.0f), total);
-                }
+                for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[0][ks]);
+                fold(0, blk, acc, qn);
                 stash((u + 1) % kAhead, blk + 1);
                 lds_barrier();
             }
         }
-        total += __shfl_xor(total, 16);
-        total += __shfl_xor(total, 32);
-        mixed[pass] = total + a.c2[pass][0];
     }
-    if (valid && q4 == 0) {
-        const float y = a.reward[row] + a.gamma * (a.terminated[row] ? 0.0f : 1.0f) * mixed[1];
-        if (a.q_total) a.q_total[row] = mixed[0];
-        if (a.y_total) a.y_total[row] = y;
-        if (a.td_err) a.td_err[row] = a.filled[row] ? y - mixed[0] : 0.0f;
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        float sum = total[i];
+        sum += __shfl_xor(sum, 16);
+        sum += __shfl_xor(sum, 32);
+        const float mixed = sum + a.c2[pass][0];
+        const int r = row[i];
+        if (r < a.rows && q4 == 0) {
+            if (pass == 0) {
+                if (a.q_total) a.q_total[r] = mixed;
+                if (a.td_err && a.filled[r]) atomicAdd(a.td_err + r, -mixed);
+            } else {
+                const float y = a.reward[r] + a.gamma * (a.terminated[r] ? 0.0f : 1.0f) * mixed;
+                if (a.y_total) a.y_total[r] = y;
+                if (a.td_err && a.filled[r]) atomicAdd(a.td_err + r, y);
+            }
+        }
     }
+}
+
+__global__ __launch_bounds__(256) void mixer_clear_kernel(float *__restrict__ x, int n)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) x[i] = 0.0f;
 }
 
 // loss[0] = sum of the squared errors, loss[1] = number of filled transitions.  One workgroup, each
@@ -245,15 +327,30 @@ __global__ __launch_bounds__(256) void mixer_loss_kernel(const float *__restrict
     }
 }
 
+template <int MB, int P, int KS, int TPW>
+hipError_t mixer_launch_tiles(const MixerArgs &a, hipStream_t stream)
+{
+    const int per_group = 16 * kMixWaves * TPW;
+    const dim3 grid((unsigned)((a.rows + per_group - 1) / per_group), 2), block(kMixThreads);
+    const size_t lds = (size_t)2 * KS * P * 1024 + sizeof(float) * ((size_t)(a.N + 3) * MB * 16 + (size_t)kMixWaves * TPW * a.N * 16);
+    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KS, TPW>>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KS, TPW>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+
+// Two tiles per wave halve the fragment traffic of a transition and the number of workgroups: taken
+// once one tile per wave would give more workgroups than there are compute units.
 template <int MB, int P, int KS>
 hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
 {
-    const dim3 grid((unsigned)((a.rows + 16 * kMixWaves - 1) / (16 * kMixWaves))), block(kMixThreads);
-    const size_t lds = (size_t)2 * KS * P * 1024 + sizeof(float) * ((size_t)(a.N + 3) * MB * 16 + (size_t)kMixWaves * a.N * 16);
-    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KS>>(kLdsLimit);
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KS>), grid, block, lds, stream, a);
-    return hipGetLastError();
+    if constexpr (mixer_two_tiles_fit<P, KS>()) {
+        int dev = 0, n_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+            n_cu = 256;
+        if (2 * ((a.rows + 16 * kMixWaves - 1) / (16 * kMixWaves)) > n_cu) return mixer_launch_tiles<MB, P, KS, 2>(a, stream);
+    }
+    return mixer_launch_tiles<MB, P, KS, 1>(a, stream);
 }
 
 template <int P, int KS>
@@ -473,6 +570,11 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const int mb = online->desc.embed / 16;
     hipError_t err;
+    if (td_err) {                                          // both passes add their term to it
+        hipLaunchKernelGGL(marl::mixer_clear_kernel, dim3((unsigned)((a.rows + 255) / 256)), dim3(256), 0, stream, td_err, a.rows);
+        err = hipGetLastError();
+        if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td clear launch");
+    }
     if (online->planes == 2) err = marl::mixer_dispatch_ks<2>(a.ks, mb, a, stream);
     else err = marl::mixer_dispatch_ks<1>(a.ks, mb, a, stream);
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_td launch");
