@@ -199,51 +199,66 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         }
     };
     if constexpr (kReadAhead) {
-        // A block's fragments are read from LDS into registers while the previous block is being
-        // multiplied (two register sets by the block's parity), so that the waves' LDS reads
-        // (64 KB per block) and their products run side by side instead of in turns.  The small
-        // reads of the step (bias, agent value) are issued before them: LDS answers in order, and
-        // the products need those first.  Block b + 2 goes to LDS while block b is multiplied: its
-        // buffer held block b, whose reads every wave finished before the barrier that ended the
-        // previous step.
+        // One wave per SIMD issues in order, so whatever is to run beside the products has to sit
+        // between them in the instruction stream.  A step multiplies block b from one register set
+        // while, k-step by k-step, block b + 1 is read from LDS into the other set (by the block's
+        // parity), the step's share of block b + 5 is asked for and block b + 2 is written to LDS:
+        // its buffer held block b, whose reads every wave finished before the barrier that ended
+        // the previous step.  Bias and agent value of block b + 1 are read at the head of the step.
         WFrag<P> w[2][KS];
-        auto read = [&](int set, int blk) {
+        auto read_step = [&](int set, int blk, int ks) {
             const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                w[set][ks].hi = src[(ks * P) * 64];
-                if constexpr (P == 2) w[set][ks].lo = src[(ks * P + 1) * 64];
-            }
+            w[set][ks].hi = src[(ks * P) * 64];
+            if constexpr (P == 2) w[set][ks].lo = src[(ks * P + 1) * 64];
         };
+        auto fetch_one = [&](int set, int blk, int i) {
+            const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
+            stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
+        };
+        auto stash_one = [&](int set, int blk, int i) {
+            const int at = i * kMixThreads + threadIdx.x;
+            if (at < kChunk) buf[(size_t)(blk & 1) * kChunk + at] = stage[set][i];
+        };
+        auto head = [&](int blk, f32x4 &bias4, float (&qn)[TPW]) {
+            bias4 = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) qn[i] = q_lds[(i * N + min(blk / MB, N - 1)) * 16 + c];
+        };
+        static_assert(2 * kStage <= KS, "a step's loads and its LDS writes sit at different k-steps");
         stash(0, 0);
         stash(1, 1);
         fetch(0, kAhead);
         lds_barrier();
-        read(0, 0);
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) read_step(0, 0, ks);
+        f32x4 bias_next;
+        float qn_next[TPW];
+        head(0, bias_next, qn_next);
         lds_barrier();                         // every wave holds block 0 before its buffer is written again
         for (int base = 0; base < n_blocks; base += kAhead) {
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
                 const int blk = base + u;
-                const f32x4 bias4 = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
                 f32x4 acc[TPW];
                 float qn[TPW];
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) {
-                    acc[i] = bias4;
-                    qn[i] = q_lds[(i * N + min(blk / MB, N - 1)) * 16 + c];
+                    acc[i] = bias_next;
+                    qn[i] = qn_next[i];
                 }
+                head(blk + 1, bias_next, qn_next);
                 __builtin_amdgcn_sched_barrier(0);
-                read((u + 1) & 1, blk + 1);
-                __builtin_amdgcn_sched_barrier(0);                 // the reads stay ahead of the products
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
+                for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
                     for (int i = 0; i < TPW; ++i) mma16<P>(acc[i], w[u & 1][ks], st[i][ks]);
+                    read_step((u + 1) & 1, blk + 1, ks);
+                    if (ks < kStage) fetch_one((u + 1) % kAhead, blk + kAhead + 1, ks);      // that set held block blk + 1, in LDS since the last step
+                    if (ks >= KS - kStage) stash_one((u + 2) % kAhead, blk + 2, ks - (KS - kStage));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
 #pragma unroll
                 for (int i = 0; i < TPW; ++i) fold(i, blk, acc[i], qn[i]);
-                fetch((u + 1) % kAhead, blk + kAhead + 1);         // that set held block blk + 1, in LDS since the last step
-                stash((u + 2) % kAhead, blk + 2);
                 lds_barrier();
             }
         }
