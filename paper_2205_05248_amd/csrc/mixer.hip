@@ -113,9 +113,23 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
             if (at < kChunk) dst[at] = stage[set][i];
         }
     };
+    // Everything the prologue reads is asked for before any of it is used, smallest first (loads
+    // answer in order): a loop of load-then-store over a run-time count would pay a memory round
+    // trip per iteration.
+    constexpr int kBatch = 8;
+    const float c2 = a.c2[pass][0];
+    {
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(a.bias[pass]);      // F is a multiple of 16, the table 16-byte aligned
+        f32x4 *dst = reinterpret_cast<f32x4 *>(bias_lds);
+        for (int i0 = threadIdx.x; i0 < F / 4; i0 += 4 * kMixThreads) {
+            f32x4 v[4];
 #pragma unroll
-    for (int u = 0; u < kAhead; ++u) fetch(u, u);
-    for (int i = threadIdx.x; i < F; i += kMixThreads) bias_lds[i] = a.bias[pass][i];
+            for (int e = 0; e < 4; ++e) v[e] = src[min(i0 + e * kMixThreads, F / 4 - 1)];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (i0 + e * kMixThreads < F / 4) dst[i0 + e * kMixThreads] = v[e];
+        }
+    }
     // The tiles' states as B operands: lane (row c, quarter q) holds values 32 ks + 8 q + 0..7.
     // K-steps wholly inside the row are two 16-byte loads (only 4-byte alignment is assumed); a
     // partial one is read element by element from positions clamped into the row and zeroed past
@@ -123,39 +137,85 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
     const int nfull = S / 32;
     Frag<P> st[TPW][KS];
     int row[TPW];
+    const float *srow[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         const int tile_row0 = ((blockIdx.x * kMixWaves + wave) * TPW + i) * 16;
         row[i] = tile_row0 + c;
         const int rr = min(row[i], a.rows - 1);
-        const float *srow = a.state + ((size_t)(rr / T) * (T + 1) + rr % T + pass) * S;
-        for (int k = lane; k < 16 * N; k += 64) {  // the tile's agent values: its rows are consecutive in memory
-            const int r = k / N, n = k % N;
-            q_lds[(i * N + n) * 16 + r] = a.q[pass][(size_t)min(tile_row0 + r, a.rows - 1) * N + n];
-        }
+        srow[i] = a.state + ((size_t)(rr / T) * (T + 1) + rr % T + pass) * S;
+        for (int k0 = lane; k0 < 16 * N; k0 += 64 * kBatch) {      // the tile's agent values: its rows are consecutive in memory
+            float v[kBatch];
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            float v[8];
-            if (ks < nfull) {
-                f32x4 lo4, hi4;
-                __builtin_memcpy(&lo4, srow + 32 * ks + 8 * q4, 16);
-                __builtin_memcpy(&hi4, srow + 32 * ks + 8 * q4 + 4, 16);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) { v[e] = lo4[e]; v[4 + e] = hi4[e]; }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int at = 32 * ks + 8 * q4 + e;
-                    const float x = srow[min(at, S - 1)];
-                    v[e] = at < S ? x : 0.0f;
-                }
+            for (int e = 0; e < kBatch; ++e) {
+                const int k = min(k0 + 64 * e, 16 * N - 1);
+                v[e] = a.q[pass][(size_t)min(tile_row0 + k / N, a.rows - 1) * N + k % N];
             }
-            st[i][ks] = to_frag<P>(v);
+#pragma unroll
+            for (int e = 0; e < kBatch; ++e) {
+                const int k = k0 + 64 * e;
+                if (k < 16 * N) q_lds[(i * N + k % N) * 16 + k / N] = v[e];
+            }
         }
+    }
+    if (nfull == KS) {                         // the state fills its k-steps: every load first, then the first blocks' fragments
+        f32x4 raw[TPW][KS][2];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                __builtin_memcpy(&raw[i][ks][0], srow[i] + 32 * ks + 8 * q4, 16);
+                __builtin_memcpy(&raw[i][ks][1], srow[i] + 32 * ks + 8 * q4 + 4, 16);
+            }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                float v[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) { v[e] = raw[i][ks][0][e]; v[4 + e] = raw[i][ks][1][e]; }
+                st[i][ks] = to_frag<P>(v);
+            }
+    } else {
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+#pragma unroll
+        for (int i = 0; i < TPW; ++i)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                float v[8];
+                if (ks < nfull) {
+                    f32x4 lo4, hi4;
+                    __builtin_memcpy(&lo4, srow[i] + 32 * ks + 8 * q4, 16);
+                    __builtin_memcpy(&hi4, srow[i] + 32 * ks + 8 * q4 + 4, 16);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { v[e] = lo4[e]; v[4 + e] = hi4[e]; }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int at = 32 * ks + 8 * q4 + e;
+                        const float x = srow[i][min(at, S - 1)];
+                        v[e] = at < S ? x : 0.0f;
+                    }
+                }
+                st[i][ks] = to_frag<P>(v);
+            }
     }
     f32x4 gain[MB];                            // v2, this lane's units
 #pragma unroll
     for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2[pass], j, q4);
+    // what the end of the pass reads, asked for now
+    float reward[TPW];
+    bool live[TPW], open_end[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int rr = min(row[i], a.rows - 1);
+        reward[i] = a.reward[rr];
+        live[i] = a.filled[rr] != 0;
+        open_end[i] = a.terminated[rr] == 0;
+    }
     f32x4 hidden[TPW][MB];
     float total[TPW];
 #pragma unroll
@@ -292,16 +352,16 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         float sum = total[i];
         sum += __shfl_xor(sum, 16);
         sum += __shfl_xor(sum, 32);
-        const float mixed = sum + a.c2[pass][0];
+        const float mixed = sum + c2;
         const int r = row[i];
         if (r < a.rows && q4 == 0) {
             if (pass == 0) {
                 if (a.q_total) a.q_total[r] = mixed;
-                if (a.td_err && a.filled[r]) atomicAdd(a.td_err + r, -mixed);
+                if (a.td_err && live[i]) atomicAdd(a.td_err + r, -mixed);
             } else {
-                const float y = a.reward[r] + a.gamma * (a.terminated[r] ? 0.0f : 1.0f) * mixed;
+                const float y = reward[i] + a.gamma * (open_end[i] ? 1.0f : 0.0f) * mixed;
                 if (a.y_total) a.y_total[r] = y;
-                if (a.td_err && a.filled[r]) atomicAdd(a.td_err + r, y);
+                if (a.td_err && live[i]) atomicAdd(a.td_err + r, y);
             }
         }
     }
