@@ -2,14 +2,14 @@
 //
 // The work is one dense contraction, [ (N + 3) M generated quantities x S ] . [ S x B T states ],
 // followed by a cheap per-transition combination, done for the online mixer on state[b, t] and for
-// the target mixer on state[b, t + 1].  A workgroup of four wavefronts takes 64 consecutive
-// transitions, one tile of 16 per wave; a wave keeps its tile's states in registers as MFMA B
-// operands (bf16, plus the bf16 remainder for fp32 parameters) for a whole pass.  The state
-// matrices stream past as A-operand fragments, one block of 16 generated quantities at a time:
-// the block's fragments are copied global -> registers -> LDS by all four waves while the previous
-// blocks are being multiplied (asked for four blocks ahead), so every wave reads them from LDS and
-// L2 sees each block once per workgroup.  A block's 16 x 16 result lands with lane (row c, quarter q) holding quantities
-// 4 q .. 4 q + 3 of row c, and is folded into the running mix right away:
+// the target mixer on state[b, t + 1].  A workgroup takes one of the two passes for 64 consecutive
+// transitions (128 on large batches), one tile of 16 per wave; a wave keeps its tile's states in
+// registers as MFMA B operands (bf16, plus the bf16 remainder for fp32 parameters) for the whole
+// pass.  The state matrices stream past as A-operand fragments, one block of 16 generated quantities
+// at a time: the block's fragments are copied global -> registers -> LDS by all waves while earlier
+// blocks are being multiplied (asked for five blocks ahead), so every wave reads them from LDS and
+// L2 sees each block once per workgroup.  A block's 16 x 16 result lands with lane (row c, quarter q)
+// holding quantities 4 q .. 4 q + 3 of row c, and is folded into the running mix:
 //   blocks of agent n        hidden += q[n] |result + hb1|
 //   blocks of b1             hidden += result + hbb1
 //   blocks of w2             total  += |result + hb2| elu(hidden)     (hidden is complete by then)
@@ -49,7 +49,7 @@ struct marl_mixer {
 namespace marl {
 namespace {
 
-constexpr int kMixWaves = 4, kMixThreads = 64 * kMixWaves;
+constexpr int kBigTiles = 1, kBigWaves = 8;       // shape of a workgroup on large batches: tiles per wave, waves
 constexpr int kAhead = 4;             // blocks between asking for a block's fragments and multiplying them
 
 struct MixerArgs {
@@ -74,9 +74,11 @@ template <int P, int KS> constexpr bool mixer_two_tiles_fit() { return KS * P <=
 // -Q + y and y + (-Q) round alike).
 // KS: k-steps of 32 over the state (the packed fragments are zero past the state's end).
 // TPW: tiles of 16 transitions per wave; each fragment read from LDS then feeds TPW products.
-template <int MB, int P, int KS, int TPW>
-__global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a)
+// W: wavefronts per workgroup, one (4) or two (8) per SIMD.
+template <int MB, int P, int KS, int TPW, int W>
+__global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
 {
+    constexpr int kMixWaves = W, kMixThreads = 64 * W;      // of this kernel
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -226,36 +228,27 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
 #pragma unroll
             for (int r = 0; r < 4; ++r) hidden[i][j][r] = 0.0f;
     }
-    // A block's 16 x 16 result of tile i, folded into the tile's running mix
-    auto fold = [&](int i, int blk, const f32x4 &acc, float qn) {
-        const int group = blk / MB, j = blk % MB;                  // group: agents 0 .. N-1, then b1, w2, offset
-        if (group < N) {
+    // A block's 16 x 16 result of tile i, folded into the tile's running mix.  j = blk % MB, given by the
+    // caller from the unrolled step number (kAhead is a multiple of MB), so that the registers it
+    // touches are known when compiling.  Agent and b1 blocks take the same straight-line code with two
+    // coefficients (q[n], 0) or (0, 1): a product with zero adds nothing and a product with one is
+    // exact, so the sums are the ones of `hidden += q[n] |result|` and `hidden += result`.  Only the
+    // last blocks branch (uniformly, around arithmetic alone).
+    static_assert(kAhead % MB == 0, "a block's place among its group's blocks follows from the step number");
+    auto fold = [&](int i, int j, int blk, const f32x4 &acc, float qn) {
+        const int group = blk / MB;                                // agents 0 .. N-1, then b1, w2, offset
+        const float by_abs = group < N ? qn : 0.0f, by_value = group == N ? 1.0f : 0.0f;
 #pragma unroll
-            for (int jj = 0; jj < MB; ++jj)
-                if (jj == j)
+        for (int r = 0; r < 4; ++r) hidden[i][j][r] = fmaf(by_value, acc[r], fmaf(by_abs, fabsf(acc[r]), hidden[i][j][r]));
+        if (group == N + 1) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) hidden[i][jj][r] = fmaf(qn, fabsf(acc[r]), hidden[i][jj][r]);
-        } else if (group == N) {
-#pragma unroll
-            for (int jj = 0; jj < MB; ++jj)
-                if (jj == j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) hidden[i][jj][r] += acc[r];
-        } else if (group == N + 1) {
-#pragma unroll
-            for (int jj = 0; jj < MB; ++jj)
-                if (jj == j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const float x = hidden[i][jj][r];
-                        total[i] = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total[i]);
-                    }
+            for (int r = 0; r < 4; ++r) {
+                const float x = hidden[i][j][r];
+                total[i] = fmaf(fabsf(acc[r]), x > 0.0f ? x : expm1f(x), total[i]);
+            }
         } else if (group == N + 2) {
 #pragma unroll
-            for (int jj = 0; jj < MB; ++jj)
-                if (jj == j)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) total[i] = fmaf(gain[jj][r], fmaxf(acc[r], 0.0f), total[i]);
+            for (int r = 0; r < 4; ++r) total[i] = fmaf(gain[j][r], fmaxf(acc[r], 0.0f), total[i]);
         }
     };
     if constexpr (kReadAhead) {
@@ -277,7 +270,7 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         };
         auto stash_one = [&](int set, int blk, int i) {
             const int at = i * kMixThreads + threadIdx.x;
-            if (at < kChunk) buf[(size_t)(blk & 1) * kChunk + at] = stage[set][i];
+            if (kChunk % kMixThreads == 0 || at < kChunk) buf[(size_t)(blk & 1) * kChunk + at] = stage[set][i];
         };
         auto head = [&](int blk, f32x4 &bias4, float (&qn)[TPW]) {
             bias4 = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
@@ -295,6 +288,17 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
         float qn_next[TPW];
         head(0, bias_next, qn_next);
         lds_barrier();                         // every wave holds block 0 before its buffer is written again
+        // A block's result is folded in the middle of the next step, between that step's products:
+        // at the end of its own step the wave would wait for the last product, fold, and only then
+        // reach the barrier.
+        f32x4 done[TPW];
+        float done_qn[TPW];
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            done_qn[i] = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) done[i][r] = 0.0f;         // "block -1": adds nothing
+        }
         for (int base = 0; base < n_blocks; base += kAhead) {
 #pragma unroll
             for (int u = 0; u < kAhead; ++u) {
@@ -315,12 +319,25 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
                     read_step((u + 1) & 1, blk + 1, ks);
                     if (ks < kStage) fetch_one((u + 1) % kAhead, blk + kAhead + 1, ks);      // that set held block blk + 1, in LDS since the last step
                     if (ks >= KS - kStage) stash_one((u + 2) % kAhead, blk + 2, ks - (KS - kStage));
+                    if (ks == KS / 2) {
+#pragma unroll
+                        for (int i = 0; i < TPW; ++i) fold(i, (u + kAhead - 1) % MB, max(blk - 1, 0), done[i], done_qn[i]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
 #pragma unroll
-                for (int i = 0; i < TPW; ++i) fold(i, blk, acc[i], qn[i]);
+                for (int i = 0; i < TPW; ++i) {
+                    done[i] = acc[i];
+                    done_qn[i] = qn[i];
+                }
                 lds_barrier();
             }
+        }
+        {
+            // the last step's block: the loop runs whole rounds of kAhead steps
+            const int last = (n_blocks + kAhead - 1) / kAhead * kAhead - 1;
+#pragma unroll
+            for (int i = 0; i < TPW; ++i) fold(i, (kAhead - 1) % MB, last, done[i], done_qn[i]);
         }
     } else {
         stash(0, 0);
@@ -341,7 +358,7 @@ __global__ __launch_bounds__(kMixThreads) void mixer_td_kernel(const MixerArgs a
                 const float qn = q_lds[min(blk / MB, N - 1) * 16 + c];
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[0][ks]);
-                fold(0, blk, acc, qn);
+                fold(0, u % MB, blk, acc, qn);
                 stash((u + 1) % kAhead, blk + 1);
                 lds_barrier();
             }
@@ -402,20 +419,22 @@ __global__ __launch_bounds__(256) void mixer_loss_kernel(const float *__restrict
     }
 }
 
-template <int MB, int P, int KS, int TPW>
-hipError_t mixer_launch_tiles(const MixerArgs &a, hipStream_t stream)
+template <int MB, int P, int KS, int TPW, int W>
+hipError_t mixer_launch_shape(const MixerArgs &a, hipStream_t stream)
 {
-    const int per_group = 16 * kMixWaves * TPW;
-    const dim3 grid((unsigned)((a.rows + per_group - 1) / per_group), 2), block(kMixThreads);
-    const size_t lds = (size_t)2 * KS * P * 1024 + sizeof(float) * ((size_t)(a.N + 3) * MB * 16 + (size_t)kMixWaves * TPW * a.N * 16);
-    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KS, TPW>>(kLdsLimit);
+    const int per_group = 16 * W * TPW;
+    const dim3 grid((unsigned)((a.rows + per_group - 1) / per_group), 2), block(64 * W);
+    const size_t lds = (size_t)2 * KS * P * 1024 + sizeof(float) * ((size_t)(a.N + 3) * MB * 16 + (size_t)W * TPW * a.N * 16);
+    hipError_t err = allow_large_lds<mixer_td_kernel<MB, P, KS, TPW, W>>(kLdsLimit);
     if (err != hipSuccess) return err;
-    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KS, TPW>), grid, block, lds, stream, a);
+    hipLaunchKernelGGL((mixer_td_kernel<MB, P, KS, TPW, W>), grid, block, lds, stream, a);
     return hipGetLastError();
 }
 
-// Two tiles per wave halve the fragment traffic of a transition and the number of workgroups: taken
-// once one tile per wave would give more workgroups than there are compute units.
+// Once groups of 64 transitions would give more workgroups than there are compute units, a workgroup
+// takes 128 with eight waves: a block's fragments then come from L2 half as often, and with two waves
+// on a SIMD one's LDS reads (a wave issues a 16-byte-per-lane read only every ~29 cycles) run beside
+// the other's products.
 template <int MB, int P, int KS>
 hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
 {
@@ -423,9 +442,9 @@ hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
         int dev = 0, n_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             n_cu = 256;
-        if (2 * ((a.rows + 16 * kMixWaves - 1) / (16 * kMixWaves)) > n_cu) return mixer_launch_tiles<MB, P, KS, 2>(a, stream);
+        if (2 * ((a.rows + 63) / 64) > n_cu) return mixer_launch_shape<MB, P, KS, kBigTiles, kBigWaves>(a, stream);
     }
-    return mixer_launch_tiles<MB, P, KS, 1>(a, stream);
+    return mixer_launch_shape<MB, P, KS, 1, 4>(a, stream);
 }
 
 template <int P, int KS>
