@@ -63,73 +63,179 @@ struct MixerArgs {
     float *q_total, *y_total, *td_err;
 };
 
-// Two tiles per wave: when a block's fragments fit two register sets and the state is long enough
-// for the fragment traffic to matter.
-template <int P, int KS> constexpr bool mixer_two_tiles_fit() { return KS * P <= 16 && KS >= 8; }
+// The larger workgroup shape needs two register sets of a block's fragments, and pays off once the
+// state is long enough for the fragment traffic to matter.
+template <int P, int KS> constexpr bool mixer_big_shape_fits() { return KS * P <= 16 && KS >= 8; }
 
-// One pass of one group of 64 TPW transitions: blockIdx.y = 0 is the online mixer on the chosen
-// values and the slot's state (Q_total), 1 the target mixer on the bootstrap values and the next
-// slot's state (y_total).  td_err = filled ? y_total - Q_total : 0 is formed by both passes adding
-// their term to an array cleared beforehand: the two orders give the same bits (0 + x = x, and
-// -Q + y and y + (-Q) round alike).
-// KS: k-steps of 32 over the state (the packed fragments are zero past the state's end).
-// TPW: tiles of 16 transitions per wave; each fragment read from LDS then feeds TPW products.
-// W: wavefronts per workgroup, one (4) or two (8) per SIMD.
-template <int MB, int P, int KS, int TPW, int W>
-__global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
+// Streams blocks of 16 generated quantities past the waves of a workgroup: fragments travel
+// global -> registers -> LDS, and every wave multiplies each block with its own tiles' states.  A
+// block is asked for kAhead (+ 1) blocks before it is multiplied (an L2 round trip is several blocks
+// long) into one of kAhead register sets, indexed by block % kAhead with the loop unrolled over them
+// so that a wait covers only that set.  Blocks past the last one re-read it (their results are the
+// caller's to ignore), which keeps every step the same straight-line code with no other global load
+// in it: biases and agent values come from LDS.
+template <int P, int KS, int W>
+struct BlockStream {
+    static constexpr int kThreads = 64 * W;
+    static constexpr int kChunk = KS * P * 64;                             // 16-byte vectors of one block
+    static constexpr int kStage = (kChunk + kThreads - 1) / kThreads;      // vectors per thread and block
+    static constexpr bool kReadAhead = KS * P <= 16;                       // two register sets of a block's fragments fit
+    static constexpr size_t kLdsBytes = (size_t)2 * kChunk * 16;           // two block buffers
+    const bf16x8 *frags;
+    int n_blocks;
+    bf16x8 *buf;
+    bf16x8 stage[kAhead][kStage];
+
+    __device__ __forceinline__ void fetch_one(int set, int blk, int i)
+    {
+        const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
+        stage[set][i] = src[min(i * kThreads + (int)threadIdx.x, kChunk - 1)];
+    }
+    __device__ __forceinline__ void fetch(int set, int blk)
+    {
+#pragma unroll
+        for (int i = 0; i < kStage; ++i) fetch_one(set, blk, i);
+    }
+    __device__ __forceinline__ void stash_one(int set, int blk, int i)
+    {
+        const int at = i * kThreads + threadIdx.x;
+        if (kChunk % kThreads == 0 || at < kChunk) buf[(size_t)(blk & 1) * kChunk + at] = stage[set][i];
+    }
+    __device__ __forceinline__ void stash(int set, int blk)
+    {
+#pragma unroll
+        for (int i = 0; i < kStage; ++i) stash_one(set, blk, i);
+    }
+    // asks for the first blocks; nothing of LDS is touched yet
+    __device__ __forceinline__ void begin(const bf16x8 *blocks, int count, bf16x8 *lds_buffers)
+    {
+        frags = blocks;
+        n_blocks = count;
+        buf = lds_buffers;
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+    }
+    // Multiplies every block with the wave's TPW tiles and hands the 16 x 16 results to
+    // fold(tile, blk % MB, blk, result, agent value).  bias: the streamed blocks' bias table in LDS;
+    // qv: the wave's agent values in LDS, [tile][agent][row], n_q agents (block blk belongs to agent
+    // blk / MB; later blocks get the last agent's value, to ignore).  The workgroup must have
+    // finished with the block buffers and written bias and qv before the call (the first barrier
+    // inside orders the latter).
+    template <int MB, int TPW, typename Fold>
+    __device__ __forceinline__ void run(const Frag<P> (&st)[TPW][KS], const float *bias, const float *qv, int n_q, Fold &&fold)
+    {
+        static_assert(kAhead % MB == 0, "a block's place among its group's blocks follows from the step number");
+        const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+        if constexpr (kReadAhead) {
+            // One wave issues in order, so whatever is to run beside the products has to sit between
+            // them in the instruction stream.  A step multiplies block b from one register set while,
+            // k-step by k-step, block b + 1 is read from LDS into the other set (by the block's
+            // parity), the step's share of block b + 5 is asked for and block b + 2 is written to
+            // LDS: its buffer held block b, whose reads every wave finished before the barrier that
+            // ended the previous step.  Bias and agent value of block b + 1 are read at the head of
+            // the step.
+            static_assert(2 * kStage <= KS, "a step's loads and its LDS writes sit at different k-steps");
+            WFrag<P> w[2][KS];
+            auto read_step = [&](int set, int blk, int ks) {
+                const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
+                w[set][ks].hi = src[(ks * P) * 64];
+                if constexpr (P == 2) w[set][ks].lo = src[(ks * P + 1) * 64];
+            };
+            auto head = [&](int blk, f32x4 &bias4, float (&qn)[TPW]) {
+                bias4 = load_feature4(bias, min(blk, n_blocks - 1), q4);
+#pragma unroll
+                for (int i = 0; i < TPW; ++i) qn[i] = qv[(i * n_q + min(blk / MB, n_q - 1)) * 16 + c];
+            };
+            stash(0, 0);
+            stash(1, 1);
+            fetch(0, kAhead);
+            lds_barrier();
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) read_step(0, 0, ks);
+            f32x4 bias_next;
+            float qn_next[TPW];
+            head(0, bias_next, qn_next);
+            lds_barrier();                         // every wave holds block 0 before its buffer is written again
+            for (int base = 0; base < n_blocks; base += kAhead) {
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int blk = base + u;
+                    f32x4 acc[TPW];
+                    float qn[TPW];
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) {
+                        acc[i] = bias_next;
+                        qn[i] = qn_next[i];
+                    }
+                    head(blk + 1, bias_next, qn_next);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                        for (int i = 0; i < TPW; ++i) mma16<P>(acc[i], w[u & 1][ks], st[i][ks]);
+                        read_step((u + 1) & 1, blk + 1, ks);
+                        if (ks < kStage) fetch_one((u + 1) % kAhead, blk + kAhead + 1, ks);      // that set held block blk + 1, in LDS since the last step
+                        if (ks >= KS - kStage) stash_one((u + 2) % kAhead, blk + 2, ks - (KS - kStage));
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+#pragma unroll
+                    for (int i = 0; i < TPW; ++i) fold(i, u % MB, blk, acc[i], qn[i]);
+                    lds_barrier();
+                }
+            }
+        } else {
+            static_assert(TPW == 1, "more tiles per wave come with the read-ahead loop");
+            stash(0, 0);
+            lds_barrier();
+            for (int base = 0; base < n_blocks; base += kAhead) {
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int blk = base + u;
+                    fetch(u, blk + kAhead);                            // this set held block blk, already in LDS
+                    const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
+                    WFrag<P> w[KS];
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) {
+                        w[ks].hi = src[(ks * P) * 64];
+                        if constexpr (P == 2) w[ks].lo = src[(ks * P + 1) * 64];
+                    }
+                    f32x4 acc = load_feature4(bias, min(blk, n_blocks - 1), q4);
+                    const float qn = qv[min(blk / MB, n_q - 1) * 16 + c];
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[0][ks]);
+                    fold(0, u % MB, blk, acc, qn);
+                    stash((u + 1) % kAhead, blk + 1);
+                    lds_barrier();
+                }
+            }
+        }
+    }
+};
+
+// What a wave needs of its tiles before the blocks stream: the bias table and the tiles' agent values in
+// LDS, the tiles' states as B operands in registers; `stream.begin` is called once every load of the
+// prologue has been issued.  Everything is asked for before any of it is used, smallest first (loads
+// answer in order): a loop of load-then-store over a run-time count would pay a memory round trip per
+// iteration.  slot_shift: 0 the slot's own state, 1 the next slot's.
+template <int P, int KS, int TPW, int W>
+__device__ __forceinline__ void mixer_prologue(const float *bias_src, int F, float *bias_lds, const float *q_src, int N, float *q_lds,
+                                               const float *state, int S, int T, int rows, int slot_shift, int (&row)[TPW],
+                                               Frag<P> (&st)[TPW][KS], BlockStream<P, KS, W> &stream, const bf16x8 *blocks, int n_blocks,
+                                               bf16x8 *buf)
 {
-    constexpr int kMixWaves = W, kMixThreads = 64 * W;      // of this kernel
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    constexpr int kThreads = 64 * W, kBatch = 8;
     const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int pass = blockIdx.y;
-    const int N = a.N, S = a.S, T = a.T;
-    const int n_blocks = (N + 3) * MB, F = n_blocks * 16;
-    constexpr int kChunk = KS * P * 64;                            // 16-byte vectors of one block
-    constexpr int kStage = (kChunk + kMixThreads - 1) / kMixThreads;      // vectors per thread and block
-    constexpr bool kReadAhead = KS * P <= 16;                      // two register sets of a block's fragments fit
-    static_assert(TPW == 1 || kReadAhead, "two tiles per wave come with the read-ahead loop");
-    // LDS: two block buffers, the pass's bias table, the tiles' agent values [wave][tile][agent][row]
-    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);
-    float *const bias_lds = reinterpret_cast<float *>(lds + (size_t)2 * kChunk * 16);
-    float *const q_lds = bias_lds + F + (size_t)wave * TPW * N * 16;
-
-    const bf16x8 *frags = a.frags[pass];
-    // Fragments travel global -> registers -> LDS.  A block is asked for kAhead blocks before it
-    // is multiplied (an L2 round trip is several blocks long) into one of kAhead register sets,
-    // indexed by block % kAhead with the loop unrolled over them so that a wait covers only that
-    // set.  Blocks past the last one re-read it and contribute nothing, which keeps every step the
-    // same straight-line code with no other global access in it (biases and agent values come
-    // from LDS).
-    bf16x8 stage[kAhead][kStage];
-    auto fetch = [&](int set, int blk) {       // the block's fragments, this thread's share
-        const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
-#pragma unroll
-        for (int i = 0; i < kStage; ++i) stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
-    };
-    auto stash = [&](int set, int blk) {
-        bf16x8 *dst = buf + (size_t)(blk & 1) * kChunk;
-#pragma unroll
-        for (int i = 0; i < kStage; ++i) {
-            const int at = i * kMixThreads + threadIdx.x;
-            if (at < kChunk) dst[at] = stage[set][i];
-        }
-    };
-    // Everything the prologue reads is asked for before any of it is used, smallest first (loads
-    // answer in order): a loop of load-then-store over a run-time count would pay a memory round
-    // trip per iteration.
-    constexpr int kBatch = 8;
-    const float c2 = a.c2[pass][0];
     {
-        const f32x4 *src = reinterpret_cast<const f32x4 *>(a.bias[pass]);      // F is a multiple of 16, the table 16-byte aligned
+        const f32x4 *src = reinterpret_cast<const f32x4 *>(bias_src);          // F is a multiple of 16, the table 16-byte aligned
         f32x4 *dst = reinterpret_cast<f32x4 *>(bias_lds);
-        for (int i0 = threadIdx.x; i0 < F / 4; i0 += 4 * kMixThreads) {
+        for (int i0 = threadIdx.x; i0 < F / 4; i0 += 4 * kThreads) {
             f32x4 v[4];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = src[min(i0 + e * kMixThreads, F / 4 - 1)];
+            for (int e = 0; e < 4; ++e) v[e] = src[min(i0 + e * kThreads, F / 4 - 1)];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (i0 + e * kMixThreads < F / 4) dst[i0 + e * kMixThreads] = v[e];
+                if (i0 + e * kThreads < F / 4) dst[i0 + e * kThreads] = v[e];
         }
     }
     // The tiles' states as B operands: lane (row c, quarter q) holds values 32 ks + 8 q + 0..7.
@@ -137,21 +243,19 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
     // partial one is read element by element from positions clamped into the row and zeroed past
     // its end.  Rows past the end re-read the last one.
     const int nfull = S / 32;
-    Frag<P> st[TPW][KS];
-    int row[TPW];
     const float *srow[TPW];
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
-        const int tile_row0 = ((blockIdx.x * kMixWaves + wave) * TPW + i) * 16;
+        const int tile_row0 = ((blockIdx.x * W + wave) * TPW + i) * 16;
         row[i] = tile_row0 + c;
-        const int rr = min(row[i], a.rows - 1);
-        srow[i] = a.state + ((size_t)(rr / T) * (T + 1) + rr % T + pass) * S;
+        const int rr = min(row[i], rows - 1);
+        srow[i] = state + ((size_t)(rr / T) * (T + 1) + rr % T + slot_shift) * S;
         for (int k0 = lane; k0 < 16 * N; k0 += 64 * kBatch) {      // the tile's agent values: its rows are consecutive in memory
             float v[kBatch];
 #pragma unroll
             for (int e = 0; e < kBatch; ++e) {
                 const int k = min(k0 + 64 * e, 16 * N - 1);
-                v[e] = a.q[pass][(size_t)min(tile_row0 + k / N, a.rows - 1) * N + k % N];
+                v[e] = q_src[(size_t)min(tile_row0 + k / N, rows - 1) * N + k % N];
             }
 #pragma unroll
             for (int e = 0; e < kBatch; ++e) {
@@ -169,8 +273,7 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
                 __builtin_memcpy(&raw[i][ks][0], srow[i] + 32 * ks + 8 * q4, 16);
                 __builtin_memcpy(&raw[i][ks][1], srow[i] + 32 * ks + 8 * q4 + 4, 16);
             }
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+        stream.begin(blocks, n_blocks, buf);
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
@@ -181,8 +284,7 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
                 st[i][ks] = to_frag<P>(v);
             }
     } else {
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) fetch(u, u);
+        stream.begin(blocks, n_blocks, buf);
 #pragma unroll
         for (int i = 0; i < TPW; ++i)
 #pragma unroll
@@ -205,6 +307,37 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
                 st[i][ks] = to_frag<P>(v);
             }
     }
+}
+
+// One pass of one group of 16 W TPW transitions: blockIdx.y = 0 is the online mixer on the chosen
+// values and the slot's state (Q_total), 1 the target mixer on the bootstrap values and the next
+// slot's state (y_total).  td_err = filled ? y_total - Q_total : 0 is formed by both passes adding
+// their term to an array cleared beforehand: the two orders give the same bits (0 + x = x, and
+// -Q + y and y + (-Q) round alike).
+// KS: k-steps of 32 over the state (the packed fragments are zero past the state's end).
+// TPW: tiles of 16 transitions per wave; each fragment read from LDS then feeds TPW products.
+// W: wavefronts per workgroup, one (4) or two (8) per SIMD.
+template <int MB, int P, int KS, int TPW, int W>
+__global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int lane = threadIdx.x & 63, q4 = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int pass = blockIdx.y;
+    const int N = a.N;
+    const int n_blocks = (N + 3) * MB, F = n_blocks * 16;
+    using Stream = BlockStream<P, KS, W>;
+    // LDS: two block buffers, the pass's bias table, the tiles' agent values [wave][tile][agent][row]
+    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);
+    float *const bias_lds = reinterpret_cast<float *>(lds + Stream::kLdsBytes);
+    float *const q_lds = bias_lds + F + (size_t)wave * TPW * N * 16;
+
+    Stream stream;
+    const float c2 = a.c2[pass][0];
+    Frag<P> st[TPW][KS];
+    int row[TPW];
+    mixer_prologue<P, KS, TPW, W>(a.bias[pass], F, bias_lds, a.q[pass], N, q_lds, a.state, a.S, a.T, a.rows, pass, row, st, stream,
+                                  a.frags[pass], n_blocks, buf);
     f32x4 gain[MB];                            // v2, this lane's units
 #pragma unroll
     for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2[pass], j, q4);
@@ -228,13 +361,10 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
 #pragma unroll
             for (int r = 0; r < 4; ++r) hidden[i][j][r] = 0.0f;
     }
-    // A block's 16 x 16 result of tile i, folded into the tile's running mix.  j = blk % MB, given by the
-    // caller from the unrolled step number (kAhead is a multiple of MB), so that the registers it
-    // touches are known when compiling.  Agent and b1 blocks take the same straight-line code with two
-    // coefficients (q[n], 0) or (0, 1): a product with zero adds nothing and a product with one is
-    // exact, so the sums are the ones of `hidden += q[n] |result|` and `hidden += result`.  Only the
-    // last blocks branch (uniformly, around arithmetic alone).
-    static_assert(kAhead % MB == 0, "a block's place among its group's blocks follows from the step number");
+    // A block's 16 x 16 result of tile i, folded into the tile's running mix.  Agent and b1 blocks take
+    // the same straight-line code with two coefficients (q[n], 0) or (0, 1): a product with zero adds
+    // nothing and a product with one is exact, so the sums are the ones of `hidden += q[n] |result|`
+    // and `hidden += result`.  Only the last blocks branch (uniformly, around arithmetic alone).
     auto fold = [&](int i, int j, int blk, const f32x4 &acc, float qn) {
         const int group = blk / MB;                                // agents 0 .. N-1, then b1, w2, offset
         const float by_abs = group < N ? qn : 0.0f, by_value = group == N ? 1.0f : 0.0f;
@@ -251,119 +381,7 @@ __global__ __launch_bounds__(64 * W) void mixer_td_kernel(const MixerArgs a)
             for (int r = 0; r < 4; ++r) total[i] = fmaf(gain[j][r], fmaxf(acc[r], 0.0f), total[i]);
         }
     };
-    if constexpr (kReadAhead) {
-        // One wave per SIMD issues in order, so whatever is to run beside the products has to sit
-        // between them in the instruction stream.  A step multiplies block b from one register set
-        // while, k-step by k-step, block b + 1 is read from LDS into the other set (by the block's
-        // parity), the step's share of block b + 5 is asked for and block b + 2 is written to LDS:
-        // its buffer held block b, whose reads every wave finished before the barrier that ended
-        // the previous step.  Bias and agent value of block b + 1 are read at the head of the step.
-        WFrag<P> w[2][KS];
-        auto read_step = [&](int set, int blk, int ks) {
-            const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
-            w[set][ks].hi = src[(ks * P) * 64];
-            if constexpr (P == 2) w[set][ks].lo = src[(ks * P + 1) * 64];
-        };
-        auto fetch_one = [&](int set, int blk, int i) {
-            const bf16x8 *src = frags + (size_t)min(blk, n_blocks - 1) * kChunk;
-            stage[set][i] = src[min(i * kMixThreads + (int)threadIdx.x, kChunk - 1)];
-        };
-        auto stash_one = [&](int set, int blk, int i) {
-            const int at = i * kMixThreads + threadIdx.x;
-            if (kChunk % kMixThreads == 0 || at < kChunk) buf[(size_t)(blk & 1) * kChunk + at] = stage[set][i];
-        };
-        auto head = [&](int blk, f32x4 &bias4, float (&qn)[TPW]) {
-            bias4 = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) qn[i] = q_lds[(i * N + min(blk / MB, N - 1)) * 16 + c];
-        };
-        static_assert(2 * kStage <= KS, "a step's loads and its LDS writes sit at different k-steps");
-        stash(0, 0);
-        stash(1, 1);
-        fetch(0, kAhead);
-        lds_barrier();
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) read_step(0, 0, ks);
-        f32x4 bias_next;
-        float qn_next[TPW];
-        head(0, bias_next, qn_next);
-        lds_barrier();                         // every wave holds block 0 before its buffer is written again
-        // A block's result is folded in the middle of the next step, between that step's products:
-        // at the end of its own step the wave would wait for the last product, fold, and only then
-        // reach the barrier.
-        f32x4 done[TPW];
-        float done_qn[TPW];
-#pragma unroll
-        for (int i = 0; i < TPW; ++i) {
-            done_qn[i] = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) done[i][r] = 0.0f;         // "block -1": adds nothing
-        }
-        for (int base = 0; base < n_blocks; base += kAhead) {
-#pragma unroll
-            for (int u = 0; u < kAhead; ++u) {
-                const int blk = base + u;
-                f32x4 acc[TPW];
-                float qn[TPW];
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    acc[i] = bias_next;
-                    qn[i] = qn_next[i];
-                }
-                head(blk + 1, bias_next, qn_next);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-#pragma unroll
-                    for (int i = 0; i < TPW; ++i) mma16<P>(acc[i], w[u & 1][ks], st[i][ks]);
-                    read_step((u + 1) & 1, blk + 1, ks);
-                    if (ks < kStage) fetch_one((u + 1) % kAhead, blk + kAhead + 1, ks);      // that set held block blk + 1, in LDS since the last step
-                    if (ks >= KS - kStage) stash_one((u + 2) % kAhead, blk + 2, ks - (KS - kStage));
-                    if (ks == KS / 2) {
-#pragma unroll
-                        for (int i = 0; i < TPW; ++i) fold(i, (u + kAhead - 1) % MB, max(blk - 1, 0), done[i], done_qn[i]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#pragma unroll
-                for (int i = 0; i < TPW; ++i) {
-                    done[i] = acc[i];
-                    done_qn[i] = qn[i];
-                }
-                lds_barrier();
-            }
-        }
-        {
-            // the last step's block: the loop runs whole rounds of kAhead steps
-            const int last = (n_blocks + kAhead - 1) / kAhead * kAhead - 1;
-#pragma unroll
-            for (int i = 0; i < TPW; ++i) fold(i, (kAhead - 1) % MB, last, done[i], done_qn[i]);
-        }
-    } else {
-        stash(0, 0);
-        lds_barrier();
-        for (int base = 0; base < n_blocks; base += kAhead) {
-#pragma unroll
-            for (int u = 0; u < kAhead; ++u) {
-                const int blk = base + u;
-                fetch(u, blk + kAhead);                            // this set held block blk, already in LDS
-                const bf16x8 *src = buf + (size_t)(blk & 1) * kChunk + lane;
-                WFrag<P> w[KS];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    w[ks].hi = src[(ks * P) * 64];
-                    if constexpr (P == 2) w[ks].lo = src[(ks * P + 1) * 64];
-                }
-                f32x4 acc = load_feature4(bias_lds, min(blk, n_blocks - 1), q4);
-                const float qn = q_lds[min(blk / MB, N - 1) * 16 + c];
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) mma16<P>(acc, w[ks], st[0][ks]);
-                fold(0, u % MB, blk, acc, qn);
-                stash((u + 1) % kAhead, blk + 1);
-                lds_barrier();
-            }
-        }
-    }
+    stream.template run<MB, TPW>(st, bias_lds, q_lds, N, fold);
 #pragma unroll
     for (int i = 0; i < TPW; ++i) {
         float sum = total[i];
@@ -438,7 +456,7 @@ hipError_t mixer_launch_shape(const MixerArgs &a, hipStream_t stream)
 template <int MB, int P, int KS>
 hipError_t mixer_launch(const MixerArgs &a, hipStream_t stream)
 {
-    if constexpr (mixer_two_tiles_fit<P, KS>()) {
+    if constexpr (mixer_big_shape_fits<P, KS>()) {
         int dev = 0, n_cu = 0;
         if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
             n_cu = 256;
@@ -705,99 +723,147 @@ struct MixerBackArgs {
     float *grad_q;      // [rows, N]
 };
 
-constexpr int kMixBackGenMax = 1536;       // generated quantities per transition whose values fit LDS
-
-// KS: k-steps of 32 over the state, a template parameter so that a block's fragment loads are all issued
-// before its first product (a loop over a run-time count would take them from L2 one round trip at a time).
-template <int P, int KS>
-__global__ __launch_bounds__(256) void mixer_back_kernel(const MixerBackArgs a)
+// The adjoints are computed as the forward pass computes the mix: a workgroup of W waves takes 16 W
+// transitions, the fragments stream past through LDS (BlockStream) and nothing but a tile's states, its
+// hidden units and their adjoints is kept, in registers.  The blocks stream three times:
+//   agents and b1         hidden pre-activation of every unit (as the forward pass)
+//   w2 and offset         with the hidden units known: adjoints of the hidden pre-activations, of the w2 and
+//                         offset quantities, and the columns for v2 and c2
+//   agents again          each quantity once more, to give its adjoint (sign, agent value, adjoint of its
+//                         unit) and its share of dL/dq
+// so L2 serves every block three times per 16 W transitions instead of once per 16, and no generated
+// quantity is stored.  Every store goes through a buffer descriptor, rows past the end and padding blocks
+// at an offset the hardware drops, so the streaming steps stay straight-line code.
+template <int MB, int P, int KS, int W>
+__global__ __launch_bounds__(64 * W) void mixer_back_stream_kernel(const MixerBackArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) char lds[];
-    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int lane = threadIdx.x & 63, q4 = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int N = a.N, M = a.M, S = a.S, T = a.T, F = a.F;
-    const int row0 = blockIdx.x * 16;
-    // LDS: the tile's states as operand fragments [KS][P][64], every generated quantity [16][F + 4], the
-    // tile's agent values [16][N], adjoints of the hidden units [16][M], and e [16]
-    typedef bf16x8 (*FragBuf)[P][64];
-    const FragBuf stf = reinterpret_cast<FragBuf>(lds);
-    const int gp = F + 4;
-    float *const gen = reinterpret_cast<float *>(lds + (size_t)KS * P * 1024);
-    float *const q_lds = gen + 16 * gp;
-    float *const dpre = q_lds + 16 * N;
-    float *const e_lds = dpre + 16 * M;
+    const int N = a.N, M = a.M, F = a.F;
+    using Stream = BlockStream<P, KS, W>;
+    bf16x8 *const buf = reinterpret_cast<bf16x8 *>(lds);
+    float *const bias_lds = reinterpret_cast<float *>(lds + Stream::kLdsBytes);
+    float *const q_lds = bias_lds + F + (size_t)wave * N * 16;
 
-    // states: lane (row c, quarter q4) holds values 32 ks + 8 q4 + 0..7 of its transition's state; zero past S
-    {
-        const int row = min(row0 + c, a.rows - 1);
-        const float *srow = a.state + ((size_t)(row / T) * (T + 1) + row % T) * S;
-        for (int ks = wave; ks < KS; ks += 4) {
-            float v[8];
+    Stream stream;
+    Frag<P> st[1][KS];
+    int row[1];
+    mixer_prologue<P, KS, 1, W>(a.bias, F, bias_lds, a.q, N, q_lds, a.state, a.S, a.T, a.rows, 0, row, st, stream, a.frags,
+                                (N + 1) * MB, buf);
+    const bool valid = row[0] < a.rows;
+    const float e = a.e[min(row[0], a.rows - 1)];
+    f32x4 gain[MB];                            // v2, this lane's units
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int k = 32 * ks + 8 * q4 + i;
-                v[i] = k < S ? srow[k] : 0.0f;
+    for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2, j, q4);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    constexpr uint32_t kDrop = 0xFFFFFFF0u;
+    const __amdgpu_buffer_rsrc_t dgen_buf = __builtin_amdgcn_make_buffer_rsrc(a.dgen, 0, (int)((uint32_t)a.rows * (uint32_t)a.ldd * 4u), kRawBuffer);
+    const __amdgpu_buffer_rsrc_t gq_buf = __builtin_amdgcn_make_buffer_rsrc(a.grad_q, 0, (int)((uint32_t)a.rows * (uint32_t)N * 4u), kRawBuffer);
+    uint32_t drop = valid ? 0u : kDrop;
+    asm volatile("" : "+v"(drop));
+    const uint32_t row_at = (uint32_t)min(row[0], a.rows - 1) * (uint32_t)a.ldd;       // first element of the row in dgen
+    auto store4 = [&](const f32x4 &v, uint32_t column, uint32_t drop_mask) {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dgen_buf, ((row_at + column) * 4u) | drop_mask, 0, 0);
+    };
+
+    // 1. hidden pre-activations
+    f32x4 hidden[MB];
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) hidden[j][r] = 0.0f;
+    stream.template run<MB, 1>(st, bias_lds, q_lds, N, [&](int, int j, int blk, const f32x4 &acc, float qn) {
+        const int group = blk / MB;
+        const float by_abs = group < N ? qn : 0.0f, by_value = group == N ? 1.0f : 0.0f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) hidden[j][r] = fmaf(by_value, acc[r], fmaf(by_abs, fabsf(acc[r]), hidden[j][r]));
+    });
+
+    // 2. the w2 and offset blocks
+    f32x4 dpre[MB];                            // adjoints of the hidden pre-activations, this lane's units
+#pragma unroll
+    for (int j = 0; j < MB; ++j)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dpre[j][r] = 0.0f;
+    lds_barrier();                             // every wave has finished with the block buffers
+    stream.begin(a.frags + (size_t)(N + 1) * MB * Stream::kChunk, 2 * MB, buf);
+    stream.template run<MB, 1>(st, bias_lds + (N + 1) * MB * 16, q_lds, N, [&](int, int j, int blk, const f32x4 &acc, float) {
+        const int kind = blk / MB;             // 0: w2, 1: offset, beyond: padding of the last round of steps
+        f32x4 first, second;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float pre = hidden[j][r], x = acc[r];
+            const float hid = pre > 0.0f ? pre : expm1f(pre);
+            const float d_pre = e * fabsf(x) * (pre > 0.0f ? 1.0f : expf(pre));
+            const float d_gen2 = e * hid * (x > 0.0f ? 1.0f : x < 0.0f ? -1.0f : 0.0f);
+            const float d_off = x > 0.0f ? e * gain[j][r] : 0.0f;
+            first[r] = kind == 0 ? d_gen2 : d_off;
+            second[r] = kind == 0 ? d_pre : e * fmaxf(x, 0.0f);
+            dpre[j][r] = kind == 0 ? d_pre : dpre[j][r];
+        }
+        const uint32_t unit = 16 * j + 4 * q4, keep = kind < 2 ? drop : kDrop;
+        store4(first, (kind == 0 ? (N + 1) * M : (N + 2) * M) + unit, keep);
+        store4(second, (kind == 0 ? N * M : F) + unit, keep);
+    });
+    if (q4 == 0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, e), dgen_buf, ((row_at + F + M) * 4u) | drop, 0, 0);
+
+    // 3. the agents' blocks again
+    lds_barrier();
+    stream.begin(a.frags, N * MB, buf);
+    float share = 0.0f;                        // of dL/dq[n]: over this lane's units
+    const uint32_t gq_row = (uint32_t)min(row[0], a.rows - 1) * (uint32_t)N;
+    stream.template run<MB, 1>(st, bias_lds, q_lds, N, [&](int, int j, int blk, const f32x4 &acc, float qn) {
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float x = acc[r];
+            v[r] = dpre[j][r] * qn * (x > 0.0f ? 1.0f : x < 0.0f ? -1.0f : 0.0f);
+            share = fmaf(dpre[j][r], fabsf(x), share);
+        }
+        const uint32_t keep = blk < N * MB ? drop : kDrop;
+        store4(v, 16 * blk + 4 * q4, keep);
+        if (j == MB - 1) {                     // the agent's last block: its row sum is complete
+            float sum = share;
+            sum += __shfl_xor(sum, 16);
+            sum += __shfl_xor(sum, 32);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, sum), gq_buf,
+                                                  ((gq_row + (uint32_t)(blk / MB)) * 4u) | (q4 == 0 ? keep : kDrop), 0, 0);
+            share = 0.0f;
+        }
+    });
+}
+
+template <int MB, int P, int KS, int W>
+hipError_t mixer_back_stream_launch(const MixerBackArgs &a, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((a.rows + 16 * W - 1) / (16 * W))), block(64 * W);
+    const size_t lds = BlockStream<P, KS, W>::kLdsBytes + sizeof(float) * ((size_t)a.F + (size_t)W * a.N * 16);
+    hipError_t err = allow_large_lds<mixer_back_stream_kernel<MB, P, KS, W>>(kLdsLimit);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL((mixer_back_stream_kernel<MB, P, KS, W>), grid, block, lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int P, int KS>
+hipError_t mixer_back_stream_dispatch(int mb, const MixerBackArgs &a, hipStream_t stream)
+{
+    const bool big = mixer_big_shape_fits<P, KS>() && a.rows >= 8192;
+    if constexpr (mixer_big_shape_fits<P, KS>()) {
+        if (big) {
+            switch (mb) {
+            case 1: return mixer_back_stream_launch<1, P, KS, 8>(a, stream);
+            case 2: return mixer_back_stream_launch<2, P, KS, 8>(a, stream);
+            case 4: return mixer_back_stream_launch<4, P, KS, 8>(a, stream);
+            default: return hipErrorInvalidValue;
             }
-            const Frag<P> f = to_frag<P>(v);
-            stf[ks][0][lane] = f.hi;
-            if constexpr (P == 2) stf[ks][1][lane] = f.lo;
-        }
-        for (int i = threadIdx.x; i < 16 * N; i += 256) q_lds[i] = a.q[(size_t)min(row0 + i / N, a.rows - 1) * N + i % N];
-        if (threadIdx.x < 16) e_lds[threadIdx.x] = row0 + (int)threadIdx.x < a.rows ? a.e[row0 + threadIdx.x] : 0.0f;
-    }
-    __syncthreads();
-    // generated quantities: block fb of 16, lane (transition c, quantities 16 fb + 4 q4 + 0..3)
-    for (int fb = wave; fb < F / 16; fb += 4) {
-        f32x4 acc = load_feature4(a.bias, fb, q4);
-        const bf16x8 *blk = a.frags + (size_t)fb * KS * P * 64 + lane;
-        WFrag<P> wf[KS];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) wf[ks] = load_wfrag<P>(blk + (size_t)ks * P * 64);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            Frag<P> st;
-            st.hi = stf[ks][0][lane];
-            if constexpr (P == 2) st.lo = stf[ks][1][lane];
-            mma16<P>(acc, wf[ks], st);
-        }
-        *reinterpret_cast<f32x4 *>(gen + c * gp + 16 * fb + 4 * q4) = acc;
-    }
-    __syncthreads();
-    // per (transition, hidden unit): the mix forward, then the adjoints that do not depend on the agent
-    for (int idx = threadIdx.x; idx < 16 * M; idx += 256) {
-        const int tr = idx / M, m = idx % M;
-        const float *g = gen + tr * gp;
-        float pre = g[N * M + m];
-        for (int n = 0; n < N; ++n) pre += q_lds[tr * N + n] * fabsf(g[n * M + m]);
-        const float hid = pre > 0.0f ? pre : expm1f(pre);
-        const float gen2 = g[(N + 1) * M + m], off = g[(N + 2) * M + m];
-        const float e = e_lds[tr];
-        const float d_pre = e * fabsf(gen2) * (pre > 0.0f ? 1.0f : expf(pre));
-        const float d_gen2 = e * hid * (gen2 > 0.0f ? 1.0f : gen2 < 0.0f ? -1.0f : 0.0f);
-        const float d_off = off > 0.0f ? e * a.v2[m] : 0.0f;
-        dpre[tr * M + m] = d_pre;
-        if (row0 + tr < a.rows) {
-            float *d = a.dgen + (size_t)(row0 + tr) * a.ldd;
-            d[N * M + m] = d_pre;
-            d[(N + 1) * M + m] = d_gen2;
-            d[(N + 2) * M + m] = d_off;
-            d[F + m] = e * fmaxf(off, 0.0f);
-            if (m == 0) d[F + M] = e;
         }
     }
-    __syncthreads();
-    // adjoints of the per-agent weights, and what flows on to the agents' values
-    for (int idx = threadIdx.x; idx < 16 * N * M; idx += 256) {
-        const int tr = idx / (N * M), f = idx % (N * M);
-        const float g1 = gen[tr * gp + f];
-        const float v = dpre[tr * M + f % M] * q_lds[tr * N + f / M] * (g1 > 0.0f ? 1.0f : g1 < 0.0f ? -1.0f : 0.0f);
-        if (row0 + tr < a.rows) a.dgen[(size_t)(row0 + tr) * a.ldd + f] = v;
-    }
-    for (int idx = threadIdx.x; idx < 16 * N; idx += 256) {
-        const int tr = idx / N, n = idx % N;
-        float s = 0.0f;
-        for (int m = 0; m < M; ++m) s += dpre[tr * M + m] * fabsf(gen[tr * gp + n * M + m]);
-        if (row0 + tr < a.rows) a.grad_q[(size_t)(row0 + tr) * N + n] = s;
+    switch (mb) {
+    case 1: return mixer_back_stream_launch<1, P, KS, 4>(a, stream);
+    case 2: return mixer_back_stream_launch<2, P, KS, 4>(a, stream);
+    case 4: return mixer_back_stream_launch<4, P, KS, 4>(a, stream);
+    default: return hipErrorInvalidValue;
     }
 }
 
@@ -824,12 +890,6 @@ MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
     return p;
 }
 
-size_t mixer_back_lds(const marl_mixer *m)
-{
-    const int F = (m->desc.n_agents + 3) * m->desc.embed;
-    return (size_t)m->ks * m->planes * 1024 + sizeof(float) * (16 * (F + 4) + 16 * m->desc.n_agents + 16 * m->desc.embed + 16);
-}
-
 }  // namespace
 }  // namespace marl
 
@@ -840,7 +900,6 @@ int marl_mixer_grad_workspace_bytes(const marl_mixer *m, int32_t B, int32_t T, s
     if (!m || !bytes) return MARL_ERR_NULL;
     const int F = (m->desc.n_agents + 3) * m->desc.embed;
     if (B < 1 || T < 1 || (int64_t)B * T * (F + m->desc.embed + 4) >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
-    if (F > marl::kMixBackGenMax || marl::mixer_back_lds(m) > (size_t)marl::kLdsLimit) return MARL_ERR_BAD_DIM;
     *bytes = marl::mixer_grad_plan(m->desc, B, T).bytes;
     return MARL_OK;
 }
@@ -869,27 +928,25 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     a.frags = m->frags; a.bias = m->bias; a.v2 = m->v2;
     a.N = N; a.M = M; a.S = S; a.ks = m->ks; a.rows = (int)R; a.T = T; a.F = F; a.ldd = plan.ldd;
     a.state = state; a.q = q_taken; a.e = grad_q_total; a.dgen = dgen; a.grad_q = grad_q_taken;
-    const size_t lds = marl::mixer_back_lds(m);
     hipError_t err = hipErrorInvalidValue;
-    const dim3 grid((unsigned)((R + 15) / 16));
-#define MARL_MIXBACK(PL, KSTEPS)                                                                          \
-    do {                                                                                                  \
-        err = marl::allow_large_lds<marl::mixer_back_kernel<PL, KSTEPS>>(marl::kLdsLimit);                \
-        if (err == hipSuccess) hipLaunchKernelGGL((marl::mixer_back_kernel<PL, KSTEPS>), grid, dim3(256), lds, stream, a); \
-    } while (0)
+    const int mb = M / 16;
 #define MARL_MIXBACK_KS(PL)                                                                               \
     switch (m->ks) {                                                                                      \
-    case 2: MARL_MIXBACK(PL, 2); break;                                                                   \
-    case 4: MARL_MIXBACK(PL, 4); break;                                                                   \
-    case 6: MARL_MIXBACK(PL, 6); break;                                                                   \
-    case 8: MARL_MIXBACK(PL, 8); break;                                                                   \
-    case 16: MARL_MIXBACK(PL, 16); break;                                                                 \
-    case 32: MARL_MIXBACK(PL, 32); break;                                                                 \
+    case 2: err = marl::mixer_back_stream_dispatch<PL, 2>(mb, a, stream); break;                          \
+    case 4: err = marl::mixer_back_stream_dispatch<PL, 4>(mb, a, stream); break;                          \
+    case 6: err = marl::mixer_back_stream_dispatch<PL, 6>(mb, a, stream); break;                          \
+    case 8: err = marl::mixer_back_stream_dispatch<PL, 8>(mb, a, stream); break;                          \
+    case 16: err = marl::mixer_back_stream_dispatch<PL, 16>(mb, a, stream); break;                        \
     default: break;                                                                                       \
     }
-    if (m->planes == 2) { MARL_MIXBACK_KS(2); } else { MARL_MIXBACK_KS(1); }
+    if (m->planes == 2) {
+        MARL_MIXBACK_KS(2);
+    } else if (m->ks == 32) {
+        err = marl::mixer_back_stream_dispatch<1, 32>(mb, a, stream);
+    } else {
+        MARL_MIXBACK_KS(1);
+    }
 #undef MARL_MIXBACK_KS
-#undef MARL_MIXBACK
     if (err == hipSuccess) err = hipGetLastError();
     if (err != hipSuccess) return marl::report_device_error(err, "marl_mixer_grad launch");
 

@@ -120,6 +120,8 @@ SHAPES = [
     (4, 32, 512, "fp32", 2, 9),          # the largest fp32 state
     (4, 16, 1024, "bf16", 2, 9),         # the largest bf16 state
     (7, 64, 257, "bf16", 5, 27),
+    (3, 32, 256, "fp32", 129, 64),       # 8256 transitions of two-plane operands: workgroups of eight waves, the last one ragged
+    (6, 16, 300, "bf16", 70, 120),       # the same with one plane and a padded state
 ]
 
 
@@ -240,10 +242,42 @@ def test_mixer_gradient_matches_the_oracle(ci, B, T, dtype):
     cfg = dict(wl.config(ci), dtype=dtype)
     dims = wl.mixer_dims(cfg)
     w = wl.make_mixer_weights(cfg)
-    mixer = binding.Mixer(dims, w, dtype)
     m = wl.make_mixer_inputs(cfg, B=B, T=T)
     # dL/dQ_total as the loss hands it over: zero on padding transitions (whose state rows are all zero)
     e = np.random.default_rng(ci).normal(size=(B, T)).astype(np.float32) * m["filled"]
+    _compare_mixer_gradient(cfg["name"], dims, w, dtype, m, e)
+
+
+GRAD_SHAPES = [
+    # N, M, S, dtype, B, T
+    (1, 16, 1, "fp32", 1, 1),            # the smallest of everything: one transition
+    (5, 64, 33, "fp32", 13, 5),          # one value past a k-step, 65 transitions: one past a workgroup of four waves
+    (40, 64, 40, "bf16", 3, 30),         # 2752 generated quantities per transition
+    (64, 16, 98, "fp32", 2, 40),         # the most agents
+    (4, 32, 512, "fp32", 2, 9),          # the largest fp32 state: fragments of a block read as they are used
+    (4, 16, 1024, "bf16", 2, 9),         # the largest bf16 state
+    (6, 32, 300, "bf16", 70, 120),       # 8400 transitions: workgroups of eight waves, the last one ragged
+    (3, 32, 256, "fp32", 129, 64),       # the same with two-plane operands, 8256 transitions
+]
+
+
+@pytest.mark.parametrize("shape", GRAD_SHAPES, ids=lambda s: "N%d_M%d_S%d_%s_B%d_T%d" % s)
+def test_mixer_gradient_shapes_at_the_edges(shape):
+    """The same comparison on shapes chosen for the kernel's own limits and workgroup shapes."""
+    N, M, S, dtype, B, T = shape
+    cfg = dict(wl.config(0), N=N, S=S, B=B, T=T)
+    dims = (N, M, S)
+    w = wl.pack_mixer(dims, {k: np.random.default_rng([11, i]).uniform(-1, 1, shp) / np.sqrt(max(shp[-1], 1) if len(shp) == 2 else 4)
+                             for i, (k, (_, _, shp)) in enumerate(wl.mixer_slices(*dims).items())})
+    m = wl.make_mixer_inputs(cfg)
+    # an upstream gradient of one sign: the sums then grow with the number of transitions as the switches'
+    # ambiguity budget does, and the budget stays a small share of them on the large batches too
+    e = np.abs(np.random.default_rng([12, N, S]).normal(size=(B, T))).astype(np.float32) * m["filled"]
+    _compare_mixer_gradient("N%d M%d S%d" % dims, dims, w, dtype, m, e)
+
+
+def _compare_mixer_gradient(label, dims, w, dtype, m, e):
+    mixer = binding.Mixer(dims, w, dtype)
     got_q, got_w = _gpu_mixer_grad(mixer, dims, m, e)
     w_ref = w
     if dtype == "bf16":
@@ -270,7 +304,7 @@ def test_mixer_gradient_matches_the_oracle(ci, B, T, dtype):
         assert amb[a:b].max() <= BUDGET_CAP * max(scale, 1e-30), (name, amb[a:b].max() / max(scale, 1e-30))
         if (diff - (rel * scale + 1e-6 + amb[a:b])).max() > 0:
             bad.append((name, worst[name], amb[a:b].max() / max(scale, 1e-30)))
-    print(cfg["name"], dtype, {k: f"{v:.1e}" for k, v in worst.items()})
+    print(label, dtype, {k: f"{v:.1e}" for k, v in worst.items()})
     assert not bad, bad
     again_q, again_w = _gpu_mixer_grad(mixer, dims, m, e)
     np.testing.assert_array_equal(again_w, got_w)
