@@ -376,7 +376,17 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     // loop addresses statically.  Every load is unconditional (rows past the end of the arrays repeat the last
     // row, columns past an operand's width repeat its first), so the loop is straight-line code.
     constexpr int kDepth = 2;
-    float rv[kDepth][kSetsPerWave][8];
+    // bf16 adjoints (ABF) are not fetched column by column like the rest: a thread takes 16 bytes, eight columns
+    // of one sample, and the tile goes to LDS as it lies in memory, sample-major; the transposition into
+    // fragments (eight samples of one column per lane) is left to the transposing LDS read.  kAVec such loads
+    // per thread cover the step's 32 samples of kPp columns.
+    constexpr int kAVec = ABF ? 32 * kPp * 2 / 16 / kTnThreads : 0;
+    constexpr int kAChunks = kPp / 8;                              // 16-byte pieces of a staged row of A
+    constexpr int kAPitch = kPp * 2 + 32;                          // bytes from a sample's row to the next in LDS
+    static_assert(!ABF || (32 * kPp * 2) % (16 * kTnThreads) == 0, "whole loads per thread");
+    static_assert(32 * kAPitch <= kPp * kPitch, "the sample-major tile fits where A's columns would lie");
+    struct Staged { float col[kSetsPerWave][8]; uint4 a[kAVec > 0 ? kAVec : 1]; };
+    Staged rv[kDepth];
     // kPp is a multiple of 128, so set i of either half of the waves is one of A's exactly for i < kPp / 128:
     // known at compile time, and with it the element type, so that a load is one instruction with no branch
     constexpr int kSetsOfA = kPp / 128;
@@ -407,6 +417,23 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     int sample = wave_begin;                                          // first sample of the step being staged
     unsigned agent0 = (unsigned)wave_begin % (unsigned)g.N;          // its agent, where rows are (.., agent) samples
     const unsigned agent_step = 8u % (unsigned)g.N;
+    // wide loads of A: load i of this thread is piece a_piece of row a_k (sample 8 (a_k / 8) + a_k % 8 of the step:
+    // the a_k % 8-th of quarter a_k / 8), at a_at bytes from A's base; every step moves eight rows on
+    // (a_fetch: the sample the next load takes, a_staged: the one the next deposit puts down, a_end: the end of
+    // the quarter's share)
+    long a_at[kAVec > 0 ? kAVec : 1];
+    int a_fetch[kAVec > 0 ? kAVec : 1], a_staged[kAVec > 0 ? kAVec : 1], a_end[kAVec > 0 ? kAVec : 1], a_lds[kAVec > 0 ? kAVec : 1];
+    if constexpr (ABF) {
+#pragma unroll
+        for (int i = 0; i < kAVec; ++i) {
+            const int v = (int)threadIdx.x + kTnThreads * i, k = v / kAChunks, piece = v % kAChunks;
+            const int quarter_begin = m_begin + 8 * n_steps * (k >> 3);
+            a_fetch[i] = a_staged[i] = quarter_begin + (k & 7);
+            a_end[i] = min(m_end, quarter_begin + 8 * n_steps);
+            a_at[i] = ((long)min(a_fetch[i], g.M - 1) * g.a.ld + (8 * piece < g.P ? 8 * piece : 0)) * 2;
+            a_lds[i] = k * kAPitch + 16 * piece;
+        }
+    }
 
     // The loop comes twice.  ENDS = false: every row the workgroup touches, those fetched ahead included, exists
     // and every sample of every step counts - all chunks but the last one or two.  ENDS = true: past the last
@@ -414,19 +441,25 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
     // values are; B's may stay).
     auto run = [&](auto ends_tag) {
         constexpr bool ENDS = decltype(ends_tag)::value;
-        auto fetch = [&](float (&f)[kSetsPerWave][8]) {             // this wave's next eight rows
+        auto fetch = [&](Staged &into) {                             // this wave's next eight rows
+            float (&f)[kSetsPerWave][8] = into.col;
+            if constexpr (ABF) {
+#pragma unroll
+                for (int i = 0; i < kAVec; ++i) {
+                    into.a[i] = *reinterpret_cast<const uint4 *>(static_cast<const char *>(g.a.base) + a_at[i]);
+                    // eight rows on, or (ENDS) stay where the arrays end: what is fetched there again is not used
+                    long step_bytes = (long)8 * g.next_a * 2;
+                    if constexpr (ENDS) step_bytes = a_fetch[i] + 8 < g.M ? step_bytes : 0;
+                    a_at[i] += step_bytes;
+                    a_fetch[i] += 8;
+                }
+            }
 #pragma unroll
             for (int r = 0; r < 8; ++r) {
                 const char *arow = static_cast<const char *>(g.a.base) + off_a * (ABF ? 2 : 4);
                 const char *brow = static_cast<const char *>(g.b.base) + off_b * (BBF ? 2 : 4);
 #pragma unroll
-                for (int i = 0; i < kSetsPerWave; ++i) {
-                    if constexpr (ABF) {
-                        if (i < kSetsOfA) {      // a bf16 element stays as it is (nothing here may need the value: that would be a wait)
-                            f[i][r] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(arow)[set_col[i]]);
-                            continue;
-                        }
-                    }
+                for (int i = ABF ? kSetsOfA : 0; i < kSetsPerWave; ++i) {
                     if constexpr (BBF) {
                         if (i >= kSetsOfA) {
                             f[i][r] = __uint_as_float((uint32_t)reinterpret_cast<const uint16_t *>(brow)[set_col[i]]);
@@ -451,24 +484,24 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
         // 16 bytes that lane quarter sg of a fragment of that column reads.  Converted once here, not by every
         // reader.  A loaded value is first passed through an empty asm: that is where the wait for it goes, and
         // it keeps the compiler from turning "loaded value or zero" into a branch around the load.
-        auto deposit = [&](char *buf, float (&f)[kSetsPerWave][8]) {
+        auto deposit = [&](char *buf, Staged &from) {
+            float (&f)[kSetsPerWave][8] = from.col;
+            if constexpr (ABF) {
 #pragma unroll
-            for (int i = 0; i < kSetsPerWave; ++i) {
-                const int col = lane + 64 * (2 * i + half);
-                if constexpr (ABF) {
-                    if (i < kSetsOfA) {       // two bf16 values to a word, the earlier sample in the lower half: the fragment
-                        uint32_t word[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            asm volatile("" : "+v"(f[i][2 * j]), "+v"(f[i][2 * j + 1]));
-                            word[j] = __float_as_uint(f[i][2 * j]) | (__float_as_uint(f[i][2 * j + 1]) << 16);
-                            if constexpr (ENDS)
-                                word[j] &= sample + 2 * j + 1 < wave_end ? 0xFFFFFFFFu : (sample + 2 * j < wave_end ? 0x0000FFFFu : 0u);
-                        }
-                        if (col < cols) *reinterpret_cast<uint4 *>(buf + col * kPitch + 16 * sg) = make_uint4(word[0], word[1], word[2], word[3]);
-                        continue;
+                for (int i = 0; i < kAVec; ++i) {
+                    uint4 v = from.a[i];
+                    asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+                    if constexpr (ENDS) {
+                        const uint32_t keep = a_staged[i] < a_end[i] ? 0xFFFFFFFFu : 0u;
+                        v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep;
                     }
+                    *reinterpret_cast<uint4 *>(buf + a_lds[i]) = v;
+                    a_staged[i] += 8;
                 }
+            }
+#pragma unroll
+            for (int i = ABF ? kSetsOfA : 0; i < kSetsPerWave; ++i) {
+                const int col = lane + 64 * (2 * i + half);
                 if constexpr (BBF) {
                     if (i >= kSetsOfA) {      // bf16 values of B, or the bf16 of an appended column's 1 or 0
                         uint32_t word[4];
@@ -521,8 +554,23 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
             WFrag<P> af[PBW];
 #pragma unroll
             for (int k = 0; k < PBW; ++k) {
-                af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
-                if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
+                if constexpr (ABF) {
+                    // The transposing read works on blocks of 16 lanes: lane 4 a + e of a block receives, as its
+                    // i-th value, element e of the four that lane a + 4 i of the block points at.  With lane a + 4 i
+                    // pointing at sample 8 q4 + i, columns 4 a .. 4 a + 3, lane c gets column c of samples
+                    // 8 q4 + 0..3; the second read gives samples 8 q4 + 4..7.
+                    typedef short s16x4 __attribute__((ext_vector_type(4)));
+                    typedef s16x4 __attribute__((address_space(3))) *LdsQuad;
+                    const char *at = buf + (8 * q4 + (c >> 2)) * kAPitch + (16 * (w + 8 * k) + 4 * (c & 3)) * 2;
+                    const s16x4 first = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsQuad)(at));
+                    const s16x4 second = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsQuad)(at + 4 * kAPitch));
+                    typedef short s16x8 __attribute__((ext_vector_type(8)));
+                    const s16x8 both = __builtin_shufflevector(first, second, 0, 1, 2, 3, 4, 5, 6, 7);
+                    af[k].hi = __builtin_bit_cast(bf16x8, both);
+                } else {
+                    af[k].hi = *reinterpret_cast<const bf16x8 *>(mine + 16 * (w + 8 * k) * kPitch);
+                    if constexpr (P == 2) af[k].lo = *reinterpret_cast<const bf16x8 *>(mine + plane_bytes + 16 * (w + 8 * k) * kPitch);
+                }
             }
 #pragma unroll
             for (int j = 0; j < QBN; ++j)
@@ -715,6 +763,8 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
             };
             unsigned wrap_a = 0;
             if (t.a.rows_per_group < M || !steps(t.a, &g.next_a, &wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
+            // bf16 adjoints are read 16 bytes (eight columns) at a time
+            if (t.a.bf16 && (reinterpret_cast<uintptr_t>(t.a.base) % 16 != 0 || t.a.ld % 8 != 0 || t.a.ld < (t.P + 7) / 8 * 8)) return hipErrorInvalidValue;
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
             const bool is_wide = t.P > 128;
             if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336)) return hipErrorInvalidValue;
