@@ -629,6 +629,218 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_kernel(const TnGemmBatc
                 for (int r = 0; r < 4; ++r) out[(size_t)(16 * (w + 8 * k) + 4 * q4 + r) * g.qp + 16 * j + c] = acc[k][j][r];
 }
 
+// The same product for a bf16 network whose operands allow it (tn_wide_fits): neither operand is fetched
+// column by column.  A thread takes 16 bytes of a sample's row (eight bf16 or four fp32 columns), the step's 32
+// samples go to LDS as they lie in memory, sample-major and as bf16, and the transposition into fragments
+// (eight samples of one column per lane) is left to the transposing LDS read: a tenth of the load
+// instructions.  Chunks, the order of samples within a step (eight consecutive ones from each quarter of the
+// chunk), the made-up columns and the partial results are those of tn_gemm_kernel.
+template <int PBW, int QBN, bool BBF>
+__global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGemmBatch batch)
+{
+    const TnGemmArgs g = batch.g[blockIdx.y];
+    constexpr int kPp = 16 * 8 * PBW;                              // result rows, padded = columns of A staged
+    constexpr int kQp = 16 * QBN;                                  // most columns of B staged
+    constexpr int kColsB = BBF ? 8 : 4;                            // columns of B in 16 bytes
+    static_assert(kPp / 8 % 16 == 0, "whole loads of A per thread");
+    // bytes from a sample's row to the next in LDS: 48 past a multiple of 256, so that the four rows a block of
+    // 16 lanes reads together, 32 bytes of each, lie in different banks
+    constexpr int kAPitch = kPp * 2 + 48, kBPitch = (kQp * 2 + 255) / 256 * 256 + 48;
+    constexpr int kBufBytes = 32 * (kAPitch + kBPitch);
+    extern __shared__ __attribute__((aligned(16))) char stage[];
+    const int lane = threadIdx.x & 63, q4 = lane >> 4, c = lane & 15;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_qb = g.qp / 16;
+    const int m_begin = (int)blockIdx.x * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
+    const int n_steps = (m_end - m_begin + 31) / 32;
+
+    f32x4 acc[PBW][QBN];
+#pragma unroll
+    for (int k = 0; k < PBW; ++k)
+#pragma unroll
+        for (int j = 0; j < QBN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[k][j][r] = 0.0f;
+
+    // A thread's loads all take pieces of one row: thread (quarter t / 128, row (t % 128) / 16, first piece t % 16)
+    // fetches pieces first + 16 i of row 8 quarter + row of the step, i.e. of that quarter's next sample but
+    // `row`, so that one address, one sample number and one end serve them all.  Pieces past the operand's
+    // width repeat the first one (their results are rows or columns nobody reads, or they are made up below).
+    constexpr int kALoads = kPp / 8 / 16;                          // per thread and step: of A,
+    constexpr int kBLoads = (kQp / kColsB + 15) / 16;              // of B
+    const int quarter = (int)threadIdx.x >> 7, row_in_quarter = ((int)threadIdx.x & 127) >> 4, first_piece = (int)threadIdx.x & 15;
+    const int k_row = 8 * quarter + row_in_quarter;
+    const int pieces_b = g.qp / kColsB;
+    int sample_next = m_begin + 8 * n_steps * quarter + row_in_quarter;      // the sample the next loads take
+    const int share_end = min(m_end, m_begin + 8 * n_steps * (quarter + 1));  // end of the quarter's share of the chunk
+    const char *a_row, *b_row;                                     // the next loads' rows
+    unsigned b_left;                                               // rows from the next load's to the end of its group
+    unsigned agent;                                                // of the sample being staged next
+    {
+        const unsigned row = (unsigned)min(sample_next, g.M - 1);
+        const unsigned group = row / (unsigned)g.b.rows_per_group, in_group = row - group * (unsigned)g.b.rows_per_group;
+        a_row = static_cast<const char *>(g.a.base) + (long)row * g.a.ld * 2;
+        b_row = static_cast<const char *>(g.b.base) + ((long)group * g.b.group_stride + (long)in_group * g.b.ld) * (BBF ? 2 : 4);
+        b_left = (unsigned)g.b.rows_per_group - in_group;
+        agent = (unsigned)sample_next % (unsigned)g.N;
+    }
+    const unsigned agent_step = 8u % (unsigned)g.N;
+    int a_piece[kALoads], b_piece[kBLoads];                        // byte offsets within the row
+#pragma unroll
+    for (int i = 0; i < kALoads; ++i) a_piece[i] = 8 * (first_piece + 16 * i) < g.P ? 16 * (first_piece + 16 * i) : 0;
+#pragma unroll
+    for (int i = 0; i < kBLoads; ++i) b_piece[i] = kColsB * (first_piece + 16 * i) < g.Q ? 16 * (first_piece + 16 * i) : 0;
+    const int a_lds = k_row * kAPitch + 16 * first_piece;          // + 256 i
+    const int b_lds = 32 * kAPitch + k_row * kBPitch + 2 * kColsB * first_piece;      // + 32 kColsB i
+    const int b_spare = 32 * kAPitch + k_row * kBPitch + (kBPitch - 48);             // 48 bytes that no fragment reads
+
+    constexpr int kDepth = 2;
+    struct Staged { uint4 a[kALoads], b[kBLoads]; };
+    Staged rv[kDepth];
+    int staged_sample = sample_next;                               // the sample the next deposit puts down
+
+    auto run = [&](auto ends_tag) {
+        constexpr bool ENDS = decltype(ends_tag)::value;           // the chunk reaches the end of the samples
+        auto fetch = [&](Staged &into) {
+#pragma unroll
+            for (int i = 0; i < kALoads; ++i) into.a[i] = *reinterpret_cast<const uint4 *>(a_row + a_piece[i]);
+#pragma unroll
+            for (int i = 0; i < kBLoads; ++i) into.b[i] = *reinterpret_cast<const uint4 *>(b_row + b_piece[i]);
+            // eight rows on; B: inside the group, or seven steps inside and one from a group's last row to the
+            // next group's first.  (ENDS) Past the arrays' end the rows stay: what is fetched there again is not used.
+            bool go = true;
+            if constexpr (ENDS) go = sample_next + 8 < g.M;
+            const bool wraps = b_left <= 8u;
+            const long b_step = (wraps ? (long)7 * g.next_b + g.wrap_b : (long)8 * g.next_b) * (BBF ? 2 : 4);
+            a_row += go ? (long)8 * g.next_a * 2 : 0;
+            b_row += go ? b_step : 0;
+            b_left = go ? (wraps ? b_left + (unsigned)g.b.rows_per_group - 8u : b_left - 8u) : b_left;
+            sample_next += 8;
+        };
+        auto deposit = [&](char *buf, Staged &from) {
+            uint32_t keep = 0xFFFFFFFFu;       // samples past the chunk's end count for nothing: A's values are cleared, B's may stay
+            if constexpr (ENDS) keep = staged_sample < share_end ? 0xFFFFFFFFu : 0u;
+#pragma unroll
+            for (int i = 0; i < kALoads; ++i) {
+                uint4 v = from.a[i];
+                asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+                if constexpr (ENDS) { v.x &= keep; v.y &= keep; v.z &= keep; v.w &= keep; }
+                *reinterpret_cast<uint4 *>(buf + a_lds + 256 * i) = v;
+            }
+#pragma unroll
+            for (int i = 0; i < kBLoads; ++i) {
+                uint4 v = from.b[i];
+                asm volatile("" : "+v"(v.x), "+v"(v.y), "+v"(v.z), "+v"(v.w));
+                const int piece = first_piece + 16 * i, col = kColsB * piece;
+                // a piece past B's own columns is made up: the column of ones, or the one-hot columns of the sample's agent
+                const bool made_up = col >= g.Q;
+                uint32_t word[kColsB / 2];
+#pragma unroll
+                for (int e = 0; e < kColsB / 2; ++e) {
+                    uint32_t pair[2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int extra = col + 2 * e + h - g.Q;            // which appended column, if any
+                        const bool one = extra >= 0 && extra < g.n_extra && (g.extra_mode == kExtraOnes || (unsigned)extra == agent);
+                        pair[h] = one ? 0x3F80u : 0u;
+                    }
+                    word[e] = pair[0] | (pair[1] << 16);
+                }
+                // a spare load (a piece past the staged columns) goes to the padding at the end of the row
+                const int at = piece < pieces_b ? b_lds + 32 * kColsB * i : b_spare;
+                if constexpr (BBF) {
+                    const uint4 out = made_up && piece < pieces_b ? make_uint4(word[0], word[1], word[2], word[3]) : v;
+                    *reinterpret_cast<uint4 *>(buf + at) = out;
+                } else {
+                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+                    bf16x4 r;
+                    r[0] = (__bf16)__uint_as_float(v.x); r[1] = (__bf16)__uint_as_float(v.y);
+                    r[2] = (__bf16)__uint_as_float(v.z); r[3] = (__bf16)__uint_as_float(v.w);
+                    const uint2 real = __builtin_bit_cast(uint2, r);
+                    const uint2 out = made_up && piece < pieces_b ? make_uint2(word[0], word[1]) : real;
+                    *reinterpret_cast<uint2 *>(buf + at) = out;
+                }
+            }
+            staged_sample += 8;
+            agent += agent_step;
+            agent = agent >= (unsigned)g.N ? agent - (unsigned)g.N : agent;
+        };
+        // The transposing read works on blocks of 16 lanes: lane 4 a + e of a block receives, as its i-th value,
+        // element e of the four that lane a + 4 i of the block points at.  With lane a + 4 i pointing at sample
+        // 8 q4 + i, columns 4 a .. 4 a + 3 of a block of 16 columns, lane c gets column c of samples 8 q4 + 0..3;
+        // a second read four rows on gives samples 8 q4 + 4..7: the fragment of lane (c, q4).
+        auto fragment = [&](const char *rows, int pitch, int first_col) {
+            typedef short s16x4 __attribute__((ext_vector_type(4)));
+            typedef short s16x8 __attribute__((ext_vector_type(8)));
+            typedef s16x4 __attribute__((address_space(3))) *LdsQuad;
+            const char *at = rows + (8 * q4 + (c >> 2)) * pitch + (first_col + 4 * (c & 3)) * 2;
+            const s16x4 first = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsQuad)(at));
+            const s16x4 second = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LdsQuad)(at + 4 * pitch));
+            return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(first, second, 0, 1, 2, 3, 4, 5, 6, 7));
+        };
+        auto multiply = [&](const char *buf) {
+            WFrag<1> af[PBW];
+#pragma unroll
+            for (int k = 0; k < PBW; ++k) af[k].hi = fragment(buf, kAPitch, 16 * (w + 8 * k));
+#pragma unroll
+            for (int j = 0; j < QBN; ++j)
+                if (j < n_qb) {
+                    Frag<1> bf;
+                    bf.hi = fragment(buf + 32 * kAPitch, kBPitch, 16 * j);
+#pragma unroll
+                    for (int k = 0; k < PBW; ++k) mma16<1>(acc[k][j], af[k], bf);
+                }
+        };
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) fetch(rv[d]);
+        // a round: stage both steps, ask for the next two, multiply both - every load has both multiplications to arrive in
+        for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
+            deposit(stage, rv[0]);
+            deposit(stage + kBufBytes, rv[1]);
+            fetch(rv[0]);
+            fetch(rv[1]);
+            __syncthreads();
+            multiply(stage);
+            multiply(stage + kBufBytes);
+            __syncthreads();                   // every wave is done reading before the next round writes
+        }
+    };
+    // Rows touched: the last quarter's, plus what is fetched ahead of the last step (the loop runs whole rounds).
+    const int rounds_end = (n_steps + kDepth - 1) / kDepth * kDepth;
+    const bool all_inside = m_begin + 8 * (3 * n_steps + rounds_end + kDepth) <= g.M
+                            && rounds_end == n_steps && m_end - m_begin == 32 * n_steps;
+    if (all_inside) run(std::false_type{});
+    else run(std::true_type{});
+
+    // C layout: lane (c, q4) holds result[16 block + 4 q4 + r][16 j + c]
+    float *out = g.partial + (size_t)blockIdx.x * kPp * g.qp;
+#pragma unroll
+    for (int k = 0; k < PBW; ++k)
+#pragma unroll
+        for (int j = 0; j < QBN; ++j)
+            if (j < n_qb)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) out[(size_t)(16 * (w + 8 * k) + 4 * q4 + r) * g.qp + 16 * j + c] = acc[k][j][r];
+}
+
+template <int PBW, int QBN> constexpr size_t tn_wide_lds()
+{
+    return (size_t)2 * 32 * ((16 * 8 * PBW * 2 + 48) + ((16 * QBN * 2 + 255) / 256 * 256 + 48));
+}
+
+// Whether tn_gemm_wide_kernel can take a product: bf16 adjoints, and every row of both operands a whole number
+// of 16-byte pieces at 16-byte aligned addresses, B's own columns ending on a piece.
+bool tn_wide_fits(const TnProduct &t, long M)
+{
+    if (!t.a.bf16) return false;
+    const int cols_b = t.b.bf16 ? 8 : 4, bytes_b = t.b.bf16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(t.a.base) % 16 != 0 || t.a.ld % 8 != 0 || t.a.ld < (t.P + 7) / 8 * 8) return false;
+    if (t.Q < cols_b) return false;
+    if (reinterpret_cast<uintptr_t>(t.b.base) % 16 != 0 || t.b.ld % cols_b != 0 || t.Q % cols_b != 0 || t.b.ld < cols_b) return false;
+    if (t.b.rows_per_group < M && (t.b.rows_per_group < 8 || (t.b.group_stride * bytes_b) % 16 != 0)) return false;
+    return true;
+}
+
 // Sum of the chunks, in a fixed order, into the packed gradient vector.  Result row p goes to row
 // (p + row_shift) % P of the destination matrix (the adjoint array lists the gates as n, r, z, the
 // parameters as r, z, n); columns < Q go to dst_w[row * ld_w + column]; the appended column of ones
@@ -799,6 +1011,26 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
     } while (0)
         // the element type of A is the same for every product of a call (bf16 adjoints only with one plane)
         const bool a_bf16 = list[done].a.bf16 != 0;
+        bool all_wide = planes == 1 && a_bf16;
+        for (int i = done; i < taken && all_wide; ++i) all_wide = tn_wide_fits(list[i], M);
+#define MARL_TN_WIDE(PBW, QBN, BBF, BATCH, COUNT)                                                         \
+    do {                                                                                                 \
+        err = allow_large_lds<tn_gemm_wide_kernel<PBW, QBN, BBF>>(kLdsLimit);                            \
+        if (err != hipSuccess) return err;                                                               \
+        const size_t lds_wide = tn_wide_lds<PBW, QBN>();                                                 \
+        hipLaunchKernelGGL((tn_gemm_wide_kernel<PBW, QBN, BBF>), dim3(chunks, COUNT), dim3(kTnThreads), lds_wide, stream, BATCH); \
+        err = hipGetLastError();                                                                         \
+        if (err != hipSuccess) return err;                                                               \
+    } while (0)
+        if (all_wide) {
+            if (n_wide) {
+                if (list[done].b.bf16) MARL_TN_WIDE(3, 9, true, wide, n_wide);
+                else MARL_TN_WIDE(3, 9, false, wide, n_wide);
+            }
+            if (n_narrow) MARL_TN_WIDE(1, 21, false, narrow, n_narrow);
+            n_wide = n_narrow = 0;
+        }
+#undef MARL_TN_WIDE
         if (n_wide) {
             if (planes == 2) MARL_TN(3, 9, 2, false, wide, n_wide, 384, max_q_wide);
             else if (a_bf16 && list[done].b.bf16) MARL_TN2(3, 9, 1, true, true, wide, n_wide, 384, max_q_wide);

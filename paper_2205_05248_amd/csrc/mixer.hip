@@ -416,10 +416,23 @@ __global__ __launch_bounds__(256) void mixer_loss_kernel(const float *__restrict
 {
     __shared__ float sq[256], cnt[256];
     float s = 0.0f, n = 0.0f;
-    for (int i = threadIdx.x; i < rows; i += 256) {
-        const float e = td_err[i];
-        s = fmaf(e, e, s);
-        n += filled[i] ? 1.0f : 0.0f;
+    // eight loads in flight per thread (positions past the end clamped, their terms dropped); the terms are
+    // added in the same order as one by one
+    for (int i0 = threadIdx.x; i0 < rows; i0 += 256 * 8) {
+        float e[8];
+        uint8_t f[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int i = min(i0 + 256 * k, rows - 1);
+            e[k] = td_err[i];
+            f[k] = filled[i];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+            if (i0 + 256 * k < rows) {
+                s = fmaf(e[k], e[k], s);
+                n += f[k] ? 1.0f : 0.0f;
+            }
     }
     sq[threadIdx.x] = s;
     cnt[threadIdx.x] = n;
