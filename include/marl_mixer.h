@@ -116,7 +116,7 @@ int marl_mixer_td(marl_mixer *online, marl_mixer *target, int32_t B, int32_t T, 
  *   grad_q_taken   dev [B,T,N] f32, overwritten
  *   grad_weights   dev [marl_mixer_param_count] f32, overwritten, packed like the weights
  * Sums run in a fixed order.  Arithmetic as the forward pass (bf16 MFMA products, fp32 accumulation; fp32
- * mixers split operands into two bf16 parts).  MARL_ERR_BAD_DIM for B < 1, T < 1, B T ((N + 4) embed + 4) >= 2^30, a
+ * mixers split operands into two bf16 parts).  MARL_ERR_BAD_DIM for B < 1, T < 1, B T ((N + 4) embed + 8) >= 2^30, a
  * workspace that is too small; MARL_ERR_BAD_ARG for a misaligned workspace.
  */
 int marl_mixer_grad_workspace_bytes(const marl_mixer *m, int32_t B, int32_t T, size_t *bytes);

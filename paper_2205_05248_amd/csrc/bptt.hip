@@ -835,7 +835,8 @@ bool tn_wide_fits(const TnProduct &t, long M)
     if (!t.a.bf16) return false;
     const int cols_b = t.b.bf16 ? 8 : 4, bytes_b = t.b.bf16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(t.a.base) % 16 != 0 || t.a.ld % 8 != 0 || t.a.ld < (t.P + 7) / 8 * 8) return false;
-    if (t.Q < cols_b) return false;
+    if (t.Q == 0) return t.b.ld >= cols_b && t.b.ld % cols_b == 0 && reinterpret_cast<uintptr_t>(t.b.base) % 16 == 0
+                         && (t.b.rows_per_group >= M || (t.b.rows_per_group >= 8 && (t.b.group_stride * bytes_b) % 16 == 0));
     if (reinterpret_cast<uintptr_t>(t.b.base) % 16 != 0 || t.b.ld % cols_b != 0 || t.Q % cols_b != 0 || t.b.ld < cols_b) return false;
     if (t.b.rows_per_group < M && (t.b.rows_per_group < 8 || (t.b.group_stride * bytes_b) % 16 != 0)) return false;
     return true;

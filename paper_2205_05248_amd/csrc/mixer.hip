@@ -732,7 +732,7 @@ struct MixerBackArgs {
     const float *bias, *v2;
     int N, M, S, ks, rows, T, F, ldd;
     const float *state, *q, *e;
-    float *dgen;        // [rows, ldd]
+    void *dgen;         // [rows, ldd]: fp32, or bf16 for a one-plane mixer (whose products round the adjoints to bf16 anyway)
     float *grad_q;      // [rows, N]
 };
 
@@ -771,13 +771,23 @@ __global__ __launch_bounds__(64 * W) void mixer_back_stream_kernel(const MixerBa
     for (int j = 0; j < MB; ++j) gain[j] = load_feature4(a.v2, j, q4);
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     constexpr uint32_t kDrop = 0xFFFFFFF0u;
-    const __amdgpu_buffer_rsrc_t dgen_buf = __builtin_amdgcn_make_buffer_rsrc(a.dgen, 0, (int)((uint32_t)a.rows * (uint32_t)a.ldd * 4u), kRawBuffer);
+    constexpr uint32_t kElem = P == 1 ? 2u : 4u;                   // bytes per stored adjoint
+    const __amdgpu_buffer_rsrc_t dgen_buf = __builtin_amdgcn_make_buffer_rsrc(a.dgen, 0, (int)((uint32_t)a.rows * (uint32_t)a.ldd * kElem), kRawBuffer);
     const __amdgpu_buffer_rsrc_t gq_buf = __builtin_amdgcn_make_buffer_rsrc(a.grad_q, 0, (int)((uint32_t)a.rows * (uint32_t)N * 4u), kRawBuffer);
     uint32_t drop = valid ? 0u : kDrop;
     asm volatile("" : "+v"(drop));
     const uint32_t row_at = (uint32_t)min(row[0], a.rows - 1) * (uint32_t)a.ldd;       // first element of the row in dgen
     auto store4 = [&](const f32x4 &v, uint32_t column, uint32_t drop_mask) {
-        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dgen_buf, ((row_at + column) * 4u) | drop_mask, 0, 0);
+        if constexpr (P == 1) {
+            typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            bf16x4 r;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = (__bf16)v[i];
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, r), dgen_buf, ((row_at + column) * 2u) | drop_mask, 0, 0);
+        } else {
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), dgen_buf, ((row_at + column) * 4u) | drop_mask, 0, 0);
+        }
     };
 
     // 1. hidden pre-activations
@@ -819,7 +829,12 @@ __global__ __launch_bounds__(64 * W) void mixer_back_stream_kernel(const MixerBa
         store4(first, (kind == 0 ? (N + 1) * M : (N + 2) * M) + unit, keep);
         store4(second, (kind == 0 ? N * M : F) + unit, keep);
     });
-    if (q4 == 0) __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, e), dgen_buf, ((row_at + F + M) * 4u) | drop, 0, 0);
+    if (q4 == 0) {
+        if constexpr (P == 1)
+            __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(uint16_t, (__bf16)e), dgen_buf, ((row_at + F + M) * 2u) | drop, 0, 0);
+        else
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, e), dgen_buf, ((row_at + F + M) * 4u) | drop, 0, 0);
+    }
 
     // 3. the agents' blocks again
     lds_barrier();
@@ -890,7 +905,8 @@ MixerGradPlan mixer_grad_plan(const marl_mixer_desc &d, int B, int T)
     MixerGradPlan p{};
     const long R = (long)B * T;
     const int F = (d.n_agents + 3) * d.embed;
-    p.ldd = (F + d.embed + 1 + 3) / 4 * 4;
+    // whole 16-byte pieces, and eight columns from the last product's first one on (it takes the last embed + 1)
+    p.ldd = F + (d.embed + 1 + 7) / 8 * 8;
     // few samples (B T, not B T N) and many products that run side by side: chunks of about 256 transitions
     const long chunks = std::max<long>(1, std::min<long>(256, R / 256));
     p.chunk = (int)(((R + chunks - 1) / chunks + 63) / 64 * 64);
@@ -912,7 +928,7 @@ int marl_mixer_grad_workspace_bytes(const marl_mixer *m, int32_t B, int32_t T, s
 {
     if (!m || !bytes) return MARL_ERR_NULL;
     const int F = (m->desc.n_agents + 3) * m->desc.embed;
-    if (B < 1 || T < 1 || (int64_t)B * T * (F + m->desc.embed + 4) >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
+    if (B < 1 || T < 1 || (int64_t)B * T * (F + m->desc.embed + 8) >= (int64_t)1 << 30) return MARL_ERR_BAD_DIM;
     *bytes = marl::mixer_grad_plan(m->desc, B, T).bytes;
     return MARL_OK;
 }
@@ -934,7 +950,9 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     const marl::MixerGradPlan plan = marl::mixer_grad_plan(m->desc, B, T);
     const int N = m->desc.n_agents, M = m->desc.embed, S = m->desc.state_dim, F = (N + 3) * M;
     const long R = (long)B * T;
-    float *dgen = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_dgen);
+    char *dgen = static_cast<char *>(workspace) + plan.off_dgen;
+    const bool dgen_bf16 = m->planes == 1;
+    const size_t elem = dgen_bf16 ? 2 : 4;
     float *partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_partial);
 
     marl::MixerBackArgs a{};
@@ -966,7 +984,7 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     // parameter gradients: packed order Hw1 [N M, S], hb1, Hb1 [M, S], hbb1, Hw2 [M, S], hb2, V1 [M, S], c1, v2, c2
     float *gHw1 = grad_weights, *ghb1 = gHw1 + (size_t)N * M * S, *gHb1 = ghb1 + (size_t)N * M, *ghbb1 = gHb1 + (size_t)M * S;
     float *gHw2 = ghbb1 + M, *ghb2 = gHw2 + (size_t)M * S, *gV1 = ghb2 + M, *gc1 = gV1 + (size_t)M * S, *gv2 = gc1 + M;
-    const marl::RowMap plain{dgen, 0, (int)R, plan.ldd, 0};
+    const marl::RowMap plain{dgen, 0, (int)R, plan.ldd, dgen_bf16 ? 1 : 0};
     const marl::RowMap states{state, (long)(T + 1) * S, T, S, 0};
     // one matrix: rows [r0, r0 + P) of it are adjoint columns [col0 + r0, ..); state columns in slices, the
     // column of ones (the bias) rides with the last slice
@@ -979,7 +997,7 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
                 const int P = std::min(p_step, rows_total - r0), Q = std::min(q_step, S - k0);
                 const bool last = k0 + q_step >= S;
                 marl::RowMap ar = plain, br = states;
-                ar.base = dgen + col0 + r0;
+                ar.base = dgen + (size_t)(col0 + r0) * elem;
                 br.base = state + k0;
                 products.push_back({ar, br, P, Q, last ? marl::kExtraOnes : marl::kExtraNone, last ? 1 : 0, 1, 0, S,
                                     dst_w + (size_t)r0 * S + k0, dst_b + r0});
@@ -991,7 +1009,7 @@ int marl_mixer_grad(marl_mixer *m, int32_t B, int32_t T, const float *state, con
     matrix((N + 2) * M, M, gV1, gc1);
     {        // v2 and c2: the last M + 1 adjoint columns against the column of ones alone
         marl::RowMap ar = plain;
-        ar.base = dgen + F;
+        ar.base = dgen + (size_t)F * elem;
         products.push_back({ar, states, M + 1, 0, marl::kExtraOnes, 1, 1, 0, 1, gv2, gv2});
     }
     err = marl::launch_tn_products(m->planes, products.data(), (int)products.size(), R, plan.chunk, partial, plan.partial_bytes, stream);
