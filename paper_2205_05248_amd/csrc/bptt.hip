@@ -47,6 +47,11 @@ struct BpttArgs {
     void *da;                    // [B, T, N, 4H]   adjoints of the gate pre-activations: n (input side), r, z, n (hidden side)
     void *dpre1;                 // [B, T, N, H]    adjoint of fc1's pre-activation
     void *dq;                    // [B, T, N, a16]  adjoint of Q, dense (one non-zero per row)
+    // The launch walks slots t_end - 1 .. t_begin.  One launch takes all of them (0, T); two take the later and
+    // then the earlier slots and hand dL/dh over in `carry` [rows rounded up to 16][H] fp32, so that the later
+    // slots' weight-gradient products can run beside the second launch.
+    int t_begin, t_end;
+    float *carry;
 };
 
 template <int H, int P> struct BpttShape {
@@ -164,10 +169,13 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
     };
 
     f32x4 dh[NBC];                                                 // dL/dh flowing into the state after slot t
+    float *const carry_row = a.carry + (size_t)(blockIdx.x * 16 + c) * H + unit0;      // rows past the end have room too
 #pragma unroll
-    for (int j = 0; j < NBC; ++j)
+    for (int j = 0; j < NBC; ++j) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) dh[j][r] = 0.0f;
+        if (a.t_end < T) dh[j] = *reinterpret_cast<const f32x4 *>(carry_row + 16 * j);
+    }
 
     // Every global access inside the loop is unconditional, so that the loop body is straight-line code and
     // the waits for the prefetched inputs count exactly the stores issued after them: rows past the end
@@ -196,8 +204,8 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
     asm volatile("" : "+v"(drop));
     const uint32_t drop_dq = (16 * w < a.a16) ? drop : kDrop;      // wave w writes block w of the row's dQ
 
-    StepIn nxt = fetch(T - 1, load_action(T - 1));
-    int u_ahead = load_action(max(T - 2, 0));
+    StepIn nxt = fetch(a.t_end - 1, load_action(a.t_end - 1));
+    int u_ahead = load_action(max(a.t_end - 2, 0));
     // Nothing may be in flight when the loop is entered: the waits inside it are then the ones of the loop
     // itself (the entry would otherwise add its own, stricter ones, which make every iteration wait for the
     // previous iteration's stores).
@@ -206,7 +214,7 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
     for (int j = 0; j < NBC; ++j) asm volatile("" : "+v"(nxt.hp[j]), "+v"(nxt.xv[j]), "+v"(nxt.w2[j]));
     asm volatile("" : "+v"(nxt.gq_raw), "+v"(u_ahead));
     lds_barrier();                                                 // W_ih and the biases are in LDS
-    for (int t = T - 1; t >= 0; --t) {
+    for (int t = a.t_end - 1; t >= a.t_begin; --t) {
         const StepIn in = nxt;
         const int u_next = u_ahead;
         u_ahead = load_action(max(t - 2, 0));
@@ -313,6 +321,10 @@ __global__ __launch_bounds__(64 * NW, NW / 4) void bptt_back_kernel(BpttArgs a)
             store4(dp, pre_buf, m * H + unit0 + 16 * j, drop);
         }
     }
+    if (a.t_begin > 0) {
+#pragma unroll
+        for (int j = 0; j < NBC; ++j) *reinterpret_cast<f32x4 *>(carry_row + 16 * j) = dh[j];
+    }
 }
 
 // ------------------------------------------------------------------------------------------ weight gradients
@@ -327,6 +339,7 @@ struct TnGemmArgs {
     // elements from a row to the next: inside a group, and from a group's last row to the next group's first
     // (A's rows are one group: the adjoint arrays are)
     unsigned next_a, next_b, wrap_b;
+    unsigned wrap_a;    // tn_gemm_wide_kernel only: A in groups too
     float *partial;     // [chunks][128 or 384 rows][qp]
 };
 
@@ -674,13 +687,15 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGem
     int sample_next = m_begin + 8 * n_steps * quarter + row_in_quarter;      // the sample the next loads take
     const int share_end = min(m_end, m_begin + 8 * n_steps * (quarter + 1));  // end of the quarter's share of the chunk
     const char *a_row, *b_row;                                     // the next loads' rows
-    unsigned b_left;                                               // rows from the next load's to the end of its group
+    unsigned a_left, b_left;                                       // rows from the next load's to the end of its group
     unsigned agent;                                                // of the sample being staged next
     {
         const unsigned row = (unsigned)min(sample_next, g.M - 1);
         const unsigned group = row / (unsigned)g.b.rows_per_group, in_group = row - group * (unsigned)g.b.rows_per_group;
-        a_row = static_cast<const char *>(g.a.base) + (long)row * g.a.ld * 2;
+        const unsigned group_a = row / (unsigned)g.a.rows_per_group, in_group_a = row - group_a * (unsigned)g.a.rows_per_group;
+        a_row = static_cast<const char *>(g.a.base) + ((long)group_a * g.a.group_stride + (long)in_group_a * g.a.ld) * 2;
         b_row = static_cast<const char *>(g.b.base) + ((long)group * g.b.group_stride + (long)in_group * g.b.ld) * (BBF ? 2 : 4);
+        a_left = (unsigned)g.a.rows_per_group - in_group_a;
         b_left = (unsigned)g.b.rows_per_group - in_group;
         agent = (unsigned)sample_next % (unsigned)g.N;
     }
@@ -706,14 +721,16 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGem
             for (int i = 0; i < kALoads; ++i) into.a[i] = *reinterpret_cast<const uint4 *>(a_row + a_piece[i]);
 #pragma unroll
             for (int i = 0; i < kBLoads; ++i) into.b[i] = *reinterpret_cast<const uint4 *>(b_row + b_piece[i]);
-            // eight rows on; B: inside the group, or seven steps inside and one from a group's last row to the
+            // eight rows on: inside the group, or seven steps inside and one from a group's last row to the
             // next group's first.  (ENDS) Past the arrays' end the rows stay: what is fetched there again is not used.
             bool go = true;
             if constexpr (ENDS) go = sample_next + 8 < g.M;
-            const bool wraps = b_left <= 8u;
+            const bool wraps = b_left <= 8u, wraps_a = a_left <= 8u;
             const long b_step = (wraps ? (long)7 * g.next_b + g.wrap_b : (long)8 * g.next_b) * (BBF ? 2 : 4);
-            a_row += go ? (long)8 * g.next_a * 2 : 0;
+            const long a_step = (wraps_a ? (long)7 * g.next_a + g.wrap_a : (long)8 * g.next_a) * 2;
+            a_row += go ? a_step : 0;
             b_row += go ? b_step : 0;
+            a_left = go ? (wraps_a ? a_left + (unsigned)g.a.rows_per_group - 8u : a_left - 8u) : a_left;
             b_left = go ? (wraps ? b_left + (unsigned)g.b.rows_per_group - 8u : b_left - 8u) : b_left;
             sample_next += 8;
         };
@@ -835,6 +852,7 @@ bool tn_wide_fits(const TnProduct &t, long M)
     if (!t.a.bf16) return false;
     const int cols_b = t.b.bf16 ? 8 : 4, bytes_b = t.b.bf16 ? 2 : 4;
     if (reinterpret_cast<uintptr_t>(t.a.base) % 16 != 0 || t.a.ld % 8 != 0 || t.a.ld < (t.P + 7) / 8 * 8) return false;
+    if (t.a.rows_per_group < M && (t.a.rows_per_group < 8 || (t.a.group_stride * 2) % 16 != 0)) return false;
     if (t.Q == 0) return t.b.ld >= cols_b && t.b.ld % cols_b == 0 && reinterpret_cast<uintptr_t>(t.b.base) % 16 == 0
                          && (t.b.rows_per_group >= M || (t.b.rows_per_group >= 8 && (t.b.group_stride * bytes_b) % 16 == 0));
     if (reinterpret_cast<uintptr_t>(t.b.base) % 16 != 0 || t.b.ld % cols_b != 0 || t.Q % cols_b != 0 || t.b.ld < cols_b) return false;
@@ -897,7 +915,7 @@ namespace {
 size_t align_up(size_t v) { return (v + 255) / 256 * 256; }
 
 struct Plan {
-    size_t off_h, off_x, off_da, off_dpre1, off_dq, off_partial, partial_bytes, bytes;
+    size_t off_h, off_x, off_da, off_dpre1, off_dq, off_carry, off_partial, partial_bytes, bytes;
     int a16, chunks, chunk;
 };
 
@@ -920,8 +938,10 @@ Plan make_plan(const NetFrags &net, int B, int T)
     // the four products run together: room for all their partial results
     const long chunks_real = (M + p.chunk - 1) / p.chunk;
     auto part = [&](size_t P, size_t Qt) { return (size_t)chunks_real * (P > 128 ? 384 : 128) * ((Qt + 15) / 16 * 16) * 4; };
-    const size_t need = 2 * part(3 * H, H + 1) + part(H, (size_t)net.D + net.N) + part(net.A, H + 1);
+    // (one-plane networks: twice, for the two halves of the slots whose products run apart, each in up to 256 chunks)
+    const size_t need = (net.planes == 1 ? 2 : 1) * (2 * part(3 * H, H + 1) + part(H, (size_t)net.D + net.N) + part(net.A, H + 1));
     p.partial_bytes = need;
+    p.off_carry = off;  off = align_up(off + (R + 15) / 16 * 16 * H * 4);
     p.off_partial = off; off = align_up(off + need);
     p.bytes = off;
     return p;
@@ -959,6 +979,7 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
         int n_wide = 0, n_narrow = 0, n_red = 0, max_q_wide = 0, max_q_narrow = 0, max_total = 0;
         size_t used = 0;
         int taken = done;
+        bool a_in_groups = false;
         for (; taken < count; ++taken) {
             const TnProduct &t = list[taken];
             TnGemmArgs g{};
@@ -974,8 +995,10 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
                 *next = (unsigned)n; *wrap = (unsigned)w;
                 return true;
             };
-            unsigned wrap_a = 0;
-            if (t.a.rows_per_group < M || !steps(t.a, &g.next_a, &wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
+            if (!steps(t.a, &g.next_a, &g.wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
+            // A in groups: the wide kernel only
+            if (t.a.rows_per_group < M && !(planes == 1 && tn_wide_fits(t, M))) return hipErrorInvalidValue;
+            a_in_groups = a_in_groups || t.a.rows_per_group < M;
             // bf16 adjoints are read 16 bytes (eight columns) at a time
             if (t.a.bf16 && (reinterpret_cast<uintptr_t>(t.a.base) % 16 != 0 || t.a.ld % 8 != 0 || t.a.ld < (t.P + 7) / 8 * 8)) return hipErrorInvalidValue;
             // two shapes: up to 384 rows x 144 columns (the GRU matrices), up to 128 rows x 336 columns (fc1, fc2)
@@ -1014,6 +1037,7 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
         const bool a_bf16 = list[done].a.bf16 != 0;
         bool all_wide = planes == 1 && a_bf16;
         for (int i = done; i < taken && all_wide; ++i) all_wide = tn_wide_fits(list[i], M);
+        if (a_in_groups && !all_wide) return hipErrorInvalidValue;
 #define MARL_TN_WIDE(PBW, QBN, BBF, BATCH, COUNT)                                                         \
     do {                                                                                                 \
         err = allow_large_lds<tn_gemm_wide_kernel<PBW, QBN, BBF>>(kLdsLimit);                            \
@@ -1062,6 +1086,52 @@ hipError_t launch_tn_products(int planes, const TnProduct *list, int count, long
 }
 
 
+// The products of `list` (every one fits the wide kernel; same M and chunk), without the sum of their chunks:
+// product i's partial sums go to partial[i].  One launch per shape and element type of B.
+hipError_t launch_tn_gemms_wide(const TnProduct *list, int count, long M, int chunk, float *const *partial, hipStream_t stream)
+{
+    const int chunks = (int)((M + chunk - 1) / chunk);
+    TnGemmBatch batch[3]{};             // wide with bf16 B, wide, narrow
+    int n[3] = {0, 0, 0};
+    for (int i = 0; i < count; ++i) {
+        const TnProduct &t = list[i];
+        TnGemmArgs g{};
+        g.a = t.a; g.b = t.b; g.M = (int)M; g.P = t.P; g.Q = t.Q; g.extra_mode = t.extra_mode; g.n_extra = t.n_extra;
+        g.N = t.N > 0 ? t.N : 1;
+        g.qp = (t.Q + t.n_extra + 15) / 16 * 16;
+        g.chunk = chunk;
+        auto steps = [&](const RowMap &m, unsigned *next, unsigned *wrap) {
+            const long nx = (long)m.ld;
+            const long w = m.rows_per_group >= M ? nx : m.group_stride - (long)(m.rows_per_group - 1) * m.ld;
+            if (nx < 0 || w < 0 || nx >= (1L << 31) || w >= (1L << 31)) return false;
+            *next = (unsigned)nx; *wrap = (unsigned)w;
+            return true;
+        };
+        if (!tn_wide_fits(t, M) || !steps(t.a, &g.next_a, &g.wrap_a) || !steps(t.b, &g.next_b, &g.wrap_b)) return hipErrorInvalidValue;
+        const bool is_wide = t.P > 128;
+        if ((is_wide && (t.P > 384 || g.qp > 144)) || (!is_wide && g.qp > 336) || (t.b.bf16 && !is_wide)) return hipErrorInvalidValue;
+        g.partial = partial[i];
+        const int kind = is_wide ? (t.b.bf16 ? 0 : 1) : 2;
+        if (n[kind] == kTnBatchMax) return hipErrorInvalidValue;
+        batch[kind].g[n[kind]++] = g;
+    }
+    hipError_t err = hipSuccess;
+#define MARL_TN_WIDE(PBW, QBN, BBF, KIND)                                                                 \
+    if (n[KIND]) {                                                                                       \
+        err = allow_large_lds<tn_gemm_wide_kernel<PBW, QBN, BBF>>(kLdsLimit);                            \
+        if (err != hipSuccess) return err;                                                               \
+        const size_t lds_wide = tn_wide_lds<PBW, QBN>();                                                 \
+        hipLaunchKernelGGL((tn_gemm_wide_kernel<PBW, QBN, BBF>), dim3(chunks, n[KIND]), dim3(kTnThreads), lds_wide, stream, batch[KIND]); \
+        err = hipGetLastError();                                                                         \
+        if (err != hipSuccess) return err;                                                               \
+    }
+    MARL_TN_WIDE(3, 9, true, 0)
+    MARL_TN_WIDE(3, 9, false, 1)
+    MARL_TN_WIDE(1, 21, false, 2)
+#undef MARL_TN_WIDE
+    return hipSuccess;
+}
+
 bool qnet_grad_fits(const NetFrags &net)
 {
     return unroll_fused_fits(net) && net.D + net.N <= 336;        // the widest product the gradient kernel stages
@@ -1079,7 +1149,7 @@ void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspa
 
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
                             const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream,
-                            bool activations_kept)
+                            bool activations_kept, const SideStream *side, int n_cu)
 {
     const Plan plan = make_plan(net, B, T);
     char *ws = static_cast<char *>(workspace);
@@ -1100,34 +1170,102 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     BpttArgs a{};
     a.net = net; a.B = B; a.T = T; a.a16 = plan.a16; a.actions = actions; a.filled = filled; a.grad_q = grad_q;
     a.h_all = h_all; a.x_all = x_all; a.da = da; a.dpre1 = dpre1; a.dq = dq;
-    if (H == 64 && net.planes == 2) err = back_dispatch<64, 2, 4>(a, stream);
-    else if (H == 64 && net.planes == 1) err = back_dispatch<64, 1, 4>(a, stream);
-    else if (H == 128 && net.planes == 1) err = back_dispatch<128, 1, 8>(a, stream);
-    else err = hipErrorInvalidValue;
-    if (err != hipSuccess) return err;
+    a.carry = reinterpret_cast<float *>(ws + plan.off_carry);
+    auto reverse = [&](int t_begin, int t_end, hipStream_t on) {
+        a.t_begin = t_begin; a.t_end = t_end;
+        if (H == 64 && net.planes == 2) return back_dispatch<64, 2, 4>(a, on);
+        if (H == 64 && net.planes == 1) return back_dispatch<64, 1, 4>(a, on);
+        if (H == 128 && net.planes == 1) return back_dispatch<128, 1, 8>(a, on);
+        return hipErrorInvalidValue;
+    };
 
     // offsets of the tensors in the packed vector
     float *gW1 = grad, *gb1 = gW1 + (size_t)H * (D + N), *gWih = gb1 + H, *gWhh = gWih + (size_t)3 * H * H;
     float *gbih = gWhh + (size_t)3 * H * H, *gbhh = gbih + 3 * H, *gW2 = gbhh + 3 * H, *gb2 = gW2 + (size_t)A * H;
-    const long M = (long)B * N * T;
-    const int TN = T * N;
-    const RowMap plain_da{da, 0, (int)std::min<long>(M, 1 << 30), 4 * H, adj_bf16};
-    const RowMap da_i = plain_da;                                        // columns n, r, z
-    RowMap da_h = plain_da; da_h.base = da + (size_t)H * adj_bytes;      // columns r, z, n (hidden side)
-    const RowMap x_rows{x_all, (long)S * N * H, TN, H, adj_bf16};      // stored as the adjoints are
-    const RowMap h_prev{h_all, (long)S * N * H, TN, H, 0};
-    const RowMap h_new{h_all + (size_t)N * H, (long)S * N * H, TN, H, 0};
-    const RowMap pre_rows{dpre1, 0, (int)std::min<long>(M, 1 << 30), H, adj_bf16};
-    const RowMap obs_rows{obs, (long)S * N * D, TN, D, 0};
-    const RowMap dq_rows{dq, 0, (int)std::min<long>(M, 1 << 30), plan.a16, adj_bf16};
-    // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
-    const TnProduct products[4] = {
-        {da_i, x_rows, 3 * H, H, kExtraOnes, 1, N, 2 * H, H, gWih, gbih},
-        {da_h, h_prev, 3 * H, H, kExtraOnes, 1, N, 0, H, gWhh, gbhh},
-        {pre_rows, obs_rows, H, D, kExtraAgent, N, N, 0, D + N, gW1, gb1},
-        {dq_rows, h_new, A, H, kExtraOnes, 1, N, 0, H, gW2, gb2},
+    // The four products over the samples (b, t, n) of slots [t0, t1): every operand's rows come in groups of
+    // (t1 - t0) N, one per episode.
+    struct Four { TnProduct p[4]; };
+    auto products_of = [&](int t0, int t1) {
+        const int rows = (t1 - t0) * N;
+        const size_t first = (size_t)t0 * N;                                 // rows of an episode before the window
+        // (all slots: the adjoint arrays' rows follow one another across episodes, one group)
+        const bool whole = t0 == 0 && t1 == T;
+        const int rows_adj = whole ? (int)std::min<long>((long)B * N * T, 1 << 30) : rows;
+        const RowMap da_i{da + first * 4 * H * adj_bytes, whole ? 0 : (long)T * N * 4 * H, rows_adj, 4 * H, adj_bf16};      // columns n, r, z
+        RowMap da_h = da_i; da_h.base = da + (first * 4 * H + H) * adj_bytes;                            // columns r, z, n (hidden side)
+        const RowMap x_rows{static_cast<const char *>(x_all) + first * H * adj_bytes, (long)S * N * H, rows, H, adj_bf16};      // stored as the adjoints are
+        const RowMap h_prev{h_all + first * H, (long)S * N * H, rows, H, 0};
+        const RowMap h_new{h_all + (first + N) * H, (long)S * N * H, rows, H, 0};
+        const RowMap pre_rows{dpre1 + first * H * adj_bytes, whole ? 0 : (long)T * N * H, rows_adj, H, adj_bf16};
+        const RowMap obs_rows{obs + first * D, (long)S * N * D, rows, D, 0};
+        const RowMap dq_rows{dq + first * plan.a16 * adj_bytes, whole ? 0 : (long)T * N * plan.a16, rows_adj, plan.a16, adj_bf16};
+        // W_ih and b_ih: the adjoint columns are n, r, z -> parameter rows r, z, n: shift by 2H
+        return Four{{
+            {da_i, x_rows, 3 * H, H, kExtraOnes, 1, N, 2 * H, H, gWih, gbih},
+            {da_h, h_prev, 3 * H, H, kExtraOnes, 1, N, 0, H, gWhh, gbhh},
+            {pre_rows, obs_rows, H, D, kExtraAgent, N, N, 0, D + N, gW1, gb1},
+            {dq_rows, h_new, A, H, kExtraOnes, 1, N, 0, H, gW2, gb2},
+        }};
     };
-    return launch_tn_products(net.planes, products, 4, M, plan.chunk, partial, plan.partial_bytes, stream);
+
+    // The reverse recurrence is one workgroup per 16 rows: a batch with fewer tiles than compute units leaves the
+    // rest of the chip idle for as long as the episodes are.  Then the slots are walked in two launches, and the
+    // products over the later half run on a second stream beside the earlier half's recurrence.
+    const int tiles = (B * N + 15) / 16, t_mid = T / 2;
+    bool split = side && side->stream && net.planes == 1 && T >= 16 && 2 * tiles <= 3 * n_cu / 2;
+    Four late{}, early{};
+    long m_late = 0, m_early = 0;
+    if (split) {
+        late = products_of(t_mid, T); early = products_of(0, t_mid);
+        m_late = (long)B * N * (T - t_mid); m_early = (long)B * N * t_mid;
+        for (int i = 0; i < 4 && split; ++i) split = tn_wide_fits(late.p[i], m_late) && tn_wide_fits(early.p[i], m_early);
+    }
+    if (!split) {
+        err = reverse(0, T, stream);
+        if (err != hipSuccess) return err;
+        const Four all = products_of(0, T);
+        return launch_tn_products(net.planes, all.p, 4, (long)B * N * T, plan.chunk, partial, plan.partial_bytes, stream);
+    }
+    // the later half's products share the chip with the recurrence, whose workgroups hold half the compute units
+    // or less: half as many chunks (every chunk's partial sums are written once and read once more)
+    auto chunk_of = [](long m, long most) { const long chunks = std::max<long>(1, std::min<long>(most, (m + 31) / 32)); return (int)(((m + chunks - 1) / chunks + 63) / 64 * 64); };
+    const int chunk_late = chunk_of(m_late, 128), chunk_early = chunk_of(m_early, 256);
+    const int chunks_late = (int)((m_late + chunk_late - 1) / chunk_late), chunks_early = (int)((m_early + chunk_early - 1) / chunk_early);
+    // a product's partial sums: the later half's chunks, then the earlier half's, summed in that order
+    float *part_late[4], *part_early[4];
+    TnReduceBatch red{};
+    int max_total = 0;
+    {
+        size_t used = 0;
+        for (int i = 0; i < 4; ++i) {
+            const TnProduct &t = late.p[i];
+            const size_t p_pad = t.P > 128 ? 384 : 128, qp = (size_t)(t.Q + t.n_extra + 15) / 16 * 16;
+            part_late[i] = reinterpret_cast<float *>(reinterpret_cast<char *>(partial) + used);
+            part_early[i] = part_late[i] + (size_t)chunks_late * p_pad * qp;
+            used += (size_t)(chunks_late + chunks_early) * p_pad * qp * sizeof(float);
+            TnReduceArgs r{};
+            r.partial = part_late[i]; r.chunks = chunks_late + chunks_early; r.P = t.P; r.p_pad = (int)p_pad; r.qp = (int)qp;
+            r.Q = t.Q; r.n_extra = t.n_extra; r.extra_mode = t.extra_mode;
+            r.row_shift = t.row_shift; r.w_cols = t.Q; r.ld_w = t.ld_w; r.dst_w = t.dst_w; r.dst_b = t.dst_b;
+            red.r[i] = r;
+            max_total = std::max(max_total, t.P * (t.Q + t.n_extra));
+        }
+        if (used > plan.partial_bytes) return hipErrorInvalidValue;
+    }
+    err = reverse(t_mid, T, stream);
+    if (err == hipSuccess) err = hipEventRecord(side->fork, stream);
+    if (err == hipSuccess) err = hipStreamWaitEvent(side->stream, side->fork, 0);
+    if (err == hipSuccess) err = launch_tn_gemms_wide(late.p, 4, m_late, chunk_late, part_late, side->stream);
+    if (err == hipSuccess) err = hipEventRecord(side->join, side->stream);
+    if (err == hipSuccess) err = reverse(0, t_mid, stream);
+    if (err == hipSuccess) err = launch_tn_gemms_wide(early.p, 4, m_early, chunk_early, part_early, stream);
+    if (err == hipSuccess) err = hipStreamWaitEvent(stream, side->join, 0);
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(tn_reduce_kernel, dim3((max_total + 255) / 256, 4), dim3(256), 0, stream, red);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(bias_from_columns_kernel, dim3((H + 255) / 256), dim3(256), 0, stream, gW1, H, D + N, D, N, gb1);
+    return hipGetLastError();
 }
 
 }  // namespace marl

@@ -199,10 +199,26 @@ int marl_qnet_create(const marl_qnet_desc *desc, const float *host_weights, size
         const int rc = static_scratch_of(desc->device, &q->static_scratch);      // the handle's device is current here
         if (rc != MARL_OK) { delete q; return rc; }
     }
+    // The backward pass's second stream (default priority) and its events are made here, not at first use: a call
+    // under graph capture may create nothing.  Without them the pass runs on the caller's stream alone.
+    q->side = marl::SideStream{nullptr, nullptr, nullptr};
+    if (hipStreamCreateWithFlags(&q->side.stream, hipStreamNonBlocking) != hipSuccess
+        || hipEventCreateWithFlags(&q->side.fork, hipEventDisableTiming) != hipSuccess
+        || hipEventCreateWithFlags(&q->side.join, hipEventDisableTiming) != hipSuccess) {
+        if (q->side.fork) (void)hipEventDestroy(q->side.fork);
+        if (q->side.stream) (void)hipStreamDestroy(q->side.stream);
+        q->side = marl::SideStream{nullptr, nullptr, nullptr};
+        (void)hipGetLastError();
+    }
+    auto drop_side = [&]() {
+        if (q->side.join) (void)hipEventDestroy(q->side.join);
+        if (q->side.fork) (void)hipEventDestroy(q->side.fork);
+        if (q->side.stream) (void)hipStreamDestroy(q->side.stream);
+    };
     err = hipMalloc(&q->dev_weights, img.bytes);
-    if (err != hipSuccess) { delete q; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipMalloc"); }
+    if (err != hipSuccess) { drop_side(); delete q; return err == hipErrorOutOfMemory ? MARL_ERR_NOMEM : device_fail(err, "hipMalloc"); }
     err = hipMemcpy(q->dev_weights, img.host, img.bytes, hipMemcpyHostToDevice);
-    if (err != hipSuccess) { (void)hipFree(q->dev_weights); delete q; return device_fail(err, "hipMemcpy"); }
+    if (err != hipSuccess) { (void)hipFree(q->dev_weights); drop_side(); delete q; return device_fail(err, "hipMemcpy"); }
 
     const char *base = static_cast<const char *>(q->dev_weights);
     marl::NetFrags &n = q->net;
@@ -582,7 +598,7 @@ int qnet_grad_call(marl_qnet *q, int32_t B, int32_t T, const float *obs, const i
     DeviceGuard guard(q->desc.device);
     if (!guard.ok) return device_fail(hipErrorInvalidDevice, "hipSetDevice");
     MARL_HIP(marl::launch_qnet_grad(q->net, B, T, obs, actions, filled, grad_q_taken, workspace, grad_weights,
-                                    static_cast<hipStream_t>(hip_stream), activations_kept));
+                                    static_cast<hipStream_t>(hip_stream), activations_kept, &q->side, q->n_cu));
     return MARL_OK;
 }
 }  // namespace
@@ -724,6 +740,9 @@ int marl_destroy(marl_qnet *q)
         }
         if (q->staging_done) (void)hipEventDestroy(q->staging_done);
         if (q->staging) (void)hipHostFree(q->staging);
+        if (q->side.join) (void)hipEventDestroy(q->side.join);
+        if (q->side.fork) (void)hipEventDestroy(q->side.fork);
+        if (q->side.stream) (void)hipStreamDestroy(q->side.stream);
     }
     delete q;
     return rc;

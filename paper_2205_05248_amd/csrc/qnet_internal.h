@@ -68,6 +68,9 @@ struct PackedImage {
     int kc1, mb2, planes, nc1, act_chunks, proj_chunks;
 };
 
+// A second stream of a handle's, with the two events that fork work onto it and join it again.
+struct SideStream { hipStream_t stream; hipEvent_t fork, join; };
+
 }  // namespace marl
 
 struct marl_qnet {
@@ -81,6 +84,7 @@ struct marl_qnet {
     void *scratch;            // input-projection buffer of marl_unroll_td, grown on demand
     size_t scratch_bytes;
     void *static_scratch;     // this device's address of the library's static buffer (marl_unroll_td_static)
+    marl::SideStream side;    // second stream of the backward pass, made with the handle
     int n_cu;                          // compute units of the device
     int kernels;                       // MARL_KERNELS_AUTO / MARL_KERNELS_TILE32
     bool timing;                       // record events around the kernels of each call
@@ -221,9 +225,11 @@ size_t qnet_grad_workspace_bytes(const NetFrags &net, int B, int T);
 // activations_kept: the workspace already holds x and h of this batch (an unroll in kTdKeep mode wrote them to the
 // places qnet_grad_activation_slots names); otherwise the call runs its own forward pass first.
 void qnet_grad_activation_slots(const NetFrags &net, int B, int T, void *workspace, float **h_all, void **x_all);
+// side: a second stream of the handle's, with two events, on which part of the products may run beside the
+// recurrence (null: everything on `stream`); n_cu: compute units of the device.
 hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs, const int32_t *actions,
                             const uint8_t *filled, const float *grad_q, void *workspace, float *grad, hipStream_t stream,
-                            bool activations_kept = false);
+                            bool activations_kept, const SideStream *side, int n_cu);
 
 // Device-side parameter update (repack.hip).  build_repack_map (host): for every 16-bit element of the image's
 // fragment part, the parameter it holds; launch_sgd_step: weights -= lr * grad, then the image rebuilt from them.

@@ -81,7 +81,10 @@ CASES = [(0, 4, 6, {}), (0, 32, 25, {}), (1, 5, 9, {}), (2, 7, 12, {}), (3, 33, 
          (4, 3, 7, dict(H=64, D=150, dtype="fp32")), (1, 6, 8, dict(dtype="bf16")),
          # odd shapes: one agent, odd observation and action counts, the most actions, a hidden-128 network with few inputs
          (0, 5, 13, dict(N=1, D=7, A=5)), (0, 3, 6, dict(N=17, D=33, A=64, dtype="bf16")),
-         (4, 4, 9, dict(N=2, D=160, A=4)), (1, 1, 40, dict(N=3, D=1, A=7))]
+         (4, 4, 9, dict(N=2, D=160, A=4)), (1, 1, 40, dict(N=3, D=1, A=7)),
+         # bf16 networks over sixteen slots or more: the slots are walked in two launches (an odd count: halves of
+         # eight and nine) and the products run per half; the last one's first layer keeps the narrow loads
+         (4, 2, 17, {}), (1, 3, 24, dict(dtype="bf16")), (0, 2, 16, dict(N=17, D=33, A=64, dtype="bf16"))]
 
 
 @pytest.mark.parametrize("ci,B,T,over", CASES, ids=lambda v: str(v).replace(" ", ""))
