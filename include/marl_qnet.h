@@ -327,8 +327,12 @@ int marl_qnet_check_refresh_map(const marl_qnet_desc *desc, const float *host_we
  *                 the call allocates nothing, the contents afterwards are unspecified
  *   grad_weights  dev [marl_param_count] f32, overwritten
  * The call enqueues a forward pass that keeps the activations, the time-reversed pass and the
- * weight-gradient products on the stream.  Sums run in a fixed order: the same inputs give the
- * same bits.  Arithmetic: bf16 MFMA products with fp32 accumulation; fp32 networks split every
+ * weight-gradient products on the stream.  For a bf16 network part of the products may run on a
+ * second stream that the handle owns, forked from hip_stream after the later half of the slots
+ * and joined to it before the call's last kernels: to the caller everything is ordered as if on
+ * hip_stream (work enqueued there afterwards sees the result; a stream capture of hip_stream takes
+ * the fork and the join in).  Two calls on one handle must not be enqueued from two host threads at
+ * once.  Sums run in a fixed order: the same inputs give the same bits.  Arithmetic: bf16 MFMA products with fp32 accumulation; fp32 networks split every
  * operand into two bf16 parts, bf16 networks round the operands of every product (adjoints, activations) to bf16.
  * Only networks that run on the fused16 kernels are served (see marl_qnet_set_kernels), with
  * D + N <= 336: MARL_ERR_BAD_DIM otherwise, and for B < 1, T < 1, B (T+1) N 4H >= 2^30, or a

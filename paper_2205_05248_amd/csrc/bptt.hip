@@ -21,8 +21,15 @@
 //                                      writes its partial sum; extra columns of B made up on the fly (a column
 //                                      of ones, or the one-hot agent id) yield the bias gradients in the same
 //                                      product.
+//   tn_gemm_wide_kernel                the same products for a bf16 network: both operands are fetched 16 bytes
+//                                      at a time and staged as they lie in memory; the transposing LDS read
+//                                      turns the staged rows into fragments.
 //   tn_reduce_kernel                   adds the chunks' partial sums in a fixed order and writes the result
 //                                      into the packed gradient vector.
+// A batch with fewer row tiles than compute units leaves most of the chip idle while bptt_back_kernel walks the
+// slots.  For a bf16 network the slots are therefore walked in two launches (dL/dh handed over in memory), and the
+// products over the later half run on a second stream of the handle's beside the earlier half's recurrence
+// (launch_qnet_grad); the sum over all chunks, later half first, follows on the caller's stream.
 // The precision follows the network's, in every product of the pass: fp32 networks split every operand into two
 // bf16 planes (three MFMAs per product), bf16 networks round the operands (adjoints, activations) to bf16.
 #include <type_traits>
