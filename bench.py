@@ -553,12 +553,15 @@ def learner_section(ci, launches=10):
     ws = torch.empty(need, dtype=torch.uint8, device="cuda")
     mws = torch.empty(mneed, dtype=torch.uint8, device="cuda")
 
+    # dL/dQ_total = -2 td_err / count as one element-wise kernel: 0 + (-2) * td / count
+    zero, e = torch.zeros(B, T, device="cuda"), torch.empty(B, T, device="cuda")
+
     def iteration():
         online.unroll_td_keep(target, d["obs"], d["avail"], d["actions"], d["reward"], d["terminated"], d["filled"],
                               u["gamma"], q_taken, next_max, y, ws)          # leaves x and h for the backward pass
         mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
                  q_total, y_total, td, loss2)
-        e = td * (-2.0 / loss2[1])
+        torch.addcdiv(zero, td, loss2[1], value=-2.0, out=e)
         mixer.grad(state, q_taken, e, mws, gq, mgrad)
         online.grad(d["obs"], d["actions"], d["filled"], gq, ws, grad, kept=True)
         online.sgd_step(master, grad, 0.0)
@@ -587,7 +590,7 @@ def learner_section(ci, launches=10):
         mixer.td(mixer_tg, state, q_taken, next_max, d["reward"], d["terminated"], d["filled"], u["gamma"],
                  q_total, y_total, td, loss2)
         ev[2].record()
-        e = td * (-2.0 / loss2[1])
+        torch.addcdiv(zero, td, loss2[1], value=-2.0, out=e)
         ev[3].record()
         mixer.grad(state, q_taken, e, mws, gq, mgrad)
         ev[4].record()

@@ -1236,7 +1236,8 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     // the later half's products share the chip with the recurrence, whose workgroups hold half the compute units
     // or less: half as many chunks (every chunk's partial sums are written once and read once more)
     auto chunk_of = [](long m, long most) { const long chunks = std::max<long>(1, std::min<long>(most, (m + 31) / 32)); return (int)(((m + chunks - 1) / chunks + 63) / 64 * 64); };
-    const int chunk_late = chunk_of(m_late, 128), chunk_early = chunk_of(m_early, 256);
+    // (the earlier half's too: its two GRU products then run side by side, one on each stream, 128 workgroups each)
+    const int chunk_late = chunk_of(m_late, 128), chunk_early = chunk_of(m_early, 128);
     const int chunks_late = (int)((m_late + chunk_late - 1) / chunk_late), chunks_early = (int)((m_early + chunk_early - 1) / chunk_early);
     // a product's partial sums: the later half's chunks, then the earlier half's, summed in that order
     float *part_late[4], *part_early[4];
@@ -1263,9 +1264,15 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     if (err == hipSuccess) err = hipEventRecord(side->fork, stream);
     if (err == hipSuccess) err = hipStreamWaitEvent(side->stream, side->fork, 0);
     if (err == hipSuccess) err = launch_tn_gemms_wide(late.p, 4, m_late, chunk_late, part_late, side->stream);
-    if (err == hipSuccess) err = hipEventRecord(side->join, side->stream);
     if (err == hipSuccess) err = reverse(0, t_mid, stream);
-    if (err == hipSuccess) err = launch_tn_gemms_wide(early.p, 4, m_early, chunk_early, part_early, stream);
+    // the earlier half: W_hh's product follows on the second stream (a second fork: it needs the recurrence's end),
+    // the other three on the caller's
+    if (err == hipSuccess) err = hipEventRecord(side->fork, stream);
+    if (err == hipSuccess) err = hipStreamWaitEvent(side->stream, side->fork, 0);
+    if (err == hipSuccess) err = launch_tn_gemms_wide(early.p + 1, 1, m_early, chunk_early, part_early + 1, side->stream);
+    if (err == hipSuccess) err = hipEventRecord(side->join, side->stream);
+    if (err == hipSuccess) err = launch_tn_gemms_wide(early.p, 1, m_early, chunk_early, part_early, stream);
+    if (err == hipSuccess) err = launch_tn_gemms_wide(early.p + 2, 2, m_early, chunk_early, part_early + 2, stream);
     if (err == hipSuccess) err = hipStreamWaitEvent(stream, side->join, 0);
     if (err != hipSuccess) return err;
     hipLaunchKernelGGL(tn_reduce_kernel, dim3((max_total + 255) / 256, 4), dim3(256), 0, stream, red);

@@ -73,9 +73,8 @@ __global__ void rmsprop_kernel(float *w, const float *g, float *v, float lr, flo
     w[i] = w[i] - step;
 }
 
-__global__ void repack_frag_kernel(const float *w, const int32_t *map, uint16_t *image, size_t n)
+__device__ __forceinline__ void repack_frag_element(const float *w, const int32_t *map, uint16_t *image, size_t n, size_t e)
 {
-    const size_t e = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (e >= n) return;
     const int32_t m = map[e];
     uint32_t out = 0;
@@ -85,6 +84,11 @@ __global__ void repack_frag_kernel(const float *w, const int32_t *map, uint16_t 
         out = (m & kLowPlane) ? bf16_rne(__fsub_rn(v, __uint_as_float(hi << 16))) : hi;
     }
     image[e] = (uint16_t)out;
+}
+
+__global__ void repack_frag_kernel(const float *w, const int32_t *map, uint16_t *image, size_t n)
+{
+    repack_frag_element(w, map, image, n, (size_t)blockIdx.x * blockDim.x + threadIdx.x);
 }
 
 // fp32 tables that are plain copies of parameters: dst[i] = w[src[i]]
@@ -101,13 +105,12 @@ struct TableArgs {
     int N, D, A, H, planes;
 };
 
-__global__ void repack_tables_kernel(TableArgs t)
+__device__ __forceinline__ void repack_table_entries(const TableArgs &t, int i)
 {
     const int N = t.N, D = t.D, A = t.A, H = t.H, Din = D + N;
     const float *W1 = t.w, *b1 = W1 + (size_t)H * Din, *Wih = b1 + H, *Whh = Wih + (size_t)3 * H * H;
     const float *bih = Whh + (size_t)3 * H * H, *bhh = bih + 3 * H, *W2 = bhh + 3 * H, *b2 = W2 + (size_t)A * H;
     auto as_stored = [&](float v) { return t.planes == 1 ? __uint_as_float(bf16_rne(v) << 16) : v; };
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < A * H) reinterpret_cast<float *>(t.image + t.off_w2_plain)[i] = as_stored(W2[i]);
     if (i < N * H) {
         const int n = i / H, j = i % H;
@@ -121,6 +124,14 @@ __global__ void repack_tables_kernel(TableArgs t)
         reinterpret_cast<float *>(t.image + t.off_bias_hn)[i] = bhh[2 * H + i];
     }
     if (i < A) reinterpret_cast<float *>(t.image + t.off_b2)[i] = b2[i];
+}
+
+// The whole image of a Q-network from its updated weights in one launch: the first frag_blocks workgroups rebuild
+// the fragment part, the others the fp32 tables (the two do not depend on each other).
+__global__ void repack_image_kernel(const float *w, const int32_t *map, uint16_t *image, size_t n, unsigned frag_blocks, TableArgs t)
+{
+    if (blockIdx.x < frag_blocks) repack_frag_element(w, map, image, n, (size_t)blockIdx.x * blockDim.x + threadIdx.x);
+    else repack_table_entries(t, (int)((blockIdx.x - frag_blocks) * blockDim.x + threadIdx.x));
 }
 
 }  // namespace
@@ -230,7 +241,10 @@ hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout
                            size_t map_elems, void *image_dev, float *weights, const float *grad, size_t n_params, float lr,
                            hipStream_t stream, const UpdateRule &rule)
 {
-    hipError_t err = launch_sgd_and_fragments(weights, grad, lr, n_params, map_dev, map_elems, image_dev, stream, rule);
+    const dim3 grid((unsigned)((n_params + 255) / 256));
+    if (rule.sq_avg) hipLaunchKernelGGL(rmsprop_kernel, grid, dim3(256), 0, stream, weights, grad, rule.sq_avg, lr, rule.alpha, rule.eps, n_params);
+    else hipLaunchKernelGGL(sgd_kernel, grid, dim3(256), 0, stream, weights, grad, lr, n_params);
+    hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     TableArgs t{};
     t.w = weights; t.image = static_cast<char *>(image_dev);
@@ -239,7 +253,9 @@ hipError_t launch_sgd_step(const marl_qnet_desc &desc, const PackedImage &layout
     t.off_b2 = layout.off_b2;
     t.N = desc.n_agents; t.D = desc.obs_dim; t.A = desc.n_actions; t.H = desc.hidden; t.planes = planes;
     const int widest = std::max(std::max(t.A * t.H, t.N * t.H), std::max(t.H, t.A));
-    hipLaunchKernelGGL(repack_tables_kernel, dim3((unsigned)((widest + 255) / 256)), dim3(256), 0, stream, t);
+    const unsigned frag_blocks = (unsigned)((map_elems + 255) / 256), table_blocks = (unsigned)((widest + 255) / 256);
+    hipLaunchKernelGGL(repack_image_kernel, dim3(frag_blocks + table_blocks), dim3(256), 0, stream, weights, map_dev,
+                       static_cast<uint16_t *>(image_dev), map_elems, frag_blocks, t);
     return hipGetLastError();
 }
 
