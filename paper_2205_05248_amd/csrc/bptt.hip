@@ -674,11 +674,19 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGem
     const int m_begin = (int)blockIdx.x * g.chunk, m_end = min(g.M, m_begin + g.chunk);     // M < 2^30
     const int n_steps = (m_end - m_begin + 31) / 32;
 
-    f32x4 acc[PBW][QBN];
+    // Which blocks of the result a wave owns.  Three row blocks (w, w + 8, w + 16) and every column block where the
+    // result is tall: a fragment of B then feeds three products.  Where it is 128 rows by up to 336 columns, all
+    // eight row blocks and every eighth column block (w, w + 8, w + 16): 11 fragments per step for 24 products,
+    // where one row block and all 21 column blocks would read 22 for 21 - and a wave can only issue so many LDS reads.
+    constexpr bool kSplitColumns = PBW == 1;
+    constexpr int kRB = kSplitColumns ? 8 : PBW, kCB = kSplitColumns ? (QBN + 7) / 8 : QBN;
+    auto row_block = [&](int k) { return kSplitColumns ? k : w + 8 * k; };
+    auto col_block = [&](int j) { return kSplitColumns ? w + 8 * j : j; };
+    f32x4 acc[kRB][kCB];
 #pragma unroll
-    for (int k = 0; k < PBW; ++k)
+    for (int k = 0; k < kRB; ++k)
 #pragma unroll
-        for (int j = 0; j < QBN; ++j)
+        for (int j = 0; j < kCB; ++j)
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[k][j][r] = 0.0f;
 
@@ -803,16 +811,16 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGem
             return __builtin_bit_cast(bf16x8, (s16x8)__builtin_shufflevector(first, second, 0, 1, 2, 3, 4, 5, 6, 7));
         };
         auto multiply = [&](const char *buf) {
-            WFrag<1> af[PBW];
+            WFrag<1> af[kRB];
 #pragma unroll
-            for (int k = 0; k < PBW; ++k) af[k].hi = fragment(buf, kAPitch, 16 * (w + 8 * k));
+            for (int k = 0; k < kRB; ++k) af[k].hi = fragment(buf, kAPitch, 16 * row_block(k));
 #pragma unroll
-            for (int j = 0; j < QBN; ++j)
-                if (j < n_qb) {
+            for (int j = 0; j < kCB; ++j)
+                if (col_block(j) < n_qb) {
                     Frag<1> bf;
-                    bf.hi = fragment(buf + 32 * kAPitch, kBPitch, 16 * j);
+                    bf.hi = fragment(buf + 32 * kAPitch, kBPitch, 16 * col_block(j));
 #pragma unroll
-                    for (int k = 0; k < PBW; ++k) mma16<1>(acc[k][j], af[k], bf);
+                    for (int k = 0; k < kRB; ++k) mma16<1>(acc[k][j], af[k], bf);
                 }
         };
 #pragma unroll
@@ -839,12 +847,12 @@ __global__ __launch_bounds__(kTnThreads, 2) void tn_gemm_wide_kernel(const TnGem
     // C layout: lane (c, q4) holds result[16 block + 4 q4 + r][16 j + c]
     float *out = g.partial + (size_t)blockIdx.x * kPp * g.qp;
 #pragma unroll
-    for (int k = 0; k < PBW; ++k)
+    for (int k = 0; k < kRB; ++k)
 #pragma unroll
-        for (int j = 0; j < QBN; ++j)
-            if (j < n_qb)
+        for (int j = 0; j < kCB; ++j)
+            if (col_block(j) < n_qb)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) out[(size_t)(16 * (w + 8 * k) + 4 * q4 + r) * g.qp + 16 * j + c] = acc[k][j][r];
+                for (int r = 0; r < 4; ++r) out[(size_t)(16 * row_block(k) + 4 * q4 + r) * g.qp + 16 * col_block(j) + c] = acc[k][j][r];
 }
 
 template <int PBW, int QBN> constexpr size_t tn_wide_lds()
@@ -1236,7 +1244,8 @@ hipError_t launch_qnet_grad(const NetFrags &net, int B, int T, const float *obs,
     // the later half's products share the chip with the recurrence, whose workgroups hold half the compute units
     // or less: half as many chunks (every chunk's partial sums are written once and read once more)
     auto chunk_of = [](long m, long most) { const long chunks = std::max<long>(1, std::min<long>(most, (m + 31) / 32)); return (int)(((m + chunks - 1) / chunks + 63) / 64 * 64); };
-    // (the earlier half's too: its two GRU products then run side by side, one on each stream, 128 workgroups each)
+    // (the earlier half's too: its two GRU products then run side by side, one on each stream, 128 workgroups each;
+    // 256 chunks for the first layer's product, which runs last and alone, changed nothing)
     const int chunk_late = chunk_of(m_late, 128), chunk_early = chunk_of(m_early, 128);
     const int chunks_late = (int)((m_late + chunk_late - 1) / chunk_late), chunks_early = (int)((m_early + chunk_early - 1) / chunk_early);
     // a product's partial sums: the later half's chunks, then the earlier half's, summed in that order
