@@ -224,18 +224,21 @@ def test_updated_mixer_equals_one_created_from_the_updated_weights(ci, dtype):
     mixer.close(); fresh.close()
 
 
-def test_learner_iteration_replays_from_a_hip_graph():
+@pytest.mark.parametrize("dtype,T", [("fp32", 15), ("bf16", 18)])
+def test_learner_iteration_replays_from_a_hip_graph(dtype, T):
     """The whole learner iteration captured into a HIP graph after two eager iterations (which build the update
     maps and set the launch attributes), then replayed: four replays, with eager work and synchronisation in
     between, leave exactly the weights that four eager iterations leave (the iteration reads and updates the
-    weights, so any replay that went wrong shows in every later one)."""
-    cfg = dict(wl.config(1), B=8, T=15)
+    weights, so any replay that went wrong shows in every later one).  The bf16 case has enough slots for the
+    backward pass to walk them in two launches and fork part of its products onto the handle's second stream: the
+    capture has to take that fork and its join in."""
+    B = 8
+    cfg = dict(wl.config(1), B=B, T=T, dtype=dtype)
     dims, mdims = wl.dims(cfg), wl.mixer_dims(cfg)
     N = dims[0]
-    B, T = 8, 15
     w, mw = wl.make_weights(cfg, 0), wl.make_mixer_weights(cfg, 0)
-    online, target = binding.QNet(dims, w), binding.QNet(dims, wl.make_weights(cfg, 1))
-    mixer, mixer_tg = binding.Mixer(mdims, mw), binding.Mixer(mdims, wl.make_mixer_weights(cfg, 1))
+    online, target = binding.QNet(dims, w, dtype), binding.QNet(dims, wl.make_weights(cfg, 1), dtype)
+    mixer, mixer_tg = binding.Mixer(mdims, mw, dtype), binding.Mixer(mdims, wl.make_mixer_weights(cfg, 1), dtype)
     u = wl.make_unroll_inputs(cfg, B=B, T=T)
     d = pu.to_dev(u, ["obs", "avail", "actions", "reward", "terminated", "filled"])
     state = torch.from_numpy(wl.make_mixer_inputs(cfg, B=B, T=T)["state"]).cuda()
